@@ -1,0 +1,165 @@
+"""CPU oracle for the AnTKV online path: TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this package.  It shares no code with the HIP path and imports nothing from it.
+
+The arithmetic lives in antkv_oracle.c (plain C, fp64); this module marshals numpy
+arrays into it and adds the top-k step, which is a stable library sort.
+
+  encode(x, cb)                 paper Sec. 3.1 (sub-vector -> nearest centroid)
+  anchor_score(q, k, scale)     paper Eq. (4), causal prefill/window form
+  topk(scores, k)               keep the k highest scores (Sec. 3, "anchor tokens")
+  decode_attn(...)              Attn (Sec. 2.1) over codes + FP16 anchors, and the
+                                decode-time Anchor Score (Sec. 3.2, last paragraph)
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "antkv_oracle.c")
+_LIB = os.path.join(_HERE, "libantkv_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (host code only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-march=x86-64-v3", "-fopenmp", "-fPIC", "-shared", "-Wall",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            build()
+        lib = ctypes.CDLL(_LIB)
+        i64, dbl, vp = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
+        lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_encode.restype = ctypes.c_int
+        lib.oracle_encode.argtypes = [vp, vp, i64, i64, i64, i64, i64, i64, vp, vp]
+        lib.oracle_anchor_score.restype = ctypes.c_int
+        lib.oracle_anchor_score.argtypes = [vp, vp, i64, i64, i64, i64, i64, i64, dbl, ctypes.c_int,
+                                            vp, vp, vp, vp, vp]
+        lib.oracle_decode_attn.restype = ctypes.c_int
+        lib.oracle_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64,
+                                           i64, i64, i64, i64, i64, i64, i64, dbl, vp, vp, vp, vp]
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def _f32(a) -> np.ndarray:
+    """fp16 (or any float) array -> contiguous fp32 holding the same values exactly."""
+    a = np.asarray(a)
+    if a.dtype == np.float64:
+        raise TypeError("oracle inputs are fp16-valued; pass float16 or float32")
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def encode(x, cb, want_margin: bool = False):
+    """x [B,Hkv,n,D], cb [Hkv,M,C,d] -> codes int32 [B,Hkv,n,M] (and margins fp64)."""
+    x32, cb32 = _f32(x), _f32(cb)
+    B, Hkv, n, D = x32.shape
+    Hc, M, C, d = cb32.shape
+    assert Hc == Hkv and M * d == D
+    codes = np.empty((B, Hkv, n, M), dtype=np.int32)
+    margin = np.empty((B, Hkv, n, M), dtype=np.float64) if want_margin else None
+    rc = _load().oracle_encode(_ptr(x32), _ptr(cb32), B, Hkv, n, D, d, C, _ptr(codes), _ptr(margin))
+    if rc != 0:
+        raise RuntimeError(f"oracle_encode failed: {rc}")
+    return (codes, margin) if want_margin else codes
+
+
+def anchor_score(q, k, scale: float, causal: bool = True, want_stats: bool = False):
+    """q [B,Hq,Nq,D] = the last Nq positions, k [B,Hkv,N,D] -> (AnS_K, AnS_V) fp64 [B,Hkv,N]."""
+    q32, k32 = _f32(q), _f32(k)
+    B, Hq, Nq, D = q32.shape
+    Bk, Hkv, N, Dk = k32.shape
+    assert Bk == B and Dk == D
+    ans_k = np.zeros((B, Hkv, N), dtype=np.float64)
+    ans_v = np.zeros((B, Hkv, N), dtype=np.float64)
+    stats = [np.zeros((B, Hq, Nq), dtype=np.float64) for _ in range(3)] if want_stats else [None] * 3
+    rc = _load().oracle_anchor_score(_ptr(q32), _ptr(k32), B, Hq, Hkv, N, Nq, D, float(scale),
+                                     1 if causal else 0, _ptr(ans_k), _ptr(ans_v),
+                                     _ptr(stats[0]), _ptr(stats[1]), _ptr(stats[2]))
+    if rc != 0:
+        raise RuntimeError(f"oracle_anchor_score failed: {rc}")
+    if want_stats:
+        return ans_k, ans_v, {"row_max": stats[0], "row_sum": stats[1], "q_norm": stats[2]}
+    return ans_k, ans_v
+
+
+def topk(scores, k: int, want_margin: bool = False):
+    """Indices of the k largest scores per row, ties to the lower index, ascending output.
+
+    scores [..., N] -> idx int32 [..., k].  margin [..., N] is |score - tau| / max(|tau|, 1e-30)
+    with tau halfway between the k-th and (k+1)-th largest score (inf if k is 0 or N):
+    candidates with a tiny margin are the ones a differently-rounded scorer may swap.
+    """
+    s = np.asarray(scores, dtype=np.float64)
+    N = s.shape[-1]
+    assert 0 <= k <= N
+    flat = s.reshape(-1, N)
+    idx = np.empty((flat.shape[0], k), dtype=np.int32)
+    margin = np.full(flat.shape, np.inf) if want_margin else None
+    for r in range(flat.shape[0]):
+        order = np.argsort(-flat[r], kind="stable")  # descending score, ascending index on ties
+        idx[r] = np.sort(order[:k]).astype(np.int32)
+        if want_margin and 0 < k < N:
+            tau = 0.5 * (flat[r, order[k - 1]] + flat[r, order[k]])
+            margin[r] = np.abs(flat[r] - tau) / max(abs(tau), 1e-30)
+    idx = idx.reshape(s.shape[:-1] + (k,))
+    if want_margin:
+        return idx, margin.reshape(s.shape)
+    return idx
+
+
+def decode_attn(q, codes_k, codes_v, cb_k, cb_v, idx_k, rows_k, idx_v, rows_v, scale: float,
+                want_lse: bool = False, want_ans: bool = False):
+    """Decode attention over codes + anchors.  Returns out fp64 [B,Hq,D] (+ extras dict)."""
+    q32, cbk, cbv = _f32(q), _f32(cb_k), _f32(cb_v)
+    B, Hq, D = q32.shape
+    ck = np.ascontiguousarray(codes_k, dtype=np.int32)
+    cv = np.ascontiguousarray(codes_v, dtype=np.int32)
+    _, Hkv, N, M = ck.shape
+    Hc, Mc, C, d = cbk.shape
+    assert Hc == Hkv and Mc == M and M * d == D and cbv.shape == cbk.shape and cv.shape == ck.shape
+    ik = np.ascontiguousarray(idx_k, dtype=np.int32).reshape(B, Hkv, -1)
+    iv = np.ascontiguousarray(idx_v, dtype=np.int32).reshape(B, Hkv, -1)
+    k_k, k_v = ik.shape[-1], iv.shape[-1]
+    rk = _f32(rows_k).reshape(B, Hkv, k_k, D)
+    rv = _f32(rows_v).reshape(B, Hkv, k_v, D)
+    for name, ix in (("idx_k", ik), ("idx_v", iv)):
+        if ix.shape[-1] > 1 and not np.all(np.diff(ix, axis=-1) > 0):
+            raise ValueError(f"{name} must be strictly ascending")
+    out = np.zeros((B, Hq, D), dtype=np.float64)
+    lse = np.zeros((B, Hq), dtype=np.float64) if want_lse else None
+    ans_k = np.zeros((B, Hkv, N), dtype=np.float64) if want_ans else None
+    ans_v = np.zeros((B, Hkv, N), dtype=np.float64) if want_ans else None
+    rc = _load().oracle_decode_attn(_ptr(q32), _ptr(ck), _ptr(cv), _ptr(cbk), _ptr(cbv),
+                                    _ptr(ik), _ptr(rk), k_k, _ptr(iv), _ptr(rv), k_v,
+                                    B, Hq, Hkv, N, D, d, C, float(scale),
+                                    _ptr(out), _ptr(lse), _ptr(ans_k), _ptr(ans_v))
+    if rc != 0:
+        raise RuntimeError(f"oracle_decode_attn failed: {rc}")
+    extras = {}
+    if want_lse:
+        extras["lse"] = lse
+    if want_ans:
+        extras["ans_k"], extras["ans_v"] = ans_k, ans_v
+    return (out, extras) if extras else out
