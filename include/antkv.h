@@ -1,0 +1,150 @@
+/*
+ * antkv.h - C ABI of the AnTKV online path on AMD MI355X (gfx950).
+ *
+ * AnTKV (Anchor Token-Aware Sub-Bit Vector Quantization for KV Cache) keeps the KV
+ * cache as vector-quantization codes and preserves a small set of "anchor" tokens
+ * in FP16.  This library holds the online stage (paper Sec. 3, Fig. 2(b)):
+ *
+ *   antkv_encode         VQ assignment of K / V sub-vectors            (Sec. 3.1)
+ *   antkv_anchor_select  Anchor Score of every token + top-k select    (Sec. 3.2, Eq. (4); Sec. 3.3, Alg. 1)
+ *   antkv_topk           the selection step alone
+ *   antkv_gather_rows    copy the selected FP16 rows into the anchor store
+ *   antkv_decode_attn    decode attention over codes + FP16 anchors    (Sec. 2.1 Attn; Sec. 3.2 last par.)
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless stated otherwise.  The caller owns all
+ *     buffers; the library never allocates, frees or synchronises.  Scratch memory is
+ *     a caller-provided workspace whose size comes from the *_workspace query
+ *     (256-byte aligned).  Work is enqueued on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream).
+ *   - Every call returns an int: ANTKV_OK or one of the error codes below.  Argument
+ *     errors are detected on the host before anything is enqueued.
+ *   - Tensors are dense, row-major, last index fastest, in the layouts given per call.
+ *     fp16 = IEEE binary16.  "KV head g of query head h" is g = h / (Hq / Hkv).
+ *   - Geometry: D must be 128, n_centroids 256 (one byte per code), d_sub in {4, 8, 16}
+ *     (2 / 1 / 0.5 bit per element, the paper's d4m256 / d8m256 notation, Sec. 4), and
+ *     Hq / Hkv in {1, 2, 4}.  M = D / d_sub sub-spaces per head.
+ *   - Codebooks: fp16 [Hkv][M][256][d_sub], separate for K and V; sub-space m covers
+ *     channels [m*d_sub, (m+1)*d_sub).
+ *   - Codes: uint8 [B][Hkv][N_cap][M], token-major.
+ *   - Calls that share a workspace must not overlap in time.
+ */
+#ifndef ANTKV_H
+#define ANTKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ANTKV_OK 0
+#define ANTKV_EINVAL 1       /* null pointer, bad shape, misaligned pointer, k out of range */
+#define ANTKV_EUNSUPPORTED 2 /* geometry outside the supported set */
+#define ANTKV_EWORKSPACE 3   /* workspace missing or too small */
+#define ANTKV_ELAUNCH 4      /* a HIP call failed while enqueueing */
+
+typedef struct antkv_geom {
+    int32_t B;           /* sequences in the batch */
+    int32_t Hq;          /* query heads */
+    int32_t Hkv;         /* KV heads */
+    int32_t D;           /* head dim (128) */
+    int32_t d_sub;       /* sub-vector dim: 4, 8 or 16 */
+    int32_t n_centroids; /* 256 */
+} antkv_geom;
+
+int antkv_version(void);
+const char* antkv_strerror(int code); /* host pointer to a static string */
+
+/*
+ * VQ encode (Sec. 3.1: each token row is split into sub-vectors and each sub-vector is
+ * replaced by the index of its k-means centroid, i.e. the Euclidean-nearest one).
+ *
+ *   x        fp16 [B][Hkv][n_tok][D] with element strides xs_b, xs_h, xs_t (channel stride 1);
+ *            16-byte aligned, strides multiples of 8 elements.
+ *   codebook fp16 [Hkv][M][256][d_sub]
+ *   codes    uint8 [B][Hkv][N_cap][M]; rows token_offset .. token_offset+n_tok-1 are written:
+ *            codes[b][g][token_offset+t][m] = argmin_c || x[b][g][t][m*d_sub : (m+1)*d_sub] - codebook[g][m][c] ||^2,
+ *            the lowest c among equal distances (distances compared in fp32).
+ * Call once for K with the K codebook and once for V with the V codebook.
+ * n_tok == 0 is a no-op.  Errors: EINVAL (null, alignment, token_offset + n_tok > N_cap), EUNSUPPORTED.
+ */
+int antkv_encode(const antkv_geom* geom, const void* x, int64_t xs_b, int64_t xs_h, int64_t xs_t,
+                 int64_t n_tok, const void* codebook, uint8_t* codes, int64_t N_cap,
+                 int64_t token_offset, void* stream);
+
+/*
+ * Anchor Score + selection (Eq. (4)):
+ *   AnS(V_j) = sum_i A_ij,   AnS(K_j) = sum_i A_ij (1 - A_ij) ||Q_i||_2,
+ *   A = softmax(scale * Q K^T) with a causal mask, computed without materialising A
+ *   from per-row statistics (row max, row sum) as in Alg. 1, and summed over the
+ *   Hq/Hkv query heads that read a KV head.
+ *
+ *   q        fp16 [B][Hq][Nq][D]: the LAST Nq positions of an N-token context; query row i sits
+ *            at position N-Nq+i and sees keys 0 .. N-Nq+i.  1 <= Nq <= N.
+ *   k_fp16   fp16 [B][Hkv][N][D], the full-precision keys
+ *   row_max, row_sum  optional fp32 [B][Hq][Nq] as an attention kernel extended per Sec. 3.3
+ *            would supply them: row_max[i] = max_j scale*S_ij, row_sum[i] = sum_j exp(scale*S_ij - row_max[i]).
+ *            Pass both or neither (NULL): with NULL the library computes them in a first pass.
+ *   ans_k, ans_v      optional fp32 [B][Hkv][N] outputs (the scores); NULL = keep them in the workspace
+ *   idx_k, idx_v      int32 [B][Hkv][k]: positions of the k highest AnS(K) / AnS(V) scores, ascending
+ *            by position; equal scores resolve to the lower position.  0 <= k <= N.
+ *            Either may be NULL to skip that selection.
+ * Scores are accumulated in fp64 and rounded once to fp32; selection compares those fp32 values.
+ */
+size_t antkv_anchor_select_workspace(const antkv_geom* geom, int64_t N, int64_t Nq, int64_t k);
+int antkv_anchor_select(const antkv_geom* geom, const void* q, const void* k_fp16, int64_t N,
+                        int64_t Nq, float scale, int64_t k, const float* row_max,
+                        const float* row_sum, float* ans_k, float* ans_v, int32_t* idx_k,
+                        int32_t* idx_v, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Selection alone: for each of n_rows score rows (fp32 [n_rows][N], finite values), the positions
+ * of the k largest, ascending; ties to the lower position.  idx: int32 [n_rows][k].
+ */
+size_t antkv_topk_workspace(int64_t n_rows, int64_t N, int64_t k);
+int antkv_topk(const float* scores, int64_t n_rows, int64_t N, int64_t k, int32_t* idx,
+               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Anchor store fill: rows_out[b][g][i][:] = x[b][g][idx[b][g][i]][:] (fp16 rows of D channels).
+ *   x fp16 [B][Hkv][N][D]; idx int32 [B][Hkv][k] with entries in [0, N); rows_out fp16 [B][Hkv][k][D].
+ */
+int antkv_gather_rows(const antkv_geom* geom, const void* x, int64_t N, const int32_t* idx,
+                      int64_t k, void* rows_out, void* stream);
+
+/*
+ * Decode attention for one new token per sequence (Attn of Sec. 2.1 with one query row):
+ *   out[b][h] = softmax_j(scale * q[b][h] . K_eff[b][g][j]) . V_eff[b][g],   j = 0 .. N-1
+ *   K_eff[j] = rows_k[slot] if j == idx_k[slot], else concat_m cb_k[g][m][codes_k[j][m]]
+ *   V_eff[j] = rows_v[slot] if j == idx_v[slot], else concat_m cb_v[g][m][codes_v[j][m]]
+ * (anchor tokens keep their FP16 rows, every other token is read from its codes; Fig. 2(b)).
+ *
+ *   q        fp16 [B][Hq][D]
+ *   codes_k, codes_v  uint8 [B][Hkv][N_cap][M], tokens 0..N-1 valid (anchor positions hold codes
+ *            too; they are ignored).  16-byte aligned.
+ *   cb_k, cb_v        fp16 [Hkv][M][256][d_sub]
+ *   idx_k    int32 [B][Hkv][k_k] strictly ascending in [0, N); rows_k fp16 [B][Hkv][k_k][D]
+ *   idx_v, rows_v     likewise with k_v.  k_k and k_v may be 0 (pointers may then be NULL) up to N.
+ *   out      fp16 [B][Hq][D]; accumulation is fp32, rounded once.
+ * Optional decode-time Anchor Score (Eq. (4) with the single query row over K_eff):
+ *   ans_k, ans_v      fp32 [B][Hkv][N], both or neither (NULL):  ans_v[j] = sum_h p_hj,
+ *            ans_k[j] = sum_h p_hj (1 - p_hj) ||q_h||_2
+ *   resel_idx_k, resel_idx_v  int32 [B][Hkv][k_resel] or NULL: top-k_resel positions of those scores
+ *            (ascending, ties to the lower position).  Needs ans_k / ans_v respectively to be non-NULL.
+ * N == 0 writes zeros.  Errors: EINVAL, EUNSUPPORTED, EWORKSPACE, ELAUNCH.
+ */
+size_t antkv_decode_attn_workspace(const antkv_geom* geom, int64_t N, int64_t k_k, int64_t k_v,
+                                   int64_t k_resel);
+int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const uint8_t* codes_k,
+                      const uint8_t* codes_v, int64_t N, int64_t N_cap, const void* cb_k,
+                      const void* cb_v, const int32_t* idx_k, const void* rows_k, int64_t k_k,
+                      const int32_t* idx_v, const void* rows_v, int64_t k_v, void* out,
+                      float* ans_k, float* ans_v, int32_t* resel_idx_k, int32_t* resel_idx_v,
+                      int64_t k_resel, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ANTKV_H */

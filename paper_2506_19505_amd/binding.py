@@ -1,0 +1,230 @@
+"""ctypes binding with the same names as the C ABI (include/antkv.h).  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libantkv.so")
+_lib = None
+
+EXPORTS = (
+    "antkv_version", "antkv_strerror", "antkv_encode", "antkv_anchor_select_workspace", "antkv_anchor_select",
+    "antkv_topk_workspace", "antkv_topk", "antkv_gather_rows", "antkv_decode_attn_workspace", "antkv_decode_attn",
+)
+
+
+class AntkvError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: error {code} ({_strerror(code)})")
+        self.code = code
+
+
+class _Geom(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "Hq", "Hkv", "D", "d_sub", "n_centroids")]
+
+
+@dataclass(frozen=True)
+class Geometry:
+    B: int
+    Hq: int
+    Hkv: int
+    d_sub: int
+    D: int = 128
+    n_centroids: int = 256
+
+    @property
+    def M(self) -> int:
+        return self.D // self.d_sub
+
+    def c(self) -> _Geom:
+        return _Geom(self.B, self.Hq, self.Hkv, self.D, self.d_sub, self.n_centroids)
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libantkv.so; fails loudly if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2506_19505_amd.build` "
+                              "(or __graft_entry__.build()); the AnTKV path has no CPU fallback")
+        lib = ctypes.CDLL(_LIB_PATH)
+        i64, vp, sz, f32 = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float
+        gp = ctypes.POINTER(_Geom)
+        lib.antkv_version.restype = ctypes.c_int
+        lib.antkv_strerror.restype = ctypes.c_char_p
+        lib.antkv_strerror.argtypes = [ctypes.c_int]
+        lib.antkv_encode.restype = ctypes.c_int
+        lib.antkv_encode.argtypes = [gp, vp, i64, i64, i64, i64, vp, vp, i64, i64, vp]
+        lib.antkv_anchor_select_workspace.restype = sz
+        lib.antkv_anchor_select_workspace.argtypes = [gp, i64, i64, i64]
+        lib.antkv_anchor_select.restype = ctypes.c_int
+        lib.antkv_anchor_select.argtypes = [gp, vp, vp, i64, i64, f32, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.antkv_topk_workspace.restype = sz
+        lib.antkv_topk_workspace.argtypes = [i64, i64, i64]
+        lib.antkv_topk.restype = ctypes.c_int
+        lib.antkv_topk.argtypes = [vp, i64, i64, i64, vp, vp, sz, vp]
+        lib.antkv_gather_rows.restype = ctypes.c_int
+        lib.antkv_gather_rows.argtypes = [gp, vp, i64, vp, i64, vp, vp]
+        lib.antkv_decode_attn_workspace.restype = sz
+        lib.antkv_decode_attn_workspace.argtypes = [gp, i64, i64, i64, i64]
+        lib.antkv_decode_attn.restype = ctypes.c_int
+        lib.antkv_decode_attn.argtypes = [gp, vp, f32, vp, vp, i64, i64, vp, vp, vp, vp, i64, vp, vp, i64, vp,
+                                          vp, vp, vp, vp, i64, vp, sz, vp]
+        _lib = lib
+    return _lib
+
+
+def _strerror(code: int) -> str:
+    return load_library().antkv_strerror(code).decode()
+
+
+def version() -> int:
+    return int(load_library().antkv_version())
+
+
+def _p(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(t: torch.Tensor):
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise AntkvError(rc, what)
+
+
+def _need(t: torch.Tensor, dtype, name: str):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def encode(geom: Geometry, x: torch.Tensor, codebook: torch.Tensor, codes: torch.Tensor | None = None,
+           token_offset: int = 0) -> torch.Tensor:
+    """antkv_encode: x fp16 [B,Hkv,n,D] (last dim contiguous) -> codes uint8 [B,Hkv,N_cap,M]."""
+    if not x.is_cuda or x.dtype != torch.float16 or x.stride(-1) != 1:
+        raise ValueError("x must be an fp16 device tensor with contiguous channels")
+    _need(codebook, torch.float16, "codebook")
+    B, Hkv, n, _ = x.shape
+    if codes is None:
+        codes = torch.empty((B, Hkv, n, geom.M), dtype=torch.uint8, device=x.device)
+    _need(codes, torch.uint8, "codes")
+    g = geom.c()
+    rc = load_library().antkv_encode(ctypes.byref(g), _p(x), x.stride(0), x.stride(1), x.stride(2), n, _p(codebook),
+                                     _p(codes), codes.shape[2], token_offset, _stream(x))
+    _check(rc, "antkv_encode")
+    return codes
+
+
+def topk(scores: torch.Tensor, k: int) -> torch.Tensor:
+    """antkv_topk: scores fp32 [..., N] -> idx int32 [..., k]."""
+    _need(scores, torch.float32, "scores")
+    N = scores.shape[-1]
+    rows = scores.numel() // max(N, 1)
+    idx = torch.empty(scores.shape[:-1] + (k,), dtype=torch.int32, device=scores.device)
+    lib = load_library()
+    ws = _workspace(lib.antkv_topk_workspace(rows, N, k), scores.device)
+    rc = lib.antkv_topk(_p(scores), rows, N, k, _p(idx), _p(ws), ws.numel(), _stream(scores))
+    _check(rc, "antkv_topk")
+    return idx
+
+
+def anchor_select(geom: Geometry, q: torch.Tensor, k_fp16: torch.Tensor, scale: float, k: int,
+                  row_max: torch.Tensor | None = None, row_sum: torch.Tensor | None = None,
+                  want_scores: bool = True):
+    """antkv_anchor_select: q fp16 [B,Hq,Nq,D], k fp16 [B,Hkv,N,D] -> (idx_k, idx_v, ans_k, ans_v)."""
+    _need(q, torch.float16, "q")
+    _need(k_fp16, torch.float16, "k_fp16")
+    B, Hkv, N, _ = k_fp16.shape
+    Nq = q.shape[2]
+    dev = q.device
+    ans_k = torch.empty((B, Hkv, N), dtype=torch.float32, device=dev) if want_scores else None
+    ans_v = torch.empty((B, Hkv, N), dtype=torch.float32, device=dev) if want_scores else None
+    idx_k = torch.empty((B, Hkv, k), dtype=torch.int32, device=dev)
+    idx_v = torch.empty((B, Hkv, k), dtype=torch.int32, device=dev)
+    lib = load_library()
+    g = geom.c()
+    ws = _workspace(lib.antkv_anchor_select_workspace(ctypes.byref(g), N, Nq, k), dev)
+    rc = lib.antkv_anchor_select(ctypes.byref(g), _p(q), _p(k_fp16), N, Nq, float(scale), k, _p(row_max), _p(row_sum),
+                                 _p(ans_k), _p(ans_v), _p(idx_k), _p(idx_v), _p(ws), ws.numel(), _stream(q))
+    _check(rc, "antkv_anchor_select")
+    return idx_k, idx_v, ans_k, ans_v
+
+
+def gather_rows(geom: Geometry, x: torch.Tensor, idx: torch.Tensor) -> torch.Tensor:
+    """antkv_gather_rows: x fp16 [B,Hkv,N,D], idx int32 [B,Hkv,k] -> rows fp16 [B,Hkv,k,D]."""
+    _need(x, torch.float16, "x")
+    _need(idx, torch.int32, "idx")
+    B, Hkv, N, D = x.shape
+    k = idx.shape[-1]
+    rows = torch.empty((B, Hkv, k, D), dtype=torch.float16, device=x.device)
+    g = geom.c()
+    rc = load_library().antkv_gather_rows(ctypes.byref(g), _p(x), N, _p(idx), k, _p(rows), _stream(x))
+    _check(rc, "antkv_gather_rows")
+    return rows
+
+
+class DecodeWorkspace:
+    """Caller-owned scratch for antkv_decode_attn, sized once and reused across calls."""
+
+    def __init__(self, geom: Geometry, N: int, k_k: int, k_v: int, k_resel: int, device):
+        g = geom.c()
+        self.nbytes = load_library().antkv_decode_attn_workspace(ctypes.byref(g), N, k_k, k_v, k_resel)
+        self.buf = _workspace(self.nbytes, device)
+
+
+def decode_attn(geom: Geometry, q: torch.Tensor, scale: float, codes_k: torch.Tensor, codes_v: torch.Tensor,
+                cb_k: torch.Tensor, cb_v: torch.Tensor, idx_k: torch.Tensor | None, rows_k: torch.Tensor | None,
+                idx_v: torch.Tensor | None, rows_v: torch.Tensor | None, N: int | None = None,
+                out: torch.Tensor | None = None, want_ans: bool = False, k_resel: int = 0,
+                workspace: DecodeWorkspace | None = None):
+    """antkv_decode_attn.  Returns out fp16 [B,Hq,D], or (out, ans_k, ans_v, resel_idx_k, resel_idx_v)."""
+    _need(q, torch.float16, "q")
+    _need(codes_k, torch.uint8, "codes_k")
+    _need(codes_v, torch.uint8, "codes_v")
+    dev = q.device
+    B, Hq, D = q.shape
+    Hkv = geom.Hkv
+    N_cap = codes_k.shape[2]
+    if N is None:
+        N = N_cap
+    k_k = 0 if idx_k is None else idx_k.shape[-1]
+    k_v = 0 if idx_v is None else idx_v.shape[-1]
+    if out is None:
+        out = torch.empty((B, Hq, D), dtype=torch.float16, device=dev)
+    ans_k = ans_v = rk = rv = None
+    if want_ans or k_resel > 0:
+        ans_k = torch.empty((B, Hkv, N), dtype=torch.float32, device=dev)
+        ans_v = torch.empty((B, Hkv, N), dtype=torch.float32, device=dev)
+    if k_resel > 0:
+        rk = torch.empty((B, Hkv, k_resel), dtype=torch.int32, device=dev)
+        rv = torch.empty((B, Hkv, k_resel), dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = DecodeWorkspace(geom, N, k_k, k_v, k_resel, dev)
+    g = geom.c()
+    rc = load_library().antkv_decode_attn(
+        ctypes.byref(g), _p(q), float(scale), _p(codes_k), _p(codes_v), N, N_cap, _p(cb_k), _p(cb_v),
+        _p(idx_k) if k_k else None, _p(rows_k) if k_k else None, k_k,
+        _p(idx_v) if k_v else None, _p(rows_v) if k_v else None, k_v,
+        _p(out), _p(ans_k), _p(ans_v), _p(rk), _p(rv), k_resel, _p(workspace.buf), workspace.buf.numel(), _stream(q))
+    _check(rc, "antkv_decode_attn")
+    if want_ans or k_resel > 0:
+        return out, ans_k, ans_v, rk, rv
+    return out

@@ -1,0 +1,274 @@
+// Anchor Score (paper Eq. (4); two-phase procedure of Alg. 1, Sec. 3.3):
+//   AnS(V_j) = sum_i A_ij,   AnS(K_j) = sum_i A_ij (1 - A_ij) ||Q_i||_2,   A = causal softmax(scale Q K^T),
+// summed over the query heads of a KV head.  A is never materialised.
+//
+//   phase 1  row statistics: per (head, query row) the running max and sum of exp over the visible keys.
+//            MFMA tile with keys on the row axis and queries on the column axis, so a lane owns one query
+//            and reduces over keys in its own registers.  Long contexts with few query rows are split
+//            over the key axis; a small kernel merges the splits and adds ||Q_i||_2.
+//            (Skipped when the caller supplies row max / row sum, as an extended attention kernel would.)
+//   phase 2  column reduction: per (KV head, block of keys) loop over the group's heads and all query
+//            tiles that can see the block, rebuild A = exp2(S*c1 - c_i) from the row statistic
+//            c_i = max_i*log2(e) + log2(sum_i), and reduce over queries.  Queries sit on the MFMA row
+//            axis and keys on the column axis, so a lane owns one key; per-tile partial sums are fp32,
+//            the running column sums are fp64.
+// All contractions are v_mfma_f32_32x32x16_f16 on the raw fp16 Q and K (exact products, fp32 accumulate);
+// the softmax scale is applied to the fp32 result.
+#include "common.h"
+
+namespace antkv {
+
+namespace {
+
+constexpr int kAsThreads = 512;   // 8 waves
+
+// MFMA operand for 32 rows x 128 channels: lane (r = lane%32, kh = lane/32) holds, for each of the
+// 8 k-steps s, the 8 channels 16*s + 8*kh .. +7 of row r.
+struct Tile128 {
+    half8_t v[8];
+};
+
+__device__ __forceinline__ void load_tile(Tile128& t, const half_t* row_ptr, int kh)
+{
+#pragma unroll
+    for (int s = 0; s < 8; ++s) t.v[s] = *(const half8_t*)(row_ptr + 16 * s + 8 * kh);
+}
+
+__device__ __forceinline__ float16_t tile_dot(const Tile128& a, const Tile128& b)
+{
+    float16_t acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a.v[s], b.v[s], acc, 0, 0, 0);
+    return acc;
+}
+
+// -------------------------------------------------------------------------------------------------
+// phase 1: partial row statistics.  grid = (key splits, query blocks of 64, B*Hkv); 8 waves =
+// 4 heads of the group (G <= 4 per pass; larger groups loop) x 2 query tiles of 32.
+// part: [B][Hq][Nq][KS][2] = (max in log2 units, sum of exp2)
+// -------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kAsThreads) void ans_row_stats(
+    const half_t* __restrict__ q, const half_t* __restrict__ k, int64_t N, int64_t Nq, float c1,
+    float* __restrict__ part, int Hq, int Hkv, int G, int KS, int64_t keys_per_split)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 31, kh = lane >> 5;
+    const int ks = blockIdx.x;
+    const int64_t qblk = blockIdx.y;
+    const int b = blockIdx.z / Hkv, g = blockIdx.z % Hkv;
+    const int64_t q0 = qblk * 64 + (wave >> 2) * 32;           // first query row of this wave's tile
+    if (q0 >= Nq) return;
+    const int64_t qi = q0 + n;                                  // this lane's query row
+    const int64_t qrow = qi < Nq ? qi : Nq - 1;
+    const int64_t qpos = N - Nq + qrow;                         // absolute position = last visible key
+    const int64_t tile_last_pos = N - Nq + ((q0 + 31 < Nq) ? q0 + 31 : Nq - 1);
+    const int64_t k_lo = (int64_t)ks * keys_per_split;
+    int64_t k_hi = k_lo + keys_per_split;
+    if (k_hi > tile_last_pos + 1) k_hi = tile_last_pos + 1;
+    const half_t* kbase = k + ((int64_t)b * Hkv + g) * N * kD;
+
+    for (int hh = (wave & 3); hh < G; hh += 4) {
+        const int h = g * G + hh;
+        Tile128 tq;
+        load_tile(tq, q + (((int64_t)b * Hq + h) * Nq + qrow) * kD, kh);
+        float m_run = kNegBig, l_run = 0.f;
+        for (int64_t kt = k_lo; kt < k_hi; kt += 32) {
+            const int64_t krow = (kt + n < N) ? kt + n : N - 1;
+            Tile128 tk;
+            load_tile(tk, kbase + krow * kD, kh);
+            const float16_t acc = tile_dot(tk, tq);             // rows = keys, cols = queries
+            float s2[16];
+            float mx = kNegBig;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t key = kt + 8 * (r >> 2) + 4 * kh + (r & 3);
+                const bool vis = (key <= qpos) && (key < k_hi);
+                s2[r] = vis ? acc[r] * c1 : kNegBig;
+                mx = fmaxf(mx, s2[r]);
+            }
+            const float m_new = fmaxf(m_run, mx);
+            float sum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum += fast_exp2(s2[r] - m_new);
+            // all-masked so far: m_new stays at kNegBig and exp2(0) terms must not count
+            if (m_new <= kNegBig) sum = 0.f;
+            l_run = l_run * fast_exp2(m_run - m_new) + sum;
+            m_run = m_new;
+        }
+        // merge the two half-waves (they saw complementary keys of the same query)
+        const float m_o = __shfl_xor(m_run, 32, 64), l_o = __shfl_xor(l_run, 32, 64);
+        const float m_f = fmaxf(m_run, m_o);
+        const float l_f = l_run * fast_exp2(m_run - m_f) + l_o * fast_exp2(m_o - m_f);
+        if (kh == 0 && qi < Nq) {
+            float* p = part + ((((int64_t)b * Hq + h) * Nq + qi) * KS + ks) * 2;
+            p[0] = m_f;
+            p[1] = l_f;
+        }
+    }
+}
+
+// merge key splits -> c_i = m + log2(l); also ||Q_i||_2.  One 16-lane group per (b, h, i).
+__global__ __launch_bounds__(256) void ans_finalize_stats(
+    const half_t* __restrict__ q, const float* __restrict__ part, int KS, const float* __restrict__ row_max,
+    const float* __restrict__ row_sum, float* __restrict__ c_out, float* __restrict__ nq_out, int64_t n_rows)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t row = t >> 4;
+    const int part_i = (int)(t & 15);
+    if (row >= n_rows) return;
+    const half8_t v = *(const half8_t*)(q + row * kD + part_i * 8);
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s = fmaf((float)v[e], (float)v[e], s);
+#pragma unroll
+    for (int off = 8; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (part_i != 0) return;
+    nq_out[row] = sqrtf(s);
+    if (row_max) {
+        c_out[row] = row_max[row] * kLog2e + log2f(row_sum[row]);
+    } else {
+        float m = kNegBig;
+        for (int i = 0; i < KS; ++i) m = fmaxf(m, part[(row * KS + i) * 2]);
+        float l = 0.f;
+        for (int i = 0; i < KS; ++i) l += part[(row * KS + i) * 2 + 1] * exp2f(part[(row * KS + i) * 2] - m);
+        c_out[row] = m + log2f(l);
+    }
+}
+
+// -------------------------------------------------------------------------------------------------
+// phase 2: column reduction.  grid = (key blocks of 256, B*Hkv); each of the 8 waves owns 32 keys.
+// -------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kAsThreads) void ans_col_reduce(
+    const half_t* __restrict__ q, const half_t* __restrict__ k, int64_t N, int64_t Nq, float c1,
+    const float* __restrict__ c_row, const float* __restrict__ nq_row, float* __restrict__ ans_k,
+    float* __restrict__ ans_v, int Hq, int Hkv, int G)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 31, kh = lane >> 5;
+    const int b = blockIdx.y / Hkv, g = blockIdx.y % Hkv;
+    const int64_t k0 = (int64_t)blockIdx.x * 256 + wave * 32;   // first key of this wave
+    if (k0 >= N) return;
+    const int64_t key = k0 + n;
+    const int64_t krow = key < N ? key : N - 1;
+    Tile128 tk;
+    load_tile(tk, k + (((int64_t)b * Hkv + g) * N + krow) * kD, kh);
+    // first query row that can see key k0:  N - Nq + i >= k0
+    int64_t i_first = k0 - (N - Nq);
+    if (i_first < 0) i_first = 0;
+    i_first &= ~(int64_t)31;
+    double sum_v = 0.0, sum_k = 0.0;
+    for (int hh = 0; hh < G; ++hh) {
+        const int h = g * G + hh;
+        const int64_t rbase = ((int64_t)b * Hq + h) * Nq;
+        for (int64_t i0 = i_first; i0 < Nq; i0 += 32) {
+            const int64_t qrow = (i0 + n < Nq) ? i0 + n : Nq - 1;
+            Tile128 tq;
+            load_tile(tq, q + (rbase + qrow) * kD, kh);
+            const float16_t acc = tile_dot(tq, tk);             // rows = queries, cols = keys
+            float pv = 0.f, pk = 0.f;
+            const bool diag = (N - Nq + i0) < (k0 + 31);        // some query of the tile cannot see some key
+            const bool tail = (i0 + 32 > Nq) || (Nq & 3);          // vector loads of the row statistics need alignment
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                const int64_t ib = i0 + 8 * qd + 4 * kh;         // rows ib .. ib+3 live in acc[4qd .. 4qd+3]
+                float cr[4], nr[4];
+                if (!tail) {
+                    const float4_t c4 = *(const float4_t*)(c_row + rbase + ib);
+                    const float4_t n4 = *(const float4_t*)(nq_row + rbase + ib);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { cr[e] = c4[e]; nr[e] = n4[e]; }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const bool ok = ib + e < Nq;
+                        cr[e] = ok ? c_row[rbase + ib + e] : 3.0e38f;   // exp2(-huge) = 0 for rows past the end
+                        nr[e] = ok ? nq_row[rbase + ib + e] : 0.f;
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float arg = fmaf(acc[4 * qd + e], c1, -cr[e]);
+                    if (diag && (N - Nq + ib + e) < key) arg = -3.0e38f;   // causal mask
+                    const float a = fast_exp2(arg);
+                    const float t = a * nr[e];
+                    pv += a;
+                    pk += fmaf(-a, t, t);
+                }
+            }
+            sum_v += (double)pv;
+            sum_k += (double)pk;
+        }
+    }
+    // lanes l and l+32 hold complementary query rows of the same key
+    const double ov = __shfl_xor(sum_v, 32, 64), ok = __shfl_xor(sum_k, 32, 64);
+    if (kh == 0 && key < N) {
+        const int64_t o = ((int64_t)b * Hkv + g) * N + key;
+        ans_v[o] = (float)(sum_v + ov);
+        ans_k[o] = (float)(sum_k + ok);
+    }
+}
+
+struct AsPlan {
+    int KS;
+    int64_t keys_per_split;
+    size_t off_part, off_c, off_nq, off_ans_k, off_ans_v, total;
+};
+
+AsPlan plan(const Geom& g, int64_t N, int64_t Nq)
+{
+    AsPlan p;
+    const int64_t qblocks = (Nq + 63) / 64;
+    const int64_t base_wgs = (int64_t)g.B * g.Hkv * qblocks;
+    int64_t ks = (1024 + base_wgs - 1) / base_wgs;
+    const int64_t max_ks = (N + 4095) / 4096;
+    if (ks > max_ks) ks = max_ks;
+    if (ks < 1) ks = 1;
+    int64_t per = (N + ks - 1) / ks;
+    per = (per + 31) / 32 * 32;
+    p.keys_per_split = per;
+    p.KS = (int)((N + per - 1) / per);
+    const size_t rows = (size_t)g.B * g.Hq * Nq;
+    size_t off = 0;
+    p.off_part = off; off += align_up(rows * p.KS * 2 * sizeof(float));
+    p.off_c = off;    off += align_up(rows * sizeof(float) + 16);
+    p.off_nq = off;   off += align_up(rows * sizeof(float) + 16);
+    p.off_ans_k = off; off += align_up((size_t)g.B * g.Hkv * N * sizeof(float));
+    p.off_ans_v = off; off += align_up((size_t)g.B * g.Hkv * N * sizeof(float));
+    p.total = off;
+    return p;
+}
+
+}  // namespace
+
+size_t anchor_score_workspace_bytes(const Geom& g, int64_t N, int64_t Nq) { return plan(g, N, Nq).total; }
+
+// ans_k / ans_v may be NULL: the scores then live in the workspace at the offsets of the plan.
+hipError_t launch_anchor_score(const Geom& g, const half_t* q, const half_t* k, int64_t N, int64_t Nq, float scale,
+                               const float* row_max, const float* row_sum, float* ans_k, float* ans_v, void* ws,
+                               hipStream_t st)
+{
+    const AsPlan p = plan(g, N, Nq);
+    char* w = (char*)ws;
+    float* part = (float*)(w + p.off_part);
+    float* c_row = (float*)(w + p.off_c);
+    float* nq_row = (float*)(w + p.off_nq);
+    if (!ans_k) ans_k = (float*)(w + p.off_ans_k);
+    if (!ans_v) ans_v = (float*)(w + p.off_ans_v);
+    const float c1 = scale * kLog2e;
+    const int64_t rows = (int64_t)g.B * g.Hq * Nq;
+    if (!row_max) {
+        dim3 grid((unsigned)p.KS, (unsigned)((Nq + 63) / 64), (unsigned)(g.B * g.Hkv));
+        hipLaunchKernelGGL(ans_row_stats, grid, dim3(kAsThreads), 0, st, q, k, N, Nq, c1, part, g.Hq, g.Hkv, g.G,
+                           p.KS, p.keys_per_split);
+    }
+    hipLaunchKernelGGL(ans_finalize_stats, dim3((unsigned)((rows * 16 + 255) / 256)), dim3(256), 0, st, q, part, p.KS,
+                       row_max, row_sum, c_row, nq_row, rows);
+    dim3 grid2((unsigned)((N + 255) / 256), (unsigned)(g.B * g.Hkv));
+    hipLaunchKernelGGL(ans_col_reduce, grid2, dim3(kAsThreads), 0, st, q, k, N, Nq, c1, c_row, nq_row, ans_k, ans_v,
+                       g.Hq, g.Hkv, g.G);
+    return hipGetLastError();
+}
+
+}  // namespace antkv

@@ -1,0 +1,217 @@
+// extern "C" boundary of the AnTKV library: argument validation, workspace layout, kernel launches.
+#include "common.h"
+
+using namespace antkv;
+
+namespace {
+
+int check_geom(const antkv_geom* gm, Geom& g)
+{
+    if (!gm) return ANTKV_EINVAL;
+    if (gm->B < 0 || gm->Hq <= 0 || gm->Hkv <= 0 || gm->D <= 0 || gm->d_sub <= 0 || gm->n_centroids <= 0)
+        return ANTKV_EINVAL;
+    if (gm->Hq % gm->Hkv != 0) return ANTKV_EINVAL;
+    if (gm->D != kD || gm->n_centroids != kC) return ANTKV_EUNSUPPORTED;
+    if (gm->d_sub != 4 && gm->d_sub != 8 && gm->d_sub != 16) return ANTKV_EUNSUPPORTED;
+    const int G = gm->Hq / gm->Hkv;
+    if (G != 1 && G != 2 && G != 4) return ANTKV_EUNSUPPORTED;
+    if ((int64_t)gm->B * gm->Hkv > 65535) return ANTKV_EUNSUPPORTED;
+    g.B = gm->B; g.Hq = gm->Hq; g.Hkv = gm->Hkv; g.G = G; g.d = gm->d_sub; g.M = kD / gm->d_sub;
+    return ANTKV_OK;
+}
+
+inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+struct SelPlan {
+    size_t off_score, off_topk, total;
+};
+
+SelPlan sel_plan(const Geom& g, int64_t N, int64_t Nq, int64_t k)
+{
+    SelPlan p;
+    p.off_score = 0;
+    p.off_topk = align_up(anchor_score_workspace_bytes(g, N, Nq));
+    p.total = p.off_topk + align_up(topk_workspace_bytes((int64_t)g.B * g.Hkv, N, k));
+    return p;
+}
+
+struct DecPlan {
+    size_t off_dec, off_topk, total;
+};
+
+DecPlan dec_plan(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, int64_t k_resel, bool want_ans)
+{
+    DecPlan p;
+    p.off_dec = 0;
+    p.off_topk = align_up(decode_workspace_bytes(g, N, k_k, k_v, want_ans));
+    p.total = p.off_topk + (k_resel > 0 ? align_up(topk_workspace_bytes((int64_t)g.B * g.Hkv, N, k_resel)) : 0);
+    return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int antkv_version(void) { return 1; }
+
+const char* antkv_strerror(int code)
+{
+    switch (code) {
+    case ANTKV_OK: return "ok";
+    case ANTKV_EINVAL: return "invalid argument";
+    case ANTKV_EUNSUPPORTED: return "unsupported geometry";
+    case ANTKV_EWORKSPACE: return "workspace missing or too small";
+    case ANTKV_ELAUNCH: return "HIP launch failed";
+    default: return "unknown error";
+    }
+}
+
+int antkv_encode(const antkv_geom* geom, const void* x, int64_t xs_b, int64_t xs_h, int64_t xs_t, int64_t n_tok,
+                 const void* codebook, uint8_t* codes, int64_t N_cap, int64_t token_offset, void* stream)
+{
+    Geom g;
+    int rc = check_geom(geom, g);
+    if (rc) return rc;
+    if (n_tok < 0 || N_cap < 0 || token_offset < 0 || token_offset + n_tok > N_cap) return ANTKV_EINVAL;
+    if (n_tok == 0 || g.B == 0) return ANTKV_OK;
+    if (!x || !codebook || !codes) return ANTKV_EINVAL;
+    if (misaligned(x, 16) || misaligned(codebook, 16) || misaligned(codes, 16)) return ANTKV_EINVAL;
+    if (xs_t < kD || (xs_b & 7) || (xs_h & 7) || (xs_t & 7) || xs_b < 0 || xs_h < 0) return ANTKV_EINVAL;
+    hipError_t e = launch_encode(g, (const half_t*)x, xs_b, xs_h, xs_t, n_tok, (const half_t*)codebook, codes, N_cap,
+                                 token_offset, (hipStream_t)stream);
+    return e == hipSuccess ? ANTKV_OK : ANTKV_ELAUNCH;
+}
+
+size_t antkv_topk_workspace(int64_t n_rows, int64_t N, int64_t k)
+{
+    if (n_rows < 0 || N < 0 || k < 0) return 0;
+    return topk_workspace_bytes(n_rows, N, k);
+}
+
+int antkv_topk(const float* scores, int64_t n_rows, int64_t N, int64_t k, int32_t* idx, void* workspace,
+               size_t workspace_bytes, void* stream)
+{
+    if (n_rows < 0 || N < 0 || k < 0 || k > N || N > 0x7fffffffLL || n_rows > 65535) return ANTKV_EINVAL;
+    if (k == 0 || n_rows == 0) return ANTKV_OK;
+    if (!scores || !idx) return ANTKV_EINVAL;
+    if (!workspace || misaligned(workspace, 256) || workspace_bytes < topk_workspace_bytes(n_rows, N, k))
+        return ANTKV_EWORKSPACE;
+    hipError_t e = launch_topk(scores, n_rows, N, k, idx, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? ANTKV_OK : ANTKV_ELAUNCH;
+}
+
+size_t antkv_anchor_select_workspace(const antkv_geom* geom, int64_t N, int64_t Nq, int64_t k)
+{
+    Geom g;
+    if (check_geom(geom, g) || N <= 0 || Nq <= 0 || Nq > N || k < 0) return 0;
+    return sel_plan(g, N, Nq, k).total;
+}
+
+int antkv_anchor_select(const antkv_geom* geom, const void* q, const void* k_fp16, int64_t N, int64_t Nq, float scale,
+                        int64_t k, const float* row_max, const float* row_sum, float* ans_k, float* ans_v,
+                        int32_t* idx_k, int32_t* idx_v, void* workspace, size_t workspace_bytes, void* stream)
+{
+    Geom g;
+    int rc = check_geom(geom, g);
+    if (rc) return rc;
+    if (N <= 0 || Nq <= 0 || Nq > N || k < 0 || k > N || N > 0x7fffffffLL) return ANTKV_EINVAL;
+    if ((row_max == nullptr) != (row_sum == nullptr)) return ANTKV_EINVAL;
+    if (g.B == 0) return ANTKV_OK;
+    if (!q || !k_fp16) return ANTKV_EINVAL;
+    if (misaligned(q, 16) || misaligned(k_fp16, 16)) return ANTKV_EINVAL;
+    if (!(scale > 0.f)) return ANTKV_EINVAL;
+    const SelPlan sp = sel_plan(g, N, Nq, k);
+    if (!workspace || misaligned(workspace, 256) || workspace_bytes < sp.total) return ANTKV_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    char* w = (char*)workspace;
+    // scores default to the tail of the score workspace
+    const size_t as_bytes = anchor_score_workspace_bytes(g, N, Nq);
+    const size_t score_bytes = align_up((size_t)g.B * g.Hkv * N * sizeof(float));
+    float* sk = ans_k ? ans_k : (float*)(w + as_bytes - 2 * score_bytes);
+    float* sv = ans_v ? ans_v : (float*)(w + as_bytes - score_bytes);
+    hipError_t e = launch_anchor_score(g, (const half_t*)q, (const half_t*)k_fp16, N, Nq, scale, row_max, row_sum, sk, sv,
+                                       w + sp.off_score, st);
+    if (e != hipSuccess) return ANTKV_ELAUNCH;
+    const int64_t rows = (int64_t)g.B * g.Hkv;
+    if (idx_k && k > 0) {
+        e = launch_topk(sk, rows, N, k, idx_k, w + sp.off_topk, st);
+        if (e != hipSuccess) return ANTKV_ELAUNCH;
+    }
+    if (idx_v && k > 0) {
+        e = launch_topk(sv, rows, N, k, idx_v, w + sp.off_topk, st);
+        if (e != hipSuccess) return ANTKV_ELAUNCH;
+    }
+    return ANTKV_OK;
+}
+
+int antkv_gather_rows(const antkv_geom* geom, const void* x, int64_t N, const int32_t* idx, int64_t k, void* rows_out,
+                      void* stream)
+{
+    Geom g;
+    int rc = check_geom(geom, g);
+    if (rc) return rc;
+    if (N < 0 || k < 0 || k > N) return ANTKV_EINVAL;
+    if (k == 0 || g.B == 0) return ANTKV_OK;
+    if (!x || !idx || !rows_out || misaligned(x, 16) || misaligned(rows_out, 16)) return ANTKV_EINVAL;
+    hipError_t e = launch_gather_rows(g, (const half_t*)x, N, idx, k, (half_t*)rows_out, (hipStream_t)stream);
+    return e == hipSuccess ? ANTKV_OK : ANTKV_ELAUNCH;
+}
+
+size_t antkv_decode_attn_workspace(const antkv_geom* geom, int64_t N, int64_t k_k, int64_t k_v, int64_t k_resel)
+{
+    Geom g;
+    if (check_geom(geom, g) || N < 0 || k_k < 0 || k_v < 0 || k_resel < 0) return 0;
+    return dec_plan(g, N, k_k, k_v, k_resel, true).total;
+}
+
+int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const uint8_t* codes_k,
+                      const uint8_t* codes_v, int64_t N, int64_t N_cap, const void* cb_k, const void* cb_v,
+                      const int32_t* idx_k, const void* rows_k, int64_t k_k, const int32_t* idx_v, const void* rows_v,
+                      int64_t k_v, void* out, float* ans_k, float* ans_v, int32_t* resel_idx_k, int32_t* resel_idx_v,
+                      int64_t k_resel, void* workspace, size_t workspace_bytes, void* stream)
+{
+    Geom g;
+    int rc = check_geom(geom, g);
+    if (rc) return rc;
+    if (N < 0 || N_cap < N || k_k < 0 || k_v < 0 || k_k > N || k_v > N || k_resel < 0 || k_resel > N ||
+        N > 0x7fffffffLL)
+        return ANTKV_EINVAL;
+    if (g.B == 0) return ANTKV_OK;
+    if (!q || !out || misaligned(q, 16) || misaligned(out, 16)) return ANTKV_EINVAL;
+    if (!(scale > 0.f)) return ANTKV_EINVAL;
+    if (N > 0) {
+        if (!codes_k || !codes_v || !cb_k || !cb_v) return ANTKV_EINVAL;
+        if (misaligned(codes_k, 16) || misaligned(codes_v, 16) || misaligned(cb_k, 16) || misaligned(cb_v, 16))
+            return ANTKV_EINVAL;
+        if (k_k > 0 && (!idx_k || !rows_k || misaligned(rows_k, 16))) return ANTKV_EINVAL;
+        if (k_v > 0 && (!idx_v || !rows_v || misaligned(rows_v, 16))) return ANTKV_EINVAL;
+    }
+    if ((resel_idx_k && !ans_k) || (resel_idx_v && !ans_v)) return ANTKV_EINVAL;
+    const bool want_ans = ans_k || ans_v;
+    if (want_ans && !(ans_k && ans_v)) return ANTKV_EINVAL;   // the two scores are produced together
+    const DecPlan dp = dec_plan(g, N, k_k, k_v, k_resel, true);
+    if (N > 0 && (!workspace || misaligned(workspace, 256) || workspace_bytes < dp.total)) return ANTKV_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    DecodeArgs a;
+    a.q = (const half_t*)q; a.scale = scale; a.codes_k = codes_k; a.codes_v = codes_v; a.N = N; a.N_cap = N_cap;
+    a.cb_k = (const half_t*)cb_k; a.cb_v = (const half_t*)cb_v; a.idx_k = idx_k; a.rows_k = (const half_t*)rows_k;
+    a.k_k = k_k; a.idx_v = idx_v; a.rows_v = (const half_t*)rows_v; a.k_v = k_v; a.out = (half_t*)out;
+    a.ans_k = ans_k; a.ans_v = ans_v;
+    hipError_t e = launch_decode_attn(g, a, workspace, st);
+    if (e != hipSuccess) return ANTKV_ELAUNCH;
+    if (N > 0 && k_resel > 0) {
+        char* w = (char*)workspace;
+        const int64_t rows = (int64_t)g.B * g.Hkv;
+        if (resel_idx_k) {
+            e = launch_topk(ans_k, rows, N, k_resel, resel_idx_k, w + dp.off_topk, st);
+            if (e != hipSuccess) return ANTKV_ELAUNCH;
+        }
+        if (resel_idx_v) {
+            e = launch_topk(ans_v, rows, N, k_resel, resel_idx_v, w + dp.off_topk, st);
+            if (e != hipSuccess) return ANTKV_ELAUNCH;
+        }
+    }
+    return ANTKV_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,98 @@
+// Shared declarations of the AnTKV HIP library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/antkv.h"
+
+namespace antkv {
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t uint2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kD = 128;          // head dim
+constexpr int kC = 256;          // centroids per sub-space
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kNegBig = -1.0e30f;   // stands for -inf in running maxima (exp2 of it is 0)
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// ---- device helpers -------------------------------------------------------------------------
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// order-preserving map float -> uint32 (larger float <=> larger key), any finite sign
+__device__ __forceinline__ uint32_t float_key(float f)
+{
+    uint32_t b = __float_as_uint(f);
+    return b ^ ((uint32_t)((int32_t)b >> 31) | 0x80000000u);
+}
+
+// ---- launchers (each enqueues on `stream` and returns a hipError_t) --------------------------
+struct Geom {
+    int B, Hq, Hkv, G, d, M;
+};
+
+hipError_t launch_encode(const Geom& g, const half_t* x, int64_t xs_b, int64_t xs_h, int64_t xs_t,
+                         int64_t n_tok, const half_t* cb, uint8_t* codes, int64_t N_cap,
+                         int64_t token_offset, hipStream_t st);
+
+size_t topk_workspace_bytes(int64_t n_rows, int64_t N, int64_t k);
+hipError_t launch_topk(const float* scores, int64_t n_rows, int64_t N, int64_t k, int32_t* idx,
+                       void* ws, hipStream_t st);
+
+hipError_t launch_gather_rows(const Geom& g, const half_t* x, int64_t N, const int32_t* idx,
+                              int64_t k, half_t* rows, hipStream_t st);
+
+size_t anchor_score_workspace_bytes(const Geom& g, int64_t N, int64_t Nq);
+hipError_t launch_anchor_score(const Geom& g, const half_t* q, const half_t* k, int64_t N, int64_t Nq,
+                               float scale, const float* row_max, const float* row_sum,
+                               float* ans_k, float* ans_v, void* ws, hipStream_t st);
+
+struct DecodeArgs {
+    const half_t* q;
+    float scale;
+    const uint8_t *codes_k, *codes_v;
+    int64_t N, N_cap;
+    const half_t *cb_k, *cb_v;
+    const int32_t* idx_k;
+    const half_t* rows_k;
+    int64_t k_k;
+    const int32_t* idx_v;
+    const half_t* rows_v;
+    int64_t k_v;
+    half_t* out;
+    float *ans_k, *ans_v;
+};
+int decode_num_splits(const Geom& g, int64_t N);
+size_t decode_workspace_bytes(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans);
+hipError_t launch_decode_attn(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st);
+
+}  // namespace antkv

@@ -1,0 +1,55 @@
+"""Helpers shared by the GPU parity tests: device transfer and the comparison rules.
+
+Comparison rules (the bar the HIP path is held to):
+  * codes and anchor index sets are bit-exact against the oracle, except for candidates whose oracle
+    margin is below 1e-6 (near-ties that fp32 and fp64 arithmetic may legitimately order differently);
+    those are counted and reported separately.
+  * attention outputs: relative L2 error per (b, head) row <= 2e-3 against the fp64 oracle.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+NEAR_TIE = 1e-6
+ATTN_TOL = 2e-3
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def rel_l2_rows(got: np.ndarray, want: np.ndarray) -> np.ndarray:
+    got = got.astype(np.float64).reshape(-1, got.shape[-1])
+    want = want.astype(np.float64).reshape(-1, want.shape[-1])
+    den = np.linalg.norm(want, axis=1)
+    den[den == 0] = 1.0
+    return np.linalg.norm(got - want, axis=1) / den
+
+
+def check_codes(got: np.ndarray, want: np.ndarray, margin: np.ndarray, what: str = "codes") -> int:
+    """Bit-exact outside the near-tie list; returns the number of near-tie disagreements."""
+    bad = got.astype(np.int64) != want.astype(np.int64)
+    hard = bad & (margin >= NEAR_TIE)
+    assert not hard.any(), (f"{what}: {int(hard.sum())} mismatches outside the near-tie list "
+                            f"(smallest margin {margin[hard].min():.3e}); {int(bad.sum())} in total")
+    return int(bad.sum())
+
+
+def check_index_sets(got: np.ndarray, want: np.ndarray, margin: np.ndarray, what: str = "indices") -> int:
+    """got/want [..., k] ascending index sets, margin [..., N].  Differences must be near-ties."""
+    k = want.shape[-1]
+    assert got.shape == want.shape, (got.shape, want.shape)
+    g2 = got.reshape(-1, k)
+    w2 = want.reshape(-1, k)
+    m2 = margin.reshape(g2.shape[0], -1)
+    soft = 0
+    for r in range(g2.shape[0]):
+        assert k == 0 or np.all(np.diff(g2[r]) > 0), f"{what}: row {r} is not strictly ascending"
+        diff = np.setxor1d(g2[r], w2[r])
+        if diff.size:
+            worst = m2[r][diff].max()
+            assert worst < NEAR_TIE, (f"{what}: row {r} differs in {diff.size} positions, "
+                                      f"largest oracle margin {worst:.3e} >= {NEAR_TIE}")
+            soft += diff.size
+    return soft

