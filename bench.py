@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the AnTKV online path on one MI355X.
+
+Headline (the metric's 128K-context configuration, "cfg2"): decode attention over a VQ-coded KV cache with
+1 % FP16 anchors, batch 4 x 8 KV heads x 131072 tokens, 1-bit VQ.  One step = one antkv_decode_attn call
+(one decode token per sequence, one layer).  The cache is built by the library itself from seeded synthetic
+K/V: encode -> Anchor Score over a 32-query window -> top-1 % -> gather.  Timed steps rotate over several
+distinct copies of the cache so that no buffer is re-read out of the 256 MB last-level cache; the warm
+(single-copy) rate is reported beside it.  Encode and anchor-selection rates on the 32768-token prefill
+shape ("cfg3") are reported as extras.
+
+Prints one JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(w, k_k, k_v):
+    """Bytes one decode step must read/write: codes + anchor rows + anchor indices + codebooks + q/out."""
+    per_bg = w.N * w.M * 2 + (k_k + k_v) * (w.D * 2 + 4)
+    return w.B * w.Hkv * per_bg + 2 * w.Hkv * w.M * w.C * w.d_sub * 2 + 2 * w.B * w.Hq * w.D * 2
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2", help="decode workload: cfg0 | cfg1 | cfg2 | cfg4")
+    ap.add_argument("--copies", type=int, default=8, help="distinct cache copies the timed steps rotate over")
+    ap.add_argument("--no-extras", action="store_true", help="skip encode / anchor-select rates and the CPU baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path is a single-GPU kernel path; "
+              "see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2506_19505_amd as antkv
+    from workloads import (CONFIGS, make_codebooks, make_decode_query, make_qkv, normal_fp16, random_anchor_sets,
+                           random_codes)
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    antkv.load_library()
+    devc = torch.device("cuda:0")
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(devc)
+    w = CONFIGS[args.workload]
+    geom = antkv.Geometry(w.B, w.Hq, w.Hkv, w.d_sub)
+
+    # ------------------------------------------------------------------ build the cache with the library
+    t_setup = time.time()
+    qwin, k, v = make_qkv(w.seed, w.B, w.Hq, w.Hkv, w.N, min(w.Nq_select, 32), w.D)
+    log(f"generated K/V {k.shape} in {time.time() - t_setup:.1f}s")
+    cbk, cbv = make_codebooks(w.seed, k, w.d_sub, w.C, "k"), make_codebooks(w.seed, v, w.d_sub, w.C, "v")
+    log(f"codebooks done at {time.time() - t_setup:.1f}s")
+    kd, vd, cbk_d, cbv_d = dev(k), dev(v), dev(cbk), dev(cbv)
+    del k, v
+    codes_k, codes_v = antkv.encode(geom, kd, cbk_d), antkv.encode(geom, vd, cbv_d)
+    idx_k, idx_v, _, _ = antkv.anchor_select(geom, dev(qwin), kd, w.scale, w.k, want_scores=False)
+    rows_k, rows_v = antkv.gather_rows(geom, kd, idx_k), antkv.gather_rows(geom, vd, idx_v)
+    torch.cuda.synchronize()
+    del kd, vd
+    torch.cuda.empty_cache()
+    q = dev(make_decode_query(w.seed, w.B, w.Hq, w.D))
+    out = torch.empty((w.B, w.Hq, w.D), dtype=torch.float16, device=devc)
+    caches = [(codes_k, codes_v, idx_k, rows_k, idx_v, rows_v)]
+    for _ in range(max(args.copies, 1) - 1):
+        caches.append(tuple(t.clone() for t in caches[0]))
+    ws = antkv.DecodeWorkspace(geom, w.N, w.k, w.k, 0, devc)
+    log(f"cache ready at {time.time() - t_setup:.1f}s ({len(caches)} copies)")
+
+    def step(i):
+        ck, cv, ik, rk, iv, rv = caches[i % len(caches)]
+        antkv.decode_attn(geom, q, w.scale, ck, cv, cbk_d, cbv_d, ik, rk, iv, rv, out=out, workspace=ws)
+
+    def timed(n, fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n   # ms per call
+
+    for i in range(args.warmup):
+        step(i)
+    ms_step = timed(args.steps, step)                          # headline: rotating over the cache copies
+    ms_warm = timed(args.steps, lambda i: step(0))             # same buffers every step (cache-warm)
+
+    # dominant kernel alone, with HIP events recorded by the library around that launch on its stream
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for a, b in pairs:
+        a.record(); b.record()                                 # create the underlying HIP events
+    torch.cuda.synchronize()
+    for i, (a, b) in enumerate(pairs):
+        antkv.profile_next_decode(a, b)
+        step(i)
+    torch.cuda.synchronize()
+    ms_kernel = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
+
+    abytes = algorithmic_bytes(w, w.k, w.k)
+    achieved = abytes / (ms_kernel * 1e-3) / 1e9
+    result = {
+        "metric": "decode-attn tokens/s at 128K ctx + achieved HBM GB/s (% peak); encode Mvec/s",
+        "value": w.B * w.N / (ms_step * 1e-3),
+        "unit": "context tokens/s (one layer, all KV heads)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8 codes, f16 tables, f32 accumulate",
+        "data": "synthetic (seeded N(0,1) K/V with channel outliers, k-means++ codebooks; stands in for LLaMA-3-8B / "
+                "Mistral-7B KV caches)",
+        "config": {"workload": f"{w.name}: {w.description}", "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "N": w.N,
+                   "d_sub": w.d_sub, "bits_per_element": w.bits_per_element, "anchors_per_head": w.k,
+                   "cache_copies_rotated": len(caches)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "decode_attn_kernel",
+                     "kernel_ms": ms_kernel, "algorithmic_bytes": abytes},
+        "extra": {"decode_steps_per_s": w.B / (ms_step * 1e-3), "ms_per_step_warm": ms_warm,
+                  "tokens_per_s_warm": w.B * w.N / (ms_warm * 1e-3),
+                  "step_GBs": abytes / (ms_step * 1e-3) / 1e9, "step_frac_of_peak": abytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+    }
+    log(f"decode: {ms_step * 1e3:.1f} us/step rotating, {ms_warm * 1e3:.1f} us warm, kernel {ms_kernel * 1e3:.1f} us "
+        f"-> {achieved:.0f} GB/s ({100 * achieved / HBM_PEAK_GBS:.1f}% of peak)")
+
+    if not args.no_extras:
+        # ------------------------------------------------------------ encode + anchor selection on the prefill shape
+        del caches, codes_k, codes_v, rows_k, rows_v
+        torch.cuda.empty_cache()
+        p = CONFIGS["cfg3"]
+        pg = antkv.Geometry(p.B, p.Hq, p.Hkv, p.d_sub)
+        pq, pk, pv = make_qkv(p.seed, p.B, p.Hq, p.Hkv, p.N, p.N, p.D)
+        pcbk, pcbv = make_codebooks(p.seed, pk, p.d_sub, p.C, "k", max_sample=4096), make_codebooks(p.seed, pv, p.d_sub, p.C, "v", max_sample=4096)
+        pkd, pvd, pqd, pcbk_d, pcbv_d = dev(pk), dev(pv), dev(pq), dev(pcbk), dev(pcbv)
+        ck = torch.empty((p.B, p.Hkv, p.N, p.M), dtype=torch.uint8, device=devc)
+        cv = torch.empty_like(ck)
+
+        def enc(i):
+            antkv.encode(pg, pkd, pcbk_d, codes=ck)
+            antkv.encode(pg, pvd, pcbv_d, codes=cv)
+        enc(0)
+        ms_enc = timed(20, enc)
+        n_vec = 2 * p.B * p.Hkv * p.N
+        antkv.anchor_select(pg, pqd, pkd, p.scale, p.k, want_scores=False)
+        ms_sel = timed(3, lambda i: antkv.anchor_select(pg, pqd, pkd, p.scale, p.k, want_scores=False))
+        result["extra"].update({
+            "encode_Mvec_per_s": n_vec / (ms_enc * 1e-3) / 1e6, "encode_ms": ms_enc,
+            "encode_input_GBs": n_vec * 256 / (ms_enc * 1e-3) / 1e9,
+            "encode_workload": f"cfg3: K and V of {p.N} tokens x {p.Hkv} KV heads, d_sub {p.d_sub} ({n_vec} vectors)",
+            "anchor_select_ms": ms_sel,
+            "anchor_select_TFLOPs": 2 * 2.0 * p.B * p.Hq * (p.N * (p.N + 1) / 2) * p.D / (ms_sel * 1e-3) / 1e12,
+            "anchor_select_workload": f"cfg3: Nq = N = {p.N}, {p.Hq} query heads, top-{p.k} for K and V (two QK^T passes)",
+        })
+        log(f"encode {result['extra']['encode_Mvec_per_s']:.0f} Mvec/s ({ms_enc * 1e3:.0f} us); anchor select {ms_sel:.2f} ms")
+        del pkd, pvd, pqd
+        torch.cuda.empty_cache()
+
+        # ------------------------------------------------------------ CPU baseline: the oracle, as it stands
+        import oracle
+        oracle.build()
+        sB = 1                                                  # bounded sample: one sequence of the decode workload
+        c = dict(q=make_decode_query(w.seed, sB, w.Hq, w.D),
+                 ck=random_codes(w.seed, "k", sB, w.Hkv, w.N, w.M), cv=random_codes(w.seed, "v", sB, w.Hkv, w.N, w.M),
+                 ik=random_anchor_sets(w.seed, "k", sB, w.Hkv, w.N, w.k), iv=random_anchor_sets(w.seed, "v", sB, w.Hkv, w.N, w.k),
+                 rk=normal_fp16(w.seed, "rows_k", (sB, w.Hkv, w.k, w.D)), rv=normal_fp16(w.seed, "rows_v", (sB, w.Hkv, w.k, w.D)))
+        t0 = time.time()
+        oracle.decode_attn(c["q"], c["ck"], c["cv"], cbk, cbv, c["ik"], c["rk"], c["iv"], c["rv"], w.scale)
+        t_cpu = time.time() - t0
+        result["cpu_baseline"] = {"value": sB * w.N / t_cpu, "unit": "context tokens/s (one layer, all KV heads)",
+                                  "cores": oracle.num_threads(), "kind": "oracle",
+                                  "sample": f"one decode step of one sequence of {w.name} (N={w.N}, {w.Hkv} KV heads, "
+                                            f"{w.k} anchors/head, cache-shaped random codes): {t_cpu:.2f} s wall incl. "
+                                            f"fp16->fp32 widening"}
+        log(f"cpu oracle: {t_cpu:.2f}s on {oracle.num_threads()} threads")
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

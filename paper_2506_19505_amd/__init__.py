@@ -6,6 +6,7 @@ binding without a built library, or calling it without a GPU, raises.
 """
 from .binding import (
     AntkvError,
+    DecodeWorkspace,
     Geometry,
     anchor_select,
     decode_attn,
@@ -13,12 +14,14 @@ from .binding import (
     gather_rows,
     lib_path,
     load_library,
+    profile_next_decode,
     topk,
     version,
 )
 
 __all__ = [
     "AntkvError",
+    "DecodeWorkspace",
     "Geometry",
     "anchor_select",
     "decode_attn",
@@ -26,6 +29,7 @@ __all__ = [
     "gather_rows",
     "lib_path",
     "load_library",
+    "profile_next_decode",
     "topk",
     "version",
 ]

@@ -14,6 +14,7 @@ _lib = None
 EXPORTS = (
     "antkv_version", "antkv_strerror", "antkv_encode", "antkv_anchor_select_workspace", "antkv_anchor_select",
     "antkv_topk_workspace", "antkv_topk", "antkv_gather_rows", "antkv_decode_attn_workspace", "antkv_decode_attn",
+    "antkv_profile_next_decode",
 )
 
 
@@ -78,6 +79,8 @@ def load_library():
         lib.antkv_decode_attn.restype = ctypes.c_int
         lib.antkv_decode_attn.argtypes = [gp, vp, f32, vp, vp, i64, i64, vp, vp, vp, vp, i64, vp, vp, i64, vp,
                                           vp, vp, vp, vp, i64, vp, sz, vp]
+        lib.antkv_profile_next_decode.restype = None
+        lib.antkv_profile_next_decode.argtypes = [vp, vp]
         _lib = lib
     return _lib
 
@@ -179,6 +182,12 @@ def gather_rows(geom: Geometry, x: torch.Tensor, idx: torch.Tensor) -> torch.Ten
     rc = load_library().antkv_gather_rows(ctypes.byref(g), _p(x), N, _p(idx), k, _p(rows), _stream(x))
     _check(rc, "antkv_gather_rows")
     return rows
+
+
+def profile_next_decode(start: "torch.cuda.Event | None", stop: "torch.cuda.Event | None") -> None:
+    """antkv_profile_next_decode: record the two (already created) timing events around the next decode kernel."""
+    h = lambda e: None if e is None else ctypes.c_void_p(e.cuda_event)
+    load_library().antkv_profile_next_decode(h(start), h(stop))
 
 
 class DecodeWorkspace:

@@ -157,6 +157,11 @@ int antkv_gather_rows(const antkv_geom* geom, const void* x, int64_t N, const in
     return e == hipSuccess ? ANTKV_OK : ANTKV_ELAUNCH;
 }
 
+void antkv_profile_next_decode(void* start_event, void* stop_event)
+{
+    decode_profile_next((hipEvent_t)start_event, (hipEvent_t)stop_event);
+}
+
 size_t antkv_decode_attn_workspace(const antkv_geom* geom, int64_t N, int64_t k_k, int64_t k_v, int64_t k_resel)
 {
     Geom g;

@@ -13,6 +13,7 @@ typedef _Float16 half_t;
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef short short2_t __attribute__((ext_vector_type(2)));
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
@@ -92,6 +93,7 @@ struct DecodeArgs {
     float *ans_k, *ans_v;
 };
 int decode_num_splits(const Geom& g, int64_t N);
+void decode_profile_next(hipEvent_t start, hipEvent_t stop);
 size_t decode_workspace_bytes(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans);
 hipError_t launch_decode_attn(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st);
 

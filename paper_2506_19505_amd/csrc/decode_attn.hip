@@ -5,10 +5,10 @@
 // One launch holds two kinds of workgroups (8 waves each):
 //
 //  * stream workgroups own a contiguous token range of one (sequence, KV head).  They build the
-//    q.centroid lookup table LUT[m][c][head] (fp16, pre-multiplied by scale*log2e) and copy the V
+//    q.centroid lookup table LUT[m][c][head] (16-bit fixed point, pre-multiplied by scale*log2e) and copy the V
 //    codebook into LDS once, then every wave walks over 64-token tiles:
 //      K side  one lane per token: 16-byte coalesced code loads, one 8-byte LUT gather per sub-space
-//              serves the group's four query heads, fp32 accumulation;
+//              serves the group's four query heads, exact integer accumulation;
 //      softmax base-2 online softmax against a lazily updated reference maximum (the wave only pays
 //              the cross-lane reduction when some score exceeds the reference);
 //      V side  P (fp16) goes through a 512-byte LDS staging buffer into MFMA A-operand layout; V
@@ -128,7 +128,7 @@ struct DaParams {
 template <int DSUB>
 struct Lds {
     static constexpr int M = kD / DSUB;
-    static constexpr int lut = 0;                                  // [M][256][4] fp16
+    static constexpr int lut = 0;                                  // [M][256][4] int16
     static constexpr int cbv = lut + M * 256 * 8;                  // [M][256][DSUB] fp16 = 64 KB
     static constexpr int pst = cbv + 65536;                        // [waves][4][64] fp16
     static constexpr int qf = pst + kDaWaves * 512;                // [4][128] fp32
@@ -254,10 +254,14 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             if (lane == 0) s_misc[wave] = r;
         }
         __syncthreads();
-        {   // LUT[m][c][h] = c1 * q_h[m*d : (m+1)*d] . cb_k[g][m][c]
+        // LUT[m][c][h] = c1 * q_h[m*d : (m+1)*d] . cb_k[g][m][c], stored as 16-bit fixed point with one scale per
+        // head (quantum = max|LUT_h| / 32767): the per-token sum over sub-spaces is then exact integer arithmetic
+        // and the table error is uniform instead of growing with the entry's magnitude as it would in fp16.
+        float lut_q[kNH];
+        {
             const half_t* cbk = p.cb_k + (size_t)g * 32768;
-            half4_t* s_lut = (half4_t*)(smem + L::lut);
-            for (int e = tid; e < M * 256; e += kDaThreads) {
+            // one table entry (4 heads) in fp32; evaluated twice (range pass, quantise pass) to keep registers low
+            auto entry = [&](int e, float (&val)[kNH]) {
                 const int m = e >> 8;
                 float cen[DSUB];
                 if (DSUB == 4) {
@@ -272,15 +276,47 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                         for (int t = 0; t < 8; ++t) cen[8 * u + t] = (float)v[t];
                     }
                 }
-                half4_t o;
 #pragma unroll
                 for (int h = 0; h < kNH; ++h) {
-                    float s = 0.f;
+                    float sdot = 0.f;
 #pragma unroll
-                    for (int t = 0; t < DSUB; ++t) s = fmaf(s_qf[h * kD + m * DSUB + t], cen[t], s);
-                    o[h] = (half_t)(s * p.c1);
+                    for (int t = 0; t < DSUB; ++t) sdot = fmaf(s_qf[h * kD + m * DSUB + t], cen[t], sdot);
+                    val[h] = sdot * p.c1;
                 }
-                s_lut[e] = o;
+            };
+            float amax[kNH] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+            for (int e = tid; e < M * 256; e += kDaThreads) {
+                float val[kNH];
+                entry(e, val);
+#pragma unroll
+                for (int h = 0; h < kNH; ++h) amax[h] = fmaxf(amax[h], fabsf(val[h]));
+            }
+            float* s_red = (float*)(smem + L::red);
+#pragma unroll
+            for (int h = 0; h < kNH; ++h) {
+                const float wm = wave_max_uniform(amax[h]);
+                if (lane == 0) s_red[wave * 8 + h] = wm;
+            }
+            __syncthreads();
+            float inv_q[kNH];
+#pragma unroll
+            for (int h = 0; h < kNH; ++h) {
+                float r = 0.f;
+                for (int wv = 0; wv < kDaWaves; ++wv) r = fmaxf(r, s_red[wv * 8 + h]);
+                lut_q[h] = (r > 0.f) ? r / 32767.0f : 1.0f;
+                inv_q[h] = (r > 0.f) ? 32767.0f / r : 0.f;
+            }
+            uint2_t* s_lut = (uint2_t*)(smem + L::lut);
+#pragma unroll 1
+            for (int e = tid; e < M * 256; e += kDaThreads) {
+                float val[kNH];
+                entry(e, val);
+                int qv[kNH];
+#pragma unroll
+                for (int h = 0; h < kNH; ++h) qv[h] = (int)rintf(val[h] * inv_q[h]);
+                s_lut[e] = uint2_t{((uint32_t)qv[0] & 0xffffu) | ((uint32_t)qv[1] << 16),
+                                   ((uint32_t)qv[2] & 0xffffu) | ((uint32_t)qv[3] << 16)};
             }
             // bitmap of anchored tokens in this range
             const int lo_k = s_misc[0], hi_k = s_misc[1], lo_v = s_misc[2], hi_v = s_misc[3];
@@ -329,14 +365,20 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             const bool masked = !in_range || ((s_mask[(rel >> 5) & (L::mask_words - 1)] >> (rel & 31)) & 1u);
 
             // ---- K side: scores in log2 units
-            float s[kNH] = {0.f, 0.f, 0.f, 0.f};
+            int si[kNH] = {0, 0, 0, 0};
 #pragma unroll
             for (int m = 0; m < M; ++m) {
                 const uint32_t code = (kw[m >> 2] >> (8 * (m & 3))) & 255u;
-                const half4_t e = *(const half4_t*)(smem + L::lut + (m * 256 + code) * 8);
-#pragma unroll
-                for (int h = 0; h < kNH; ++h) s[h] += (float)e[h];
+                const uint2_t e = *(const uint2_t*)(smem + L::lut + (m * 256 + code) * 8);
+                // plain integer half-word adds (the sdot2 builtin mis-compiles here: it drops the second dword)
+                si[0] += (int)(short)(e[0] & 0xffffu);
+                si[1] += ((int)e[0]) >> 16;
+                si[2] += (int)(short)(e[1] & 0xffffu);
+                si[3] += ((int)e[1]) >> 16;
             }
+            float s[kNH];
+#pragma unroll
+            for (int h = 0; h < kNH; ++h) s[h] = (float)si[h] * lut_q[h];
             bool grow = false;
 #pragma unroll
             for (int h = 0; h < kNH; ++h) {
@@ -758,6 +800,9 @@ __global__ __launch_bounds__(64) void decode_ans_lse_kernel(const float* __restr
     lse2[bh] = m + log2f(l);
 }
 
+// measurement aid: events to record around the next code-stream kernel launched from this host thread
+thread_local hipEvent_t t_ev_start = nullptr, t_ev_stop = nullptr;
+
 struct DaPlan {
     int S, A;
     int64_t chunk;
@@ -793,6 +838,12 @@ DaPlan da_plan(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans
 
 int decode_num_splits(const Geom& g, int64_t N) { return da_plan(g, N, 0, 0, false).S; }
 
+void decode_profile_next(hipEvent_t start, hipEvent_t stop)
+{
+    t_ev_start = start;
+    t_ev_stop = stop;
+}
+
 size_t decode_workspace_bytes(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans)
 {
     return da_plan(g, N, k_k, k_v, want_ans).total;
@@ -815,7 +866,10 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     hipError_t e = hipFuncSetAttribute((const void*)decode_attn_kernel<DSUB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((int64_t)g.B * g.Hkv * (pl.S + pl.A));
+    if (t_ev_start) (void)hipEventRecord(t_ev_start, st);
     hipLaunchKernelGGL(decode_attn_kernel<DSUB>, dim3(grid), dim3(kDaThreads), shmem, st, p);
+    if (t_ev_stop) (void)hipEventRecord(t_ev_stop, st);
+    t_ev_start = t_ev_stop = nullptr;
     hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)(g.B * g.Hq)), dim3(128), 0, st, part, pl.S + pl.A, a.out);
     if (want_ans) {
         DsParams d;

@@ -40,6 +40,8 @@ def check_index_sets(got: np.ndarray, want: np.ndarray, margin: np.ndarray, what
     """got/want [..., k] ascending index sets, margin [..., N].  Differences must be near-ties."""
     k = want.shape[-1]
     assert got.shape == want.shape, (got.shape, want.shape)
+    if k == 0:
+        return 0
     g2 = got.reshape(-1, k)
     w2 = want.reshape(-1, k)
     m2 = margin.reshape(g2.shape[0], -1)
