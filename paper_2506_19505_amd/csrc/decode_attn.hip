@@ -2,11 +2,15 @@
 // Fig. 2(b): anchor tokens stay FP16, every other token is read from its codes), and the decode-time
 // Anchor Score (Sec. 3.2 last paragraph: Eq. (4) evaluated for the single decode query).
 //
-// One launch holds two kinds of workgroups (8 waves each):
+// A workgroup (16 waves) owns a contiguous token range of one (sequence, KV head).
 //
-//  * stream workgroups own a contiguous token range of one (sequence, KV head).  They build the
-//    q.centroid lookup table LUT[m][c][head] (16-bit fixed point, pre-multiplied by scale*log2e) and copy the V
-//    codebook into LDS once, then every wave walks over 64-token tiles:
+//  prologue  build the q.centroid lookup table LUT[code][slot][head] (16-bit fixed point, pre-multiplied by
+//            scale*log2e), copy the V codebook into LDS, mark the anchored tokens of the range in an LDS bitmap.
+//            The table is stored with 32 eight-byte slots per code row (= all 64 LDS banks); slot j holds
+//            sub-space j mod M.  Lane l reads slot (step XOR (l mod 32)) at every step, i.e. it walks the
+//            sub-spaces in its own XOR-permuted order: the 32 lanes that the LDS serves per clock always hit
+//            32 different bank pairs, whatever the codes are (random gathers would run at a third of that).
+//  stream    waves pull 64-token tiles from a shared counter, code loads running one tile ahead:
 //      K side  one lane per token: 16-byte coalesced code loads, one 8-byte LUT gather per sub-space
 //              serves the group's four query heads, exact integer accumulation;
 //      softmax base-2 online softmax against a lazily updated reference maximum (the wave only pays
@@ -15,28 +19,34 @@
 //              centroids are fetched from the LDS codebook with ds_read_b64_tr_b16, whose lane
 //              transposition yields the MFMA B operand (tokens along k) directly;
 //              v_mfma_f32_16x16x32_f16 accumulates P.V in fp32.
-//    Tokens that have an FP16 anchor row (for K or for V) are masked out of the stream via an LDS bitmap.
+//      Tokens that have an FP16 anchor row (for K or for V) are masked out of the stream.
+//  anchors   the first kAnchorWaves waves start on the anchor lists instead (then join the stream): the
+//            lists of the (sequence, KV head) are cut into 32-token tiles dealt round-robin to the workgroups
+//            (balanced by list index, not by position: anchors cluster at the head and tail of a context).
+//            A wave stages K_eff rows (the FP16 row, or the de-quantised codes when only V of that token is
+//            anchored) in its own LDS tile, scores them with one MFMA chain, stages V_eff rows and accumulates
+//            P.V through the same transposed-read + MFMA path.  This latency-bound work overlaps the
+//            LDS-bound stream of the other waves.
 //
-//  * anchor workgroups take 32-token tiles of the anchor lists (balanced by list index, not by position):
-//    they stage K_eff / V_eff rows (the FP16 row, or the de-quantised codes when only the other tensor
-//    of that token is anchored) in LDS and run the same two MFMA contractions on dense rows.
-//
-// Every workgroup writes one partial (reference max, sum, accumulator) per query head; a second kernel
-// merges the partials by log-sum-exp and rounds once to fp16.
+// The workgroup merges its waves and writes one partial (reference max, sum, accumulator) per query head;
+// the last workgroup of a (sequence, KV head) to finish merges the partials by log-sum-exp and rounds once
+// to fp16, so the whole step is one kernel behind a small counter-clearing launch.
 #include "common.h"
 
 namespace antkv {
 
 namespace {
 
-constexpr int kDaWaves = 8;
+#ifndef ANTKV_DA_WAVES
+#define ANTKV_DA_WAVES 16
+#endif
+constexpr int kDaWaves = ANTKV_DA_WAVES;
 constexpr int kDaThreads = kDaWaves * 64;
 constexpr int kNH = 4;                 // query-head slots per workgroup (group size G <= 4)
 constexpr float kPShift = 8.0f;        // P is scaled by 2^8 so that small weights stay normal in fp16
+constexpr int kAnchorWaves = 2;        // waves that work through the anchor lists before joining the stream
 constexpr float kEmptyRef = -1.0e4f;   // softmax reference before any token was seen: finite, below every real score,
                                        // and far above the masked score kNegBig so that exp2(masked - ref) is 0
-constexpr int kAnchorTilesPerWave = 1;
-constexpr int kAnchorTilesPerWg = kDaWaves * kAnchorTilesPerWave;
 
 typedef __attribute__((address_space(3))) char lds_char;
 typedef __attribute__((address_space(3))) short4_t lds_short4;
@@ -46,11 +56,28 @@ __device__ __forceinline__ half4_t lds_read_tr16(const lds_char* base, uint32_t 
     const short4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(base + off));
     return __builtin_bit_cast(half4_t, v);
 }
+// same, from an absolute LDS byte address (lets the caller fold the array base into a per-lane constant
+// and keeps compile-time addends in the instruction's immediate offset)
+__device__ __forceinline__ half4_t lds_read_tr16_abs(uint32_t addr)
+{
+    const short4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(uintptr_t)addr);
+    return __builtin_bit_cast(half4_t, v);
+}
 
 template <int SRC>
 __device__ __forceinline__ uint32_t quad_bcast(uint32_t x)
 {
     return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, SRC * 0x55, 0xf, 0xf, true);
+}
+
+__device__ __forceinline__ uint32_t quad_bcast_sel(uint32_t x, int src)
+{
+    switch (src) {
+    case 0: return quad_bcast<0>(x);
+    case 1: return quad_bcast<1>(x);
+    case 2: return quad_bcast<2>(x);
+    default: return quad_bcast<3>(x);
+    }
 }
 
 // max over the 64 lanes, result uniform
@@ -67,7 +94,15 @@ __device__ __forceinline__ float wave_max_uniform(float v)
     return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 
-// sum over each row of 16 lanes, result in all 16 lanes
+// max / sum over each row of 16 lanes, result in all 16 lanes of the row
+__device__ __forceinline__ float row16_max(float v)
+{
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, true)));
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, true)));
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x141, 0xf, 0xf, true)));
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x140, 0xf, 0xf, true)));
+    return v;
+}
 __device__ __forceinline__ float row16_sum(float v)
 {
     v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, true));
@@ -75,6 +110,10 @@ __device__ __forceinline__ float row16_sum(float v)
     v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x141, 0xf, 0xf, true));
     v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x140, 0xf, 0xf, true));
     return v;
+}
+__device__ __forceinline__ float lane_bcast(float v, int src_lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), src_lane));
 }
 
 // first index in arr[0..n) whose value is >= key; executed by a whole wave, result uniform
@@ -114,62 +153,70 @@ struct DaParams {
     const half_t *cb_k, *cb_v;
     const int32_t *idx_k, *idx_v;
     const half_t *rows_k, *rows_v;
-    float* part;                // [B][Hq][slots][kD + 2]
+    float* part;                // [B][Hq][S][kD + 2]
+    half_t* out;                // [B][Hq][kD]
+    unsigned int* done;         // [B][Hkv] arrival counters, zero at launch; the last workgroup of a (b, g) merges
     int64_t N, N_cap;
     int k_k, k_v;
     float c1;                   // scale * log2(e)
     int Hq, Hkv, G;
-    int S;                      // stream splits per (b, g)
-    int A;                      // anchor workgroups per (b, g)
-    int64_t chunk;              // tokens per stream split (multiple of 64)
+    int S;                      // workgroups (token ranges) per (b, g)
+    int64_t chunk;              // tokens per range (multiple of 64)
+    unsigned long long* trace;  // ANTKV_DA_TRACE builds: [grid][4] wall-clock stamps (100 MHz), else unused
 };
 
-// LDS layout (bytes).  The stream layout and the anchor layout overlap; a workgroup uses one of them.
+#ifdef ANTKV_DA_TRACE
+#define DA_STAMP(i) do { if (threadIdx.x == 0) p.trace[(size_t)blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define DA_STAMP(i) do { } while (0)
+#endif
+
+// LDS layout (bytes); the final merge re-uses the table area.
 template <int DSUB>
 struct Lds {
     static constexpr int M = kD / DSUB;
-    static constexpr int lut = 0;                                  // [M][256][4] int16
-    static constexpr int cbv = lut + M * 256 * 8;                  // [M][256][DSUB] fp16 = 64 KB
-    static constexpr int pst = cbv + 65536;                        // [waves][4][64] fp16
+    static constexpr int lut = 0;                                  // [256 codes][32 slots][4] int16 = 64 KB
+    static constexpr int cbv = lut + 65536;                        // [M][256][DSUB] fp16 = 64 KB
+    static constexpr int stage = cbv + 65536;                      // [anchor waves][32][128] fp16 (8 KB each)
+    static constexpr int mrg = 0;                                  // merge: [waves][4][128] fp32 (2 KB per wave)
+    static constexpr int pst = stage + kAnchorWaves * 8192;        // [waves][4][64] fp16
     static constexpr int qf = pst + kDaWaves * 512;                // [4][128] fp32
-    static constexpr int red = qf + 2048;                          // [waves][8] fp32 + misc ints
+    static constexpr int qh = qf + 2048;                           // [4][128] fp16 (MFMA operand source)
+    static constexpr int red = qh + 1024;                          // [waves][8] fp32 + 16 ints
     static constexpr int mask = red + kDaWaves * 32 + 64;          // bitmap over the token range
-    static constexpr int mask_words = 1024;                        // up to 32768 tokens per split
-    static constexpr int stream_total = mask + mask_words * 4;
-    // anchor layout: per wave a 32 x 128 fp16 row tile (8 KB) + P staging + slot table
-    static constexpr int a_rows = 0;                               // [waves][32][128] fp16
-    static constexpr int a_pst = a_rows + kDaWaves * 8192;         // [waves][4][32] fp16
-    static constexpr int a_qf = a_pst + kDaWaves * 256;
-    static constexpr int a_red = a_qf + 2048;
-    static constexpr int anchor_total = a_red + kDaWaves * 32 + 64;
-    static constexpr int total = stream_total > anchor_total ? stream_total : anchor_total;
-    // merge buffer re-uses the front of LDS after the main loop: [waves][4][128] fp32 = 32 KB
-    static constexpr int mrg = 0;
+    static constexpr int mask_words = 1024;                        // up to 32768 tokens per range
+    static constexpr int total = mask + mask_words * 4;
+    static_assert(total <= 163840, "LDS budget of one CU");
 };
 
-// Merge the 16 waves' (m_ref, l, acc) into one partial and write it.  acc is in MFMA C layout:
+// Merge the waves' (m_ref, l, acc) into one partial and write it.  acc is in MFMA C layout:
 // lanes 0..15 of a wave hold, for slab c and register r, head r and channel 16c + lane.
 template <int DSUB>
 __device__ void wg_merge_and_store(char* smem, float (&m_ref)[kNH], float (&l_sum)[kNH], float4_t (&acc)[8],
-                                   float* __restrict__ part_bg, int slot, int slots, int nheads, int red_off)
+                                   float* __restrict__ part_bg, int slot, int slots, int nheads,
+                                   unsigned long long* trace_slot = nullptr)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    float* s_red = (float*)(smem + red_off);
-    __syncthreads();   // everyone is done with the tables in LDS
+    float* s_red = (float*)(smem + Lds<DSUB>::red);
+    __syncthreads();   // everyone is done with the staging area
+#ifdef ANTKV_DA_TRACE
+    if (threadIdx.x == 0 && trace_slot) *trace_slot = wall_clock64();
+#endif
     if (lane == 0) {
 #pragma unroll
         for (int h = 0; h < kNH; ++h) { s_red[wave * 8 + h] = m_ref[h]; s_red[wave * 8 + 4 + h] = l_sum[h]; }
     }
     __syncthreads();
+    static_assert(kDaWaves <= 16, "one row of 16 lanes covers the waves");
     float m_all[kNH], l_all[kNH];
+    {
+        const int hh = lane >> 4, ws = lane & 15;               // this lane looks at (head hh, wave ws)
+        const float m_w = (ws < kDaWaves) ? s_red[ws * 8 + hh] : kNegBig;
+        const float l_w = (ws < kDaWaves) ? s_red[ws * 8 + 4 + hh] : 0.f;
+        const float m_r = row16_max(m_w);
+        const float l_r = row16_sum(l_w * fast_exp2(m_w - m_r));
 #pragma unroll
-    for (int h = 0; h < kNH; ++h) {
-        float m = kNegBig;
-        for (int w = 0; w < kDaWaves; ++w) m = fmaxf(m, s_red[w * 8 + h]);
-        float l = 0.f;
-        for (int w = 0; w < kDaWaves; ++w) l += s_red[w * 8 + 4 + h] * fast_exp2(s_red[w * 8 + h] - m);
-        m_all[h] = m;
-        l_all[h] = l;
+        for (int h = 0; h < kNH; ++h) { m_all[h] = lane_bcast(m_r, 16 * h); l_all[h] = lane_bcast(l_r, 16 * h); }
     }
     float* s_mrg = (float*)(smem + Lds<DSUB>::mrg);
     if (lane < 16) {
@@ -186,8 +233,13 @@ __device__ void wg_merge_and_store(char* smem, float (&m_ref)[kNH], float (&l_su
             float s = 0.f;
             for (int w = 0; w < kDaWaves; ++w) s += s_mrg[(w * kNH + h) * kD + dim];
             float* dst = part_bg + ((int64_t)h * slots + slot) * (kD + 2);
-            dst[dim] = s;
-            if (dim == 0) { dst[kD] = m_all[h]; dst[kD + 1] = l_all[h]; }
+            // Device-scope stores: they write through this die's L2, so the merging workgroup (possibly
+            // on another die) can read them without any cache write-back.
+            __hip_atomic_store(dst + dim, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (dim == 0) {
+                __hip_atomic_store(dst + kD, m_all[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(dst + kD + 1, l_all[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
 }
@@ -196,22 +248,190 @@ template <int DSUB>
 __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams p)
 {
     constexpr int M = kD / DSUB;
-    constexpr int CW = M / 4;              // code dwords per token
+    constexpr int CW = M / 4;                          // code dwords per token
+    constexpr int EPT = M * 256 / kDaThreads;          // LUT entries per thread
+    static_assert(EPT >= 1 && EPT * kDaThreads == M * 256, "LUT entries must divide evenly over the threads");
     using L = Lds<DSUB>;
     extern __shared__ uint4_t smem_u4[];
     char* smem = (char*)smem_u4;
     const lds_char* lsm = (const lds_char*)smem_u4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int per_bg = p.A + p.S;
-    const int bg = blockIdx.x / per_bg, role = blockIdx.x % per_bg;
+    const int bg = blockIdx.x / p.S, sp = blockIdx.x % p.S;
     const int b = bg / p.Hkv, g = bg % p.Hkv;
     const int nheads = p.G;               // <= kNH
     const int h0 = g * p.G;
-    const int slots = per_bg;
-    float* part_bg = p.part + ((int64_t)b * p.Hq + h0) * slots * (kD + 2);
+    float* part_bg = p.part + ((int64_t)b * p.Hq + h0) * p.S * (kD + 2);
     const half_t* qb = p.q + ((int64_t)b * p.Hq + h0) * kD;
     const int32_t* idx_k = p.idx_k + (int64_t)bg * p.k_k;
     const int32_t* idx_v = p.idx_v + (int64_t)bg * p.k_v;
+    const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * M;
+    const uint8_t* cv = p.codes_v + (int64_t)bg * p.N_cap * M;
+    const half_t* cbk = p.cb_k + (size_t)g * 32768;
+    const half_t* cbv = p.cb_v + (size_t)g * 32768;
+    const int64_t t0 = (int64_t)sp * p.chunk;
+    const int64_t t1 = (t0 + p.chunk < p.N) ? t0 + p.chunk : p.N;
+
+    DA_STAMP(0);
+    // MFMA lane coordinates
+    const int kgrp = lane >> 4;           // tr block / k group
+    const int tj = (lane >> 2) & 3;       // token within a group of four
+    const int tq = lane & 3;              // 8-byte chunk of a 32-byte channel slab / quad lane
+    const int arow = lane & 15;           // A-operand row (head) / C column (channel)
+
+    float* s_qf = (float*)(smem + L::qf);
+    int* s_misc = (int*)(smem + L::red + kDaWaves * 32);
+    uint32_t* s_mask = (uint32_t*)(smem + L::mask);
+
+    // ================================================================================== prologue
+    float lut_q[kNH];
+    {
+        // all global loads of the prologue are issued before anything waits on them.
+        // Threads are grouped by sub-space (TPM threads each) so that a thread reads its q sub-vectors once.
+        // (sub-space fastest across lanes: the table stores of a wave then spread over all LDS banks)
+        constexpr int TPM = kDaThreads / M;               // threads per sub-space
+        static_assert(TPM * M == kDaThreads && TPM * EPT == 256, "thread to LUT-entry mapping");
+        const int lm = tid % M, lc0 = tid / M;            // entries (lm, lc0 + TPM*i), i < EPT
+        uint4_t cen[EPT][DSUB / 8 > 0 ? DSUB / 8 : 1];
+        uint2_t cen4[EPT];
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+            const int e = lm * 256 + lc0 + TPM * i;
+            if (DSUB == 4) cen4[i] = *(const uint2_t*)(cbk + e * 4);
+            else {
+#pragma unroll
+                for (int u = 0; u < DSUB / 8; ++u) cen[i][u] = *(const uint4_t*)(cbk + e * DSUB + 8 * u);
+            }
+        }
+        uint4_t vcopy[4096 / kDaThreads];
+        {
+            const uint4_t* src = (const uint4_t*)cbv;
+#pragma unroll
+            for (int i = 0; i < 4096 / kDaThreads; ++i) vcopy[i] = src[tid + i * kDaThreads];
+        }
+        if (tid < kNH * kD) {
+            const int h = tid >> 7;
+            const half_t qv16 = (h < nheads) ? qb[tid] : (half_t)0.f;
+            s_qf[tid] = (float)qv16;
+            ((half_t*)(smem + L::qh))[tid] = qv16;
+        }
+        for (int i = tid; i < L::mask_words; i += kDaThreads) s_mask[i] = 0u;
+        if (tid == 0) { s_misc[8] = 0; s_misc[9] = 0; }          // next stream tile, next anchor tile of this workgroup
+        // anchored positions of this range: short lists are scanned whole (one load latency), long lists are
+        // cut to the range by a cooperative search first (a few dependent load latencies)
+        constexpr int kScanMax = 8 * kDaThreads;
+        const bool scan_k = p.k_k <= kScanMax, scan_v = p.k_v <= kScanMax;
+        int scan_val[2][8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int j = tid + i * kDaThreads;
+            scan_val[0][i] = (scan_k && j < p.k_k) ? idx_k[j] : -1;
+            scan_val[1][i] = (scan_v && j < p.k_v) ? idx_v[j] : -1;
+        }
+        if (wave < 4) {
+            const int32_t* arr = (wave < 2) ? idx_k : idx_v;
+            const int n = (wave < 2) ? p.k_k : p.k_v;
+            int r = 0;
+            if (!((wave < 2) ? scan_k : scan_v)) r = wave_lower_bound(arr, n, (int)((wave & 1) ? t1 : t0), lane);
+            if (lane == 0) s_misc[wave] = r;
+        }
+        {
+            uint4_t* dst = (uint4_t*)(smem + L::cbv);
+#pragma unroll
+            for (int i = 0; i < 4096 / kDaThreads; ++i) dst[tid + i * kDaThreads] = vcopy[i];
+        }
+        __syncthreads();
+        DA_STAMP(7);
+        // LUT[m][c][h] = c1 * q_h[m*d : (m+1)*d] . cb_k[g][m][c], stored as 16-bit fixed point with one scale per
+        // head (quantum = max|LUT_h| / 32767): the per-token sum over sub-spaces is then exact integer arithmetic
+        // and the table error is uniform instead of growing with the entry's magnitude as it would in fp16.
+        float val[EPT][kNH];
+        float amax[kNH] = {0.f, 0.f, 0.f, 0.f};
+        {
+            float qs[kNH][DSUB];
+#pragma unroll
+            for (int h = 0; h < kNH; ++h)
+#pragma unroll
+                for (int t = 0; t < DSUB; ++t) qs[h][t] = s_qf[h * kD + lm * DSUB + t] * p.c1;
+#pragma unroll
+            for (int i = 0; i < EPT; ++i) {
+                float cf[DSUB];
+                if (DSUB == 4) {
+                    const half4_t v = __builtin_bit_cast(half4_t, cen4[i]);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) cf[t] = (float)v[t];
+                } else {
+#pragma unroll
+                    for (int u = 0; u < DSUB / 8; ++u) {
+                        const half8_t v = __builtin_bit_cast(half8_t, cen[i][u]);
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) cf[8 * u + t] = (float)v[t];
+                    }
+                }
+#pragma unroll
+                for (int h = 0; h < kNH; ++h) {
+                    float sdot = 0.f;
+#pragma unroll
+                    for (int t = 0; t < DSUB; ++t) sdot = fmaf(qs[h][t], cf[t], sdot);
+                    val[i][h] = sdot;
+                    amax[h] = fmaxf(amax[h], fabsf(sdot));
+                }
+            }
+        }
+        float* s_red = (float*)(smem + L::red);
+#pragma unroll
+        for (int h = 0; h < kNH; ++h) {
+            const float wm = wave_max_uniform(amax[h]);
+            if (lane == 0) s_red[wave * 8 + h] = wm;
+        }
+        __syncthreads();
+        float inv_q[kNH];
+        {
+            const int hh = lane >> 4, ws = lane & 15;
+            const float r_r = row16_max((ws < kDaWaves) ? s_red[ws * 8 + hh] : 0.f);
+#pragma unroll
+            for (int h = 0; h < kNH; ++h) {
+                const float r = lane_bcast(r_r, 16 * h);
+                lut_q[h] = (r > 0.f) ? r / 32767.0f : 1.0f;
+                inv_q[h] = (r > 0.f) ? 32767.0f / r : 0.f;
+            }
+        }
+        uint2_t* s_lut = (uint2_t*)(smem + L::lut);
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+            int qv[kNH];
+#pragma unroll
+            for (int h = 0; h < kNH; ++h) qv[h] = (int)rintf(val[i][h] * inv_q[h]);
+            const uint2_t ent = uint2_t{((uint32_t)qv[0] & 0xffffu) | ((uint32_t)qv[1] << 16),
+                                        ((uint32_t)qv[2] & 0xffffu) | ((uint32_t)qv[3] << 16)};
+#pragma unroll
+            for (int rep = 0; rep < 32 / M; ++rep) s_lut[(lc0 + TPM * i) * 32 + lm + M * rep] = ent;
+        }
+        // bitmap of anchored tokens in this range
+#pragma unroll
+        for (int w2 = 0; w2 < 2; ++w2)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int64_t pos_i = scan_val[w2][i];
+                if (pos_i >= t0 && pos_i < t1) {
+                    const int rel = (int)(pos_i - t0);
+                    atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
+                }
+            }
+        if (!scan_k) {
+            for (int i = s_misc[0] + tid; i < s_misc[1]; i += kDaThreads) {
+                const int rel = idx_k[i] - (int)t0;
+                atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
+            }
+        }
+        if (!scan_v) {
+            for (int i = s_misc[2] + tid; i < s_misc[3]; i += kDaThreads) {
+                const int rel = idx_v[i] - (int)t0;
+                atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
+            }
+        }
+    }
+    __syncthreads();
+    DA_STAMP(1);
 
     float m_ref[kNH], l_lane[kNH];
     float4_t acc[8];
@@ -219,299 +439,122 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     for (int h = 0; h < kNH; ++h) { m_ref[h] = kEmptyRef; l_lane[h] = 0.f; }
 #pragma unroll
     for (int c = 0; c < 8; ++c) acc[c] = float4_t{0.f, 0.f, 0.f, 0.f};
+    half_t* s_p = (half_t*)(smem + L::pst) + wave * 256;          // this wave's P staging, [4][64] fp16
 
-    // MFMA lane coordinates
-    const int kgrp = lane >> 4;           // tr block / k group
-    const int tj = (lane >> 2) & 3;       // token within a group of four
-    const int tq = lane & 3;              // 8-byte chunk of a 32-byte channel slab / quad lane
-    const int arow = lane & 15;           // A-operand row (head) / C column (channel)
-
-    if (role >= p.A) {
-        // ======================================================================= stream role
-        const int sp = role - p.A;
-        const int64_t t0 = (int64_t)sp * p.chunk;
-        const int64_t t1 = (t0 + p.chunk < p.N) ? t0 + p.chunk : p.N;
-        float* s_qf = (float*)(smem + L::qf);
-        int* s_misc = (int*)(smem + L::red + kDaWaves * 32);
-        uint32_t* s_mask = (uint32_t*)(smem + L::mask);
-
-        if (tid < kNH * kD) {
-            const int h = tid >> 7;
-            s_qf[tid] = (h < nheads) ? (float)qb[tid] : 0.f;
-        }
-        for (int i = tid; i < L::mask_words; i += kDaThreads) s_mask[i] = 0u;
-        {   // V codebook -> LDS
-            const uint4_t* src = (const uint4_t*)(p.cb_v + (size_t)g * 32768);
-            uint4_t* dst = (uint4_t*)(smem + L::cbv);
-            for (int i = tid; i < 4096; i += kDaThreads) dst[i] = src[i];
-        }
-        // anchor list ranges that fall into [t0, t1)
-        if (wave < 4) {
-            const int32_t* arr = (wave < 2) ? idx_k : idx_v;
-            const int n = (wave < 2) ? p.k_k : p.k_v;
-            const int64_t key = (wave & 1) ? t1 : t0;
-            const int r = wave_lower_bound(arr, n, (int)key, lane);
-            if (lane == 0) s_misc[wave] = r;
-        }
-        __syncthreads();
-        // LUT[m][c][h] = c1 * q_h[m*d : (m+1)*d] . cb_k[g][m][c], stored as 16-bit fixed point with one scale per
-        // head (quantum = max|LUT_h| / 32767): the per-token sum over sub-spaces is then exact integer arithmetic
-        // and the table error is uniform instead of growing with the entry's magnitude as it would in fp16.
-        float lut_q[kNH];
-        {
-            const half_t* cbk = p.cb_k + (size_t)g * 32768;
-            // one table entry (4 heads) in fp32; evaluated twice (range pass, quantise pass) to keep registers low
-            auto entry = [&](int e, float (&val)[kNH]) {
-                const int m = e >> 8;
-                float cen[DSUB];
-                if (DSUB == 4) {
-                    const half4_t v = *(const half4_t*)(cbk + e * 4);
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) cen[t] = (float)v[t];
-                } else {
-#pragma unroll
-                    for (int u = 0; u < DSUB / 8; ++u) {
-                        const half8_t v = *(const half8_t*)(cbk + e * DSUB + 8 * u);
-#pragma unroll
-                        for (int t = 0; t < 8; ++t) cen[8 * u + t] = (float)v[t];
-                    }
-                }
-#pragma unroll
-                for (int h = 0; h < kNH; ++h) {
-                    float sdot = 0.f;
-#pragma unroll
-                    for (int t = 0; t < DSUB; ++t) sdot = fmaf(s_qf[h * kD + m * DSUB + t], cen[t], sdot);
-                    val[h] = sdot * p.c1;
-                }
-            };
-            float amax[kNH] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 1
-            for (int e = tid; e < M * 256; e += kDaThreads) {
-                float val[kNH];
-                entry(e, val);
-#pragma unroll
-                for (int h = 0; h < kNH; ++h) amax[h] = fmaxf(amax[h], fabsf(val[h]));
-            }
-            float* s_red = (float*)(smem + L::red);
-#pragma unroll
-            for (int h = 0; h < kNH; ++h) {
-                const float wm = wave_max_uniform(amax[h]);
-                if (lane == 0) s_red[wave * 8 + h] = wm;
-            }
-            __syncthreads();
-            float inv_q[kNH];
-#pragma unroll
-            for (int h = 0; h < kNH; ++h) {
-                float r = 0.f;
-                for (int wv = 0; wv < kDaWaves; ++wv) r = fmaxf(r, s_red[wv * 8 + h]);
-                lut_q[h] = (r > 0.f) ? r / 32767.0f : 1.0f;
-                inv_q[h] = (r > 0.f) ? 32767.0f / r : 0.f;
-            }
-            uint2_t* s_lut = (uint2_t*)(smem + L::lut);
-#pragma unroll 1
-            for (int e = tid; e < M * 256; e += kDaThreads) {
-                float val[kNH];
-                entry(e, val);
-                int qv[kNH];
-#pragma unroll
-                for (int h = 0; h < kNH; ++h) qv[h] = (int)rintf(val[h] * inv_q[h]);
-                s_lut[e] = uint2_t{((uint32_t)qv[0] & 0xffffu) | ((uint32_t)qv[1] << 16),
-                                   ((uint32_t)qv[2] & 0xffffu) | ((uint32_t)qv[3] << 16)};
-            }
-            // bitmap of anchored tokens in this range
-            const int lo_k = s_misc[0], hi_k = s_misc[1], lo_v = s_misc[2], hi_v = s_misc[3];
-            for (int i = lo_k + tid; i < hi_k; i += kDaThreads) {
-                const int rel = idx_k[i] - (int)t0;
-                atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
-            }
-            for (int i = lo_v + tid; i < hi_v; i += kDaThreads) {
-                const int rel = idx_v[i] - (int)t0;
-                atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
-            }
-        }
-        __syncthreads();
-
-        // lane -> token position inside a 64-token tile, chosen so that the four lanes of a quad hold
-        // the V codes of exactly the four tokens whose centroids that quad must fetch for the MFMA
-        const int pos = 32 * (tq >> 1) + 8 * kgrp + 4 * (tq & 1) + tj;
-        half_t* s_p = (half_t*)(smem + L::pst) + wave * 256;          // [4][64]
-        const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * M;
-        const uint8_t* cv = p.codes_v + (int64_t)bg * p.N_cap * M;
-        // V gather address pieces (bytes): ((m*256 + code)*DSUB + within)*2
-        uint32_t v_lane_off, v_shift_lane;
-        if (DSUB == 8) { v_lane_off = (tq >> 1) * 4096 + (tq & 1) * 8; v_shift_lane = 8 * (tq >> 1); }
-        else if (DSUB == 4) { v_lane_off = tq * 2048; v_shift_lane = 8 * tq; }
-        else { v_lane_off = tq * 8; v_shift_lane = 0; }
-        v_lane_off += L::cbv;
-
-        const int64_t n_tiles = (t1 - t0 + 63) >> 6;
-        for (int64_t tile = wave; tile < n_tiles; tile += kDaWaves) {
-            const int64_t tok = t0 + tile * 64 + pos;
-            const bool in_range = tok < t1;
-            const int64_t ltok = in_range ? tok : (p.N - 1);
-            uint32_t kw[CW], vw[CW];
-            if (CW == 2) {
-                const uint2_t a = *(const uint2_t*)(ck + ltok * M), c = *(const uint2_t*)(cv + ltok * M);
-                kw[0] = a[0]; kw[1] = a[1]; vw[0] = c[0]; vw[1] = c[1];
-            } else {
-#pragma unroll
-                for (int i = 0; i < CW / 4; ++i) {
-                    const uint4_t a = *(const uint4_t*)(ck + ltok * M + 16 * i), c = *(const uint4_t*)(cv + ltok * M + 16 * i);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) { kw[4 * i + e] = a[e]; vw[4 * i + e] = c[e]; }
-                }
-            }
-            const int rel = (int)(tok - t0);
-            const bool masked = !in_range || ((s_mask[(rel >> 5) & (L::mask_words - 1)] >> (rel & 31)) & 1u);
-
-            // ---- K side: scores in log2 units
-            int si[kNH] = {0, 0, 0, 0};
-#pragma unroll
-            for (int m = 0; m < M; ++m) {
-                const uint32_t code = (kw[m >> 2] >> (8 * (m & 3))) & 255u;
-                const uint2_t e = *(const uint2_t*)(smem + L::lut + (m * 256 + code) * 8);
-                // plain integer half-word adds (the sdot2 builtin mis-compiles here: it drops the second dword)
-                si[0] += (int)(short)(e[0] & 0xffffu);
-                si[1] += ((int)e[0]) >> 16;
-                si[2] += (int)(short)(e[1] & 0xffffu);
-                si[3] += ((int)e[1]) >> 16;
-            }
-            float s[kNH];
-#pragma unroll
-            for (int h = 0; h < kNH; ++h) s[h] = (float)si[h] * lut_q[h];
-            bool grow = false;
-#pragma unroll
-            for (int h = 0; h < kNH; ++h) {
-                s[h] = masked ? kNegBig : s[h];
-                grow = grow || (s[h] > m_ref[h] + kPShift);
-            }
-            if (__any(grow)) {   // some score exceeds the running maximum: move the reference, rescale
-#pragma unroll
-                for (int h = 0; h < kNH; ++h) {
-                    const float mx = wave_max_uniform(s[h]);
-                    const float m_new = fmaxf(m_ref[h], mx - kPShift);
-                    const float alpha = fast_exp2(m_ref[h] - m_new);
-                    l_lane[h] *= alpha;
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) acc[c][h] *= alpha;
-                    m_ref[h] = m_new;
-                }
-            }
-            float pw[kNH];
-#pragma unroll
-            for (int h = 0; h < kNH; ++h) {
-                pw[h] = fast_exp2(s[h] - m_ref[h]);
-                l_lane[h] += pw[h];
-                s_p[h * 64 + pos] = (half_t)pw[h];
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-
-            // ---- V side
-            // V codes of the quad's four tokens: quad lane 2u+hi holds token (u, hi)
-            uint32_t vq[4][CW];
-#pragma unroll
-            for (int i = 0; i < CW; ++i) {
-                vq[0][i] = quad_bcast<0>(vw[i]);
-                vq[1][i] = quad_bcast<1>(vw[i]);
-                vq[2][i] = quad_bcast<2>(vw[i]);
-                vq[3][i] = quad_bcast<3>(vw[i]);
-            }
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                half8_t pa = *(const half8_t*)(s_p + (arow & 3) * 64 + 32 * u + 8 * kgrp);
-                if (arow >= kNH) pa = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    half4_t vb[2];
-#pragma unroll
-                    for (int hi = 0; hi < 2; ++hi) {
-                        // channel slab c (16 channels), this lane's chunk tq: sub-space and code byte
-                        int dw, sh_c, moff;
-                        if (DSUB == 8) { dw = c >> 1; sh_c = 16 * (c & 1); moff = c * 8192; }
-                        else if (DSUB == 4) { dw = c; sh_c = 0; moff = c * 8192; }
-                        else { dw = c >> 2; sh_c = 8 * (c & 3); moff = c * 8192; }
-                        const uint32_t code = (vq[2 * u + hi][dw] >> (sh_c + v_shift_lane)) & 255u;
-                        vb[hi] = lds_read_tr16(lsm, code * (2 * DSUB) + v_lane_off + moff);
-                    }
-                    const half8_t bop = {vb[0][0], vb[0][1], vb[0][2], vb[0][3], vb[1][0], vb[1][1], vb[1][2], vb[1][3]};
-                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, bop, acc[c], 0, 0, 0);
-                }
-            }
-            __builtin_amdgcn_wave_barrier();
-        }
-        float l_sum[kNH];
-#pragma unroll
-        for (int h = 0; h < kNH; ++h) l_sum[h] = wave_sum(l_lane[h]);
-        wg_merge_and_store<DSUB>(smem, m_ref, l_sum, acc, part_bg, p.A + sp, slots, nheads, L::red);
-        return;
-    }
-
-    // =========================================================================== anchor role
-    {
-        const int aw = role;                                  // anchor workgroup index within (b, g)
-        const int n_items = p.k_k + p.k_v;                    // K-anchor entries, then V-anchor entries
-        float* s_qf = (float*)(smem + L::a_qf);
-        if (tid < kNH * kD) {
-            const int h = tid >> 7;
-            s_qf[tid] = (h < nheads) ? (float)qb[tid] : 0.f;
-        }
-        __syncthreads();
-        // Q as MFMA A operand: row = head, 4 k-steps of 32 channels
-        half8_t qa[4];
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                qa[st][e] = (arow < nheads) ? qb[arow * kD + 32 * st + 8 * kgrp + e] : (half_t)0.f;
-        }
-        half_t* s_rows = (half_t*)(smem + L::a_rows) + wave * 4096;     // [32][128]
-        half_t* s_p = (half_t*)(smem + L::a_pst) + wave * 128;          // [4][32]
-        const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * M;
-        const uint8_t* cv = p.codes_v + (int64_t)bg * p.N_cap * M;
-        const half_t* cbk = p.cb_k + (size_t)g * 32768;
-        const half_t* cbv = p.cb_v + (size_t)g * 32768;
-
-        for (int tw = 0; tw < kAnchorTilesPerWave; ++tw) {
-            const int tile = (aw * kDaWaves + wave) * kAnchorTilesPerWave + tw;
-            const int item0 = tile * 32;
-            if (item0 >= n_items) break;
-            // lanes 0..31 each own one item of the tile: resolve where its K and V rows come from
-            int my_tok = -1, my_kslot = -1, my_vslot = -1;     // slot >= 0: FP16 row; -1: from codes
-            bool my_valid = false;
+    // ================================================================================== anchors
+    const int n_items = p.k_k + p.k_v;                    // K-anchor entries, then V-anchor entries
+    const int n_atiles = (n_items + 31) >> 5;
+    if (wave < kAnchorWaves && n_atiles > 0) {
+        const half_t* s_qh = (const half_t*)(smem + L::qh);               // Q as MFMA A operand: row = head
+        half_t* s_rows = (half_t*)(smem + L::stage) + wave * 4096;        // [32][128]
+        int* s_win = (int*)(s_p + 128);                                   // 64 ints behind the [4][32] P tile
+        const uint32_t rows_off = (uint32_t)(L::stage + wave * 8192);
+        const int srow = lane >> 1, shalf = lane & 1;                      // staging: this lane fills 64 channels of a row
+        for (;;) {
+            // tiles of the (b, g) lists are dealt round-robin to the workgroups; this workgroup's tiles are
+            // handed out to its anchor waves through a counter
+            int lt = 0;
+            if (lane == 0) lt = atomicAdd(&s_misc[9], 1);
+            lt = __builtin_amdgcn_readfirstlane(lt);
+            const int t = sp + p.S * lt;
+            if (t >= n_atiles) break;
+            const int item0 = t * 32;
+            // lanes 0..31 each own one item of the tile
+            const bool is_k_tile_lane = (item0 + lane) < p.k_k;
+            int my_tok = 0x7fffffff, my_kslot = -1, my_vslot = -1, my_valid = 0;
             if (lane < 32) {
                 const int it = item0 + lane;
-                if (it < p.k_k) {
-                    my_tok = idx_k[it];
-                    my_kslot = it;
-                    my_vslot = find_sorted(idx_v, p.k_v, my_tok);
-                    my_valid = true;
-                } else if (it < n_items) {
-                    my_tok = idx_v[it - p.k_k];
-                    my_vslot = it - p.k_k;
-                    my_valid = find_sorted(idx_k, p.k_k, my_tok) < 0;   // handled as a K item otherwise
+                if (it < p.k_k) { my_tok = idx_k[it]; my_kslot = it; my_valid = 1; }
+                else if (it < n_items) { my_tok = idx_v[it - p.k_k]; my_vslot = it - p.k_k; my_valid = 1; }
+            }
+            // Cross membership: a K item looks its token up in idx_v (is its V row FP16 too?), a V item in idx_k
+            // (if found there, the token is handled as a K item and this entry is skipped).  A tile can straddle
+            // the two lists, so both lookups are run; each is a cooperative search for the window of the other
+            // list that can contain the tile's tokens, then a search inside the window from LDS.
+#pragma unroll 1
+            for (int side = 0; side < 2; ++side) {
+                const int32_t* arr = side ? idx_k : idx_v;
+                const int n = side ? p.k_k : p.k_v;
+                const bool mine = my_valid && (side ? !is_k_tile_lane : is_k_tile_lane) && lane < 32;
+                const unsigned long long act = __ballot(mine);
+                if (act == 0ull || n == 0) continue;
+                const int l_first = __builtin_ctzll(act), l_last = 63 - __builtin_clzll(act);
+                const int tok_first = __shfl(my_tok, l_first, 64), tok_last = __shfl(my_tok, l_last, 64);
+                const int w_lo = wave_lower_bound(arr, n, tok_first, lane);
+                const int w_hi = wave_lower_bound(arr, n, tok_last + 1, lane);
+                int found = -1;
+                if (w_hi - w_lo <= 64) {
+                    const int wv = (w_lo + lane < w_hi) ? arr[w_lo + lane] : 0x7fffffff;
+                    s_win[lane] = wv;
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    if (mine) {
+                        int lo = 0, hi = w_hi - w_lo;
+                        while (lo < hi) { const int mid = (lo + hi) >> 1; if (s_win[mid] < my_tok) lo = mid + 1; else hi = mid; }
+                        if (lo < w_hi - w_lo && s_win[lo] == my_tok) found = w_lo + lo;
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                } else if (mine) {
+                    const int f = find_sorted(arr + w_lo, w_hi - w_lo, my_tok);
+                    found = (f >= 0) ? w_lo + f : -1;
+                }
+                if (mine) {
+                    if (side == 0) my_vslot = found;            // K item: FP16 V row if the token is a V anchor too
+                    else if (found >= 0) my_valid = 0;          // V item whose token is also a K anchor: skip
                 }
             }
-            // ---- stage K_eff rows: half-wave hw fills rows hw, hw+2, ...; lane covers 4 channels
-            const int hw = lane >> 5, l32 = lane & 31;
-            for (int r = hw; r < 32; r += 2) {
-                const int tok = __shfl(my_tok, r, 64);
-                const int kslot = __shfl(my_kslot, r, 64);
-                const bool valid = __shfl((int)my_valid, r, 64) != 0;
-                half4_t v = {0, 0, 0, 0};
-                if (valid) {
-                    if (kslot >= 0) {
-                        v = *(const half4_t*)(p.rows_k + ((int64_t)bg * p.k_k + kslot) * kD + 4 * l32);
-                    } else {
-                        const int dim = 4 * l32, m = dim / DSUB;
-                        const int code = ck[(int64_t)tok * M + m];
-                        v = *(const half4_t*)(cbk + (m * 256 + code) * DSUB + (dim % DSUB));
+            const int r_tok = __shfl(my_tok, srow, 64);
+            const int r_kslot = __shfl(my_kslot, srow, 64);
+            const int r_vslot = __shfl(my_vslot, srow, 64);
+            const bool r_valid = __shfl(my_valid, srow, 64) != 0;
+
+            // 64 channels (8 x 16 bytes) of row `srow`: the FP16 row, or centroids looked up from the codes
+            auto fetch_half_row = [&](int slot, const half_t* rows, int64_t n_rows_per_bg, const uint8_t* codes,
+                                      const half_t* cb, uint4_t (&buf)[8]) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) buf[i] = uint4_t{0u, 0u, 0u, 0u};
+                if (!r_valid) return;
+                if (slot >= 0) {
+                    const uint4_t* src = (const uint4_t*)(rows + ((int64_t)bg * n_rows_per_bg + slot) * kD + 64 * shalf);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) buf[i] = src[i];
+                } else {
+                    constexpr int SUBS = 64 / DSUB;                       // sub-spaces in half a row
+                    const uint8_t* cp = codes + (int64_t)r_tok * M + SUBS * shalf;
+                    uint32_t cw[SUBS / 4];
+                    if constexpr (SUBS == 4) cw[0] = *(const uint32_t*)cp;
+                    else if constexpr (SUBS == 8) { const uint2_t a = *(const uint2_t*)cp; cw[0] = a[0]; cw[1] = a[1]; }
+                    else { const uint4_t a = *(const uint4_t*)cp; cw[0] = a[0]; cw[1] = a[1]; cw[2] = a[2]; cw[3] = a[3]; }
+#pragma unroll
+                    for (int j = 0; j < SUBS; ++j) {
+                        const int m = SUBS * shalf + j;
+                        const uint32_t code = (cw[j >> 2] >> (8 * (j & 3))) & 255u;
+                        const half_t* cen = cb + ((int64_t)m * 256 + code) * DSUB;
+                        if constexpr (DSUB == 4) {
+                            const uint2_t v = *(const uint2_t*)cen;
+                            if (j & 1) { buf[j >> 1][2] = v[0]; buf[j >> 1][3] = v[1]; }
+                            else { buf[j >> 1][0] = v[0]; buf[j >> 1][1] = v[1]; }
+                        } else if constexpr (DSUB == 8) {
+                            buf[j] = *(const uint4_t*)cen;
+                        } else {
+                            buf[2 * j] = *(const uint4_t*)cen;
+                            buf[2 * j + 1] = *(const uint4_t*)(cen + 8);
+                        }
                     }
                 }
-                *(half4_t*)(s_rows + r * kD + 4 * l32) = v;
+            };
+            uint4_t buf[8];
+            fetch_half_row(r_kslot, p.rows_k, p.k_k, ck, cbk, buf);
+            {
+                uint4_t* dst = (uint4_t*)(s_rows + srow * kD + 64 * shalf);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) dst[i] = buf[i];
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
+            // start the V rows while the scores are computed
+            fetch_half_row(r_vslot, p.rows_v, p.k_v, cv, cbv, buf);
+
             // ---- scores: S[head][item] for the two 16-item halves
             float sc[2][4];
 #pragma unroll
@@ -520,18 +563,19 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
 #pragma unroll
                 for (int st = 0; st < 4; ++st) {
                     const half8_t kb = *(const half8_t*)(s_rows + (16 * u + arow) * kD + 32 * st + 8 * kgrp);
-                    c4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[st], kb, c4, 0, 0, 0);
+                    half8_t qa = *(const half8_t*)(s_qh + (arow & 3) * kD + 32 * st + 8 * kgrp);
+                    if (arow >= kNH) qa = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                    c4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa, kb, c4, 0, 0, 0);
                 }
 #pragma unroll
                 for (int r = 0; r < 4; ++r) sc[u][r] = c4[r] * p.c1;   // lanes 0..15: head r, item 16u + lane
             }
-            // validity of item 16u + arow, then the tile maximum per head
             float mx[kNH];
 #pragma unroll
             for (int h = 0; h < kNH; ++h) mx[h] = kNegBig;
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                const bool valid = __shfl((int)my_valid, 16 * u + arow, 64) != 0;
+                const bool valid = __shfl(my_valid, 16 * u + arow, 64) != 0;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     if (!(valid && kgrp == 0)) sc[u][r] = kNegBig;
@@ -557,29 +601,17 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                     if (kgrp == 0) s_p[r * 32 + 16 * u + arow] = (half_t)pw;
                 }
             __builtin_amdgcn_wave_barrier();
-            // ---- stage V_eff rows over the K rows
-            for (int r = hw; r < 32; r += 2) {
-                const int tok = __shfl(my_tok, r, 64);
-                const int vslot = __shfl(my_vslot, r, 64);
-                const bool valid = __shfl((int)my_valid, r, 64) != 0;
-                half4_t v = {0, 0, 0, 0};
-                if (valid) {
-                    if (vslot >= 0) {
-                        v = *(const half4_t*)(p.rows_v + ((int64_t)bg * p.k_v + vslot) * kD + 4 * l32);
-                    } else {
-                        const int dim = 4 * l32, m = dim / DSUB;
-                        const int code = cv[(int64_t)tok * M + m];
-                        v = *(const half4_t*)(cbv + (m * 256 + code) * DSUB + (dim % DSUB));
-                    }
-                }
-                *(half4_t*)(s_rows + r * kD + 4 * l32) = v;
+            // ---- V_eff rows replace the K rows in the staging tile
+            {
+                uint4_t* dst = (uint4_t*)(s_rows + srow * kD + 64 * shalf);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) dst[i] = buf[i];
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             // ---- P.V: tokens along k; transposed LDS reads turn row-major V rows into the B operand
             half8_t pa = *(const half8_t*)(s_p + (arow & 3) * 32 + 8 * kgrp);
             if (arow >= kNH) pa = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-            const uint32_t rows_off = (uint32_t)(L::a_rows + wave * 8192);
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
                 half4_t vb[2];
@@ -593,28 +625,191 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             }
             __builtin_amdgcn_wave_barrier();
         }
-        float l_sum[kNH];
-#pragma unroll
-        for (int h = 0; h < kNH; ++h) l_sum[h] = wave_sum(l_lane[h]);
-        wg_merge_and_store<DSUB>(smem, m_ref, l_sum, acc, part_bg, aw, slots, nheads, L::a_red);
     }
+
+    // ================================================================================== stream
+    {
+        // lane -> token position inside a 64-token tile, chosen so that the four lanes of a quad hold
+        // the V codes of exactly the four tokens whose centroids that quad must fetch for the MFMA
+        const int pos = 32 * (tq >> 1) + 8 * kgrp + 4 * (tq & 1) + tj;
+        // V gather address = cbv + ((m*256 + code)*DSUB + within)*2; the lane part goes into one OR-able constant
+        uint32_t v_lane_off, v_shift_lane;
+        if (DSUB == 8) { v_lane_off = (tq >> 1) * 4096 + (tq & 1) * 8; v_shift_lane = 8 * (tq >> 1); }
+        else if (DSUB == 4) { v_lane_off = tq * 2048; v_shift_lane = 8 * tq; }
+        else { v_lane_off = tq * 8; v_shift_lane = 0; }
+        v_lane_off += L::cbv + (uint32_t)(uintptr_t)lsm;             // absolute LDS address of the lane's table part
+        constexpr int VSH = (DSUB == 8) ? 4 : (DSUB == 4 ? 3 : 5);   // log2(bytes per centroid)
+        // K gather: this lane visits sub-space (step XOR xr) mod M at every step and reads slot (step XOR xr)
+        const uint32_t xr = lane & 31;
+        const uint32_t xr8 = xr << 3;
+        const uint32_t kr = xr & (M - 1);                            // XOR applied to the code byte index
+        uint32_t ksh[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ksh[j] = 8 * (j ^ (kr & 3));
+
+        const int64_t n_tiles = (t1 - t0 + 63) >> 6;
+        auto grab_tile = [&]() -> int64_t {
+            int t = 0;
+            if (lane == 0) t = atomicAdd(&s_misc[8], 1);
+            return (int64_t)__builtin_amdgcn_readfirstlane(t);
+        };
+        // code loads run one tile ahead of their use: HBM latency hides behind the previous tile's work
+        auto load_codes = [&](int64_t tile, uint32_t (&kw_)[CW], uint32_t (&vw_)[CW]) {
+            const int64_t tok_ = t0 + tile * 64 + pos;
+            const int64_t ltok = (tok_ < t1) ? tok_ : (p.N - 1);
+            if (CW == 2) {
+                const uint2_t a = *(const uint2_t*)(ck + ltok * M), c = *(const uint2_t*)(cv + ltok * M);
+                kw_[0] = a[0]; kw_[1] = a[1]; vw_[0] = c[0]; vw_[1] = c[1];
+            } else {
+#pragma unroll
+                for (int i = 0; i < CW / 4; ++i) {
+                    const uint4_t a = *(const uint4_t*)(ck + ltok * M + 16 * i), c = *(const uint4_t*)(cv + ltok * M + 16 * i);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { kw_[4 * i + e] = a[e]; vw_[4 * i + e] = c[e]; }
+                }
+            }
+        };
+        uint32_t kw_next[CW], vw_next[CW];
+        int64_t tile = grab_tile();
+        if (tile < n_tiles) load_codes(tile, kw_next, vw_next);
+        while (tile < n_tiles) {
+            const int64_t tok = t0 + tile * 64 + pos;
+            uint32_t kw[CW], vw[CW];
+#pragma unroll
+            for (int i = 0; i < CW; ++i) { kw[i] = kw_next[i]; vw[i] = vw_next[i]; }
+            const int64_t tile_next = grab_tile();
+            if (tile_next < n_tiles) load_codes(tile_next, kw_next, vw_next);
+            const int rel = (int)(tok - t0);
+            const uint32_t mbit = (s_mask[(rel >> 5) & (L::mask_words - 1)] >> (rel & 31)) & 1u;
+            // 1.0 for tokens that are anchored or past the end of the range: an arithmetic mask keeps the
+            // table gathers below unconditional (no divergent branch around them)
+            const float mf = (tok < t1) ? (float)mbit : 1.0f;
+
+            // ---- K side: scores in log2 units.  Code dwords are XOR-permuted so that step s finds the code of
+            // sub-space (s XOR kr) at a compile-time register and a per-lane constant byte shift.
+#pragma unroll
+            for (int bit = 0; (4 << bit) < M; ++bit) {
+                const bool sw = (kr >> (2 + bit)) & 1u;
+#pragma unroll
+                for (int i = 0; i < CW; ++i) {
+                    if (!(i & (1 << bit))) {
+                        const uint32_t a = kw[i], c = kw[i | (1 << bit)];
+                        kw[i] = sw ? c : a;
+                        kw[i | (1 << bit)] = sw ? a : c;
+                    }
+                }
+            }
+            int si[kNH] = {0, 0, 0, 0};
+#pragma unroll
+            for (int st = 0; st < M; ++st) {
+                const uint32_t code = __builtin_amdgcn_ubfe(kw[st >> 2], ksh[st & 3], 8);
+                const uint32_t slot8 = xr8 ^ (uint32_t)(8 * st);
+                const short4_t e = *(const short4_t*)(smem + L::lut + ((code << 8) | slot8));
+                const short2_t e01 = __builtin_shufflevector(e, e, 0, 1), e23 = __builtin_shufflevector(e, e, 2, 3);
+                si[0] = __builtin_amdgcn_sdot2(e01, short2_t{1, 0}, si[0], false);
+                si[1] = __builtin_amdgcn_sdot2(e01, short2_t{0, 1}, si[1], false);
+                si[2] = __builtin_amdgcn_sdot2(e23, short2_t{1, 0}, si[2], false);
+                si[3] = __builtin_amdgcn_sdot2(e23, short2_t{0, 1}, si[3], false);
+            }
+            float s[kNH];
+            bool grow = false;
+#pragma unroll
+            for (int h = 0; h < kNH; ++h) {
+                s[h] = fmaf(mf, kNegBig, (float)si[h] * lut_q[h]);
+                grow = grow || (s[h] > m_ref[h] + kPShift);
+            }
+            if (__any(grow)) {   // some score exceeds the running maximum: move the reference, rescale
+#pragma unroll
+                for (int h = 0; h < kNH; ++h) {
+                    const float mx = wave_max_uniform(s[h]);
+                    const float m_new = fmaxf(m_ref[h], mx - kPShift);
+                    const float alpha = fast_exp2(m_ref[h] - m_new);
+                    l_lane[h] *= alpha;
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) acc[c][h] *= alpha;
+                    m_ref[h] = m_new;
+                }
+            }
+#pragma unroll
+            for (int h = 0; h < kNH; ++h) {
+                const float pw = fast_exp2(s[h] - m_ref[h]);
+                l_lane[h] += pw;
+                s_p[h * 64 + pos] = (half_t)pw;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+
+            // ---- V side: the V codes of token (u, hi) of this quad sit in quad lane 2u+hi
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                half8_t pa = *(const half8_t*)(s_p + (arow & 3) * 64 + 32 * u + 8 * kgrp);
+                if (arow >= kNH) pa = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                constexpr int SPD = (DSUB == 8) ? 2 : (DSUB == 4 ? 1 : 4);   // channel slabs served by one code dword
+#pragma unroll
+                for (int cd = 0; cd < 8 / SPD; ++cd) {
+                    const uint32_t w0 = quad_bcast_sel(vw[cd], 2 * u), w1 = quad_bcast_sel(vw[cd], 2 * u + 1);
+#pragma unroll
+                    for (int cs = 0; cs < SPD; ++cs) {
+                        const int c = cd * SPD + cs;
+                        const int sh_c = (DSUB == 8) ? 16 * cs : (DSUB == 4 ? 0 : 8 * cs);   // code byte inside the dword
+                        const uint32_t code0 = __builtin_amdgcn_ubfe(w0, sh_c + v_shift_lane, 8);
+                        const uint32_t code1 = __builtin_amdgcn_ubfe(w1, sh_c + v_shift_lane, 8);
+                        // (the slab offset c*8192 is a compile-time addend that lands in the DS immediate field)
+                        const half4_t vb0 = lds_read_tr16_abs(((code0 << VSH) + v_lane_off) + c * 8192);
+                        const half4_t vb1 = lds_read_tr16_abs(((code1 << VSH) + v_lane_off) + c * 8192);
+                        const half8_t bop = {vb0[0], vb0[1], vb0[2], vb0[3], vb1[0], vb1[1], vb1[2], vb1[3]};
+                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, bop, acc[c], 0, 0, 0);
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            tile = tile_next;
+        }
+    }
+    DA_STAMP(2);
+    float l_sum[kNH];
+#pragma unroll
+    for (int h = 0; h < kNH; ++h) l_sum[h] = wave_sum(l_lane[h]);
+#ifdef ANTKV_DA_TRACE
+    wg_merge_and_store<DSUB>(smem, m_ref, l_sum, acc, part_bg, sp, p.S, nheads, p.trace + (size_t)blockIdx.x * 8 + 6);
+#else
+    wg_merge_and_store<DSUB>(smem, m_ref, l_sum, acc, part_bg, sp, p.S, nheads);
+#endif
+    // The last workgroup of this (sequence, KV head) to arrive merges the S partials by log-sum-exp and
+    // rounds once to fp16: out = sum_s acc_s 2^(m_s - m) / sum_s l_s 2^(m_s - m).
+    // Ordering without a cache-wide release: the partial was written with device-scope stores, each wave
+    // waits for its own stores to be acknowledged, the barrier collects the waves, and only then does one
+    // thread bump the device-scope counter.  The merging workgroup reads with device-scope loads.
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (tid == 0) s_misc[10] = (int)__hip_atomic_fetch_add(&p.done[bg], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (s_misc[10] == p.S - 1) {
+        if (tid < kNH * kD) {
+            const int h = tid >> 7, dim = tid & 127;
+            if (h < nheads) {
+                const float* pb = part_bg + (int64_t)h * p.S * (kD + 2);
+                float m = kNegBig;
+                auto ld = [](const float* q) { return __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+                for (int sl = 0; sl < p.S; ++sl) m = fmaxf(m, ld(pb + sl * (kD + 2) + kD));
+                float l = 0.f, a = 0.f;
+                for (int sl = 0; sl < p.S; ++sl) {
+                    const float w = fast_exp2(ld(pb + sl * (kD + 2) + kD) - m);
+                    l += ld(pb + sl * (kD + 2) + kD + 1) * w;
+                    a += ld(pb + sl * (kD + 2) + dim) * w;
+                }
+                p.out[((int64_t)b * p.Hq + h0 + h) * kD + dim] = (half_t)(l > 0.f ? a / l : 0.f);
+            }
+        }
+        if (tid == 0) __hip_atomic_store(&p.done[bg], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    DA_STAMP(5);
 }
 
-// out[b][h] = sum_s acc_s 2^(m_s - m) / sum_s l_s 2^(m_s - m).  One 128-thread workgroup per (b, h).
-__global__ __launch_bounds__(128) void decode_merge_kernel(const float* __restrict__ part, int slots,
-                                                           half_t* __restrict__ out)
+__global__ __launch_bounds__(256) void zero_done_kernel(unsigned int* done, int n)
 {
-    const int bh = blockIdx.x, dim = threadIdx.x;
-    const float* pb = part + (int64_t)bh * slots * (kD + 2);
-    float m = kNegBig;
-    for (int s = 0; s < slots; ++s) m = fmaxf(m, pb[s * (kD + 2) + kD]);
-    float l = 0.f, a = 0.f;
-    for (int s = 0; s < slots; ++s) {
-        const float w = fast_exp2(pb[s * (kD + 2) + kD] - m);
-        l += pb[s * (kD + 2) + kD + 1] * w;
-        a += pb[s * (kD + 2) + dim] * w;
-    }
-    out[(int64_t)bh * kD + dim] = (half_t)(l > 0.f ? a / l : 0.f);
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) done[i] = 0u;
 }
 
 __global__ __launch_bounds__(128) void zero_out_kernel(half_t* out, int64_t n)
@@ -804,9 +999,9 @@ __global__ __launch_bounds__(64) void decode_ans_lse_kernel(const float* __restr
 thread_local hipEvent_t t_ev_start = nullptr, t_ev_stop = nullptr;
 
 struct DaPlan {
-    int S, A;
+    int S;
     int64_t chunk;
-    size_t off_part, off_stat, off_lse, total;
+    size_t off_part, off_done, off_stat, off_lse, total;
 };
 
 DaPlan da_plan(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans)
@@ -824,10 +1019,13 @@ DaPlan da_plan(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans
     pl.chunk = chunk;
     pl.S = (int)((N + chunk - 1) / chunk);
     if (pl.S < 1) pl.S = 1;
-    const int64_t tiles = (k_k + k_v + 31) / 32;
-    pl.A = (int)((tiles + kAnchorTilesPerWg - 1) / kAnchorTilesPerWg);
+    (void)k_k; (void)k_v;
     size_t off = 0;
-    pl.off_part = off; off += align_up((size_t)g.B * g.Hq * (pl.S + pl.A) * (kD + 2) * sizeof(float));
+#ifdef ANTKV_DA_TRACE
+    off += align_up((size_t)g.B * g.Hkv * pl.S * 8 * sizeof(unsigned long long));   // trace lives at offset 0
+#endif
+    pl.off_part = off; off += align_up((size_t)g.B * g.Hq * pl.S * (kD + 2) * sizeof(float));
+    pl.off_done = off; off += align_up((size_t)g.B * g.Hkv * sizeof(unsigned int));
     pl.off_stat = off; off += want_ans ? align_up((size_t)g.B * g.Hq * pl.S * 2 * sizeof(float)) : 0;
     pl.off_lse = off;  off += align_up((size_t)g.B * g.Hq * sizeof(float));
     pl.total = off;
@@ -860,17 +1058,18 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     DaParams p;
     p.q = a.q; p.codes_k = a.codes_k; p.codes_v = a.codes_v; p.cb_k = a.cb_k; p.cb_v = a.cb_v;
     p.idx_k = a.idx_k; p.idx_v = a.idx_v; p.rows_k = a.rows_k; p.rows_v = a.rows_v;
-    p.part = part; p.N = a.N; p.N_cap = a.N_cap; p.k_k = (int)a.k_k; p.k_v = (int)a.k_v;
-    p.c1 = a.scale * kLog2e; p.Hq = g.Hq; p.Hkv = g.Hkv; p.G = g.G; p.S = pl.S; p.A = pl.A; p.chunk = pl.chunk;
+    p.part = part; p.out = a.out; p.done = (unsigned int*)(w + pl.off_done); p.N = a.N; p.N_cap = a.N_cap; p.k_k = (int)a.k_k; p.k_v = (int)a.k_v;
+    p.trace = (unsigned long long*)ws;
+    p.c1 = a.scale * kLog2e; p.Hq = g.Hq; p.Hkv = g.Hkv; p.G = g.G; p.S = pl.S; p.chunk = pl.chunk;
     const size_t shmem = Lds<DSUB>::total;
     hipError_t e = hipFuncSetAttribute((const void*)decode_attn_kernel<DSUB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (e != hipSuccess) return e;
-    const unsigned grid = (unsigned)((int64_t)g.B * g.Hkv * (pl.S + pl.A));
+    const unsigned grid = (unsigned)((int64_t)g.B * g.Hkv * pl.S);
+    hipLaunchKernelGGL(zero_done_kernel, dim3((unsigned)((g.B * g.Hkv + 255) / 256)), dim3(256), 0, st, p.done, g.B * g.Hkv);
     if (t_ev_start) (void)hipEventRecord(t_ev_start, st);
     hipLaunchKernelGGL(decode_attn_kernel<DSUB>, dim3(grid), dim3(kDaThreads), shmem, st, p);
     if (t_ev_stop) (void)hipEventRecord(t_ev_stop, st);
     t_ev_start = t_ev_stop = nullptr;
-    hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)(g.B * g.Hq)), dim3(128), 0, st, part, pl.S + pl.A, a.out);
     if (want_ans) {
         DsParams d;
         d.q = a.q; d.codes_k = a.codes_k; d.cb_k = a.cb_k; d.idx_k = a.idx_k; d.rows_k = a.rows_k;
