@@ -36,6 +36,19 @@ def algorithmic_bytes(w, k_k, k_v):
     return w.B * w.Hkv * per_bg + 2 * w.Hkv * w.M * w.C * w.d_sub * 2 + 2 * w.B * w.Hq * w.D * 2
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch of the decode kernel from the committed hardware-counter summary (FETCH_SIZE + WRITE_SIZE,
+    scaled by the copy-kernel calibration), or None when no summary covers this workload."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"decode_attn_{workload}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -44,6 +57,10 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2", help="decode workload: cfg0 | cfg1 | cfg2 | cfg4")
     ap.add_argument("--copies", type=int, default=8, help="distinct cache copies the timed steps rotate over")
     ap.add_argument("--no-extras", action="store_true", help="skip encode / anchor-select rates and the CPU baseline")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also launch one row-copy kernel of known size (gather_rows with identity indices), so that a "
+                         "hardware-counter run can scale its byte counters against it")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time to spend on the oracle baseline")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path is a single-GPU kernel path; "
@@ -78,6 +95,16 @@ def main() -> int:
     torch.cuda.synchronize()
     del kd, vd
     torch.cuda.empty_cache()
+    if args.calibrate:
+        # 8 heads x 131072 rows x 256 B read and written once each, plus 4 B of index per row
+        cal_geom = antkv.Geometry(1, w.Hq, w.Hkv, w.d_sub)
+        cal_src = torch.zeros((1, w.Hkv, 131072, w.D), dtype=torch.float16, device=devc)
+        cal_idx = torch.arange(131072, dtype=torch.int32, device=devc).repeat(1, w.Hkv, 1).contiguous()
+        antkv.gather_rows(cal_geom, cal_src, cal_idx)
+        torch.cuda.synchronize()
+        log(f"calibration copy: gather_rows_kernel read {cal_src.numel() * 2 + cal_idx.numel() * 4} B, "
+            f"wrote {cal_src.numel() * 2} B")
+        del cal_src, cal_idx
     q = dev(make_decode_query(w.seed, w.B, w.Hq, w.D))
     out = torch.empty((w.B, w.Hq, w.D), dtype=torch.float16, device=devc)
     caches = [(codes_k, codes_v, idx_k, rows_k, idx_v, rows_v)]
@@ -117,22 +144,25 @@ def main() -> int:
     ms_kernel = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
 
     abytes = algorithmic_bytes(w, w.k, w.k)
+    traffic = measured_traffic(w.name)
     achieved = abytes / (ms_kernel * 1e-3) / 1e9
     result = {
         "metric": "decode-attn tokens/s at 128K ctx + achieved HBM GB/s (% peak); encode Mvec/s",
         "value": w.B * w.N / (ms_step * 1e-3),
         "unit": "context tokens/s (one layer, all KV heads)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8 codes, f16 tables, f32 accumulate",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic (seeded N(0,1) K/V with channel outliers, k-means++ codebooks; stands in for LLaMA-3-8B / "
                 "Mistral-7B KV caches)",
         "config": {"workload": f"{w.name}: {w.description}", "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "N": w.N,
                    "d_sub": w.d_sub, "bits_per_element": w.bits_per_element, "anchors_per_head": w.k,
                    "cache_copies_rotated": len(caches)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "decode_attn_kernel",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": "decode_attn_kernel",
                      "kernel_ms": ms_kernel, "algorithmic_bytes": abytes},
-        "extra": {"decode_steps_per_s": w.B / (ms_step * 1e-3), "ms_per_step_warm": ms_warm,
+        "extra": {"arithmetic": "u8 codes; int16 fixed-point q.centroid table; f16 softmax weights and V centroids into "
+                                "f32 MFMA accumulators; f32 online softmax; f16 output",
+                  "decode_steps_per_s": w.B / (ms_step * 1e-3), "ms_per_step_warm": ms_warm,
                   "tokens_per_s_warm": w.B * w.N / (ms_warm * 1e-3),
                   "step_GBs": abytes / (ms_step * 1e-3) / 1e9, "step_frac_of_peak": abytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
@@ -174,20 +204,22 @@ def main() -> int:
         # ------------------------------------------------------------ CPU baseline: the oracle, as it stands
         import oracle
         oracle.build()
-        sB = 1                                                  # bounded sample: one sequence of the decode workload
+        sB = w.B                                                # bounded sample: whole decode steps, repeated
         c = dict(q=make_decode_query(w.seed, sB, w.Hq, w.D),
                  ck=random_codes(w.seed, "k", sB, w.Hkv, w.N, w.M), cv=random_codes(w.seed, "v", sB, w.Hkv, w.N, w.M),
                  ik=random_anchor_sets(w.seed, "k", sB, w.Hkv, w.N, w.k), iv=random_anchor_sets(w.seed, "v", sB, w.Hkv, w.N, w.k),
                  rk=normal_fp16(w.seed, "rows_k", (sB, w.Hkv, w.k, w.D)), rv=normal_fp16(w.seed, "rows_v", (sB, w.Hkv, w.k, w.D)))
-        t0 = time.time()
-        oracle.decode_attn(c["q"], c["ck"], c["cv"], cbk, cbv, c["ik"], c["rk"], c["iv"], c["rv"], w.scale)
+        reps, t0 = 0, time.time()
+        while reps < 1 or (time.time() - t0 < args.cpu_seconds and reps < 1000):
+            oracle.decode_attn(c["q"], c["ck"], c["cv"], cbk, cbv, c["ik"], c["rk"], c["iv"], c["rv"], w.scale)
+            reps += 1
         t_cpu = time.time() - t0
-        result["cpu_baseline"] = {"value": sB * w.N / t_cpu, "unit": "context tokens/s (one layer, all KV heads)",
+        result["cpu_baseline"] = {"value": reps * sB * w.N / t_cpu, "unit": "context tokens/s (one layer, all KV heads)",
                                   "cores": oracle.num_threads(), "kind": "oracle",
-                                  "sample": f"one decode step of one sequence of {w.name} (N={w.N}, {w.Hkv} KV heads, "
-                                            f"{w.k} anchors/head, cache-shaped random codes): {t_cpu:.2f} s wall incl. "
-                                            f"fp16->fp32 widening"}
-        log(f"cpu oracle: {t_cpu:.2f}s on {oracle.num_threads()} threads")
+                                  "sample": f"{reps} decode steps of {w.name} (B={sB}, N={w.N}, {w.Hkv} KV heads, "
+                                            f"{w.k} anchors/head, cache-shaped random codes) in {t_cpu:.1f} s wall, "
+                                            f"fp16->fp64 widening included"}
+        log(f"cpu oracle: {reps} steps in {t_cpu:.2f}s on {oracle.num_threads()} threads")
     print(json.dumps(result))
     return 0
 
