@@ -44,12 +44,15 @@ constexpr int kDaWaves = ANTKV_DA_WAVES;
 constexpr int kDaThreads = kDaWaves * 64;
 constexpr int kNH = 4;                 // query-head slots per workgroup (group size G <= 4)
 constexpr float kPShift = 8.0f;        // P is scaled by 2^8 so that small weights stay normal in fp16
-constexpr int kAnchorWaves = 2;        // waves that work through the anchor lists before joining the stream
+constexpr float kLutMax = 16256.0f;    // largest table magnitude: 127 * 128, so that both bytes of an entry fit int8
+constexpr int kPStride = 72;           // fp16 elements between the heads of a wave's P tile (64 + pad against bank conflicts)
+constexpr int kStgBytes = 4 * kPStride * 2 + 1024;  // per-wave staging: P tile, then 1 KB of V code words / anchor V rows
 constexpr float kEmptyRef = -1.0e4f;   // softmax reference before any token was seen: finite, below every real score,
                                        // and far above the masked score kNegBig so that exp2(masked - ref) is 0
 
 typedef __attribute__((address_space(3))) char lds_char;
 typedef __attribute__((address_space(3))) short4_t lds_short4;
+typedef __attribute__((address_space(3))) uint2_t lds_uint2;
 
 __device__ __forceinline__ half4_t lds_read_tr16(const lds_char* base, uint32_t off)
 {
@@ -171,17 +174,17 @@ struct DaParams {
 #define DA_STAMP(i) do { } while (0)
 #endif
 
-// LDS layout (bytes); the final merge re-uses the table area.
+// LDS layout (bytes); the final merge re-uses the table area.  The two tables sit at multiples of 64 KB so
+// that a gather address is (table base | code << 8 | byte inside the code's 256-byte row).
 template <int DSUB>
 struct Lds {
     static constexpr int M = kD / DSUB;
-    static constexpr int lut = 0;                                  // [256 codes][32 slots][4] int16 = 64 KB
-    static constexpr int cbv = lut + 65536;                        // [M][256][DSUB] fp16 = 64 KB
-    static constexpr int stage = cbv + 65536;                      // [anchor waves][32][128] fp16 (8 KB each)
+    static constexpr int lut = 0;                                  // [256 codes][32 slots][4 x (lo, hi) bytes] = 64 KB
+    static constexpr int cbv = lut + 65536;                        // [256 codes][M][DSUB] fp16 = 64 KB (a 256-byte row per code)
+    static constexpr int pst = cbv + 65536;                        // [waves] staging (P tile + V code words / anchor V rows)
+    static constexpr int qf = pst;                                 // prologue only: [4][128] fp32 query
     static constexpr int mrg = 0;                                  // merge: [waves][4][128] fp32 (2 KB per wave)
-    static constexpr int pst = stage + kAnchorWaves * 8192;        // [waves][4][64] fp16
-    static constexpr int qf = pst + kDaWaves * 512;                // [4][128] fp32
-    static constexpr int qh = qf + 2048;                           // [4][128] fp16 (MFMA operand source)
+    static constexpr int qh = pst + kDaWaves * kStgBytes;          // [4][128] fp16 (MFMA operand source)
     static constexpr int red = qh + 1024;                          // [waves][8] fp32 + 16 ints
     static constexpr int mask = red + kDaWaves * 32 + 64;          // bitmap over the token range
     static constexpr int mask_words = 1024;                        // up to 32768 tokens per range
@@ -189,10 +192,10 @@ struct Lds {
     static_assert(total <= 163840, "LDS budget of one CU");
 };
 
-// Merge the waves' (m_ref, l, acc) into one partial and write it.  acc is in MFMA C layout:
-// lanes 0..15 of a wave hold, for slab c and register r, head r and channel 16c + lane.
+// Merge the waves' (m_ref, l, acc) into one partial and write it.  acc is in the C layout of the class-structured
+// sparse MFMA: register h of acc[a] in lane (cls = lane / 16, n = lane % 16) is head h, channel 16 (4a + cls) + n.
 template <int DSUB>
-__device__ void wg_merge_and_store(char* smem, float (&m_ref)[kNH], float (&l_sum)[kNH], float4_t (&acc)[8],
+__device__ void wg_merge_and_store(char* smem, float (&m_ref)[kNH], float (&l_sum)[kNH], float4_t (&acc)[2],
                                    float* __restrict__ part_bg, int slot, int slots, int nheads,
                                    unsigned long long* trace_slot = nullptr)
 {
@@ -219,13 +222,11 @@ __device__ void wg_merge_and_store(char* smem, float (&m_ref)[kNH], float (&l_su
         for (int h = 0; h < kNH; ++h) { m_all[h] = lane_bcast(m_r, 16 * h); l_all[h] = lane_bcast(l_r, 16 * h); }
     }
     float* s_mrg = (float*)(smem + Lds<DSUB>::mrg);
-    if (lane < 16) {
 #pragma unroll
-        for (int c = 0; c < 8; ++c)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-            for (int r = 0; r < kNH; ++r)
-                s_mrg[(wave * kNH + r) * kD + 16 * c + lane] = acc[c][r] * fast_exp2(m_ref[r] - m_all[r]);
-    }
+        for (int r = 0; r < kNH; ++r)
+            s_mrg[(wave * kNH + r) * kD + 16 * (4 * a + (lane >> 4)) + (lane & 15)] = acc[a][r] * fast_exp2(m_ref[r] - m_all[r]);
     __syncthreads();
     if (tid < kNH * kD) {
         const int h = tid >> 7, dim = tid & 127;
@@ -302,11 +303,20 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 for (int u = 0; u < DSUB / 8; ++u) cen[i][u] = *(const uint4_t*)(cbk + e * DSUB + 8 * u);
             }
         }
+        // V codebook: LDS holds it code-major ([code][m][DSUB], a 256-byte row per code), so 16-byte chunk ci of
+        // the LDS image comes from a permuted place of the sub-space-major global array
         uint4_t vcopy[4096 / kDaThreads];
-        {
-            const uint4_t* src = (const uint4_t*)cbv;
 #pragma unroll
-            for (int i = 0; i < 4096 / kDaThreads; ++i) vcopy[i] = src[tid + i * kDaThreads];
+        for (int i = 0; i < 4096 / kDaThreads; ++i) {
+            const int ci = tid + i * kDaThreads, code = ci >> 4, w16 = ci & 15;
+            if constexpr (DSUB == 8) {
+                vcopy[i] = ((const uint4_t*)cbv)[w16 * 256 + code];
+            } else if constexpr (DSUB == 16) {
+                vcopy[i] = ((const uint4_t*)cbv)[((w16 >> 1) * 256 + code) * 2 + (w16 & 1)];
+            } else {
+                const uint2_t lo = ((const uint2_t*)cbv)[(2 * w16) * 256 + code], hi = ((const uint2_t*)cbv)[(2 * w16 + 1) * 256 + code];
+                vcopy[i] = uint4_t{lo[0], lo[1], hi[0], hi[1]};
+            }
         }
         if (tid < kNH * kD) {
             const int h = tid >> 7;
@@ -341,9 +351,11 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         }
         __syncthreads();
         DA_STAMP(7);
-        // LUT[m][c][h] = c1 * q_h[m*d : (m+1)*d] . cb_k[g][m][c], stored as 16-bit fixed point with one scale per
-        // head (quantum = max|LUT_h| / 32767): the per-token sum over sub-spaces is then exact integer arithmetic
-        // and the table error is uniform instead of growing with the entry's magnitude as it would in fp16.
+        // LUT[m][c][h] = c1 * q_h[m*d : (m+1)*d] . cb_k[g][m][c], stored as fixed point with one scale per head
+        // (quantum = max|LUT_h| / 16256): the per-token sum over sub-spaces is then exact integer arithmetic and
+        // the table error is uniform instead of growing with the entry's magnitude as it would in fp16.
+        // An entry is two signed bytes (lo, -hi) with value lo + 128 * hi, so that the int8 MFMA of the stream
+        // loop can sum entries with the weights (1, -128).
         float val[EPT][kNH];
         float amax[kNH] = {0.f, 0.f, 0.f, 0.f};
         {
@@ -391,18 +403,22 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
 #pragma unroll
             for (int h = 0; h < kNH; ++h) {
                 const float r = lane_bcast(r_r, 16 * h);
-                lut_q[h] = (r > 0.f) ? r / 32767.0f : 1.0f;
-                inv_q[h] = (r > 0.f) ? 32767.0f / r : 0.f;
+                lut_q[h] = (r > 0.f) ? r / kLutMax : 1.0f;
+                inv_q[h] = (r > 0.f) ? kLutMax / r : 0.f;
             }
         }
         uint2_t* s_lut = (uint2_t*)(smem + L::lut);
 #pragma unroll
         for (int i = 0; i < EPT; ++i) {
-            int qv[kNH];
+            uint32_t hw[kNH];
 #pragma unroll
-            for (int h = 0; h < kNH; ++h) qv[h] = (int)rintf(val[i][h] * inv_q[h]);
-            const uint2_t ent = uint2_t{((uint32_t)qv[0] & 0xffffu) | ((uint32_t)qv[1] << 16),
-                                        ((uint32_t)qv[2] & 0xffffu) | ((uint32_t)qv[3] << 16)};
+            for (int h = 0; h < kNH; ++h) {
+                const int qv = (int)rintf(val[i][h] * inv_q[h]);     // |qv| <= kLutMax
+                const int hi = (qv + 64) >> 7;                          // qv = lo + 128 * hi, lo in [-64, 63]
+                const int lo = qv - 128 * hi;
+                hw[h] = ((uint32_t)lo & 0xffu) | (((uint32_t)(-hi) & 0xffu) << 8);
+            }
+            const uint2_t ent = uint2_t{hw[0] | (hw[1] << 16), hw[2] | (hw[3] << 16)};
 #pragma unroll
             for (int rep = 0; rep < 32 / M; ++rep) s_lut[(lc0 + TPM * i) * 32 + lm + M * rep] = ent;
         }
@@ -434,22 +450,40 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     DA_STAMP(1);
 
     float m_ref[kNH], l_lane[kNH];
-    float4_t acc[8];
+    float4_t acc[2];
 #pragma unroll
     for (int h = 0; h < kNH; ++h) { m_ref[h] = kEmptyRef; l_lane[h] = 0.f; }
-#pragma unroll
-    for (int c = 0; c < 8; ++c) acc[c] = float4_t{0.f, 0.f, 0.f, 0.f};
-    half_t* s_p = (half_t*)(smem + L::pst) + wave * 256;          // this wave's P staging, [4][64] fp16
+    acc[0] = acc[1] = float4_t{0.f, 0.f, 0.f, 0.f};
+    half_t* s_p = (half_t*)(smem + L::pst + wave * kStgBytes);    // this wave's P tile, [4][kPStride] fp16
+    uint32_t* s_cw = (uint32_t*)(s_p + 4 * kPStride);             // this wave's V code words, 512 bytes
+
+    // P.V runs on the 2:4-sparse MFMA (16x16x64 f16).  Its 64 k positions are (token, channel slab) pairs; the
+    // position inside each group of four is the slab's class, and row 4 cls + h of the sparse operand keeps,
+    // in every group, only the position of its own class: the softmax weight of head h for that group's
+    // token.  Output rows (cls, h) therefore accumulate slab 4a + cls of head h, all 16 rows carry useful
+    // work, and the compressed operand is just the zero-extended fp16 weights (the index register, a per-lane
+    // constant, says where they sit).  Operand geometry: compressed dword p of a lane in k-group ga pairs with
+    // the dense operand's k-group 2 (ga % 2) + p / 2, elements 4 (2 (ga / 2) + p % 2) .. + 3.
+    const int sm_idx = (int)(0x1111u * (uint32_t)(tj | ((tj ^ 1) << 2)));
+    // P-tile slot of the (token, head) weights so that the four weights a lane needs are contiguous:
+    // the item in dense k-group gb, element quad e4 of sparse MFMA i -> slot 16 i + 4 ga + p
+    auto p_slot = [](int i, int gb_, int e4) {
+        return 16 * i + 4 * ((gb_ >> 1) + 2 * (e4 >> 1)) + 2 * (gb_ & 1) + (e4 & 1);
+    };
+    auto load_pa = [&](int i) -> half8_t {
+        const uint2_t w2 = *(const uint2_t*)(s_p + (lane & 3) * kPStride + 16 * i + 4 * kgrp);
+        const uint4_t a4 = {w2[0] & 0xffffu, w2[0] >> 16, w2[1] & 0xffffu, w2[1] >> 16};
+        return __builtin_bit_cast(half8_t, a4);
+    };
 
     // ================================================================================== anchors
     const int n_items = p.k_k + p.k_v;                    // K-anchor entries, then V-anchor entries
     const int n_atiles = (n_items + 31) >> 5;
-    if (wave < kAnchorWaves && n_atiles > 0) {
+    if (n_atiles > 0) {
         const half_t* s_qh = (const half_t*)(smem + L::qh);               // Q as MFMA A operand: row = head
-        half_t* s_rows = (half_t*)(smem + L::stage) + wave * 4096;        // [32][128]
-        int* s_win = (int*)(s_p + 128);                                   // 64 ints behind the [4][32] P tile
-        const uint32_t rows_off = (uint32_t)(L::stage + wave * 8192);
-        const int srow = lane >> 1, shalf = lane & 1;                      // staging: this lane fills 64 channels of a row
+        half_t* s_vrows = (half_t*)s_cw;                                  // [8 items][64 channels] fp16
+        int* s_win = (int*)s_cw;                                          // 64 ints in the code-word area
+        const uint32_t rows_off = (uint32_t)(L::pst + wave * kStgBytes + 4 * kPStride * 2);
         for (;;) {
             // tiles of the (b, g) lists are dealt round-robin to the workgroups; this workgroup's tiles are
             // handed out to its anchor waves through a counter
@@ -503,69 +537,65 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                     else if (found >= 0) my_valid = 0;          // V item whose token is also a K anchor: skip
                 }
             }
-            const int r_tok = __shfl(my_tok, srow, 64);
-            const int r_kslot = __shfl(my_kslot, srow, 64);
-            const int r_vslot = __shfl(my_vslot, srow, 64);
-            const bool r_valid = __shfl(my_valid, srow, 64) != 0;
-
-            // 64 channels (8 x 16 bytes) of row `srow`: the FP16 row, or centroids looked up from the codes
-            auto fetch_half_row = [&](int slot, const half_t* rows, int64_t n_rows_per_bg, const uint8_t* codes,
-                                      const half_t* cb, uint4_t (&buf)[8]) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) buf[i] = uint4_t{0u, 0u, 0u, 0u};
-                if (!r_valid) return;
-                if (slot >= 0) {
-                    const uint4_t* src = (const uint4_t*)(rows + ((int64_t)bg * n_rows_per_bg + slot) * kD + 64 * shalf);
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) buf[i] = src[i];
-                } else {
-                    constexpr int SUBS = 64 / DSUB;                       // sub-spaces in half a row
-                    const uint8_t* cp = codes + (int64_t)r_tok * M + SUBS * shalf;
-                    uint32_t cw[SUBS / 4];
-                    if constexpr (SUBS == 4) cw[0] = *(const uint32_t*)cp;
-                    else if constexpr (SUBS == 8) { const uint2_t a = *(const uint2_t*)cp; cw[0] = a[0]; cw[1] = a[1]; }
-                    else { const uint4_t a = *(const uint4_t*)cp; cw[0] = a[0]; cw[1] = a[1]; cw[2] = a[2]; cw[3] = a[3]; }
-#pragma unroll
-                    for (int j = 0; j < SUBS; ++j) {
-                        const int m = SUBS * shalf + j;
-                        const uint32_t code = (cw[j >> 2] >> (8 * (j & 3))) & 255u;
-                        const half_t* cen = cb + ((int64_t)m * 256 + code) * DSUB;
-                        if constexpr (DSUB == 4) {
-                            const uint2_t v = *(const uint2_t*)cen;
-                            if (j & 1) { buf[j >> 1][2] = v[0]; buf[j >> 1][3] = v[1]; }
-                            else { buf[j >> 1][0] = v[0]; buf[j >> 1][1] = v[1]; }
-                        } else if constexpr (DSUB == 8) {
-                            buf[j] = *(const uint4_t*)cen;
-                        } else {
-                            buf[2 * j] = *(const uint4_t*)cen;
-                            buf[2 * j + 1] = *(const uint4_t*)(cen + 8);
-                        }
+            // 16-byte chunk c (channels 8c .. 8c+7) of an item's effective row: from the FP16 row, or centroids
+            // looked up from the token's codes; zero for an entry that is skipped
+            auto fetch_chunk = [&](bool valid, int slot, const half_t* rows, int64_t n_rows_per_bg, int tok,
+                                   const uint8_t* codes, const half_t* cb, int c) -> uint4_t {
+                uint4_t r = {0u, 0u, 0u, 0u};
+                if (valid) {
+                    if (slot >= 0) {
+                        r = *(const uint4_t*)(rows + ((int64_t)bg * n_rows_per_bg + slot) * kD + 8 * c);
+                    } else if constexpr (DSUB == 8) {
+                        const uint32_t code = codes[(int64_t)tok * M + c];
+                        r = *(const uint4_t*)(cb + ((int64_t)c * 256 + code) * 8);
+                    } else if constexpr (DSUB == 16) {
+                        const int m = c >> 1;
+                        const uint32_t code = codes[(int64_t)tok * M + m];
+                        r = *(const uint4_t*)(cb + ((int64_t)m * 256 + code) * 16 + 8 * (c & 1));
+                    } else {
+                        const uint32_t c0 = codes[(int64_t)tok * M + 2 * c], c1 = codes[(int64_t)tok * M + 2 * c + 1];
+                        const uint2_t lo = *(const uint2_t*)(cb + ((int64_t)(2 * c) * 256 + c0) * 4);
+                        const uint2_t hi = *(const uint2_t*)(cb + ((int64_t)(2 * c + 1) * 256 + c1) * 4);
+                        r = uint4_t{lo[0], lo[1], hi[0], hi[1]};
                     }
                 }
+                return r;
             };
-            uint4_t buf[8];
-            fetch_half_row(r_kslot, p.rows_k, p.k_k, ck, cbk, buf);
-            {
-                uint4_t* dst = (uint4_t*)(s_rows + srow * kD + 64 * shalf);
+            // ---- scores: S[head][item] for the two 16-item halves.  The dense operand (item along n, channels
+            // along k) is 8 consecutive channels per lane: it comes straight from global memory.
+            uint4_t kb[2][4];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) dst[i] = buf[i];
+            for (int u = 0; u < 2; ++u) {
+                const int i_tok = __shfl(my_tok, 16 * u + arow, 64), i_slot = __shfl(my_kslot, 16 * u + arow, 64);
+                const bool i_valid = __shfl(my_valid, 16 * u + arow, 64) != 0;
+#pragma unroll
+                for (int st = 0; st < 4; ++st)
+                    kb[u][st] = fetch_chunk(i_valid, i_slot, p.rows_k, p.k_k, i_tok, ck, cbk, 4 * st + kgrp);
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            // start the V rows while the scores are computed
-            fetch_half_row(r_vslot, p.rows_v, p.k_v, cv, cbv, buf);
-
-            // ---- scores: S[head][item] for the two 16-item halves
+            // V rows go through LDS for the transposed reads, 8 items x 64 channels at a time (two of the four
+            // transposed reads of one sparse MFMA): for MFMA i, element-quad pair eh and slab set a this lane
+            // supplies chunk 8a + lane % 8 of item 16 i + 4 (lane / 16) + 2 eh + (lane / 8) % 2
+            uint4_t vq[2][2][2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int eh = 0; eh < 2; ++eh) {
+                    const int it = 16 * i + 4 * kgrp + 2 * eh + ((lane >> 3) & 1);
+                    const int r_tok = __shfl(my_tok, it, 64), r_vslot = __shfl(my_vslot, it, 64);
+                    const bool r_valid = __shfl(my_valid, it, 64) != 0;
+#pragma unroll
+                    for (int a = 0; a < 2; ++a)
+                        vq[i][eh][a] = fetch_chunk(r_valid, r_vslot, p.rows_v, p.k_v, r_tok, cv, cbv, 8 * a + (lane & 7));
+                }
             float sc[2][4];
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 float4_t c4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int st = 0; st < 4; ++st) {
-                    const half8_t kb = *(const half8_t*)(s_rows + (16 * u + arow) * kD + 32 * st + 8 * kgrp);
                     half8_t qa = *(const half8_t*)(s_qh + (arow & 3) * kD + 32 * st + 8 * kgrp);
                     if (arow >= kNH) qa = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-                    c4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa, kb, c4, 0, 0, 0);
+                    c4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa, __builtin_bit_cast(half8_t, kb[u][st]), c4, 0, 0, 0);
                 }
 #pragma unroll
                 for (int r = 0; r < 4; ++r) sc[u][r] = c4[r] * p.c1;   // lanes 0..15: head r, item 16u + lane
@@ -588,8 +618,8 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 const float m_new = fmaxf(m_ref[h], m_tile - kPShift);
                 const float alpha = fast_exp2(m_ref[h] - m_new);
                 l_lane[h] *= alpha;
-#pragma unroll
-                for (int c = 0; c < 8; ++c) acc[c][h] *= alpha;
+                acc[0][h] *= alpha;
+                acc[1][h] *= alpha;
                 m_ref[h] = m_new;
             }
 #pragma unroll
@@ -598,54 +628,82 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 for (int r = 0; r < 4; ++r) {
                     const float pw = fast_exp2(sc[u][r] - m_ref[r]);       // 0 for masked / non-row lanes
                     l_lane[r] += pw;
-                    if (kgrp == 0) s_p[r * 32 + 16 * u + arow] = (half_t)pw;
+                    if (kgrp == 0) s_p[r * kPStride + p_slot(u, arow >> 2, arow & 3)] = (half_t)pw;
                 }
-            __builtin_amdgcn_wave_barrier();
-            // ---- V_eff rows replace the K rows in the staging tile
-            {
-                uint4_t* dst = (uint4_t*)(s_rows + srow * kD + 64 * shalf);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) dst[i] = buf[i];
-            }
+            // ---- P.V: (item, slab) pairs along k; transposed LDS reads turn row-major V rows into the dense operand
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
-            // ---- P.V: tokens along k; transposed LDS reads turn row-major V rows into the B operand
-            half8_t pa = *(const half8_t*)(s_p + (arow & 3) * 32 + 8 * kgrp);
-            if (arow >= kNH) pa = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                half4_t vb[2];
+            for (int i = 0; i < 2; ++i) {
+                const half8_t pa = load_pa(i);
 #pragma unroll
-                for (int hi = 0; hi < 2; ++hi) {
-                    const int row = 8 * kgrp + 4 * hi + tj;
-                    vb[hi] = lds_read_tr16(lsm, rows_off + (uint32_t)(row * kD + 16 * c + 4 * tq) * 2);
+                for (int a = 0; a < 2; ++a) {
+                    half4_t vb[4];
+#pragma unroll
+                    for (int eh = 0; eh < 2; ++eh) {
+                        *(uint4_t*)(s_vrows + (2 * kgrp + ((lane >> 3) & 1)) * 64 + 8 * (lane & 7)) = vq[i][eh][a];
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                        for (int e = 0; e < 2; ++e)
+                            vb[2 * eh + e] = lds_read_tr16(lsm, rows_off + (uint32_t)((2 * kgrp + e) * 64 + 16 * tj + 4 * tq) * 2);
+                        __builtin_amdgcn_wave_barrier();
+                    }
+                    const half16_t bop = {vb[0][0], vb[0][1], vb[0][2], vb[0][3], vb[1][0], vb[1][1], vb[1][2], vb[1][3],
+                                          vb[2][0], vb[2][1], vb[2][2], vb[2][3], vb[3][0], vb[3][1], vb[3][2], vb[3][3]};
+                    acc[a] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(pa, bop, acc[a], sm_idx, 0, 0);
                 }
-                const half8_t bop = {vb[0][0], vb[0][1], vb[0][2], vb[0][3], vb[1][0], vb[1][1], vb[1][2], vb[1][3]};
-                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, bop, acc[c], 0, 0, 0);
             }
-            __builtin_amdgcn_wave_barrier();
         }
     }
 
     // ================================================================================== stream
     {
-        // lane -> token position inside a 64-token tile, chosen so that the four lanes of a quad hold
-        // the V codes of exactly the four tokens whose centroids that quad must fetch for the MFMA
-        const int pos = 32 * (tq >> 1) + 8 * kgrp + 4 * (tq & 1) + tj;
-        // V gather address = cbv + ((m*256 + code)*DSUB + within)*2; the lane part goes into one OR-able constant
-        uint32_t v_lane_off, v_shift_lane;
-        if (DSUB == 8) { v_lane_off = (tq >> 1) * 4096 + (tq & 1) * 8; v_shift_lane = 8 * (tq >> 1); }
-        else if (DSUB == 4) { v_lane_off = tq * 2048; v_shift_lane = 8 * tq; }
-        else { v_lane_off = tq * 8; v_shift_lane = 0; }
-        v_lane_off += L::cbv + (uint32_t)(uintptr_t)lsm;             // absolute LDS address of the lane's table part
-        constexpr int VSH = (DSUB == 8) ? 4 : (DSUB == 4 ? 3 : 5);   // log2(bytes per centroid)
+        // lane -> token position inside a 64-token tile: the identity.  In the P.V geometry the token is item
+        // 16 gb + y of the tile, handled by dense k-group gb = lane / 16.
+        const int pos = lane;
+        const int pslot = p_slot(tj, kgrp, tq);
+        // V gather address = table base | code << 8 | (32 cls + 8 q), plus 128 a as an immediate: one byte permute
+        // of the staged code word (byte v_byte) and a per-lane constant
+        static_assert((L::cbv & 0xffff) == 0, "the V table base must be a multiple of 64 KB");
+        const uint32_t v_const = (uint32_t)(32 * tj + 8 * tq) | (((L::cbv + (uint32_t)(uintptr_t)lsm) >> 16) << 16);
+        const uint32_t v_byte = (DSUB == 8) ? (uint32_t)(2 * (tj & 1) + (tq >> 1)) : (DSUB == 16 ? (uint32_t)tj : (uint32_t)tq);
+        const uint32_t v_sel = 0x0c020000u | ((4u + v_byte) << 8);
+        // V code words are staged per step: DW dwords of TOKS tokens, word-major ([DW][TOKS])
+        constexpr int NSTEP = (DSUB == 16) ? 1 : (DSUB == 8 ? 2 : 4);
+        constexpr int DW = (DSUB == 4) ? 4 : 2;
+        constexpr int TOKS = (DSUB == 4) ? 32 : 64;
+        static_assert(DW * TOKS * 4 <= 512, "code-word staging area");
+        const int stok = (DSUB == 4) ? 8 * kgrp + (lane & 7) : lane;                    // where this lane's token is staged
+        const uint32_t* s_cw_r = s_cw + ((DSUB == 8) ? (tj >> 1) : (DSUB == 4 ? tj : 0)) * TOKS + (TOKS / 4) * kgrp;
         // K gather: this lane visits sub-space (step XOR xr) mod M at every step and reads slot (step XOR xr)
         const uint32_t xr = lane & 31;
-        const uint32_t xr8 = xr << 3;
         const uint32_t kr = xr & (M - 1);                            // XOR applied to the code byte index
-        uint32_t ksh[4];
+        static_assert(L::lut == 0, "the table gather address is an absolute LDS address below 64 KB");
+        uint32_t ksel[4], kc[CW];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) ksh[j] = 8 * (j ^ (kr & 3));
+        for (int j = 0; j < 4; ++j) ksel[j] = 0x0c0c0000u | ((4u + (uint32_t)(j ^ (kr & 3))) << 8) | (uint32_t)j;
+#pragma unroll
+        for (int i = 0; i < CW; ++i) {
+            kc[i] = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) kc[i] |= ((xr ^ (uint32_t)(4 * i + j)) << 3) << (8 * j);
+        }
+        int4_t k_wgt;
+        {
+            const int row_blk = (lane & 15) >> 2, row_h = lane & 3;
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw) {
+                uint32_t wv = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int i = 4 * dw + j;                              // byte of the 16-byte operand
+                    const uint32_t wt = (i & 1) ? 0x80u : 0x01u;           // -128 on hi bytes, 1 on lo bytes
+                    if (kgrp == row_blk && ((i & 7) >> 1) == row_h) wv |= wt << (8 * j);
+                }
+                k_wgt[dw] = (int)wv;
+            }
+        }
 
         const int64_t n_tiles = (t1 - t0 + 63) >> 6;
         auto grab_tile = [&]() -> int64_t {
@@ -699,17 +757,19 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                     }
                 }
             }
-            int si[kNH] = {0, 0, 0, 0};
+            // One table read per (token, sub-space): the address (code << 8 | slot << 3) is a single byte permute
+            // of the code dword and a per-lane constant.  Two entries (16 bytes) form this lane's B operand of an
+            // int8 MFMA whose A operand is block-diagonal: row 4*(lane/16) + h carries the weights (1, -128) on
+            // the (lo, hi) bytes of head h in k-group lane/16 only, so C row r of a lane is its own token's sum
+            // for head r.
+            int4_t si = {0, 0, 0, 0};
 #pragma unroll
-            for (int st = 0; st < M; ++st) {
-                const uint32_t code = __builtin_amdgcn_ubfe(kw[st >> 2], ksh[st & 3], 8);
-                const uint32_t slot8 = xr8 ^ (uint32_t)(8 * st);
-                const short4_t e = *(const short4_t*)(smem + L::lut + ((code << 8) | slot8));
-                const short2_t e01 = __builtin_shufflevector(e, e, 0, 1), e23 = __builtin_shufflevector(e, e, 2, 3);
-                si[0] = __builtin_amdgcn_sdot2(e01, short2_t{1, 0}, si[0], false);
-                si[1] = __builtin_amdgcn_sdot2(e01, short2_t{0, 1}, si[1], false);
-                si[2] = __builtin_amdgcn_sdot2(e23, short2_t{1, 0}, si[2], false);
-                si[3] = __builtin_amdgcn_sdot2(e23, short2_t{0, 1}, si[3], false);
+            for (int st = 0; st < M; st += 2) {
+                const uint32_t a0 = __builtin_amdgcn_perm(kw[st >> 2], kc[st >> 2], ksel[st & 3]);
+                const uint32_t a1 = __builtin_amdgcn_perm(kw[(st + 1) >> 2], kc[(st + 1) >> 2], ksel[(st + 1) & 3]);
+                const uint2_t e0 = *(const lds_uint2*)(uintptr_t)a0;
+                const uint2_t e1 = *(const lds_uint2*)(uintptr_t)a1;
+                si = __builtin_amdgcn_mfma_i32_16x16x64_i8(k_wgt, int4_t{(int)e0[0], (int)e0[1], (int)e1[0], (int)e1[1]}, si, 0, 0, 0);
             }
             float s[kNH];
             bool grow = false;
@@ -725,8 +785,8 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                     const float m_new = fmaxf(m_ref[h], mx - kPShift);
                     const float alpha = fast_exp2(m_ref[h] - m_new);
                     l_lane[h] *= alpha;
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) acc[c][h] *= alpha;
+                    acc[0][h] *= alpha;
+                    acc[1][h] *= alpha;
                     m_ref[h] = m_new;
                 }
             }
@@ -734,31 +794,42 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             for (int h = 0; h < kNH; ++h) {
                 const float pw = fast_exp2(s[h] - m_ref[h]);
                 l_lane[h] += pw;
-                s_p[h * 64 + pos] = (half_t)pw;
+                s_p[h * kPStride + pslot] = (half_t)pw;
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
 
-            // ---- V side: the V codes of token (u, hi) of this quad sit in quad lane 2u+hi
+            // ---- V side: sparse MFMA i of slab set a takes tokens 16 gb + 4 i + e4 (e4 < 4) in dense k-group gb,
+            // the four rows of each transposed read being the four slabs 4a + cls of one token
+            half8_t pa[4];
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                half8_t pa = *(const half8_t*)(s_p + (arow & 3) * 64 + 32 * u + 8 * kgrp);
-                if (arow >= kNH) pa = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-                constexpr int SPD = (DSUB == 8) ? 2 : (DSUB == 4 ? 1 : 4);   // channel slabs served by one code dword
+            for (int i = 0; i < 4; ++i) pa[i] = load_pa(i);
 #pragma unroll
-                for (int cd = 0; cd < 8 / SPD; ++cd) {
-                    const uint32_t w0 = quad_bcast_sel(vw[cd], 2 * u), w1 = quad_bcast_sel(vw[cd], 2 * u + 1);
+            for (int step = 0; step < NSTEP; ++step) {
+                const int a_s = (DSUB == 8) ? step : (DSUB == 4 ? (step >> 1) : 0);
+                const int th = (DSUB == 4) ? (step & 1) : 0;
+                if (step) __builtin_amdgcn_wave_barrier();
+                if (DSUB != 4 || ((lane >> 3) & 1) == th) {
 #pragma unroll
-                    for (int cs = 0; cs < SPD; ++cs) {
-                        const int c = cd * SPD + cs;
-                        const int sh_c = (DSUB == 8) ? 16 * cs : (DSUB == 4 ? 0 : 8 * cs);   // code byte inside the dword
-                        const uint32_t code0 = __builtin_amdgcn_ubfe(w0, sh_c + v_shift_lane, 8);
-                        const uint32_t code1 = __builtin_amdgcn_ubfe(w1, sh_c + v_shift_lane, 8);
-                        // (the slab offset c*8192 is a compile-time addend that lands in the DS immediate field)
-                        const half4_t vb0 = lds_read_tr16_abs(((code0 << VSH) + v_lane_off) + c * 8192);
-                        const half4_t vb1 = lds_read_tr16_abs(((code1 << VSH) + v_lane_off) + c * 8192);
-                        const half8_t bop = {vb0[0], vb0[1], vb0[2], vb0[3], vb1[0], vb1[1], vb1[2], vb1[3]};
-                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, bop, acc[c], 0, 0, 0);
+                    for (int dl = 0; dl < DW; ++dl)
+                        s_cw[dl * TOKS + stok] = vw[((DSUB == 8) ? 2 * a_s : (DSUB == 4 ? 4 * a_s : 0)) + dl];
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int ii = 0; ii < TOKS / 16; ++ii) {
+                    const int i = (DSUB == 4) ? 2 * th + ii : ii;
+#pragma unroll
+                    for (int aa = 0; aa < ((DSUB == 16) ? 2 : 1); ++aa) {
+                        const int a = (DSUB == 16) ? aa : a_s;
+                        const uint4_t cw = *(const uint4_t*)(s_cw_r + ((DSUB == 16) ? a * TOKS : 0) + 4 * ii);
+                        half4_t vb[4];
+#pragma unroll
+                        for (int e4 = 0; e4 < 4; ++e4)
+                            vb[e4] = lds_read_tr16_abs(__builtin_amdgcn_perm(cw[e4], v_const, v_sel) + 128 * a);
+                        const half16_t bop = {vb[0][0], vb[0][1], vb[0][2], vb[0][3], vb[1][0], vb[1][1], vb[1][2], vb[1][3],
+                                              vb[2][0], vb[2][1], vb[2][2], vb[2][3], vb[3][0], vb[3][1], vb[3][2], vb[3][3]};
+                        acc[a] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(pa[i], bop, acc[a], sm_idx, 0, 0);
                     }
                 }
             }
