@@ -33,6 +33,8 @@
 // to fp16, so the whole step is one kernel behind a small counter-clearing launch.
 #include "common.h"
 
+#include <atomic>
+
 namespace antkv {
 
 namespace {
@@ -158,7 +160,8 @@ struct DaParams {
     const half_t *rows_k, *rows_v;
     float* part;                // [B][Hq][S][kD + 2]
     half_t* out;                // [B][Hq][kD]
-    unsigned int* done;         // [B][Hkv] arrival counters, zero at launch; the last workgroup of a (b, g) merges
+    unsigned long long* done;   // [B][Hkv] arrival words (launch tag << 32 | count); the last workgroup of a (b, g) merges
+    unsigned int tag;           // this launch's tag: words carrying another tag count as zero, so no clearing pass
     int64_t N, N_cap;
     int k_k, k_v;
     float c1;                   // scale * log2(e)
@@ -273,6 +276,13 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     const int64_t t1 = (t0 + p.chunk < p.N) ? t0 + p.chunk : p.N;
 
     DA_STAMP(0);
+    // Arrival word of this (b, g): (launch tag << 32 | arrivals).  A word left by an earlier launch (another tag,
+    // or this tag with all S arrivals when a captured launch is replayed) is replaced by (tag, 0) now, by
+    // whichever workgroup gets there first, so that the arrival at the end is a single fetch-add.  Launches
+    // that share a workspace do not overlap, hence nobody of an earlier launch still touches the word.
+    // (the word is loaded here, with the other loads of the prologue, and swapped once those have landed)
+    unsigned long long done_seen = 0ull;
+    if (tid == 0) done_seen = __hip_atomic_load(&p.done[bg], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // MFMA lane coordinates
     const int kgrp = lane >> 4;           // tr block / k group
     const int tj = (lane >> 2) & 3;       // token within a group of four
@@ -344,13 +354,11 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             if (!((wave < 2) ? scan_k : scan_v)) r = wave_lower_bound(arr, n, (int)((wave & 1) ? t1 : t0), lane);
             if (lane == 0) s_misc[wave] = r;
         }
-        {
-            uint4_t* dst = (uint4_t*)(smem + L::cbv);
-#pragma unroll
-            for (int i = 0; i < 4096 / kDaThreads; ++i) dst[tid + i * kDaThreads] = vcopy[i];
-        }
         __syncthreads();
         DA_STAMP(7);
+        if (tid == 0 && ((unsigned int)(done_seen >> 32) != p.tag || (unsigned int)done_seen >= (unsigned int)p.S))
+            __hip_atomic_compare_exchange_strong(&p.done[bg], &done_seen, (unsigned long long)p.tag << 32, __ATOMIC_RELAXED,
+                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         // LUT[m][c][h] = c1 * q_h[m*d : (m+1)*d] . cb_k[g][m][c], stored as fixed point with one scale per head
         // (quantum = max|LUT_h| / 16256): the per-token sum over sub-spaces is then exact integer arithmetic and
         // the table error is uniform instead of growing with the entry's magnitude as it would in fp16.
@@ -421,6 +429,12 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             const uint2_t ent = uint2_t{hw[0] | (hw[1] << 16), hw[2] | (hw[3] << 16)};
 #pragma unroll
             for (int rep = 0; rep < 32 / M; ++rep) s_lut[(lc0 + TPM * i) * 32 + lm + M * rep] = ent;
+        }
+        // the V table is not needed before the first P.V: its loads had the whole table build to land
+        {
+            uint4_t* dst = (uint4_t*)(smem + L::cbv);
+#pragma unroll
+            for (int i = 0; i < 4096 / kDaThreads; ++i) dst[tid + i * kDaThreads] = vcopy[i];
         }
         // bitmap of anchored tokens in this range
 #pragma unroll
@@ -853,9 +867,10 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     // thread bump the device-scope counter.  The merging workgroup reads with device-scope loads.
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    if (tid == 0) s_misc[10] = (int)__hip_atomic_fetch_add(&p.done[bg], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0)
+        s_misc[10] = (int)(unsigned int)__hip_atomic_fetch_add(&p.done[bg], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
     __syncthreads();
-    if (s_misc[10] == p.S - 1) {
+    if (s_misc[10] == p.S) {
         if (tid < kNH * kD) {
             const int h = tid >> 7, dim = tid & 127;
             if (h < nheads) {
@@ -872,15 +887,8 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 p.out[((int64_t)b * p.Hq + h0 + h) * kD + dim] = (half_t)(l > 0.f ? a / l : 0.f);
             }
         }
-        if (tid == 0) __hip_atomic_store(&p.done[bg], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     DA_STAMP(5);
-}
-
-__global__ __launch_bounds__(256) void zero_done_kernel(unsigned int* done, int n)
-{
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n) done[i] = 0u;
 }
 
 __global__ __launch_bounds__(128) void zero_out_kernel(half_t* out, int64_t n)
@@ -1096,7 +1104,7 @@ DaPlan da_plan(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans
     off += align_up((size_t)g.B * g.Hkv * pl.S * 8 * sizeof(unsigned long long));   // trace lives at offset 0
 #endif
     pl.off_part = off; off += align_up((size_t)g.B * g.Hq * pl.S * (kD + 2) * sizeof(float));
-    pl.off_done = off; off += align_up((size_t)g.B * g.Hkv * sizeof(unsigned int));
+    pl.off_done = off; off += align_up((size_t)g.B * g.Hkv * sizeof(unsigned long long));
     pl.off_stat = off; off += want_ans ? align_up((size_t)g.B * g.Hq * pl.S * 2 * sizeof(float)) : 0;
     pl.off_lse = off;  off += align_up((size_t)g.B * g.Hq * sizeof(float));
     pl.total = off;
@@ -1118,6 +1126,16 @@ size_t decode_workspace_bytes(const Geom& g, int64_t N, int64_t k_k, int64_t k_v
     return da_plan(g, N, k_k, k_v, want_ans).total;
 }
 
+// Launch tags are unique within the process (a wrap after 2^32 launches could only matter for a workspace
+// last used exactly 2^32 launches earlier); 0 is never handed out.
+static unsigned int next_launch_tag()
+{
+    static std::atomic<unsigned int> counter{1u};
+    unsigned int t = counter.fetch_add(1u, std::memory_order_relaxed);
+    if (t == 0u) t = counter.fetch_add(1u, std::memory_order_relaxed);
+    return t;
+}
+
 template <int DSUB>
 static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st)
 {
@@ -1129,14 +1147,13 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     DaParams p;
     p.q = a.q; p.codes_k = a.codes_k; p.codes_v = a.codes_v; p.cb_k = a.cb_k; p.cb_v = a.cb_v;
     p.idx_k = a.idx_k; p.idx_v = a.idx_v; p.rows_k = a.rows_k; p.rows_v = a.rows_v;
-    p.part = part; p.out = a.out; p.done = (unsigned int*)(w + pl.off_done); p.N = a.N; p.N_cap = a.N_cap; p.k_k = (int)a.k_k; p.k_v = (int)a.k_v;
+    p.part = part; p.out = a.out; p.done = (unsigned long long*)(w + pl.off_done); p.tag = next_launch_tag(); p.N = a.N; p.N_cap = a.N_cap; p.k_k = (int)a.k_k; p.k_v = (int)a.k_v;
     p.trace = (unsigned long long*)ws;
     p.c1 = a.scale * kLog2e; p.Hq = g.Hq; p.Hkv = g.Hkv; p.G = g.G; p.S = pl.S; p.chunk = pl.chunk;
     const size_t shmem = Lds<DSUB>::total;
     hipError_t e = hipFuncSetAttribute((const void*)decode_attn_kernel<DSUB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((int64_t)g.B * g.Hkv * pl.S);
-    hipLaunchKernelGGL(zero_done_kernel, dim3((unsigned)((g.B * g.Hkv + 255) / 256)), dim3(256), 0, st, p.done, g.B * g.Hkv);
     if (t_ev_start) (void)hipEventRecord(t_ev_start, st);
     hipLaunchKernelGGL(decode_attn_kernel<DSUB>, dim3(grid), dim3(kDaThreads), shmem, st, p);
     if (t_ev_stop) (void)hipEventRecord(t_ev_stop, st);
