@@ -48,7 +48,11 @@ constexpr int kNH = 4;                 // query-head slots per workgroup (group 
 constexpr float kPShift = 8.0f;        // P is scaled by 2^8 so that small weights stay normal in fp16
 constexpr float kLutMax = 16256.0f;    // largest table magnitude: 127 * 128, so that both bytes of an entry fit int8
 constexpr int kPStride = 72;           // fp16 elements between the heads of a wave's P tile (64 + pad against bank conflicts)
-constexpr int kStgBytes = 4 * kPStride * 2 + 1024;  // per-wave staging: P tile, then 1 KB of V code words / anchor V rows
+constexpr int kPStride32 = 68;         // dwords between the heads of the stream's P tile (zero-extended fp16 weights)
+// per-wave staging.  Anchor tiles: fp16 P tile, then 1 KB of V rows.  Stream: dword P tile, then the V code words
+// (two padded rows of 68 dwords, or four of 36).
+constexpr int kStgBytes = 4 * kPStride32 * 4 + 4 * 36 * 4;
+static_assert(4 * kPStride * 2 + 1024 <= kStgBytes && kStgBytes % 16 == 0, "anchor staging fits the per-wave area");
 constexpr float kEmptyRef = -1.0e4f;   // softmax reference before any token was seen: finite, below every real score,
                                        // and far above the masked score kNegBig so that exp2(masked - ref) is 0
 
@@ -687,9 +691,9 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         constexpr int NSTEP = (DSUB == 16) ? 1 : (DSUB == 8 ? 2 : 4);
         constexpr int DW = (DSUB == 4) ? 4 : 2;
         constexpr int TOKS = (DSUB == 4) ? 32 : 64;
-        static_assert(DW * TOKS * 4 <= 512, "code-word staging area");
+        constexpr int CWROW = TOKS + 4;                    // padded row: rows read together fall on different banks
+        static_assert(DW * CWROW * 4 <= kStgBytes - 4 * kPStride32 * 4, "code-word staging area");
         const int stok = (DSUB == 4) ? 8 * kgrp + (lane & 7) : lane;                    // where this lane's token is staged
-        const uint32_t* s_cw_r = s_cw + ((DSUB == 8) ? (tj >> 1) : (DSUB == 4 ? tj : 0)) * TOKS + (TOKS / 4) * kgrp;
         // K gather: this lane visits sub-space (step XOR xr) mod M at every step and reads slot (step XOR xr)
         const uint32_t xr = lane & 31;
         const uint32_t kr = xr & (M - 1);                            // XOR applied to the code byte index
@@ -741,24 +745,27 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 }
             }
         };
-        uint32_t kw_next[CW], vw_next[CW];
-        int64_t tile = grab_tile();
-        if (tile < n_tiles) load_codes(tile, kw_next, vw_next);
-        while (tile < n_tiles) {
-            const int64_t tok = t0 + tile * 64 + pos;
-            uint32_t kw[CW], vw[CW];
+        uint32_t* s_p32 = (uint32_t*)s_p;                          // stream P tile: the sparse operand's dwords, ready-made
+        uint32_t* s_cws = s_p32 + 4 * kPStride32;                  // stream code words
+        const uint32_t* s_cws_r = s_cws + ((DSUB == 8) ? (tj >> 1) : (DSUB == 4 ? tj : 0)) * CWROW + (TOKS / 4) * kgrp;
+        const uint32_t* s_pa_r = s_p32 + (lane & 3) * kPStride32 + 4 * kgrp;
+        float neg_m[kNH];                                          // -m_ref, the addend of the exponent
 #pragma unroll
-            for (int i = 0; i < CW; ++i) { kw[i] = kw_next[i]; vw[i] = vw_next[i]; }
-            const int64_t tile_next = grab_tile();
-            if (tile_next < n_tiles) load_codes(tile_next, kw_next, vw_next);
+        for (int h = 0; h < kNH; ++h) neg_m[h] = -m_ref[h];
+
+        auto do_tile = [&](int64_t tile, const uint32_t (&kw_in)[CW], const uint32_t (&vw)[CW]) {
+            const int64_t tok = t0 + tile * 64 + pos;
             const int rel = (int)(tok - t0);
             const uint32_t mbit = (s_mask[(rel >> 5) & (L::mask_words - 1)] >> (rel & 31)) & 1u;
-            // 1.0 for tokens that are anchored or past the end of the range: an arithmetic mask keeps the
-            // table gathers below unconditional (no divergent branch around them)
-            const float mf = (tok < t1) ? (float)mbit : 1.0f;
+            // tokens that are anchored or past the end of the range get weight zero; their table gathers still
+            // run (no divergent branch around them)
+            const bool masked = (tok >= t1) || (mbit != 0u);
 
             // ---- K side: scores in log2 units.  Code dwords are XOR-permuted so that step s finds the code of
-            // sub-space (s XOR kr) at a compile-time register and a per-lane constant byte shift.
+            // sub-space (s XOR kr) at a compile-time register and a per-lane constant byte selector.
+            uint32_t kw[CW];
+#pragma unroll
+            for (int i = 0; i < CW; ++i) kw[i] = kw_in[i];
 #pragma unroll
             for (int bit = 0; (4 << bit) < M; ++bit) {
                 const bool sw = (kr >> (2 + bit)) & 1u;
@@ -785,30 +792,32 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 const uint2_t e1 = *(const lds_uint2*)(uintptr_t)a1;
                 si = __builtin_amdgcn_mfma_i32_16x16x64_i8(k_wgt, int4_t{(int)e0[0], (int)e0[1], (int)e1[0], (int)e1[1]}, si, 0, 0, 0);
             }
-            float s[kNH];
+            // exponent of the weight relative to the reference: x = score - m_ref
+            float x[kNH];
             bool grow = false;
 #pragma unroll
             for (int h = 0; h < kNH; ++h) {
-                s[h] = fmaf(mf, kNegBig, (float)si[h] * lut_q[h]);
-                grow = grow || (s[h] > m_ref[h] + kPShift);
+                x[h] = fmaf((float)si[h], lut_q[h], neg_m[h]);
+                grow = grow || (x[h] > kPShift);
             }
-            if (__any(grow)) {   // some score exceeds the running maximum: move the reference, rescale
+            if (__any(grow && !masked)) {   // some score exceeds the running maximum: move the reference, rescale
 #pragma unroll
                 for (int h = 0; h < kNH; ++h) {
-                    const float mx = wave_max_uniform(s[h]);
-                    const float m_new = fmaxf(m_ref[h], mx - kPShift);
-                    const float alpha = fast_exp2(m_ref[h] - m_new);
+                    const float mx = wave_max_uniform(masked ? kNegBig : x[h]) - neg_m[h];   // largest unmasked score
+                    const float m_new = fmaxf(-neg_m[h], mx - kPShift);
+                    const float alpha = fast_exp2(-neg_m[h] - m_new);
                     l_lane[h] *= alpha;
                     acc[0][h] *= alpha;
                     acc[1][h] *= alpha;
-                    m_ref[h] = m_new;
+                    neg_m[h] = -m_new;
+                    x[h] = fmaf((float)si[h], lut_q[h], neg_m[h]);
                 }
             }
 #pragma unroll
             for (int h = 0; h < kNH; ++h) {
-                const float pw = fast_exp2(s[h] - m_ref[h]);
+                const float pw = masked ? 0.f : fast_exp2(x[h]);
                 l_lane[h] += pw;
-                s_p[h * kPStride + pslot] = (half_t)pw;
+                s_p32[h * kPStride32 + pslot] = (uint32_t)__builtin_bit_cast(unsigned short, (half_t)pw);
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -817,7 +826,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             // the four rows of each transposed read being the four slabs 4a + cls of one token
             half8_t pa[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) pa[i] = load_pa(i);
+            for (int i = 0; i < 4; ++i) pa[i] = __builtin_bit_cast(half8_t, *(const uint4_t*)(s_pa_r + 16 * i));
 #pragma unroll
             for (int step = 0; step < NSTEP; ++step) {
                 const int a_s = (DSUB == 8) ? step : (DSUB == 4 ? (step >> 1) : 0);
@@ -826,7 +835,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 if (DSUB != 4 || ((lane >> 3) & 1) == th) {
 #pragma unroll
                     for (int dl = 0; dl < DW; ++dl)
-                        s_cw[dl * TOKS + stok] = vw[((DSUB == 8) ? 2 * a_s : (DSUB == 4 ? 4 * a_s : 0)) + dl];
+                        s_cws[dl * CWROW + stok] = vw[((DSUB == 8) ? 2 * a_s : (DSUB == 4 ? 4 * a_s : 0)) + dl];
                 }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
@@ -836,7 +845,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
 #pragma unroll
                     for (int aa = 0; aa < ((DSUB == 16) ? 2 : 1); ++aa) {
                         const int a = (DSUB == 16) ? aa : a_s;
-                        const uint4_t cw = *(const uint4_t*)(s_cw_r + ((DSUB == 16) ? a * TOKS : 0) + 4 * ii);
+                        const uint4_t cw = *(const uint4_t*)(s_cws_r + ((DSUB == 16) ? a * CWROW : 0) + 4 * ii);
                         half4_t vb[4];
 #pragma unroll
                         for (int e4 = 0; e4 < 4; ++e4)
@@ -848,8 +857,22 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 }
             }
             __builtin_amdgcn_wave_barrier();
+        };
+
+        uint32_t kw_next[CW], vw_next[CW];
+        int64_t tile = grab_tile();
+        if (tile < n_tiles) load_codes(tile, kw_next, vw_next);
+        while (tile < n_tiles) {
+            uint32_t kw_c[CW], vw_c[CW];
+#pragma unroll
+            for (int i = 0; i < CW; ++i) { kw_c[i] = kw_next[i]; vw_c[i] = vw_next[i]; }
+            const int64_t tile_next = grab_tile();
+            if (tile_next < n_tiles) load_codes(tile_next, kw_next, vw_next);
+            do_tile(tile, kw_c, vw_c);
             tile = tile_next;
         }
+#pragma unroll
+        for (int h = 0; h < kNH; ++h) m_ref[h] = -neg_m[h];
     }
     DA_STAMP(2);
     float l_sum[kNH];
