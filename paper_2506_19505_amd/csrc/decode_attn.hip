@@ -4,33 +4,34 @@
 //
 // A workgroup (16 waves) owns a contiguous token range of one (sequence, KV head).
 //
-//  prologue  build the q.centroid lookup table LUT[code][slot][head] (16-bit fixed point, pre-multiplied by
-//            scale*log2e), copy the V codebook into LDS, mark the anchored tokens of the range in an LDS bitmap.
-//            The table is stored with 32 eight-byte slots per code row (= all 64 LDS banks); slot j holds
-//            sub-space j mod M.  Lane l reads slot (step XOR (l mod 32)) at every step, i.e. it walks the
-//            sub-spaces in its own XOR-permuted order: the 32 lanes that the LDS serves per clock always hit
-//            32 different bank pairs, whatever the codes are (random gathers would run at a third of that).
+//  prologue  build the q.centroid lookup table LUT[code][slot][head] (15-bit fixed point stored as two signed
+//            bytes, pre-multiplied by scale*log2e), copy the V codebook into LDS code-major, mark the anchored
+//            tokens of the range in an LDS bitmap.  The table has 32 eight-byte slots per code row (= all 64
+//            LDS banks); slot j holds sub-space j mod M.  Lane l reads slot (step XOR (l mod 32)) at every
+//            step, i.e. it walks the sub-spaces in its own XOR-permuted order: the 32 lanes that the LDS
+//            serves per clock always hit 32 different bank pairs, whatever the codes are (random gathers
+//            would run at a third of that).
+//  anchors   the (sequence, KV head)'s anchor lists are cut into 32-entry tiles dealt round-robin to the
+//            workgroups (balanced by list index, not by position: anchors cluster at the head and tail of a
+//            context); inside a workgroup whichever wave is free takes the next tile before it joins the
+//            stream.  K_eff chunks (the FP16 row, or the de-quantised codes when only V of that token is
+//            anchored) go straight from global memory into the MFMA operand; V_eff rows pass through the
+//            wave's staging area for the transposed reads.
 //  stream    waves pull 64-token tiles from a shared counter, code loads running one tile ahead:
 //      K side  one lane per token: 16-byte coalesced code loads, one 8-byte LUT gather per sub-space
-//              serves the group's four query heads, exact integer accumulation;
+//              serves the group's four query heads; an int8 MFMA with a constant block-diagonal operand
+//              sums the entries exactly (C row r of a lane = its own token, head r);
 //      softmax base-2 online softmax against a lazily updated reference maximum (the wave only pays
 //              the cross-lane reduction when some score exceeds the reference);
-//      V side  P (fp16) goes through a 512-byte LDS staging buffer into MFMA A-operand layout; V
-//              centroids are fetched from the LDS codebook with ds_read_b64_tr_b16, whose lane
-//              transposition yields the MFMA B operand (tokens along k) directly;
-//              v_mfma_f32_16x16x32_f16 accumulates P.V in fp32.
+//      V side  the weights (fp16, zero-extended) and the V code words go through the wave's LDS staging
+//              area; V centroids are fetched with ds_read_b64_tr_b16, whose lane transposition yields the
+//              dense MFMA operand; the 2:4-sparse MFMA accumulates P.V in fp32 with all 16 rows in use
+//              (rows = slab class x head, see the comment at sm_idx).
 //      Tokens that have an FP16 anchor row (for K or for V) are masked out of the stream.
-//  anchors   the first kAnchorWaves waves start on the anchor lists instead (then join the stream): the
-//            lists of the (sequence, KV head) are cut into 32-token tiles dealt round-robin to the workgroups
-//            (balanced by list index, not by position: anchors cluster at the head and tail of a context).
-//            A wave stages K_eff rows (the FP16 row, or the de-quantised codes when only V of that token is
-//            anchored) in its own LDS tile, scores them with one MFMA chain, stages V_eff rows and accumulates
-//            P.V through the same transposed-read + MFMA path.  This latency-bound work overlaps the
-//            LDS-bound stream of the other waves.
 //
 // The workgroup merges its waves and writes one partial (reference max, sum, accumulator) per query head;
 // the last workgroup of a (sequence, KV head) to finish merges the partials by log-sum-exp and rounds once
-// to fp16, so the whole step is one kernel behind a small counter-clearing launch.
+// to fp16: the whole step is one kernel.
 #include "common.h"
 
 #include <atomic>
