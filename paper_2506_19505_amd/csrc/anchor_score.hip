@@ -34,6 +34,25 @@ __device__ __forceinline__ void load_tile(Tile128& t, const half_t* row_ptr, int
     for (int s = 0; s < 8; ++s) t.v[s] = *(const half8_t*)(row_ptr + 16 * s + 8 * kh);
 }
 
+// A 32-row x 128-channel tile shared by the waves of a workgroup sits in LDS with rows padded to 136 halfs
+// (272 bytes): the 16 lanes that one 16-byte LDS read serves per clock then fall on 16 different bank quads.
+constexpr int kRowPad = 136;
+constexpr int kTileHalfs = 32 * kRowPad;
+
+// rows x staged tile: the staged tile is the A operand (rows of the result), the register tile the B operand
+__device__ __forceinline__ float16_t tile_dot_lds_a(const half_t* __restrict__ st, const Tile128& b, int n, int kh)
+{
+    float16_t acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        const half8_t a = *(const half8_t*)(st + n * kRowPad + 16 * s + 8 * kh);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b.v[s], acc, 0, 0, 0);
+    }
+    return acc;
+}
+
 __device__ __forceinline__ float16_t tile_dot(const Tile128& a, const Tile128& b)
 {
     float16_t acc;
@@ -53,59 +72,90 @@ __global__ __launch_bounds__(kAsThreads) void ans_row_stats(
     const half_t* __restrict__ q, const half_t* __restrict__ k, int64_t N, int64_t Nq, float c1,
     float* __restrict__ part, int Hq, int Hkv, int G, int KS, int64_t keys_per_split)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ __attribute__((aligned(16))) half_t s_k[2][kTileHalfs];   // key tiles, double-buffered
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, kh = lane >> 5;
     const int ks = blockIdx.x;
     const int64_t qblk = blockIdx.y;
     const int b = blockIdx.z / Hkv, g = blockIdx.z % Hkv;
     const int64_t q0 = qblk * 64 + (wave >> 2) * 32;           // first query row of this wave's tile
-    if (q0 >= Nq) return;
+    const bool wave_on = q0 < Nq;
     const int64_t qi = q0 + n;                                  // this lane's query row
     const int64_t qrow = qi < Nq ? qi : Nq - 1;
     const int64_t qpos = N - Nq + qrow;                         // absolute position = last visible key
     const int64_t tile_last_pos = N - Nq + ((q0 + 31 < Nq) ? q0 + 31 : Nq - 1);
     const int64_t k_lo = (int64_t)ks * keys_per_split;
-    int64_t k_hi = k_lo + keys_per_split;
+    // keys this workgroup walks: up to the last key any of its queries can see
+    const int64_t blk_last_pos = N - Nq + ((qblk * 64 + 63 < Nq) ? qblk * 64 + 63 : Nq - 1);
+    int64_t k_end = k_lo + keys_per_split;
+    if (k_end > blk_last_pos + 1) k_end = blk_last_pos + 1;
+    int64_t k_hi = k_lo + keys_per_split;                       // this wave's own limit
     if (k_hi > tile_last_pos + 1) k_hi = tile_last_pos + 1;
     const half_t* kbase = k + ((int64_t)b * Hkv + g) * N * kD;
+    // staging: thread t moves 16 bytes: row t / 16, chunk t % 16 of the tile
+    const int srow = tid >> 4, schunk = tid & 15;
+    auto fetch = [&](int64_t kt) -> uint4_t {
+        const int64_t krow = (kt + srow < N) ? kt + srow : N - 1;
+        return *(const uint4_t*)(kbase + krow * kD + 8 * schunk);
+    };
 
-    for (int hh = (wave & 3); hh < G; hh += 4) {
-        const int h = g * G + hh;
+    for (int h_it = 0; h_it < (G + 3) / 4; ++h_it) {
+        const int hh = 4 * h_it + (wave & 3);
+        const bool head_on = wave_on && hh < G;
+        const int h = g * G + (hh < G ? hh : G - 1);
         Tile128 tq;
         load_tile(tq, q + (((int64_t)b * Hq + h) * Nq + qrow) * kD, kh);
         float m_run = kNegBig, l_run = 0.f;
-        for (int64_t kt = k_lo; kt < k_hi; kt += 32) {
-            const int64_t krow = (kt + n < N) ? kt + n : N - 1;
-            Tile128 tk;
-            load_tile(tk, kbase + krow * kD, kh);
-            const float16_t acc = tile_dot(tk, tq);             // rows = keys, cols = queries
-            float s2[16];
-            float mx = kNegBig;
+        int buf = 0;
+        if (k_lo < k_end) *(uint4_t*)(&s_k[0][srow * kRowPad + 8 * schunk]) = fetch(k_lo);
+        __syncthreads();
+        for (int64_t kt = k_lo; kt < k_end; kt += 32) {
+            const bool more = kt + 32 < k_end;
+            uint4_t nxt = {0u, 0u, 0u, 0u};
+            if (more) nxt = fetch(kt + 32);
+            if (head_on && kt < k_hi) {
+                const float16_t acc = tile_dot_lds_a(s_k[buf], tq, n, kh);   // rows = keys, cols = queries
+                float s2[16];
+                float mx = kNegBig;
+                if (kt + 31 <= N - Nq + q0 && kt + 31 < k_hi) {    // every key of the tile is visible to every query
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t key = kt + 8 * (r >> 2) + 4 * kh + (r & 3);
-                const bool vis = (key <= qpos) && (key < k_hi);
-                s2[r] = vis ? acc[r] * c1 : kNegBig;
-                mx = fmaxf(mx, s2[r]);
+                    for (int r = 0; r < 16; ++r) {
+                        s2[r] = acc[r] * c1;
+                        mx = fmaxf(mx, s2[r]);
+                    }
+                } else {
+                    const int lim_q = (int)(qpos - kt), lim_k = (int)(k_hi - kt);   // visible: offset <= lim_q, < lim_k
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int off = 8 * (r >> 2) + 4 * kh + (r & 3);
+                        const bool vis = (off <= lim_q) && (off < lim_k);
+                        s2[r] = vis ? acc[r] * c1 : kNegBig;
+                        mx = fmaxf(mx, s2[r]);
+                    }
+                }
+                const float m_new = fmaxf(m_run, mx);
+                float sum = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sum += fast_exp2(s2[r] - m_new);
+                // all-masked so far: m_new stays at kNegBig and exp2(0) terms must not count
+                if (m_new <= kNegBig) sum = 0.f;
+                l_run = l_run * fast_exp2(m_run - m_new) + sum;
+                m_run = m_new;
             }
-            const float m_new = fmaxf(m_run, mx);
-            float sum = 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sum += fast_exp2(s2[r] - m_new);
-            // all-masked so far: m_new stays at kNegBig and exp2(0) terms must not count
-            if (m_new <= kNegBig) sum = 0.f;
-            l_run = l_run * fast_exp2(m_run - m_new) + sum;
-            m_run = m_new;
+            if (more) *(uint4_t*)(&s_k[buf ^ 1][srow * kRowPad + 8 * schunk]) = nxt;
+            __syncthreads();
+            buf ^= 1;
         }
         // merge the two half-waves (they saw complementary keys of the same query)
         const float m_o = __shfl_xor(m_run, 32, 64), l_o = __shfl_xor(l_run, 32, 64);
         const float m_f = fmaxf(m_run, m_o);
         const float l_f = l_run * fast_exp2(m_run - m_f) + l_o * fast_exp2(m_o - m_f);
-        if (kh == 0 && qi < Nq) {
+        if (head_on && kh == 0 && qi < Nq) {
             float* p = part + ((((int64_t)b * Hq + h) * Nq + qi) * KS + ks) * 2;
             p[0] = m_f;
             p[1] = l_f;
         }
+        __syncthreads();
     }
 }
 
@@ -145,54 +195,80 @@ __global__ __launch_bounds__(kAsThreads) void ans_col_reduce(
     const float* __restrict__ c_row, const float* __restrict__ nq_row, float* __restrict__ ans_k,
     float* __restrict__ ans_v, int Hq, int Hkv, int G)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ __attribute__((aligned(16))) half_t s_q[2][kTileHalfs];   // query tiles, double-buffered
+    __shared__ __attribute__((aligned(16))) float s_c[2][32], s_n[2][32];  // their row statistics
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, kh = lane >> 5;
     const int b = blockIdx.y / Hkv, g = blockIdx.y % Hkv;
-    const int64_t k0 = (int64_t)blockIdx.x * 256 + wave * 32;   // first key of this wave
-    if (k0 >= N) return;
+    const int64_t kblk0 = (int64_t)blockIdx.x * 256;
+    const int64_t k0 = kblk0 + wave * 32;                       // first key of this wave
+    const bool wave_on = k0 < N;
     const int64_t key = k0 + n;
     const int64_t krow = key < N ? key : N - 1;
     Tile128 tk;
     load_tile(tk, k + (((int64_t)b * Hkv + g) * N + krow) * kD, kh);
-    // first query row that can see key k0:  N - Nq + i >= k0
-    int64_t i_first = k0 - (N - Nq);
+    // first query tile that can see a key of this block:  N - Nq + i >= kblk0
+    int64_t i_first = kblk0 - (N - Nq);
     if (i_first < 0) i_first = 0;
     i_first &= ~(int64_t)31;
+    const int64_t n_qt = (Nq - i_first + 31) >> 5;               // query tiles per head
+    const int64_t n_steps = n_qt * G;                            // step = (head of the group, query tile)
+    const int srow = tid >> 4, schunk = tid & 15;
+    auto row_of = [&](int64_t step, int64_t& rbase, int64_t& i0) {
+        const int hh = (int)(step / n_qt);
+        i0 = i_first + (step - hh * n_qt) * 32;
+        rbase = ((int64_t)b * Hq + g * G + hh) * Nq;
+    };
+    auto fetch = [&](int64_t step, float& c_o, float& n_o) -> uint4_t {
+        int64_t rbase, i0;
+        row_of(step, rbase, i0);
+        const int64_t qrow = (i0 + srow < Nq) ? i0 + srow : Nq - 1;
+        if (tid < 32) {
+            const bool ok = i0 + tid < Nq;
+            c_o = ok ? c_row[rbase + i0 + tid] : 3.0e38f;       // exp2(-huge) = 0 for rows past the end
+            n_o = ok ? nq_row[rbase + i0 + tid] : 0.f;
+        }
+        return *(const uint4_t*)(q + (rbase + qrow) * kD + 8 * schunk);
+    };
     double sum_v = 0.0, sum_k = 0.0;
-    for (int hh = 0; hh < G; ++hh) {
-        const int h = g * G + hh;
-        const int64_t rbase = ((int64_t)b * Hq + h) * Nq;
-        for (int64_t i0 = i_first; i0 < Nq; i0 += 32) {
-            const int64_t qrow = (i0 + n < Nq) ? i0 + n : Nq - 1;
-            Tile128 tq;
-            load_tile(tq, q + (rbase + qrow) * kD, kh);
-            const float16_t acc = tile_dot(tq, tk);             // rows = queries, cols = keys
+    int buf = 0;
+    {
+        float c_o = 0.f, n_o = 0.f;
+        if (n_steps > 0) {
+            *(uint4_t*)(&s_q[0][srow * kRowPad + 8 * schunk]) = fetch(0, c_o, n_o);
+            if (tid < 32) { s_c[0][tid] = c_o; s_n[0][tid] = n_o; }
+        }
+    }
+    __syncthreads();
+    for (int64_t step = 0; step < n_steps; ++step) {
+        const bool more = step + 1 < n_steps;
+        uint4_t nxt = {0u, 0u, 0u, 0u};
+        float c_o = 0.f, n_o = 0.f;
+        if (more) nxt = fetch(step + 1, c_o, n_o);
+        int64_t rbase, i0;
+        row_of(step, rbase, i0);
+        // tiles whose last query cannot see this wave's first key contribute nothing
+        if (wave_on && (N - Nq + i0 + 31) >= k0) {
+            const float16_t acc = tile_dot_lds_a(s_q[buf], tk, n, kh);   // rows = queries, cols = keys
             float pv = 0.f, pk = 0.f;
             const bool diag = (N - Nq + i0) < (k0 + 31);        // some query of the tile cannot see some key
-            const bool tail = (i0 + 32 > Nq) || (Nq & 3);          // vector loads of the row statistics need alignment
+            const int lim = (int)(key - (N - Nq + i0));          // tile row r sees this lane's key iff r >= lim
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
-                const int64_t ib = i0 + 8 * qd + 4 * kh;         // rows ib .. ib+3 live in acc[4qd .. 4qd+3]
-                float cr[4], nr[4];
-                if (!tail) {
-                    const float4_t c4 = *(const float4_t*)(c_row + rbase + ib);
-                    const float4_t n4 = *(const float4_t*)(nq_row + rbase + ib);
+                const int rl = 8 * qd + 4 * kh;                  // tile rows rl .. rl+3 live in acc[4qd .. 4qd+3]
+                const float4_t c4 = *(const float4_t*)(&s_c[buf][rl]);
+                const float4_t n4 = *(const float4_t*)(&s_n[buf][rl]);
+                float arg[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { cr[e] = c4[e]; nr[e] = n4[e]; }
-                } else {
+                for (int e = 0; e < 4; ++e) arg[e] = fmaf(acc[4 * qd + e], c1, -c4[e]);
+                if (diag) {                                      // causal mask
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const bool ok = ib + e < Nq;
-                        cr[e] = ok ? c_row[rbase + ib + e] : 3.0e38f;   // exp2(-huge) = 0 for rows past the end
-                        nr[e] = ok ? nq_row[rbase + ib + e] : 0.f;
-                    }
+                    for (int e = 0; e < 4; ++e) if (rl + e < lim) arg[e] = -3.0e38f;
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    float arg = fmaf(acc[4 * qd + e], c1, -cr[e]);
-                    if (diag && (N - Nq + ib + e) < key) arg = -3.0e38f;   // causal mask
-                    const float a = fast_exp2(arg);
-                    const float t = a * nr[e];
+                    const float a = fast_exp2(arg[e]);
+                    const float t = a * n4[e];
                     pv += a;
                     pk += fmaf(-a, t, t);
                 }
@@ -200,10 +276,16 @@ __global__ __launch_bounds__(kAsThreads) void ans_col_reduce(
             sum_v += (double)pv;
             sum_k += (double)pk;
         }
+        if (more) {
+            *(uint4_t*)(&s_q[buf ^ 1][srow * kRowPad + 8 * schunk]) = nxt;
+            if (tid < 32) { s_c[buf ^ 1][tid] = c_o; s_n[buf ^ 1][tid] = n_o; }
+        }
+        __syncthreads();
+        buf ^= 1;
     }
     // lanes l and l+32 hold complementary query rows of the same key
     const double ov = __shfl_xor(sum_v, 32, 64), ok = __shfl_xor(sum_k, 32, 64);
-    if (kh == 0 && key < N) {
+    if (wave_on && kh == 0 && key < N) {
         const int64_t o = ((int64_t)b * Hkv + g) * N + key;
         ans_v[o] = (float)(sum_v + ov);
         ans_k[o] = (float)(sum_k + ok);

@@ -307,6 +307,30 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         constexpr int TPM = kDaThreads / M;               // threads per sub-space
         static_assert(TPM * M == kDaThreads && TPM * EPT == 256, "thread to LUT-entry mapping");
         const int lm = tid % M, lc0 = tid / M;            // entries (lm, lc0 + TPM*i), i < EPT
+        // the small loads go first: the first barrier then waits for them only, and the two 64 KB tables
+        // keep streaming in behind it
+        half_t qv16 = (half_t)0.f;
+        if (tid < kNH * kD && (tid >> 7) < nheads) qv16 = qb[tid];
+        // anchored positions of this range: short lists are scanned whole (one load latency), long lists are
+        // cut to the range by a cooperative search first (a few dependent load latencies)
+        constexpr int kScanMax = 8 * kDaThreads;
+        const bool scan_k = p.k_k <= kScanMax, scan_v = p.k_v <= kScanMax;
+        int scan_val[2][8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int j = tid + i * kDaThreads;
+            scan_val[0][i] = -1;
+            scan_val[1][i] = -1;
+            if (scan_k && i * kDaThreads < p.k_k) scan_val[0][i] = (j < p.k_k) ? idx_k[j] : -1;   // uniform skip of empty rounds
+            if (scan_v && i * kDaThreads < p.k_v) scan_val[1][i] = (j < p.k_v) ? idx_v[j] : -1;
+        }
+        if (wave < 4) {
+            const int32_t* arr = (wave < 2) ? idx_k : idx_v;
+            const int n = (wave < 2) ? p.k_k : p.k_v;
+            int r = 0;
+            if (!((wave < 2) ? scan_k : scan_v)) r = wave_lower_bound(arr, n, (int)((wave & 1) ? t1 : t0), lane);
+            if (lane == 0) s_misc[wave] = r;
+        }
         uint4_t cen[EPT][DSUB / 8 > 0 ? DSUB / 8 : 1];
         uint2_t cen4[EPT];
 #pragma unroll
@@ -334,36 +358,40 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             }
         }
         if (tid < kNH * kD) {
-            const int h = tid >> 7;
-            const half_t qv16 = (h < nheads) ? qb[tid] : (half_t)0.f;
             s_qf[tid] = (float)qv16;
             ((half_t*)(smem + L::qh))[tid] = qv16;
         }
         for (int i = tid; i < L::mask_words; i += kDaThreads) s_mask[i] = 0u;
         if (tid == 0) { s_misc[8] = 0; s_misc[9] = 0; }          // next stream tile, next anchor tile of this workgroup
-        // anchored positions of this range: short lists are scanned whole (one load latency), long lists are
-        // cut to the range by a cooperative search first (a few dependent load latencies)
-        constexpr int kScanMax = 8 * kDaThreads;
-        const bool scan_k = p.k_k <= kScanMax, scan_v = p.k_v <= kScanMax;
-        int scan_val[2][8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int j = tid + i * kDaThreads;
-            scan_val[0][i] = (scan_k && j < p.k_k) ? idx_k[j] : -1;
-            scan_val[1][i] = (scan_v && j < p.k_v) ? idx_v[j] : -1;
-        }
-        if (wave < 4) {
-            const int32_t* arr = (wave < 2) ? idx_k : idx_v;
-            const int n = (wave < 2) ? p.k_k : p.k_v;
-            int r = 0;
-            if (!((wave < 2) ? scan_k : scan_v)) r = wave_lower_bound(arr, n, (int)((wave & 1) ? t1 : t0), lane);
-            if (lane == 0) s_misc[wave] = r;
-        }
         __syncthreads();
         DA_STAMP(7);
         if (tid == 0 && ((unsigned int)(done_seen >> 32) != p.tag || (unsigned int)done_seen >= (unsigned int)p.S))
             __hip_atomic_compare_exchange_strong(&p.done[bg], &done_seen, (unsigned long long)p.tag << 32, __ATOMIC_RELAXED,
                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // bitmap of anchored tokens in this range
+        const uint32_t range_len = (uint32_t)(t1 - t0);
+#pragma unroll
+        for (int w2 = 0; w2 < 2; ++w2)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (i * kDaThreads < (w2 ? p.k_v : p.k_k)) {
+                    // unsigned compare: positions below t0 (and the -1 filler) wrap to huge values
+                    const uint32_t rel = (uint32_t)scan_val[w2][i] - (uint32_t)t0;
+                    if (scan_val[w2][i] >= 0 && rel < range_len) atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
+                }
+            }
+        if (!scan_k) {
+            for (int i = s_misc[0] + tid; i < s_misc[1]; i += kDaThreads) {
+                const int rel = idx_k[i] - (int)t0;
+                atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
+            }
+        }
+        if (!scan_v) {
+            for (int i = s_misc[2] + tid; i < s_misc[3]; i += kDaThreads) {
+                const int rel = idx_v[i] - (int)t0;
+                atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
+            }
+        }
         // LUT[m][c][h] = c1 * q_h[m*d : (m+1)*d] . cb_k[g][m][c], stored as fixed point with one scale per head
         // (quantum = max|LUT_h| / 16256): the per-token sum over sub-spaces is then exact integer arithmetic and
         // the table error is uniform instead of growing with the entry's magnitude as it would in fp16.
@@ -409,6 +437,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             if (lane == 0) s_red[wave * 8 + h] = wm;
         }
         __syncthreads();
+        DA_STAMP(3);
         float inv_q[kNH];
         {
             const int hh = lane >> 4, ws = lane & 15;
@@ -435,34 +464,12 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
 #pragma unroll
             for (int rep = 0; rep < 32 / M; ++rep) s_lut[(lc0 + TPM * i) * 32 + lm + M * rep] = ent;
         }
+        DA_STAMP(4);
         // the V table is not needed before the first P.V: its loads had the whole table build to land
         {
             uint4_t* dst = (uint4_t*)(smem + L::cbv);
 #pragma unroll
             for (int i = 0; i < 4096 / kDaThreads; ++i) dst[tid + i * kDaThreads] = vcopy[i];
-        }
-        // bitmap of anchored tokens in this range
-#pragma unroll
-        for (int w2 = 0; w2 < 2; ++w2)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int64_t pos_i = scan_val[w2][i];
-                if (pos_i >= t0 && pos_i < t1) {
-                    const int rel = (int)(pos_i - t0);
-                    atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
-                }
-            }
-        if (!scan_k) {
-            for (int i = s_misc[0] + tid; i < s_misc[1]; i += kDaThreads) {
-                const int rel = idx_k[i] - (int)t0;
-                atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
-            }
-        }
-        if (!scan_v) {
-            for (int i = s_misc[2] + tid; i < s_misc[3]; i += kDaThreads) {
-                const int rel = idx_v[i] - (int)t0;
-                atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
-            }
         }
     }
     __syncthreads();
