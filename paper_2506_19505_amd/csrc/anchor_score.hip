@@ -16,6 +16,8 @@
 // the softmax scale is applied to the fp32 result.
 #include "common.h"
 
+#include <type_traits>
+
 namespace antkv {
 
 namespace {
@@ -211,17 +213,13 @@ __global__ __launch_bounds__(kAsThreads) void ans_col_reduce(
     int64_t i_first = kblk0 - (N - Nq);
     if (i_first < 0) i_first = 0;
     i_first &= ~(int64_t)31;
-    const int64_t n_qt = (Nq - i_first + 31) >> 5;               // query tiles per head
-    const int64_t n_steps = n_qt * G;                            // step = (head of the group, query tile)
+    const int n_qt = (int)((Nq - i_first + 31) >> 5);           // query tiles per head
+    const int n_steps = n_qt * G;                                // step = (head of the group, query tile)
     const int srow = tid >> 4, schunk = tid & 15;
-    auto row_of = [&](int64_t step, int64_t& rbase, int64_t& i0) {
-        const int hh = (int)(step / n_qt);
-        i0 = i_first + (step - hh * n_qt) * 32;
-        rbase = ((int64_t)b * Hq + g * G + hh) * Nq;
-    };
-    auto fetch = [&](int64_t step, float& c_o, float& n_o) -> uint4_t {
-        int64_t rbase, i0;
-        row_of(step, rbase, i0);
+    // (head, tile) of a step are tracked incrementally: no division in the loop
+    auto fetch = [&](int hh, int qt, float& c_o, float& n_o) -> uint4_t {
+        const int64_t i0 = i_first + (int64_t)qt * 32;
+        const int64_t rbase = ((int64_t)b * Hq + g * G + hh) * Nq;
         const int64_t qrow = (i0 + srow < Nq) ? i0 + srow : Nq - 1;
         if (tid < 32) {
             const bool ok = i0 + tid < Nq;
@@ -235,44 +233,46 @@ __global__ __launch_bounds__(kAsThreads) void ans_col_reduce(
     {
         float c_o = 0.f, n_o = 0.f;
         if (n_steps > 0) {
-            *(uint4_t*)(&s_q[0][srow * kRowPad + 8 * schunk]) = fetch(0, c_o, n_o);
+            *(uint4_t*)(&s_q[0][srow * kRowPad + 8 * schunk]) = fetch(0, 0, c_o, n_o);
             if (tid < 32) { s_c[0][tid] = c_o; s_n[0][tid] = n_o; }
         }
     }
     __syncthreads();
-    for (int64_t step = 0; step < n_steps; ++step) {
+    int qt = 0, hh = 0;                                          // current step
+    const int rel0 = (int)(N - Nq + i_first - k0);               // position of tile 0's first query minus this wave's first key
+    for (int step = 0; step < n_steps; ++step) {
         const bool more = step + 1 < n_steps;
+        int qt_n = qt + 1, hh_n = hh;
+        if (qt_n == n_qt) { qt_n = 0; ++hh_n; }
         uint4_t nxt = {0u, 0u, 0u, 0u};
         float c_o = 0.f, n_o = 0.f;
-        if (more) nxt = fetch(step + 1, c_o, n_o);
-        int64_t rbase, i0;
-        row_of(step, rbase, i0);
+        if (more) nxt = fetch(hh_n, qt_n, c_o, n_o);
+        const int rel = rel0 + 32 * qt;                          // (position of the tile's first query) - k0
         // tiles whose last query cannot see this wave's first key contribute nothing
-        if (wave_on && (N - Nq + i0 + 31) >= k0) {
+        if (wave_on && rel + 31 >= 0) {
             const float16_t acc = tile_dot_lds_a(s_q[buf], tk, n, kh);   // rows = queries, cols = keys
             float pv = 0.f, pk = 0.f;
-            const bool diag = (N - Nq + i0) < (k0 + 31);        // some query of the tile cannot see some key
-            const int lim = (int)(key - (N - Nq + i0));          // tile row r sees this lane's key iff r >= lim
+            const int lim = n - rel;                             // tile row r sees this lane's key iff r >= lim
+            auto reduce_tile = [&](auto masked) {
 #pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                const int rl = 8 * qd + 4 * kh;                  // tile rows rl .. rl+3 live in acc[4qd .. 4qd+3]
-                const float4_t c4 = *(const float4_t*)(&s_c[buf][rl]);
-                const float4_t n4 = *(const float4_t*)(&s_n[buf][rl]);
-                float arg[4];
+                for (int qd = 0; qd < 4; ++qd) {
+                    const int rl = 8 * qd + 4 * kh;              // tile rows rl .. rl+3 live in acc[4qd .. 4qd+3]
+                    const float4_t c4 = *(const float4_t*)(&s_c[buf][rl]);
+                    const float4_t n4 = *(const float4_t*)(&s_n[buf][rl]);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) arg[e] = fmaf(acc[4 * qd + e], c1, -c4[e]);
-                if (diag) {                                      // causal mask
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) if (rl + e < lim) arg[e] = -3.0e38f;
+                    for (int e = 0; e < 4; ++e) {
+                        float arg = fmaf(acc[4 * qd + e], c1, -c4[e]);
+                        if (decltype(masked)::value && rl + e < lim) arg = -3.0e38f;   // causal mask
+                        const float a = fast_exp2(arg);
+                        const float t = a * n4[e];
+                        pv += a;
+                        pk += fmaf(-a, t, t);
+                    }
                 }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float a = fast_exp2(arg[e]);
-                    const float t = a * n4[e];
-                    pv += a;
-                    pk += fmaf(-a, t, t);
-                }
-            }
+            };
+            // only tiles on the diagonal (some query cannot see some key) pay for the mask; the branch is uniform
+            if (__builtin_expect(rel < 31, 0)) reduce_tile(std::true_type{});
+            else reduce_tile(std::false_type{});
             sum_v += (double)pv;
             sum_k += (double)pk;
         }
@@ -282,6 +282,7 @@ __global__ __launch_bounds__(kAsThreads) void ans_col_reduce(
         }
         __syncthreads();
         buf ^= 1;
+        qt = qt_n; hh = hh_n;
     }
     // lanes l and l+32 hold complementary query rows of the same key
     const double ov = __shfl_xor(sum_v, 32, 64), ok = __shfl_xor(sum_k, 32, 64);
