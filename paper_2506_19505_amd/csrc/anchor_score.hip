@@ -117,32 +117,39 @@ __global__ __launch_bounds__(kAsThreads) void ans_row_stats(
             if (more) nxt = fetch(kt + 32);
             if (head_on && kt < k_hi) {
                 const float16_t acc = tile_dot_lds_a(s_k[buf], tq, n, kh);   // rows = keys, cols = queries
-                float s2[16];
-                float mx = kNegBig;
+                // Exponents are taken against this lane's reference m_run, which only moves when a tile brings
+                // a score more than 64 (log2 units) above it, or when the lane has seen nothing yet: the common
+                // tile costs one fma, one exp2, one add and one max per element.
+                const bool init = m_run > kNegBig;
+                const float base = init ? m_run : 0.f;
+                float arg[16];
+                float mx = kNegBig, sum = 0.f;
                 if (kt + 31 <= N - Nq + q0 && kt + 31 < k_hi) {    // every key of the tile is visible to every query
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        s2[r] = acc[r] * c1;
-                        mx = fmaxf(mx, s2[r]);
-                    }
+                    for (int r = 0; r < 16; ++r) arg[r] = fmaf(acc[r], c1, -base);
                 } else {
                     const int lim_q = (int)(qpos - kt), lim_k = (int)(k_hi - kt);   // visible: offset <= lim_q, < lim_k
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int off = 8 * (r >> 2) + 4 * kh + (r & 3);
                         const bool vis = (off <= lim_q) && (off < lim_k);
-                        s2[r] = vis ? acc[r] * c1 : kNegBig;
-                        mx = fmaxf(mx, s2[r]);
+                        arg[r] = vis ? fmaf(acc[r], c1, -base) : kNegBig;
                     }
                 }
-                const float m_new = fmaxf(m_run, mx);
-                float sum = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) sum += fast_exp2(s2[r] - m_new);
-                // all-masked so far: m_new stays at kNegBig and exp2(0) terms must not count
-                if (m_new <= kNegBig) sum = 0.f;
-                l_run = l_run * fast_exp2(m_run - m_new) + sum;
-                m_run = m_new;
+                for (int r = 0; r < 16; ++r) {
+                    mx = fmaxf(mx, arg[r]);
+                    sum += fast_exp2(arg[r]);
+                }
+                if (init && mx <= 64.f) {
+                    l_run += sum;
+                } else if (mx > 0.5f * kNegBig) {                  // the tile has a visible element: move the reference
+                    float sum2 = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sum2 += fast_exp2(arg[r] - mx);
+                    l_run = (init ? l_run * fast_exp2(-mx) : 0.f) + sum2;
+                    m_run = base + mx;
+                }
             }
             if (more) *(uint4_t*)(&s_k[buf ^ 1][srow * kRowPad + 8 * schunk]) = nxt;
             __syncthreads();
