@@ -299,7 +299,6 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     uint32_t* s_mask = (uint32_t*)(smem + L::mask);
 
     // ================================================================================== prologue
-    float lut_q[kNH];
     {
         // all global loads of the prologue are issued before anything waits on them.
         // Threads are grouped by sub-space (TPM threads each) so that a thread reads its q sub-vectors once.
@@ -313,11 +312,12 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         if (tid < kNH * kD && (tid >> 7) < nheads) qv16 = qb[tid];
         // anchored positions of this range: short lists are scanned whole (one load latency), long lists are
         // cut to the range by a cooperative search first (a few dependent load latencies)
-        constexpr int kScanMax = 8 * kDaThreads;
+        constexpr int kScanRounds = 4;
+        constexpr int kScanMax = kScanRounds * kDaThreads;
         const bool scan_k = p.k_k <= kScanMax, scan_v = p.k_v <= kScanMax;
-        int scan_val[2][8];
+        int scan_val[2][kScanRounds];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < kScanRounds; ++i) {
             const int j = tid + i * kDaThreads;
             scan_val[0][i] = -1;
             scan_val[1][i] = -1;
@@ -373,7 +373,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
 #pragma unroll
         for (int w2 = 0; w2 < 2; ++w2)
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < kScanRounds; ++i) {
                 if (i * kDaThreads < (w2 ? p.k_v : p.k_k)) {
                     // unsigned compare: positions below t0 (and the -1 filler) wrap to huge values
                     const uint32_t rel = (uint32_t)scan_val[w2][i] - (uint32_t)t0;
@@ -445,7 +445,8 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
 #pragma unroll
             for (int h = 0; h < kNH; ++h) {
                 const float r = lane_bcast(r_r, 16 * h);
-                lut_q[h] = (r > 0.f) ? r / kLutMax : 1.0f;
+                // the table quantum is parked in LDS until the stream starts (keeps registers free for the anchors)
+                if (tid == 0) ((float*)s_misc)[12 + h] = (r > 0.f) ? r / kLutMax : 1.0f;
                 inv_q[h] = (r > 0.f) ? kLutMax / r : 0.f;
             }
         }
@@ -757,6 +758,9 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         uint32_t* s_cws = s_p32 + 4 * kPStride32;                  // stream code words
         const uint32_t* s_cws_r = s_cws + ((DSUB == 8) ? (tj >> 1) : (DSUB == 4 ? tj : 0)) * CWROW + (TOKS / 4) * kgrp;
         const uint32_t* s_pa_r = s_p32 + (lane & 3) * kPStride32 + 4 * kgrp;
+        float lut_q[kNH];                                          // table quantum per head
+#pragma unroll
+        for (int h = 0; h < kNH; ++h) lut_q[h] = ((const float*)s_misc)[12 + h];
         float neg_m[kNH];                                          // -m_ref, the addend of the exponent
 #pragma unroll
         for (int h = 0; h < kNH; ++h) neg_m[h] = -m_ref[h];

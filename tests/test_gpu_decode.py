@@ -185,3 +185,67 @@ def test_extreme_context_reselection(oracle):
         wi, margin = oracle.topk(score, w.k, want_margin=True)
         soft += check_index_sets(got.cpu().numpy(), wi, margin, "cfg4 re-selection")
     print(f"cfg4 re-selection near-tie disagreements: {soft}")
+
+
+def test_decode_workspace_reuse_across_shapes(oracle):
+    """One workspace serves calls of different context lengths in turn (the number of workgroups per (b, g), and with
+    it the arrival count the in-kernel merge waits for, changes from call to call)."""
+    B, Hq, Hkv, d = 1, 8, 2, 8
+    geom = antkv.Geometry(B, Hq, Hkv, d)
+    scale = 1 / np.sqrt(128)
+    N_big = 9000
+    c = _cache_from_kv(oracle, 77, B, Hq, Hkv, N_big, d, 40, 40, anchors="random")
+    t = {n: dev(a) for n, a in c.items()}
+    ws = antkv.DecodeWorkspace(geom, N_big, 40, 40, 0, t["q"].device)
+    ws.buf.fill_(0x5A)                                    # arbitrary content: nothing may rely on zeros
+    for rep, n in enumerate((9000, 700, 9000, 130, 4200, 4200)):
+        keep_k, keep_v = c["ik"] < n, c["iv"] < n          # anchors inside the shorter context (lists are ascending)
+        kk = int(keep_k.sum(-1).min()); kv = int(keep_v.sum(-1).min())
+        ik, iv = c["ik"][..., :kk], c["iv"][..., :kv]
+        rk, rv = c["rk"][:, :, :kk], c["rv"][:, :, :kv]
+        got = antkv.decode_attn(geom, t["q"], scale, t["ck"], t["cv"], t["cbk"], t["cbv"],
+                                dev(ik) if kk else None, dev(rk) if kk else None, dev(iv) if kv else None,
+                                dev(rv) if kv else None, N=n, workspace=ws)
+        torch.cuda.synchronize()
+        want = oracle.decode_attn(c["q"], c["ck"][:, :, :n], c["cv"][:, :, :n], c["cbk"], c["cbv"], ik, rk, iv, rv, scale)
+        _check_out(got, want, f"reused workspace, call {rep}, N={n}")
+
+
+def test_decode_graph_replay(oracle):
+    """The decode step captured into a HIP graph and replayed: every replay must equal the eager result for the inputs
+    of that moment (the launch tag of the arrival words is frozen in the captured launch)."""
+    B, Hq, Hkv, d, N = 2, 8, 2, 8, 5000
+    geom = antkv.Geometry(B, Hq, Hkv, d)
+    scale = 1 / np.sqrt(128)
+    c = _cache_from_kv(oracle, 91, B, Hq, Hkv, N, d, 50, 50, anchors="random")
+    t = {n: dev(a) for n, a in c.items()}
+    ws = antkv.DecodeWorkspace(geom, N, 50, 50, 0, t["q"].device)
+    out = torch.empty((B, Hq, 128), dtype=torch.float16, device=t["q"].device)
+    q_live = t["q"].clone()
+
+    def step():
+        antkv.decode_attn(geom, q_live, scale, t["ck"], t["cv"], t["cbk"], t["cbv"], t["ik"], t["rk"], t["iv"], t["rv"],
+                          out=out, workspace=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                            # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(4):
+        q_np = make_decode_query(500 + rep, B, Hq, 128)
+        q_live.copy_(dev(q_np))
+        graph.replay()
+        torch.cuda.synchronize()
+        got_graph = out.clone()
+        step()                                            # eager launch between the replays, same workspace
+        torch.cuda.synchronize()
+        # (tiles are handed to waves dynamically, so two runs may differ in the last bits of the fp32 sums)
+        diff = rel_l2_rows(got_graph.cpu().numpy(), out.cpu().numpy().astype(np.float64))
+        assert diff.max() <= 1e-3, f"replay {rep} differs from the eager result: {diff.max():.2e}"
+        want = oracle.decode_attn(q_np, c["ck"], c["cv"], c["cbk"], c["cbv"], c["ik"], c["rk"], c["iv"], c["rv"], scale)
+        _check_out(got_graph, want, f"graph replay {rep}")
