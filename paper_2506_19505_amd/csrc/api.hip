@@ -31,7 +31,7 @@ SelPlan sel_plan(const Geom& g, int64_t N, int64_t Nq, int64_t k)
     SelPlan p;
     p.off_score = 0;
     p.off_topk = align_up(anchor_score_workspace_bytes(g, N, Nq));
-    p.total = p.off_topk + align_up(topk_workspace_bytes((int64_t)g.B * g.Hkv, N, k));
+    p.total = p.off_topk + align_up(topk_workspace_bytes(2 * (int64_t)g.B * g.Hkv, N, k));   // K and V rows in one go
     return p;
 }
 
@@ -44,7 +44,7 @@ DecPlan dec_plan(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, int64_t k_r
     DecPlan p;
     p.off_dec = 0;
     p.off_topk = align_up(decode_workspace_bytes(g, N, k_k, k_v, want_ans));
-    p.total = p.off_topk + (k_resel > 0 ? align_up(topk_workspace_bytes((int64_t)g.B * g.Hkv, N, k_resel)) : 0);
+    p.total = p.off_topk + (k_resel > 0 ? align_up(topk_workspace_bytes(2 * (int64_t)g.B * g.Hkv, N, k_resel)) : 0);
     return p;
 }
 
@@ -133,12 +133,11 @@ int antkv_anchor_select(const antkv_geom* geom, const void* q, const void* k_fp1
                                        w + sp.off_score, st);
     if (e != hipSuccess) return ANTKV_ELAUNCH;
     const int64_t rows = (int64_t)g.B * g.Hkv;
-    if (idx_k && k > 0) {
-        e = launch_topk(sk, rows, N, k, idx_k, w + sp.off_topk, st);
+    if (idx_k && idx_v && k > 0) {
+        e = launch_topk2(sk, idx_k, sv, idx_v, rows, N, k, w + sp.off_topk, st);
         if (e != hipSuccess) return ANTKV_ELAUNCH;
-    }
-    if (idx_v && k > 0) {
-        e = launch_topk(sv, rows, N, k, idx_v, w + sp.off_topk, st);
+    } else if ((idx_k || idx_v) && k > 0) {
+        e = launch_topk(idx_k ? sk : sv, rows, N, k, idx_k ? idx_k : idx_v, w + sp.off_topk, st);
         if (e != hipSuccess) return ANTKV_ELAUNCH;
     }
     return ANTKV_OK;
@@ -207,12 +206,12 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
     if (N > 0 && k_resel > 0) {
         char* w = (char*)workspace;
         const int64_t rows = (int64_t)g.B * g.Hkv;
-        if (resel_idx_k) {
-            e = launch_topk(ans_k, rows, N, k_resel, resel_idx_k, w + dp.off_topk, st);
+        if (resel_idx_k && resel_idx_v) {
+            e = launch_topk2(ans_k, resel_idx_k, ans_v, resel_idx_v, rows, N, k_resel, w + dp.off_topk, st);
             if (e != hipSuccess) return ANTKV_ELAUNCH;
-        }
-        if (resel_idx_v) {
-            e = launch_topk(ans_v, rows, N, k_resel, resel_idx_v, w + dp.off_topk, st);
+        } else if (resel_idx_k || resel_idx_v) {
+            e = launch_topk(resel_idx_k ? ans_k : ans_v, rows, N, k_resel, resel_idx_k ? resel_idx_k : resel_idx_v,
+                            w + dp.off_topk, st);
             if (e != hipSuccess) return ANTKV_ELAUNCH;
         }
     }

@@ -70,6 +70,8 @@ hipError_t launch_encode(const Geom& g, const half_t* x, int64_t xs_b, int64_t x
 size_t topk_workspace_bytes(int64_t n_rows, int64_t N, int64_t k);
 hipError_t launch_topk(const float* scores, int64_t n_rows, int64_t N, int64_t k, int32_t* idx,
                        void* ws, hipStream_t st);
+hipError_t launch_topk2(const float* scores, int32_t* idx, const float* scores_b, int32_t* idx_b, int64_t n_rows,
+                        int64_t N, int64_t k, void* ws, hipStream_t st);
 
 hipError_t launch_gather_rows(const Geom& g, const half_t* x, int64_t N, const int32_t* idx,
                               int64_t k, half_t* rows, hipStream_t st);

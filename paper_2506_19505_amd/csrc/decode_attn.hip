@@ -983,15 +983,29 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
     }
     __syncthreads();
     {
+        // fp32 table: entry e = (m, code) holds the four heads' c1 * q_h[m] . cb_k[g][m][code]
         const half_t* cbk = p.cb_k + (size_t)g * 32768;
         for (int e = tid; e < M * 256; e += kDaThreads) {
             const int m = e >> 8;
+            float cf[DSUB];
+            if constexpr (DSUB == 4) {
+                const half4_t v = *(const half4_t*)(cbk + e * 4);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) cf[t] = (float)v[t];
+            } else {
+#pragma unroll
+                for (int u = 0; u < DSUB / 8; ++u) {
+                    const half8_t v = *(const half8_t*)(cbk + e * DSUB + 8 * u);
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) cf[8 * u + t] = (float)v[t];
+                }
+            }
             float4_t o;
 #pragma unroll
             for (int h = 0; h < kNH; ++h) {
                 float s = 0.f;
 #pragma unroll
-                for (int t = 0; t < DSUB; ++t) s = fmaf(s_qf[h * kD + m * DSUB + t], (float)cbk[e * DSUB + t], s);
+                for (int t = 0; t < DSUB; ++t) s = fmaf(s_qf[h * kD + m * DSUB + t], cf[t], s);
                 o[h] = s * p.c1;
             }
             s_lut[e] = o;
@@ -1001,13 +1015,17 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
         const int rel = idx_k[i] - (int)t0;
         atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
     }
+    // ||q_h||_2: one wave per head
+    if (wave < kNH) {
+        const float a = s_qf[wave * kD + lane], c = s_qf[wave * kD + 64 + lane];
+        const float ss = wave_sum(fmaf(a, a, c * c));
+        if (lane == 0) s_red[kDaWaves * 8 - 4 + wave] = sqrtf(ss);       // parked in the last wave's slots until the barrier
+    }
+    __syncthreads();
     float qn[kNH], lse[kNH];
 #pragma unroll
     for (int h = 0; h < kNH; ++h) {
-        float s = 0.f;
-#pragma unroll 1
-        for (int t = 0; t < kD; ++t) s = fmaf(s_qf[h * kD + t], s_qf[h * kD + t], s);
-        qn[h] = sqrtf(s);
+        qn[h] = s_red[kDaWaves * 8 - 4 + h];
         lse[h] = (PASS == 1 && h < p.G) ? p.lse2[(int64_t)b * p.Hq + h0 + h] : 0.f;
     }
     __syncthreads();
@@ -1017,50 +1035,19 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
 #pragma unroll
     for (int h = 0; h < kNH; ++h) { m_run[h] = kNegBig; l_run[h] = 0.f; }
 
-    for (int64_t tok = t0 + tid; tok < t1; tok += kDaThreads) {
-        uint32_t kw[CW];
-        if (CW == 2) { const uint2_t a = *(const uint2_t*)(ck + tok * M); kw[0] = a[0]; kw[1] = a[1]; }
-        else {
-#pragma unroll
-            for (int i = 0; i < CW / 4; ++i) {
-                const uint4_t a = *(const uint4_t*)(ck + tok * M + 16 * i);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) kw[4 * i + e] = a[e];
-            }
-        }
-        float s[kNH] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int m = 0; m < M; ++m) {
-            const uint32_t code = (kw[m >> 2] >> (8 * (m & 3))) & 255u;
-            const float4_t e = s_lut[m * 256 + code];
-#pragma unroll
-            for (int h = 0; h < kNH; ++h) s[h] += e[h];
-        }
-        // K-anchored token: its score comes from the FP16 row (slot found in the slice of the list
-        // that lies in this range)
-        const int rel = (int)(tok - t0);
-        if ((s_mask[rel >> 5] >> (rel & 31)) & 1u) {
-            const int slot = find_sorted(idx_k + lo_k, hi_k - lo_k, (int)tok);
-            const half_t* row = p.rows_k + ((int64_t)bg * p.k_k + lo_k + slot) * kD;
-#pragma unroll
-            for (int h = 0; h < kNH; ++h) s[h] = 0.f;
-#pragma unroll 1
-            for (int t = 0; t < kD; t += 8) {
-                const half8_t v = *(const half8_t*)(row + t);
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-#pragma unroll
-                    for (int h = 0; h < kNH; ++h) s[h] = fmaf(s_qf[h * kD + t + e], (float)v[e], s[h]);
-            }
-#pragma unroll
-            for (int h = 0; h < kNH; ++h) s[h] *= p.c1;
-        }
+    // PASS 0 keeps, per lane and head, a sum of exp2(score - reference); the reference only moves when a score
+    // exceeds it by more than 64 (or on the lane's first token), so the common token costs one exp2 per head.
+    auto consume = [&](const float (&s)[kNH], int64_t tok) {
         if (PASS == 0) {
 #pragma unroll
             for (int h = 0; h < kNH; ++h) {
-                const float m_new = fmaxf(m_run[h], s[h]);
-                l_run[h] = l_run[h] * fast_exp2(m_run[h] - m_new) + fast_exp2(s[h] - m_new);
-                m_run[h] = m_new;
+                const float x = s[h] - m_run[h];
+                if (x > 64.f) {                                  // first token (reference = kNegBig) or a big jump
+                    l_run[h] = l_run[h] * fast_exp2(-x) + 1.f;
+                    m_run[h] = s[h];
+                } else {
+                    l_run[h] += fast_exp2(x);
+                }
             }
         } else {
             float av = 0.f, ak = 0.f;
@@ -1075,6 +1062,64 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
             }
             p.ans_v[(int64_t)bg * p.N + tok] = av;
             p.ans_k[(int64_t)bg * p.N + tok] = ak;
+        }
+    };
+
+    // ---- code stream: one token per lane, code loads one round ahead; tokens with an FP16 K row are left to
+    // the loop below
+    auto load_kw = [&](int64_t tok, uint32_t (&kw)[CW]) {
+        if (CW == 2) { const uint2_t a = *(const uint2_t*)(ck + tok * M); kw[0] = a[0]; kw[1] = a[1]; }
+        else {
+#pragma unroll
+            for (int i = 0; i < CW / 4; ++i) {
+                const uint4_t a = *(const uint4_t*)(ck + tok * M + 16 * i);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) kw[4 * i + e] = a[e];
+            }
+        }
+    };
+    uint32_t kw_next[CW];
+#pragma unroll
+    for (int i = 0; i < CW; ++i) kw_next[i] = 0u;
+    if (t0 + tid < t1) load_kw(t0 + tid, kw_next);
+    for (int64_t tok = t0 + tid; tok < t1; tok += kDaThreads) {
+        uint32_t kw[CW];
+#pragma unroll
+        for (int i = 0; i < CW; ++i) kw[i] = kw_next[i];
+        if (tok + kDaThreads < t1) load_kw(tok + kDaThreads, kw_next);
+        float s[kNH] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            const uint32_t code = (kw[m >> 2] >> (8 * (m & 3))) & 255u;
+            const float4_t e = s_lut[m * 256 + code];
+#pragma unroll
+            for (int h = 0; h < kNH; ++h) s[h] += e[h];
+        }
+        const int rel = (int)(tok - t0);
+        if (!((s_mask[rel >> 5] >> (rel & 31)) & 1u)) consume(s, tok);
+    }
+    // ---- K-anchored tokens of the range: the score comes from the FP16 row.  16 lanes per token, 8 channels each.
+    {
+        const int sub = lane >> 4, l16 = lane & 15;
+        float qv[kNH][8];
+#pragma unroll
+        for (int h = 0; h < kNH; ++h)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qv[h][e] = s_qf[h * kD + 8 * l16 + e];
+        for (int i0 = lo_k + 4 * wave; i0 < hi_k; i0 += 4 * kDaWaves) {
+            const int i = i0 + sub;
+            const bool on = i < hi_k;
+            const int64_t tok = on ? idx_k[i] : t0;
+            const half8_t v = *(const half8_t*)(p.rows_k + ((int64_t)bg * p.k_k + (on ? i : lo_k)) * kD + 8 * l16);
+            float s[kNH];
+#pragma unroll
+            for (int h = 0; h < kNH; ++h) {
+                float d = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) d = fmaf(qv[h][e], (float)v[e], d);
+                s[h] = row16_sum(d) * p.c1;
+            }
+            if (on && l16 == 0) consume(s, tok);
         }
     }
     if (PASS == 0) {

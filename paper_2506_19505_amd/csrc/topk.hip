@@ -60,7 +60,8 @@ __global__ __launch_bounds__(256) void zero_u32(uint32_t* p, int64_t n)
 }
 
 template <int PASS>
-__global__ __launch_bounds__(kTopkThreads) void topk_hist(const float* __restrict__ scores, int64_t N,
+__global__ __launch_bounds__(kTopkThreads) void topk_hist(const float* __restrict__ scores,
+                                                          const float* __restrict__ scores_b, int rows_a, int64_t N,
                                                           uint32_t k, uint32_t* __restrict__ ws_hist)
 {
     __shared__ uint32_t lh[kBins];
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist(const float* __restric
     __syncthreads();
     const int64_t lo = (int64_t)blockIdx.x * kSlice;
     const int64_t hi = (lo + kSlice < N) ? lo + kSlice : N;
-    const float* src = scores + row * N;
+    const float* src = (row < rows_a) ? scores + row * N : scores_b + (row - rows_a) * N;
     for (int64_t i = lo + threadIdx.x; i < hi; i += kTopkThreads) {
         const uint32_t key = float_key(src[i]);
         if (PASS == 0) atomicAdd(&lh[key >> 21], 1u);
@@ -105,7 +106,8 @@ __device__ void resolve_tau(const uint32_t* hist, uint32_t k, uint32_t& tau, uin
 }
 
 // per slice: how many keys are > tau and == tau
-__global__ __launch_bounds__(kTopkThreads) void topk_count(const float* __restrict__ scores, int64_t N,
+__global__ __launch_bounds__(kTopkThreads) void topk_count(const float* __restrict__ scores,
+                                                           const float* __restrict__ scores_b, int rows_a, int64_t N,
                                                            uint32_t k, const uint32_t* __restrict__ ws_hist,
                                                            uint32_t* __restrict__ counts, int n_slices)
 {
@@ -116,7 +118,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_count(const float* __restri
     resolve_tau(ws_hist + row * 3 * kBins, k, tau, need_eq, sh);
     const int64_t lo = (int64_t)blockIdx.x * kSlice;
     const int64_t hi = (lo + kSlice < N) ? lo + kSlice : N;
-    const float* src = scores + row * N;
+    const float* src = (row < rows_a) ? scores + row * N : scores_b + (row - rows_a) * N;
     uint32_t gt = 0, eq = 0;
     for (int64_t i = lo + threadIdx.x; i < hi; i += kTopkThreads) {
         const uint32_t key = float_key(src[i]);
@@ -134,10 +136,11 @@ __global__ __launch_bounds__(kTopkThreads) void topk_count(const float* __restri
     }
 }
 
-__global__ __launch_bounds__(kTopkThreads) void topk_emit(const float* __restrict__ scores, int64_t N,
+__global__ __launch_bounds__(kTopkThreads) void topk_emit(const float* __restrict__ scores,
+                                                          const float* __restrict__ scores_b, int rows_a, int64_t N,
                                                           uint32_t k, const uint32_t* __restrict__ ws_hist,
                                                           const uint32_t* __restrict__ counts, int n_slices,
-                                                          int32_t* __restrict__ idx)
+                                                          int32_t* __restrict__ idx, int32_t* __restrict__ idx_b)
 {
     __shared__ uint32_t sh[8];
     __shared__ uint32_t red[2][4];
@@ -162,12 +165,28 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit(const float* __restric
     const int64_t lo = (int64_t)blockIdx.x * kSlice + (int64_t)tid * (kSlice / kTopkThreads);
     int64_t hi = lo + kSlice / kTopkThreads;
     if (hi > N) hi = N;
-    const float* src = scores + row * N;
+    const float* src = (row < rows_a) ? scores + row * N : scores_b + (row - rows_a) * N;
+    // the thread's 32 scores are read once (16-byte loads when the row allows it) and kept as keys
+    constexpr int kPer = kSlice / kTopkThreads;
+    static_assert(kPer == 32, "a thread owns 32 consecutive scores");
+    uint32_t key[kPer];
+    const int n_own = (hi > lo) ? (int)(hi - lo) : 0;
+    if (n_own == kPer && (((uintptr_t)(src + lo)) & 15) == 0) {
+#pragma unroll
+        for (int j = 0; j < kPer / 4; ++j) {
+            const float4_t v = *(const float4_t*)(src + lo + 4 * j);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) key[4 * j + e] = float_key(v[e]);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) key[j] = (j < n_own) ? float_key(src[lo + j]) : 0u;
+    }
     uint32_t gt = 0, eq = 0;
-    for (int64_t i = lo; i < hi; ++i) {
-        const uint32_t key = float_key(src[i]);
-        gt += (key > tau);
-        eq += (key == tau);
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        gt += (j < n_own) && (key[j] > tau);
+        eq += (j < n_own) && (key[j] == tau);
     }
     uint32_t igt = gt, ieq = eq;
 #pragma unroll
@@ -179,15 +198,18 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit(const float* __restric
     __syncthreads();
     uint32_t run_gt = base_gt + igt - gt, run_eq = base_eq + ieq - eq;
     for (int w = 0; w < wave; ++w) { run_gt += red[0][w]; run_eq += red[1][w]; }
-    int32_t* out = idx + row * (int64_t)k;
-    for (int64_t i = lo; i < hi; ++i) {
-        const uint32_t key = float_key(src[i]);
-        if (key > tau) {
-            out[run_gt + (run_eq < need_eq ? run_eq : need_eq)] = (int32_t)i;
-            ++run_gt;
-        } else if (key == tau) {
-            if (run_eq < need_eq) out[run_gt + run_eq] = (int32_t)i;
-            ++run_eq;
+    int32_t* out = (row < rows_a) ? idx + row * (int64_t)k : idx_b + (row - rows_a) * (int64_t)k;
+    if (gt == 0 && (eq == 0 || run_eq >= need_eq)) return;       // nothing of this thread is selected
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        if (j < n_own) {
+            if (key[j] > tau) {
+                out[run_gt + (run_eq < need_eq ? run_eq : need_eq)] = (int32_t)(lo + j);
+                ++run_gt;
+            } else if (key[j] == tau) {
+                if (run_eq < need_eq) out[run_gt + run_eq] = (int32_t)(lo + j);
+                ++run_eq;
+            }
         }
     }
 }
@@ -215,22 +237,33 @@ size_t topk_workspace_bytes(int64_t n_rows, int64_t N, int64_t k)
     return align_up((size_t)n_rows * 3 * kBins * 4) + align_up((size_t)n_rows * (n_slices > 0 ? n_slices : 1) * 2 * 4);
 }
 
+// Two score arrays of n_rows rows each can be selected in one go (scores_b / idx_b may be NULL): the launches then
+// cover 2 n_rows rows, the first n_rows from `scores` into `idx`, the rest from `scores_b` into `idx_b`.
+hipError_t launch_topk2(const float* scores, int32_t* idx, const float* scores_b, int32_t* idx_b, int64_t n_rows,
+                        int64_t N, int64_t k, void* ws, hipStream_t st)
+{
+    if (k == 0 || n_rows == 0) return hipSuccess;
+    const int64_t rows = scores_b ? 2 * n_rows : n_rows;
+    const int n_slices = (int)((N + kSlice - 1) / kSlice);
+    uint32_t* hist = (uint32_t*)ws;
+    uint32_t* counts = (uint32_t*)((char*)ws + align_up((size_t)rows * 3 * kBins * 4));
+    const int64_t nh = rows * 3 * kBins;
+    const int ra = (int)n_rows;
+    hipLaunchKernelGGL(zero_u32, dim3((unsigned)((nh + 255) / 256)), dim3(256), 0, st, hist, nh);
+    dim3 grid(n_slices, (unsigned)rows);
+    hipLaunchKernelGGL(topk_hist<0>, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist);
+    hipLaunchKernelGGL(topk_hist<1>, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist);
+    hipLaunchKernelGGL(topk_hist<2>, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist);
+    hipLaunchKernelGGL(topk_count, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist, counts, n_slices);
+    hipLaunchKernelGGL(topk_emit, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist, counts, n_slices,
+                       idx, idx_b);
+    return hipGetLastError();
+}
+
 hipError_t launch_topk(const float* scores, int64_t n_rows, int64_t N, int64_t k, int32_t* idx, void* ws,
                        hipStream_t st)
 {
-    if (k == 0 || n_rows == 0) return hipSuccess;
-    const int n_slices = (int)((N + kSlice - 1) / kSlice);
-    uint32_t* hist = (uint32_t*)ws;
-    uint32_t* counts = (uint32_t*)((char*)ws + align_up((size_t)n_rows * 3 * kBins * 4));
-    const int64_t nh = n_rows * 3 * kBins;
-    hipLaunchKernelGGL(zero_u32, dim3((unsigned)((nh + 255) / 256)), dim3(256), 0, st, hist, nh);
-    dim3 grid(n_slices, (unsigned)n_rows);
-    hipLaunchKernelGGL(topk_hist<0>, grid, dim3(kTopkThreads), 0, st, scores, N, (uint32_t)k, hist);
-    hipLaunchKernelGGL(topk_hist<1>, grid, dim3(kTopkThreads), 0, st, scores, N, (uint32_t)k, hist);
-    hipLaunchKernelGGL(topk_hist<2>, grid, dim3(kTopkThreads), 0, st, scores, N, (uint32_t)k, hist);
-    hipLaunchKernelGGL(topk_count, grid, dim3(kTopkThreads), 0, st, scores, N, (uint32_t)k, hist, counts, n_slices);
-    hipLaunchKernelGGL(topk_emit, grid, dim3(kTopkThreads), 0, st, scores, N, (uint32_t)k, hist, counts, n_slices, idx);
-    return hipGetLastError();
+    return launch_topk2(scores, idx, nullptr, nullptr, n_rows, N, k, ws, st);
 }
 
 hipError_t launch_gather_rows(const Geom& g, const half_t* x, int64_t N, const int32_t* idx, int64_t k,
