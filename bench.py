@@ -95,16 +95,26 @@ def main() -> int:
     torch.cuda.synchronize()
     del kd, vd
     torch.cuda.empty_cache()
-    if args.calibrate:
+    copy_gbs = None
+    if not args.no_extras or args.calibrate:
         # 8 heads x 131072 rows x 256 B read and written once each, plus 4 B of index per row
         cal_geom = antkv.Geometry(1, w.Hq, w.Hkv, w.d_sub)
         cal_src = torch.zeros((1, w.Hkv, 131072, w.D), dtype=torch.float16, device=devc)
         cal_idx = torch.arange(131072, dtype=torch.int32, device=devc).repeat(1, w.Hkv, 1).contiguous()
-        antkv.gather_rows(cal_geom, cal_src, cal_idx)
+        cal_dst = antkv.gather_rows(cal_geom, cal_src, cal_idx)
         torch.cuda.synchronize()
         log(f"calibration copy: gather_rows_kernel read {cal_src.numel() * 2 + cal_idx.numel() * 4} B, "
             f"wrote {cal_src.numel() * 2} B")
-        del cal_src, cal_idx
+        # the same copy, timed: the box's plain streaming rate, for comparison with the decode kernel's
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            antkv.gather_rows(cal_geom, cal_src, cal_idx, out=cal_dst)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs = (cal_src.numel() * 4 + cal_idx.numel() * 4) / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9
+        log(f"row copy (read + write) {copy_gbs:.0f} GB/s")
+        del cal_src, cal_idx, cal_dst
     q = dev(make_decode_query(w.seed, w.B, w.Hq, w.D))
     out = torch.empty((w.B, w.Hq, w.D), dtype=torch.float16, device=devc)
     caches = [(codes_k, codes_v, idx_k, rows_k, idx_v, rows_v)]
@@ -164,6 +174,7 @@ def main() -> int:
                                 "f32 MFMA accumulators; f32 online softmax; f16 output",
                   "decode_steps_per_s": w.B / (ms_step * 1e-3), "ms_per_step_warm": ms_warm,
                   "tokens_per_s_warm": w.B * w.N / (ms_warm * 1e-3),
+                  "measured_copy_GBs": copy_gbs,
                   "step_GBs": abytes / (ms_step * 1e-3) / 1e9, "step_frac_of_peak": abytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
     log(f"decode: {ms_step * 1e3:.1f} us/step rotating, {ms_warm * 1e3:.1f} us warm, kernel {ms_kernel * 1e3:.1f} us "
@@ -199,6 +210,31 @@ def main() -> int:
         })
         log(f"encode {result['extra']['encode_Mvec_per_s']:.0f} Mvec/s ({ms_enc * 1e3:.0f} us); anchor select {ms_sel:.2f} ms")
         del pkd, pvd, pqd
+        torch.cuda.empty_cache()
+
+        # ------------------------------------------------------------ decode step + anchor re-selection (cfg4)
+        r = CONFIGS["cfg4"]
+        rg = antkv.Geometry(r.B, r.Hq, r.Hkv, r.d_sub)
+        _, rks, rvs = make_qkv(r.seed, 1, r.Hq, r.Hkv, 2048, 1, r.D)
+        rcbk, rcbv = dev(make_codebooks(r.seed, rks, r.d_sub, r.C, "k")), dev(make_codebooks(r.seed, rvs, r.d_sub, r.C, "v"))
+        rt = dict(q=dev(make_decode_query(r.seed, r.B, r.Hq, r.D)),
+                  ck=dev(random_codes(r.seed, "k", r.B, r.Hkv, r.N, r.M)), cv=dev(random_codes(r.seed, "v", r.B, r.Hkv, r.N, r.M)),
+                  ik=dev(random_anchor_sets(r.seed, "k", r.B, r.Hkv, r.N, r.k)), iv=dev(random_anchor_sets(r.seed, "v", r.B, r.Hkv, r.N, r.k)),
+                  rk=dev(normal_fp16(r.seed, "rows_k", (r.B, r.Hkv, r.k, r.D))), rv=dev(normal_fp16(r.seed, "rows_v", (r.B, r.Hkv, r.k, r.D))))
+        ms_r = {}
+        for resel in (0, r.k):
+            rws = antkv.DecodeWorkspace(rg, r.N, r.k, r.k, resel, devc)
+            f = lambda i: antkv.decode_attn(rg, rt["q"], r.scale, rt["ck"], rt["cv"], rcbk, rcbv, rt["ik"], rt["rk"], rt["iv"],
+                                            rt["rv"], k_resel=resel, workspace=rws)
+            f(0)
+            ms_r[resel] = timed(20, f)
+        result["extra"].update({
+            "cfg4_decode_ms": ms_r[0], "cfg4_decode_plus_reselection_ms": ms_r[r.k],
+            "cfg4_workload": f"cfg4: B1, N={r.N}, d_sub {r.d_sub}, {r.k} anchors per head (cache-shaped random codes, warm); "
+                             f"re-selection = decode-time Anchor Score over all tokens + top-{r.k} for K and V",
+        })
+        log(f"cfg4 decode {ms_r[0] * 1e3:.0f} us; with re-selection {ms_r[r.k] * 1e3:.0f} us")
+        del rt
         torch.cuda.empty_cache()
 
         # ------------------------------------------------------------ CPU baseline: the oracle, as it stands

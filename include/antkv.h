@@ -27,7 +27,10 @@
  *   - Codebooks: fp16 [Hkv][M][256][d_sub], separate for K and V; sub-space m covers
  *     channels [m*d_sub, (m+1)*d_sub).
  *   - Codes: uint8 [B][Hkv][N_cap][M], token-major.
- *   - Calls that share a workspace must not overlap in time.
+ *   - Calls that share a workspace must not overlap in time.  A workspace may hold any bytes when it is first
+ *     used (nothing has to be cleared) and may be reused by calls of different shapes.
+ *   - Codes and index sets are deterministic.  The fp16 output of antkv_decode_attn can differ between two runs
+ *     in its last bits (work is handed to wavefronts dynamically, so the order of the fp32 partial sums varies).
  */
 #ifndef ANTKV_H
 #define ANTKV_H

@@ -172,13 +172,16 @@ def anchor_select(geom: Geometry, q: torch.Tensor, k_fp16: torch.Tensor, scale: 
     return idx_k, idx_v, ans_k, ans_v
 
 
-def gather_rows(geom: Geometry, x: torch.Tensor, idx: torch.Tensor) -> torch.Tensor:
+def gather_rows(geom: Geometry, x: torch.Tensor, idx: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
     """antkv_gather_rows: x fp16 [B,Hkv,N,D], idx int32 [B,Hkv,k] -> rows fp16 [B,Hkv,k,D]."""
     _need(x, torch.float16, "x")
     _need(idx, torch.int32, "idx")
     B, Hkv, N, D = x.shape
     k = idx.shape[-1]
-    rows = torch.empty((B, Hkv, k, D), dtype=torch.float16, device=x.device)
+    if out is None:
+        out = torch.empty((B, Hkv, k, D), dtype=torch.float16, device=x.device)
+    _need(out, torch.float16, "out")
+    rows = out
     g = geom.c()
     rc = load_library().antkv_gather_rows(ctypes.byref(g), _p(x), N, _p(idx), k, _p(rows), _stream(x))
     _check(rc, "antkv_gather_rows")
