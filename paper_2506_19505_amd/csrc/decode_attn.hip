@@ -146,6 +146,42 @@ __device__ int wave_lower_bound(const int32_t* __restrict__ arr, int n, int key,
     return lo;
 }
 
+// two searches in lockstep (key_a <= key_b): the probe loads of a round are issued together, so the pair costs
+// the latency of one search
+__device__ void wave_lower_bound2(const int32_t* __restrict__ arr, int n, int key_a, int key_b, int lane,
+                                  int& res_a, int& res_b)
+{
+    int lo_a = 0, hi_a = n, lo_b = 0, hi_b = n;
+    while (hi_a > lo_a || hi_b > lo_b) {
+        const int st_a = (hi_a - lo_a + 63) >> 6, st_b = (hi_b - lo_b + 63) >> 6;
+        const int p_a = lo_a + lane * st_a, p_b = lo_b + lane * st_b;
+        const int v_a = (p_a < hi_a) ? arr[p_a] : 0x7fffffff;
+        const int v_b = (p_b < hi_b) ? arr[p_b] : 0x7fffffff;
+        if (hi_a > lo_a) {
+            const int c = __builtin_popcountll(__ballot(v_a < key_a));
+            if (c == 0) hi_a = lo_a;
+            else {
+                const int nlo = lo_a + (c - 1) * st_a + 1, nhi = lo_a + c * st_a;
+                lo_a = nlo;
+                hi_a = nhi < hi_a ? nhi : hi_a;
+                if (st_a == 1) hi_a = lo_a;
+            }
+        }
+        if (hi_b > lo_b) {
+            const int c = __builtin_popcountll(__ballot(v_b < key_b));
+            if (c == 0) hi_b = lo_b;
+            else {
+                const int nlo = lo_b + (c - 1) * st_b + 1, nhi = lo_b + c * st_b;
+                lo_b = nlo;
+                hi_b = nhi < hi_b ? nhi : hi_b;
+                if (st_b == 1) hi_b = lo_b;
+            }
+        }
+    }
+    res_a = lo_a;
+    res_b = lo_b;
+}
+
 // per-lane binary search: position of key in sorted arr[0..n) or -1
 __device__ __forceinline__ int find_sorted(const int32_t* __restrict__ arr, int n, int key)
 {
@@ -541,8 +577,8 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 if (act == 0ull || n == 0) continue;
                 const int l_first = __builtin_ctzll(act), l_last = 63 - __builtin_clzll(act);
                 const int tok_first = __shfl(my_tok, l_first, 64), tok_last = __shfl(my_tok, l_last, 64);
-                const int w_lo = wave_lower_bound(arr, n, tok_first, lane);
-                const int w_hi = wave_lower_bound(arr, n, tok_last + 1, lane);
+                int w_lo, w_hi;
+                wave_lower_bound2(arr, n, tok_first, tok_last + 1, lane, w_lo, w_hi);
                 int found = -1;
                 if (w_hi - w_lo <= 64) {
                     const int wv = (w_lo + lane < w_hi) ? arr[w_lo + lane] : 0x7fffffff;
@@ -1231,7 +1267,17 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     p.trace = (unsigned long long*)ws;
     p.c1 = a.scale * kLog2e; p.Hq = g.Hq; p.Hkv = g.Hkv; p.G = g.G; p.S = pl.S; p.chunk = pl.chunk;
     const size_t shmem = Lds<DSUB>::total;
-    hipError_t e = hipFuncSetAttribute((const void*)decode_attn_kernel<DSUB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    // One-time set-up per instantiation (and per process): raise the dynamic LDS limit, and make sure the kernel has
+    // no static LDS — its table gathers use absolute LDS addresses, which assumes the dynamic block starts at 0.
+    static const hipError_t setup = [] {
+        hipFuncAttributes attr;
+        hipError_t r = hipFuncGetAttributes(&attr, (const void*)decode_attn_kernel<DSUB>);
+        if (r != hipSuccess) return r;
+        if (attr.sharedSizeBytes != 0) return hipErrorInvalidConfiguration;
+        return hipFuncSetAttribute((const void*)decode_attn_kernel<DSUB>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)Lds<DSUB>::total);
+    }();
+    hipError_t e = setup;
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((int64_t)g.B * g.Hkv * pl.S);
     if (t_ev_start) (void)hipEventRecord(t_ev_start, st);
