@@ -942,19 +942,48 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         s_misc[10] = (int)(unsigned int)__hip_atomic_fetch_add(&p.done[bg], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
     __syncthreads();
     if (s_misc[10] == p.S) {
+        // S can be a few hundred: the statistics of all slots go through LDS first (one round of loads), then every
+        // (head, channel) thread sums its column with eight independent loads in flight.
+        auto ld = [](const float* q) { return __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+        float* s_w = (float*)(smem + L::mrg);                       // [4 heads][S]: slot weights 2^(m_s - m) (table area is free now)
+        float* s_tot = s_w + kNH * 1024;                            // [4]: total l per head
+        const int S = p.S;
+        for (int i = tid; i < kNH * S; i += kDaThreads) {
+            const int h = i / S, sl = i - h * S;
+            s_w[h * 1024 + sl] = (h < nheads) ? ld(part_bg + ((int64_t)h * S + sl) * (kD + 2) + kD) : kNegBig;
+        }
+        __syncthreads();
+        if (wave < kNH) {                                           // one wave per head: global maximum, weights, total
+            const int h = wave;
+            float m = kNegBig;
+            for (int sl = lane; sl < S; sl += 64) m = fmaxf(m, s_w[h * 1024 + sl]);
+            m = wave_max(m);
+            float l = 0.f;
+            for (int sl = lane; sl < S; sl += 64) {
+                const float w = fast_exp2(s_w[h * 1024 + sl] - m);
+                s_w[h * 1024 + sl] = w;
+                if (h < nheads) l += ld(part_bg + ((int64_t)h * S + sl) * (kD + 2) + kD + 1) * w;
+            }
+            l = wave_sum(l);
+            if (lane == 0) s_tot[h] = l;
+        }
+        __syncthreads();
         if (tid < kNH * kD) {
             const int h = tid >> 7, dim = tid & 127;
             if (h < nheads) {
-                const float* pb = part_bg + (int64_t)h * p.S * (kD + 2);
-                float m = kNegBig;
-                auto ld = [](const float* q) { return __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
-                for (int sl = 0; sl < p.S; ++sl) m = fmaxf(m, ld(pb + sl * (kD + 2) + kD));
-                float l = 0.f, a = 0.f;
-                for (int sl = 0; sl < p.S; ++sl) {
-                    const float w = fast_exp2(ld(pb + sl * (kD + 2) + kD) - m);
-                    l += ld(pb + sl * (kD + 2) + kD + 1) * w;
-                    a += ld(pb + sl * (kD + 2) + dim) * w;
+                const float* pb = part_bg + (int64_t)h * S * (kD + 2) + dim;
+                float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                int sl = 0;
+                for (; sl + 8 <= S; sl += 8) {
+                    float v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v[u] = ld(pb + (int64_t)(sl + u) * (kD + 2));
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) a8[u] = fmaf(v[u], s_w[h * 1024 + sl + u], a8[u]);
                 }
+                for (; sl < S; ++sl) a8[0] = fmaf(ld(pb + (int64_t)sl * (kD + 2)), s_w[h * 1024 + sl], a8[0]);
+                const float a = ((a8[0] + a8[1]) + (a8[2] + a8[3])) + ((a8[4] + a8[5]) + (a8[6] + a8[7]));
+                const float l = s_tot[h];
                 p.out[((int64_t)b * p.Hq + h0 + h) * kD + dim] = (half_t)(l > 0.f ? a / l : 0.f);
             }
         }
@@ -1266,6 +1295,7 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     p.part = part; p.out = a.out; p.done = (unsigned long long*)(w + pl.off_done); p.tag = next_launch_tag(); p.N = a.N; p.N_cap = a.N_cap; p.k_k = (int)a.k_k; p.k_v = (int)a.k_v;
     p.trace = (unsigned long long*)ws;
     p.c1 = a.scale * kLog2e; p.Hq = g.Hq; p.Hkv = g.Hkv; p.G = g.G; p.S = pl.S; p.chunk = pl.chunk;
+    if (pl.S > 1024) return hipErrorInvalidValue;        // the in-kernel merge keeps one weight per slot in LDS
     const size_t shmem = Lds<DSUB>::total;
     // One-time set-up per instantiation (and per process): raise the dynamic LDS limit, and make sure the kernel has
     // no static LDS — its table gathers use absolute LDS addresses, which assumes the dynamic block starts at 0.
