@@ -226,7 +226,6 @@ struct Lds {
     static constexpr int lut = 0;                                  // [256 codes][32 slots][4 x (lo, hi) bytes] = 64 KB
     static constexpr int cbv = lut + 65536;                        // [256 codes][M][DSUB] fp16 = 64 KB (a 256-byte row per code)
     static constexpr int pst = cbv + 65536;                        // [waves] staging (P tile + V code words / anchor V rows)
-    static constexpr int qf = pst;                                 // prologue only: [4][128] fp32 query
     static constexpr int mrg = 0;                                  // merge: [waves][4][128] fp32 (2 KB per wave)
     static constexpr int qh = pst + kDaWaves * kStgBytes;          // [4][128] fp16 (MFMA operand source)
     static constexpr int red = qh + 1024;                          // [waves][8] fp32 + 16 ints
@@ -294,8 +293,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
 {
     constexpr int M = kD / DSUB;
     constexpr int CW = M / 4;                          // code dwords per token
-    constexpr int EPT = M * 256 / kDaThreads;          // LUT entries per thread
-    static_assert(EPT >= 1 && EPT * kDaThreads == M * 256, "LUT entries must divide evenly over the threads");
+    static_assert(kDaWaves == 16, "the table build gives each of 16 waves 16 of the 256 codes");
     using L = Lds<DSUB>;
     extern __shared__ uint4_t smem_u4[];
     char* smem = (char*)smem_u4;
@@ -330,18 +328,12 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     const int tq = lane & 3;              // 8-byte chunk of a 32-byte channel slab / quad lane
     const int arow = lane & 15;           // A-operand row (head) / C column (channel)
 
-    float* s_qf = (float*)(smem + L::qf);
     int* s_misc = (int*)(smem + L::red + kDaWaves * 32);
     uint32_t* s_mask = (uint32_t*)(smem + L::mask);
 
     // ================================================================================== prologue
     {
         // all global loads of the prologue are issued before anything waits on them.
-        // Threads are grouped by sub-space (TPM threads each) so that a thread reads its q sub-vectors once.
-        // (sub-space fastest across lanes: the table stores of a wave then spread over all LDS banks)
-        constexpr int TPM = kDaThreads / M;               // threads per sub-space
-        static_assert(TPM * M == kDaThreads && TPM * EPT == 256, "thread to LUT-entry mapping");
-        const int lm = tid % M, lc0 = tid / M;            // entries (lm, lc0 + TPM*i), i < EPT
         // the small loads go first: the first barrier then waits for them only, and the two 64 KB tables
         // keep streaming in behind it
         half_t qv16 = (half_t)0.f;
@@ -367,15 +359,30 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             if (!((wave < 2) ? scan_k : scan_v)) r = wave_lower_bound(arr, n, (int)((wave & 1) ? t1 : t0), lane);
             if (lane == 0) s_misc[wave] = r;
         }
-        uint4_t cen[EPT][DSUB / 8 > 0 ? DSUB / 8 : 1];
-        uint2_t cen4[EPT];
+        // The q.centroid table is one small matrix product per sub-space, batched on the MFMA by making the
+        // query operand block-diagonal: an MFMA takes 16 codes (columns) and four sub-spaces; k-group kg of the
+        // centroid operand holds sub-space kg's centroid (or half / two of them for d = 16 / 4), and row 4 m' + h of
+        // the query operand is q_h's matching slice in k-group m' and zero elsewhere.  C then holds, in lane
+        // (code, block m'), the four heads' products for (sub-space of block m', code): one table entry per lane.
+        constexpr int NJ = (DSUB == 4) ? 8 : 4;            // MFMAs per wave; each wave owns 16 codes
+        const int l_code = 16 * wave + (lane & 15);        // this lane's code (column)
+        const int l_mp = (lane & 15) >> 2, l_h = lane & 3; // query-operand row = 4 m' + h
+        uint4_t opb[4], opa[4];
 #pragma unroll
-        for (int i = 0; i < EPT; ++i) {
-            const int e = lm * 256 + lc0 + TPM * i;
-            if (DSUB == 4) cen4[i] = *(const uint2_t*)(cbk + e * 4);
-            else {
-#pragma unroll
-                for (int u = 0; u < DSUB / 8; ++u) cen[i][u] = *(const uint4_t*)(cbk + e * DSUB + 8 * u);
+        for (int j = 0; j < 4; ++j) {
+            opa[j] = uint4_t{0u, 0u, 0u, 0u};
+            if constexpr (DSUB == 8) {
+                opb[j] = *(const uint4_t*)(cbk + ((4 * j + kgrp) * 256 + l_code) * 8);
+                if (kgrp == l_mp && l_h < nheads) opa[j] = *(const uint4_t*)(qb + l_h * kD + (4 * j + l_mp) * 8);
+            } else if constexpr (DSUB == 16) {
+                opb[j] = *(const uint4_t*)(cbk + ((2 * j + (kgrp >> 1)) * 256 + l_code) * 16 + 8 * (kgrp & 1));
+                if ((kgrp >> 1) == l_mp && l_h < nheads)
+                    opa[j] = *(const uint4_t*)(qb + l_h * kD + (2 * j + l_mp) * 16 + 8 * (kgrp & 1));
+            } else {
+                const uint2_t lo = *(const uint2_t*)(cbk + ((8 * j + 2 * kgrp) * 256 + l_code) * 4);
+                const uint2_t hi = *(const uint2_t*)(cbk + ((8 * j + 2 * kgrp + 1) * 256 + l_code) * 4);
+                opb[j] = uint4_t{lo[0], lo[1], hi[0], hi[1]};
+                if (kgrp == l_mp && l_h < nheads) opa[j] = *(const uint4_t*)(qb + l_h * kD + (8 * j + 2 * l_mp) * 4);
             }
         }
         // V codebook: LDS holds it code-major ([code][m][DSUB], a 256-byte row per code), so 16-byte chunk ci of
@@ -393,10 +400,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 vcopy[i] = uint4_t{lo[0], lo[1], hi[0], hi[1]};
             }
         }
-        if (tid < kNH * kD) {
-            s_qf[tid] = (float)qv16;
-            ((half_t*)(smem + L::qh))[tid] = qv16;
-        }
+        if (tid < kNH * kD) ((half_t*)(smem + L::qh))[tid] = qv16;
         for (int i = tid; i < L::mask_words; i += kDaThreads) s_mask[i] = 0u;
         if (tid == 0) { s_misc[8] = 0; s_misc[9] = 0; }          // next stream tile, next anchor tile of this workgroup
         __syncthreads();
@@ -433,37 +437,22 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         // the table error is uniform instead of growing with the entry's magnitude as it would in fp16.
         // An entry is two signed bytes (lo, -hi) with value lo + 128 * hi, so that the int8 MFMA of the stream
         // loop can sum entries with the weights (1, -128).
-        float val[EPT][kNH];
+        float val[NJ][kNH];
         float amax[kNH] = {0.f, 0.f, 0.f, 0.f};
-        {
-            float qs[kNH][DSUB];
+        const bool ent_on = (DSUB != 16) || kgrp < 2;       // d = 16: only blocks 0 and 1 carry sub-spaces
 #pragma unroll
-            for (int h = 0; h < kNH; ++h)
+        for (int j = 0; j < NJ; ++j) {
+            uint4_t a4 = opa[(DSUB == 4) ? (j >> 1) : j];
+            if constexpr (DSUB == 4) {                       // sub-space 2 m' + u of the pair lives in half u of the slice
+                if (j & 1) { a4[0] = 0u; a4[1] = 0u; } else { a4[2] = 0u; a4[3] = 0u; }
+            }
+            const float4_t c4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                __builtin_bit_cast(half8_t, a4), __builtin_bit_cast(half8_t, opb[(DSUB == 4) ? (j >> 1) : j]),
+                float4_t{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
 #pragma unroll
-                for (int t = 0; t < DSUB; ++t) qs[h][t] = s_qf[h * kD + lm * DSUB + t] * p.c1;
-#pragma unroll
-            for (int i = 0; i < EPT; ++i) {
-                float cf[DSUB];
-                if (DSUB == 4) {
-                    const half4_t v = __builtin_bit_cast(half4_t, cen4[i]);
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) cf[t] = (float)v[t];
-                } else {
-#pragma unroll
-                    for (int u = 0; u < DSUB / 8; ++u) {
-                        const half8_t v = __builtin_bit_cast(half8_t, cen[i][u]);
-#pragma unroll
-                        for (int t = 0; t < 8; ++t) cf[8 * u + t] = (float)v[t];
-                    }
-                }
-#pragma unroll
-                for (int h = 0; h < kNH; ++h) {
-                    float sdot = 0.f;
-#pragma unroll
-                    for (int t = 0; t < DSUB; ++t) sdot = fmaf(qs[h][t], cf[t], sdot);
-                    val[i][h] = sdot;
-                    amax[h] = fmaxf(amax[h], fabsf(sdot));
-                }
+            for (int h = 0; h < kNH; ++h) {
+                val[j][h] = c4[h] * p.c1;
+                if (ent_on) amax[h] = fmaxf(amax[h], fabsf(val[j][h]));
             }
         }
         float* s_red = (float*)(smem + L::red);
@@ -487,19 +476,35 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             }
         }
         uint2_t* s_lut = (uint2_t*)(smem + L::lut);
+        uint2_t ent[NJ];
 #pragma unroll
-        for (int i = 0; i < EPT; ++i) {
+        for (int j = 0; j < NJ; ++j) {
             uint32_t hw[kNH];
 #pragma unroll
             for (int h = 0; h < kNH; ++h) {
-                const int qv = (int)rintf(val[i][h] * inv_q[h]);     // |qv| <= kLutMax
+                const int qv = (int)rintf(val[j][h] * inv_q[h]);     // |qv| <= kLutMax
                 const int hi = (qv + 64) >> 7;                          // qv = lo + 128 * hi, lo in [-64, 63]
                 const int lo = qv - 128 * hi;
                 hw[h] = ((uint32_t)lo & 0xffu) | (((uint32_t)(-hi) & 0xffu) << 8);
             }
-            const uint2_t ent = uint2_t{hw[0] | (hw[1] << 16), hw[2] | (hw[3] << 16)};
+            ent[j] = uint2_t{hw[0] | (hw[1] << 16), hw[2] | (hw[3] << 16)};
+        }
+        // The lanes of a block hold the same sub-space for 16 different codes, i.e. 16 rows at the same bank.  In
+        // round r a lane therefore stores entry (r + code) mod NJ, and starts with copy (code / 4) mod REPS of it:
+        // the 32 lanes of an LDS pass then spread over 16 or 32 different slots.
+        constexpr int REPS = 32 / M;
+        if (ent_on) {
 #pragma unroll
-            for (int rep = 0; rep < 32 / M; ++rep) s_lut[(lc0 + TPM * i) * 32 + lm + M * rep] = ent;
+            for (int r = 0; r < NJ; ++r) {
+                const int j = (r + lane) & (NJ - 1);
+                uint2_t e = ent[0];
+#pragma unroll
+                for (int jj = 1; jj < NJ; ++jj) e = (j == jj) ? ent[jj] : e;
+                const int m = (DSUB == 8) ? 4 * j + kgrp : (DSUB == 16 ? 2 * j + kgrp : 8 * (j >> 1) + 2 * kgrp + (j & 1));
+#pragma unroll
+                for (int rep = 0; rep < REPS; ++rep)
+                    s_lut[l_code * 32 + m + M * ((rep + (lane >> 2)) & (REPS - 1))] = e;
+            }
         }
         DA_STAMP(4);
         // the V table is not needed before the first P.V: its loads had the whole table build to land
@@ -887,21 +892,30 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
+                // The units of this step (one sparse MFMA each) are software-pipelined: the transposed reads of
+                // unit u+1 are in flight while unit u waits for its own and multiplies.
+                constexpr int NU = (TOKS / 16) * ((DSUB == 16) ? 2 : 1);
+                auto unit_a = [&](int u) { return (DSUB == 16) ? (u & 1) : a_s; };
+                auto unit_i = [&](int u) { const int ii = (DSUB == 16) ? (u >> 1) : u; return (DSUB == 4) ? 2 * th + ii : ii; };
+                auto fetch_unit = [&](int u, half4_t (&vb)[4]) {
+                    const int ii = (DSUB == 16) ? (u >> 1) : u;
+                    const int a = unit_a(u);
+                    const uint4_t cw = *(const uint4_t*)(s_cws_r + ((DSUB == 16) ? a * CWROW : 0) + 4 * ii);
 #pragma unroll
-                for (int ii = 0; ii < TOKS / 16; ++ii) {
-                    const int i = (DSUB == 4) ? 2 * th + ii : ii;
+                    for (int e4 = 0; e4 < 4; ++e4)
+                        vb[e4] = lds_read_tr16_abs(__builtin_amdgcn_perm(cw[e4], v_const, v_sel) + 128 * a);
+                };
+                half4_t vb0[4], vb1[4];
+                fetch_unit(0, vb0);
 #pragma unroll
-                    for (int aa = 0; aa < ((DSUB == 16) ? 2 : 1); ++aa) {
-                        const int a = (DSUB == 16) ? aa : a_s;
-                        const uint4_t cw = *(const uint4_t*)(s_cws_r + ((DSUB == 16) ? a * CWROW : 0) + 4 * ii);
-                        half4_t vb[4];
-#pragma unroll
-                        for (int e4 = 0; e4 < 4; ++e4)
-                            vb[e4] = lds_read_tr16_abs(__builtin_amdgcn_perm(cw[e4], v_const, v_sel) + 128 * a);
-                        const half16_t bop = {vb[0][0], vb[0][1], vb[0][2], vb[0][3], vb[1][0], vb[1][1], vb[1][2], vb[1][3],
-                                              vb[2][0], vb[2][1], vb[2][2], vb[2][3], vb[3][0], vb[3][1], vb[3][2], vb[3][3]};
-                        acc[a] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(pa[i], bop, acc[a], sm_idx, 0, 0);
-                    }
+                for (int u = 0; u < NU; ++u) {
+                    half4_t (&cur)[4] = (u & 1) ? vb1 : vb0;
+                    half4_t (&nxt)[4] = (u & 1) ? vb0 : vb1;
+                    if (u + 1 < NU) fetch_unit(u + 1, nxt);
+                    const half16_t bop = {cur[0][0], cur[0][1], cur[0][2], cur[0][3], cur[1][0], cur[1][1], cur[1][2], cur[1][3],
+                                          cur[2][0], cur[2][1], cur[2][2], cur[2][3], cur[3][0], cur[3][1], cur[3][2], cur[3][3]};
+                    const int a = unit_a(u);
+                    acc[a] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(pa[unit_i(u)], bop, acc[a], sm_idx, 0, 0);
                 }
             }
             __builtin_amdgcn_wave_barrier();
