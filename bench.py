@@ -237,6 +237,31 @@ def main() -> int:
         del rt
         torch.cuda.empty_cache()
 
+        # ------------------------------------------------------------ decode append with a 32-token FP16 window
+        a_W, a_k, a_N0, a_steps = 32, 64 + 32, 1024, 200
+        a_cap = a_N0 + a_steps + 20
+        a_codes_k = torch.zeros((w.B, w.Hkv, a_cap, w.M), dtype=torch.uint8, device=devc)
+        a_codes_v = torch.zeros_like(a_codes_k)
+        a_idx = torch.cat([torch.arange(0, a_k - a_W, dtype=torch.int32), torch.arange(a_N0 - a_W, a_N0, dtype=torch.int32)])
+        a_idx_k = a_idx.repeat(w.B, w.Hkv, 1).contiguous().to(devc)
+        a_idx_v = a_idx_k.clone()
+        a_rows_k = dev(normal_fp16(w.seed, "win_rows_k", (w.B, w.Hkv, a_k, w.D)))
+        a_rows_v = dev(normal_fp16(w.seed, "win_rows_v", (w.B, w.Hkv, a_k, w.D)))
+        a_new_k = dev(normal_fp16(w.seed, "new_k", (w.B, w.Hkv, w.D)))
+        a_new_v = dev(normal_fp16(w.seed, "new_v", (w.B, w.Hkv, w.D)))
+        a_n = [a_N0]
+
+        def app(i):
+            a_n[0] = antkv.append_token(geom, a_new_k, a_new_v, a_n[0], a_W, cbk_d, cbv_d, a_codes_k, a_codes_v,
+                                        a_idx_k, a_rows_k, a_idx_v, a_rows_v)
+        for i in range(10):
+            app(i)
+        ms_app = timed(a_steps, app)
+        result["extra"].update({"append_token_us": ms_app * 1e3,
+                                "append_workload": f"B={w.B}, {w.Hkv} KV heads, d_sub {w.d_sub}, window {a_W}: retire one token "
+                                                   f"(encode K and V rows), shift the window, insert the new rows"})
+        log(f"append_token {ms_app * 1e3:.1f} us per step")
+
         # ------------------------------------------------------------ CPU baseline: the oracle, as it stands
         import oracle
         oracle.build()

@@ -148,6 +148,28 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
                       int64_t k_resel, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Decode append with an FP16 sliding window (Sec. 3.2, last paragraph: during decoding the Anchor Score's tail
+ * locality is served by a sliding window of recent tokens kept in full precision; Sec. 4 uses a window of 32).
+ * The window is the last W entries of BOTH anchor lists: before the call they are the positions N-W .. N-1.
+ * The call (a) retires the oldest window token: its FP16 K / V rows are encoded against cb_k / cb_v (nearest centroid
+ * per sub-vector with the lowest index among equal fp32 distances, as antkv_encode) into codes_k / codes_v at position N-W; (b) moves the other W-1 window entries one
+ * place down; (c) stores k_new / v_new as the last entry with position N.  Afterwards the context has N+1 tokens
+ * and the window is N-W+1 .. N; antkv_decode_attn can be called with N+1 and the same lists.  With W == 0 there is
+ * no window: the new rows are encoded straight to position N.
+ *
+ *   k_new, v_new  fp16 [B][Hkv][D], 16-byte aligned
+ *   codes_k, codes_v  uint8 [B][Hkv][N_cap][M];  N + 1 <= N_cap
+ *   idx_k int32 [B][Hkv][k_k], rows_k fp16 [B][Hkv][k_k][D] (16-byte aligned), k_k >= W; likewise idx_v, rows_v, k_v.
+ *   0 <= W <= 64, W <= N.
+ * All work is enqueued on `stream` in order; nothing else may touch the lists or the codes meanwhile.
+ * Errors: EINVAL, EUNSUPPORTED (W > 64), ELAUNCH.
+ */
+int antkv_append_token(const antkv_geom* geom, const void* k_new, const void* v_new, int64_t N, int64_t W,
+                       const void* cb_k, const void* cb_v, uint8_t* codes_k, uint8_t* codes_v, int64_t N_cap,
+                       int32_t* idx_k, void* rows_k, int64_t k_k, int32_t* idx_v, void* rows_v, int64_t k_v,
+                       void* stream);
+
+/*
  * Measurement aid, not part of the method: the next antkv_decode_attn call made from this host thread
  * records `start_event` right before and `stop_event` right after its dominant kernel (the one that
  * streams the codes) on that call's stream.  Both are hipEvent_t handles (host handles, created by the

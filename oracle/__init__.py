@@ -11,6 +11,8 @@ arrays into it and adds the top-k step, which is a stable library sort.
   topk(scores, k)               keep the k highest scores (Sec. 3, "anchor tokens")
   decode_attn(...)              Attn (Sec. 2.1) over codes + FP16 anchors, and the
                                 decode-time Anchor Score (Sec. 3.2, last paragraph)
+  append_token(...)             decode append with an FP16 sliding window (Sec. 3.2, last
+                                paragraph; window of 32 in Sec. 4)
 """
 from __future__ import annotations
 
@@ -163,3 +165,32 @@ def decode_attn(q, codes_k, codes_v, cb_k, cb_v, idx_k, rows_k, idx_v, rows_v, s
     if want_ans:
         extras["ans_k"], extras["ans_v"] = ans_k, ans_v
     return (out, extras) if extras else out
+
+
+def append_token(k_new, v_new, N: int, W: int, cb_k, cb_v, codes_k, codes_v, idx_k, rows_k, idx_v, rows_v,
+                 want_margin: bool = False):
+    """One decode append with a sliding window of W full-precision tokens (paper Sec. 3.2, last paragraph).
+
+    The window is the last W entries of both anchor lists (positions N-W .. N-1).  In place: the oldest window
+    token is encoded to its codes at position N-W, the window moves one place down, the new rows k_new / v_new
+    [B,Hkv,D] become the last entry with position N.  W == 0: the new rows are encoded straight to position N.
+    Returns N + 1 (and, if asked, the near-tie margins of the two code rows that were written).
+    """
+    if W == 0:
+        ck, mk = encode(np.asarray(k_new)[:, :, None, :], cb_k, want_margin=True)
+        cv, mv = encode(np.asarray(v_new)[:, :, None, :], cb_v, want_margin=True)
+        codes_k[:, :, N] = ck[:, :, 0]
+        codes_v[:, :, N] = cv[:, :, 0]
+        return (N + 1, mk[:, :, 0], mv[:, :, 0]) if want_margin else N + 1
+    margins = []
+    for codes, cb, idx, rows, new in ((codes_k, cb_k, idx_k, rows_k, k_new), (codes_v, cb_v, idx_v, rows_v, v_new)):
+        k = idx.shape[-1]
+        first = k - W                                   # the window's oldest entry
+        assert (idx[..., first:] == np.arange(N - W, N)).all(), "the window must be the last W positions"
+        c, m = encode(rows[:, :, first:first + 1, :], cb, want_margin=True)
+        codes[:, :, N - W] = c[:, :, 0]
+        margins.append(m[:, :, 0])
+        rows[:, :, first:k - 1] = rows[:, :, first + 1:k].copy()
+        rows[:, :, k - 1] = new
+        idx[..., first:] = np.arange(N - W + 1, N + 1)
+    return (N + 1, margins[0], margins[1]) if want_margin else N + 1

@@ -9,6 +9,7 @@ from .binding import (
     DecodeWorkspace,
     Geometry,
     anchor_select,
+    append_token,
     decode_attn,
     encode,
     gather_rows,
@@ -24,6 +25,7 @@ __all__ = [
     "DecodeWorkspace",
     "Geometry",
     "anchor_select",
+    "append_token",
     "decode_attn",
     "encode",
     "gather_rows",

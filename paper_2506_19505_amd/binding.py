@@ -15,7 +15,7 @@ _lib = None
 EXPORTS = (
     "antkv_version", "antkv_strerror", "antkv_encode", "antkv_anchor_select_workspace", "antkv_anchor_select",
     "antkv_topk_workspace", "antkv_topk", "antkv_gather_rows", "antkv_decode_attn_workspace", "antkv_decode_attn",
-    "antkv_profile_next_decode",
+    "antkv_append_token", "antkv_profile_next_decode",
 )
 
 
@@ -75,6 +75,8 @@ def load_library():
         lib.antkv_topk.argtypes = [vp, i64, i64, i64, vp, vp, sz, vp]
         lib.antkv_gather_rows.restype = ctypes.c_int
         lib.antkv_gather_rows.argtypes = [gp, vp, i64, vp, i64, vp, vp]
+        lib.antkv_append_token.restype = ctypes.c_int
+        lib.antkv_append_token.argtypes = [gp, vp, vp, i64, i64, vp, vp, vp, vp, i64, vp, vp, i64, vp, vp, i64, vp]
         lib.antkv_decode_attn_workspace.restype = sz
         lib.antkv_decode_attn_workspace.argtypes = [gp, i64, i64, i64, i64]
         lib.antkv_decode_attn.restype = ctypes.c_int
@@ -192,6 +194,31 @@ def profile_next_decode(start: "torch.cuda.Event | None", stop: "torch.cuda.Even
     """antkv_profile_next_decode: record the two (already created) timing events around the next decode kernel."""
     h = lambda e: None if e is None else ctypes.c_void_p(e.cuda_event)
     load_library().antkv_profile_next_decode(h(start), h(stop))
+
+
+def append_token(geom: Geometry, k_new: torch.Tensor, v_new: torch.Tensor, N: int, W: int, cb_k: torch.Tensor,
+                 cb_v: torch.Tensor, codes_k: torch.Tensor, codes_v: torch.Tensor, idx_k: torch.Tensor | None,
+                 rows_k: torch.Tensor | None, idx_v: torch.Tensor | None, rows_v: torch.Tensor | None) -> int:
+    """antkv_append_token: retire the oldest of the W window tokens into the codes, shift the window (the last W
+    entries of both anchor lists) and append the new rows at position N.  Returns the new context length N + 1."""
+    _need(k_new, torch.float16, "k_new")
+    _need(v_new, torch.float16, "v_new")
+    _need(codes_k, torch.uint8, "codes_k")
+    _need(codes_v, torch.uint8, "codes_v")
+    k_k = 0 if idx_k is None else idx_k.shape[-1]
+    k_v = 0 if idx_v is None else idx_v.shape[-1]
+    for name, t, dt in (("idx_k", idx_k, torch.int32), ("rows_k", rows_k, torch.float16), ("idx_v", idx_v, torch.int32),
+                        ("rows_v", rows_v, torch.float16)):
+        if t is not None:
+            _need(t, dt, name)
+    null = ctypes.c_void_p(0)
+    g = geom.c()
+    rc = load_library().antkv_append_token(
+        ctypes.byref(g), _p(k_new), _p(v_new), N, W, _p(cb_k), _p(cb_v), _p(codes_k), _p(codes_v), codes_k.shape[2],
+        _p(idx_k) if idx_k is not None else null, _p(rows_k) if rows_k is not None else null, k_k,
+        _p(idx_v) if idx_v is not None else null, _p(rows_v) if rows_v is not None else null, k_v, _stream(k_new))
+    _check(rc, "antkv_append_token")
+    return N + 1
 
 
 class DecodeWorkspace:

@@ -156,6 +156,28 @@ int antkv_gather_rows(const antkv_geom* geom, const void* x, int64_t N, const in
     return e == hipSuccess ? ANTKV_OK : ANTKV_ELAUNCH;
 }
 
+int antkv_append_token(const antkv_geom* geom, const void* k_new, const void* v_new, int64_t N, int64_t W,
+                       const void* cb_k, const void* cb_v, uint8_t* codes_k, uint8_t* codes_v, int64_t N_cap,
+                       int32_t* idx_k, void* rows_k, int64_t k_k, int32_t* idx_v, void* rows_v, int64_t k_v,
+                       void* stream)
+{
+    Geom g;
+    int rc = check_geom(geom, g);
+    if (rc) return rc;
+    if (N < 0 || W < 0 || W > N || N + 1 > N_cap || k_k < W || k_v < W) return ANTKV_EINVAL;
+    if (W > 64) return ANTKV_EUNSUPPORTED;
+    if (g.B == 0) return ANTKV_OK;
+    if (!k_new || !v_new || !cb_k || !cb_v || !codes_k || !codes_v || misaligned(k_new, 16) || misaligned(v_new, 16) ||
+        misaligned(cb_k, 16) || misaligned(cb_v, 16) || misaligned(codes_k, 16) || misaligned(codes_v, 16))
+        return ANTKV_EINVAL;
+    if (W > 0 && (!idx_k || !rows_k || !idx_v || !rows_v || misaligned(rows_k, 16) || misaligned(rows_v, 16)))
+        return ANTKV_EINVAL;
+    hipError_t e = launch_append(g, (const half_t*)k_new, (const half_t*)v_new, (const half_t*)cb_k, (const half_t*)cb_v,
+                                 codes_k, codes_v, N_cap, idx_k, (half_t*)rows_k, k_k, idx_v, (half_t*)rows_v, k_v, N, (int)W,
+                                 (hipStream_t)stream);
+    return e == hipSuccess ? ANTKV_OK : ANTKV_ELAUNCH;
+}
+
 void antkv_profile_next_decode(void* start_event, void* stop_event)
 {
     decode_profile_next((hipEvent_t)start_event, (hipEvent_t)stop_event);

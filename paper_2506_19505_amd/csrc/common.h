@@ -75,6 +75,9 @@ hipError_t launch_topk2(const float* scores, int32_t* idx, const float* scores_b
 
 hipError_t launch_gather_rows(const Geom& g, const half_t* x, int64_t N, const int32_t* idx,
                               int64_t k, half_t* rows, hipStream_t st);
+hipError_t launch_append(const Geom& g, const half_t* k_new, const half_t* v_new, const half_t* cb_k, const half_t* cb_v,
+                         uint8_t* codes_k, uint8_t* codes_v, int64_t N_cap, int32_t* idx_k, half_t* rows_k, int64_t k_k,
+                         int32_t* idx_v, half_t* rows_v, int64_t k_v, int64_t N, int W, hipStream_t st);
 
 size_t anchor_score_workspace_bytes(const Geom& g, int64_t N, int64_t Nq);
 hipError_t launch_anchor_score(const Geom& g, const half_t* q, const half_t* k, int64_t N, int64_t Nq,

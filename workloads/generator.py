@@ -40,6 +40,10 @@ _TENSOR_ID = {
     "rows_k": 14,
     "rows_v": 15,
     "misc": 16,
+    "win_rows_k": 17,
+    "win_rows_v": 18,
+    "new_k": 19,
+    "new_v": 20,
 }
 
 
