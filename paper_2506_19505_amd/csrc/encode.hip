@@ -4,10 +4,10 @@
 // centroids runs on one v_mfma_f32_32x32x8_f16 whose accumulator is pre-loaded with -||c||^2/2, so the
 // matrix core emits the comparison value directly.  Centroids sit on the MFMA row axis and tokens on
 // the column axis: a lane then owns one token and sees 16 centroid scores per tile in its accumulator
-// registers, which makes the running arg-max a per-lane affair with compile-time centroid indices.
-// Lanes l and l+32 hold complementary centroid subsets of the same token and are combined once per
-// sub-space.  Ties resolve to the lower centroid index (strict '>' while indices ascend, explicit
-// index compare across the lane pair).
+// registers, which makes the running arg-max a per-lane affair with compile-time centroid indices
+// (done on groups of 8 scores, see below).  Lanes l and l+32 hold complementary centroid subsets of the
+// same token and are combined once per sub-space.  Ties resolve to the lower centroid index (strict '>'
+// while indices ascend, explicit index compare across the lane pair).
 //
 // One workgroup keeps the whole codebook of one KV head (64 KB fp16) plus the -||c||^2/2 table in LDS
 // and walks over 32-token blocks; token sub-vectors are loaded straight from global memory in MFMA
@@ -17,6 +17,11 @@
 namespace antkv {
 
 namespace {
+
+// maxima of finite scores; this file is compiled with -fno-honor-nans so that the chains below become
+// v_max3_f32 / v_max_f32 without NaN canonicalisation of the MFMA results
+__device__ __forceinline__ float max3f(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+__device__ __forceinline__ float max2f(float a, float b) { return fmaxf(a, b); }
 
 constexpr int kEncThreads = 512;
 constexpr int kEncWaves = kEncThreads / 64;
@@ -74,8 +79,15 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(
                 b0 = *(const half4_t*)(xr + m * 16 + 4 * h);
                 b1 = *(const half4_t*)(xr + m * 16 + 8 + 4 * h);
             }
+            // Running maximum over groups of 8 candidates (registers 8*hf .. 8*hf+7 of a tile).  The group maximum
+            // comes from a max3 tree; when a group raises the running maximum (strictly, so the lowest group wins
+            // ties) its id and its 8 scores are kept.  Which of the 8 it was is settled once per sub-space, from
+            // the kept scores, in ascending index order: 15 VALU ops per 8 candidates instead of 24.
             float best = -3.0e38f;
-            int bidx = 0;
+            int gid = 0;
+            float keep[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) keep[e] = -3.0e38f;
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
                 const int crow = m * kC + 32 * t;
@@ -100,13 +112,33 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(
                 acc = __builtin_amdgcn_mfma_f32_32x32x8f16(a0, b0, acc, 0, 0, 0);
                 if (DSUB == 16) acc = __builtin_amdgcn_mfma_f32_32x32x8f16(a1, b1, acc, 0, 0, 0);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const bool better = acc[r] > best;
-                    best = better ? acc[r] : best;
-                    bidx = better ? (32 * t + 8 * (r >> 2) + (r & 3)) : bidx;
+                for (int hf = 0; hf < 2; ++hf) {
+                    const int r0 = 8 * hf;
+                    const float m0 = max3f(acc[r0 + 0], acc[r0 + 1], acc[r0 + 2]);
+                    const float m1 = max3f(acc[r0 + 3], acc[r0 + 4], acc[r0 + 5]);
+                    const float m2 = max3f(m0, m1, acc[r0 + 6]);
+                    const float m3 = max2f(m2, acc[r0 + 7]);
+                    const bool better = m3 > best;
+                    best = better ? m3 : best;
+                    gid = better ? (2 * t + hf) : gid;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) keep[e] = better ? acc[r0 + e] : keep[e];
                 }
             }
-            bidx += 4 * h;
+            // the winning group's centroids are 32 t + 16 hf + 8 j2 + 4 h + e (j2 < 2, e < 4), ascending in j = 4 j2 + e
+            int bidx;
+            {
+                const int c_base = 32 * (gid >> 1) + 16 * (gid & 1) + 4 * h;
+                float fbest = keep[0];
+                int jb = 0;
+#pragma unroll
+                for (int j = 1; j < 8; ++j) {
+                    const bool better = keep[j] > fbest;
+                    fbest = better ? keep[j] : fbest;
+                    jb = better ? j : jb;
+                }
+                bidx = c_base + 8 * (jb >> 2) + (jb & 3);
+            }
             const float ob = __shfl_xor(best, 32, 64);
             const int oi = __shfl_xor(bidx, 32, 64);
             if (ob > best || (ob == best && oi < bidx)) bidx = oi;
