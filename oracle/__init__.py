@@ -13,6 +13,8 @@ arrays into it and adds the top-k step, which is a stable library sort.
                                 decode-time Anchor Score (Sec. 3.2, last paragraph)
   append_token(...)             decode append with an FP16 sliding window (Sec. 3.2, last
                                 paragraph; window of 32 in Sec. 4)
+  prefill_attn(q, k, v, scale)  causal Attn (Sec. 2.1) over the prompt with the softmax row statistics
+                                that the Anchor Score pass reuses (Alg. 1, first step)
 """
 from __future__ import annotations
 
@@ -194,3 +196,32 @@ def append_token(k_new, v_new, N: int, W: int, cb_k, cb_v, codes_k, codes_v, idx
         rows[:, :, k - 1] = new
         idx[..., first:] = np.arange(N - W + 1, N + 1)
     return (N + 1, margins[0], margins[1]) if want_margin else N + 1
+
+
+def prefill_attn(q, k, v, scale: float):
+    """Causal attention over the prompt (paper Sec. 2.1) with the row statistics of Alg. 1's first step.
+
+    q [B,Hq,Nq,D] = the last Nq positions, k and v [B,Hkv,N,D]; query head h reads KV head h // (Hq // Hkv).
+    Query row i sits at position N - Nq + i and sees the keys 0 .. N - Nq + i.
+    Returns out fp64 [B,Hq,Nq,D], row_max [B,Hq,Nq] = max_j scale*S_ij, row_sum = sum_j exp(scale*S_ij - row_max).
+    Written as the definition: the whole score matrix of one head at a time, fp64.
+    """
+    q64, k64, v64 = (np.asarray(a).astype(np.float64) for a in (q, k, v))
+    B, Hq, Nq, D = q64.shape
+    _, Hkv, N, _ = k64.shape
+    G = Hq // Hkv
+    out = np.zeros((B, Hq, Nq, D))
+    row_max = np.zeros((B, Hq, Nq))
+    row_sum = np.zeros((B, Hq, Nq))
+    pos = N - Nq + np.arange(Nq)
+    visible = np.arange(N)[None, :] <= pos[:, None]
+    for b in range(B):
+        for h in range(Hq):
+            s = scale * (q64[b, h] @ k64[b, h // G].T)
+            s = np.where(visible, s, -np.inf)
+            m = s.max(axis=1)
+            e = np.exp(s - m[:, None])
+            l = e.sum(axis=1)
+            out[b, h] = (e / l[:, None]) @ v64[b, h // G]
+            row_max[b, h], row_sum[b, h] = m, l
+    return out, row_max, row_sum
