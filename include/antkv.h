@@ -6,6 +6,7 @@
  * in FP16.  This library holds the online stage (paper Sec. 3, Fig. 2(b)):
  *
  *   antkv_encode         VQ assignment of K / V sub-vectors            (Sec. 3.1)
+ *   antkv_prefill_attn   causal prompt attention + softmax row stats   (Sec. 2.1; Sec. 3.3, Alg. 1 first step)
  *   antkv_anchor_select  Anchor Score of every token + top-k select    (Sec. 3.2, Eq. (4); Sec. 3.3, Alg. 1)
  *   antkv_topk           the selection step alone
  *   antkv_gather_rows    copy the selected FP16 rows into the anchor store
@@ -168,6 +169,23 @@ int antkv_append_token(const antkv_geom* geom, const void* k_new, const void* v_
                        const void* cb_k, const void* cb_v, uint8_t* codes_k, uint8_t* codes_v, int64_t N_cap,
                        int32_t* idx_k, void* rows_k, int64_t k_k, int32_t* idx_v, void* rows_v, int64_t k_v,
                        void* stream);
+
+/*
+ * Causal attention over the prompt (Sec. 2.1) that also returns the softmax row statistics, i.e. the
+ * attention pass that Alg. 1 (Sec. 3.3) runs first and whose statistics antkv_anchor_select accepts.
+ *
+ *   q        fp16 [B][Hq][Nq][D]: the LAST Nq positions of an N-token context; query row i sits at
+ *            position N-Nq+i and sees keys 0 .. N-Nq+i.  1 <= Nq <= N.
+ *   k, v     fp16 [B][Hkv][N][D]; query head h reads KV head h / (Hq/Hkv)
+ *   out      fp16 [B][Hq][Nq][D] = softmax(scale * q k^T, causal) v
+ *   row_max, row_sum  optional fp32 [B][Hq][Nq] (both or neither): row_max[i] = max_j scale*S_ij,
+ *            row_sum[i] = sum_j exp(scale*S_ij - row_max[i])
+ * All pointers are device memory, 16-byte aligned; products are exact fp16 x fp16, accumulation is fp32,
+ * probabilities enter the value product rounded to fp16.  No workspace.  geom.d_sub is not used but must
+ * be valid.  Errors: EINVAL, ELAUNCH.
+ */
+int antkv_prefill_attn(const antkv_geom* geom, const void* q, const void* k, const void* v, int64_t N, int64_t Nq,
+                       float scale, void* out, float* row_max, float* row_sum, void* stream);
 
 /*
  * Measurement aid, not part of the method: the next antkv_decode_attn call made from this host thread

@@ -10,6 +10,7 @@ from .binding import (
     Geometry,
     anchor_select,
     append_token,
+    prefill_attn,
     decode_attn,
     encode,
     gather_rows,
@@ -26,6 +27,7 @@ __all__ = [
     "Geometry",
     "anchor_select",
     "append_token",
+    "prefill_attn",
     "decode_attn",
     "encode",
     "gather_rows",

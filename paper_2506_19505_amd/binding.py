@@ -15,7 +15,7 @@ _lib = None
 EXPORTS = (
     "antkv_version", "antkv_strerror", "antkv_encode", "antkv_anchor_select_workspace", "antkv_anchor_select",
     "antkv_topk_workspace", "antkv_topk", "antkv_gather_rows", "antkv_decode_attn_workspace", "antkv_decode_attn",
-    "antkv_append_token", "antkv_profile_next_decode",
+    "antkv_append_token", "antkv_prefill_attn", "antkv_profile_next_decode",
 )
 
 
@@ -75,6 +75,8 @@ def load_library():
         lib.antkv_topk.argtypes = [vp, i64, i64, i64, vp, vp, sz, vp]
         lib.antkv_gather_rows.restype = ctypes.c_int
         lib.antkv_gather_rows.argtypes = [gp, vp, i64, vp, i64, vp, vp]
+        lib.antkv_prefill_attn.restype = ctypes.c_int
+        lib.antkv_prefill_attn.argtypes = [gp, vp, vp, vp, i64, i64, f32, vp, vp, vp, vp]
         lib.antkv_append_token.restype = ctypes.c_int
         lib.antkv_append_token.argtypes = [gp, vp, vp, i64, i64, vp, vp, vp, vp, i64, vp, vp, i64, vp, vp, i64, vp]
         lib.antkv_decode_attn_workspace.restype = sz
@@ -150,6 +152,24 @@ def topk(scores: torch.Tensor, k: int) -> torch.Tensor:
     rc = lib.antkv_topk(_p(scores), rows, N, k, _p(idx), _p(ws), ws.numel(), _stream(scores))
     _check(rc, "antkv_topk")
     return idx
+
+
+def prefill_attn(geom: Geometry, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, scale: float,
+                 want_stats: bool = True):
+    """antkv_prefill_attn: q fp16 [B,Hq,Nq,D], k / v fp16 [B,Hkv,N,D] -> (out fp16 [B,Hq,Nq,D], row_max, row_sum)."""
+    _need(q, torch.float16, "q")
+    _need(k, torch.float16, "k")
+    _need(v, torch.float16, "v")
+    B, Hq, Nq, D = q.shape
+    N = k.shape[2]
+    out = torch.empty((B, Hq, Nq, D), dtype=torch.float16, device=q.device)
+    row_max = torch.empty((B, Hq, Nq), dtype=torch.float32, device=q.device) if want_stats else None
+    row_sum = torch.empty((B, Hq, Nq), dtype=torch.float32, device=q.device) if want_stats else None
+    g = geom.c()
+    rc = load_library().antkv_prefill_attn(ctypes.byref(g), _p(q), _p(k), _p(v), N, Nq, float(scale), _p(out),
+                                           _p(row_max), _p(row_sum), _stream(q))
+    _check(rc, "antkv_prefill_attn")
+    return out, row_max, row_sum
 
 
 def anchor_select(geom: Geometry, q: torch.Tensor, k_fp16: torch.Tensor, scale: float, k: int,

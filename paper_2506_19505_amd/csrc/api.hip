@@ -107,6 +107,23 @@ size_t antkv_anchor_select_workspace(const antkv_geom* geom, int64_t N, int64_t 
     return sel_plan(g, N, Nq, k).total;
 }
 
+int antkv_prefill_attn(const antkv_geom* geom, const void* q, const void* k, const void* v, int64_t N, int64_t Nq,
+                       float scale, void* out, float* row_max, float* row_sum, void* stream)
+{
+    Geom g;
+    int rc = check_geom(geom, g);
+    if (rc) return rc;
+    if (N <= 0 || Nq <= 0 || Nq > N || N > 0x7fffffffLL) return ANTKV_EINVAL;
+    if ((row_max == nullptr) != (row_sum == nullptr)) return ANTKV_EINVAL;
+    if (g.B == 0) return ANTKV_OK;
+    if (!q || !k || !v || !out) return ANTKV_EINVAL;
+    if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(out, 16)) return ANTKV_EINVAL;
+    if (!(scale > 0.f)) return ANTKV_EINVAL;
+    const hipError_t e = launch_prefill_attn(g, (const half_t*)q, (const half_t*)k, (const half_t*)v, N, Nq, scale,
+                                             (half_t*)out, row_max, row_sum, (hipStream_t)stream);
+    return e == hipSuccess ? ANTKV_OK : ANTKV_ELAUNCH;
+}
+
 int antkv_anchor_select(const antkv_geom* geom, const void* q, const void* k_fp16, int64_t N, int64_t Nq, float scale,
                         int64_t k, const float* row_max, const float* row_sum, float* ans_k, float* ans_v,
                         int32_t* idx_k, int32_t* idx_v, void* workspace, size_t workspace_bytes, void* stream)

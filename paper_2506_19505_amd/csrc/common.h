@@ -80,6 +80,8 @@ hipError_t launch_append(const Geom& g, const half_t* k_new, const half_t* v_new
                          int32_t* idx_v, half_t* rows_v, int64_t k_v, int64_t N, int W, hipStream_t st);
 
 size_t anchor_score_workspace_bytes(const Geom& g, int64_t N, int64_t Nq);
+hipError_t launch_prefill_attn(const Geom& g, const half_t* q, const half_t* k, const half_t* v, int64_t N, int64_t Nq,
+                               float scale, half_t* out, float* row_max, float* row_sum, hipStream_t st);
 hipError_t launch_anchor_score(const Geom& g, const half_t* q, const half_t* k, int64_t N, int64_t Nq,
                                float scale, const float* row_max, const float* row_sum,
                                float* ans_k, float* ans_v, void* ws, hipStream_t st);
