@@ -208,7 +208,20 @@ def main() -> int:
             "anchor_select_TFLOPs": 2 * 2.0 * p.B * p.Hq * (p.N * (p.N + 1) / 2) * p.D / (ms_sel * 1e-3) / 1e12,
             "anchor_select_workload": f"cfg3: Nq = N = {p.N}, {p.Hq} query heads, top-{p.k} for K and V (two QK^T passes)",
         })
-        log(f"encode {result['extra']['encode_Mvec_per_s']:.0f} Mvec/s ({ms_enc * 1e3:.0f} us); anchor select {ms_sel:.2f} ms")
+        # prompt attention that hands its row statistics to the Anchor Score pass (Alg. 1)
+        p_out, p_rm, p_rs = antkv.prefill_attn(pg, pqd, pkd, pvd, p.scale)
+        ms_pa = timed(3, lambda i: antkv.prefill_attn(pg, pqd, pkd, pvd, p.scale))
+        antkv.anchor_select(pg, pqd, pkd, p.scale, p.k, row_max=p_rm, row_sum=p_rs, want_scores=False)
+        ms_sel2 = timed(3, lambda i: antkv.anchor_select(pg, pqd, pkd, p.scale, p.k, row_max=p_rm, row_sum=p_rs,
+                                                         want_scores=False))
+        result["extra"].update({
+            "prefill_attn_ms": ms_pa,
+            "prefill_attn_TFLOPs": 2 * 2.0 * p.B * p.Hq * (p.N * (p.N + 1) / 2) * p.D / (ms_pa * 1e-3) / 1e12,
+            "anchor_select_given_row_stats_ms": ms_sel2,
+        })
+        del p_out, p_rm, p_rs
+        log(f"encode {result['extra']['encode_Mvec_per_s']:.0f} Mvec/s ({ms_enc * 1e3:.0f} us); anchor select {ms_sel:.2f} ms; "
+            f"prefill attention {ms_pa:.2f} ms, anchor select after it {ms_sel2:.2f} ms")
         del pkd, pvd, pqd
         torch.cuda.empty_cache()
 

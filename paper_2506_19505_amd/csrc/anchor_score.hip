@@ -34,6 +34,8 @@ __device__ __forceinline__ void load_tile(Tile128& t, const half_t* row_ptr, int
 {
 #pragma unroll
     for (int s = 0; s < 8; ++s) t.v[s] = *(const half8_t*)(row_ptr + 16 * s + 8 * kh);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) pin(t.v[s]);
 }
 
 // A 32-row x 128-channel tile shared by the waves of a workgroup sits in LDS with rows padded to 136 halfs
@@ -107,6 +109,7 @@ __global__ __launch_bounds__(kAsThreads) void ans_row_stats(
         const int h = g * G + (hh < G ? hh : G - 1);
         Tile128 tq;
         load_tile(tq, q + (((int64_t)b * Hq + h) * Nq + qrow) * kD, kh);
+        wait_all_loads();
         float m_run = kNegBig, l_run = 0.f;
         int buf = 0;
         if (k_lo < k_end) *(uint4_t*)(&s_k[0][srow * kRowPad + 8 * schunk]) = fetch(k_lo);
@@ -216,6 +219,7 @@ __global__ __launch_bounds__(kAsThreads) void ans_col_reduce(
     const int64_t krow = key < N ? key : N - 1;
     Tile128 tk;
     load_tile(tk, k + (((int64_t)b * Hkv + g) * N + krow) * kD, kh);
+    wait_all_loads();
     // first query tile that can see a key of this block:  N - Nq + i >= kblk0
     int64_t i_first = kblk0 - (N - Nq);
     if (i_first < 0) i_first = 0;

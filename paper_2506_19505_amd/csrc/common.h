@@ -51,6 +51,22 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Wait until every global load issued so far has landed.  Placed after the loads of a loop-invariant register
+// tile: the compiler otherwise keeps those loads "possibly pending" across the loop's back edge and makes the
+// loop body wait for its own prefetches of the next tile before it may touch the invariant registers.
+// (pin() on the loaded registers first keeps the compiler from moving their loads below the wait)
+template <typename T>
+__device__ __forceinline__ void pin(T& x)
+{
+    asm volatile("" : "+v"(x));
+}
+__device__ __forceinline__ void wait_all_loads()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), other counters untouched
+    asm volatile("" ::: "memory");
+}
+
 // order-preserving map float -> uint32 (larger float <=> larger key), any finite sign
 __device__ __forceinline__ uint32_t float_key(float f)
 {

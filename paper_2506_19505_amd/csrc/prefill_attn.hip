@@ -65,6 +65,9 @@ __global__ __launch_bounds__(kPaThreads) void prefill_attn_kernel(
             const half_t* qp = q + (((int64_t)b * Hq + h) * Nq + qrow) * kD;
 #pragma unroll
             for (int s = 0; s < 8; ++s) tq[s] = *(const half8_t*)(qp + 16 * s + 8 * kh);
+#pragma unroll
+            for (int s = 0; s < 8; ++s) pin(tq[s]);
+            wait_all_loads();
         }
         float16_t o[4];
 #pragma unroll
