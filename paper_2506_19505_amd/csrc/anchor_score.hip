@@ -201,20 +201,22 @@ __global__ __launch_bounds__(256) void ans_finalize_stats(
 
 // -------------------------------------------------------------------------------------------------
 // phase 2: column reduction.  grid = (key blocks of 256, B*Hkv); each of the 8 waves owns 32 keys.
+// Software-pipelined by one step: while the VALU rebuilds and reduces the probabilities of step t, the
+// matrix pipe already computes the scores of step t+1, so the staged Q tiles run one step ahead of
+// their row statistics (rings of three).
 // -------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kAsThreads) void ans_col_reduce(
+__global__ __launch_bounds__(kAsThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void ans_col_reduce(
     const half_t* __restrict__ q, const half_t* __restrict__ k, int64_t N, int64_t Nq, float c1,
     const float* __restrict__ c_row, const float* __restrict__ nq_row, float* __restrict__ ans_k,
     float* __restrict__ ans_v, int Hq, int Hkv, int G)
 {
-    __shared__ __attribute__((aligned(16))) half_t s_q[2][kTileHalfs];   // query tiles, double-buffered
-    __shared__ __attribute__((aligned(16))) float s_c[2][32], s_n[2][32];  // their row statistics
+    __shared__ __attribute__((aligned(16))) half_t s_q[3][kTileHalfs];     // query tiles of steps t+1, t+2 (and t, spent)
+    __shared__ __attribute__((aligned(16))) float s_c[3][32], s_n[3][32];  // row statistics of steps t, t+1, t+2
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, kh = lane >> 5;
     const int b = blockIdx.y / Hkv, g = blockIdx.y % Hkv;
     const int64_t kblk0 = (int64_t)blockIdx.x * 256;
     const int64_t k0 = kblk0 + wave * 32;                       // first key of this wave
-    const bool wave_on = k0 < N;
     const int64_t key = k0 + n;
     const int64_t krow = key < N ? key : N - 1;
     Tile128 tk;
@@ -239,65 +241,81 @@ __global__ __launch_bounds__(kAsThreads) void ans_col_reduce(
         }
         return *(const uint4_t*)(q + (rbase + qrow) * kD + 8 * schunk);
     };
-    double sum_v = 0.0, sum_k = 0.0;
-    int buf = 0;
-    {
+    auto stage = [&](int slot, const uint4_t& d, float c_o, float n_o) {
+        *(uint4_t*)(&s_q[slot][srow * kRowPad + 8 * schunk]) = d;
+        if (tid < 32) { s_c[slot][tid] = c_o; s_n[slot][tid] = n_o; }
+    };
+    int qt_f = 0, hh_f = 0;                                      // next step to fetch
+    for (int i = 0; i < 2 && i < n_steps; ++i) {
         float c_o = 0.f, n_o = 0.f;
-        if (n_steps > 0) {
-            *(uint4_t*)(&s_q[0][srow * kRowPad + 8 * schunk]) = fetch(0, 0, c_o, n_o);
-            if (tid < 32) { s_c[0][tid] = c_o; s_n[0][tid] = n_o; }
-        }
+        const uint4_t d = fetch(hh_f, qt_f, c_o, n_o);
+        stage(i, d, c_o, n_o);
+        if (++qt_f == n_qt) { qt_f = 0; ++hh_f; }
     }
     __syncthreads();
-    int qt = 0, hh = 0;                                          // current step
+    float16_t acc_cur;
+    if (n_steps > 0) acc_cur = tile_dot_lds_a(s_q[0], tk, n, kh);   // rows = queries, cols = keys
+    double sum_v = 0.0, sum_k = 0.0;
+    int slot = 0, qt = 0;                                        // ring slot and query tile of the current step
     const int rel0 = (int)(N - Nq + i_first - k0);               // position of tile 0's first query minus this wave's first key
     for (int step = 0; step < n_steps; ++step) {
-        const bool more = step + 1 < n_steps;
-        int qt_n = qt + 1, hh_n = hh;
-        if (qt_n == n_qt) { qt_n = 0; ++hh_n; }
+        const bool more = step + 2 < n_steps;
         uint4_t nxt = {0u, 0u, 0u, 0u};
         float c_o = 0.f, n_o = 0.f;
-        if (more) nxt = fetch(hh_n, qt_n, c_o, n_o);
+        if (more) nxt = fetch(hh_f, qt_f, c_o, n_o);
+        const int s1 = slot == 2 ? 0 : slot + 1, s2 = s1 == 2 ? 0 : s1 + 1;
         const int rel = rel0 + 32 * qt;                          // (position of the tile's first query) - k0
-        // tiles whose last query cannot see this wave's first key contribute nothing
-        if (wave_on && rel + 31 >= 0) {
-            const float16_t acc = tile_dot_lds_a(s_q[buf], tk, n, kh);   // rows = queries, cols = keys
-            float pv = 0.f, pk = 0.f;
-            const int lim = n - rel;                             // tile row r sees this lane's key iff r >= lim
-            auto reduce_tile = [&](auto masked) {
+        const int lim = n - rel;                                 // tile row r sees this lane's key iff r >= lim
+        float pv = 0.f, pk = 0.f;
+        float16_t acc_next;
 #pragma unroll
-                for (int qd = 0; qd < 4; ++qd) {
-                    const int rl = 8 * qd + 4 * kh;              // tile rows rl .. rl+3 live in acc[4qd .. 4qd+3]
-                    const float4_t c4 = *(const float4_t*)(&s_c[buf][rl]);
-                    const float4_t n4 = *(const float4_t*)(&s_n[buf][rl]);
+        for (int r = 0; r < 16; ++r) acc_next[r] = 0.f;
+        // scores of step t+1 (slot s1; past the last step the slot holds stale data and the result is dropped)
+        // interleaved in program order with the reduction of step t, two elements per MFMA
+        auto body = [&](auto masked) {
+            float4_t c4 = {0.f, 0.f, 0.f, 0.f}, n4 = {0.f, 0.f, 0.f, 0.f};
+            const half_t* ap = &s_q[s1][n * kRowPad + 8 * kh];
+            half8_t a_op[8];
+            a_op[0] = *(const half8_t*)(ap);
+            a_op[1] = *(const half8_t*)(ap + 16);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float arg = fmaf(acc[4 * qd + e], c1, -c4[e]);
-                        if (decltype(masked)::value && rl + e < lim) arg = -3.0e38f;   // causal mask
-                        const float a = fast_exp2(arg);
-                        const float t = a * n4[e];
-                        pv += a;
-                        pk += fmaf(-a, t, t);
-                    }
+            for (int s = 0; s < 8; ++s) {
+                if (s + 2 < 8) a_op[s + 2] = *(const half8_t*)(ap + 16 * (s + 2));   // operand reads run two MFMAs ahead
+                acc_next = __builtin_amdgcn_mfma_f32_32x32x16_f16(a_op[s], tk.v[s], acc_next, 0, 0, 0);
+                const int qd = s >> 1;
+                const int rl = 8 * qd + 4 * kh;                  // tile rows rl .. rl+3 live in acc[4qd .. 4qd+3]
+                if ((s & 1) == 0) {
+                    c4 = *(const float4_t*)(&s_c[slot][rl]);
+                    n4 = *(const float4_t*)(&s_n[slot][rl]);
                 }
-            };
-            // only tiles on the diagonal (some query cannot see some key) pay for the mask; the branch is uniform
-            if (__builtin_expect(rel < 31, 0)) reduce_tile(std::true_type{});
-            else reduce_tile(std::false_type{});
-            sum_v += (double)pv;
-            sum_k += (double)pk;
-        }
+#pragma unroll
+                for (int e2 = 0; e2 < 2; ++e2) {
+                    const int e = 2 * (s & 1) + e2;
+                    float arg = fmaf(acc_cur[4 * qd + e], c1, -c4[e]);
+                    if (decltype(masked)::value && rl + e < lim) arg = -3.0e38f;   // causal mask
+                    const float a_ij = fast_exp2(arg);
+                    pv += a_ij;
+                    pk = fmaf(a_ij, fmaf(-a_ij, n4[e], n4[e]), pk);               // a (1 - a) ||q||
+                }
+            }
+        };
+        // only tiles on or above the diagonal (some query cannot see some key) pay for the mask; the branch is uniform
+        if (__builtin_expect(rel < 31, 0)) body(std::true_type{});
+        else body(std::false_type{});
+        sum_v += (double)pv;
+        sum_k += (double)pk;
         if (more) {
-            *(uint4_t*)(&s_q[buf ^ 1][srow * kRowPad + 8 * schunk]) = nxt;
-            if (tid < 32) { s_c[buf ^ 1][tid] = c_o; s_n[buf ^ 1][tid] = n_o; }
+            stage(s2, nxt, c_o, n_o);
+            if (++qt_f == n_qt) { qt_f = 0; ++hh_f; }
         }
         __syncthreads();
-        buf ^= 1;
-        qt = qt_n; hh = hh_n;
+        acc_cur = acc_next;
+        slot = s1;
+        if (++qt == n_qt) qt = 0;
     }
     // lanes l and l+32 hold complementary query rows of the same key
     const double ov = __shfl_xor(sum_v, 32, 64), ok = __shfl_xor(sum_k, 32, 64);
-    if (wave_on && kh == 0 && key < N) {
+    if (kh == 0 && key < N) {
         const int64_t o = ((int64_t)b * Hkv + g) * N + key;
         ans_v[o] = (float)(sum_v + ov);
         ans_k[o] = (float)(sum_k + ok);
