@@ -72,7 +72,7 @@ __device__ __forceinline__ float16_t tile_dot(const Tile128& a, const Tile128& b
 // 4 heads of the group (G <= 4 per pass; larger groups loop) x 2 query tiles of 32.
 // part: [B][Hq][Nq][KS][2] = (max in log2 units, sum of exp2)
 // -------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kAsThreads) void ans_row_stats(
+__global__ __launch_bounds__(kAsThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void ans_row_stats(
     const half_t* __restrict__ q, const half_t* __restrict__ k, int64_t N, int64_t Nq, float c1,
     float* __restrict__ part, int Hq, int Hkv, int G, int KS, int64_t keys_per_split)
 {
@@ -111,15 +111,21 @@ __global__ __launch_bounds__(kAsThreads) void ans_row_stats(
         load_tile(tq, q + (((int64_t)b * Hq + h) * Nq + qrow) * kD, kh);
         wait_all_loads();
         float m_run = kNegBig, l_run = 0.f;
-        int buf = 0;
+        // One-step software pipeline: the scores of tile t+1 are computed while the statistics of tile t are
+        // updated, so LDS holds tiles t+1 (read) and t+2 (being written); tile t's buffer is the one rewritten.
         if (k_lo < k_end) *(uint4_t*)(&s_k[0][srow * kRowPad + 8 * schunk]) = fetch(k_lo);
+        if (k_lo + 32 < k_end) *(uint4_t*)(&s_k[1][srow * kRowPad + 8 * schunk]) = fetch(k_lo + 32);
         __syncthreads();
+        float16_t acc_cur;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_cur[r] = 0.f;
+        if (head_on && k_lo < k_hi) acc_cur = tile_dot_lds_a(s_k[0], tq, n, kh);   // rows = keys, cols = queries
+        int buf = 0;                                                // buffer of tile t
         for (int64_t kt = k_lo; kt < k_end; kt += 32) {
-            const bool more = kt + 32 < k_end;
+            const bool more = kt + 64 < k_end;
             uint4_t nxt = {0u, 0u, 0u, 0u};
-            if (more) nxt = fetch(kt + 32);
+            if (more) nxt = fetch(kt + 64);
             if (head_on && kt < k_hi) {
-                const float16_t acc = tile_dot_lds_a(s_k[buf], tq, n, kh);   // rows = keys, cols = queries
                 // Exponents are taken against this lane's reference m_run, which only moves when a tile brings
                 // a score more than 64 (log2 units) above it, or when the lane has seen nothing yet: the common
                 // tile costs one fma, one exp2, one add and one max per element.
@@ -127,23 +133,36 @@ __global__ __launch_bounds__(kAsThreads) void ans_row_stats(
                 const float base = init ? m_run : 0.f;
                 float arg[16];
                 float mx = kNegBig, sum = 0.f;
-                if (kt + 31 <= N - Nq + q0 && kt + 31 < k_hi) {    // every key of the tile is visible to every query
+                float16_t acc_next;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) arg[r] = fmaf(acc[r], c1, -base);
-                } else {
-                    const int lim_q = (int)(qpos - kt), lim_k = (int)(k_hi - kt);   // visible: offset <= lim_q, < lim_k
+                for (int r = 0; r < 16; ++r) acc_next[r] = 0.f;
+                const int lim_q = (int)(qpos - kt), lim_k = (int)(k_hi - kt);   // visible: offset <= lim_q, < lim_k
+                auto body = [&](auto masked) {
+                    const half_t* ap = &s_k[buf ^ 1][n * kRowPad + 8 * kh];
+                    half8_t a_op[8];
+                    a_op[0] = *(const half8_t*)(ap);
+                    a_op[1] = *(const half8_t*)(ap + 16);
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int off = 8 * (r >> 2) + 4 * kh + (r & 3);
-                        const bool vis = (off <= lim_q) && (off < lim_k);
-                        arg[r] = vis ? fmaf(acc[r], c1, -base) : kNegBig;
+                    for (int s = 0; s < 8; ++s) {
+                        if (s + 2 < 8) a_op[s + 2] = *(const half8_t*)(ap + 16 * (s + 2));
+                        acc_next = __builtin_amdgcn_mfma_f32_32x32x16_f16(a_op[s], tq.v[s], acc_next, 0, 0, 0);
+#pragma unroll
+                        for (int e2 = 0; e2 < 2; ++e2) {
+                            const int r = 2 * s + e2;
+                            float x = fmaf(acc_cur[r], c1, -base);
+                            if (decltype(masked)::value) {
+                                const int off = 8 * (r >> 2) + 4 * kh + (r & 3);
+                                if (!((off <= lim_q) && (off < lim_k))) x = kNegBig;
+                            }
+                            arg[r] = x;
+                            mx = fmaxf(mx, x);
+                            sum += fast_exp2(x);
+                        }
                     }
-                }
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    mx = fmaxf(mx, arg[r]);
-                    sum += fast_exp2(arg[r]);
-                }
+                };
+                // every key of the tile is visible to every query of the wave: no mask
+                if (kt + 31 <= N - Nq + q0 && kt + 31 < k_hi) body(std::false_type{});
+                else body(std::true_type{});
                 if (init && mx <= 64.f) {
                     l_run += sum;
                 } else if (mx > 0.5f * kNegBig) {                  // the tile has a visible element: move the reference
@@ -153,8 +172,9 @@ __global__ __launch_bounds__(kAsThreads) void ans_row_stats(
                     l_run = (init ? l_run * fast_exp2(-mx) : 0.f) + sum2;
                     m_run = base + mx;
                 }
+                acc_cur = acc_next;
             }
-            if (more) *(uint4_t*)(&s_k[buf ^ 1][srow * kRowPad + 8 * schunk]) = nxt;
+            if (more) *(uint4_t*)(&s_k[buf][srow * kRowPad + 8 * schunk]) = nxt;
             __syncthreads();
             buf ^= 1;
         }
