@@ -70,10 +70,10 @@ def test_anchor_select_long_context_window(oracle):
     _run(oracle, 25, 1, 8, 2, 131072, 32, anchor_count(131072))
 
 
-def test_anchor_select_full_prefill_invariants():
-    """Config 3 at full size (Nq = N = 32768, 32 heads): too large for the oracle inside a test, so check what
-    holds at any size: rows of A sum to one, AnS(K) within its bound, ascending unique index sets that pick the
-    largest scores."""
+def test_anchor_select_full_prefill_invariants(oracle):
+    """Config 3 at full size (Nq = N = 32768, 32 heads).  All heads: what holds at any size (rows of A sum to one,
+    AnS(K) within its bound, ascending unique index sets that pick the largest scores).  One KV head with its four
+    query heads: every score and both index sets against the oracle (the oracle needs ~10-20 s for one head)."""
     w = CONFIGS["cfg3"]
     q, kk, _ = make_qkv(w.seed, w.B, w.Hq, w.Hkv, w.N, w.N, w.D, want_v=False)
     geom = antkv.Geometry(w.B, w.Hq, w.Hkv, w.d_sub)
@@ -89,3 +89,13 @@ def test_anchor_select_full_prefill_invariants():
                 assert np.all(np.diff(sel) > 0) and sel.min() >= 0 and sel.max() < w.N
                 rest = np.delete(sc[b, g], sel)
                 assert sc[b, g][sel].min() >= rest.max()
+    g = 5                                                      # a KV head in the middle: non-zero head offsets
+    print("oracle on one KV head of cfg3 ...", flush=True)
+    ok, ov = oracle.anchor_score(q[:, g * w.G:(g + 1) * w.G], kk[:, g:g + 1], w.scale)
+    np.testing.assert_allclose(gv[:, g], ov[:, 0], rtol=3e-5, atol=1e-9)
+    np.testing.assert_allclose(gk[:, g], ok[:, 0], rtol=3e-5, atol=1e-9)
+    soft = 0
+    for got, score in ((idx_k, ok), (idx_v, ov)):
+        want, margin = oracle.topk(score, w.k, want_margin=True)
+        soft += check_index_sets(got.cpu().numpy()[:, g:g + 1], want, margin)
+    print(f"cfg3, KV head {g}: scores within 3e-5, near-tie index disagreements {soft}")
