@@ -13,6 +13,8 @@
 // tile brings a score more than kPMax (log2 units) above it, which keeps fp16 P below 2^kPMax.
 #include "common.h"
 
+#include <type_traits>
+
 namespace antkv {
 
 namespace {
@@ -36,7 +38,8 @@ __global__ __launch_bounds__(kPaThreads) void prefill_attn_kernel(
 {
     __shared__ __attribute__((aligned(16))) half_t s_k[2][32 * kKRow];
     __shared__ __attribute__((aligned(16))) half_t s_v[2][32 * kVRow];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // scalar, so that per-wave conditions are scalar branches
     const int n = lane & 31, kh = lane >> 5;
     const int64_t qblk = (int64_t)gridDim.x - 1 - blockIdx.x;      // longest rows first
     const int b = blockIdx.y / Hkv, g = blockIdx.y % Hkv;
@@ -103,20 +106,20 @@ __global__ __launch_bounds__(kPaThreads) void prefill_attn_kernel(
                 const bool init = m_ref > kNegBig;
                 const float base = init ? m_ref : 0.f;
                 float p[16];
-                if (kt + 31 <= N - Nq + q0) {                      // the whole tile is visible to every query of the wave
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) p[r] = fmaf(acc[r], c1, -base);
-                } else {
-                    const int lim = (int)(qpos - kt);              // key offset <= lim is visible
+                float mx = kNegBig;
+                const int lim = (int)(qpos - kt);                  // key offset <= lim is visible
+                auto scores = [&](auto masked) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const int off = 8 * (r >> 2) + 4 * kh + (r & 3);
-                        p[r] = off <= lim ? fmaf(acc[r], c1, -base) : kNegBig;
+                        float x = fmaf(acc[r], c1, -base);
+                        if (decltype(masked)::value && 8 * (r >> 2) + 4 * kh + (r & 3) > lim) x = kNegBig;
+                        p[r] = x;
+                        mx = fmaxf(mx, x);
                     }
-                }
-                float mx = kNegBig;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, p[r]);
+                };
+                // only tiles on the causal diagonal pay for the mask; the branch is uniform
+                if (__builtin_expect(kt + 31 <= N - Nq + q0, 1)) scores(std::false_type{});
+                else scores(std::true_type{});
                 mx = fmaxf(mx, __shfl_xor(mx, 32, 64));            // the two key halves of a query agree on the reference
                 const bool seen = mx > 0.5f * kNegBig;
                 if (seen) m_true = fmaxf(m_true, base + mx);
