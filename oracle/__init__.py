@@ -13,6 +13,8 @@ arrays into it and adds the top-k step, which is a stable library sort.
                                 decode-time Anchor Score (Sec. 3.2, last paragraph)
   append_token(...)             decode append with an FP16 sliding window (Sec. 3.2, last
                                 paragraph; window of 32 in Sec. 4)
+  kmeans_update / kmeans_step   one iteration of the offline token-weighted k-means (Sec. 3.1, "Offline
+                                Token-Aware Centroids Learning"): nearest-centroid assignment, then weighted means
   prefill_attn(q, k, v, scale)  causal Attn (Sec. 2.1) over the prompt with the softmax row statistics
                                 that the Anchor Score pass reuses (Alg. 1, first step)
 """
@@ -225,3 +227,41 @@ def prefill_attn(q, k, v, scale: float):
             out[b, h] = (e / l[:, None]) @ v64[b, h // G]
             row_max[b, h], row_sum[b, h] = m, l
     return out, row_max, row_sum
+
+
+def kmeans_update(x, w, codes, cb_old):
+    """Centroid update of token-weighted k-means (paper Sec. 3.1: clustering of the sub-vectors with one weight per
+    token, the weight standing for that token's error-propagation factor).
+
+    x [B,Hkv,n,D], w [B,Hkv,n] >= 0, codes int [B,Hkv,n,M], cb_old [Hkv,M,C,d].  Per (KV head, sub-space):
+    centroid c becomes sum_j w_j x_j / sum_j w_j over the tokens j (of all B sequences) assigned to it; a centroid
+    whose assigned weight is zero keeps its old value.  Returns (cb_new fp64 [Hkv,M,C,d], wsum fp64 [Hkv,M,C],
+    objective fp64 [Hkv,M] = sum_j w_j ||x_j - cb_old[code_j]||^2, the weighted distortion of the assignment).
+    """
+    x64, w64, cb64 = np.asarray(x).astype(np.float64), np.asarray(w).astype(np.float64), np.asarray(cb_old).astype(np.float64)
+    codes = np.asarray(codes).astype(np.int64)
+    Hkv, M, C, d = cb64.shape
+    cb_new = cb64.copy()
+    wsum = np.zeros((Hkv, M, C))
+    objective = np.zeros((Hkv, M))
+    for g in range(Hkv):
+        ws = w64[:, g].reshape(-1)
+        for m in range(M):
+            xs = x64[:, g, :, m * d:(m + 1) * d].reshape(-1, d)
+            cs = codes[:, g, :, m].reshape(-1)
+            sums = np.zeros((C, d))
+            np.add.at(sums, cs, ws[:, None] * xs)
+            tot = np.bincount(cs, weights=ws, minlength=C)
+            hit = tot > 0
+            cb_new[g, m, hit] = sums[hit] / tot[hit, None]
+            wsum[g, m] = tot
+            objective[g, m] = (ws * ((xs - cb64[g, m, cs]) ** 2).sum(axis=1)).sum()
+    return cb_new, wsum, objective
+
+
+def kmeans_step(x, w, cb):
+    """One Lloyd iteration of the token-weighted k-means: assign every sub-vector to its nearest centroid (the online
+    encode, Sec. 3.1), then kmeans_update.  Returns (cb_new, codes, wsum, objective)."""
+    codes = encode(x, cb)
+    cb_new, wsum, objective = kmeans_update(x, w, codes, cb)
+    return cb_new, codes, wsum, objective
