@@ -228,6 +228,14 @@ def main() -> int:
             "anchor_select_TFLOPs": 2 * 2.0 * p.B * p.Hq * (p.N * (p.N + 1) / 2) * p.D / (ms_sel * 1e-3) / 1e12,
             "anchor_select_workload": f"cfg3: Nq = N = {p.N}, {p.Hq} query heads, top-{p.k} for K and V (two QK^T passes)",
         })
+        # one iteration of the offline token-weighted k-means on the same K rows (assignment + weighted update)
+        km_w = torch.rand((p.B, p.Hkv, p.N), dtype=torch.float32, device=devc)
+        km = lambda i: antkv.kmeans_step(pg, pkd, km_w, pcbk_d)
+        settle(km, 0.1)
+        ms_km = timed(50, km)
+        result["extra"].update({"kmeans_step_us": ms_km * 1e3,
+                                "kmeans_step_Mvec_per_s": p.B * p.Hkv * p.N / (ms_km * 1e-3) / 1e6})
+        del km_w
         # prompt attention that hands its row statistics to the Anchor Score pass (Alg. 1)
         p_out, p_rm, p_rs = antkv.prefill_attn(pg, pqd, pkd, pvd, p.scale)
         ms_pa = timed(3, lambda i: antkv.prefill_attn(pg, pqd, pkd, pvd, p.scale))
@@ -241,7 +249,7 @@ def main() -> int:
         })
         del p_out, p_rm, p_rs
         log(f"encode {result['extra']['encode_Mvec_per_s']:.0f} Mvec/s ({ms_enc * 1e3:.0f} us); anchor select {ms_sel:.2f} ms; "
-            f"prefill attention {ms_pa:.2f} ms, anchor select after it {ms_sel2:.2f} ms")
+            f"prefill attention {ms_pa:.2f} ms, anchor select after it {ms_sel2:.2f} ms; k-means iteration {ms_km * 1e3:.0f} us")
         del pkd, pvd, pqd
         torch.cuda.empty_cache()
 

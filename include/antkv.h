@@ -6,6 +6,7 @@
  * in FP16.  This library holds the online stage (paper Sec. 3, Fig. 2(b)):
  *
  *   antkv_encode         VQ assignment of K / V sub-vectors            (Sec. 3.1)
+ *   antkv_kmeans_step    one iteration of the offline token-weighted k-means (Sec. 3.1)
  *   antkv_prefill_attn   causal prompt attention + softmax row stats   (Sec. 2.1; Sec. 3.3, Alg. 1 first step)
  *   antkv_anchor_select  Anchor Score of every token + top-k select    (Sec. 3.2, Eq. (4); Sec. 3.3, Alg. 1)
  *   antkv_topk           the selection step alone
@@ -186,6 +187,29 @@ int antkv_append_token(const antkv_geom* geom, const void* k_new, const void* v_
  */
 int antkv_prefill_attn(const antkv_geom* geom, const void* q, const void* k, const void* v, int64_t N, int64_t Nq,
                        float scale, void* out, float* row_max, float* row_sum, void* stream);
+
+/*
+ * One iteration of the offline token-weighted k-means that learns a codebook (Sec. 3.1, "Offline Token-Aware
+ * Centroids Learning"): every sub-vector of x is assigned to its nearest centroid of codebook_in (the same rule as
+ * antkv_encode), then each centroid becomes the weighted mean of the sub-vectors assigned to it, over all B
+ * sequences, with one weight per token (the paper uses the token's error-propagation factor; any w >= 0 works).
+ * A centroid that no weight was assigned to keeps its old value.
+ *
+ *   x            fp16 [B][Hkv][n_tok][D] calibration rows of K (or V), contiguous, 16-byte aligned
+ *   w            fp32 [B][Hkv][n_tok], >= 0
+ *   codebook_in  fp16 [Hkv][M][256][d_sub];  codebook_out the same shape, a different buffer
+ *   codes        uint8 [B][Hkv][n_tok][M], written: the assignment that was used
+ *   wsum         optional fp32 [Hkv][M][256]: weight assigned to each centroid
+ *   objective    optional fp64 [Hkv][M]: sum_j w_j ||x_j - codebook_in[code_j]||^2 per sub-space, i.e. the weighted
+ *                distortion after the assignment and before the update
+ *   workspace    antkv_kmeans_step_workspace(geom) bytes, 256-byte aligned; may hold any bytes on entry
+ * Sums are fp32 and added with atomics: the new centroids agree to fp32 rounding from run to run, not bit for bit.
+ * n_tok == 0 copies the codebook.  Errors: EINVAL, EUNSUPPORTED, EWORKSPACE, ELAUNCH.
+ */
+size_t antkv_kmeans_step_workspace(const antkv_geom* geom);
+int antkv_kmeans_step(const antkv_geom* geom, const void* x, const float* w, int64_t n_tok, const void* codebook_in,
+                      void* codebook_out, uint8_t* codes, float* wsum, double* objective, void* workspace,
+                      size_t workspace_bytes, void* stream);
 
 /*
  * Measurement aid, not part of the method: the next antkv_decode_attn call made from this host thread

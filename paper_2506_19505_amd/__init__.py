@@ -11,6 +11,7 @@ from .binding import (
     anchor_select,
     append_token,
     prefill_attn,
+    kmeans_step,
     decode_attn,
     encode,
     gather_rows,
@@ -28,6 +29,7 @@ __all__ = [
     "anchor_select",
     "append_token",
     "prefill_attn",
+    "kmeans_step",
     "decode_attn",
     "encode",
     "gather_rows",

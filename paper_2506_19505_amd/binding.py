@@ -15,7 +15,7 @@ _lib = None
 EXPORTS = (
     "antkv_version", "antkv_strerror", "antkv_encode", "antkv_anchor_select_workspace", "antkv_anchor_select",
     "antkv_topk_workspace", "antkv_topk", "antkv_gather_rows", "antkv_decode_attn_workspace", "antkv_decode_attn",
-    "antkv_append_token", "antkv_prefill_attn", "antkv_profile_next_decode",
+    "antkv_append_token", "antkv_prefill_attn", "antkv_kmeans_step_workspace", "antkv_kmeans_step", "antkv_profile_next_decode",
 )
 
 
@@ -75,6 +75,10 @@ def load_library():
         lib.antkv_topk.argtypes = [vp, i64, i64, i64, vp, vp, sz, vp]
         lib.antkv_gather_rows.restype = ctypes.c_int
         lib.antkv_gather_rows.argtypes = [gp, vp, i64, vp, i64, vp, vp]
+        lib.antkv_kmeans_step_workspace.restype = sz
+        lib.antkv_kmeans_step_workspace.argtypes = [gp]
+        lib.antkv_kmeans_step.restype = ctypes.c_int
+        lib.antkv_kmeans_step.argtypes = [gp, vp, vp, i64, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.antkv_prefill_attn.restype = ctypes.c_int
         lib.antkv_prefill_attn.argtypes = [gp, vp, vp, vp, i64, i64, f32, vp, vp, vp, vp]
         lib.antkv_append_token.restype = ctypes.c_int
@@ -152,6 +156,27 @@ def topk(scores: torch.Tensor, k: int) -> torch.Tensor:
     rc = lib.antkv_topk(_p(scores), rows, N, k, _p(idx), _p(ws), ws.numel(), _stream(scores))
     _check(rc, "antkv_topk")
     return idx
+
+
+def kmeans_step(geom: Geometry, x: torch.Tensor, w: torch.Tensor, codebook: torch.Tensor):
+    """antkv_kmeans_step: x fp16 [B,Hkv,n,D], w fp32 [B,Hkv,n], codebook fp16 [Hkv,M,256,d] ->
+    (new codebook fp16, codes uint8 [B,Hkv,n,M], wsum fp32 [Hkv,M,256], objective fp64 [Hkv,M])."""
+    _need(x, torch.float16, "x")
+    _need(w, torch.float32, "w")
+    _need(codebook, torch.float16, "codebook")
+    B, Hkv, n, _ = x.shape
+    dev = x.device
+    out = torch.empty_like(codebook)
+    codes = torch.empty((B, Hkv, n, geom.M), dtype=torch.uint8, device=dev)
+    wsum = torch.empty((Hkv, geom.M, 256), dtype=torch.float32, device=dev)
+    objective = torch.empty((Hkv, geom.M), dtype=torch.float64, device=dev)
+    lib = load_library()
+    g = geom.c()
+    ws = _workspace(lib.antkv_kmeans_step_workspace(ctypes.byref(g)), dev)
+    rc = lib.antkv_kmeans_step(ctypes.byref(g), _p(x), _p(w), n, _p(codebook), _p(out), _p(codes), _p(wsum),
+                               _p(objective), _p(ws), ws.numel(), _stream(x))
+    _check(rc, "antkv_kmeans_step")
+    return out, codes, wsum, objective
 
 
 def prefill_attn(geom: Geometry, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, scale: float,

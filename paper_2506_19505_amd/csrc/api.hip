@@ -107,6 +107,38 @@ size_t antkv_anchor_select_workspace(const antkv_geom* geom, int64_t N, int64_t 
     return sel_plan(g, N, Nq, k).total;
 }
 
+size_t antkv_kmeans_step_workspace(const antkv_geom* geom)
+{
+    Geom g;
+    if (check_geom(geom, g)) return 0;
+    return kmeans_workspace_bytes(g);
+}
+
+int antkv_kmeans_step(const antkv_geom* geom, const void* x, const float* w, int64_t n_tok, const void* codebook_in,
+                      void* codebook_out, uint8_t* codes, float* wsum, double* objective, void* workspace,
+                      size_t workspace_bytes, void* stream)
+{
+    Geom g;
+    int rc = check_geom(geom, g);
+    if (rc) return rc;
+    if (n_tok < 0 || n_tok > 0x7fffffffLL) return ANTKV_EINVAL;
+    if (!codebook_in || !codebook_out || codebook_in == codebook_out) return ANTKV_EINVAL;
+    if (misaligned(codebook_in, 16) || misaligned(codebook_out, 16) || misaligned(objective, 8)) return ANTKV_EINVAL;
+    const bool have_tokens = n_tok > 0 && g.B > 0;
+    if (have_tokens && (!x || !w || !codes || misaligned(x, 16) || misaligned(codes, 16) || misaligned(w, 4)))
+        return ANTKV_EINVAL;
+    if (!workspace || misaligned(workspace, 256) || workspace_bytes < kmeans_workspace_bytes(g)) return ANTKV_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (have_tokens) {
+        const hipError_t e = launch_encode(g, (const half_t*)x, (int64_t)g.Hkv * n_tok * kD, n_tok * kD, kD, n_tok,
+                                           (const half_t*)codebook_in, codes, n_tok, 0, st);
+        if (e != hipSuccess) return ANTKV_ELAUNCH;
+    }
+    const hipError_t e = launch_kmeans_update(g, (const half_t*)x, w, have_tokens ? n_tok : 0, (const half_t*)codebook_in,
+                                              (half_t*)codebook_out, codes, wsum, objective, workspace, st);
+    return e == hipSuccess ? ANTKV_OK : ANTKV_ELAUNCH;
+}
+
 int antkv_prefill_attn(const antkv_geom* geom, const void* q, const void* k, const void* v, int64_t N, int64_t Nq,
                        float scale, void* out, float* row_max, float* row_sum, void* stream)
 {

@@ -96,6 +96,10 @@ hipError_t launch_append(const Geom& g, const half_t* k_new, const half_t* v_new
                          int32_t* idx_v, half_t* rows_v, int64_t k_v, int64_t N, int W, hipStream_t st);
 
 size_t anchor_score_workspace_bytes(const Geom& g, int64_t N, int64_t Nq);
+size_t kmeans_workspace_bytes(const Geom& g);
+hipError_t launch_kmeans_update(const Geom& g, const half_t* x, const float* w, int64_t n_tok, const half_t* cb_in,
+                                half_t* cb_out, const uint8_t* codes, float* wsum_out, double* objective, void* ws,
+                                hipStream_t st);
 hipError_t launch_prefill_attn(const Geom& g, const half_t* q, const half_t* k, const half_t* v, int64_t N, int64_t Nq,
                                float scale, half_t* out, float* row_max, float* row_sum, hipStream_t st);
 hipError_t launch_anchor_score(const Geom& g, const half_t* q, const half_t* k, int64_t N, int64_t Nq,
