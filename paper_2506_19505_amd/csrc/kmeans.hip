@@ -5,8 +5,8 @@
 // assigned weight, then the weighted mean.
 //
 // Accumulation: a workgroup takes a chunk of tokens and a quarter of the sub-spaces, adds w*x and w into fp32
-// accumulators in LDS (ds_add_f32: a centroid's row is 4*d_sub bytes, so tokens of one wave mostly hit
-// different banks), and flushes the non-zero accumulators to the global sums with hardware float atomics.  Sums are
+// accumulators in LDS (ds_add_f32; laid out [sub-space][channel][centroid] so that the lanes of one instruction
+// spread over the banks by their codes), and flushes the non-zero accumulators to the global sums with hardware float atomics.  Sums are
 // therefore fp32 and their order is not fixed: results agree to fp32 rounding, not bit for bit, from run to run.
 #include "common.h"
 
@@ -66,12 +66,12 @@ __global__ __launch_bounds__(kKmThreads) void km_accumulate(
             }
         }
         float dist = 0.f;
-        float* acc = &s_sum[(mi * kC + c) * DSUB];
+        float* acc = &s_sum[mi * DSUB * kC + c];                // [mi][e][c]: for one e the lanes' banks follow their codes
 #pragma unroll
         for (int e = 0; e < DSUB; ++e) {
             const float df = xv[e] - cv[e];
             dist = fmaf(df, df, dist);
-            atomicAdd(acc + e, wt * xv[e]);
+            atomicAdd(acc + e * kC, wt * xv[e]);
         }
         atomicAdd(&s_w[mi * kC + c], wt);
         obj += (double)wt * (double)dist;
@@ -82,8 +82,9 @@ __global__ __launch_bounds__(kKmThreads) void km_accumulate(
     if ((tid & 63) < MG && objective) unsafeAtomicAdd(objective + (int64_t)g * M + m, obj);
     __syncthreads();
     float* gs = sums + ((int64_t)g * M + m0) * kC * DSUB;
-    for (int i = tid; i < MG * kC * DSUB; i += kKmThreads) {
-        const float v = s_sum[i];
+    for (int i = tid; i < MG * kC * DSUB; i += kKmThreads) {   // i = (mi, c, e) in the global [m][c][e] order
+        const int e = i % DSUB, c = (i / DSUB) % kC, mi2 = i / (DSUB * kC);
+        const float v = s_sum[(mi2 * DSUB + e) * kC + c];
         if (v != 0.f) unsafeAtomicAdd(gs + i, v);
     }
     float* gw = wsum + ((int64_t)g * M + m0) * kC;
