@@ -21,7 +21,7 @@ namespace {
 
 constexpr int kPaThreads = 512;
 constexpr int kKRow = 136;      // halfs per staged K row: 16-byte reads of 16 consecutive rows hit 16 bank quads
-constexpr int kVRow = 144;      // halfs per staged V row: the 4 rows x 32 bytes of one transposed read hit 32 banks
+constexpr int kVRow = 160;      // halfs per staged V row (320 B): the 4 rows x 64 bytes that two 16-lane blocks read in one pass hit 64 banks
 constexpr float kPMax = 12.f;
 
 typedef __attribute__((address_space(3))) short4_t lds_short4;
