@@ -68,8 +68,8 @@ __device__ __forceinline__ float16_t tile_dot(const Tile128& a, const Tile128& b
 }
 
 // -------------------------------------------------------------------------------------------------
-// phase 1: partial row statistics.  grid = (key splits, query blocks of 64, B*Hkv); 8 waves =
-// 4 heads of the group (G <= 4 per pass; larger groups loop) x 2 query tiles of 32.
+// phase 1: partial row statistics.  grid = (key splits, query blocks, B*Hkv); 8 waves = HG heads of the
+// group x 8/HG query tiles of 32 with HG = min(G, 4), so that no wave idles for small groups (larger groups loop).
 // part: [B][Hq][Nq][KS][2] = (max in log2 units, sum of exp2)
 // -------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kAsThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void ans_row_stats(
@@ -82,7 +82,9 @@ __global__ __launch_bounds__(kAsThreads) __attribute__((amdgpu_waves_per_eu(4, 4
     const int ks = blockIdx.x;
     const int64_t qblk = blockIdx.y;
     const int b = blockIdx.z / Hkv, g = blockIdx.z % Hkv;
-    const int64_t q0 = qblk * 64 + (wave >> 2) * 32;           // first query row of this wave's tile
+    const int HG = G >= 4 ? 4 : G;                              // head slots of the workgroup
+    const int qspan = 32 * (8 / HG);                            // query rows per workgroup
+    const int64_t q0 = qblk * qspan + (wave >> (HG >> 1)) * 32;        // first query row of this wave's tile
     const bool wave_on = q0 < Nq;
     const int64_t qi = q0 + n;                                  // this lane's query row
     const int64_t qrow = qi < Nq ? qi : Nq - 1;
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(kAsThreads) __attribute__((amdgpu_waves_per_eu(4, 4
     const int64_t tile_last_pos = N - Nq + ((q0 + 31 < Nq) ? q0 + 31 : Nq - 1);
     const int64_t k_lo = (int64_t)ks * keys_per_split;
     // keys this workgroup walks: up to the last key any of its queries can see
-    const int64_t blk_last_pos = N - Nq + ((qblk * 64 + 63 < Nq) ? qblk * 64 + 63 : Nq - 1);
+    const int64_t blk_last_pos = N - Nq + ((qblk * qspan + qspan - 1 < Nq) ? qblk * qspan + qspan - 1 : Nq - 1);
     int64_t k_end = k_lo + keys_per_split;
     if (k_end > blk_last_pos + 1) k_end = blk_last_pos + 1;
     int64_t k_hi = k_lo + keys_per_split;                       // this wave's own limit
@@ -103,8 +105,8 @@ __global__ __launch_bounds__(kAsThreads) __attribute__((amdgpu_waves_per_eu(4, 4
         return *(const uint4_t*)(kbase + krow * kD + 8 * schunk);
     };
 
-    for (int h_it = 0; h_it < (G + 3) / 4; ++h_it) {
-        const int hh = 4 * h_it + (wave & 3);
+    for (int h_it = 0; h_it < (G + HG - 1) / HG; ++h_it) {
+        const int hh = HG * h_it + (wave & (HG - 1));
         const bool head_on = wave_on && hh < G;
         const int h = g * G + (hh < G ? hh : G - 1);
         Tile128 tq;
@@ -351,7 +353,8 @@ struct AsPlan {
 AsPlan plan(const Geom& g, int64_t N, int64_t Nq)
 {
     AsPlan p;
-    const int64_t qblocks = (Nq + 63) / 64;
+    const int qspan = 32 * (8 / (g.G >= 4 ? 4 : g.G));          // query rows per workgroup of phase 1
+    const int64_t qblocks = (Nq + qspan - 1) / qspan;
     const int64_t base_wgs = (int64_t)g.B * g.Hkv * qblocks;
     int64_t ks = (1024 + base_wgs - 1) / base_wgs;
     const int64_t max_ks = (N + 4095) / 4096;
@@ -391,7 +394,8 @@ hipError_t launch_anchor_score(const Geom& g, const half_t* q, const half_t* k, 
     const float c1 = scale * kLog2e;
     const int64_t rows = (int64_t)g.B * g.Hq * Nq;
     if (!row_max) {
-        dim3 grid((unsigned)p.KS, (unsigned)((Nq + 63) / 64), (unsigned)(g.B * g.Hkv));
+        const int qspan = 32 * (8 / (g.G >= 4 ? 4 : g.G));
+        dim3 grid((unsigned)p.KS, (unsigned)((Nq + qspan - 1) / qspan), (unsigned)(g.B * g.Hkv));
         hipLaunchKernelGGL(ans_row_stats, grid, dim3(kAsThreads), 0, st, q, k, N, Nq, c1, part, g.Hq, g.Hkv, g.G,
                            p.KS, p.keys_per_split);
     }

@@ -1,7 +1,8 @@
 // Causal attention over the prompt (paper Sec. 2.1) that also writes the softmax row statistics which the
 // Anchor Score pass consumes (Alg. 1, first step: attention extended to return row maximum and row sum).
 //
-// grid = (query blocks of 64, B*Hkv); 8 waves = 4 heads of the group x 2 query tiles of 32 (larger groups loop).
+// grid = (query blocks, B*Hkv); 8 waves = HG heads of the group x 8/HG query tiles of 32, HG = min(G, 4), so that
+// every wave has work whatever the group size (4 x 2, 2 x 4 or 1 x 8; larger groups loop over the heads).
 // The waves of a workgroup share each 32-key tile of K and V through double-buffered LDS.
 //   scores   S^T tile (keys on the MFMA row axis, queries on the column axis): lane (n, kh) owns query n and
 //            16 of the tile's 32 keys, so the running softmax is lane-local up to one exchange between the two
@@ -43,13 +44,15 @@ __global__ __launch_bounds__(kPaThreads) void prefill_attn_kernel(
     const int n = lane & 31, kh = lane >> 5;
     const int64_t qblk = (int64_t)gridDim.x - 1 - blockIdx.x;      // longest rows first
     const int b = blockIdx.y / Hkv, g = blockIdx.y % Hkv;
-    const int64_t q0 = qblk * 64 + (wave >> 2) * 32;
+    const int HG = G >= 4 ? 4 : G;                                 // head slots of the workgroup
+    const int qspan = 32 * (8 / HG);                               // query rows per workgroup
+    const int64_t q0 = qblk * qspan + (wave >> (HG >> 1)) * 32;
     const bool wave_on = q0 < Nq;
     const int64_t qi = q0 + n;
     const int64_t qrow = qi < Nq ? qi : Nq - 1;
     const int64_t qpos = N - Nq + qrow;                            // last key this lane's query sees
     const int64_t tile_last_pos = N - Nq + ((q0 + 31 < Nq) ? q0 + 31 : Nq - 1);
-    const int64_t blk_last_pos = N - Nq + ((qblk * 64 + 63 < Nq) ? qblk * 64 + 63 : Nq - 1);
+    const int64_t blk_last_pos = N - Nq + ((qblk * qspan + qspan - 1 < Nq) ? qblk * qspan + qspan - 1 : Nq - 1);
     const int64_t k_end = blk_last_pos + 1;                        // keys the workgroup walks
     const int64_t k_hi = tile_last_pos + 1;                        // keys this wave needs
     const half_t* kbase = k + ((int64_t)b * Hkv + g) * N * kD;
@@ -59,8 +62,8 @@ __global__ __launch_bounds__(kPaThreads) void prefill_attn_kernel(
     // cover the two channel halves of a 32-channel group, blocks 2/3 the same for the other key half (kh)
     const int tr_off = (4 * kh + ((lane & 15) >> 2)) * kVRow + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
-    for (int h_it = 0; h_it < (G + 3) / 4; ++h_it) {
-        const int hh = 4 * h_it + (wave & 3);
+    for (int h_it = 0; h_it < (G + HG - 1) / HG; ++h_it) {
+        const int hh = HG * h_it + (wave & (HG - 1));
         const bool head_on = wave_on && hh < G;
         const int h = g * G + (hh < G ? hh : G - 1);
         half8_t tq[8];
@@ -191,7 +194,8 @@ __global__ __launch_bounds__(kPaThreads) void prefill_attn_kernel(
 hipError_t launch_prefill_attn(const Geom& g, const half_t* q, const half_t* k, const half_t* v, int64_t N, int64_t Nq,
                                float scale, half_t* out, float* row_max, float* row_sum, hipStream_t st)
 {
-    dim3 grid((unsigned)((Nq + 63) / 64), (unsigned)(g.B * g.Hkv));
+    const int qspan = 32 * (8 / (g.G >= 4 ? 4 : g.G));
+    dim3 grid((unsigned)((Nq + qspan - 1) / qspan), (unsigned)(g.B * g.Hkv));
     hipLaunchKernelGGL(prefill_attn_kernel, grid, dim3(kPaThreads), 0, st, q, k, v, N, Nq, scale * kLog2e, out, row_max,
                        row_sum, g.Hq, g.Hkv, g.G);
     return hipGetLastError();
