@@ -1,12 +1,15 @@
 // Top-k selection of Anchor Scores (keep the ~1 % highest-scoring tokens in FP16; paper Sec. 3,
 // Fig. 2(b)) and the gather of the selected FP16 rows.
 //
-// Exact radix select on an order-preserving 32-bit key: three histogram passes (11 + 11 + 10 bits)
-// find the k-th largest key tau; one counting pass and one ordered emission pass then write the
-// positions of all keys > tau plus the lowest-positioned keys == tau needed to reach k, in
-// ascending position order.  Rows are split into slices of 8192 scores so that a launch has
-// (slices x rows) workgroups; every workgroup re-derives tau's known digits from the global
-// histograms itself, so no extra "scan" launches are needed.
+// Exact radix select on an order-preserving 32-bit key, with two reads of the scores before the emission:
+//   1. histogram of the top 11 key bits per row;
+//   2. every workgroup (slice of 8192 scores) finds the bin d0 that holds the k-th largest key, counts its keys in
+//      higher bins and appends its keys of bin d0 (with their positions) to the row's candidate list;
+//   3. one workgroup per row selects the exact k-th largest key tau among the candidates (two more radix rounds
+//      on the remaining 21 bits, in LDS) and adds the candidates' contributions to the per-slice counts of keys
+//      > tau and == tau (a list that overflowed its buffer is replaced by a filtered walk over the row);
+//   4. an ordered emission pass writes the positions of all keys > tau plus the lowest-positioned keys == tau
+//      needed to reach k, in ascending position order.
 #include "common.h"
 
 namespace antkv {
@@ -19,12 +22,13 @@ constexpr int kBins = 2048;
 
 // Find the bin where the count of keys taken from the top reaches k_rem.
 // On return digit = that bin, k_new = how many keys are still needed inside it.
+template <int THREADS = kTopkThreads>
 __device__ void find_digit(const uint32_t* __restrict__ hist, int nbins, uint32_t k_rem,
-                           uint32_t& digit, uint32_t& k_new, uint32_t* sh)
+                           uint32_t& digit, uint32_t& k_new, uint32_t* sh)   // sh: 2 + THREADS / 64 words
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int bpt = nbins / kTopkThreads;
-    uint32_t c[kBins / kTopkThreads];
+    const int bpt = nbins / THREADS;
+    uint32_t c[kBins / THREADS];
     uint32_t tot = 0;
     for (int i = 0; i < bpt; ++i) {
         c[i] = hist[nbins - 1 - (tid * bpt + i)];
@@ -59,95 +63,179 @@ __global__ __launch_bounds__(256) void zero_u32(uint32_t* p, int64_t n)
     if (i < n) p[i] = 0u;
 }
 
-template <int PASS>
-__global__ __launch_bounds__(kTopkThreads) void topk_hist(const float* __restrict__ scores,
-                                                          const float* __restrict__ scores_b, int rows_a, int64_t N,
-                                                          uint32_t k, uint32_t* __restrict__ ws_hist)
+__device__ __forceinline__ const float* row_scores(const float* scores, const float* scores_b, int rows_a, int64_t row,
+                                                   int64_t N)
+{
+    return (row < rows_a) ? scores + row * N : scores_b + (row - rows_a) * N;
+}
+
+// per-row header in the workspace
+enum { kHeadCount = 0, kHeadTau = 1, kHeadNeedEq = 2, kHeadWords = 8 };
+
+__global__ __launch_bounds__(kTopkThreads) void topk_hist0(const float* __restrict__ scores,
+                                                           const float* __restrict__ scores_b, int rows_a, int64_t N,
+                                                           uint32_t* __restrict__ ws_hist)
 {
     __shared__ uint32_t lh[kBins];
-    __shared__ uint32_t sh[8];
     const int64_t row = blockIdx.y;
-    uint32_t* hist = ws_hist + row * 3 * kBins;
     for (int i = threadIdx.x; i < kBins; i += kTopkThreads) lh[i] = 0u;
-    uint32_t prefix = 0, k_rem = k;
-    if (PASS >= 1) {
-        uint32_t d0;
-        find_digit(hist, kBins, k_rem, d0, k_rem, sh);
-        prefix = d0;
-    }
-    if (PASS >= 2) {
-        uint32_t d1;
-        find_digit(hist + kBins, kBins, k_rem, d1, k_rem, sh);
-        prefix = (prefix << 11) | d1;
-    }
     __syncthreads();
     const int64_t lo = (int64_t)blockIdx.x * kSlice;
     const int64_t hi = (lo + kSlice < N) ? lo + kSlice : N;
-    const float* src = (row < rows_a) ? scores + row * N : scores_b + (row - rows_a) * N;
-    for (int64_t i = lo + threadIdx.x; i < hi; i += kTopkThreads) {
-        const uint32_t key = float_key(src[i]);
-        if (PASS == 0) atomicAdd(&lh[key >> 21], 1u);
-        else if (PASS == 1) { if ((key >> 21) == prefix) atomicAdd(&lh[(key >> 10) & 2047u], 1u); }
-        else { if ((key >> 10) == prefix) atomicAdd(&lh[key & 1023u], 1u); }
+    const float* src = row_scores(scores, scores_b, rows_a, row, N);
+    if (hi - lo == kSlice && (((uintptr_t)(src + lo)) & 15) == 0) {
+#pragma unroll
+        for (int j = 0; j < kSlice / (4 * kTopkThreads); ++j) {
+            const float4_t v = *(const float4_t*)(src + lo + 4 * (threadIdx.x + kTopkThreads * j));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) atomicAdd(&lh[float_key(v[e]) >> 21], 1u);
+        }
+    } else {
+        for (int64_t i = lo + threadIdx.x; i < hi; i += kTopkThreads) atomicAdd(&lh[float_key(src[i]) >> 21], 1u);
     }
     __syncthreads();
+    uint32_t* hist = ws_hist + row * kBins;
     for (int i = threadIdx.x; i < kBins; i += kTopkThreads)
-        if (lh[i]) atomicAdd(&hist[PASS * kBins + i], lh[i]);
+        if (lh[i]) atomicAdd(&hist[i], lh[i]);
 }
 
-__device__ void resolve_tau(const uint32_t* hist, uint32_t k, uint32_t& tau, uint32_t& need_eq, uint32_t* sh)
-{
-    uint32_t d0, d1, d2, k_rem = k;
-    find_digit(hist, kBins, k_rem, d0, k_rem, sh);
-    find_digit(hist + kBins, kBins, k_rem, d1, k_rem, sh);
-    find_digit(hist + 2 * kBins, 1024, k_rem, d2, k_rem, sh);
-    tau = (d0 << 21) | (d1 << 10) | d2;
-    need_eq = k_rem;
-}
-
-// per slice: how many keys are > tau and == tau
-__global__ __launch_bounds__(kTopkThreads) void topk_count(const float* __restrict__ scores,
-                                                           const float* __restrict__ scores_b, int rows_a, int64_t N,
-                                                           uint32_t k, const uint32_t* __restrict__ ws_hist,
-                                                           uint32_t* __restrict__ counts, int n_slices)
+// per slice: count the keys above bin d0, append the keys of bin d0 to the row's candidate list
+__global__ __launch_bounds__(kTopkThreads) void topk_collect(const float* __restrict__ scores,
+                                                             const float* __restrict__ scores_b, int rows_a, int64_t N,
+                                                             uint32_t k, const uint32_t* __restrict__ ws_hist,
+                                                             uint32_t* __restrict__ head, uint32_t* __restrict__ counts,
+                                                             int n_slices, uint2_t* __restrict__ cand, uint32_t cap)
 {
     __shared__ uint32_t sh[8];
     __shared__ uint32_t red[2][4];
+    __shared__ uint32_t s_base;
     const int64_t row = blockIdx.y;
-    uint32_t tau, need_eq;
-    resolve_tau(ws_hist + row * 3 * kBins, k, tau, need_eq, sh);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t d0, k_rem;
+    find_digit(ws_hist + row * kBins, kBins, k, d0, k_rem, sh);
     const int64_t lo = (int64_t)blockIdx.x * kSlice;
     const int64_t hi = (lo + kSlice < N) ? lo + kSlice : N;
-    const float* src = (row < rows_a) ? scores + row * N : scores_b + (row - rows_a) * N;
+    const float* src = row_scores(scores, scores_b, rows_a, row, N);
+    constexpr int kPer = kSlice / kTopkThreads;                 // 32 scores per thread, in 8 groups of 4
+    uint32_t key[kPer];
+    const bool fast = hi - lo == kSlice && (((uintptr_t)(src + lo)) & 15) == 0;
+    // element j of the thread sits at position lo + pos(j); out-of-range elements get key 0 and never qualify
+    auto pos = [&](int j) -> int64_t {
+        return fast ? 4 * (tid + kTopkThreads * (j >> 2)) + (j & 3) : (int64_t)tid + (int64_t)kTopkThreads * j;
+    };
+    if (fast) {
+#pragma unroll
+        for (int j = 0; j < kPer / 4; ++j) {
+            const float4_t v = *(const float4_t*)(src + lo + 4 * (tid + kTopkThreads * j));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) key[4 * j + e] = float_key(v[e]);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) key[j] = (lo + pos(j) < hi) ? float_key(src[lo + pos(j)]) : 0u;
+    }
     uint32_t gt = 0, eq = 0;
-    for (int64_t i = lo + threadIdx.x; i < hi; i += kTopkThreads) {
-        const uint32_t key = float_key(src[i]);
-        gt += (key > tau);
-        eq += (key == tau);
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const bool in = fast || lo + pos(j) < hi;
+        gt += in && (key[j] >> 21) > d0;
+        eq += in && (key[j] >> 21) == d0;
+    }
+    // block-wide: total of gt, exclusive prefix of eq
+    uint32_t ieq = eq;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t a = __shfl_up(ieq, off, 64);
+        if (lane >= off) ieq += a;
     }
     gt = wave_sum_u32(gt);
-    eq = wave_sum_u32(eq);
-    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = gt; red[1][threadIdx.x >> 6] = eq; }
+    if (lane == 63) red[1][wave] = ieq;
+    if (lane == 0) red[0][wave] = gt;
     __syncthreads();
-    if (threadIdx.x == 0) {
+    uint32_t off_eq = ieq - eq;
+    for (int w = 0; w < wave; ++w) off_eq += red[1][w];
+    const uint32_t tot_eq = red[1][0] + red[1][1] + red[1][2] + red[1][3];
+    if (tid == 0) {
         uint32_t* c = counts + (row * n_slices + blockIdx.x) * 2;
         c[0] = red[0][0] + red[0][1] + red[0][2] + red[0][3];
-        c[1] = red[1][0] + red[1][1] + red[1][2] + red[1][3];
+        c[1] = 0u;
+        s_base = tot_eq ? atomicAdd(&head[row * kHeadWords + kHeadCount], tot_eq) : 0u;
+    }
+    __syncthreads();
+    if (eq == 0) return;
+    uint32_t at = s_base + off_eq;
+    uint2_t* out = cand + row * (int64_t)cap;
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const bool in = fast || lo + pos(j) < hi;
+        if (in && (key[j] >> 21) == d0) {
+            if (at < cap) out[at] = uint2_t{key[j], (uint32_t)(lo + pos(j))};
+            ++at;
+        }
+    }
+}
+
+// per row: exact k-th largest key among the candidates, and the candidates' share of the per-slice counts
+constexpr int kResolveThreads = 1024;
+
+__global__ __launch_bounds__(kResolveThreads) void topk_resolve(const float* __restrict__ scores,
+                                                             const float* __restrict__ scores_b, int rows_a, int64_t N,
+                                                             uint32_t k, const uint32_t* __restrict__ ws_hist,
+                                                             uint32_t* __restrict__ head, uint32_t* __restrict__ counts,
+                                                             int n_slices, const uint2_t* __restrict__ cand, uint32_t cap)
+{
+    __shared__ uint32_t lh[kBins];
+    __shared__ uint32_t sh[2 + kResolveThreads / 64];
+    const int64_t row = blockIdx.x;
+    const int tid = threadIdx.x;
+    uint32_t d0, d1, d2, k_rem, need_eq;
+    find_digit<kResolveThreads>(ws_hist + row * kBins, kBins, k, d0, k_rem, sh);
+    const uint32_t n_cand = head[row * kHeadWords + kHeadCount];
+    const bool listed = n_cand <= cap;                           // else the list overflowed: walk the row instead
+    const uint2_t* list = cand + row * (int64_t)cap;
+    const float* src = row_scores(scores, scores_b, rows_a, row, N);
+    auto for_each = [&](auto fn) {
+        if (listed) {
+            for (uint32_t i = tid; i < n_cand; i += kResolveThreads) fn(list[i][0], list[i][1]);
+        } else {
+            for (int64_t i = tid; i < N; i += kResolveThreads) {
+                const uint32_t key = float_key(src[i]);
+                if ((key >> 21) == d0) fn(key, (uint32_t)i);
+            }
+        }
+    };
+    for (int i = tid; i < kBins; i += kResolveThreads) lh[i] = 0u;
+    __syncthreads();
+    for_each([&](uint32_t key, uint32_t) { atomicAdd(&lh[(key >> 10) & 2047u], 1u); });
+    __syncthreads();
+    find_digit<kResolveThreads>(lh, kBins, k_rem, d1, k_rem, sh);
+    for (int i = tid; i < kBins; i += kResolveThreads) lh[i] = 0u;
+    __syncthreads();
+    for_each([&](uint32_t key, uint32_t) { if (((key >> 10) & 2047u) == d1) atomicAdd(&lh[key & 1023u], 1u); });
+    __syncthreads();
+    find_digit<kResolveThreads>(lh, 1024, k_rem, d2, need_eq, sh);
+    const uint32_t tau = (d0 << 21) | (d1 << 10) | d2;
+    uint32_t* c = counts + row * (int64_t)n_slices * 2;
+    for_each([&](uint32_t key, uint32_t i) {
+        if (key > tau) atomicAdd(&c[(i / kSlice) * 2], 1u);
+        else if (key == tau) atomicAdd(&c[(i / kSlice) * 2 + 1], 1u);
+    });
+    if (tid == 0) {
+        head[row * kHeadWords + kHeadTau] = tau;
+        head[row * kHeadWords + kHeadNeedEq] = need_eq;
     }
 }
 
 __global__ __launch_bounds__(kTopkThreads) void topk_emit(const float* __restrict__ scores,
                                                           const float* __restrict__ scores_b, int rows_a, int64_t N,
-                                                          uint32_t k, const uint32_t* __restrict__ ws_hist,
+                                                          uint32_t k, const uint32_t* __restrict__ head,
                                                           const uint32_t* __restrict__ counts, int n_slices,
                                                           int32_t* __restrict__ idx, int32_t* __restrict__ idx_b)
 {
-    __shared__ uint32_t sh[8];
     __shared__ uint32_t red[2][4];
     const int64_t row = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    uint32_t tau, need_eq;
-    resolve_tau(ws_hist + row * 3 * kBins, k, tau, need_eq, sh);
+    const uint32_t tau = head[row * kHeadWords + kHeadTau], need_eq = head[row * kHeadWords + kHeadNeedEq];
     // keys > tau and == tau in the slices before this one
     uint32_t bgt = 0, beq = 0;
     for (int s = tid; s < (int)blockIdx.x; s += kTopkThreads) {
@@ -165,7 +253,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_emit(const float* __restric
     const int64_t lo = (int64_t)blockIdx.x * kSlice + (int64_t)tid * (kSlice / kTopkThreads);
     int64_t hi = lo + kSlice / kTopkThreads;
     if (hi > N) hi = N;
-    const float* src = (row < rows_a) ? scores + row * N : scores_b + (row - rows_a) * N;
+    const float* src = row_scores(scores, scores_b, rows_a, row, N);
     // the thread's 32 scores are read once (16-byte loads when the row allows it) and kept as keys
     constexpr int kPer = kSlice / kTopkThreads;
     static_assert(kPer == 32, "a thread owns 32 consecutive scores");
@@ -230,11 +318,36 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4_t* __restr
 
 }  // namespace
 
+namespace {
+
+struct TopkPlan {
+    int n_slices;
+    uint32_t cap;                      // candidate entries per row
+    size_t off_hist, off_head, off_counts, off_cand, total;
+};
+
+TopkPlan topk_plan(int64_t rows, int64_t N)
+{
+    TopkPlan p;
+    p.n_slices = (int)((N + kSlice - 1) / kSlice);
+    if (p.n_slices < 1) p.n_slices = 1;
+    // the bin of the k-th key usually holds a few percent of a row; a fuller bin makes topk_resolve walk the row
+    p.cap = (uint32_t)(N / 8 + 4096);
+    size_t off = 0;
+    p.off_hist = off;   off += align_up((size_t)rows * kBins * 4);
+    p.off_head = off;   off += align_up((size_t)rows * kHeadWords * 4);     // directly after the histograms: zeroed together
+    p.off_counts = off; off += align_up((size_t)rows * p.n_slices * 2 * 4);
+    p.off_cand = off;   off += align_up((size_t)rows * p.cap * sizeof(uint2_t));
+    p.total = off;
+    return p;
+}
+
+}  // namespace
+
 size_t topk_workspace_bytes(int64_t n_rows, int64_t N, int64_t k)
 {
     (void)k;
-    const int64_t n_slices = (N + kSlice - 1) / kSlice;
-    return align_up((size_t)n_rows * 3 * kBins * 4) + align_up((size_t)n_rows * (n_slices > 0 ? n_slices : 1) * 2 * 4);
+    return topk_plan(n_rows, N).total;
 }
 
 // Two score arrays of n_rows rows each can be selected in one go (scores_b / idx_b may be NULL): the launches then
@@ -244,19 +357,23 @@ hipError_t launch_topk2(const float* scores, int32_t* idx, const float* scores_b
 {
     if (k == 0 || n_rows == 0) return hipSuccess;
     const int64_t rows = scores_b ? 2 * n_rows : n_rows;
-    const int n_slices = (int)((N + kSlice - 1) / kSlice);
-    uint32_t* hist = (uint32_t*)ws;
-    uint32_t* counts = (uint32_t*)((char*)ws + align_up((size_t)rows * 3 * kBins * 4));
-    const int64_t nh = rows * 3 * kBins;
+    const TopkPlan p = topk_plan(rows, N);
+    char* w = (char*)ws;
+    uint32_t* hist = (uint32_t*)(w + p.off_hist);
+    uint32_t* head = (uint32_t*)(w + p.off_head);
+    uint32_t* counts = (uint32_t*)(w + p.off_counts);
+    uint2_t* cand = (uint2_t*)(w + p.off_cand);
+    const int64_t nz = (int64_t)(p.off_counts / 4);             // histograms and headers
     const int ra = (int)n_rows;
-    hipLaunchKernelGGL(zero_u32, dim3((unsigned)((nh + 255) / 256)), dim3(256), 0, st, hist, nh);
-    dim3 grid(n_slices, (unsigned)rows);
-    hipLaunchKernelGGL(topk_hist<0>, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist);
-    hipLaunchKernelGGL(topk_hist<1>, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist);
-    hipLaunchKernelGGL(topk_hist<2>, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist);
-    hipLaunchKernelGGL(topk_count, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist, counts, n_slices);
-    hipLaunchKernelGGL(topk_emit, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist, counts, n_slices,
-                       idx, idx_b);
+    hipLaunchKernelGGL(zero_u32, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, hist, nz);
+    dim3 grid(p.n_slices, (unsigned)rows);
+    hipLaunchKernelGGL(topk_hist0, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, hist);
+    hipLaunchKernelGGL(topk_collect, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist, head,
+                       counts, p.n_slices, cand, p.cap);
+    hipLaunchKernelGGL(topk_resolve, dim3((unsigned)rows), dim3(kResolveThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k,
+                       hist, head, counts, p.n_slices, cand, p.cap);
+    hipLaunchKernelGGL(topk_emit, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, head, counts,
+                       p.n_slices, idx, idx_b);
     return hipGetLastError();
 }
 
