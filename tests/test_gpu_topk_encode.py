@@ -36,6 +36,18 @@ def test_topk_degenerate_rows(oracle):
     assert np.array_equal(antkv.topk(dev(t), 3000).cpu().numpy(), np.tile(np.arange(3000), (2, 1)))
 
 
+def test_topk_scores_crowded_into_one_bin(oracle):
+    """All scores of a row share their top 11 key bits, so the candidate list of the k-th key's bin overflows its
+    buffer (N/8 + 4096 entries) and the selection falls back to walking the row; with and without ties."""
+    rng = np.random.default_rng(3)
+    N = 100000
+    s = (1.0 + 0.18 * rng.random((3, N))).astype(np.float32)
+    s[1] = np.round(s[1] * 64) / 64                        # a dozen distinct values: long runs of ties
+    s[2] = -s[2]
+    for k in (1, 1000, 99999):
+        assert np.array_equal(antkv.topk(dev(s), k).cpu().numpy(), oracle.topk(s, k))
+
+
 @pytest.mark.parametrize("d", [4, 8, 16])
 @pytest.mark.parametrize("B,Hq,Hkv,n", [(2, 4, 2, 333), (1, 8, 8, 70)])
 def test_encode_matches_oracle(oracle, d, B, Hq, Hkv, n):
