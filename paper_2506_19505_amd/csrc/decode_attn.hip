@@ -299,7 +299,10 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     char* smem = (char*)smem_u4;
     const lds_char* lsm = (const lds_char*)smem_u4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int bg = blockIdx.x / p.S, sp = blockIdx.x % p.S;
+    // Workgroups go to the 8 XCDs round-robin by their id; remap so that the S workgroups of one (sequence, KV head)
+    // sit on one XCD and share its L2 for the codebooks and the anchor lists.
+    const int wg = (gridDim.x & 7) == 0 ? (int)((blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3)) : (int)blockIdx.x;
+    const int bg = wg / p.S, sp = wg % p.S;
     const int b = bg / p.Hkv, g = bg % p.Hkv;
     const int nheads = p.G;               // <= kNH
     const int h0 = g * p.G;
