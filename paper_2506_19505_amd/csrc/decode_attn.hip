@@ -1027,7 +1027,6 @@ struct DsParams {
     const int32_t* idx_k;
     const half_t* rows_k;
     float* stat_part;      // [B][Hq][S][2]
-    float* lse2;           // [B][Hq]
     float *ans_k, *ans_v;  // [B][Hkv][N]
     int64_t N, N_cap;
     int k_k;
@@ -1103,12 +1102,25 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
         const float ss = wave_sum(fmaf(a, a, c * c));
         if (lane == 0) s_red[kDaWaves * 8 - 4 + wave] = sqrtf(ss);       // parked in the last wave's slots until the barrier
     }
+    // pass 1: log-sum-exp of each head from the S partial (max, sum) pairs that pass 0 left
+    if (PASS == 1 && wave == kNH && lane < kNH) {
+        float v = 0.f;
+        if (lane < p.G) {
+            const float* sp_ = p.stat_part + ((int64_t)b * p.Hq + h0 + lane) * p.S * 2;
+            float m = kNegBig;
+            for (int s = 0; s < p.S; ++s) m = fmaxf(m, sp_[2 * s]);
+            float l = 0.f;
+            for (int s = 0; s < p.S; ++s) l += sp_[2 * s + 1] * exp2f(sp_[2 * s] - m);
+            v = m + log2f(l);
+        }
+        s_red[kDaWaves * 8 - 8 + lane] = v;
+    }
     __syncthreads();
     float qn[kNH], lse[kNH];
 #pragma unroll
     for (int h = 0; h < kNH; ++h) {
         qn[h] = s_red[kDaWaves * 8 - 4 + h];
-        lse[h] = (PASS == 1 && h < p.G) ? p.lse2[(int64_t)b * p.Hq + h0 + h] : 0.f;
+        lse[h] = (PASS == 1) ? s_red[kDaWaves * 8 - 8 + h] : 0.f;
     }
     __syncthreads();
     const int lo_k = s_misc[0], hi_k = s_misc[1];
@@ -1224,17 +1236,6 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
     }
 }
 
-__global__ __launch_bounds__(64) void decode_ans_lse_kernel(const float* __restrict__ stat_part, int S,
-                                                            float* __restrict__ lse2, int n_bh)
-{
-    const int bh = blockIdx.x * 64 + threadIdx.x;
-    if (bh >= n_bh) return;
-    float m = kNegBig;
-    for (int s = 0; s < S; ++s) m = fmaxf(m, stat_part[((int64_t)bh * S + s) * 2]);
-    float l = 0.f;
-    for (int s = 0; s < S; ++s) l += stat_part[((int64_t)bh * S + s) * 2 + 1] * exp2f(stat_part[((int64_t)bh * S + s) * 2] - m);
-    lse2[bh] = m + log2f(l);
-}
 
 // measurement aid: events to record around the next code-stream kernel launched from this host thread
 thread_local hipEvent_t t_ev_start = nullptr, t_ev_stop = nullptr;
@@ -1242,7 +1243,7 @@ thread_local hipEvent_t t_ev_start = nullptr, t_ev_stop = nullptr;
 struct DaPlan {
     int S;
     int64_t chunk;
-    size_t off_part, off_done, off_stat, off_lse, total;
+    size_t off_part, off_done, off_stat, total;
 };
 
 DaPlan da_plan(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans)
@@ -1268,7 +1269,6 @@ DaPlan da_plan(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans
     pl.off_part = off; off += align_up((size_t)g.B * g.Hq * pl.S * (kD + 2) * sizeof(float));
     pl.off_done = off; off += align_up((size_t)g.B * g.Hkv * sizeof(unsigned long long));
     pl.off_stat = off; off += want_ans ? align_up((size_t)g.B * g.Hq * pl.S * 2 * sizeof(float)) : 0;
-    pl.off_lse = off;  off += align_up((size_t)g.B * g.Hq * sizeof(float));
     pl.total = off;
     return pl;
 }
@@ -1305,7 +1305,6 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     const DaPlan pl = da_plan(g, a.N, a.k_k, a.k_v, want_ans);
     char* w = (char*)ws;
     float* part = (float*)(w + pl.off_part);
-    float* lse2 = (float*)(w + pl.off_lse);
     DaParams p;
     p.q = a.q; p.codes_k = a.codes_k; p.codes_v = a.codes_v; p.cb_k = a.cb_k; p.cb_v = a.cb_v;
     p.idx_k = a.idx_k; p.idx_v = a.idx_v; p.rows_k = a.rows_k; p.rows_v = a.rows_v;
@@ -1334,18 +1333,20 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     if (want_ans) {
         DsParams d;
         d.q = a.q; d.codes_k = a.codes_k; d.cb_k = a.cb_k; d.idx_k = a.idx_k; d.rows_k = a.rows_k;
-        d.stat_part = (float*)(w + pl.off_stat); d.lse2 = lse2; d.ans_k = a.ans_k; d.ans_v = a.ans_v;
+        d.stat_part = (float*)(w + pl.off_stat); d.ans_k = a.ans_k; d.ans_v = a.ans_v;
         d.N = a.N; d.N_cap = a.N_cap; d.k_k = (int)a.k_k; d.c1 = p.c1; d.Hq = g.Hq; d.Hkv = g.Hkv; d.G = g.G;
         d.S = pl.S; d.chunk = pl.chunk;
         const size_t sh2 = (size_t)g.M * 256 * 16 + kNH * kD * 4 + kDaWaves * 32 + 64 + 4096;
-        e = hipFuncSetAttribute((const void*)decode_ans_kernel<DSUB, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh2);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void*)decode_ans_kernel<DSUB, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh2);
-        if (e != hipSuccess) return e;
+        static const hipError_t ans_setup = [sh2]() {              // once per process and DSUB
+            hipError_t e1 = hipFuncSetAttribute((const void*)decode_ans_kernel<DSUB, 0>,
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh2);
+            if (e1 != hipSuccess) return e1;
+            return hipFuncSetAttribute((const void*)decode_ans_kernel<DSUB, 1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)sh2);
+        }();
+        if (ans_setup != hipSuccess) return ans_setup;
         const unsigned grid2 = (unsigned)((int64_t)g.B * g.Hkv * pl.S);
         hipLaunchKernelGGL((decode_ans_kernel<DSUB, 0>), dim3(grid2), dim3(kDaThreads), sh2, st, d);
-        hipLaunchKernelGGL(decode_ans_lse_kernel, dim3((unsigned)((g.B * g.Hq + 63) / 64)), dim3(64), 0, st,
-                           d.stat_part, pl.S, lse2, g.B * g.Hq);
         hipLaunchKernelGGL((decode_ans_kernel<DSUB, 1>), dim3(grid2), dim3(kDaThreads), sh2, st, d);
     }
     return hipGetLastError();
