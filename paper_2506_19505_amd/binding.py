@@ -42,6 +42,11 @@ class Geometry:
     def M(self) -> int:
         return self.D // self.d_sub
 
+    @property
+    def code_bytes(self) -> int:
+        """Bytes of one token's codes: one byte per sub-space, or the M 12-bit codes packed (4096 centroids)."""
+        return self.M if self.n_centroids <= 256 else (self.M * 12 + 7) // 8
+
     def c(self) -> _Geom:
         return _Geom(self.B, self.Hq, self.Hkv, self.D, self.d_sub, self.n_centroids)
 
@@ -136,7 +141,7 @@ def encode(geom: Geometry, x: torch.Tensor, codebook: torch.Tensor, codes: torch
     _need(codebook, torch.float16, "codebook")
     B, Hkv, n, _ = x.shape
     if codes is None:
-        codes = torch.empty((B, Hkv, n, geom.M), dtype=torch.uint8, device=x.device)
+        codes = torch.empty((B, Hkv, n, geom.code_bytes), dtype=torch.uint8, device=x.device)
     _need(codes, torch.uint8, "codes")
     g = geom.c()
     rc = load_library().antkv_encode(ctypes.byref(g), _p(x), x.stride(0), x.stride(1), x.stride(2), n, _p(codebook),

@@ -11,12 +11,16 @@ int check_geom(const antkv_geom* gm, Geom& g)
     if (gm->B < 0 || gm->Hq <= 0 || gm->Hkv <= 0 || gm->D <= 0 || gm->d_sub <= 0 || gm->n_centroids <= 0)
         return ANTKV_EINVAL;
     if (gm->Hq % gm->Hkv != 0) return ANTKV_EINVAL;
-    if (gm->D != kD || gm->n_centroids != kC) return ANTKV_EUNSUPPORTED;
-    if (gm->d_sub != 4 && gm->d_sub != 8 && gm->d_sub != 16) return ANTKV_EUNSUPPORTED;
+    if (gm->D != kD) return ANTKV_EUNSUPPORTED;
+    const bool wide = gm->n_centroids == 4096 && gm->d_sub == 32;             // 12-bit codes
+    const bool byte_codes = gm->n_centroids == kC && (gm->d_sub == 4 || gm->d_sub == 8 || gm->d_sub == 16);
+    if (!wide && !byte_codes) return ANTKV_EUNSUPPORTED;
     const int G = gm->Hq / gm->Hkv;
     if (G != 1 && G != 2 && G != 4) return ANTKV_EUNSUPPORTED;
     if ((int64_t)gm->B * gm->Hkv > 65535) return ANTKV_EUNSUPPORTED;
     g.B = gm->B; g.Hq = gm->Hq; g.Hkv = gm->Hkv; g.G = G; g.d = gm->d_sub; g.M = kD / gm->d_sub;
+    g.C = gm->n_centroids;
+    g.code_bytes = wide ? 6 : g.M;
     return ANTKV_OK;
 }
 
@@ -77,8 +81,11 @@ int antkv_encode(const antkv_geom* geom, const void* x, int64_t xs_b, int64_t xs
     if (!x || !codebook || !codes) return ANTKV_EINVAL;
     if (misaligned(x, 16) || misaligned(codebook, 16) || misaligned(codes, 16)) return ANTKV_EINVAL;
     if (xs_t < kD || (xs_b & 7) || (xs_h & 7) || (xs_t & 7) || xs_b < 0 || xs_h < 0) return ANTKV_EINVAL;
-    hipError_t e = launch_encode(g, (const half_t*)x, xs_b, xs_h, xs_t, n_tok, (const half_t*)codebook, codes, N_cap,
-                                 token_offset, (hipStream_t)stream);
+    const hipError_t e =
+        g.C == 4096 ? launch_encode12(g, (const half_t*)x, xs_b, xs_h, xs_t, n_tok, (const half_t*)codebook, codes, N_cap,
+                                      token_offset, (hipStream_t)stream)
+                    : launch_encode(g, (const half_t*)x, xs_b, xs_h, xs_t, n_tok, (const half_t*)codebook, codes, N_cap,
+                                    token_offset, (hipStream_t)stream);
     return e == hipSuccess ? ANTKV_OK : ANTKV_ELAUNCH;
 }
 
@@ -110,7 +117,7 @@ size_t antkv_anchor_select_workspace(const antkv_geom* geom, int64_t N, int64_t 
 size_t antkv_kmeans_step_workspace(const antkv_geom* geom)
 {
     Geom g;
-    if (check_geom(geom, g)) return 0;
+    if (check_geom(geom, g) || g.C != kC) return 0;
     return kmeans_workspace_bytes(g);
 }
 
@@ -121,6 +128,7 @@ int antkv_kmeans_step(const antkv_geom* geom, const void* x, const float* w, int
     Geom g;
     int rc = check_geom(geom, g);
     if (rc) return rc;
+    if (g.C != kC) return ANTKV_EUNSUPPORTED;                    // one-byte codes only
     if (n_tok < 0 || n_tok > 0x7fffffffLL) return ANTKV_EINVAL;
     if (!codebook_in || !codebook_out || codebook_in == codebook_out) return ANTKV_EINVAL;
     if (misaligned(codebook_in, 16) || misaligned(codebook_out, 16) || misaligned(objective, 8)) return ANTKV_EINVAL;
@@ -213,6 +221,7 @@ int antkv_append_token(const antkv_geom* geom, const void* k_new, const void* v_
     Geom g;
     int rc = check_geom(geom, g);
     if (rc) return rc;
+    if (g.C != kC) return ANTKV_EUNSUPPORTED;                    // one-byte codes only
     if (N < 0 || W < 0 || W > N || N + 1 > N_cap || k_k < W || k_v < W) return ANTKV_EINVAL;
     if (W > 64) return ANTKV_EUNSUPPORTED;
     if (g.B == 0) return ANTKV_OK;
@@ -236,6 +245,7 @@ size_t antkv_decode_attn_workspace(const antkv_geom* geom, int64_t N, int64_t k_
 {
     Geom g;
     if (check_geom(geom, g) || N < 0 || k_k < 0 || k_v < 0 || k_resel < 0) return 0;
+    if (g.C != kC) return 0;
     return dec_plan(g, N, k_k, k_v, k_resel, true).total;
 }
 
@@ -251,6 +261,7 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
     if (N < 0 || N_cap < N || k_k < 0 || k_v < 0 || k_k > N || k_v > N || k_resel < 0 || k_resel > N ||
         N > 0x7fffffffLL)
         return ANTKV_EINVAL;
+    if (g.C != kC) return ANTKV_EUNSUPPORTED;
     if (g.B == 0) return ANTKV_OK;
     if (!q || !out || misaligned(q, 16) || misaligned(out, 16)) return ANTKV_EINVAL;
     if (!(scale > 0.f)) return ANTKV_EINVAL;

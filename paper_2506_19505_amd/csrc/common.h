@@ -77,11 +77,17 @@ __device__ __forceinline__ uint32_t float_key(float f)
 // ---- launchers (each enqueues on `stream` and returns a hipError_t) --------------------------
 struct Geom {
     int B, Hq, Hkv, G, d, M;
+    int C;            // centroids per sub-space: 256 (one byte per code) or 4096 (12-bit codes, d = 32 only)
+    int code_bytes;   // bytes of one token's codes: M, or 6 for the four packed 12-bit codes
 };
 
 hipError_t launch_encode(const Geom& g, const half_t* x, int64_t xs_b, int64_t xs_h, int64_t xs_t,
                          int64_t n_tok, const half_t* cb, uint8_t* codes, int64_t N_cap,
                          int64_t token_offset, hipStream_t st);
+
+hipError_t launch_encode12(const Geom& g, const half_t* x, int64_t xs_b, int64_t xs_h, int64_t xs_t,
+                           int64_t n_tok, const half_t* cb, uint8_t* codes, int64_t N_cap,
+                           int64_t token_offset, hipStream_t st);
 
 size_t topk_workspace_bytes(int64_t n_rows, int64_t N, int64_t k);
 hipError_t launch_topk(const float* scores, int64_t n_rows, int64_t N, int64_t k, int32_t* idx,

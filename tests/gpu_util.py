@@ -55,3 +55,22 @@ def check_index_sets(got: np.ndarray, want: np.ndarray, margin: np.ndarray, what
                                       f"largest oracle margin {worst:.3e} >= {NEAR_TIE}")
             soft += diff.size
     return soft
+
+
+def unpack12(packed: np.ndarray, M: int = 4) -> np.ndarray:
+    """[..., 3M/2] bytes -> [..., M] codes: the M 12-bit codes of a token packed little-endian."""
+    b = packed.astype(np.int64)
+    word = np.zeros(b.shape[:-1], dtype=np.int64)
+    for i in range(b.shape[-1]):
+        word |= b[..., i] << (8 * i)
+    return np.stack([(word >> (12 * m)) & 0xFFF for m in range(M)], axis=-1).astype(np.int32)
+
+
+def pack12(codes: np.ndarray) -> np.ndarray:
+    """[..., M] codes (< 4096) -> [..., 3M/2] bytes, the inverse of unpack12."""
+    c = codes.astype(np.int64)
+    word = np.zeros(c.shape[:-1], dtype=np.int64)
+    for m in range(c.shape[-1]):
+        word |= c[..., m] << (12 * m)
+    nb = c.shape[-1] * 12 // 8
+    return np.stack([(word >> (8 * i)) & 0xFF for i in range(nb)], axis=-1).astype(np.uint8)

@@ -64,16 +64,16 @@ def test_all_tokens_anchored_is_plain_attention(oracle):
     np.testing.assert_allclose(out, _sdpa(q, k, v, 0.3), rtol=1e-11, atol=1e-13)
 
 
-@pytest.mark.parametrize("d", [4, 8, 16])
-def test_mixed_codes_and_separate_anchor_sets(oracle, d):
+@pytest.mark.parametrize("d,C,D", [(4, 256, 32), (8, 256, 32), (16, 256, 32), (32, 4096, 128)])
+def test_mixed_codes_and_separate_anchor_sets(oracle, d, C, D):
     # K anchors and V anchors are different sets; everything else comes from the code tables
-    B, Hq, Hkv, N, D = 2, 8, 2, 150, 32
+    B, Hq, Hkv, N = 2, 8, 2, 150
     M = D // d
     rng = np.random.default_rng(11 + d)
     q = _rand((B, Hq, D), 12)
-    cbk, cbv = _rand((Hkv, M, 256, d), 13, 2.0), _rand((Hkv, M, 256, d), 14)
-    codes_k = rng.integers(0, 256, (B, Hkv, N, M)).astype(np.int32)
-    codes_v = rng.integers(0, 256, (B, Hkv, N, M)).astype(np.int32)
+    cbk, cbv = _rand((Hkv, M, C, d), 13, 2.0), _rand((Hkv, M, C, d), 14)
+    codes_k = rng.integers(0, C, (B, Hkv, N, M)).astype(np.int32)
+    codes_v = rng.integers(0, C, (B, Hkv, N, M)).astype(np.int32)
     k_k, k_v = 9, 14
     ik = np.stack([[np.sort(rng.choice(N, k_k, replace=False)) for _ in range(Hkv)] for _ in range(B)]).astype(np.int32)
     iv = np.stack([[np.sort(rng.choice(N, k_v, replace=False)) for _ in range(Hkv)] for _ in range(B)]).astype(np.int32)
