@@ -131,5 +131,7 @@ int decode_num_splits(const Geom& g, int64_t N);
 void decode_profile_next(hipEvent_t start, hipEvent_t stop);
 size_t decode_workspace_bytes(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans);
 hipError_t launch_decode_attn(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st);
+size_t decode12_workspace_bytes(const Geom& g, int64_t N);
+hipError_t launch_decode12(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st);
 
 }  // namespace antkv

@@ -1,0 +1,436 @@
+// Decode attention over 12-bit VQ codes + FP16 anchors (Attn of paper Sec. 2.1 on the cache of Fig. 2(b), with the
+// d32 / 4096-centroid codebooks of Sec. 4): one query token per sequence against codes packed 6 bytes per token.
+//
+// With 4096 centroids of 32 channels only the q.centroid table of the K side fits LDS (4 sub-spaces x 4096 codes x
+// 4 heads x int16 = 128 KB); the V codebook (1 MB per KV head) stays in L2, which is why workgroup ids are mapped so
+// that KV head g runs on XCD g mod 8 and each XCD's L2 keeps one head's codebook.
+//   prologue   table: 16-bit fixed point with one scale per head (two sweeps over the K codebook: maximum, then
+//              quantise); bitmaps of the K- and V-anchored tokens of the workgroup's token range with a running
+//              count per word, so that "is token t in the V list, and where" is a bit test and a popcount.
+//   stream     lane = token: unpack the four codes, four 8-byte table reads, integer sums, online softmax per
+//              64-token tile.  Then the wave walks the tile's tokens one by one: every lane owns two output
+//              channels, fetches them from the token's V centroids (one 4-byte gather per lane) and adds
+//              P_h * v for the four heads.  Anchored tokens carry weight zero here.
+//   anchors    tokens of the range with an FP16 K row or V row, one per wave at a time: score from the FP16 row
+//              (or from the table), value from the FP16 row (or from the centroids).
+//   merge      waves through LDS, workgroups through a partial (max, sum, accumulator) per head and a second
+//              small kernel.
+#include "common.h"
+
+namespace antkv {
+
+namespace {
+
+constexpr int kT12 = 1024;               // threads
+constexpr int kW12 = kT12 / 64;          // waves
+constexpr int kC12 = 4096;
+constexpr int kD12 = 32;
+constexpr int kM12 = 4;
+constexpr int kNH = 4;                   // head slots (G <= 4)
+constexpr int kChunkMax = 32768;         // tokens per workgroup (bitmaps of 1024 words)
+constexpr float kEmptyRef12 = -1.0e4f;   // softmax reference before any token: finite, far above the masked score
+constexpr int kLutMax12 = 32767;
+
+struct D12Params {
+    const half_t* q;
+    const uint8_t *codes_k, *codes_v;
+    const half_t *cb_k, *cb_v;
+    const int32_t *idx_k, *idx_v;
+    const half_t *rows_k, *rows_v;
+    float* part;                          // [B][Hq][S][kD + 2]
+    int64_t N, N_cap;
+    int k_k, k_v;
+    float c1;
+    int Hq, Hkv, G, S, chunk;
+};
+
+__device__ __forceinline__ float dot8f(const half8_t& a, const half8_t& b, float acc)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const half2_t x = {a[2 * i], a[2 * i + 1]}, y = {b[2 * i], b[2 * i + 1]};
+        acc = __builtin_amdgcn_fdot2(x, y, acc, false);
+    }
+    return acc;
+}
+
+// first position in ascending idx[0..n) whose value is >= target; 64-ary search, every lane returns the same value
+__device__ __forceinline__ int lower_bound64(const int32_t* __restrict__ idx, int n, int target, int lane)
+{
+    int lo = 0, hi = n;                                   // the answer lies in [lo, hi]
+    while (hi > lo) {
+        const int len = hi - lo;
+        const int step = (len + 63) / 64;                 // 64 probes at lo + lane * step cover [lo, hi)
+        const int pos = lo + lane * step;
+        const bool below = pos < hi && idx[pos] < target;
+        const int cnt = (int)__popcll(__ballot(below));   // the list ascends, so these lanes form a prefix
+        if (cnt == 0) { hi = lo; break; }
+        int nhi = lo + cnt * step;                        // probe cnt is not below the target (or past the end)
+        if (nhi > hi) nhi = hi;
+        lo = lo + (cnt - 1) * step + 1;                   // probe cnt - 1 is below it
+        hi = nhi;                                         // hi - lo <= step - 1 < len: the loop ends
+    }
+    return lo;
+}
+
+__device__ __forceinline__ uint32_t code12(uint32_t lo, uint32_t hi, int m)
+{
+    const uint64_t w = ((uint64_t)hi << 32) | lo;
+    return (uint32_t)(w >> (12 * m)) & 0xFFFu;
+}
+
+__global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
+{
+    extern __shared__ uint4_t smem_u4[];
+    char* smem = (char*)smem_u4;
+    uint2_t* s_lut = (uint2_t*)smem;                                   // [4][4096] entries of 4 x int16 (128 KB)
+    uint32_t* s_mk = (uint32_t*)(smem + kM12 * kC12 * 8);              // K-anchored tokens of the range, 1024 words
+    uint32_t* s_mv = s_mk + 1024;                                      // V-anchored tokens
+    uint32_t* s_pv = s_mv + 1024;                                      // V-anchored tokens before each word
+    half_t* s_q = (half_t*)(s_pv + 1024);                              // [4][128]
+    float* s_red = (float*)(s_q + kNH * kD);                           // 64 floats of scratch
+    int* s_misc = (int*)(s_red + 64);                                  // 16 ints
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // KV head g on XCD g mod 8: workgroup ids go to the XCDs round-robin
+    const int g = blockIdx.x % p.Hkv;
+    const int rest = blockIdx.x / p.Hkv;
+    const int b = rest / p.S, sp = rest % p.S;
+    const int bg = b * p.Hkv + g;
+    const int h0 = g * p.G;
+    const int64_t t0 = (int64_t)sp * p.chunk;
+    const int64_t t1 = (t0 + p.chunk < p.N) ? t0 + p.chunk : p.N;
+    const int32_t* idx_k = p.idx_k + (int64_t)bg * p.k_k;
+    const int32_t* idx_v = p.idx_v + (int64_t)bg * p.k_v;
+
+    // ---- prologue ----------------------------------------------------------------------------------------------
+    if (tid < kNH * kD) s_q[tid] = ((tid >> 7) < p.G) ? p.q[((int64_t)b * p.Hq + h0) * kD + tid] : (half_t)0.f;
+    for (int i = tid; i < 3 * 1024; i += kT12) s_mk[i] = 0u;
+    if (wave < 4) {                                                    // list ranges that fall into [t0, t1)
+        const int32_t* l = (wave < 2) ? idx_k : idx_v;
+        const int n = (wave < 2) ? p.k_k : p.k_v;
+        const int r = lower_bound64(l, n, (int)((wave & 1) ? t1 : t0), lane);
+        if (lane == 0) s_misc[wave] = r;
+    }
+    __syncthreads();
+    const int lo_k = s_misc[0], hi_k = s_misc[1], lo_v = s_misc[2], hi_v = s_misc[3];
+    for (int i = lo_k + tid; i < hi_k; i += kT12) {
+        const int rel = idx_k[i] - (int)t0;
+        atomicOr(&s_mk[rel >> 5], 1u << (rel & 31));
+    }
+    for (int i = lo_v + tid; i < hi_v; i += kT12) {
+        const int rel = idx_v[i] - (int)t0;
+        atomicOr(&s_mv[rel >> 5], 1u << (rel & 31));
+    }
+    // table, sweep 1: per-head maximum of |c1 q_h . centroid|; sweep 2: quantise.  Thread t owns entries t + 1024 i.
+    const half_t* cbk = p.cb_k + (int64_t)g * kM12 * kC12 * kD12;
+    float amax[kNH] = {0.f, 0.f, 0.f, 0.f};
+    float inv_q[kNH] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+    for (int sweep = 0; sweep < 2; ++sweep) {
+#pragma unroll 1
+        for (int m = 0; m < kM12; ++m) {
+            half8_t qv[kNH][4];
+#pragma unroll
+            for (int h = 0; h < kNH; ++h)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) qv[h][u] = *(const half8_t*)(s_q + h * kD + m * kD12 + 8 * u);
+#pragma unroll 1
+            for (int c = tid; c < kC12; c += kT12) {
+                const half_t* cp = cbk + ((int64_t)m * kC12 + c) * kD12;
+                half8_t cv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) cv[u] = *(const half8_t*)(cp + 8 * u);
+                float s[kNH];
+#pragma unroll
+                for (int h = 0; h < kNH; ++h) {
+                    float d = 0.f;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) d = dot8f(cv[u], qv[h][u], d);
+                    s[h] = d * p.c1;
+                }
+                if (sweep == 0) {
+#pragma unroll
+                    for (int h = 0; h < kNH; ++h) amax[h] = fmaxf(amax[h], fabsf(s[h]));
+                } else {
+                    int e[kNH];
+#pragma unroll
+                    for (int h = 0; h < kNH; ++h) e[h] = (int)rintf(s[h] * inv_q[h]);
+                    uint2_t w;
+                    w[0] = ((uint32_t)e[0] & 0xFFFFu) | ((uint32_t)e[1] << 16);
+                    w[1] = ((uint32_t)e[2] & 0xFFFFu) | ((uint32_t)e[3] << 16);
+                    s_lut[m * kC12 + c] = w;
+                }
+            }
+        }
+        if (sweep == 0) {
+#pragma unroll
+            for (int h = 0; h < kNH; ++h) {
+                const float wmax = wave_max(amax[h]);
+                if (lane == 0) s_red[wave * kNH + h] = wmax;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int h = 0; h < kNH; ++h) {
+                float a = 0.f;
+                for (int w = 0; w < kW12; ++w) a = fmaxf(a, s_red[w * kNH + h]);
+                amax[h] = a;
+                inv_q[h] = a > 0.f ? (float)kLutMax12 / a : 0.f;
+            }
+            __syncthreads();
+        }
+    }
+    float lut_q[kNH];                                                  // table quantum per head (log2 units)
+#pragma unroll
+    for (int h = 0; h < kNH; ++h) lut_q[h] = amax[h] * (1.0f / (float)kLutMax12);
+    // V-anchored tokens before each bitmap word (exclusive scan over 1024 words, one word per thread)
+    static_assert(kT12 == 1024, "one bitmap word per thread");
+    {
+        const uint32_t cnt = __popc(s_mv[tid]);
+        uint32_t incl = cnt;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t nb = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += nb;
+        }
+        if (lane == 63) ((uint32_t*)s_red)[wave] = incl;
+        __syncthreads();
+        uint32_t base = 0;
+        for (int w = 0; w < wave; ++w) base += ((uint32_t*)s_red)[w];
+        s_pv[tid] = base + incl - cnt;
+    }
+    __syncthreads();
+
+    // ---- stream ------------------------------------------------------------------------------------------------
+    const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * 6;
+    const uint8_t* cv = p.codes_v + (int64_t)bg * p.N_cap * 6;
+    const half_t* cbv = p.cb_v + (int64_t)g * kM12 * kC12 * kD12;
+    const int my_m = lane >> 4;                                        // the lane's two output channels are 2 lane, 2 lane + 1
+    const half_t* cbv_lane = cbv + (int64_t)my_m * kC12 * kD12 + 2 * (lane & 15);
+    float m_ref[kNH], l_lane[kNH], acc[kNH][2];
+#pragma unroll
+    for (int h = 0; h < kNH; ++h) { m_ref[h] = kEmptyRef12; l_lane[h] = 0.f; acc[h][0] = acc[h][1] = 0.f; }
+
+    auto load6 = [&](const uint8_t* base, int64_t tok, uint32_t& lo, uint32_t& hi) {
+        const uint16_t* s = (const uint16_t*)(base + tok * 6);
+        lo = (uint32_t)s[0] | ((uint32_t)s[1] << 16);
+        hi = (uint32_t)s[2];
+    };
+    auto lut_scores = [&](uint32_t klo, uint32_t khi, float (&s)[kNH]) {
+        int sum[kNH] = {0, 0, 0, 0};
+#pragma unroll
+        for (int m = 0; m < kM12; ++m) {
+            const uint2_t e = s_lut[m * kC12 + code12(klo, khi, m)];
+            sum[0] += (int)(short)(e[0] & 0xFFFFu);
+            sum[1] += (int)e[0] >> 16;
+            sum[2] += (int)(short)(e[1] & 0xFFFFu);
+            sum[3] += (int)e[1] >> 16;
+        }
+#pragma unroll
+        for (int h = 0; h < kNH; ++h) s[h] = (float)sum[h] * lut_q[h];
+    };
+    // one token's contribution: weights pw (uniform over the wave), value channels 2 lane, 2 lane + 1 in v
+    auto add_value = [&](const float (&pw)[kNH], half2_t v) {
+        const float v0 = (float)v[0], v1 = (float)v[1];
+#pragma unroll
+        for (int h = 0; h < kNH; ++h) {
+            acc[h][0] = fmaf(pw[h], v0, acc[h][0]);
+            acc[h][1] = fmaf(pw[h], v1, acc[h][1]);
+        }
+    };
+    // move the wave's reference of head h to at least `cand` (uniform); returns nothing, rescales the running state
+    auto raise_ref = [&](int h, float cand) {
+        if (cand > m_ref[h]) {
+            const float alpha = fast_exp2(m_ref[h] - cand);
+            l_lane[h] *= alpha;
+            acc[h][0] *= alpha;
+            acc[h][1] *= alpha;
+            m_ref[h] = cand;
+        }
+    };
+
+    const int64_t n_tiles = (t1 - t0 + 63) >> 6;
+    for (int64_t tile = wave; tile < n_tiles; tile += kW12) {
+        const int64_t tok = t0 + tile * 64 + lane;
+        const int64_t ltok = tok < t1 ? tok : t1 - 1;
+        uint32_t klo, khi, vlo, vhi;
+        load6(ck, ltok, klo, khi);
+        load6(cv, ltok, vlo, vhi);
+        const int rel = (int)(ltok - t0);
+        const uint32_t mbit = ((s_mk[rel >> 5] | s_mv[rel >> 5]) >> (rel & 31)) & 1u;
+        const bool masked = tok >= t1 || mbit != 0u;
+        float s[kNH];
+        lut_scores(klo, khi, s);
+        float pw_lane[kNH];
+#pragma unroll
+        for (int h = 0; h < kNH; ++h) {
+            const float sh = masked ? kNegBig : s[h];
+            raise_ref(h, wave_max(sh));
+            pw_lane[h] = fast_exp2(sh - m_ref[h]);                     // 0 for masked lanes
+            l_lane[h] += pw_lane[h];
+        }
+        // the tile's tokens one by one; value gathers run 8 tokens ahead of their use
+        constexpr int kAhead = 8;
+#pragma unroll 1
+        for (int j0 = 0; j0 < 64; j0 += kAhead) {
+            half2_t vbuf[kAhead];
+#pragma unroll
+            for (int jj = 0; jj < kAhead; ++jj) {
+                const uint32_t lo = __builtin_amdgcn_readlane(vlo, j0 + jj), hi = __builtin_amdgcn_readlane(vhi, j0 + jj);
+                vbuf[jj] = *(const half2_t*)(cbv_lane + (int64_t)code12(lo, hi, my_m) * kD12);
+            }
+#pragma unroll
+            for (int jj = 0; jj < kAhead; ++jj) {
+                float pw[kNH];
+#pragma unroll
+                for (int h = 0; h < kNH; ++h)
+                    pw[h] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, pw_lane[h]), j0 + jj));
+                add_value(pw, vbuf[jj]);
+            }
+        }
+    }
+
+    // ---- anchors: tokens of the range with an FP16 K row and/or V row, one per wave at a time ----------------
+    float l_anchor[kNH] = {0.f, 0.f, 0.f, 0.f};                        // uniform over the wave
+    float qf[kNH][2];
+#pragma unroll
+    for (int h = 0; h < kNH; ++h) { qf[h][0] = (float)s_q[h * kD + 2 * lane]; qf[h][1] = (float)s_q[h * kD + 2 * lane + 1]; }
+    const int n_ka = hi_k - lo_k, n_va = hi_v - lo_v;
+    for (int it = wave; it < n_ka + n_va; it += kW12) {
+        const bool from_k = it < n_ka;
+        const int i = from_k ? lo_k + it : lo_v + (it - n_ka);
+        const int tok = from_k ? idx_k[i] : idx_v[i];
+        const int rel = tok - (int)t0;
+        const bool in_k = (s_mk[rel >> 5] >> (rel & 31)) & 1u, in_v = (s_mv[rel >> 5] >> (rel & 31)) & 1u;
+        if (!from_k && in_k) continue;                                 // handled as a K-list entry
+        float s[kNH];
+        if (from_k) {                                                  // score from the FP16 key row
+            const half2_t kr = *(const half2_t*)(p.rows_k + ((int64_t)bg * p.k_k + i) * kD + 2 * lane);
+#pragma unroll
+            for (int h = 0; h < kNH; ++h)
+                s[h] = wave_sum(fmaf(qf[h][0], (float)kr[0], qf[h][1] * (float)kr[1])) * p.c1;
+        } else {
+            uint32_t klo, khi;
+            load6(ck, tok, klo, khi);
+            lut_scores(klo, khi, s);
+        }
+        half2_t v;
+        if (in_v) {                                                    // value from the FP16 row: its place in the V list
+            const int pos = from_k ? lo_v + (int)(s_pv[rel >> 5] + __popc(s_mv[rel >> 5] & ((1u << (rel & 31)) - 1u))) : i;
+            v = *(const half2_t*)(p.rows_v + ((int64_t)bg * p.k_v + pos) * kD + 2 * lane);
+        } else {
+            uint32_t vlo, vhi;
+            load6(cv, tok, vlo, vhi);
+            v = *(const half2_t*)(cbv_lane + (int64_t)code12(vlo, vhi, my_m) * kD12);
+        }
+        float pw[kNH];
+#pragma unroll
+        for (int h = 0; h < kNH; ++h) {
+            if (s[h] > m_ref[h]) {
+                const float alpha = fast_exp2(m_ref[h] - s[h]);
+                l_anchor[h] *= alpha;
+            }
+            raise_ref(h, s[h]);
+            pw[h] = fast_exp2(s[h] - m_ref[h]);
+            l_anchor[h] += pw[h];
+        }
+        add_value(pw, v);
+    }
+
+    // ---- merge the waves, write the workgroup's partial -------------------------------------------------------
+    __syncthreads();                                                   // the table is dead: its LDS becomes the merge area
+    float* s_m = (float*)smem;                                         // [waves][4] references
+    float* s_l = s_m + kW12 * kNH;                                     // [waves][4] sums
+    float* s_acc = s_l + kW12 * kNH;                                   // [waves][4][128]
+#pragma unroll
+    for (int h = 0; h < kNH; ++h) {
+        const float lw = wave_sum(l_lane[h]) + l_anchor[h];
+        if (lane == 0) { s_m[wave * kNH + h] = m_ref[h]; s_l[wave * kNH + h] = lw; }
+        s_acc[(wave * kNH + h) * kD + 2 * lane] = acc[h][0];
+        s_acc[(wave * kNH + h) * kD + 2 * lane + 1] = acc[h][1];
+    }
+    __syncthreads();
+    if (tid < kNH * kD) {
+        const int h = tid >> 7, ch = tid & 127;
+        if (h < p.G) {
+            float m = kEmptyRef12;
+            for (int w = 0; w < kW12; ++w) m = fmaxf(m, s_m[w * kNH + h]);
+            float l = 0.f, a = 0.f;
+            for (int w = 0; w < kW12; ++w) {
+                const float f = fast_exp2(s_m[w * kNH + h] - m);
+                l = fmaf(s_l[w * kNH + h], f, l);
+                a = fmaf(s_acc[(w * kNH + h) * kD + ch], f, a);
+            }
+            float* dst = p.part + (((int64_t)b * p.Hq + h0 + h) * p.S + sp) * (kD + 2);
+            dst[2 + ch] = a;
+            if (ch == 0) { dst[0] = m; dst[1] = l; }
+        }
+    }
+}
+
+// merge the S partials of a (sequence, query head) by log-sum-exp and round once to fp16
+__global__ __launch_bounds__(kD) void decode12_merge(const float* __restrict__ part, int S, half_t* __restrict__ out)
+{
+    const int64_t bh = blockIdx.x;
+    const int ch = threadIdx.x;
+    const float* pb = part + bh * S * (kD + 2);
+    float m = kEmptyRef12;
+    for (int s = 0; s < S; ++s) m = fmaxf(m, pb[s * (kD + 2)]);
+    float l = 0.f, a = 0.f;
+    for (int s = 0; s < S; ++s) {
+        const float f = fast_exp2(pb[s * (kD + 2)] - m);
+        l = fmaf(pb[s * (kD + 2) + 1], f, l);
+        a = fmaf(pb[s * (kD + 2) + 2 + ch], f, a);
+    }
+    out[bh * kD + ch] = (half_t)(l > 0.f ? a / l : 0.f);
+}
+
+struct D12Plan {
+    int S, chunk;
+    size_t total;
+};
+
+D12Plan d12_plan(const Geom& g, int64_t N)
+{
+    D12Plan pl;
+    const int64_t bgc = (int64_t)g.B * g.Hkv;
+    int64_t S = (256 + bgc - 1) / bgc;                                 // about one workgroup per CU
+    const int64_t s_max = (N + 1023) / 1024;
+    if (S > s_max) S = s_max;
+    if (S < 1) S = 1;
+    int64_t chunk = ((N + S - 1) / S + 63) / 64 * 64;
+    if (chunk > kChunkMax) chunk = kChunkMax;
+    if (chunk < 64) chunk = 64;
+    S = (N + chunk - 1) / chunk;
+    if (S < 1) S = 1;
+    pl.S = (int)S;
+    pl.chunk = (int)chunk;
+    pl.total = align_up((size_t)g.B * g.Hq * S * (kD + 2) * sizeof(float));
+    return pl;
+}
+
+constexpr size_t kD12Lds = (size_t)kM12 * kC12 * 8 + 3 * 1024 * 4 + kNH * kD * 2 + 64 * 4 + 16 * 4;
+
+}  // namespace
+
+size_t decode12_workspace_bytes(const Geom& g, int64_t N) { return d12_plan(g, N).total; }
+
+hipError_t launch_decode12(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st)
+{
+    const D12Plan pl = d12_plan(g, a.N);
+    static const hipError_t setup = []() {
+        return hipFuncSetAttribute((const void*)decode12_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kD12Lds);
+    }();
+    if (setup != hipSuccess) return setup;
+    if ((int64_t)g.B * g.Hkv * pl.S > 0x7fffffffLL) return hipErrorInvalidValue;
+    D12Params p;
+    p.q = a.q; p.codes_k = a.codes_k; p.codes_v = a.codes_v; p.cb_k = a.cb_k; p.cb_v = a.cb_v;
+    p.idx_k = a.idx_k; p.idx_v = a.idx_v; p.rows_k = a.rows_k; p.rows_v = a.rows_v;
+    p.part = (float*)ws; p.N = a.N; p.N_cap = a.N_cap; p.k_k = (int)a.k_k; p.k_v = (int)a.k_v;
+    p.c1 = a.scale * kLog2e; p.Hq = g.Hq; p.Hkv = g.Hkv; p.G = g.G; p.S = a.N > 0 ? pl.S : 0; p.chunk = pl.chunk;
+    if (a.N > 0)
+        hipLaunchKernelGGL(decode12_kernel, dim3((unsigned)(g.B * g.Hkv * pl.S)), dim3(kT12), kD12Lds, st, p);
+    hipLaunchKernelGGL(decode12_merge, dim3((unsigned)(g.B * g.Hq)), dim3(kD), 0, st, (const float*)ws, p.S, a.out);
+    return hipGetLastError();
+}
+
+}  // namespace antkv

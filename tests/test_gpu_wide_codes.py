@@ -55,3 +55,79 @@ def test_encode12_duplicate_centroids_and_offsets(oracle, books):
     want, margin = oracle.encode(x, cb, want_margin=True)
     check_codes(got, want, margin)
     assert not np.isin(got, np.arange(4000, 4096)).any() and not (got == 33).any()
+
+
+def _decode_case(oracle, books, seed, B, Hq, Hkv, N, k_k, k_v, N_cap=None, scale=None):
+    from workloads import make_decode_query, normal_fp16
+    rng = np.random.default_rng(seed)
+    scale = scale or 1.0 / np.sqrt(128)
+    N_cap = N_cap or N
+    cbk, cbv = books[0][:Hkv], books[1][:Hkv]
+    ck = rng.integers(0, C, (B, Hkv, N_cap, 4)).astype(np.int32)
+    cv = rng.integers(0, C, (B, Hkv, N_cap, 4)).astype(np.int32)
+    pick = lambda k: np.stack([[np.sort(rng.choice(N, k, replace=False)) for _ in range(Hkv)]
+                               for _ in range(B)]).astype(np.int32).reshape(B, Hkv, k)
+    ik, iv = pick(k_k), pick(k_v)
+    if k_k and k_v:                                            # make some tokens anchored in both lists
+        n_common = min(k_k, k_v) // 3
+        for b in range(B):
+            for g in range(Hkv):
+                both = np.union1d(iv[b, g][n_common:], ik[b, g][:n_common])
+                extra = np.setdiff1d(np.arange(N), both)[:k_v - both.size]
+                iv[b, g] = np.sort(np.concatenate([both, extra]))[:k_v]
+    rk = normal_fp16(seed, "rows_k", (B, Hkv, k_k, 128))
+    rv = normal_fp16(seed, "rows_v", (B, Hkv, k_v, 128))
+    q = make_decode_query(seed, B, Hq, 128)
+    geom = antkv.Geometry(B, Hq, Hkv, D_SUB, n_centroids=C)
+    out = antkv.decode_attn(geom, dev(q), scale, dev(pack12(ck)), dev(pack12(cv)), dev(cbk), dev(cbv),
+                            dev(ik) if k_k else None, dev(rk) if k_k else None,
+                            dev(iv) if k_v else None, dev(rv) if k_v else None, N=N)
+    torch.cuda.synchronize()
+    want = oracle.decode_attn(q, ck[:, :, :N], cv[:, :, :N], cbk, cbv, ik, rk, iv, rv, scale)
+    got = out.cpu().numpy().astype(np.float64)
+    err = np.linalg.norm(got - want, axis=-1) / np.linalg.norm(want, axis=-1)
+    assert err.max() <= 2e-3, f"relative L2 {err.max():.3e}"
+    print(f"B={B} Hq={Hq} Hkv={Hkv} N={N} anchors {k_k}/{k_v}: rel-L2 max {err.max():.2e}")
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,N,k_k,k_v", [(2, 8, 2, 3000, 30, 30), (1, 2, 2, 1237, 0, 0), (1, 4, 2, 700, 12, 0),
+                                                (1, 4, 1, 900, 0, 9), (1, 8, 2, 70000, 700, 700)])
+def test_decode12_matches_oracle(oracle, books, B, Hq, Hkv, N, k_k, k_v):
+    _decode_case(oracle, books, 90 + N, B, Hq, Hkv, N, k_k, k_v)
+
+
+def test_decode12_tiny_contexts_and_capacity(oracle, books):
+    for N in (1, 63, 64, 65):
+        _decode_case(oracle, books, 95, 1, 4, 2, N, min(N, 2), min(N, 3))
+    _decode_case(oracle, books, 96, 1, 4, 2, 500, 5, 5, N_cap=800)
+    _decode_case(oracle, books, 97, 1, 4, 2, 300, 300, 300)      # every token anchored in both lists
+
+
+def test_encode12_then_decode12(oracle, books):
+    """Codes produced by the library's own encode feed its decode; the oracle decodes the oracle's codes."""
+    from workloads import make_decode_query
+    B, Hq, Hkv, N = 1, 8, 2, 2000
+    _, k, v = make_qkv(98, B, Hq, Hkv, N, 1, 128)
+    geom = antkv.Geometry(B, Hq, Hkv, D_SUB, n_centroids=C)
+    cbk, cbv = dev(books[0]), dev(books[1])
+    ck, cv = antkv.encode(geom, dev(k), cbk), antkv.encode(geom, dev(v), cbv)
+    q = make_decode_query(98, B, Hq, 128)
+    scale = 1.0 / np.sqrt(128)
+    out = antkv.decode_attn(geom, dev(q), scale, ck, cv, cbk, cbv, None, None, None, None)
+    none = np.zeros((B, Hkv, 0), np.int32)
+    rows = np.zeros((B, Hkv, 0, 128), np.float16)
+    want = oracle.decode_attn(q, unpack12(ck.cpu().numpy()), unpack12(cv.cpu().numpy()), books[0], books[1], none, rows,
+                              none, rows, scale)
+    err = np.linalg.norm(out.cpu().numpy().astype(np.float64) - want, axis=-1) / np.linalg.norm(want, axis=-1)
+    assert err.max() <= 2e-3
+
+
+def test_wide_geometry_rejections():
+    import ctypes
+    lib = antkv.load_library()
+    bad = antkv.Geometry(1, 4, 2, 16, n_centroids=C).c()         # 4096 centroids need d_sub 32
+    assert lib.antkv_decode_attn_workspace(ctypes.byref(bad), 100, 0, 0, 0) == 0
+    ok = antkv.Geometry(1, 4, 2, D_SUB, n_centroids=C).c()
+    assert lib.antkv_decode_attn_workspace(ctypes.byref(ok), 100, 0, 0, 0) > 0
+    assert lib.antkv_decode_attn_workspace(ctypes.byref(ok), 100, 0, 0, 5) == 0      # no re-selection on 12-bit codes
+    assert lib.antkv_kmeans_step_workspace(ctypes.byref(ok)) == 0
