@@ -23,12 +23,18 @@
  *     errors are detected on the host before anything is enqueued.
  *   - Tensors are dense, row-major, last index fastest, in the layouts given per call.
  *     fp16 = IEEE binary16.  "KV head g of query head h" is g = h / (Hq / Hkv).
- *   - Geometry: D must be 128, n_centroids 256 (one byte per code), d_sub in {4, 8, 16}
- *     (2 / 1 / 0.5 bit per element, the paper's d4m256 / d8m256 notation, Sec. 4), and
- *     Hq / Hkv in {1, 2, 4}.  M = D / d_sub sub-spaces per head.
- *   - Codebooks: fp16 [Hkv][M][256][d_sub], separate for K and V; sub-space m covers
+ *   - Geometry: D must be 128 and Hq / Hkv in {1, 2, 4}; M = D / d_sub sub-spaces per head.  Two code formats:
+ *       n_centroids 256, d_sub in {4, 8, 16}: one byte per code (2 / 1 / 0.5 bit per element, the paper's
+ *         d4m256 / d8m256 notation, Sec. 4); every entry point supports it.
+ *       n_centroids 4096, d_sub 32: 12-bit codes (0.375 bit per element, the d32m4096 point of Sec. 4).
+ *         Supported by antkv_encode and antkv_decode_attn (attention only: no scores, no re-selection);
+ *         antkv_append_token and antkv_kmeans_step return EUNSUPPORTED.  d_sub 16 with 4096 centroids is
+ *         not supported.
+ *   - Codebooks: fp16 [Hkv][M][n_centroids][d_sub], separate for K and V; sub-space m covers
  *     channels [m*d_sub, (m+1)*d_sub).
- *   - Codes: uint8 [B][Hkv][N_cap][M], token-major.
+ *   - Codes: uint8 [B][Hkv][N_cap][code_bytes], token-major.  code_bytes = M for one-byte codes.  For 12-bit
+ *     codes code_bytes = 6: the token's four codes packed little-endian into 48 bits,
+ *     c0 | c1 << 12 | c2 << 24 | c3 << 36.
  *   - Calls that share a workspace must not overlap in time.  A workspace may hold any bytes when it is first
  *     used (nothing has to be cleared) and may be reused by calls of different shapes.
  *   - Codes and index sets are deterministic.  The fp16 output of antkv_decode_attn can differ between two runs
@@ -55,8 +61,8 @@ typedef struct antkv_geom {
     int32_t Hq;          /* query heads */
     int32_t Hkv;         /* KV heads */
     int32_t D;           /* head dim (128) */
-    int32_t d_sub;       /* sub-vector dim: 4, 8 or 16 */
-    int32_t n_centroids; /* 256 */
+    int32_t d_sub;       /* sub-vector dim: 4, 8 or 16 (with 256 centroids), or 32 (with 4096) */
+    int32_t n_centroids; /* 256 or 4096 */
 } antkv_geom;
 
 int antkv_version(void);
@@ -68,8 +74,8 @@ const char* antkv_strerror(int code); /* host pointer to a static string */
  *
  *   x        fp16 [B][Hkv][n_tok][D] with element strides xs_b, xs_h, xs_t (channel stride 1);
  *            16-byte aligned, strides multiples of 8 elements.
- *   codebook fp16 [Hkv][M][256][d_sub]
- *   codes    uint8 [B][Hkv][N_cap][M]; rows token_offset .. token_offset+n_tok-1 are written:
+ *   codebook fp16 [Hkv][M][n_centroids][d_sub]
+ *   codes    uint8 [B][Hkv][N_cap][code_bytes]; rows token_offset .. token_offset+n_tok-1 are written:
  *            codes[b][g][token_offset+t][m] = argmin_c || x[b][g][t][m*d_sub : (m+1)*d_sub] - codebook[g][m][c] ||^2,
  *            the lowest c among equal distances (distances compared in fp32).
  * Call once for K with the K codebook and once for V with the V codebook.
@@ -127,9 +133,9 @@ int antkv_gather_rows(const antkv_geom* geom, const void* x, int64_t N, const in
  * (anchor tokens keep their FP16 rows, every other token is read from its codes; Fig. 2(b)).
  *
  *   q        fp16 [B][Hq][D]
- *   codes_k, codes_v  uint8 [B][Hkv][N_cap][M], tokens 0..N-1 valid (anchor positions hold codes
+ *   codes_k, codes_v  uint8 [B][Hkv][N_cap][code_bytes], tokens 0..N-1 valid (anchor positions hold codes
  *            too; they are ignored).  16-byte aligned.
- *   cb_k, cb_v        fp16 [Hkv][M][256][d_sub]
+ *   cb_k, cb_v        fp16 [Hkv][M][n_centroids][d_sub]
  *   idx_k    int32 [B][Hkv][k_k] strictly ascending in [0, N); rows_k fp16 [B][Hkv][k_k][D]
  *   idx_v, rows_v     likewise with k_v.  k_k and k_v may be 0 (pointers may then be NULL) up to N.
  *   out      fp16 [B][Hq][D]; accumulation is fp32, rounded once.
@@ -138,6 +144,7 @@ int antkv_gather_rows(const antkv_geom* geom, const void* x, int64_t N, const in
  *            ans_k[j] = sum_h p_hj (1 - p_hj) ||q_h||_2
  *   resel_idx_k, resel_idx_v  int32 [B][Hkv][k_resel] or NULL: top-k_resel positions of those scores
  *            (ascending, ties to the lower position).  Needs ans_k / ans_v respectively to be non-NULL.
+ * With 12-bit codes (n_centroids 4096) the optional outputs must be NULL and k_resel 0 (EUNSUPPORTED otherwise).
  * N == 0 writes zeros.  Errors: EINVAL, EUNSUPPORTED, EWORKSPACE, ELAUNCH.
  */
 size_t antkv_decode_attn_workspace(const antkv_geom* geom, int64_t N, int64_t k_k, int64_t k_v,

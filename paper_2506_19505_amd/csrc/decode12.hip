@@ -30,6 +30,7 @@ constexpr int kNH = 4;                   // head slots (G <= 4)
 constexpr int kChunkMax = 32768;         // tokens per workgroup (bitmaps of 1024 words)
 constexpr float kEmptyRef12 = -1.0e4f;   // softmax reference before any token: finite, far above the masked score
 constexpr int kLutMax12 = 32767;
+constexpr float kPShift12 = 12.f;        // weights are kept scaled by 2^12 so that small ones stay normal in fp16
 
 struct D12Params {
     const half_t* q;
@@ -90,6 +91,8 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     half_t* s_q = (half_t*)(s_pv + 1024);                              // [4][128]
     float* s_red = (float*)(s_q + kNH * kD);                           // 64 floats of scratch
     int* s_misc = (int*)(s_red + 64);                                  // 16 ints
+    half4_t* s_pw = (half4_t*)(s_misc + 16) + (threadIdx.x >> 6) * 64; // this wave's tile: four heads' weights per token
+    uint16_t* s_vc = (uint16_t*)((half4_t*)(s_misc + 16) + kW12 * 64) + (threadIdx.x >> 6) * 256;   // [4][64] V codes
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // KV head g on XCD g mod 8: workgroup ids go to the XCDs round-robin
     const int g = blockIdx.x % p.Hkv;
@@ -206,6 +209,8 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     const half_t* cbv = p.cb_v + (int64_t)g * kM12 * kC12 * kD12;
     const int my_m = lane >> 4;                                        // the lane's two output channels are 2 lane, 2 lane + 1
     const half_t* cbv_lane = cbv + (int64_t)my_m * kC12 * kD12 + 2 * (lane & 15);
+    const char* cbv_bytes = (const char*)cbv;
+    const uint32_t lane_off = (uint32_t)((my_m * kC12 * kD12 + 2 * (lane & 15)) * 2);   // byte offset of the lane's channels
     float m_ref[kNH], l_lane[kNH], acc[kNH][2];
 #pragma unroll
     for (int h = 0; h < kNH; ++h) { m_ref[h] = kEmptyRef12; l_lane[h] = 0.f; acc[h][0] = acc[h][1] = 0.f; }
@@ -260,32 +265,53 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         const bool masked = tok >= t1 || mbit != 0u;
         float s[kNH];
         lut_scores(klo, khi, s);
-        float pw_lane[kNH];
+        half4_t pw_h;
 #pragma unroll
         for (int h = 0; h < kNH; ++h) {
             const float sh = masked ? kNegBig : s[h];
             raise_ref(h, wave_max(sh));
-            pw_lane[h] = fast_exp2(sh - m_ref[h]);                     // 0 for masked lanes
-            l_lane[h] += pw_lane[h];
+            const float pw = fast_exp2(sh - m_ref[h] + kPShift12);     // 0 for masked lanes, at most 2^12
+            l_lane[h] += pw;
+            pw_h[h] = (half_t)pw;
         }
-        // the tile's tokens one by one; value gathers run 8 tokens ahead of their use
-        constexpr int kAhead = 8;
-#pragma unroll 1
-        for (int j0 = 0; j0 < 64; j0 += kAhead) {
-            half2_t vbuf[kAhead];
+        // hand the tile to the value phase through the wave's own LDS area (LDS operations of one wave stay in order)
+        __builtin_amdgcn_wave_barrier();
+        s_pw[lane] = pw_h;
+#pragma unroll
+        for (int m = 0; m < kM12; ++m) s_vc[m * 64 + lane] = (uint16_t)code12(vlo, vhi, m);
+        __builtin_amdgcn_wave_barrier();
+        // the tile's tokens one by one: every lane gathers its two channels of the token's centroid of sub-space my_m;
+        // gathers run 16 tokens ahead of their use
+        constexpr int kAhead = 16;
+        half2_t vbuf[2][kAhead];
+        auto gather = [&](int j0, half2_t (&dst)[kAhead]) {
+#pragma unroll
+            for (int j4 = 0; j4 < kAhead; j4 += 4) {
+                const uint2_t c4 = *(const uint2_t*)(s_vc + my_m * 64 + j0 + j4);      // four tokens' codes
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t code = (c4[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                    dst[j4 + e] = *(const half2_t*)(cbv_bytes + (lane_off + code * (uint32_t)(kD12 * 2)));
+                }
+            }
+        };
+        auto consume = [&](int j0, const half2_t (&src)[kAhead]) {
 #pragma unroll
             for (int jj = 0; jj < kAhead; ++jj) {
-                const uint32_t lo = __builtin_amdgcn_readlane(vlo, j0 + jj), hi = __builtin_amdgcn_readlane(vhi, j0 + jj);
-                vbuf[jj] = *(const half2_t*)(cbv_lane + (int64_t)code12(lo, hi, my_m) * kD12);
-            }
+                const half4_t pj = s_pw[j0 + jj];                      // same address in every lane: a broadcast read
+                const float v0 = (float)src[jj][0], v1 = (float)src[jj][1];
 #pragma unroll
-            for (int jj = 0; jj < kAhead; ++jj) {
-                float pw[kNH];
-#pragma unroll
-                for (int h = 0; h < kNH; ++h)
-                    pw[h] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, pw_lane[h]), j0 + jj));
-                add_value(pw, vbuf[jj]);
+                for (int h = 0; h < kNH; ++h) {
+                    acc[h][0] = fmaf((float)pj[h], v0, acc[h][0]);
+                    acc[h][1] = fmaf((float)pj[h], v1, acc[h][1]);
+                }
             }
+        };
+        gather(0, vbuf[0]);
+#pragma unroll
+        for (int k = 0; k < 64 / kAhead; ++k) {
+            if (k + 1 < 64 / kAhead) gather((k + 1) * kAhead, vbuf[(k + 1) & 1]);
+            consume(k * kAhead, vbuf[k & 1]);
         }
     }
 
@@ -330,7 +356,7 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
                 l_anchor[h] *= alpha;
             }
             raise_ref(h, s[h]);
-            pw[h] = fast_exp2(s[h] - m_ref[h]);
+            pw[h] = fast_exp2(s[h] - m_ref[h] + kPShift12);
             l_anchor[h] += pw[h];
         }
         add_value(pw, v);
@@ -408,7 +434,9 @@ D12Plan d12_plan(const Geom& g, int64_t N)
     return pl;
 }
 
-constexpr size_t kD12Lds = (size_t)kM12 * kC12 * 8 + 3 * 1024 * 4 + kNH * kD * 2 + 64 * 4 + 16 * 4;
+constexpr size_t kD12Lds = (size_t)kM12 * kC12 * 8 + 3 * 1024 * 4 + kNH * kD * 2 + 64 * 4 + 16 * 4 +
+                           (size_t)kW12 * 64 * 8 + (size_t)kW12 * 256 * 2;
+static_assert(kD12Lds <= 160 * 1024, "LDS budget");
 
 }  // namespace
 

@@ -44,6 +44,8 @@ _TENSOR_ID = {
     "win_rows_v": 18,
     "new_k": 19,
     "new_v": 20,
+    "cb12_k": 21,
+    "cb12_v": 22,
 }
 
 
