@@ -91,8 +91,9 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     half_t* s_q = (half_t*)(s_pv + 1024);                              // [4][128]
     float* s_red = (float*)(s_q + kNH * kD);                           // 64 floats of scratch
     int* s_misc = (int*)(s_red + 64);                                  // 16 ints
-    half4_t* s_pw = (half4_t*)(s_misc + 16) + (threadIdx.x >> 6) * 64; // this wave's tile: four heads' weights per token
-    uint16_t* s_vc = (uint16_t*)((half4_t*)(s_misc + 16) + kW12 * 64) + (threadIdx.x >> 6) * 256;   // [4][64] V codes
+    // this wave's tile: for each pair of tokens (2j, 2j+1) the four heads' weights as four half2 {P_h(2j), P_h(2j+1)}
+    half_t* s_pw = (half_t*)(s_misc + 16) + (threadIdx.x >> 6) * 256;
+    uint16_t* s_vc = (uint16_t*)((half_t*)(s_misc + 16) + kW12 * 256) + (threadIdx.x >> 6) * 256;   // [4][64] V codes
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // KV head g on XCD g mod 8: workgroup ids go to the XCDs round-robin
     const int g = blockIdx.x % p.Hkv;
@@ -265,7 +266,7 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         const bool masked = tok >= t1 || mbit != 0u;
         float s[kNH];
         lut_scores(klo, khi, s);
-        half4_t pw_h;
+        half_t pw_h[kNH];
 #pragma unroll
         for (int h = 0; h < kNH; ++h) {
             const float sh = masked ? kNegBig : s[h];
@@ -276,7 +277,8 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         }
         // hand the tile to the value phase through the wave's own LDS area (LDS operations of one wave stay in order)
         __builtin_amdgcn_wave_barrier();
-        s_pw[lane] = pw_h;
+#pragma unroll
+        for (int h = 0; h < kNH; ++h) s_pw[(lane >> 1) * 8 + 2 * h + (lane & 1)] = pw_h[h];
 #pragma unroll
         for (int m = 0; m < kM12; ++m) s_vc[m * 64 + lane] = (uint16_t)code12(vlo, vhi, m);
         __builtin_amdgcn_wave_barrier();
@@ -295,15 +297,17 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
                 }
             }
         };
+        // two tokens per step: acc[h][ch] += P_h(t) v_ch(t) + P_h(t+1) v_ch(t+1) is one v_dot2_f32_f16
         auto consume = [&](int j0, const half2_t (&src)[kAhead]) {
 #pragma unroll
-            for (int jj = 0; jj < kAhead; ++jj) {
-                const half4_t pj = s_pw[j0 + jj];                      // same address in every lane: a broadcast read
-                const float v0 = (float)src[jj][0], v1 = (float)src[jj][1];
+            for (int jj = 0; jj < kAhead; jj += 2) {
+                const half8_t pj = *(const half8_t*)(s_pw + (j0 + jj) * 4);     // same address in every lane: a broadcast read
+                const half2_t c0 = {src[jj][0], src[jj + 1][0]}, c1 = {src[jj][1], src[jj + 1][1]};
 #pragma unroll
                 for (int h = 0; h < kNH; ++h) {
-                    acc[h][0] = fmaf((float)pj[h], v0, acc[h][0]);
-                    acc[h][1] = fmaf((float)pj[h], v1, acc[h][1]);
+                    const half2_t ph = {pj[2 * h], pj[2 * h + 1]};
+                    acc[h][0] = __builtin_amdgcn_fdot2(ph, c0, acc[h][0], false);
+                    acc[h][1] = __builtin_amdgcn_fdot2(ph, c1, acc[h][1], false);
                 }
             }
         };
