@@ -11,8 +11,8 @@
 //              64-token tile.  Then the wave walks the tile's tokens one by one: every lane owns two output
 //              channels, fetches them from the token's V centroids (one 4-byte gather per lane) and adds
 //              P_h * v for the four heads.  Anchored tokens carry weight zero here.
-//   anchors    tokens of the range with an FP16 K row or V row, one per wave at a time: score from the FP16 row
-//              (or from the table), value from the FP16 row (or from the centroids).
+//   anchors    the list entries of the range form tiles of their own (lane = entry): score from the FP16 row (or
+//              from the table), then the same value phase with the FP16 row (or the centroids) as the source.
 //   merge      waves through LDS, workgroups through a partial (max, sum, accumulator) per head and a second
 //              small kernel.
 #include "common.h"
@@ -204,12 +204,11 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     }
     __syncthreads();
 
-    // ---- stream ------------------------------------------------------------------------------------------------
+    // ---- per-wave state and the helpers shared by the stream and the anchor tiles
     const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * 6;
     const uint8_t* cv = p.codes_v + (int64_t)bg * p.N_cap * 6;
     const half_t* cbv = p.cb_v + (int64_t)g * kM12 * kC12 * kD12;
     const int my_m = lane >> 4;                                        // the lane's two output channels are 2 lane, 2 lane + 1
-    const half_t* cbv_lane = cbv + (int64_t)my_m * kC12 * kD12 + 2 * (lane & 15);
     const char* cbv_bytes = (const char*)cbv;
     const uint32_t lane_off = (uint32_t)((my_m * kC12 * kD12 + 2 * (lane & 15)) * 2);   // byte offset of the lane's channels
     float m_ref[kNH], l_lane[kNH], acc[kNH][2];
@@ -234,15 +233,6 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
 #pragma unroll
         for (int h = 0; h < kNH; ++h) s[h] = (float)sum[h] * lut_q[h];
     };
-    // one token's contribution: weights pw (uniform over the wave), value channels 2 lane, 2 lane + 1 in v
-    auto add_value = [&](const float (&pw)[kNH], half2_t v) {
-        const float v0 = (float)v[0], v1 = (float)v[1];
-#pragma unroll
-        for (int h = 0; h < kNH; ++h) {
-            acc[h][0] = fmaf(pw[h], v0, acc[h][0]);
-            acc[h][1] = fmaf(pw[h], v1, acc[h][1]);
-        }
-    };
     // move the wave's reference of head h to at least `cand` (uniform); returns nothing, rescales the running state
     auto raise_ref = [&](int h, float cand) {
         if (cand > m_ref[h]) {
@@ -254,6 +244,52 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         }
     };
 
+    // value phase: the wave walks a tile's tokens; every lane gathers its two channels of the token's V row
+    // (16 tokens in flight) and adds P_h v for the four heads, two tokens per v_dot2_f32_f16:
+    // acc[h][ch] += P_h(t) v_ch(t) + P_h(t+1) v_ch(t+1)
+    constexpr int kAhead = 16;
+    auto gather = [&](int j0, half2_t (&dst)[kAhead]) {               // stream tiles: centroid of the lane's sub-space
+#pragma unroll
+        for (int j4 = 0; j4 < kAhead; j4 += 4) {
+            const uint2_t c4 = *(const uint2_t*)(s_vc + my_m * 64 + j0 + j4);      // four tokens' codes
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t code = (c4[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                dst[j4 + e] = *(const half2_t*)(cbv_bytes + (lane_off + code * (uint32_t)(kD12 * 2)));
+            }
+        }
+    };
+    auto consume = [&](int j0, const half2_t (&src)[kAhead]) {
+#pragma unroll
+        for (int jj = 0; jj < kAhead; jj += 2) {
+            const half8_t pj = *(const half8_t*)(s_pw + (j0 + jj) * 4);     // same address in every lane: a broadcast read
+            const half2_t c0 = {src[jj][0], src[jj + 1][0]}, c1 = {src[jj][1], src[jj + 1][1]};
+#pragma unroll
+            for (int h = 0; h < kNH; ++h) {
+                const half2_t ph = {pj[2 * h], pj[2 * h + 1]};
+                acc[h][0] = __builtin_amdgcn_fdot2(ph, c0, acc[h][0], false);
+                acc[h][1] = __builtin_amdgcn_fdot2(ph, c1, acc[h][1], false);
+            }
+        }
+    };
+    // online softmax of one tile: raises the wave's references, adds the weights to the lane sums and leaves the
+    // four heads' weights of every token (fp16, scaled by 2^12) in the wave's LDS area, paired for the dot products
+    auto tile_weights = [&](const float (&sc)[kNH], bool off) {
+        half_t pw_h[kNH];
+#pragma unroll
+        for (int h = 0; h < kNH; ++h) {
+            const float sh = off ? kNegBig : sc[h];
+            raise_ref(h, wave_max(sh));
+            const float pw = fast_exp2(sh - m_ref[h] + kPShift12);     // 0 for switched-off lanes, at most 2^12
+            l_lane[h] += pw;
+            pw_h[h] = (half_t)pw;
+        }
+        __builtin_amdgcn_wave_barrier();                               // LDS operations of one wave stay in order
+#pragma unroll
+        for (int h = 0; h < kNH; ++h) s_pw[(lane >> 1) * 8 + 2 * h + (lane & 1)] = pw_h[h];
+    };
+
+    // ---- stream ------------------------------------------------------------------------------------------------
     const int64_t n_tiles = (t1 - t0 + 63) >> 6;
     for (int64_t tile = wave; tile < n_tiles; tile += kW12) {
         const int64_t tok = t0 + tile * 64 + lane;
@@ -266,51 +302,13 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         const bool masked = tok >= t1 || mbit != 0u;
         float s[kNH];
         lut_scores(klo, khi, s);
-        half_t pw_h[kNH];
-#pragma unroll
-        for (int h = 0; h < kNH; ++h) {
-            const float sh = masked ? kNegBig : s[h];
-            raise_ref(h, wave_max(sh));
-            const float pw = fast_exp2(sh - m_ref[h] + kPShift12);     // 0 for masked lanes, at most 2^12
-            l_lane[h] += pw;
-            pw_h[h] = (half_t)pw;
-        }
-        // hand the tile to the value phase through the wave's own LDS area (LDS operations of one wave stay in order)
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int h = 0; h < kNH; ++h) s_pw[(lane >> 1) * 8 + 2 * h + (lane & 1)] = pw_h[h];
+        tile_weights(s, masked);
 #pragma unroll
         for (int m = 0; m < kM12; ++m) s_vc[m * 64 + lane] = (uint16_t)code12(vlo, vhi, m);
         __builtin_amdgcn_wave_barrier();
         // the tile's tokens one by one: every lane gathers its two channels of the token's centroid of sub-space my_m;
         // gathers run 16 tokens ahead of their use
-        constexpr int kAhead = 16;
         half2_t vbuf[2][kAhead];
-        auto gather = [&](int j0, half2_t (&dst)[kAhead]) {
-#pragma unroll
-            for (int j4 = 0; j4 < kAhead; j4 += 4) {
-                const uint2_t c4 = *(const uint2_t*)(s_vc + my_m * 64 + j0 + j4);      // four tokens' codes
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t code = (c4[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-                    dst[j4 + e] = *(const half2_t*)(cbv_bytes + (lane_off + code * (uint32_t)(kD12 * 2)));
-                }
-            }
-        };
-        // two tokens per step: acc[h][ch] += P_h(t) v_ch(t) + P_h(t+1) v_ch(t+1) is one v_dot2_f32_f16
-        auto consume = [&](int j0, const half2_t (&src)[kAhead]) {
-#pragma unroll
-            for (int jj = 0; jj < kAhead; jj += 2) {
-                const half8_t pj = *(const half8_t*)(s_pw + (j0 + jj) * 4);     // same address in every lane: a broadcast read
-                const half2_t c0 = {src[jj][0], src[jj + 1][0]}, c1 = {src[jj][1], src[jj + 1][1]};
-#pragma unroll
-                for (int h = 0; h < kNH; ++h) {
-                    const half2_t ph = {pj[2 * h], pj[2 * h + 1]};
-                    acc[h][0] = __builtin_amdgcn_fdot2(ph, c0, acc[h][0], false);
-                    acc[h][1] = __builtin_amdgcn_fdot2(ph, c1, acc[h][1], false);
-                }
-            }
-        };
         gather(0, vbuf[0]);
 #pragma unroll
         for (int k = 0; k < 64 / kAhead; ++k) {
@@ -319,51 +317,82 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         }
     }
 
-    // ---- anchors: tokens of the range with an FP16 K row and/or V row, one per wave at a time ----------------
-    float l_anchor[kNH] = {0.f, 0.f, 0.f, 0.f};                        // uniform over the wave
-    float qf[kNH][2];
-#pragma unroll
-    for (int h = 0; h < kNH; ++h) { qf[h][0] = (float)s_q[h * kD + 2 * lane]; qf[h][1] = (float)s_q[h * kD + 2 * lane + 1]; }
+    // ---- anchors: the entries of the K list and of the V list that fall into the range form tiles of 64 of their
+    // own (lane = entry).  A K entry's score is q . FP16 row, computed by its lane from the row's 16 chunks; a V entry
+    // that is not K-anchored scores from the table; a V entry that is also in the K list was handled there.  The value
+    // phase is the stream's, with the source of every token (centroid or FP16 row) passed through LDS as a byte offset
+    // whose top bit selects the FP16 rows, 32 tokens at a time.  (Anchor tiles come after the stream: with the anchor
+    // code first, or with both kinds of tile handed out by one counter, the stream slowed down by more than the
+    // overlap gained.)
     const int n_ka = hi_k - lo_k, n_va = hi_v - lo_v;
-    for (int it = wave; it < n_ka + n_va; it += kW12) {
-        const bool from_k = it < n_ka;
-        const int i = from_k ? lo_k + it : lo_v + (it - n_ka);
-        const int tok = from_k ? idx_k[i] : idx_v[i];
+    const int n_at = (n_ka + n_va + 63) >> 6;
+    const char* rows_v_bytes = (const char*)p.rows_v;
+    uint32_t* s_src = (uint32_t*)s_vc;                                 // [4 sub-spaces][32 tokens]
+    for (int at = wave; at < n_at; at += kW12) {
+        const int it = at * 64 + lane;
+        const bool from_k = it < n_ka, from_v = !from_k && it < n_ka + n_va;
+        int i = 0, tok = (int)t0;                                      // a lane without an entry: token t0 with weight 0
+        if (from_k) { i = lo_k + it; tok = idx_k[i]; }
+        if (from_v) { i = lo_v + (it - n_ka); tok = idx_v[i]; }
         const int rel = tok - (int)t0;
-        const bool in_k = (s_mk[rel >> 5] >> (rel & 31)) & 1u, in_v = (s_mv[rel >> 5] >> (rel & 31)) & 1u;
-        if (!from_k && in_k) continue;                                 // handled as a K-list entry
-        float s[kNH];
-        if (from_k) {                                                  // score from the FP16 key row
-            const half2_t kr = *(const half2_t*)(p.rows_k + ((int64_t)bg * p.k_k + i) * kD + 2 * lane);
+        const bool in_k = (s_mk[rel >> 5] >> (rel & 31)) & 1u;
+        const bool in_v = (from_k || from_v) && ((s_mv[rel >> 5] >> (rel & 31)) & 1u);
+        const bool active = from_k || (from_v && !in_k);
+        float s[kNH] = {0.f, 0.f, 0.f, 0.f};
+        if (from_k) {
+            const half_t* row = p.rows_k + ((int64_t)bg * p.k_k + i) * kD;
+#pragma unroll 4
+            for (int c = 0; c < kD / 8; ++c) {
+                const half8_t kr = *(const half8_t*)(row + 8 * c);
 #pragma unroll
-            for (int h = 0; h < kNH; ++h)
-                s[h] = wave_sum(fmaf(qf[h][0], (float)kr[0], qf[h][1] * (float)kr[1])) * p.c1;
+                for (int h = 0; h < kNH; ++h) s[h] = dot8f(kr, *(const half8_t*)(s_q + h * kD + 8 * c), s[h]);
+            }
+#pragma unroll
+            for (int h = 0; h < kNH; ++h) s[h] *= p.c1;
         } else {
             uint32_t klo, khi;
             load6(ck, tok, klo, khi);
             lut_scores(klo, khi, s);
         }
-        half2_t v;
-        if (in_v) {                                                    // value from the FP16 row: its place in the V list
+        uint32_t voff[kM12];                                           // byte offset of the token's 64 bytes per sub-space
+        if (in_v) {
             const int pos = from_k ? lo_v + (int)(s_pv[rel >> 5] + __popc(s_mv[rel >> 5] & ((1u << (rel & 31)) - 1u))) : i;
-            v = *(const half2_t*)(p.rows_v + ((int64_t)bg * p.k_v + pos) * kD + 2 * lane);
+#pragma unroll
+            for (int m = 0; m < kM12; ++m)
+                voff[m] = 0x80000000u | (uint32_t)((((int64_t)bg * p.k_v + pos) * kD + kD12 * m) * 2);
         } else {
             uint32_t vlo, vhi;
             load6(cv, tok, vlo, vhi);
-            v = *(const half2_t*)(cbv_lane + (int64_t)code12(vlo, vhi, my_m) * kD12);
-        }
-        float pw[kNH];
 #pragma unroll
-        for (int h = 0; h < kNH; ++h) {
-            if (s[h] > m_ref[h]) {
-                const float alpha = fast_exp2(m_ref[h] - s[h]);
-                l_anchor[h] *= alpha;
-            }
-            raise_ref(h, s[h]);
-            pw[h] = fast_exp2(s[h] - m_ref[h] + kPShift12);
-            l_anchor[h] += pw[h];
+            for (int m = 0; m < kM12; ++m) voff[m] = (uint32_t)((m * kC12 + (int)code12(vlo, vhi, m)) * kD12 * 2);
         }
-        add_value(pw, v);
+        tile_weights(s, !active);
+        auto gather_a = [&](int j0, int jb, half2_t (&dst)[kAhead]) {  // tokens j0 .. j0 + 15 of the half tile at jb
+#pragma unroll
+            for (int j4 = 0; j4 < kAhead; j4 += 4) {
+                const uint4_t o4 = *(const uint4_t*)(s_src + my_m * 32 + (j0 - jb) + j4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const char* base = (o4[e] & 0x80000000u) ? rows_v_bytes : cbv_bytes;
+                    dst[j4 + e] = *(const half2_t*)(base + (o4[e] & 0x7FFFFFFFu) + 4 * (lane & 15));
+                }
+            }
+        };
+#pragma unroll 1
+        for (int jb = 0; jb < 64; jb += 32) {
+            __builtin_amdgcn_wave_barrier();
+            if ((lane >> 5) == (jb >> 5)) {
+#pragma unroll
+                for (int m = 0; m < kM12; ++m) s_src[m * 32 + (lane & 31)] = voff[m];
+            }
+            __builtin_amdgcn_wave_barrier();
+            half2_t vbuf[2][kAhead];
+            gather_a(jb, jb, vbuf[0]);
+            gather_a(jb + kAhead, jb, vbuf[1]);
+            consume(jb, vbuf[0]);
+            consume(jb + kAhead, vbuf[1]);
+        }
+
     }
 
     // ---- merge the waves, write the workgroup's partial -------------------------------------------------------
@@ -373,7 +402,7 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     float* s_acc = s_l + kW12 * kNH;                                   // [waves][4][128]
 #pragma unroll
     for (int h = 0; h < kNH; ++h) {
-        const float lw = wave_sum(l_lane[h]) + l_anchor[h];
+        const float lw = wave_sum(l_lane[h]);
         if (lane == 0) { s_m[wave * kNH + h] = m_ref[h]; s_l[wave * kNH + h] = lw; }
         s_acc[(wave * kNH + h) * kD + 2 * lane] = acc[h][0];
         s_acc[(wave * kNH + h) * kD + 2 * lane + 1] = acc[h][1];
@@ -454,6 +483,7 @@ hipError_t launch_decode12(const Geom& g, const DecodeArgs& a, void* ws, hipStre
     }();
     if (setup != hipSuccess) return setup;
     if ((int64_t)g.B * g.Hkv * pl.S > 0x7fffffffLL) return hipErrorInvalidValue;
+    if ((int64_t)g.B * g.Hkv * a.k_v * kD * 2 >= 0x7fffffffLL) return hipErrorInvalidValue;   // 31-bit byte offsets into rows_v
     D12Params p;
     p.q = a.q; p.codes_k = a.codes_k; p.codes_v = a.codes_v; p.cb_k = a.cb_k; p.cb_v = a.cb_v;
     p.idx_k = a.idx_k; p.idx_v = a.idx_v; p.rows_k = a.rows_k; p.rows_v = a.rows_v;
