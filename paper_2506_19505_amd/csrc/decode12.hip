@@ -208,12 +208,21 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * 6;
     const uint8_t* cv = p.codes_v + (int64_t)bg * p.N_cap * 6;
     const half_t* cbv = p.cb_v + (int64_t)g * kM12 * kC12 * kD12;
-    const int my_m = lane >> 4;                                        // the lane's two output channels are 2 lane, 2 lane + 1
+    // Value phase roles: a group of 16 lanes (grp) takes the tokens t with t mod 4 == grp of a tile, four tokens per
+    // gather instruction; lane li of the group owns output channels 8 li .. 8 li + 7, i.e. 16 bytes of the centroid of
+    // sub-space li / 4.  The four groups' accumulators are added up once, before the merge.
+    const int grp = lane >> 4, li = lane & 15;
+    const int my_m = li >> 2;
     const char* cbv_bytes = (const char*)cbv;
-    const uint32_t lane_off = (uint32_t)((my_m * kC12 * kD12 + 2 * (lane & 15)) * 2);   // byte offset of the lane's channels
-    float m_ref[kNH], l_lane[kNH], acc[kNH][2];
+    const uint32_t lane_off = (uint32_t)((my_m * kC12 * kD12 + 8 * (li & 3)) * 2);      // byte offset of the lane's channels
+    float m_ref[kNH], l_lane[kNH], acc[kNH][8];
 #pragma unroll
-    for (int h = 0; h < kNH; ++h) { m_ref[h] = kEmptyRef12; l_lane[h] = 0.f; acc[h][0] = acc[h][1] = 0.f; }
+    for (int h = 0; h < kNH; ++h) {
+        m_ref[h] = kEmptyRef12;
+        l_lane[h] = 0.f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[h][c] = 0.f;
+    }
 
     auto load6 = [&](const uint8_t* base, int64_t tok, uint32_t& lo, uint32_t& hi) {
         const uint16_t* s = (const uint16_t*)(base + tok * 6);
@@ -238,37 +247,36 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         if (cand > m_ref[h]) {
             const float alpha = fast_exp2(m_ref[h] - cand);
             l_lane[h] *= alpha;
-            acc[h][0] *= alpha;
-            acc[h][1] *= alpha;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[h][c] *= alpha;
             m_ref[h] = cand;
         }
     };
 
-    // value phase: the wave walks a tile's tokens; every lane gathers its two channels of the token's V row
-    // (16 tokens in flight) and adds P_h v for the four heads, two tokens per v_dot2_f32_f16:
-    // acc[h][ch] += P_h(t) v_ch(t) + P_h(t+1) v_ch(t+1)
-    constexpr int kAhead = 16;
-    auto gather = [&](int j0, half2_t (&dst)[kAhead]) {               // stream tiles: centroid of the lane's sub-space
+    // value phase.  Token t of a tile is step t / 4 of group t mod 4.  A gather covers four steps (16 tokens of the
+    // wave); two steps are consumed together: acc[h][ch] += P_h(t) v_ch(t) + P_h(t + 4) v_ch(t + 4) is one
+    // v_dot2_f32_f16.  LDS hand-off layouts: codes [sub-space][group][step], weights [group][step pair][head] as half2.
+    constexpr int kSteps = 4;                                          // steps per gather batch
+    auto gather = [&](int s0, half8_t (&dst)[kSteps]) {               // stream tiles: centroid of the lane's sub-space
+        const uint2_t c4 = *(const uint2_t*)(s_vc + my_m * 64 + grp * 16 + s0);    // four steps' codes
 #pragma unroll
-        for (int j4 = 0; j4 < kAhead; j4 += 4) {
-            const uint2_t c4 = *(const uint2_t*)(s_vc + my_m * 64 + j0 + j4);      // four tokens' codes
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t code = (c4[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-                dst[j4 + e] = *(const half2_t*)(cbv_bytes + (lane_off + code * (uint32_t)(kD12 * 2)));
-            }
+        for (int e = 0; e < kSteps; ++e) {
+            const uint32_t code = (c4[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+            dst[e] = *(const half8_t*)(cbv_bytes + (lane_off + code * (uint32_t)(kD12 * 2)));
         }
     };
-    auto consume = [&](int j0, const half2_t (&src)[kAhead]) {
+    auto consume = [&](int s0, const half8_t (&src)[kSteps]) {
 #pragma unroll
-        for (int jj = 0; jj < kAhead; jj += 2) {
-            const half8_t pj = *(const half8_t*)(s_pw + (j0 + jj) * 4);     // same address in every lane: a broadcast read
-            const half2_t c0 = {src[jj][0], src[jj + 1][0]}, c1 = {src[jj][1], src[jj + 1][1]};
+        for (int e = 0; e < kSteps; e += 2) {
+            const half8_t pj = *(const half8_t*)(s_pw + (grp * 8 + ((s0 + e) >> 1)) * 8);   // the group's step pair
 #pragma unroll
-            for (int h = 0; h < kNH; ++h) {
-                const half2_t ph = {pj[2 * h], pj[2 * h + 1]};
-                acc[h][0] = __builtin_amdgcn_fdot2(ph, c0, acc[h][0], false);
-                acc[h][1] = __builtin_amdgcn_fdot2(ph, c1, acc[h][1], false);
+            for (int c = 0; c < 8; ++c) {
+                const half2_t vc = {src[e][c], src[e + 1][c]};
+#pragma unroll
+                for (int h = 0; h < kNH; ++h) {
+                    const half2_t ph = {pj[2 * h], pj[2 * h + 1]};
+                    acc[h][c] = __builtin_amdgcn_fdot2(ph, vc, acc[h][c], false);
+                }
             }
         }
     };
@@ -286,7 +294,8 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         }
         __builtin_amdgcn_wave_barrier();                               // LDS operations of one wave stay in order
 #pragma unroll
-        for (int h = 0; h < kNH; ++h) s_pw[(lane >> 1) * 8 + 2 * h + (lane & 1)] = pw_h[h];
+        for (int h = 0; h < kNH; ++h)                                  // token = lane: group lane % 4, step lane / 4
+            s_pw[((lane & 3) * 8 + (lane >> 3)) * 8 + 2 * h + ((lane >> 2) & 1)] = pw_h[h];
     };
 
     // ---- stream ------------------------------------------------------------------------------------------------
@@ -304,16 +313,15 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         lut_scores(klo, khi, s);
         tile_weights(s, masked);
 #pragma unroll
-        for (int m = 0; m < kM12; ++m) s_vc[m * 64 + lane] = (uint16_t)code12(vlo, vhi, m);
+        for (int m = 0; m < kM12; ++m) s_vc[m * 64 + (lane & 3) * 16 + (lane >> 2)] = (uint16_t)code12(vlo, vhi, m);
         __builtin_amdgcn_wave_barrier();
-        // the tile's tokens one by one: every lane gathers its two channels of the token's centroid of sub-space my_m;
-        // gathers run 16 tokens ahead of their use
-        half2_t vbuf[2][kAhead];
+        // 16 steps of four tokens; the gathers of the next four steps fly while four are consumed
+        half8_t vbuf[2][kSteps];
         gather(0, vbuf[0]);
 #pragma unroll
-        for (int k = 0; k < 64 / kAhead; ++k) {
-            if (k + 1 < 64 / kAhead) gather((k + 1) * kAhead, vbuf[(k + 1) & 1]);
-            consume(k * kAhead, vbuf[k & 1]);
+        for (int k = 0; k < 16 / kSteps; ++k) {
+            if (k + 1 < 16 / kSteps) gather((k + 1) * kSteps, vbuf[(k + 1) & 1]);
+            consume(k * kSteps, vbuf[k & 1]);
         }
     }
 
@@ -367,32 +375,29 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
             for (int m = 0; m < kM12; ++m) voff[m] = (uint32_t)((m * kC12 + (int)code12(vlo, vhi, m)) * kD12 * 2);
         }
         tile_weights(s, !active);
-        auto gather_a = [&](int j0, int jb, half2_t (&dst)[kAhead]) {  // tokens j0 .. j0 + 15 of the half tile at jb
+        // half tiles of 32 entries: sources [sub-space][group][step], 8 steps per group
+        auto gather_a = [&](int s0, half8_t (&dst)[kSteps]) {
+            const uint4_t o4 = *(const uint4_t*)(s_src + my_m * 32 + grp * 8 + s0);
 #pragma unroll
-            for (int j4 = 0; j4 < kAhead; j4 += 4) {
-                const uint4_t o4 = *(const uint4_t*)(s_src + my_m * 32 + (j0 - jb) + j4);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const char* base = (o4[e] & 0x80000000u) ? rows_v_bytes : cbv_bytes;
-                    dst[j4 + e] = *(const half2_t*)(base + (o4[e] & 0x7FFFFFFFu) + 4 * (lane & 15));
-                }
+            for (int e = 0; e < kSteps; ++e) {
+                const char* base = (o4[e] & 0x80000000u) ? rows_v_bytes : cbv_bytes;
+                dst[e] = *(const half8_t*)(base + (o4[e] & 0x7FFFFFFFu) + 16 * (li & 3));
             }
         };
 #pragma unroll 1
         for (int jb = 0; jb < 64; jb += 32) {
             __builtin_amdgcn_wave_barrier();
-            if ((lane >> 5) == (jb >> 5)) {
+            if ((lane >> 5) == (jb >> 5)) {                            // entry = lane: group lane % 4, step (lane % 32) / 4
 #pragma unroll
-                for (int m = 0; m < kM12; ++m) s_src[m * 32 + (lane & 31)] = voff[m];
+                for (int m = 0; m < kM12; ++m) s_src[m * 32 + (lane & 3) * 8 + ((lane & 31) >> 2)] = voff[m];
             }
             __builtin_amdgcn_wave_barrier();
-            half2_t vbuf[2][kAhead];
-            gather_a(jb, jb, vbuf[0]);
-            gather_a(jb + kAhead, jb, vbuf[1]);
-            consume(jb, vbuf[0]);
-            consume(jb + kAhead, vbuf[1]);
+            half8_t vbuf[2][kSteps];
+            gather_a(0, vbuf[0]);
+            gather_a(kSteps, vbuf[1]);
+            consume((jb >> 2), vbuf[0]);                               // steps jb / 4 .. of the whole tile's weights
+            consume((jb >> 2) + kSteps, vbuf[1]);
         }
-
     }
 
     // ---- merge the waves, write the workgroup's partial -------------------------------------------------------
@@ -404,8 +409,13 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     for (int h = 0; h < kNH; ++h) {
         const float lw = wave_sum(l_lane[h]);
         if (lane == 0) { s_m[wave * kNH + h] = m_ref[h]; s_l[wave * kNH + h] = lw; }
-        s_acc[(wave * kNH + h) * kD + 2 * lane] = acc[h][0];
-        s_acc[(wave * kNH + h) * kD + 2 * lane + 1] = acc[h][1];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {                                  // the four groups hold shares of the same channels
+            float a = acc[h][c];
+            a += __shfl_xor(a, 16, 64);
+            a += __shfl_xor(a, 32, 64);
+            if (grp == 0) s_acc[(wave * kNH + h) * kD + 8 * li + c] = a;
+        }
     }
     __syncthreads();
     if (tid < kNH * kD) {
