@@ -4,8 +4,8 @@
 // With 4096 centroids of 32 channels only the q.centroid table of the K side fits LDS (4 sub-spaces x 4096 codes x
 // 4 heads x int16 = 128 KB); the V codebook (1 MB per KV head) stays in L2, which is why workgroup ids are mapped so
 // that KV head g runs on XCD g mod 8 and each XCD's L2 keeps one head's codebook.
-//   prologue   table: 16-bit fixed point with one scale per head (two sweeps over the K codebook: maximum, then
-//              quantise); bitmaps of the K- and V-anchored tokens of the workgroup's token range with a running
+//   prologue   table: a small kernel computes the fp32 scores once per (sequence, KV head); each workgroup takes the
+//              maximum per head and quantises them to 16-bit fixed point with one scale per head into LDS; bitmaps of the K- and V-anchored tokens of the workgroup's token range with a running
 //              count per word, so that "is token t in the V list, and where" is a bit test and a popcount.
 //   stream     lane = token: unpack the four codes, four 8-byte table reads, integer sums, online softmax per
 //              64-token tile.  Then the wave walks the tile's tokens one by one: every lane owns two output
@@ -30,6 +30,8 @@ constexpr int kNH = 4;                   // head slots (G <= 4)
 constexpr int kChunkMax = 32768;         // tokens per workgroup (bitmaps of 1024 words)
 constexpr float kEmptyRef12 = -1.0e4f;   // softmax reference before any token: finite, far above the masked score
 constexpr int kLutMax12 = 32767;
+constexpr int kTabThreads = 256;
+constexpr int kTabBlocks = kM12 * kC12 / (kTabThreads * 4);   // 16 blocks per (sequence, KV head), 4 entries per thread
 constexpr float kPShift12 = 12.f;        // weights are kept scaled by 2^12 so that small ones stay normal in fp16
 
 struct D12Params {
@@ -39,6 +41,8 @@ struct D12Params {
     const int32_t *idx_k, *idx_v;
     const half_t *rows_k, *rows_v;
     float* part;                          // [B][Hq][S][kD + 2]
+    const float4_t* tab;                  // [B][Hkv][4][4096] fp32 scores of the four heads, from d12_table_kernel
+    const float* tab_amax;                // [B][Hkv][kTabBlocks][4] per-block maxima of |score|
     int64_t N, N_cap;
     int k_k, k_v;
     float c1;
@@ -78,6 +82,53 @@ __device__ __forceinline__ uint32_t code12(uint32_t lo, uint32_t hi, int m)
 {
     const uint64_t w = ((uint64_t)hi << 32) | lo;
     return (uint32_t)(w >> (12 * m)) & 0xFFFu;
+}
+
+// fp32 table of c1 q_h . centroid for one (sequence, KV head): every workgroup of the decode kernel that works on this
+// pair needs the same 16384 x 4 values, so they are computed once here (the K codebook is read once instead of twice
+// per decode workgroup) and only quantised into LDS there.
+__global__ __launch_bounds__(kTabThreads) void d12_table_kernel(const half_t* __restrict__ q, const half_t* __restrict__ cb_k,
+                                                                float c1, int Hq, int Hkv, int G, float4_t* __restrict__ tab,
+                                                                float* __restrict__ tab_amax)
+{
+    __shared__ __attribute__((aligned(16))) half_t s_q[kNH * kD];
+    __shared__ float s_red[kTabThreads / 64][kNH];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int bg = blockIdx.x, b = bg / Hkv, g = bg % Hkv;
+    for (int i = tid; i < kNH * kD; i += kTabThreads)
+        s_q[i] = ((i >> 7) < G) ? q[((int64_t)b * Hq + g * G) * kD + i] : (half_t)0.f;
+    __syncthreads();
+    float amax[kNH] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+    for (int k = 0; k < 4; ++k) {
+        const int e = (blockIdx.y * 4 + k) * kTabThreads + tid;        // entry = (sub-space, code)
+        const int m = e / kC12;
+        const half_t* cp = cb_k + ((int64_t)g * kM12 * kC12 + e) * kD12;
+        half8_t cv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) cv[u] = *(const half8_t*)(cp + 8 * u);
+        float4_t o;
+#pragma unroll
+        for (int h = 0; h < kNH; ++h) {
+            float d = 0.f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) d = dot8f(cv[u], *(const half8_t*)(s_q + h * kD + m * kD12 + 8 * u), d);
+            o[h] = d * c1;
+            amax[h] = fmaxf(amax[h], fabsf(o[h]));
+        }
+        tab[(int64_t)bg * kM12 * kC12 + e] = o;
+    }
+#pragma unroll
+    for (int h = 0; h < kNH; ++h) {
+        const float wmax = wave_max(amax[h]);
+        if (lane == 0) s_red[wave][h] = wmax;
+    }
+    __syncthreads();
+    if (tid < kNH) {
+        float a = 0.f;
+        for (int w = 0; w < kTabThreads / 64; ++w) a = fmaxf(a, s_red[w][tid]);
+        tab_amax[((int64_t)bg * kTabBlocks + blockIdx.y) * kNH + tid] = a;
+    }
 }
 
 __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
@@ -125,62 +176,28 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         const int rel = idx_v[i] - (int)t0;
         atomicOr(&s_mv[rel >> 5], 1u << (rel & 31));
     }
-    // table, sweep 1: per-head maximum of |c1 q_h . centroid|; sweep 2: quantise.  Thread t owns entries t + 1024 i.
-    const half_t* cbk = p.cb_k + (int64_t)g * kM12 * kC12 * kD12;
-    float amax[kNH] = {0.f, 0.f, 0.f, 0.f};
-    float inv_q[kNH] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 1
-    for (int sweep = 0; sweep < 2; ++sweep) {
-#pragma unroll 1
-        for (int m = 0; m < kM12; ++m) {
-            half8_t qv[kNH][4];
+    // table: the fp32 scores come from d12_table_kernel; one scale per head from the per-block maxima, then 16-bit
+    // fixed point into LDS.  Thread t owns entries t + 1024 i.
+    float amax[kNH], inv_q[kNH];
 #pragma unroll
-            for (int h = 0; h < kNH; ++h)
+    for (int h = 0; h < kNH; ++h) {
+        float a = 0.f;
+        for (int k = 0; k < kTabBlocks; ++k) a = fmaxf(a, p.tab_amax[((int64_t)bg * kTabBlocks + k) * kNH + h]);
+        amax[h] = a;
+        inv_q[h] = a > 0.f ? (float)kLutMax12 / a : 0.f;
+    }
+    {
+        const float4_t* tb = p.tab + (int64_t)bg * kM12 * kC12;
+#pragma unroll 4
+        for (int e = tid; e < kM12 * kC12; e += kT12) {
+            const float4_t sc = tb[e];
+            int q16[kNH];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) qv[h][u] = *(const half8_t*)(s_q + h * kD + m * kD12 + 8 * u);
-#pragma unroll 1
-            for (int c = tid; c < kC12; c += kT12) {
-                const half_t* cp = cbk + ((int64_t)m * kC12 + c) * kD12;
-                half8_t cv[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) cv[u] = *(const half8_t*)(cp + 8 * u);
-                float s[kNH];
-#pragma unroll
-                for (int h = 0; h < kNH; ++h) {
-                    float d = 0.f;
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) d = dot8f(cv[u], qv[h][u], d);
-                    s[h] = d * p.c1;
-                }
-                if (sweep == 0) {
-#pragma unroll
-                    for (int h = 0; h < kNH; ++h) amax[h] = fmaxf(amax[h], fabsf(s[h]));
-                } else {
-                    int e[kNH];
-#pragma unroll
-                    for (int h = 0; h < kNH; ++h) e[h] = (int)rintf(s[h] * inv_q[h]);
-                    uint2_t w;
-                    w[0] = ((uint32_t)e[0] & 0xFFFFu) | ((uint32_t)e[1] << 16);
-                    w[1] = ((uint32_t)e[2] & 0xFFFFu) | ((uint32_t)e[3] << 16);
-                    s_lut[m * kC12 + c] = w;
-                }
-            }
-        }
-        if (sweep == 0) {
-#pragma unroll
-            for (int h = 0; h < kNH; ++h) {
-                const float wmax = wave_max(amax[h]);
-                if (lane == 0) s_red[wave * kNH + h] = wmax;
-            }
-            __syncthreads();
-#pragma unroll
-            for (int h = 0; h < kNH; ++h) {
-                float a = 0.f;
-                for (int w = 0; w < kW12; ++w) a = fmaxf(a, s_red[w * kNH + h]);
-                amax[h] = a;
-                inv_q[h] = a > 0.f ? (float)kLutMax12 / a : 0.f;
-            }
-            __syncthreads();
+            for (int h = 0; h < kNH; ++h) q16[h] = (int)rintf(sc[h] * inv_q[h]);
+            uint2_t w;
+            w[0] = ((uint32_t)q16[0] & 0xFFFFu) | ((uint32_t)q16[1] << 16);
+            w[1] = ((uint32_t)q16[2] & 0xFFFFu) | ((uint32_t)q16[3] << 16);
+            s_lut[e] = w;
         }
     }
     float lut_q[kNH];                                                  // table quantum per head (log2 units)
@@ -188,6 +205,7 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     for (int h = 0; h < kNH; ++h) lut_q[h] = amax[h] * (1.0f / (float)kLutMax12);
     // V-anchored tokens before each bitmap word (exclusive scan over 1024 words, one word per thread)
     static_assert(kT12 == 1024, "one bitmap word per thread");
+    __syncthreads();                                                   // the bitmaps are complete
     {
         const uint32_t cnt = __popc(s_mv[tid]);
         uint32_t incl = cnt;
@@ -455,7 +473,7 @@ __global__ __launch_bounds__(kD) void decode12_merge(const float* __restrict__ p
 
 struct D12Plan {
     int S, chunk;
-    size_t total;
+    size_t off_part, off_tab, off_amax, total;
 };
 
 D12Plan d12_plan(const Geom& g, int64_t N)
@@ -473,7 +491,11 @@ D12Plan d12_plan(const Geom& g, int64_t N)
     if (S < 1) S = 1;
     pl.S = (int)S;
     pl.chunk = (int)chunk;
-    pl.total = align_up((size_t)g.B * g.Hq * S * (kD + 2) * sizeof(float));
+    size_t off = 0;
+    pl.off_part = off; off += align_up((size_t)g.B * g.Hq * S * (kD + 2) * sizeof(float));
+    pl.off_tab = off;  off += align_up((size_t)g.B * g.Hkv * kM12 * kC12 * sizeof(float4_t));
+    pl.off_amax = off; off += align_up((size_t)g.B * g.Hkv * kTabBlocks * kNH * sizeof(float));
+    pl.total = off;
     return pl;
 }
 
@@ -497,11 +519,16 @@ hipError_t launch_decode12(const Geom& g, const DecodeArgs& a, void* ws, hipStre
     D12Params p;
     p.q = a.q; p.codes_k = a.codes_k; p.codes_v = a.codes_v; p.cb_k = a.cb_k; p.cb_v = a.cb_v;
     p.idx_k = a.idx_k; p.idx_v = a.idx_v; p.rows_k = a.rows_k; p.rows_v = a.rows_v;
-    p.part = (float*)ws; p.N = a.N; p.N_cap = a.N_cap; p.k_k = (int)a.k_k; p.k_v = (int)a.k_v;
+    char* w = (char*)ws;
+    p.part = (float*)(w + pl.off_part); p.tab = (const float4_t*)(w + pl.off_tab); p.tab_amax = (const float*)(w + pl.off_amax);
+    p.N = a.N; p.N_cap = a.N_cap; p.k_k = (int)a.k_k; p.k_v = (int)a.k_v;
     p.c1 = a.scale * kLog2e; p.Hq = g.Hq; p.Hkv = g.Hkv; p.G = g.G; p.S = a.N > 0 ? pl.S : 0; p.chunk = pl.chunk;
-    if (a.N > 0)
+    if (a.N > 0) {
+        hipLaunchKernelGGL(d12_table_kernel, dim3((unsigned)(g.B * g.Hkv), kTabBlocks), dim3(kTabThreads), 0, st, a.q, a.cb_k,
+                           p.c1, g.Hq, g.Hkv, g.G, (float4_t*)(w + pl.off_tab), (float*)(w + pl.off_amax));
         hipLaunchKernelGGL(decode12_kernel, dim3((unsigned)(g.B * g.Hkv * pl.S)), dim3(kT12), kD12Lds, st, p);
-    hipLaunchKernelGGL(decode12_merge, dim3((unsigned)(g.B * g.Hq)), dim3(kD), 0, st, (const float*)ws, p.S, a.out);
+    }
+    hipLaunchKernelGGL(decode12_merge, dim3((unsigned)(g.B * g.Hq)), dim3(kD), 0, st, (const float*)p.part, p.S, a.out);
     return hipGetLastError();
 }
 
