@@ -27,8 +27,8 @@
  *       n_centroids 256, d_sub in {4, 8, 16}: one byte per code (2 / 1 / 0.5 bit per element, the paper's
  *         d4m256 / d8m256 notation, Sec. 4); every entry point supports it.
  *       n_centroids 4096, d_sub 32: 12-bit codes (0.375 bit per element, the d32m4096 point of Sec. 4).
- *         Supported by antkv_encode and antkv_decode_attn (attention only: no scores, no re-selection);
- *         antkv_append_token and antkv_kmeans_step return EUNSUPPORTED.  d_sub 16 with 4096 centroids is
+ *         Supported by antkv_encode, antkv_append_token and antkv_decode_attn (attention only: no scores, no
+ *         re-selection); antkv_kmeans_step returns EUNSUPPORTED.  d_sub 16 with 4096 centroids is
  *         not supported.
  *   - Codebooks: fp16 [Hkv][M][n_centroids][d_sub], separate for K and V; sub-space m covers
  *     channels [m*d_sub, (m+1)*d_sub).

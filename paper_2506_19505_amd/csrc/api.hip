@@ -221,7 +221,6 @@ int antkv_append_token(const antkv_geom* geom, const void* k_new, const void* v_
     Geom g;
     int rc = check_geom(geom, g);
     if (rc) return rc;
-    if (g.C != kC) return ANTKV_EUNSUPPORTED;                    // one-byte codes only
     if (N < 0 || W < 0 || W > N || N + 1 > N_cap || k_k < W || k_v < W) return ANTKV_EINVAL;
     if (W > 64) return ANTKV_EUNSUPPORTED;
     if (g.B == 0) return ANTKV_OK;

@@ -131,3 +131,53 @@ def test_wide_geometry_rejections():
     assert lib.antkv_decode_attn_workspace(ctypes.byref(ok), 100, 0, 0, 0) > 0
     assert lib.antkv_decode_attn_workspace(ctypes.byref(ok), 100, 0, 0, 5) == 0      # no re-selection on 12-bit codes
     assert lib.antkv_kmeans_step_workspace(ctypes.byref(ok)) == 0
+
+
+@pytest.mark.parametrize("W", [8, 0])
+def test_append12_then_decode12(oracle, books, W):
+    """Decode loop on 12-bit codes: append with an FP16 window, then attention, step by step against the oracle."""
+    from gpu_util import NEAR_TIE
+    from workloads import make_decode_query
+    B, Hq, Hkv, N0, k_a = 1, 4, 2, 200, 5
+    T = 2 * W + 3 if W else 4
+    scale = 1 / np.sqrt(128)
+    _, k_all, v_all = make_qkv(99 + W, B, Hq, Hkv, N0 + T, 1, 128)
+    cbk, cbv = books
+    N_cap = N0 + T
+    codes_k = np.zeros((B, Hkv, N_cap, 4), np.int32)
+    codes_v = np.zeros((B, Hkv, N_cap, 4), np.int32)
+    codes_k[:, :, :N0] = oracle.encode(k_all[:, :, :N0], cbk)
+    codes_v[:, :, :N0] = oracle.encode(v_all[:, :, :N0], cbv)
+    anchors = np.arange(3, 3 + 11 * k_a, 11)
+    idx = np.broadcast_to(np.concatenate([anchors, np.arange(N0 - W, N0)]), (B, Hkv, k_a + W)).astype(np.int32).copy()
+    idx_k, idx_v = idx.copy(), idx.copy()
+    rows_k = np.take_along_axis(k_all, idx[..., None].astype(np.int64), axis=2).copy()
+    rows_v = np.take_along_axis(v_all, idx[..., None].astype(np.int64), axis=2).copy()
+    geom = antkv.Geometry(B, Hq, Hkv, D_SUB, n_centroids=C)
+    g = dict(ck=dev(pack12(codes_k)), cv=dev(pack12(codes_v)), cbk=dev(cbk), cbv=dev(cbv),
+             ik=dev(idx_k), rk=dev(rows_k), iv=dev(idx_v), rv=dev(rows_v))
+    N = N0
+    for t in range(T):
+        kn, vn = k_all[:, :, N0 + t], v_all[:, :, N0 + t]
+        N_new, mk, mv = oracle.append_token(kn, vn, N, W, cbk, cbv, codes_k, codes_v, idx_k, rows_k, idx_v, rows_v,
+                                            want_margin=True)
+        N_gpu = antkv.append_token(geom, dev(kn), dev(vn), N, W, g["cbk"], g["cbv"], g["ck"], g["cv"], g["ik"], g["rk"],
+                                   g["iv"], g["rv"])
+        torch.cuda.synchronize()
+        assert N_gpu == N_new
+        pos = N - W
+        for name, got_c, want_c, margin in (("K", g["ck"], codes_k, mk), ("V", g["cv"], codes_v, mv)):
+            got = unpack12(got_c[:, :, pos].cpu().numpy())
+            bad = got != want_c[:, :, pos]
+            assert not (bad & (margin >= NEAR_TIE)).any(), f"step {t}: {name} codes of position {pos} differ"
+            got_c[:, :, pos] = dev(pack12(want_c[:, :, pos]))
+        assert (g["ik"].cpu().numpy() == idx_k).all() and (g["rk"].cpu().numpy() == rows_k).all(), f"step {t}"
+        assert (g["iv"].cpu().numpy() == idx_v).all() and (g["rv"].cpu().numpy() == rows_v).all(), f"step {t}"
+        N = N_new
+        q = make_decode_query(950 + t, B, Hq, 128)
+        out = antkv.decode_attn(geom, dev(q), scale, g["ck"], g["cv"], g["cbk"], g["cbv"], g["ik"], g["rk"], g["iv"],
+                                g["rv"], N=N)
+        want = oracle.decode_attn(q, codes_k[:, :, :N], codes_v[:, :, :N], cbk, cbv, idx_k, rows_k, idx_v, rows_v, scale)
+        err = np.linalg.norm(out.cpu().numpy().astype(np.float64) - want, axis=-1) / np.linalg.norm(want, axis=-1)
+        assert err.max() <= 2e-3, f"step {t}: decode relative L2 {err.max():.3e}"
+    print(f"W={W}: {T} appends + decodes on 12-bit codes ok")
