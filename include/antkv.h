@@ -167,7 +167,7 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
  * no window: the new rows are encoded straight to position N.
  *
  *   k_new, v_new  fp16 [B][Hkv][D], 16-byte aligned
- *   codes_k, codes_v  uint8 [B][Hkv][N_cap][M];  N + 1 <= N_cap
+ *   codes_k, codes_v  uint8 [B][Hkv][N_cap][code_bytes];  N + 1 <= N_cap
  *   idx_k int32 [B][Hkv][k_k], rows_k fp16 [B][Hkv][k_k][D] (16-byte aligned), k_k >= W; likewise idx_v, rows_v, k_v.
  *   0 <= W <= 64, W <= N.
  * All work is enqueued on `stream` in order; nothing else may touch the lists or the codes meanwhile.
@@ -196,7 +196,7 @@ int antkv_prefill_attn(const antkv_geom* geom, const void* q, const void* k, con
                        float scale, void* out, float* row_max, float* row_sum, void* stream);
 
 /*
- * One iteration of the offline token-weighted k-means that learns a codebook (Sec. 3.1, "Offline Token-Aware
+ * One iteration of the offline token-weighted k-means that learns a codebook of 256 centroids (Sec. 3.1, "Offline Token-Aware
  * Centroids Learning"): every sub-vector of x is assigned to its nearest centroid of codebook_in (the same rule as
  * antkv_encode), then each centroid becomes the weighted mean of the sub-vectors assigned to it, over all B
  * sequences, with one weight per token (the paper uses the token's error-propagation factor; any w >= 0 works).
