@@ -249,3 +249,37 @@ def test_decode_graph_replay(oracle):
         assert diff.max() <= 1e-3, f"replay {rep} differs from the eager result: {diff.max():.2e}"
         want = oracle.decode_attn(q_np, c["ck"], c["cv"], c["cbk"], c["cbv"], c["ik"], c["rk"], c["iv"], c["rv"], scale)
         _check_out(got_graph, want, f"graph replay {rep}")
+
+
+def test_decode_random_shapes(oracle):
+    """Twenty seeded random geometries: batch, heads, group size, sub-vector width, context length around tile and
+    split boundaries, anchor counts (including 0, a single one and lists that share tokens), spare capacity."""
+    rng = np.random.default_rng(2024)
+    lengths = [1, 2, 63, 64, 65, 127, 129, 1023, 1024, 1025, 2047, 2049, 3000, 4097, 6000]
+    _, ks, vs = make_qkv(77, 1, 4, 4, 1024, 1, 128)
+    books = {d: (make_codebooks(77, ks, d, 256, "k", max_sample=1024), make_codebooks(77, vs, d, 256, "v", max_sample=1024))
+             for d in (4, 8, 16)}
+    for case in range(20):
+        B, Hkv, G = int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.choice([1, 2, 4]))
+        d = int(rng.choice([4, 8, 16]))
+        N = int(rng.choice(lengths))
+        N_cap = N + int(rng.choice([0, 0, 1, 37]))
+        k_k = int(rng.choice([0, 1, min(N, 5), min(N, max(1, N // 50))]))
+        k_v = int(rng.choice([0, 1, min(N, 9), min(N, max(1, N // 70))]))
+        Hq, M = Hkv * G, 128 // d
+        seed = 500 + case
+        c = dict(q=make_decode_query(seed, B, Hq, 128),
+                 ck=random_codes(seed, "k", B, Hkv, N_cap, M), cv=random_codes(seed, "v", B, Hkv, N_cap, M),
+                 cbk=books[d][0][np.arange(Hkv) % 4], cbv=books[d][1][np.arange(Hkv) % 4],
+                 ik=random_anchor_sets(seed, "k", B, Hkv, N, k_k), iv=random_anchor_sets(seed, "v", B, Hkv, N, k_v),
+                 rk=normal_fp16(seed, "rows_k", (B, Hkv, k_k, 128)), rv=normal_fp16(seed, "rows_v", (B, Hkv, k_v, 128)))
+        if k_k and k_v:                                        # let the two lists share their first entries
+            n_common = min(k_k, k_v, 3)
+            for b in range(B):
+                for g in range(Hkv):
+                    merged = np.union1d(c["iv"][b, g][n_common:], c["ik"][b, g][:n_common])
+                    if merged.size >= k_v:
+                        c["iv"][b, g] = np.sort(merged)[:k_v]
+        geom = antkv.Geometry(B, Hq, Hkv, d)
+        res, want = _run_decode(oracle, c, geom, 1 / np.sqrt(128), N=N)
+        _check_out(res, want, f"case {case}: B{B} Hkv{Hkv} G{G} d{d} N{N}/{N_cap} anchors {k_k}/{k_v}")
