@@ -1,14 +1,18 @@
 // Top-k selection of Anchor Scores (keep the ~1 % highest-scoring tokens in FP16; paper Sec. 3,
 // Fig. 2(b)) and the gather of the selected FP16 rows.
 //
-// Exact radix select on an order-preserving 32-bit key, with two reads of the scores before the emission:
+// Exact radix select on an order-preserving 32-bit key:
 //   1. histogram of the top 11 key bits per row;
-//   2. every workgroup (slice of 8192 scores) finds the bin d0 that holds the k-th largest key, counts its keys in
-//      higher bins and appends its keys of bin d0 (with their positions) to the row's candidate list;
-//   3. one workgroup per row selects the exact k-th largest key tau among the candidates (two more radix rounds
-//      on the remaining 21 bits, in LDS) and adds the candidates' contributions to the per-slice counts of keys
-//      > tau and == tau (a list that overflowed its buffer is replaced by a filtered walk over the row);
-//   4. an ordered emission pass writes the positions of all keys > tau plus the lowest-positioned keys == tau
+//   2. every workgroup (slice of 8192 scores) finds the bin d0 that holds the k-th largest key and counts its keys in
+//      higher bins.  If bin d0 holds few keys (at most N/8 + 4096, the usual case for heavy-tailed scores) the
+//      workgroup appends its keys of that bin, with their positions, to the row's candidate list; otherwise (scores
+//      crowded into a narrow range) it adds them to a second histogram over the next 11 bits;
+//   3. only for rows that took the second branch: the same once more, one level down (count the keys of bin d0
+//      above the second digit d1, list the keys with prefix (d0, d1)); workgroups of other rows return at once;
+//   4. one workgroup per row selects the exact k-th largest key tau among the candidates (radix rounds on the
+//      remaining bits, histograms in LDS) and adds the candidates' share to the per-slice counts of keys > tau and
+//      == tau; a row whose keys agree in 22 bits for more than the list holds is walked by that workgroup instead;
+//   5. an ordered emission pass writes the positions of all keys > tau plus the lowest-positioned keys == tau
 //      needed to reach k, in ascending position order.
 #include "common.h"
 
@@ -94,32 +98,53 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist0(const float* __restri
         for (int64_t i = lo + threadIdx.x; i < hi; i += kTopkThreads) atomicAdd(&lh[float_key(src[i]) >> 21], 1u);
     }
     __syncthreads();
-    uint32_t* hist = ws_hist + row * kBins;
+    uint32_t* hist = ws_hist + row * 2 * kBins;
     for (int i = threadIdx.x; i < kBins; i += kTopkThreads)
         if (lh[i]) atomicAdd(&hist[i], lh[i]);
 }
 
-// per slice: count the keys above bin d0, append the keys of bin d0 to the row's candidate list
+// LEVEL 1: per slice, count the keys above bin d0; list the keys of bin d0, or (crowded bin) histogram their next
+// 11 bits.  LEVEL 2, rows with a crowded bin only: count the keys of bin d0 above the second digit d1 and list the
+// keys with prefix (d0, d1).
+template <int LEVEL>
 __global__ __launch_bounds__(kTopkThreads) void topk_collect(const float* __restrict__ scores,
                                                              const float* __restrict__ scores_b, int rows_a, int64_t N,
-                                                             uint32_t k, const uint32_t* __restrict__ ws_hist,
+                                                             uint32_t k, uint32_t* __restrict__ ws_hist,
                                                              uint32_t* __restrict__ head, uint32_t* __restrict__ counts,
                                                              int n_slices, uint2_t* __restrict__ cand, uint32_t cap)
 {
+    __shared__ uint32_t lh[LEVEL == 1 ? kBins : 1];
     __shared__ uint32_t sh[8];
     __shared__ uint32_t red[2][4];
     __shared__ uint32_t s_base;
     const int64_t row = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t* hist0 = ws_hist + row * 2 * kBins;
+    uint32_t* hist1 = hist0 + kBins;
     uint32_t d0, k_rem;
-    find_digit(ws_hist + row * kBins, kBins, k, d0, k_rem, sh);
+    find_digit(hist0, kBins, k, d0, k_rem, sh);
+    const bool crowded = hist0[d0] > cap;                       // the same for every workgroup of the row
+    uint32_t prefix = d0;                                       // keys that match it are the candidates of this level
+    bool list = !crowded;
+    if (LEVEL == 2) {
+        if (!crowded) return;
+        uint32_t d1;
+        find_digit(hist1, kBins, k_rem, d1, k_rem, sh);
+        prefix = (d0 << 11) | d1;
+        list = hist1[d1] <= cap;
+    }
+    constexpr int kShift = LEVEL == 1 ? 21 : 10;
+    if (LEVEL == 1 && crowded) {
+        for (int i = tid; i < kBins; i += kTopkThreads) lh[i] = 0u;
+        __syncthreads();
+    }
     const int64_t lo = (int64_t)blockIdx.x * kSlice;
     const int64_t hi = (lo + kSlice < N) ? lo + kSlice : N;
     const float* src = row_scores(scores, scores_b, rows_a, row, N);
     constexpr int kPer = kSlice / kTopkThreads;                 // 32 scores per thread, in 8 groups of 4
     uint32_t key[kPer];
     const bool fast = hi - lo == kSlice && (((uintptr_t)(src + lo)) & 15) == 0;
-    // element j of the thread sits at position lo + pos(j); out-of-range elements get key 0 and never qualify
+    // element j of the thread sits at position lo + pos(j)
     auto pos = [&](int j) -> int64_t {
         return fast ? 4 * (tid + kTopkThreads * (j >> 2)) + (j & 3) : (int64_t)tid + (int64_t)kTopkThreads * j;
     };
@@ -138,8 +163,10 @@ __global__ __launch_bounds__(kTopkThreads) void topk_collect(const float* __rest
 #pragma unroll
     for (int j = 0; j < kPer; ++j) {
         const bool in = fast || lo + pos(j) < hi;
-        gt += in && (key[j] >> 21) > d0;
-        eq += in && (key[j] >> 21) == d0;
+        const uint32_t p = key[j] >> kShift;
+        // LEVEL 2 counts only keys of bin d0 (higher bins were counted by LEVEL 1)
+        gt += in && p > prefix && (LEVEL == 1 || (key[j] >> 21) == d0);
+        eq += in && p == prefix;
     }
     // block-wide: total of gt, exclusive prefix of eq
     uint32_t ieq = eq;
@@ -157,21 +184,33 @@ __global__ __launch_bounds__(kTopkThreads) void topk_collect(const float* __rest
     const uint32_t tot_eq = red[1][0] + red[1][1] + red[1][2] + red[1][3];
     if (tid == 0) {
         uint32_t* c = counts + (row * n_slices + blockIdx.x) * 2;
-        c[0] = red[0][0] + red[0][1] + red[0][2] + red[0][3];
-        c[1] = 0u;
-        s_base = tot_eq ? atomicAdd(&head[row * kHeadWords + kHeadCount], tot_eq) : 0u;
+        const uint32_t tot_gt = red[0][0] + red[0][1] + red[0][2] + red[0][3];
+        if (LEVEL == 1) { c[0] = tot_gt; c[1] = 0u; }
+        else c[0] += tot_gt;                                    // this workgroup owns its slice's counters
+        s_base = (list && tot_eq) ? atomicAdd(&head[row * kHeadWords + kHeadCount], tot_eq) : 0u;
     }
     __syncthreads();
-    if (eq == 0) return;
-    uint32_t at = s_base + off_eq;
-    uint2_t* out = cand + row * (int64_t)cap;
+    if (list) {
+        if (eq == 0) return;
+        uint32_t at = s_base + off_eq;
+        uint2_t* out = cand + row * (int64_t)cap;
 #pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-        const bool in = fast || lo + pos(j) < hi;
-        if (in && (key[j] >> 21) == d0) {
-            if (at < cap) out[at] = uint2_t{key[j], (uint32_t)(lo + pos(j))};
-            ++at;
+        for (int j = 0; j < kPer; ++j) {
+            const bool in = fast || lo + pos(j) < hi;
+            if (in && (key[j] >> kShift) == prefix) {
+                if (at < cap) out[at] = uint2_t{key[j], (uint32_t)(lo + pos(j))};
+                ++at;
+            }
         }
+    } else if (LEVEL == 1) {                                    // crowded bin: its next 11 bits go to the second histogram
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const bool in = fast || lo + pos(j) < hi;
+            if (in && (key[j] >> 21) == d0) atomicAdd(&lh[(key[j] >> 10) & 2047u], 1u);
+        }
+        __syncthreads();
+        for (int i = tid; i < kBins; i += kTopkThreads)
+            if (lh[i]) atomicAdd(&hist1[i], lh[i]);
     }
 }
 
@@ -185,13 +224,23 @@ __global__ __launch_bounds__(kResolveThreads) void topk_resolve(const float* __r
                                                              int n_slices, const uint2_t* __restrict__ cand, uint32_t cap)
 {
     __shared__ uint32_t lh[kBins];
+    __shared__ uint32_t lh_eq[kBins];
     __shared__ uint32_t sh[2 + kResolveThreads / 64];
     const int64_t row = blockIdx.x;
     const int tid = threadIdx.x;
-    uint32_t d0, d1, d2, k_rem, need_eq;
-    find_digit<kResolveThreads>(ws_hist + row * kBins, kBins, k, d0, k_rem, sh);
-    const uint32_t n_cand = head[row * kHeadWords + kHeadCount];
-    const bool listed = n_cand <= cap;                           // else the list overflowed: walk the row instead
+    const uint32_t* hist0 = ws_hist + row * 2 * kBins;
+    const uint32_t* hist1 = hist0 + kBins;
+    uint32_t d0, d1 = 0, d2, k_rem, need_eq;
+    find_digit<kResolveThreads>(hist0, kBins, k, d0, k_rem, sh);
+    const bool crowded = hist0[d0] > cap;
+    uint32_t n_cand = hist0[d0];
+    bool listed = true;
+    if (crowded) {
+        find_digit<kResolveThreads>(hist1, kBins, k_rem, d1, k_rem, sh);
+        n_cand = hist1[d1];
+        listed = n_cand <= cap;                                  // else more than the list holds agree in 22 bits: walk the row
+    }
+    const uint32_t prefix22 = (d0 << 11) | d1;
     const uint2_t* list = cand + row * (int64_t)cap;
     const float* src = row_scores(scores, scores_b, rows_a, row, N);
     auto for_each = [&](auto fn) {
@@ -200,26 +249,45 @@ __global__ __launch_bounds__(kResolveThreads) void topk_resolve(const float* __r
         } else {
             for (int64_t i = tid; i < N; i += kResolveThreads) {
                 const uint32_t key = float_key(src[i]);
-                if ((key >> 21) == d0) fn(key, (uint32_t)i);
+                if ((key >> 10) == prefix22) fn(key, (uint32_t)i);
             }
         }
     };
-    for (int i = tid; i < kBins; i += kResolveThreads) lh[i] = 0u;
-    __syncthreads();
-    for_each([&](uint32_t key, uint32_t) { atomicAdd(&lh[(key >> 10) & 2047u], 1u); });
-    __syncthreads();
-    find_digit<kResolveThreads>(lh, kBins, k_rem, d1, k_rem, sh);
+    if (!crowded) {                                              // the candidates share d0 only: round on bits 20..10
+        for (int i = tid; i < kBins; i += kResolveThreads) lh[i] = 0u;
+        __syncthreads();
+        for_each([&](uint32_t key, uint32_t) { atomicAdd(&lh[(key >> 10) & 2047u], 1u); });
+        __syncthreads();
+        find_digit<kResolveThreads>(lh, kBins, k_rem, d1, k_rem, sh);
+    }
     for (int i = tid; i < kBins; i += kResolveThreads) lh[i] = 0u;
     __syncthreads();
     for_each([&](uint32_t key, uint32_t) { if (((key >> 10) & 2047u) == d1) atomicAdd(&lh[key & 1023u], 1u); });
     __syncthreads();
     find_digit<kResolveThreads>(lh, 1024, k_rem, d2, need_eq, sh);
     const uint32_t tau = (d0 << 21) | (d1 << 10) | d2;
+    // the candidates' share of the per-slice counts.  Thousands of candidates fall into a few slices, so they are
+    // counted in LDS first (one global add per slice afterwards) whenever the row has at most 2048 slices.
     uint32_t* c = counts + row * (int64_t)n_slices * 2;
-    for_each([&](uint32_t key, uint32_t i) {
-        if (key > tau) atomicAdd(&c[(i / kSlice) * 2], 1u);
-        else if (key == tau) atomicAdd(&c[(i / kSlice) * 2 + 1], 1u);
-    });
+    if (n_slices <= kBins) {
+        __syncthreads();
+        for (int i = tid; i < kBins; i += kResolveThreads) { lh[i] = 0u; lh_eq[i] = 0u; }
+        __syncthreads();
+        for_each([&](uint32_t key, uint32_t i) {
+            if (key > tau) atomicAdd(&lh[i / kSlice], 1u);
+            else if (key == tau) atomicAdd(&lh_eq[i / kSlice], 1u);
+        });
+        __syncthreads();
+        for (int i = tid; i < n_slices; i += kResolveThreads) {    // this workgroup is the only writer of the row's counts now
+            if (lh[i]) c[i * 2] += lh[i];
+            if (lh_eq[i]) c[i * 2 + 1] += lh_eq[i];
+        }
+    } else {
+        for_each([&](uint32_t key, uint32_t i) {
+            if (key > tau) atomicAdd(&c[(i / kSlice) * 2], 1u);
+            else if (key == tau) atomicAdd(&c[(i / kSlice) * 2 + 1], 1u);
+        });
+    }
     if (tid == 0) {
         head[row * kHeadWords + kHeadTau] = tau;
         head[row * kHeadWords + kHeadNeedEq] = need_eq;
@@ -334,7 +402,7 @@ TopkPlan topk_plan(int64_t rows, int64_t N)
     // the bin of the k-th key usually holds a few percent of a row; a fuller bin makes topk_resolve walk the row
     p.cap = (uint32_t)(N / 8 + 4096);
     size_t off = 0;
-    p.off_hist = off;   off += align_up((size_t)rows * kBins * 4);
+    p.off_hist = off;   off += align_up((size_t)rows * 2 * kBins * 4);            // two histogram levels per row
     p.off_head = off;   off += align_up((size_t)rows * kHeadWords * 4);     // directly after the histograms: zeroed together
     p.off_counts = off; off += align_up((size_t)rows * p.n_slices * 2 * 4);
     p.off_cand = off;   off += align_up((size_t)rows * p.cap * sizeof(uint2_t));
@@ -368,7 +436,9 @@ hipError_t launch_topk2(const float* scores, int32_t* idx, const float* scores_b
     hipLaunchKernelGGL(zero_u32, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, hist, nz);
     dim3 grid(p.n_slices, (unsigned)rows);
     hipLaunchKernelGGL(topk_hist0, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, hist);
-    hipLaunchKernelGGL(topk_collect, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist, head,
+    hipLaunchKernelGGL(topk_collect<1>, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist, head,
+                       counts, p.n_slices, cand, p.cap);
+    hipLaunchKernelGGL(topk_collect<2>, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist, head,
                        counts, p.n_slices, cand, p.cap);
     hipLaunchKernelGGL(topk_resolve, dim3((unsigned)rows), dim3(kResolveThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k,
                        hist, head, counts, p.n_slices, cand, p.cap);
