@@ -1123,7 +1123,6 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
         lse[h] = (PASS == 1) ? s_red[kDaWaves * 8 - 8 + h] : 0.f;
     }
     __syncthreads();
-    const int lo_k = s_misc[0], hi_k = s_misc[1];
     const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * M;
     float m_run[kNH], l_run[kNH];
 #pragma unroll
@@ -1192,7 +1191,9 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
         const int rel = (int)(tok - t0);
         if (!((s_mask[rel >> 5] >> (rel & 31)) & 1u)) consume(s, tok);
     }
-    // ---- K-anchored tokens of the range: the score comes from the FP16 row.  16 lanes per token, 8 channels each.
+    // ---- K-anchored tokens: the score comes from the FP16 row.  16 lanes per token, 8 channels each.  Blocks of 64
+    // list entries are dealt round-robin over the S workgroups of the (sequence, KV head), whatever token range an
+    // entry falls into, so that anchors clustered in one part of the context do not pile up in one workgroup.
     {
         const int sub = lane >> 4, l16 = lane & 15;
         float qv[kNH][8];
@@ -1200,11 +1201,11 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
         for (int h = 0; h < kNH; ++h)
 #pragma unroll
             for (int e = 0; e < 8; ++e) qv[h][e] = s_qf[h * kD + 8 * l16 + e];
-        for (int i0 = lo_k + 4 * wave; i0 < hi_k; i0 += 4 * kDaWaves) {
+        for (int i0 = sp * (4 * kDaWaves) + 4 * wave; i0 < p.k_k; i0 += p.S * (4 * kDaWaves)) {
             const int i = i0 + sub;
-            const bool on = i < hi_k;
+            const bool on = i < p.k_k;
             const int64_t tok = on ? idx_k[i] : t0;
-            const half8_t v = *(const half8_t*)(p.rows_k + ((int64_t)bg * p.k_k + (on ? i : lo_k)) * kD + 8 * l16);
+            const half8_t v = *(const half8_t*)(p.rows_k + ((int64_t)bg * p.k_k + (on ? i : 0)) * kD + 8 * l16);
             float s[kNH];
 #pragma unroll
             for (int h = 0; h < kNH; ++h) {
