@@ -5,14 +5,15 @@
 // 4 heads x int16 = 128 KB); the V codebook (1 MB per KV head) stays in L2, which is why workgroup ids are mapped so
 // that KV head g runs on XCD g mod 8 and each XCD's L2 keeps one head's codebook.
 //   prologue   table: a small kernel computes the fp32 scores once per (sequence, KV head); each workgroup takes the
-//              maximum per head and quantises them to 16-bit fixed point with one scale per head into LDS; bitmaps of the K- and V-anchored tokens of the workgroup's token range with a running
-//              count per word, so that "is token t in the V list, and where" is a bit test and a popcount.
+//              maximum per head and quantises them to 16-bit fixed point with one scale per head into LDS; bitmaps of the K- and V-anchored tokens of the workgroup's token range (the stream skips
+//              them).
 //   stream     lane = token: unpack the four codes, four 8-byte table reads, integer sums, online softmax per
 //              64-token tile.  Then the wave walks the tile's tokens one by one: every lane owns two output
 //              channels, fetches them from the token's V centroids (one 4-byte gather per lane) and adds
 //              P_h * v for the four heads.  Anchored tokens carry weight zero here.
-//   anchors    the list entries of the range form tiles of their own (lane = entry): score from the FP16 row (or
-//              from the table), then the same value phase with the FP16 row (or the centroids) as the source.
+//   anchors    the list entries form tiles of their own (lane = entry), dealt round-robin over the workgroups of the
+//              head: score from the FP16 row (or from the table), then the same value phase with the FP16 row (or
+//              the centroids) as the source.
 //   merge      waves through LDS, workgroups through a partial (max, sum, accumulator) per head and a second
 //              small kernel.
 #include "common.h"
@@ -138,8 +139,7 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     uint2_t* s_lut = (uint2_t*)smem;                                   // [4][4096] entries of 4 x int16 (128 KB)
     uint32_t* s_mk = (uint32_t*)(smem + kM12 * kC12 * 8);              // K-anchored tokens of the range, 1024 words
     uint32_t* s_mv = s_mk + 1024;                                      // V-anchored tokens
-    uint32_t* s_pv = s_mv + 1024;                                      // V-anchored tokens before each word
-    half_t* s_q = (half_t*)(s_pv + 1024);                              // [4][128]
+    half_t* s_q = (half_t*)(s_mv + 1024);                              // [4][128]
     float* s_red = (float*)(s_q + kNH * kD);                           // 64 floats of scratch
     int* s_misc = (int*)(s_red + 64);                                  // 16 ints
     // this wave's tile: for each pair of tokens (2j, 2j+1) the four heads' weights as four half2 {P_h(2j), P_h(2j+1)}
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
 
     // ---- prologue ----------------------------------------------------------------------------------------------
     if (tid < kNH * kD) s_q[tid] = ((tid >> 7) < p.G) ? p.q[((int64_t)b * p.Hq + h0) * kD + tid] : (half_t)0.f;
-    for (int i = tid; i < 3 * 1024; i += kT12) s_mk[i] = 0u;
+    for (int i = tid; i < 2 * 1024; i += kT12) s_mk[i] = 0u;
     if (wave < 4) {                                                    // list ranges that fall into [t0, t1)
         const int32_t* l = (wave < 2) ? idx_k : idx_v;
         const int n = (wave < 2) ? p.k_k : p.k_v;
@@ -203,24 +203,7 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     float lut_q[kNH];                                                  // table quantum per head (log2 units)
 #pragma unroll
     for (int h = 0; h < kNH; ++h) lut_q[h] = amax[h] * (1.0f / (float)kLutMax12);
-    // V-anchored tokens before each bitmap word (exclusive scan over 1024 words, one word per thread)
-    static_assert(kT12 == 1024, "one bitmap word per thread");
-    __syncthreads();                                                   // the bitmaps are complete
-    {
-        const uint32_t cnt = __popc(s_mv[tid]);
-        uint32_t incl = cnt;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const uint32_t nb = __shfl_up(incl, off, 64);
-            if (lane >= off) incl += nb;
-        }
-        if (lane == 63) ((uint32_t*)s_red)[wave] = incl;
-        __syncthreads();
-        uint32_t base = 0;
-        for (int w = 0; w < wave; ++w) base += ((uint32_t*)s_red)[w];
-        s_pv[tid] = base + incl - cnt;
-    }
-    __syncthreads();
+    __syncthreads();                                                   // table and bitmaps are complete
 
     // ---- per-wave state and the helpers shared by the stream and the anchor tiles
     const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * 6;
@@ -343,26 +326,39 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         }
     }
 
-    // ---- anchors: the entries of the K list and of the V list that fall into the range form tiles of 64 of their
-    // own (lane = entry).  A K entry's score is q . FP16 row, computed by its lane from the row's 16 chunks; a V entry
+    // ---- anchors: the entries of the K list followed by those of the V list form tiles of 64 of their own
+    // (lane = entry), dealt round-robin over the S workgroups of the (sequence, KV head) whatever token range an entry
+    // falls into, so that anchors clustered in one part of the context do not pile up in one workgroup; whether a
+    // K-anchored token is also in the V list (and where), or a V-anchored one also in the K list, is a binary search
+    // per lane.  A K entry's score is q . FP16 row, computed by its lane from the row's 16 chunks; a V entry
     // that is not K-anchored scores from the table; a V entry that is also in the K list was handled there.  The value
     // phase is the stream's, with the source of every token (centroid or FP16 row) passed through LDS as a byte offset
     // whose top bit selects the FP16 rows, 32 tokens at a time.  (Anchor tiles come after the stream: with the anchor
     // code first, or with both kinds of tile handed out by one counter, the stream slowed down by more than the
     // overlap gained.)
-    const int n_ka = hi_k - lo_k, n_va = hi_v - lo_v;
+    const int n_ka = p.k_k, n_va = p.k_v;
     const int n_at = (n_ka + n_va + 63) >> 6;
     const char* rows_v_bytes = (const char*)p.rows_v;
     uint32_t* s_src = (uint32_t*)s_vc;                                 // [4 sub-spaces][32 tokens]
-    for (int at = wave; at < n_at; at += kW12) {
+    // position of tok in an ascending list, or -1
+    auto find = [&](const int32_t* __restrict__ list, int n, int tok) -> int {
+        int lo = 0, hi = n;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (list[mid] < tok) lo = mid + 1;
+            else hi = mid;
+        }
+        return (lo < n && list[lo] == tok) ? lo : -1;
+    };
+    for (int at = sp + p.S * wave; at < n_at; at += p.S * kW12) {
         const int it = at * 64 + lane;
         const bool from_k = it < n_ka, from_v = !from_k && it < n_ka + n_va;
         int i = 0, tok = (int)t0;                                      // a lane without an entry: token t0 with weight 0
-        if (from_k) { i = lo_k + it; tok = idx_k[i]; }
-        if (from_v) { i = lo_v + (it - n_ka); tok = idx_v[i]; }
-        const int rel = tok - (int)t0;
-        const bool in_k = (s_mk[rel >> 5] >> (rel & 31)) & 1u;
-        const bool in_v = (from_k || from_v) && ((s_mv[rel >> 5] >> (rel & 31)) & 1u);
+        int pos_v = -1;                                                // the token's place in the V list, if it has one
+        bool in_k = false;
+        if (from_k) { i = it; tok = idx_k[i]; pos_v = find(idx_v, n_va, tok); }
+        if (from_v) { i = it - n_ka; tok = idx_v[i]; pos_v = i; in_k = find(idx_k, n_ka, tok) >= 0; }
+        const bool in_v = pos_v >= 0;
         const bool active = from_k || (from_v && !in_k);
         float s[kNH] = {0.f, 0.f, 0.f, 0.f};
         if (from_k) {
@@ -382,10 +378,9 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         }
         uint32_t voff[kM12];                                           // byte offset of the token's 64 bytes per sub-space
         if (in_v) {
-            const int pos = from_k ? lo_v + (int)(s_pv[rel >> 5] + __popc(s_mv[rel >> 5] & ((1u << (rel & 31)) - 1u))) : i;
 #pragma unroll
             for (int m = 0; m < kM12; ++m)
-                voff[m] = 0x80000000u | (uint32_t)((((int64_t)bg * p.k_v + pos) * kD + kD12 * m) * 2);
+                voff[m] = 0x80000000u | (uint32_t)((((int64_t)bg * p.k_v + pos_v) * kD + kD12 * m) * 2);
         } else {
             uint32_t vlo, vhi;
             load6(cv, tok, vlo, vhi);
@@ -499,7 +494,7 @@ D12Plan d12_plan(const Geom& g, int64_t N)
     return pl;
 }
 
-constexpr size_t kD12Lds = (size_t)kM12 * kC12 * 8 + 3 * 1024 * 4 + kNH * kD * 2 + 64 * 4 + 16 * 4 +
+constexpr size_t kD12Lds = (size_t)kM12 * kC12 * 8 + 2 * 1024 * 4 + kNH * kD * 2 + 64 * 4 + 16 * 4 +
                            (size_t)kW12 * 64 * 8 + (size_t)kW12 * 256 * 2;
 static_assert(kD12Lds <= 160 * 1024, "LDS budget");
 
