@@ -550,7 +550,15 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     // ================================================================================== anchors
     const int n_items = p.k_k + p.k_v;                    // K-anchor entries, then V-anchor entries
     const int n_atiles = (n_items + 31) >> 5;
-    if (n_atiles > 0) {
+    // An anchor tile is a chain of dependent loads (lists, cross membership, rows) that leaves the CU idle if every
+    // wave of the workgroup sits in one at the same time.  So only some waves take anchor tiles, up to five each,
+    // while the others start streaming at once: 2, 4, 8 or all 16 waves, by the number of tiles of the workgroup.
+    int anchor_waves = 2;
+    {
+        const int tiles_wg = (n_atiles + p.S - 1) / p.S;
+        while (anchor_waves < kDaWaves && 5 * anchor_waves < tiles_wg) anchor_waves <<= 1;
+    }
+    if (n_atiles > 0 && (wave & (kDaWaves / anchor_waves - 1)) == 0) {
         const half_t* s_qh = (const half_t*)(smem + L::qh);               // Q as MFMA A operand: row = head
         half_t* s_vrows = (half_t*)s_cw;                                  // [8 items][64 channels] fp16
         int* s_win = (int*)s_cw;                                          // 64 ints in the code-word area
