@@ -295,7 +295,12 @@ def main() -> int:
         fw = lambda i: antkv.decode_attn(wg, w_q, r.scale, w_ck, w_cv, w_cbk, w_cbv, w_ik, w_rk, w_iv, w_rv, workspace=w_ws)
         settle(fw)
         ms_w = timed(100, fw)
-        del w_ck, w_cv
+        w_ws2 = antkv.DecodeWorkspace(wg, r.N, r.k, r.k, r.k, devc)
+        fw2 = lambda i: antkv.decode_attn(wg, w_q, r.scale, w_ck, w_cv, w_cbk, w_cbv, w_ik, w_rk, w_iv, w_rv, k_resel=r.k,
+                                          workspace=w_ws2)
+        settle(fw2)
+        ms_w2 = timed(50, fw2)
+        del w_ck, w_cv, w_ws2
         w_codes = torch.empty((p.B, p.Hkv, p.N, 6), dtype=torch.uint8, device=devc)
         pg12 = antkv.Geometry(p.B, p.Hq, p.Hkv, 32, n_centroids=4096)
         pkd12 = dev(pk)
@@ -304,6 +309,7 @@ def main() -> int:
         ms_e12 = timed(20, fe)
         result["extra"].update({
             "d32m4096_decode_ms": ms_w,
+            "d32m4096_decode_plus_reselection_ms": ms_w2,
             "d32m4096_decode_tokens_per_s": r.B * r.N / (ms_w * 1e-3),
             "d32m4096_decode_L2_gather_GBs": r.B * r.Hkv * r.N * 256 / (ms_w * 1e-3) / 1e9,
             "d32m4096_encode_ms": ms_e12,
@@ -312,7 +318,7 @@ def main() -> int:
                                  f"(B1, N={r.N}, {r.k} anchors per head, random codebooks and codes); encode of cfg3's K rows "
                                  f"({p.B * p.Hkv * p.N} rows)",
         })
-        log(f"d32m4096: decode {ms_w * 1e3:.0f} us, encode of {p.B * p.Hkv * p.N} rows {ms_e12:.2f} ms")
+        log(f"d32m4096: decode {ms_w * 1e3:.0f} us, with re-selection {ms_w2 * 1e3:.0f} us, encode of {p.B * p.Hkv * p.N} rows {ms_e12:.2f} ms")
         del w_codes, pkd12, w_cbk, w_cbv
         torch.cuda.empty_cache()
 

@@ -27,8 +27,8 @@
  *       n_centroids 256, d_sub in {4, 8, 16}: one byte per code (2 / 1 / 0.5 bit per element, the paper's
  *         d4m256 / d8m256 notation, Sec. 4); every entry point supports it.
  *       n_centroids 4096, d_sub 32: 12-bit codes (0.375 bit per element, the d32m4096 point of Sec. 4).
- *         Supported by antkv_encode, antkv_append_token and antkv_decode_attn (attention only: no scores, no
- *         re-selection); antkv_kmeans_step returns EUNSUPPORTED.  d_sub 16 with 4096 centroids is
+ *         Supported by antkv_encode, antkv_append_token and antkv_decode_attn (scores and re-selection included);
+ *         antkv_kmeans_step returns EUNSUPPORTED.  d_sub 16 with 4096 centroids is
  *         not supported.
  *   - Codebooks: fp16 [Hkv][M][n_centroids][d_sub], separate for K and V; sub-space m covers
  *     channels [m*d_sub, (m+1)*d_sub).
@@ -144,7 +144,6 @@ int antkv_gather_rows(const antkv_geom* geom, const void* x, int64_t N, const in
  *            ans_k[j] = sum_h p_hj (1 - p_hj) ||q_h||_2
  *   resel_idx_k, resel_idx_v  int32 [B][Hkv][k_resel] or NULL: top-k_resel positions of those scores
  *            (ascending, ties to the lower position).  Needs ans_k / ans_v respectively to be non-NULL.
- * With 12-bit codes (n_centroids 4096) the optional outputs must be NULL and k_resel 0 (EUNSUPPORTED otherwise).
  * N == 0 writes zeros.  Errors: EINVAL, EUNSUPPORTED, EWORKSPACE, ELAUNCH.
  */
 size_t antkv_decode_attn_workspace(const antkv_geom* geom, int64_t N, int64_t k_k, int64_t k_v,

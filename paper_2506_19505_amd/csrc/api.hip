@@ -244,7 +244,9 @@ size_t antkv_decode_attn_workspace(const antkv_geom* geom, int64_t N, int64_t k_
 {
     Geom g;
     if (check_geom(geom, g) || N < 0 || k_k < 0 || k_v < 0 || k_resel < 0) return 0;
-    if (g.C != kC) return k_resel == 0 ? align_up(decode12_workspace_bytes(g, N)) : 0;   // no re-selection on 12-bit codes
+    if (g.C != kC)
+        return align_up(decode12_workspace_bytes(g, N)) +
+               (k_resel > 0 ? align_up(topk_workspace_bytes(2 * (int64_t)g.B * g.Hkv, N, k_resel)) : 0);
     return dec_plan(g, N, k_k, k_v, k_resel, true).total;
 }
 
@@ -260,8 +262,7 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
     if (N < 0 || N_cap < N || k_k < 0 || k_v < 0 || k_k > N || k_v > N || k_resel < 0 || k_resel > N ||
         N > 0x7fffffffLL)
         return ANTKV_EINVAL;
-    const bool wide = g.C != kC;                                 // 12-bit codes: attention only
-    if (wide && (ans_k || ans_v || resel_idx_k || resel_idx_v || k_resel > 0)) return ANTKV_EUNSUPPORTED;
+    const bool wide = g.C != kC;                                 // 12-bit codes
     if (g.B == 0) return ANTKV_OK;
     if (!q || !out || misaligned(q, 16) || misaligned(out, 16)) return ANTKV_EINVAL;
     if (!(scale > 0.f)) return ANTKV_EINVAL;
@@ -276,14 +277,27 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
     const bool want_ans = ans_k || ans_v;
     if (want_ans && !(ans_k && ans_v)) return ANTKV_EINVAL;   // the two scores are produced together
     if (wide) {
-        if (!workspace || misaligned(workspace, 256) || workspace_bytes < decode12_workspace_bytes(g, N))
-            return ANTKV_EWORKSPACE;
+        const size_t off_topk = align_up(decode12_workspace_bytes(g, N));
+        const size_t need = off_topk + (k_resel > 0 ? align_up(topk_workspace_bytes(2 * (int64_t)g.B * g.Hkv, N, k_resel)) : 0);
+        if (!workspace || misaligned(workspace, 256) || workspace_bytes < need) return ANTKV_EWORKSPACE;
+        hipStream_t st = (hipStream_t)stream;
         DecodeArgs a;
         a.q = (const half_t*)q; a.scale = scale; a.codes_k = codes_k; a.codes_v = codes_v; a.N = N; a.N_cap = N_cap;
         a.cb_k = (const half_t*)cb_k; a.cb_v = (const half_t*)cb_v; a.idx_k = idx_k; a.rows_k = (const half_t*)rows_k;
         a.k_k = k_k; a.idx_v = idx_v; a.rows_v = (const half_t*)rows_v; a.k_v = k_v; a.out = (half_t*)out;
-        a.ans_k = nullptr; a.ans_v = nullptr;
-        return launch_decode12(g, a, workspace, (hipStream_t)stream) == hipSuccess ? ANTKV_OK : ANTKV_ELAUNCH;
+        a.ans_k = ans_k; a.ans_v = ans_v;
+        if (launch_decode12(g, a, workspace, st) != hipSuccess) return ANTKV_ELAUNCH;
+        if (N > 0 && k_resel > 0 && (resel_idx_k || resel_idx_v)) {
+            char* w = (char*)workspace;
+            const int64_t rows = (int64_t)g.B * g.Hkv;
+            const hipError_t e =
+                (resel_idx_k && resel_idx_v)
+                    ? launch_topk2(ans_k, resel_idx_k, ans_v, resel_idx_v, rows, N, k_resel, w + off_topk, st)
+                    : launch_topk(resel_idx_k ? ans_k : ans_v, rows, N, k_resel, resel_idx_k ? resel_idx_k : resel_idx_v,
+                                  w + off_topk, st);
+            if (e != hipSuccess) return ANTKV_ELAUNCH;
+        }
+        return ANTKV_OK;
     }
     const DecPlan dp = dec_plan(g, N, k_k, k_v, k_resel, true);
     if (N > 0 && (!workspace || misaligned(workspace, 256) || workspace_bytes < dp.total)) return ANTKV_EWORKSPACE;

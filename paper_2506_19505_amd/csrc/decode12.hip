@@ -466,9 +466,195 @@ __global__ __launch_bounds__(kD) void decode12_merge(const float* __restrict__ p
     out[bh * kD + ch] = (half_t)(l > 0.f ? a / l : 0.f);
 }
 
+// ---- decode-time Anchor Score on 12-bit codes (Eq. (4) with the single query row over K_eff; Sec. 3.2, last par.) --
+// Ranking needs fp32 scores, and an fp32 table for four heads would take 256 KB, so a workgroup handles two heads of
+// the group (128 KB) and the group's two halves add their shares of a token's scores (two commutative float adds
+// onto zeroed arrays: the result does not depend on their order).  PASS 0 leaves (max, sum of exp2) per head and
+// workgroup; PASS 1 merges them into the log-sum-exp in its prologue and writes the scores.
+struct D12AnsParams {
+    const half_t* q;
+    const uint8_t* codes_k;
+    const int32_t* idx_k;
+    const half_t* rows_k;
+    const float4_t* tab;
+    float* stat_part;                     // [B][Hq][S][2]
+    float *ans_k, *ans_v;                 // [B][Hkv][N]
+    int64_t N, N_cap;
+    int k_k;
+    float c1;
+    int Hq, Hkv, G, S, chunk, HH;         // HH = head halves per group: 1 (G <= 2) or 2
+};
+
+constexpr size_t kD12AnsLds = (size_t)kM12 * kC12 * 8 + 1024 * 4 + 2 * kD * 4 + (kW12 * 4 + 8) * 4 + 16 * 4;
+
+template <int PASS>
+__global__ __launch_bounds__(kT12) void d12_ans_kernel(const D12AnsParams p)
+{
+    extern __shared__ uint4_t smem_u4[];
+    char* smem = (char*)smem_u4;
+    float2* s_lut = (float2*)smem;                                     // [4][4096] scores of the half's two heads
+    uint32_t* s_mk = (uint32_t*)(smem + kM12 * kC12 * 8);              // K-anchored tokens of the range
+    float* s_qf = (float*)(s_mk + 1024);                               // [2][128]
+    float* s_red = s_qf + 2 * kD;                                      // [waves][4] + 8
+    int* s_misc = (int*)(s_red + kW12 * 4 + 8);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = blockIdx.x % p.Hkv;
+    int rest = blockIdx.x / p.Hkv;
+    const int hh = rest % p.HH;
+    rest /= p.HH;
+    const int b = rest / p.S, sp = rest % p.S;
+    const int bg = b * p.Hkv + g;
+    const int hfirst = g * p.G + 2 * hh;                               // first query head of this half
+    const int nh = (p.G - 2 * hh) < 2 ? (p.G - 2 * hh) : 2;            // 1 or 2 heads
+    const int64_t t0 = (int64_t)sp * p.chunk;
+    const int64_t t1 = (t0 + p.chunk < p.N) ? t0 + p.chunk : p.N;
+    const int32_t* idx_k = p.idx_k + (int64_t)bg * p.k_k;
+
+    if (tid < 2 * kD) s_qf[tid] = ((tid >> 7) < nh) ? (float)p.q[((int64_t)b * p.Hq + hfirst) * kD + tid] : 0.f;
+    s_mk[tid] = 0u;
+    if (wave < 2) {
+        const int r = lower_bound64(idx_k, p.k_k, (int)(wave ? t1 : t0), lane);
+        if (lane == 0) s_misc[wave] = r;
+    }
+    __syncthreads();
+    for (int i = s_misc[0] + tid; i < s_misc[1]; i += kT12) {
+        const int rel = idx_k[i] - (int)t0;
+        atomicOr(&s_mk[rel >> 5], 1u << (rel & 31));
+    }
+    {
+        const float4_t* tb = p.tab + (int64_t)bg * kM12 * kC12;
+#pragma unroll 4
+        for (int e = tid; e < kM12 * kC12; e += kT12) {
+            const float4_t t = tb[e];
+            s_lut[e] = hh ? float2{t[2], t[3]} : float2{t[0], t[1]};
+        }
+    }
+    if (wave < 2) {                                                    // ||q_h||_2
+        const float a = s_qf[wave * kD + lane], c = s_qf[wave * kD + 64 + lane];
+        const float ss = wave_sum(fmaf(a, a, c * c));
+        if (lane == 0) s_red[kW12 * 4 + wave] = sqrtf(ss);
+    }
+    if (PASS == 1 && wave == 2 && lane < 2) {                          // log-sum-exp from the S partials of pass 0
+        float v = 0.f;
+        if (lane < nh) {
+            const float* sp_ = p.stat_part + ((int64_t)b * p.Hq + hfirst + lane) * p.S * 2;
+            float m = kNegBig;
+            for (int s = 0; s < p.S; ++s) m = fmaxf(m, sp_[2 * s]);
+            float l = 0.f;
+            for (int s = 0; s < p.S; ++s) l += sp_[2 * s + 1] * exp2f(sp_[2 * s] - m);
+            v = m + log2f(l);
+        }
+        s_red[kW12 * 4 + 4 + lane] = v;
+    }
+    __syncthreads();
+    const float qn0 = s_red[kW12 * 4], qn1 = s_red[kW12 * 4 + 1];
+    const float lse0 = s_red[kW12 * 4 + 4], lse1 = s_red[kW12 * 4 + 5];
+    float m_run[2] = {kNegBig, kNegBig}, l_run[2] = {0.f, 0.f};
+    float* out_k = p.ans_k + (int64_t)bg * p.N;
+    float* out_v = p.ans_v + (int64_t)bg * p.N;
+
+    auto consume = [&](float s0, float s1, int64_t tok) {
+        if (PASS == 0) {
+            const float sv[2] = {s0, s1};
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const float x = sv[h] - m_run[h];
+                if (x > 64.f) {                                        // first token (reference = kNegBig) or a big jump
+                    l_run[h] = l_run[h] * fast_exp2(-x) + 1.f;
+                    m_run[h] = sv[h];
+                } else {
+                    l_run[h] += fast_exp2(x);
+                }
+            }
+        } else {
+            const float a0 = fast_exp2(s0 - lse0);
+            const float a1 = nh > 1 ? fast_exp2(s1 - lse1) : 0.f;
+            const float t0_ = a0 * qn0, t1_ = a1 * qn1;
+            const float av = a0 + a1;
+            const float ak = fmaf(-a0, t0_, t0_) + fmaf(-a1, t1_, t1_);
+            if (p.HH == 1) { out_v[tok] = av; out_k[tok] = ak; }
+            else { unsafeAtomicAdd(out_v + tok, av); unsafeAtomicAdd(out_k + tok, ak); }
+        }
+    };
+
+    // ---- stream: one token per lane, code loads one round ahead; K-anchored tokens are left to the loop below
+    const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * 6;
+    auto load6 = [&](int64_t tok, uint32_t& lo, uint32_t& hi) {
+        const uint16_t* s = (const uint16_t*)(ck + tok * 6);
+        lo = (uint32_t)s[0] | ((uint32_t)s[1] << 16);
+        hi = (uint32_t)s[2];
+    };
+    uint32_t nlo = 0u, nhi = 0u;
+    if (t0 + tid < t1) load6(t0 + tid, nlo, nhi);
+    for (int64_t tok = t0 + tid; tok < t1; tok += kT12) {
+        const uint32_t klo = nlo, khi = nhi;
+        if (tok + kT12 < t1) load6(tok + kT12, nlo, nhi);
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int m = 0; m < kM12; ++m) {
+            const float2 e = s_lut[m * kC12 + code12(klo, khi, m)];
+            s0 += e.x;
+            s1 += e.y;
+        }
+        const int rel = (int)(tok - t0);
+        if (!((s_mk[rel >> 5] >> (rel & 31)) & 1u)) consume(s0, s1, tok);
+    }
+    // ---- K-anchored tokens: score from the FP16 row, 16 lanes per token and 8 channels each; blocks of 64 list
+    // entries are dealt round-robin over the S workgroups of the head half
+    {
+        const int sub = lane >> 4, l16 = lane & 15;
+        float qv[2][8];
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qv[h][e] = s_qf[h * kD + 8 * l16 + e];
+        for (int i0 = sp * (4 * kW12) + 4 * wave; i0 < p.k_k; i0 += p.S * (4 * kW12)) {
+            const int i = i0 + sub;
+            const bool on = i < p.k_k;
+            const int64_t tok = on ? idx_k[i] : t0;
+            const half8_t v = *(const half8_t*)(p.rows_k + ((int64_t)bg * p.k_k + (on ? i : 0)) * kD + 8 * l16);
+            float s[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                float d = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) d = fmaf(qv[h][e], (float)v[e], d);
+#pragma unroll
+                for (int off = 1; off < 16; off <<= 1) d += __shfl_xor(d, off, 64);
+                s[h] = d * p.c1;
+            }
+            if (on && l16 == 0) consume(s[0], s[1], tok);
+        }
+    }
+    if (PASS == 0) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const float m_w = wave_max(m_run[h]);
+            const float l_w = wave_sum(l_run[h] * fast_exp2(m_run[h] - m_w));
+            if (lane == 0) { s_red[wave * 4 + h] = m_w; s_red[wave * 4 + 2 + h] = l_w; }
+        }
+        __syncthreads();
+        if (tid < nh) {
+            float m = kNegBig;
+            for (int w = 0; w < kW12; ++w) m = fmaxf(m, s_red[w * 4 + tid]);
+            float l = 0.f;
+            for (int w = 0; w < kW12; ++w) l += s_red[w * 4 + 2 + tid] * fast_exp2(s_red[w * 4 + tid] - m);
+            float* dst = p.stat_part + (((int64_t)b * p.Hq + hfirst + tid) * p.S + sp) * 2;
+            dst[0] = m;
+            dst[1] = l;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void d12_zero(float* p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+
 struct D12Plan {
     int S, chunk;
-    size_t off_part, off_tab, off_amax, total;
+    size_t off_part, off_tab, off_amax, off_stat, total;
 };
 
 D12Plan d12_plan(const Geom& g, int64_t N)
@@ -490,6 +676,7 @@ D12Plan d12_plan(const Geom& g, int64_t N)
     pl.off_part = off; off += align_up((size_t)g.B * g.Hq * S * (kD + 2) * sizeof(float));
     pl.off_tab = off;  off += align_up((size_t)g.B * g.Hkv * kM12 * kC12 * sizeof(float4_t));
     pl.off_amax = off; off += align_up((size_t)g.B * g.Hkv * kTabBlocks * kNH * sizeof(float));
+    pl.off_stat = off; off += align_up((size_t)g.B * g.Hq * S * 2 * sizeof(float));
     pl.total = off;
     return pl;
 }
@@ -524,6 +711,29 @@ hipError_t launch_decode12(const Geom& g, const DecodeArgs& a, void* ws, hipStre
         hipLaunchKernelGGL(decode12_kernel, dim3((unsigned)(g.B * g.Hkv * pl.S)), dim3(kT12), kD12Lds, st, p);
     }
     hipLaunchKernelGGL(decode12_merge, dim3((unsigned)(g.B * g.Hq)), dim3(kD), 0, st, (const float*)p.part, p.S, a.out);
+    if (a.ans_k && a.N > 0) {
+        static const hipError_t setup_ans = []() {
+            hipError_t e1 = hipFuncSetAttribute((const void*)d12_ans_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                (int)kD12AnsLds);
+            if (e1 != hipSuccess) return e1;
+            return hipFuncSetAttribute((const void*)d12_ans_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)kD12AnsLds);
+        }();
+        if (setup_ans != hipSuccess) return setup_ans;
+        D12AnsParams d;
+        d.q = a.q; d.codes_k = a.codes_k; d.idx_k = a.idx_k; d.rows_k = a.rows_k; d.tab = p.tab;
+        d.stat_part = (float*)(w + pl.off_stat); d.ans_k = a.ans_k; d.ans_v = a.ans_v; d.N = a.N; d.N_cap = a.N_cap;
+        d.k_k = (int)a.k_k; d.c1 = p.c1; d.Hq = g.Hq; d.Hkv = g.Hkv; d.G = g.G; d.S = pl.S; d.chunk = pl.chunk;
+        d.HH = g.G > 2 ? 2 : 1;
+        const unsigned grid = (unsigned)(g.B * g.Hkv * d.HH * pl.S);
+        if (d.HH > 1) {
+            const int64_t n = (int64_t)g.B * g.Hkv * a.N;
+            hipLaunchKernelGGL(d12_zero, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a.ans_k, n);
+            hipLaunchKernelGGL(d12_zero, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a.ans_v, n);
+        }
+        hipLaunchKernelGGL(d12_ans_kernel<0>, dim3(grid), dim3(kT12), kD12AnsLds, st, d);
+        hipLaunchKernelGGL(d12_ans_kernel<1>, dim3(grid), dim3(kT12), kD12AnsLds, st, d);
+    }
     return hipGetLastError();
 }
 

@@ -129,7 +129,8 @@ def test_wide_geometry_rejections():
     assert lib.antkv_decode_attn_workspace(ctypes.byref(bad), 100, 0, 0, 0) == 0
     ok = antkv.Geometry(1, 4, 2, D_SUB, n_centroids=C).c()
     assert lib.antkv_decode_attn_workspace(ctypes.byref(ok), 100, 0, 0, 0) > 0
-    assert lib.antkv_decode_attn_workspace(ctypes.byref(ok), 100, 0, 0, 5) == 0      # no re-selection on 12-bit codes
+    assert lib.antkv_decode_attn_workspace(ctypes.byref(ok), 100, 0, 0, 5) > lib.antkv_decode_attn_workspace(
+        ctypes.byref(ok), 100, 0, 0, 0)
     assert lib.antkv_kmeans_step_workspace(ctypes.byref(ok)) == 0
 
 
@@ -181,3 +182,35 @@ def test_append12_then_decode12(oracle, books, W):
         err = np.linalg.norm(out.cpu().numpy().astype(np.float64) - want, axis=-1) / np.linalg.norm(want, axis=-1)
         assert err.max() <= 2e-3, f"step {t}: decode relative L2 {err.max():.3e}"
     print(f"W={W}: {T} appends + decodes on 12-bit codes ok")
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,N,k_k,k_v", [(1, 8, 2, 2500, 25, 25), (2, 4, 2, 900, 0, 7), (1, 2, 2, 1300, 13, 0),
+                                                (1, 8, 2, 70000, 700, 700)])
+def test_decode12_anchor_score_and_reselection(oracle, books, B, Hq, Hkv, N, k_k, k_v):
+    """Decode-time Anchor Score over 12-bit codes (two heads per workgroup, the halves add up) + re-selection."""
+    from gpu_util import check_index_sets
+    from workloads import make_decode_query, normal_fp16, random_anchor_sets
+    rng = np.random.default_rng(N)
+    scale = 1.0 / np.sqrt(128)
+    cbk, cbv = books[0][:Hkv], books[1][:Hkv]
+    ck = rng.integers(0, C, (B, Hkv, N, 4)).astype(np.int32)
+    cv = rng.integers(0, C, (B, Hkv, N, 4)).astype(np.int32)
+    ik, iv = random_anchor_sets(N, "k", B, Hkv, N, k_k), random_anchor_sets(N, "v", B, Hkv, N, k_v)
+    rk, rv = normal_fp16(N, "rows_k", (B, Hkv, k_k, 128)), normal_fp16(N, "rows_v", (B, Hkv, k_v, 128))
+    q = make_decode_query(N, B, Hq, 128)
+    k_resel = max(1, N // 100)
+    geom = antkv.Geometry(B, Hq, Hkv, D_SUB, n_centroids=C)
+    out, ans_k, ans_v, rsk, rsv = antkv.decode_attn(
+        geom, dev(q), scale, dev(pack12(ck)), dev(pack12(cv)), dev(cbk), dev(cbv), dev(ik) if k_k else None,
+        dev(rk) if k_k else None, dev(iv) if k_v else None, dev(rv) if k_v else None, k_resel=k_resel)
+    torch.cuda.synchronize()
+    want, ex = oracle.decode_attn(q, ck, cv, cbk, cbv, ik, rk, iv, rv, scale, want_ans=True)
+    err = np.linalg.norm(out.cpu().numpy().astype(np.float64) - want, axis=-1) / np.linalg.norm(want, axis=-1)
+    assert err.max() <= 2e-3
+    np.testing.assert_allclose(ans_v.cpu().numpy(), ex["ans_v"], rtol=3e-5, atol=1e-12)
+    np.testing.assert_allclose(ans_k.cpu().numpy(), ex["ans_k"], rtol=3e-5, atol=1e-12)
+    soft = 0
+    for got, score in ((rsk, ex["ans_k"]), (rsv, ex["ans_v"])):
+        w_idx, margin = oracle.topk(score, k_resel, want_margin=True)
+        soft += check_index_sets(got.cpu().numpy(), w_idx, margin)
+    print(f"N={N} G={Hq // Hkv}: scores within 3e-5, near-tie index disagreements {soft}")
