@@ -278,49 +278,55 @@ def main() -> int:
         del rt
         torch.cuda.empty_cache()
 
-        # ------------------------------------------------------------ 12-bit codebooks (d32, 4096 centroids: 0.375 bit)
-        wg = antkv.Geometry(r.B, r.Hq, r.Hkv, 32, n_centroids=4096)
-        w_cbk = dev(normal_fp16(r.seed, "cb12_k", (r.Hkv, 4, 4096, 32)))
-        w_cbv = dev(normal_fp16(r.seed, "cb12_v", (r.Hkv, 4, 4096, 32)))
-        gen = torch.Generator(device=devc)
-        gen.manual_seed(r.seed)
-        w_ck = torch.randint(0, 256, (r.B, r.Hkv, r.N, 6), dtype=torch.uint8, device=devc, generator=gen)
-        w_cv = torch.randint(0, 256, (r.B, r.Hkv, r.N, 6), dtype=torch.uint8, device=devc, generator=gen)
+        # ------------------------------------------------------------ 12-bit codebooks (4096 centroids): d32 = 0.375 bit, d16 = 0.75 bit
         w_ik = dev(random_anchor_sets(r.seed, "k", r.B, r.Hkv, r.N, r.k))
         w_iv = dev(random_anchor_sets(r.seed, "v", r.B, r.Hkv, r.N, r.k))
         w_rk = dev(normal_fp16(r.seed, "rows_k", (r.B, r.Hkv, r.k, r.D)))
         w_rv = dev(normal_fp16(r.seed, "rows_v", (r.B, r.Hkv, r.k, r.D)))
         w_q = dev(make_decode_query(r.seed, r.B, r.Hq, r.D))
-        w_ws = antkv.DecodeWorkspace(wg, r.N, r.k, r.k, 0, devc)
-        fw = lambda i: antkv.decode_attn(wg, w_q, r.scale, w_ck, w_cv, w_cbk, w_cbv, w_ik, w_rk, w_iv, w_rv, workspace=w_ws)
-        settle(fw)
-        ms_w = timed(100, fw)
-        w_ws2 = antkv.DecodeWorkspace(wg, r.N, r.k, r.k, r.k, devc)
-        fw2 = lambda i: antkv.decode_attn(wg, w_q, r.scale, w_ck, w_cv, w_cbk, w_cbv, w_ik, w_rk, w_iv, w_rv, k_resel=r.k,
-                                          workspace=w_ws2)
-        settle(fw2)
-        ms_w2 = timed(50, fw2)
-        del w_ck, w_cv, w_ws2
-        w_codes = torch.empty((p.B, p.Hkv, p.N, 6), dtype=torch.uint8, device=devc)
-        pg12 = antkv.Geometry(p.B, p.Hq, p.Hkv, 32, n_centroids=4096)
         pkd12 = dev(pk)
-        fe = lambda i: antkv.encode(pg12, pkd12, w_cbk, codes=w_codes)
-        settle(fe)
-        ms_e12 = timed(20, fe)
-        result["extra"].update({
-            "d32m4096_decode_ms": ms_w,
-            "d32m4096_decode_plus_reselection_ms": ms_w2,
-            "d32m4096_decode_tokens_per_s": r.B * r.N / (ms_w * 1e-3),
-            "d32m4096_decode_L2_gather_GBs": r.B * r.Hkv * r.N * 256 / (ms_w * 1e-3) / 1e9,
-            "d32m4096_encode_ms": ms_e12,
-            "d32m4096_encode_TFLOPs": 2.0 * p.B * p.Hkv * p.N * p.D * 4096 / (ms_e12 * 1e-3) / 1e12,
-            "d32m4096_workload": f"12-bit codes (d_sub 32, 4096 centroids, 6 bytes per token row): decode on cfg4's shape "
-                                 f"(B1, N={r.N}, {r.k} anchors per head, random codebooks and codes); encode of cfg3's K rows "
-                                 f"({p.B * p.Hkv * p.N} rows)",
-        })
-        log(f"d32m4096: decode {ms_w * 1e3:.0f} us, with re-selection {ms_w2 * 1e3:.0f} us, encode of {p.B * p.Hkv * p.N} rows {ms_e12:.2f} ms")
-        del w_codes, pkd12, w_cbk, w_cbv
-        torch.cuda.empty_cache()
+        for wd in (32, 16):
+            wm = r.D // wd
+            wb = wm * 3 // 2                                        # code bytes per token row
+            tagw = f"d{wd}m4096"
+            wg = antkv.Geometry(r.B, r.Hq, r.Hkv, wd, n_centroids=4096)
+            w_cbk = dev(normal_fp16(r.seed, "cb12_k", (r.Hkv, wm, 4096, wd)))
+            w_cbv = dev(normal_fp16(r.seed, "cb12_v", (r.Hkv, wm, 4096, wd)))
+            gen = torch.Generator(device=devc)
+            gen.manual_seed(r.seed)
+            w_ck = torch.randint(0, 256, (r.B, r.Hkv, r.N, wb), dtype=torch.uint8, device=devc, generator=gen)
+            w_cv = torch.randint(0, 256, (r.B, r.Hkv, r.N, wb), dtype=torch.uint8, device=devc, generator=gen)
+            w_ws = antkv.DecodeWorkspace(wg, r.N, r.k, r.k, 0, devc)
+            fw = lambda i: antkv.decode_attn(wg, w_q, r.scale, w_ck, w_cv, w_cbk, w_cbv, w_ik, w_rk, w_iv, w_rv, workspace=w_ws)
+            settle(fw)
+            ms_w = timed(100, fw)
+            w_ws2 = antkv.DecodeWorkspace(wg, r.N, r.k, r.k, r.k, devc)
+            fw2 = lambda i: antkv.decode_attn(wg, w_q, r.scale, w_ck, w_cv, w_cbk, w_cbv, w_ik, w_rk, w_iv, w_rv, k_resel=r.k,
+                                              workspace=w_ws2)
+            settle(fw2)
+            ms_w2 = timed(50, fw2)
+            del w_ck, w_cv, w_ws2
+            w_codes = torch.empty((p.B, p.Hkv, p.N, wb), dtype=torch.uint8, device=devc)
+            pg12 = antkv.Geometry(p.B, p.Hq, p.Hkv, wd, n_centroids=4096)
+            fe = lambda i: antkv.encode(pg12, pkd12, w_cbk, codes=w_codes)
+            settle(fe)
+            ms_e12 = timed(20, fe)
+            heads_per_wg = 4 if wd == 32 else 2                     # a group of 4 heads takes 4 / heads_per_wg gathers of a token's V centroids
+            result["extra"].update({
+                f"{tagw}_decode_ms": ms_w,
+                f"{tagw}_decode_plus_reselection_ms": ms_w2,
+                f"{tagw}_decode_tokens_per_s": r.B * r.N / (ms_w * 1e-3),
+                f"{tagw}_decode_L2_gather_GBs": r.B * r.Hkv * r.N * 256 * (min(r.Hq // r.Hkv, 4) + heads_per_wg - 1) // heads_per_wg / (ms_w * 1e-3) / 1e9,
+                f"{tagw}_encode_ms": ms_e12,
+                f"{tagw}_encode_TFLOPs": 2.0 * p.B * p.Hkv * p.N * p.D * 4096 / (ms_e12 * 1e-3) / 1e12,
+                f"{tagw}_workload": f"12-bit codes (d_sub {wd}, 4096 centroids, {wb} bytes per token row): decode on cfg4's shape "
+                                    f"(B1, N={r.N}, {r.k} anchors per head, random codebooks and codes); encode of cfg3's K rows "
+                                    f"({p.B * p.Hkv * p.N} rows)",
+            })
+            log(f"{tagw}: decode {ms_w * 1e3:.0f} us, with re-selection {ms_w2 * 1e3:.0f} us, encode of {p.B * p.Hkv * p.N} rows {ms_e12:.2f} ms")
+            del w_codes, w_cbk, w_cbv, w_ws
+            torch.cuda.empty_cache()
+        del pkd12
 
         # ------------------------------------------------------------ decode append with a 32-token FP16 window
         a_W, a_k, a_N0, a_steps = 32, 64 + 32, 1024, 200

@@ -26,15 +26,14 @@
  *   - Geometry: D must be 128 and Hq / Hkv in {1, 2, 4}; M = D / d_sub sub-spaces per head.  Two code formats:
  *       n_centroids 256, d_sub in {4, 8, 16}: one byte per code (2 / 1 / 0.5 bit per element, the paper's
  *         d4m256 / d8m256 notation, Sec. 4); every entry point supports it.
- *       n_centroids 4096, d_sub 32: 12-bit codes (0.375 bit per element, the d32m4096 point of Sec. 4).
- *         Supported by antkv_encode, antkv_append_token and antkv_decode_attn (scores and re-selection included);
- *         antkv_kmeans_step returns EUNSUPPORTED.  d_sub 16 with 4096 centroids is
- *         not supported.
+ *       n_centroids 4096, d_sub 32 or 16: 12-bit codes (0.375 / 0.75 bit per element, the d32m4096 and d16m4096
+ *         points of Sec. 4).  Supported by antkv_encode, antkv_append_token and antkv_decode_attn (scores and
+ *         re-selection included); antkv_kmeans_step returns EUNSUPPORTED.
  *   - Codebooks: fp16 [Hkv][M][n_centroids][d_sub], separate for K and V; sub-space m covers
  *     channels [m*d_sub, (m+1)*d_sub).
  *   - Codes: uint8 [B][Hkv][N_cap][code_bytes], token-major.  code_bytes = M for one-byte codes.  For 12-bit
- *     codes code_bytes = 6: the token's four codes packed little-endian into 48 bits,
- *     c0 | c1 << 12 | c2 << 24 | c3 << 36.
+ *     codes code_bytes = 3 M / 2 (6 for d_sub 32, 12 for d_sub 16): the token's M codes packed little-endian,
+ *     code m at bits 12 m .. 12 m + 11 of the row (c0 | c1 << 12 | c2 << 24 | c3 << 36 for each six bytes).
  *   - Calls that share a workspace must not overlap in time.  A workspace may hold any bytes when it is first
  *     used (nothing has to be cleared) and may be reused by calls of different shapes.
  *   - Codes and index sets are deterministic.  The fp16 output of antkv_decode_attn can differ between two runs
@@ -61,7 +60,7 @@ typedef struct antkv_geom {
     int32_t Hq;          /* query heads */
     int32_t Hkv;         /* KV heads */
     int32_t D;           /* head dim (128) */
-    int32_t d_sub;       /* sub-vector dim: 4, 8 or 16 (with 256 centroids), or 32 (with 4096) */
+    int32_t d_sub;       /* sub-vector dim: 4, 8 or 16 (with 256 centroids), or 32 or 16 (with 4096) */
     int32_t n_centroids; /* 256 or 4096 */
 } antkv_geom;
 

@@ -12,7 +12,7 @@ int check_geom(const antkv_geom* gm, Geom& g)
         return ANTKV_EINVAL;
     if (gm->Hq % gm->Hkv != 0) return ANTKV_EINVAL;
     if (gm->D != kD) return ANTKV_EUNSUPPORTED;
-    const bool wide = gm->n_centroids == 4096 && gm->d_sub == 32;             // 12-bit codes
+    const bool wide = gm->n_centroids == 4096 && (gm->d_sub == 32 || gm->d_sub == 16);   // 12-bit codes
     const bool byte_codes = gm->n_centroids == kC && (gm->d_sub == 4 || gm->d_sub == 8 || gm->d_sub == 16);
     if (!wide && !byte_codes) return ANTKV_EUNSUPPORTED;
     const int G = gm->Hq / gm->Hkv;
@@ -20,7 +20,7 @@ int check_geom(const antkv_geom* gm, Geom& g)
     if ((int64_t)gm->B * gm->Hkv > 65535) return ANTKV_EUNSUPPORTED;
     g.B = gm->B; g.Hq = gm->Hq; g.Hkv = gm->Hkv; g.G = G; g.d = gm->d_sub; g.M = kD / gm->d_sub;
     g.C = gm->n_centroids;
-    g.code_bytes = wide ? 6 : g.M;
+    g.code_bytes = wide ? 3 * g.M / 2 : g.M;
     return ANTKV_OK;
 }
 

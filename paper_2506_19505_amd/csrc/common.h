@@ -77,8 +77,8 @@ __device__ __forceinline__ uint32_t float_key(float f)
 // ---- launchers (each enqueues on `stream` and returns a hipError_t) --------------------------
 struct Geom {
     int B, Hq, Hkv, G, d, M;
-    int C;            // centroids per sub-space: 256 (one byte per code) or 4096 (12-bit codes, d = 32 only)
-    int code_bytes;   // bytes of one token's codes: M, or 6 for the four packed 12-bit codes
+    int C;            // centroids per sub-space: 256 (one byte per code) or 4096 (12-bit codes, d = 32 or 16)
+    int code_bytes;   // bytes of one token's codes: M, or 3 M / 2 for packed 12-bit codes (6 for d = 32, 12 for d = 16)
 };
 
 hipError_t launch_encode(const Geom& g, const half_t* x, int64_t xs_b, int64_t xs_h, int64_t xs_t,

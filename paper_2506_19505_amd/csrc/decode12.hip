@@ -1,22 +1,26 @@
 // Decode attention over 12-bit VQ codes + FP16 anchors (Attn of paper Sec. 2.1 on the cache of Fig. 2(b), with the
-// d32 / 4096-centroid codebooks of Sec. 4): one query token per sequence against codes packed 6 bytes per token.
+// 4096-centroid codebooks of Sec. 4): one query token per sequence against codes packed 6 bytes per token (d32, four
+// sub-spaces) or 12 bytes per token (d16, eight sub-spaces).
 //
-// With 4096 centroids of 32 channels only the q.centroid table of the K side fits LDS (4 sub-spaces x 4096 codes x
-// 4 heads x int16 = 128 KB); the V codebook (1 MB per KV head) stays in L2, which is why workgroup ids are mapped so
-// that KV head g runs on XCD g mod 8 and each XCD's L2 keeps one head's codebook.
+// With 4096 centroids only the q.centroid table of the K side fits LDS: 128 KB of int16 entries, which is 4 sub-spaces
+// x 4096 codes x 4 heads for d32 and 8 sub-spaces x 4096 codes x 2 heads for d16 -- there a query group of four heads
+// is split over two workgroups that walk the same tokens.  The V codebook (1 MB per KV head) stays in L2, which is
+// why workgroup ids are mapped so that KV head g runs on XCD g mod 8 and each XCD's L2 keeps one head's codebook.
 //   prologue   table: a small kernel computes the fp32 scores once per (sequence, KV head); each workgroup takes the
 //              maximum per head and quantises them to 16-bit fixed point with one scale per head into LDS; bitmaps of the K- and V-anchored tokens of the workgroup's token range (the stream skips
 //              them).
-//   stream     lane = token: unpack the four codes, four 8-byte table reads, integer sums, online softmax per
-//              64-token tile.  Then the wave walks the tile's tokens one by one: every lane owns two output
-//              channels, fetches them from the token's V centroids (one 4-byte gather per lane) and adds
-//              P_h * v for the four heads.  Anchored tokens carry weight zero here.
+//   stream     lane = token: unpack the codes, one table read per sub-space, integer sums, online softmax per
+//              64-token tile.  Then the value phase: 16 lanes per token, every lane owns eight output channels,
+//              fetches them from the token's V centroid of that sub-space (one 16-byte gather per lane) and adds
+//              P_h * v for the workgroup's heads.  Anchored tokens carry weight zero here.
 //   anchors    the list entries form tiles of their own (lane = entry), dealt round-robin over the workgroups of the
 //              head: score from the FP16 row (or from the table), then the same value phase with the FP16 row (or
 //              the centroids) as the source.
 //   merge      waves through LDS, workgroups through a partial (max, sum, accumulator) per head and a second
 //              small kernel.
 #include "common.h"
+
+#include <type_traits>
 
 namespace antkv {
 
@@ -25,14 +29,13 @@ namespace {
 constexpr int kT12 = 1024;               // threads
 constexpr int kW12 = kT12 / 64;          // waves
 constexpr int kC12 = 4096;
-constexpr int kD12 = 32;
-constexpr int kM12 = 4;
-constexpr int kNH = 4;                   // head slots (G <= 4)
+constexpr int kNH = 4;                   // head slots of a query group (G <= 4)
 constexpr int kChunkMax = 32768;         // tokens per workgroup (bitmaps of 1024 words)
 constexpr float kEmptyRef12 = -1.0e4f;   // softmax reference before any token: finite, far above the masked score
 constexpr int kLutMax12 = 32767;
 constexpr int kTabThreads = 256;
-constexpr int kTabBlocks = kM12 * kC12 / (kTabThreads * 4);   // 16 blocks per (sequence, KV head), 4 entries per thread
+constexpr int tab_blocks(int ds) { return (kD / ds) * kC12 / (kTabThreads * 4); }   // per (sequence, KV head), 4 entries per thread
+constexpr int heads_per_wg(int ds) { return ds == 32 ? 4 : 2; }                     // heads whose int16 table fits 128 KB
 constexpr float kPShift12 = 12.f;        // weights are kept scaled by 2^12 so that small ones stay normal in fp16
 
 struct D12Params {
@@ -42,12 +45,13 @@ struct D12Params {
     const int32_t *idx_k, *idx_v;
     const half_t *rows_k, *rows_v;
     float* part;                          // [B][Hq][S][kD + 2]
-    const float4_t* tab;                  // [B][Hkv][4][4096] fp32 scores of the four heads, from d12_table_kernel
-    const float* tab_amax;                // [B][Hkv][kTabBlocks][4] per-block maxima of |score|
+    const float4_t* tab;                  // [B][Hkv][M][4096] fp32 scores of the four heads, from d12_table_kernel
+    const float* tab_amax;                // [B][Hkv][table blocks][4] per-block maxima of |score|
     int64_t N, N_cap;
     int k_k, k_v;
     float c1;
     int Hq, Hkv, G, S, chunk;
+    int HH;                               // workgroups that share a (sequence, KV head, token range): ceil(G / heads per workgroup)
 };
 
 __device__ __forceinline__ float dot8f(const half8_t& a, const half8_t& b, float acc)
@@ -79,21 +83,43 @@ __device__ __forceinline__ int lower_bound64(const int32_t* __restrict__ idx, in
     return lo;
 }
 
-__device__ __forceinline__ uint32_t code12(uint32_t lo, uint32_t hi, int m)
+// a token's code words: 48 or 96 bits, code m at bits 12 m .. 12 m + 11
+template <int DS>
+__device__ __forceinline__ void load_cw(const uint8_t* __restrict__ base, int64_t tok, uint32_t (&w)[3])
 {
-    const uint64_t w = ((uint64_t)hi << 32) | lo;
-    return (uint32_t)(w >> (12 * m)) & 0xFFFu;
+    if constexpr (DS == 32) {
+        const uint16_t* s = (const uint16_t*)(base + tok * 6);
+        w[0] = (uint32_t)s[0] | ((uint32_t)s[1] << 16);
+        w[1] = (uint32_t)s[2];
+        w[2] = 0u;
+    } else {
+        const uint32_t* s = (const uint32_t*)(base + tok * 12);
+        w[0] = s[0];
+        w[1] = s[1];
+        w[2] = s[2];
+    }
+}
+
+__device__ __forceinline__ uint32_t code12(const uint32_t (&w)[3], int m)
+{
+    const int bit = 12 * m, d = bit >> 5, sh = bit & 31;       // m is a compile-time constant wherever this is called
+    uint32_t v = w[d] >> sh;
+    if (sh > 20) v |= w[d + 1] << (32 - sh);
+    return v & 0xFFFu;
 }
 
 // fp32 table of c1 q_h . centroid for one (sequence, KV head): every workgroup of the decode kernel that works on this
-// pair needs the same 16384 x 4 values, so they are computed once here (the K codebook is read once instead of twice
-// per decode workgroup) and only quantised into LDS there.
+// pair needs the same M x 4096 x 4 values, so they are computed once here (the K codebook is read once instead of
+// once per decode workgroup) and only quantised into LDS there.
+template <int kD12>
 __global__ __launch_bounds__(kTabThreads) void d12_table_kernel(const half_t* __restrict__ q, const half_t* __restrict__ cb_k,
                                                                 float c1, int Hq, int Hkv, int G, float4_t* __restrict__ tab,
                                                                 float* __restrict__ tab_amax)
 {
     __shared__ __attribute__((aligned(16))) half_t s_q[kNH * kD];
     __shared__ float s_red[kTabThreads / 64][kNH];
+    constexpr int kM12 = kD / kD12;
+    constexpr int kTabBlocks = tab_blocks(kD12);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bg = blockIdx.x, b = bg / Hkv, g = bg % Hkv;
     for (int i = tid; i < kNH * kD; i += kTabThreads)
@@ -105,15 +131,15 @@ __global__ __launch_bounds__(kTabThreads) void d12_table_kernel(const half_t* __
         const int e = (blockIdx.y * 4 + k) * kTabThreads + tid;        // entry = (sub-space, code)
         const int m = e / kC12;
         const half_t* cp = cb_k + ((int64_t)g * kM12 * kC12 + e) * kD12;
-        half8_t cv[4];
+        half8_t cv[kD12 / 8];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) cv[u] = *(const half8_t*)(cp + 8 * u);
+        for (int u = 0; u < kD12 / 8; ++u) cv[u] = *(const half8_t*)(cp + 8 * u);
         float4_t o;
 #pragma unroll
         for (int h = 0; h < kNH; ++h) {
             float d = 0.f;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) d = dot8f(cv[u], *(const half8_t*)(s_q + h * kD + m * kD12 + 8 * u), d);
+            for (int u = 0; u < kD12 / 8; ++u) d = dot8f(cv[u], *(const half8_t*)(s_q + h * kD + m * kD12 + 8 * u), d);
             o[h] = d * c1;
             amax[h] = fmaxf(amax[h], fabsf(o[h]));
         }
@@ -132,33 +158,52 @@ __global__ __launch_bounds__(kTabThreads) void d12_table_kernel(const half_t* __
     }
 }
 
+// LDS bytes of decode12_kernel<DS>
+constexpr size_t d12_lds(int ds)
+{
+    return (size_t)128 * 1024 + 2 * 1024 * 4 + (size_t)heads_per_wg(ds) * kD * 2 + 64 * 4 + 16 * 4 +
+           (size_t)kW12 * 64 * heads_per_wg(ds) * 2 + (size_t)kW12 * (kD / ds) * 64 * 2;
+}
+static_assert(d12_lds(32) <= 160 * 1024 && d12_lds(16) <= 160 * 1024, "LDS budget");
+
+// kD12 = sub-vector width: 32 (four sub-spaces, all four heads of a group in one workgroup) or 16 (eight sub-spaces,
+// two heads per workgroup)
+template <int kD12>
 __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
 {
+    constexpr int kM12 = kD / kD12;                                    // sub-spaces
+    constexpr int NHW = heads_per_wg(kD12);                            // heads of this workgroup
+    constexpr int LPM = kD12 / 8;                                      // value-phase lanes per sub-space
+    constexpr int kTabBlocks = tab_blocks(kD12);
+    using lut_t = typename std::conditional<NHW == 4, uint2_t, uint32_t>::type;   // NHW x int16
     extern __shared__ uint4_t smem_u4[];
     char* smem = (char*)smem_u4;
-    uint2_t* s_lut = (uint2_t*)smem;                                   // [4][4096] entries of 4 x int16 (128 KB)
-    uint32_t* s_mk = (uint32_t*)(smem + kM12 * kC12 * 8);              // K-anchored tokens of the range, 1024 words
+    lut_t* s_lut = (lut_t*)smem;                                       // [M][4096] entries of NHW x int16 (128 KB)
+    uint32_t* s_mk = (uint32_t*)(smem + 128 * 1024);                   // K-anchored tokens of the range, 1024 words
     uint32_t* s_mv = s_mk + 1024;                                      // V-anchored tokens
-    half_t* s_q = (half_t*)(s_mv + 1024);                              // [4][128]
-    float* s_red = (float*)(s_q + kNH * kD);                           // 64 floats of scratch
+    half_t* s_q = (half_t*)(s_mv + 1024);                              // [NHW][128]
+    float* s_red = (float*)(s_q + NHW * kD);                           // 64 floats of scratch
     int* s_misc = (int*)(s_red + 64);                                  // 16 ints
-    // this wave's tile: for each pair of tokens (2j, 2j+1) the four heads' weights as four half2 {P_h(2j), P_h(2j+1)}
-    half_t* s_pw = (half_t*)(s_misc + 16) + (threadIdx.x >> 6) * 256;
-    uint16_t* s_vc = (uint16_t*)((half_t*)(s_misc + 16) + kW12 * 256) + (threadIdx.x >> 6) * 256;   // [4][64] V codes
+    // this wave's tile: for each pair of tokens (2j, 2j+1) the heads' weights as NHW half2 {P_h(2j), P_h(2j+1)}
+    half_t* s_pw = (half_t*)(s_misc + 16) + (threadIdx.x >> 6) * (64 * NHW);
+    uint16_t* s_vc = (uint16_t*)((half_t*)(s_misc + 16) + kW12 * 64 * NHW) + (threadIdx.x >> 6) * (kM12 * 64);   // [M][64] V codes
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // KV head g on XCD g mod 8: workgroup ids go to the XCDs round-robin
     const int g = blockIdx.x % p.Hkv;
-    const int rest = blockIdx.x / p.Hkv;
+    int rest = blockIdx.x / p.Hkv;
+    const int hh = rest % p.HH;                                        // which NHW heads of the group
+    rest /= p.HH;
     const int b = rest / p.S, sp = rest % p.S;
     const int bg = b * p.Hkv + g;
-    const int h0 = g * p.G;
+    const int h0 = g * p.G + NHW * hh;
+    const int nh = (p.G - NHW * hh) < NHW ? (p.G - NHW * hh) : NHW;    // heads present
     const int64_t t0 = (int64_t)sp * p.chunk;
     const int64_t t1 = (t0 + p.chunk < p.N) ? t0 + p.chunk : p.N;
     const int32_t* idx_k = p.idx_k + (int64_t)bg * p.k_k;
     const int32_t* idx_v = p.idx_v + (int64_t)bg * p.k_v;
 
     // ---- prologue ----------------------------------------------------------------------------------------------
-    if (tid < kNH * kD) s_q[tid] = ((tid >> 7) < p.G) ? p.q[((int64_t)b * p.Hq + h0) * kD + tid] : (half_t)0.f;
+    if (tid < NHW * kD) s_q[tid] = ((tid >> 7) < nh) ? p.q[((int64_t)b * p.Hq + h0) * kD + tid] : (half_t)0.f;
     for (int i = tid; i < 2 * 1024; i += kT12) s_mk[i] = 0u;
     if (wave < 4) {                                                    // list ranges that fall into [t0, t1)
         const int32_t* l = (wave < 2) ? idx_k : idx_v;
@@ -178,11 +223,11 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     }
     // table: the fp32 scores come from d12_table_kernel; one scale per head from the per-block maxima, then 16-bit
     // fixed point into LDS.  Thread t owns entries t + 1024 i.
-    float amax[kNH], inv_q[kNH];
+    float amax[NHW], inv_q[NHW];
 #pragma unroll
-    for (int h = 0; h < kNH; ++h) {
+    for (int h = 0; h < NHW; ++h) {
         float a = 0.f;
-        for (int k = 0; k < kTabBlocks; ++k) a = fmaxf(a, p.tab_amax[((int64_t)bg * kTabBlocks + k) * kNH + h]);
+        for (int k = 0; k < kTabBlocks; ++k) a = fmaxf(a, p.tab_amax[((int64_t)bg * kTabBlocks + k) * kNH + NHW * hh + h]);
         amax[h] = a;
         inv_q[h] = a > 0.f ? (float)kLutMax12 / a : 0.f;
     }
@@ -191,57 +236,65 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
 #pragma unroll 4
         for (int e = tid; e < kM12 * kC12; e += kT12) {
             const float4_t sc = tb[e];
-            int q16[kNH];
+            if constexpr (NHW == 4) {
+                int q16[4];
 #pragma unroll
-            for (int h = 0; h < kNH; ++h) q16[h] = (int)rintf(sc[h] * inv_q[h]);
-            uint2_t w;
-            w[0] = ((uint32_t)q16[0] & 0xFFFFu) | ((uint32_t)q16[1] << 16);
-            w[1] = ((uint32_t)q16[2] & 0xFFFFu) | ((uint32_t)q16[3] << 16);
-            s_lut[e] = w;
+                for (int h = 0; h < 4; ++h) q16[h] = (int)rintf(sc[h] * inv_q[h]);
+                uint2_t w;
+                w[0] = ((uint32_t)q16[0] & 0xFFFFu) | ((uint32_t)q16[1] << 16);
+                w[1] = ((uint32_t)q16[2] & 0xFFFFu) | ((uint32_t)q16[3] << 16);
+                s_lut[e] = w;
+            } else {
+                const int qa = (int)rintf((hh ? sc[2] : sc[0]) * inv_q[0]), qb = (int)rintf((hh ? sc[3] : sc[1]) * inv_q[1]);
+                s_lut[e] = ((uint32_t)qa & 0xFFFFu) | ((uint32_t)qb << 16);
+            }
         }
     }
-    float lut_q[kNH];                                                  // table quantum per head (log2 units)
+    float lut_q[NHW];                                                  // table quantum per head (log2 units)
 #pragma unroll
-    for (int h = 0; h < kNH; ++h) lut_q[h] = amax[h] * (1.0f / (float)kLutMax12);
+    for (int h = 0; h < NHW; ++h) lut_q[h] = amax[h] * (1.0f / (float)kLutMax12);
     __syncthreads();                                                   // table and bitmaps are complete
 
     // ---- per-wave state and the helpers shared by the stream and the anchor tiles
-    const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * 6;
-    const uint8_t* cv = p.codes_v + (int64_t)bg * p.N_cap * 6;
+    constexpr int CB = 3 * kM12 / 2;                                   // code bytes per token
+    const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * CB;
+    const uint8_t* cv = p.codes_v + (int64_t)bg * p.N_cap * CB;
     const half_t* cbv = p.cb_v + (int64_t)g * kM12 * kC12 * kD12;
     // Value phase roles: a group of 16 lanes (grp) takes the tokens t with t mod 4 == grp of a tile, four tokens per
     // gather instruction; lane li of the group owns output channels 8 li .. 8 li + 7, i.e. 16 bytes of the centroid of
-    // sub-space li / 4.  The four groups' accumulators are added up once, before the merge.
+    // sub-space li / LPM.  The four groups' accumulators are added up once, before the merge.
     const int grp = lane >> 4, li = lane & 15;
-    const int my_m = li >> 2;
+    const int my_m = li / LPM;
     const char* cbv_bytes = (const char*)cbv;
-    const uint32_t lane_off = (uint32_t)((my_m * kC12 * kD12 + 8 * (li & 3)) * 2);      // byte offset of the lane's channels
-    float m_ref[kNH], l_lane[kNH], acc[kNH][8];
+    const uint32_t lane_off = (uint32_t)((my_m * kC12 * kD12 + 8 * (li % LPM)) * 2);    // byte offset of the lane's channels
+    float m_ref[NHW], l_lane[NHW], acc[NHW][8];
 #pragma unroll
-    for (int h = 0; h < kNH; ++h) {
+    for (int h = 0; h < NHW; ++h) {
         m_ref[h] = kEmptyRef12;
         l_lane[h] = 0.f;
 #pragma unroll
         for (int c = 0; c < 8; ++c) acc[h][c] = 0.f;
     }
 
-    auto load6 = [&](const uint8_t* base, int64_t tok, uint32_t& lo, uint32_t& hi) {
-        const uint16_t* s = (const uint16_t*)(base + tok * 6);
-        lo = (uint32_t)s[0] | ((uint32_t)s[1] << 16);
-        hi = (uint32_t)s[2];
-    };
-    auto lut_scores = [&](uint32_t klo, uint32_t khi, float (&s)[kNH]) {
-        int sum[kNH] = {0, 0, 0, 0};
+    auto lut_scores = [&](const uint32_t (&kw)[3], float (&s)[NHW]) {
+        int sum[NHW];
+#pragma unroll
+        for (int h = 0; h < NHW; ++h) sum[h] = 0;
 #pragma unroll
         for (int m = 0; m < kM12; ++m) {
-            const uint2_t e = s_lut[m * kC12 + code12(klo, khi, m)];
-            sum[0] += (int)(short)(e[0] & 0xFFFFu);
-            sum[1] += (int)e[0] >> 16;
-            sum[2] += (int)(short)(e[1] & 0xFFFFu);
-            sum[3] += (int)e[1] >> 16;
+            const lut_t e = s_lut[m * kC12 + code12(kw, m)];
+            if constexpr (NHW == 4) {
+                sum[0] += (int)(short)(e[0] & 0xFFFFu);
+                sum[1] += (int)e[0] >> 16;
+                sum[2] += (int)(short)(e[1] & 0xFFFFu);
+                sum[3] += (int)e[1] >> 16;
+            } else {
+                sum[0] += (int)(short)(e & 0xFFFFu);
+                sum[1] += (int)e >> 16;
+            }
         }
 #pragma unroll
-        for (int h = 0; h < kNH; ++h) s[h] = (float)sum[h] * lut_q[h];
+        for (int h = 0; h < NHW; ++h) s[h] = (float)sum[h] * lut_q[h];
     };
     // move the wave's reference of head h to at least `cand` (uniform); returns nothing, rescales the running state
     auto raise_ref = [&](int h, float cand) {
@@ -269,12 +322,22 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     auto consume = [&](int s0, const half8_t (&src)[kSteps]) {
 #pragma unroll
         for (int e = 0; e < kSteps; e += 2) {
-            const half8_t pj = *(const half8_t*)(s_pw + (grp * 8 + ((s0 + e) >> 1)) * 8);   // the group's step pair
+            half_t pj[2 * NHW];                                        // the group's step pair: NHW x {P_h(t), P_h(t + 4)}
+            const half_t* pp = s_pw + (grp * 8 + ((s0 + e) >> 1)) * (2 * NHW);
+            if constexpr (NHW == 4) {
+                const half8_t v8 = *(const half8_t*)pp;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) pj[i] = v8[i];
+            } else {
+                const half4_t v4 = *(const half4_t*)pp;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pj[i] = v4[i];
+            }
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
                 const half2_t vc = {src[e][c], src[e + 1][c]};
 #pragma unroll
-                for (int h = 0; h < kNH; ++h) {
+                for (int h = 0; h < NHW; ++h) {
                     const half2_t ph = {pj[2 * h], pj[2 * h + 1]};
                     acc[h][c] = __builtin_amdgcn_fdot2(ph, vc, acc[h][c], false);
                 }
@@ -282,11 +345,11 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         }
     };
     // online softmax of one tile: raises the wave's references, adds the weights to the lane sums and leaves the
-    // four heads' weights of every token (fp16, scaled by 2^12) in the wave's LDS area, paired for the dot products
-    auto tile_weights = [&](const float (&sc)[kNH], bool off) {
-        half_t pw_h[kNH];
+    // heads' weights of every token (fp16, scaled by 2^12) in the wave's LDS area, paired for the dot products
+    auto tile_weights = [&](const float (&sc)[NHW], bool off) {
+        half_t pw_h[NHW];
 #pragma unroll
-        for (int h = 0; h < kNH; ++h) {
+        for (int h = 0; h < NHW; ++h) {
             const float sh = off ? kNegBig : sc[h];
             raise_ref(h, wave_max(sh));
             const float pw = fast_exp2(sh - m_ref[h] + kPShift12);     // 0 for switched-off lanes, at most 2^12
@@ -295,8 +358,8 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         }
         __builtin_amdgcn_wave_barrier();                               // LDS operations of one wave stay in order
 #pragma unroll
-        for (int h = 0; h < kNH; ++h)                                  // token = lane: group lane % 4, step lane / 4
-            s_pw[((lane & 3) * 8 + (lane >> 3)) * 8 + 2 * h + ((lane >> 2) & 1)] = pw_h[h];
+        for (int h = 0; h < NHW; ++h)                                  // token = lane: group lane % 4, step lane / 4
+            s_pw[((lane & 3) * 8 + (lane >> 3)) * (2 * NHW) + 2 * h + ((lane >> 2) & 1)] = pw_h[h];
     };
 
     // ---- stream ------------------------------------------------------------------------------------------------
@@ -304,17 +367,17 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     for (int64_t tile = wave; tile < n_tiles; tile += kW12) {
         const int64_t tok = t0 + tile * 64 + lane;
         const int64_t ltok = tok < t1 ? tok : t1 - 1;
-        uint32_t klo, khi, vlo, vhi;
-        load6(ck, ltok, klo, khi);
-        load6(cv, ltok, vlo, vhi);
+        uint32_t kw[3], vw[3];
+        load_cw<kD12>(ck, ltok, kw);
+        load_cw<kD12>(cv, ltok, vw);
         const int rel = (int)(ltok - t0);
         const uint32_t mbit = ((s_mk[rel >> 5] | s_mv[rel >> 5]) >> (rel & 31)) & 1u;
         const bool masked = tok >= t1 || mbit != 0u;
-        float s[kNH];
-        lut_scores(klo, khi, s);
+        float s[NHW];
+        lut_scores(kw, s);
         tile_weights(s, masked);
 #pragma unroll
-        for (int m = 0; m < kM12; ++m) s_vc[m * 64 + (lane & 3) * 16 + (lane >> 2)] = (uint16_t)code12(vlo, vhi, m);
+        for (int m = 0; m < kM12; ++m) s_vc[m * 64 + (lane & 3) * 16 + (lane >> 2)] = (uint16_t)code12(vw, m);
         __builtin_amdgcn_wave_barrier();
         // 16 steps of four tokens; the gathers of the next four steps fly while four are consumed
         half8_t vbuf[2][kSteps];
@@ -339,7 +402,7 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     const int n_ka = p.k_k, n_va = p.k_v;
     const int n_at = (n_ka + n_va + 63) >> 6;
     const char* rows_v_bytes = (const char*)p.rows_v;
-    uint32_t* s_src = (uint32_t*)s_vc;                                 // [4 sub-spaces][32 tokens]
+    uint32_t* s_src = (uint32_t*)s_vc;                                 // [M sub-spaces][32 tokens]
     // position of tok in an ascending list, or -1
     auto find = [&](const int32_t* __restrict__ list, int n, int tok) -> int {
         int lo = 0, hi = n;
@@ -360,32 +423,34 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         if (from_v) { i = it - n_ka; tok = idx_v[i]; pos_v = i; in_k = find(idx_k, n_ka, tok) >= 0; }
         const bool in_v = pos_v >= 0;
         const bool active = from_k || (from_v && !in_k);
-        float s[kNH] = {0.f, 0.f, 0.f, 0.f};
+        float s[NHW];
+#pragma unroll
+        for (int h = 0; h < NHW; ++h) s[h] = 0.f;
         if (from_k) {
             const half_t* row = p.rows_k + ((int64_t)bg * p.k_k + i) * kD;
 #pragma unroll 4
             for (int c = 0; c < kD / 8; ++c) {
                 const half8_t kr = *(const half8_t*)(row + 8 * c);
 #pragma unroll
-                for (int h = 0; h < kNH; ++h) s[h] = dot8f(kr, *(const half8_t*)(s_q + h * kD + 8 * c), s[h]);
+                for (int h = 0; h < NHW; ++h) s[h] = dot8f(kr, *(const half8_t*)(s_q + h * kD + 8 * c), s[h]);
             }
 #pragma unroll
-            for (int h = 0; h < kNH; ++h) s[h] *= p.c1;
+            for (int h = 0; h < NHW; ++h) s[h] *= p.c1;
         } else {
-            uint32_t klo, khi;
-            load6(ck, tok, klo, khi);
-            lut_scores(klo, khi, s);
+            uint32_t kw[3];
+            load_cw<kD12>(ck, tok, kw);
+            lut_scores(kw, s);
         }
-        uint32_t voff[kM12];                                           // byte offset of the token's 64 bytes per sub-space
+        uint32_t voff[kM12];                                           // byte offset of the token's kD12 channels per sub-space
         if (in_v) {
 #pragma unroll
             for (int m = 0; m < kM12; ++m)
                 voff[m] = 0x80000000u | (uint32_t)((((int64_t)bg * p.k_v + pos_v) * kD + kD12 * m) * 2);
         } else {
-            uint32_t vlo, vhi;
-            load6(cv, tok, vlo, vhi);
+            uint32_t vw[3];
+            load_cw<kD12>(cv, tok, vw);
 #pragma unroll
-            for (int m = 0; m < kM12; ++m) voff[m] = (uint32_t)((m * kC12 + (int)code12(vlo, vhi, m)) * kD12 * 2);
+            for (int m = 0; m < kM12; ++m) voff[m] = (uint32_t)((m * kC12 + (int)code12(vw, m)) * kD12 * 2);
         }
         tile_weights(s, !active);
         // half tiles of 32 entries: sources [sub-space][group][step], 8 steps per group
@@ -394,7 +459,7 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
 #pragma unroll
             for (int e = 0; e < kSteps; ++e) {
                 const char* base = (o4[e] & 0x80000000u) ? rows_v_bytes : cbv_bytes;
-                dst[e] = *(const half8_t*)(base + (o4[e] & 0x7FFFFFFFu) + 16 * (li & 3));
+                dst[e] = *(const half8_t*)(base + (o4[e] & 0x7FFFFFFFu) + 16 * (li % LPM));
             }
         };
 #pragma unroll 1
@@ -415,32 +480,32 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
 
     // ---- merge the waves, write the workgroup's partial -------------------------------------------------------
     __syncthreads();                                                   // the table is dead: its LDS becomes the merge area
-    float* s_m = (float*)smem;                                         // [waves][4] references
-    float* s_l = s_m + kW12 * kNH;                                     // [waves][4] sums
-    float* s_acc = s_l + kW12 * kNH;                                   // [waves][4][128]
+    float* s_m = (float*)smem;                                         // [waves][NHW] references
+    float* s_l = s_m + kW12 * NHW;                                     // [waves][NHW] sums
+    float* s_acc = s_l + kW12 * NHW;                                   // [waves][NHW][128]
 #pragma unroll
-    for (int h = 0; h < kNH; ++h) {
+    for (int h = 0; h < NHW; ++h) {
         const float lw = wave_sum(l_lane[h]);
-        if (lane == 0) { s_m[wave * kNH + h] = m_ref[h]; s_l[wave * kNH + h] = lw; }
+        if (lane == 0) { s_m[wave * NHW + h] = m_ref[h]; s_l[wave * NHW + h] = lw; }
 #pragma unroll
         for (int c = 0; c < 8; ++c) {                                  // the four groups hold shares of the same channels
             float a = acc[h][c];
             a += __shfl_xor(a, 16, 64);
             a += __shfl_xor(a, 32, 64);
-            if (grp == 0) s_acc[(wave * kNH + h) * kD + 8 * li + c] = a;
+            if (grp == 0) s_acc[(wave * NHW + h) * kD + 8 * li + c] = a;
         }
     }
     __syncthreads();
-    if (tid < kNH * kD) {
+    if (tid < NHW * kD) {
         const int h = tid >> 7, ch = tid & 127;
-        if (h < p.G) {
+        if (h < nh) {
             float m = kEmptyRef12;
-            for (int w = 0; w < kW12; ++w) m = fmaxf(m, s_m[w * kNH + h]);
+            for (int w = 0; w < kW12; ++w) m = fmaxf(m, s_m[w * NHW + h]);
             float l = 0.f, a = 0.f;
             for (int w = 0; w < kW12; ++w) {
-                const float f = fast_exp2(s_m[w * kNH + h] - m);
-                l = fmaf(s_l[w * kNH + h], f, l);
-                a = fmaf(s_acc[(w * kNH + h) * kD + ch], f, a);
+                const float f = fast_exp2(s_m[w * NHW + h] - m);
+                l = fmaf(s_l[w * NHW + h], f, l);
+                a = fmaf(s_acc[(w * NHW + h) * kD + ch], f, a);
             }
             float* dst = p.part + (((int64_t)b * p.Hq + h0 + h) * p.S + sp) * (kD + 2);
             dst[2 + ch] = a;
@@ -467,10 +532,11 @@ __global__ __launch_bounds__(kD) void decode12_merge(const float* __restrict__ p
 }
 
 // ---- decode-time Anchor Score on 12-bit codes (Eq. (4) with the single query row over K_eff; Sec. 3.2, last par.) --
-// Ranking needs fp32 scores, and an fp32 table for four heads would take 256 KB, so a workgroup handles two heads of
-// the group (128 KB) and the group's two halves add their shares of a token's scores (two commutative float adds
-// onto zeroed arrays: the result does not depend on their order).  PASS 0 leaves (max, sum of exp2) per head and
-// workgroup; PASS 1 merges them into the log-sum-exp in its prologue and writes the scores.
+// Ranking needs fp32 scores, and an fp32 table of 128 KB holds two heads (d32) or one head (d16), so a workgroup
+// walks its token range once per two (one) heads of the group, with that table in LDS: the first walk stores a
+// token's scores, the later ones add their heads' shares to them.  A token is always handled by the same thread, so
+// these are plain loads and stores in a fixed order (heads ascending) and the result is reproducible.  PASS 0 leaves
+// (max, sum of exp2) per head and workgroup; PASS 1 merges them into the log-sum-exp and writes the scores.
 struct D12AnsParams {
     const half_t* q;
     const uint8_t* codes_k;
@@ -482,35 +548,37 @@ struct D12AnsParams {
     int64_t N, N_cap;
     int k_k;
     float c1;
-    int Hq, Hkv, G, S, chunk, HH;         // HH = head halves per group: 1 (G <= 2) or 2
+    int Hq, Hkv, G, S, chunk;
 };
 
-constexpr size_t kD12AnsLds = (size_t)kM12 * kC12 * 8 + 1024 * 4 + 2 * kD * 4 + (kW12 * 4 + 8) * 4 + 16 * 4;
+constexpr size_t kD12AnsLds = (size_t)128 * 1024 + 1024 * 4 + 2 * kD * 4 + (kW12 * 4 + 8) * 4 + 16 * 4;
 
-template <int PASS>
+template <int kD12, int PASS>
 __global__ __launch_bounds__(kT12) void d12_ans_kernel(const D12AnsParams p)
 {
+    constexpr int kM12 = kD / kD12;
+    constexpr int NHA = kD12 == 32 ? 2 : 1;                            // heads per walk
+    constexpr int CB = 3 * kM12 / 2;
+    using lut_t = typename std::conditional<NHA == 2, float2, float>::type;
     extern __shared__ uint4_t smem_u4[];
     char* smem = (char*)smem_u4;
-    float2* s_lut = (float2*)smem;                                     // [4][4096] scores of the half's two heads
-    uint32_t* s_mk = (uint32_t*)(smem + kM12 * kC12 * 8);              // K-anchored tokens of the range
+    lut_t* s_lut = (lut_t*)smem;                                       // [M][4096] scores of this walk's heads
+    uint32_t* s_mk = (uint32_t*)(smem + 128 * 1024);                   // K-anchored tokens of the range
     float* s_qf = (float*)(s_mk + 1024);                               // [2][128]
     float* s_red = s_qf + 2 * kD;                                      // [waves][4] + 8
     int* s_misc = (int*)(s_red + kW12 * 4 + 8);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = blockIdx.x % p.Hkv;
-    int rest = blockIdx.x / p.Hkv;
-    const int hh = rest % p.HH;
-    rest /= p.HH;
+    const int rest = blockIdx.x / p.Hkv;
     const int b = rest / p.S, sp = rest % p.S;
     const int bg = b * p.Hkv + g;
-    const int hfirst = g * p.G + 2 * hh;                               // first query head of this half
-    const int nh = (p.G - 2 * hh) < 2 ? (p.G - 2 * hh) : 2;            // 1 or 2 heads
     const int64_t t0 = (int64_t)sp * p.chunk;
     const int64_t t1 = (t0 + p.chunk < p.N) ? t0 + p.chunk : p.N;
     const int32_t* idx_k = p.idx_k + (int64_t)bg * p.k_k;
+    const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * CB;
+    float* out_k = p.ans_k + (int64_t)bg * p.N;
+    float* out_v = p.ans_v + (int64_t)bg * p.N;
 
-    if (tid < 2 * kD) s_qf[tid] = ((tid >> 7) < nh) ? (float)p.q[((int64_t)b * p.Hq + hfirst) * kD + tid] : 0.f;
     s_mk[tid] = 0u;
     if (wave < 2) {
         const int r = lower_bound64(idx_k, p.k_k, (int)(wave ? t1 : t0), lane);
@@ -521,135 +589,133 @@ __global__ __launch_bounds__(kT12) void d12_ans_kernel(const D12AnsParams p)
         const int rel = idx_k[i] - (int)t0;
         atomicOr(&s_mk[rel >> 5], 1u << (rel & 31));
     }
-    {
-        const float4_t* tb = p.tab + (int64_t)bg * kM12 * kC12;
+
+    const int n_walks = (p.G + NHA - 1) / NHA;
+#pragma unroll 1
+    for (int hh = 0; hh < n_walks; ++hh) {
+        const int hfirst = g * p.G + NHA * hh;                         // first query head of this walk
+        const int nh = (p.G - NHA * hh) < NHA ? (p.G - NHA * hh) : NHA;
+        __syncthreads();                                               // the previous walk no longer reads the table or s_red
+        if (tid < 2 * kD) s_qf[tid] = ((tid >> 7) < nh) ? (float)p.q[((int64_t)b * p.Hq + hfirst) * kD + tid] : 0.f;
+        {
+            const float4_t* tb = p.tab + (int64_t)bg * kM12 * kC12;
 #pragma unroll 4
-        for (int e = tid; e < kM12 * kC12; e += kT12) {
-            const float4_t t = tb[e];
-            s_lut[e] = hh ? float2{t[2], t[3]} : float2{t[0], t[1]};
-        }
-    }
-    if (wave < 2) {                                                    // ||q_h||_2
-        const float a = s_qf[wave * kD + lane], c = s_qf[wave * kD + 64 + lane];
-        const float ss = wave_sum(fmaf(a, a, c * c));
-        if (lane == 0) s_red[kW12 * 4 + wave] = sqrtf(ss);
-    }
-    if (PASS == 1 && wave == 2 && lane < 2) {                          // log-sum-exp from the S partials of pass 0
-        float v = 0.f;
-        if (lane < nh) {
-            const float* sp_ = p.stat_part + ((int64_t)b * p.Hq + hfirst + lane) * p.S * 2;
-            float m = kNegBig;
-            for (int s = 0; s < p.S; ++s) m = fmaxf(m, sp_[2 * s]);
-            float l = 0.f;
-            for (int s = 0; s < p.S; ++s) l += sp_[2 * s + 1] * exp2f(sp_[2 * s] - m);
-            v = m + log2f(l);
-        }
-        s_red[kW12 * 4 + 4 + lane] = v;
-    }
-    __syncthreads();
-    const float qn0 = s_red[kW12 * 4], qn1 = s_red[kW12 * 4 + 1];
-    const float lse0 = s_red[kW12 * 4 + 4], lse1 = s_red[kW12 * 4 + 5];
-    float m_run[2] = {kNegBig, kNegBig}, l_run[2] = {0.f, 0.f};
-    float* out_k = p.ans_k + (int64_t)bg * p.N;
-    float* out_v = p.ans_v + (int64_t)bg * p.N;
-
-    auto consume = [&](float s0, float s1, int64_t tok) {
-        if (PASS == 0) {
-            const float sv[2] = {s0, s1};
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const float x = sv[h] - m_run[h];
-                if (x > 64.f) {                                        // first token (reference = kNegBig) or a big jump
-                    l_run[h] = l_run[h] * fast_exp2(-x) + 1.f;
-                    m_run[h] = sv[h];
-                } else {
-                    l_run[h] += fast_exp2(x);
-                }
+            for (int e = tid; e < kM12 * kC12; e += kT12) {
+                const float4_t t = tb[e];
+                if constexpr (NHA == 2) s_lut[e] = hh ? float2{t[2], t[3]} : float2{t[0], t[1]};
+                else s_lut[e] = hh == 0 ? t[0] : (hh == 1 ? t[1] : (hh == 2 ? t[2] : t[3]));
             }
-        } else {
-            const float a0 = fast_exp2(s0 - lse0);
-            const float a1 = nh > 1 ? fast_exp2(s1 - lse1) : 0.f;
-            const float t0_ = a0 * qn0, t1_ = a1 * qn1;
-            const float av = a0 + a1;
-            const float ak = fmaf(-a0, t0_, t0_) + fmaf(-a1, t1_, t1_);
-            if (p.HH == 1) { out_v[tok] = av; out_k[tok] = ak; }
-            else { unsafeAtomicAdd(out_v + tok, av); unsafeAtomicAdd(out_k + tok, ak); }
-        }
-    };
-
-    // ---- stream: one token per lane, code loads one round ahead; K-anchored tokens are left to the loop below
-    const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * 6;
-    auto load6 = [&](int64_t tok, uint32_t& lo, uint32_t& hi) {
-        const uint16_t* s = (const uint16_t*)(ck + tok * 6);
-        lo = (uint32_t)s[0] | ((uint32_t)s[1] << 16);
-        hi = (uint32_t)s[2];
-    };
-    uint32_t nlo = 0u, nhi = 0u;
-    if (t0 + tid < t1) load6(t0 + tid, nlo, nhi);
-    for (int64_t tok = t0 + tid; tok < t1; tok += kT12) {
-        const uint32_t klo = nlo, khi = nhi;
-        if (tok + kT12 < t1) load6(tok + kT12, nlo, nhi);
-        float s0 = 0.f, s1 = 0.f;
-#pragma unroll
-        for (int m = 0; m < kM12; ++m) {
-            const float2 e = s_lut[m * kC12 + code12(klo, khi, m)];
-            s0 += e.x;
-            s1 += e.y;
-        }
-        const int rel = (int)(tok - t0);
-        if (!((s_mk[rel >> 5] >> (rel & 31)) & 1u)) consume(s0, s1, tok);
-    }
-    // ---- K-anchored tokens: score from the FP16 row, 16 lanes per token and 8 channels each; blocks of 64 list
-    // entries are dealt round-robin over the S workgroups of the head half
-    {
-        const int sub = lane >> 4, l16 = lane & 15;
-        float qv[2][8];
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) qv[h][e] = s_qf[h * kD + 8 * l16 + e];
-        for (int i0 = sp * (4 * kW12) + 4 * wave; i0 < p.k_k; i0 += p.S * (4 * kW12)) {
-            const int i = i0 + sub;
-            const bool on = i < p.k_k;
-            const int64_t tok = on ? idx_k[i] : t0;
-            const half8_t v = *(const half8_t*)(p.rows_k + ((int64_t)bg * p.k_k + (on ? i : 0)) * kD + 8 * l16);
-            float s[2];
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                float d = 0.f;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) d = fmaf(qv[h][e], (float)v[e], d);
-#pragma unroll
-                for (int off = 1; off < 16; off <<= 1) d += __shfl_xor(d, off, 64);
-                s[h] = d * p.c1;
-            }
-            if (on && l16 == 0) consume(s[0], s[1], tok);
-        }
-    }
-    if (PASS == 0) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const float m_w = wave_max(m_run[h]);
-            const float l_w = wave_sum(l_run[h] * fast_exp2(m_run[h] - m_w));
-            if (lane == 0) { s_red[wave * 4 + h] = m_w; s_red[wave * 4 + 2 + h] = l_w; }
         }
         __syncthreads();
-        if (tid < nh) {
-            float m = kNegBig;
-            for (int w = 0; w < kW12; ++w) m = fmaxf(m, s_red[w * 4 + tid]);
-            float l = 0.f;
-            for (int w = 0; w < kW12; ++w) l += s_red[w * 4 + 2 + tid] * fast_exp2(s_red[w * 4 + tid] - m);
-            float* dst = p.stat_part + (((int64_t)b * p.Hq + hfirst + tid) * p.S + sp) * 2;
-            dst[0] = m;
-            dst[1] = l;
+        if (wave < 2) {                                                // ||q_h||_2
+            const float a = s_qf[wave * kD + lane], c = s_qf[wave * kD + 64 + lane];
+            const float ss = wave_sum(fmaf(a, a, c * c));
+            if (lane == 0) s_red[kW12 * 4 + wave] = sqrtf(ss);
+        }
+        if (PASS == 1 && wave == 2 && lane < 2) {                      // log-sum-exp from the S partials of pass 0
+            float v = 0.f;
+            if (lane < nh) {
+                const float* sp_ = p.stat_part + ((int64_t)b * p.Hq + hfirst + lane) * p.S * 2;
+                float m = kNegBig;
+                for (int s = 0; s < p.S; ++s) m = fmaxf(m, sp_[2 * s]);
+                float l = 0.f;
+                for (int s = 0; s < p.S; ++s) l += sp_[2 * s + 1] * exp2f(sp_[2 * s] - m);
+                v = m + log2f(l);
+            }
+            s_red[kW12 * 4 + 4 + lane] = v;
+        }
+        __syncthreads();
+        const float qn0 = s_red[kW12 * 4], qn1 = s_red[kW12 * 4 + 1];
+        const float lse0 = s_red[kW12 * 4 + 4], lse1 = s_red[kW12 * 4 + 5];
+        float m_run[2] = {kNegBig, kNegBig}, l_run[2] = {0.f, 0.f};
+
+        auto consume = [&](float s0, float s1, int64_t tok) {
+            if (PASS == 0) {
+                const float sv[2] = {s0, s1};
+#pragma unroll
+                for (int h = 0; h < NHA; ++h) {
+                    const float x = sv[h] - m_run[h];
+                    if (x > 64.f) {                                    // first token (reference = kNegBig) or a big jump
+                        l_run[h] = l_run[h] * fast_exp2(-x) + 1.f;
+                        m_run[h] = sv[h];
+                    } else {
+                        l_run[h] += fast_exp2(x);
+                    }
+                }
+            } else {
+                const float a0 = fast_exp2(s0 - lse0);
+                const float a1 = (NHA > 1 && nh > 1) ? fast_exp2(s1 - lse1) : 0.f;
+                const float t0_ = a0 * qn0, t1_ = a1 * qn1;
+                float av = a0 + a1;
+                float ak = fmaf(-a0, t0_, t0_) + fmaf(-a1, t1_, t1_);
+                if (hh > 0) { av += out_v[tok]; ak += out_k[tok]; }    // earlier walks' heads, written by this thread
+                out_v[tok] = av;
+                out_k[tok] = ak;
+            }
+        };
+
+        // ---- stream: one token per lane, code loads one round ahead; K-anchored tokens are left to the loop below
+        uint32_t nw[3] = {0u, 0u, 0u};
+        if (t0 + tid < t1) load_cw<kD12>(ck, t0 + tid, nw);
+        for (int64_t tok = t0 + tid; tok < t1; tok += kT12) {
+            const uint32_t kw[3] = {nw[0], nw[1], nw[2]};
+            if (tok + kT12 < t1) load_cw<kD12>(ck, tok + kT12, nw);
+            float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+            for (int m = 0; m < kM12; ++m) {
+                const lut_t e = s_lut[m * kC12 + code12(kw, m)];
+                if constexpr (NHA == 2) { s0 += e.x; s1 += e.y; }
+                else s0 += e;
+            }
+            const int rel = (int)(tok - t0);
+            if (!((s_mk[rel >> 5] >> (rel & 31)) & 1u)) consume(s0, s1, tok);
+        }
+        // ---- K-anchored tokens: score from the FP16 row, 16 lanes per token and 8 channels each; blocks of 64 list
+        // entries are dealt round-robin over the S workgroups of the head
+        {
+            const int sub = lane >> 4, l16 = lane & 15;
+            float qv[NHA][8];
+#pragma unroll
+            for (int h = 0; h < NHA; ++h)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) qv[h][e] = s_qf[h * kD + 8 * l16 + e];
+            for (int i0 = sp * (4 * kW12) + 4 * wave; i0 < p.k_k; i0 += p.S * (4 * kW12)) {
+                const int i = i0 + sub;
+                const bool on = i < p.k_k;
+                const int64_t tok = on ? idx_k[i] : t0;
+                const half8_t v = *(const half8_t*)(p.rows_k + ((int64_t)bg * p.k_k + (on ? i : 0)) * kD + 8 * l16);
+                float s[2] = {0.f, 0.f};
+#pragma unroll
+                for (int h = 0; h < NHA; ++h) {
+                    float d = 0.f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) d = fmaf(qv[h][e], (float)v[e], d);
+#pragma unroll
+                    for (int off = 1; off < 16; off <<= 1) d += __shfl_xor(d, off, 64);
+                    s[h] = d * p.c1;
+                }
+                if (on && l16 == 0) consume(s[0], s[1], tok);
+            }
+        }
+        if (PASS == 0) {
+#pragma unroll
+            for (int h = 0; h < NHA; ++h) {
+                const float m_w = wave_max(m_run[h]);
+                const float l_w = wave_sum(l_run[h] * fast_exp2(m_run[h] - m_w));
+                if (lane == 0) { s_red[wave * 4 + h] = m_w; s_red[wave * 4 + 2 + h] = l_w; }
+            }
+            __syncthreads();
+            if (tid < nh) {
+                float m = kNegBig;
+                for (int w = 0; w < kW12; ++w) m = fmaxf(m, s_red[w * 4 + tid]);
+                float l = 0.f;
+                for (int w = 0; w < kW12; ++w) l += s_red[w * 4 + 2 + tid] * fast_exp2(s_red[w * 4 + tid] - m);
+                float* dst = p.stat_part + (((int64_t)b * p.Hq + hfirst + tid) * p.S + sp) * 2;
+                dst[0] = m;
+                dst[1] = l;
+            }
         }
     }
-}
-
-__global__ __launch_bounds__(256) void d12_zero(float* p, int64_t n)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0.f;
 }
 
 struct D12Plan {
@@ -674,29 +740,24 @@ D12Plan d12_plan(const Geom& g, int64_t N)
     pl.chunk = (int)chunk;
     size_t off = 0;
     pl.off_part = off; off += align_up((size_t)g.B * g.Hq * S * (kD + 2) * sizeof(float));
-    pl.off_tab = off;  off += align_up((size_t)g.B * g.Hkv * kM12 * kC12 * sizeof(float4_t));
-    pl.off_amax = off; off += align_up((size_t)g.B * g.Hkv * kTabBlocks * kNH * sizeof(float));
+    pl.off_tab = off;  off += align_up((size_t)g.B * g.Hkv * g.M * kC12 * sizeof(float4_t));
+    pl.off_amax = off; off += align_up((size_t)g.B * g.Hkv * tab_blocks(g.d) * kNH * sizeof(float));
     pl.off_stat = off; off += align_up((size_t)g.B * g.Hq * S * 2 * sizeof(float));
     pl.total = off;
     return pl;
 }
 
-constexpr size_t kD12Lds = (size_t)kM12 * kC12 * 8 + 2 * 1024 * 4 + kNH * kD * 2 + 64 * 4 + 16 * 4 +
-                           (size_t)kW12 * 64 * 8 + (size_t)kW12 * 256 * 2;
-static_assert(kD12Lds <= 160 * 1024, "LDS budget");
-
-}  // namespace
-
-size_t decode12_workspace_bytes(const Geom& g, int64_t N) { return d12_plan(g, N).total; }
-
-hipError_t launch_decode12(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st)
+template <int DS>
+hipError_t launch_decode12_t(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st)
 {
     const D12Plan pl = d12_plan(g, a.N);
+    constexpr size_t lds = d12_lds(DS);
     static const hipError_t setup = []() {
-        return hipFuncSetAttribute((const void*)decode12_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kD12Lds);
+        return hipFuncSetAttribute((const void*)decode12_kernel<DS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     }();
     if (setup != hipSuccess) return setup;
-    if ((int64_t)g.B * g.Hkv * pl.S > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int HH = (g.G + heads_per_wg(DS) - 1) / heads_per_wg(DS);
+    if ((int64_t)g.B * g.Hkv * pl.S * HH > 0x7fffffffLL) return hipErrorInvalidValue;
     if ((int64_t)g.B * g.Hkv * a.k_v * kD * 2 >= 0x7fffffffLL) return hipErrorInvalidValue;   // 31-bit byte offsets into rows_v
     D12Params p;
     p.q = a.q; p.codes_k = a.codes_k; p.codes_v = a.codes_v; p.cb_k = a.cb_k; p.cb_v = a.cb_v;
@@ -705,18 +766,19 @@ hipError_t launch_decode12(const Geom& g, const DecodeArgs& a, void* ws, hipStre
     p.part = (float*)(w + pl.off_part); p.tab = (const float4_t*)(w + pl.off_tab); p.tab_amax = (const float*)(w + pl.off_amax);
     p.N = a.N; p.N_cap = a.N_cap; p.k_k = (int)a.k_k; p.k_v = (int)a.k_v;
     p.c1 = a.scale * kLog2e; p.Hq = g.Hq; p.Hkv = g.Hkv; p.G = g.G; p.S = a.N > 0 ? pl.S : 0; p.chunk = pl.chunk;
+    p.HH = HH;
     if (a.N > 0) {
-        hipLaunchKernelGGL(d12_table_kernel, dim3((unsigned)(g.B * g.Hkv), kTabBlocks), dim3(kTabThreads), 0, st, a.q, a.cb_k,
-                           p.c1, g.Hq, g.Hkv, g.G, (float4_t*)(w + pl.off_tab), (float*)(w + pl.off_amax));
-        hipLaunchKernelGGL(decode12_kernel, dim3((unsigned)(g.B * g.Hkv * pl.S)), dim3(kT12), kD12Lds, st, p);
+        hipLaunchKernelGGL(d12_table_kernel<DS>, dim3((unsigned)(g.B * g.Hkv), tab_blocks(DS)), dim3(kTabThreads), 0, st, a.q,
+                           a.cb_k, p.c1, g.Hq, g.Hkv, g.G, (float4_t*)(w + pl.off_tab), (float*)(w + pl.off_amax));
+        hipLaunchKernelGGL(decode12_kernel<DS>, dim3((unsigned)(g.B * g.Hkv * HH * pl.S)), dim3(kT12), lds, st, p);
     }
     hipLaunchKernelGGL(decode12_merge, dim3((unsigned)(g.B * g.Hq)), dim3(kD), 0, st, (const float*)p.part, p.S, a.out);
     if (a.ans_k && a.N > 0) {
         static const hipError_t setup_ans = []() {
-            hipError_t e1 = hipFuncSetAttribute((const void*)d12_ans_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize,
+            hipError_t e1 = hipFuncSetAttribute((const void*)d12_ans_kernel<DS, 0>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                 (int)kD12AnsLds);
             if (e1 != hipSuccess) return e1;
-            return hipFuncSetAttribute((const void*)d12_ans_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+            return hipFuncSetAttribute((const void*)d12_ans_kernel<DS, 1>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)kD12AnsLds);
         }();
         if (setup_ans != hipSuccess) return setup_ans;
@@ -724,17 +786,20 @@ hipError_t launch_decode12(const Geom& g, const DecodeArgs& a, void* ws, hipStre
         d.q = a.q; d.codes_k = a.codes_k; d.idx_k = a.idx_k; d.rows_k = a.rows_k; d.tab = p.tab;
         d.stat_part = (float*)(w + pl.off_stat); d.ans_k = a.ans_k; d.ans_v = a.ans_v; d.N = a.N; d.N_cap = a.N_cap;
         d.k_k = (int)a.k_k; d.c1 = p.c1; d.Hq = g.Hq; d.Hkv = g.Hkv; d.G = g.G; d.S = pl.S; d.chunk = pl.chunk;
-        d.HH = g.G > 2 ? 2 : 1;
-        const unsigned grid = (unsigned)(g.B * g.Hkv * d.HH * pl.S);
-        if (d.HH > 1) {
-            const int64_t n = (int64_t)g.B * g.Hkv * a.N;
-            hipLaunchKernelGGL(d12_zero, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a.ans_k, n);
-            hipLaunchKernelGGL(d12_zero, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a.ans_v, n);
-        }
-        hipLaunchKernelGGL(d12_ans_kernel<0>, dim3(grid), dim3(kT12), kD12AnsLds, st, d);
-        hipLaunchKernelGGL(d12_ans_kernel<1>, dim3(grid), dim3(kT12), kD12AnsLds, st, d);
+        const unsigned grid = (unsigned)(g.B * g.Hkv * pl.S);
+        hipLaunchKernelGGL((d12_ans_kernel<DS, 0>), dim3(grid), dim3(kT12), kD12AnsLds, st, d);
+        hipLaunchKernelGGL((d12_ans_kernel<DS, 1>), dim3(grid), dim3(kT12), kD12AnsLds, st, d);
     }
     return hipGetLastError();
+}
+
+}  // namespace
+
+size_t decode12_workspace_bytes(const Geom& g, int64_t N) { return d12_plan(g, N).total; }
+
+hipError_t launch_decode12(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st)
+{
+    return g.d == 32 ? launch_decode12_t<32>(g, a, ws, st) : launch_decode12_t<16>(g, a, ws, st);
 }
 
 }  // namespace antkv

@@ -1,11 +1,12 @@
-// VQ encode for the 12-bit codebooks (paper Sec. 3.1 with the d32 / 4096-centroid setting of Sec. 4, "0.375 bit"):
-// nearest of 4096 centroids for each 32-channel sub-vector, M = 4 codes per token row packed into 6 bytes.
+// VQ encode for the 12-bit codebooks (paper Sec. 3.1 with the 4096-centroid settings of Sec. 4: d32, "0.375 bit", and
+// d16, "0.75 bit"): nearest of 4096 centroids for each 32- or 16-channel sub-vector, the M = 4 or 8 codes of a token
+// row packed into 6 or 12 bytes.
 //
 // argmin_c ||x - c||^2 = argmax_c (x.c - ||c||^2 / 2).  A 1 MB codebook per KV head does not fit LDS, so centroid
 // tiles come straight from global memory (L2; the four waves of a workgroup walk the same tiles, so L1 serves three
 // of them) and only the -||c||^2/2 table of the current sub-space (16 KB) is kept in LDS.
-//   level 1  per 32 tokens x 32 centroids: two v_mfma_f32_32x32x16_f16 with centroids on the row axis and tokens
-//            on the column axis, accumulator pre-loaded with -||c||^2/2.  A lane owns one token and 16 of the 32
+//   level 1  per 32 tokens x 32 centroids: v_mfma_f32_32x32x16_f16 (one per 16 channels) with centroids on the row
+//            axis and tokens on the column axis, accumulator pre-loaded with -||c||^2/2.  A lane owns one token and 16 of the 32
 //            centroid scores; it keeps the best score and the index of the tile it came from (a max3 tree, one
 //            compare and two selects per tile, i.e. under one VALU instruction per candidate).
 //   level 2  the lane recomputes the 16 scores of its best tile with packed dot products (v_dot2_f32_f16), in
@@ -22,8 +23,6 @@ namespace {
 constexpr int kE12Threads = 256;
 constexpr int kE12Tokens = 256;          // tokens per workgroup: 4 waves x 2 groups of 32
 constexpr int kC12 = 4096;
-constexpr int kD12 = 32;                 // sub-vector width
-constexpr int kM12 = kD / kD12;          // 4 sub-spaces
 
 __device__ __forceinline__ float max3f(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
@@ -37,10 +36,15 @@ __device__ __forceinline__ float dot8(const half8_t& a, const half8_t& b, float 
     return acc;
 }
 
+// kD12 = sub-vector width (32 or 16)
+template <int kD12>
 __global__ __launch_bounds__(kE12Threads) void encode12_kernel(
     const half_t* __restrict__ x, int64_t xs_b, int64_t xs_h, int64_t xs_t, int64_t n_tok,
     const half_t* __restrict__ cb, uint8_t* __restrict__ codes, int64_t N_cap, int64_t token_offset, int Hkv)
 {
+    constexpr int kM12 = kD / kD12;                                 // 4 or 8 sub-spaces
+    constexpr int NU = kD12 / 8;                                    // 16-byte chunks of a sub-vector
+    constexpr int NS = kD12 / 16;                                   // MFMA k-steps
     __shared__ __attribute__((aligned(16))) float s_nrm[kC12];      // -||c||^2 / 2 of the current sub-space
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, kh = lane >> 5;
@@ -59,7 +63,7 @@ __global__ __launch_bounds__(kE12Threads) void encode12_kernel(
         for (int c = tid; c < kC12; c += kE12Threads) {
             float s = 0.f;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < NU; ++u) {
                 const half8_t v = *(const half8_t*)(cbm + c * kD12 + 8 * u);
                 s = dot8(v, v, s);
             }
@@ -72,18 +76,24 @@ __global__ __launch_bounds__(kE12Threads) void encode12_kernel(
             const int64_t tl = t < n_tok ? t : n_tok - 1;
             const half_t* xr = xbase + tl * xs_t + m * kD12;
             // B operand: k-step s holds channels 16 s + 8 kh .. + 7 of this lane's token
-            const half8_t xb0 = *(const half8_t*)(xr + 8 * kh), xb1 = *(const half8_t*)(xr + 16 + 8 * kh);
+            half8_t xb[NS];
+#pragma unroll
+            for (int s = 0; s < NS; ++s) xb[s] = *(const half8_t*)(xr + 16 * s + 8 * kh);
             float best = -3.0e38f;
             int best_blk = 0;
             // A operand of tile blk: centroid 32 blk + n, same channel split; loads run one tile ahead
             const half_t* ap = cbm + n * kD12 + 8 * kh;
-            half8_t a0 = *(const half8_t*)(ap), a1 = *(const half8_t*)(ap + 16);
+            half8_t an[NS];
+#pragma unroll
+            for (int s = 0; s < NS; ++s) an[s] = *(const half8_t*)(ap + 16 * s);
 #pragma unroll 2
             for (int blk = 0; blk < kC12 / 32; ++blk) {
-                const half8_t c0 = a0, c1 = a1;
+                half8_t ac[NS];
+#pragma unroll
+                for (int s = 0; s < NS; ++s) ac[s] = an[s];
                 if (blk + 1 < kC12 / 32) {
-                    a0 = *(const half8_t*)(ap + (blk + 1) * 32 * kD12);
-                    a1 = *(const half8_t*)(ap + (blk + 1) * 32 * kD12 + 16);
+#pragma unroll
+                    for (int s = 0; s < NS; ++s) an[s] = *(const half8_t*)(ap + (blk + 1) * 32 * kD12 + 16 * s);
                 }
                 float16_t acc;
 #pragma unroll
@@ -92,8 +102,8 @@ __global__ __launch_bounds__(kE12Threads) void encode12_kernel(
 #pragma unroll
                     for (int e = 0; e < 4; ++e) acc[4 * qd + e] = nb[e];
                 }
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(c0, xb0, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(c1, xb1, acc, 0, 0, 0);
+#pragma unroll
+                for (int s = 0; s < NS; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ac[s], xb[s], acc, 0, 0, 0);
                 float mx = max3f(acc[0], acc[1], acc[2]);
 #pragma unroll
                 for (int r = 3; r < 15; r += 2) mx = max3f(mx, acc[r], acc[r + 1]);
@@ -101,9 +111,9 @@ __global__ __launch_bounds__(kE12Threads) void encode12_kernel(
                 if (mx > best) { best = mx; best_blk = blk; }       // strict: an equal later tile does not replace
             }
             // level 2: the 16 candidates of the best tile, ascending centroid index
-            half8_t xf[4];
+            half8_t xf[NU];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) xf[u] = *(const half8_t*)(xr + 8 * u);
+            for (int u = 0; u < NU; ++u) xf[u] = *(const half8_t*)(xr + 8 * u);
             float bv = -3.0e38f;
             int bc = 0;
 #pragma unroll 4
@@ -112,7 +122,7 @@ __global__ __launch_bounds__(kE12Threads) void encode12_kernel(
                 const half_t* cp = cbm + c * kD12;
                 float s = s_nrm[c];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) s = dot8(*(const half8_t*)(cp + 8 * u), xf[u], s);
+                for (int u = 0; u < NU; ++u) s = dot8(*(const half8_t*)(cp + 8 * u), xf[u], s);
                 if (s > bv) { bv = s; bc = c; }
             }
             // the two halves of the token's candidates: larger score wins, equal scores go to the lower index
@@ -122,18 +132,23 @@ __global__ __launch_bounds__(kE12Threads) void encode12_kernel(
             code[tg][m] = bc;
         }
     }
-    // six bytes per token: the four 12-bit codes packed little-endian (c0 | c1 << 12 | c2 << 24 | c3 << 36)
+    // the token's 12-bit codes packed little-endian (code m at bits 12 m .. 12 m + 11): 6 or 12 bytes per token
     if (kh == 0) {
 #pragma unroll
         for (int tg = 0; tg < 2; ++tg) {
             const int64_t t = (int64_t)blockIdx.x * kE12Tokens + wave * 64 + tg * 32 + n;
             if (t < n_tok) {
-                uint16_t* dst = (uint16_t*)(codes + (((int64_t)b * Hkv + g) * N_cap + token_offset + t) * 6);
-                const uint32_t lo = (uint32_t)code[tg][0] | ((uint32_t)code[tg][1] << 12) | ((uint32_t)code[tg][2] << 24);
-                const uint32_t hi = ((uint32_t)code[tg][2] >> 8) | ((uint32_t)code[tg][3] << 4);
-                dst[0] = (uint16_t)lo;
-                dst[1] = (uint16_t)(lo >> 16);
-                dst[2] = (uint16_t)hi;
+                uint16_t* dst = (uint16_t*)(codes + (((int64_t)b * Hkv + g) * N_cap + token_offset + t) * (kM12 * 3 / 2));
+#pragma unroll
+                for (int q4 = 0; q4 < kM12 / 4; ++q4) {               // four codes fill three 16-bit words
+                    const uint32_t c0 = (uint32_t)code[tg][4 * q4], c1 = (uint32_t)code[tg][4 * q4 + 1];
+                    const uint32_t c2 = (uint32_t)code[tg][4 * q4 + 2], c3 = (uint32_t)code[tg][4 * q4 + 3];
+                    const uint32_t lo = c0 | (c1 << 12) | (c2 << 24);
+                    const uint32_t hi = (c2 >> 8) | (c3 << 4);
+                    dst[3 * q4 + 0] = (uint16_t)lo;
+                    dst[3 * q4 + 1] = (uint16_t)(lo >> 16);
+                    dst[3 * q4 + 2] = (uint16_t)hi;
+                }
             }
         }
     }
@@ -146,8 +161,12 @@ hipError_t launch_encode12(const Geom& g, const half_t* x, int64_t xs_b, int64_t
 {
     if (n_tok == 0 || g.B == 0) return hipSuccess;
     dim3 grid((unsigned)((n_tok + kE12Tokens - 1) / kE12Tokens), (unsigned)(g.B * g.Hkv));
-    hipLaunchKernelGGL(encode12_kernel, grid, dim3(kE12Threads), 0, st, x, xs_b, xs_h, xs_t, n_tok, cb, codes, N_cap,
-                       token_offset, g.Hkv);
+    if (g.d == 32)
+        hipLaunchKernelGGL(encode12_kernel<32>, grid, dim3(kE12Threads), 0, st, x, xs_b, xs_h, xs_t, n_tok, cb, codes, N_cap,
+                           token_offset, g.Hkv);
+    else
+        hipLaunchKernelGGL(encode12_kernel<16>, grid, dim3(kE12Threads), 0, st, x, xs_b, xs_h, xs_t, n_tok, cb, codes, N_cap,
+                           token_offset, g.Hkv);
     return hipGetLastError();
 }
 

@@ -3,7 +3,7 @@
 // (sequence, KV head, K|V) encodes the retiring token's row to its codes (nearest centroid per sub-vector,
 // Sec. 3.1), moves the window one place down and appends the new token's row.  The step is latency-bound
 // (one row per head), so the encode here is plain fp32 FMA work, one centroid per thread at a time, not the MFMA
-// kernel.  With 4096 centroids (d_sub 32) a thread walks 16 of them per sub-space and the four 12-bit codes are packed.
+// kernel.  With 4096 centroids (d_sub 32 or 16) a thread walks 16 of them per sub-space and the 12-bit codes are packed.
 #include "common.h"
 
 namespace antkv {
@@ -12,7 +12,7 @@ namespace {
 
 constexpr int kApThreads = 256;   // thread c scores centroids c, c + 256, ... of every sub-space
 
-// NC = centroids per sub-space: 256 (one code byte per sub-space) or 4096 (d_sub 32: four 12-bit codes in 6 bytes)
+// NC = centroids per sub-space: 256 (one code byte per sub-space) or 4096 (M 12-bit codes packed into 3 M / 2 bytes)
 template <int DSUB, int NC>
 __global__ __launch_bounds__(kApThreads) void append_kernel(
     const half_t* __restrict__ k_new, const half_t* __restrict__ v_new, const half_t* __restrict__ cb_k,
@@ -21,8 +21,8 @@ __global__ __launch_bounds__(kApThreads) void append_kernel(
     half_t* __restrict__ rows_v, int64_t k_v, int64_t N, int W, int Hkv)
 {
     constexpr int M = kD / DSUB;
-    constexpr int kCodeBytes = NC == 256 ? M : 6;
-    static_assert(NC == 256 || (NC == 4096 && M == 4), "12-bit codes come four to a token");
+    constexpr int kCodeBytes = NC == 256 ? M : 3 * M / 2;
+    static_assert(NC == 256 || (NC == 4096 && M % 4 == 0), "12-bit codes are packed four to three 16-bit words");
     __shared__ float s_x[kD];
     __shared__ float s_val[M][4];
     __shared__ int s_idx[M][4];
@@ -95,12 +95,14 @@ __global__ __launch_bounds__(kApThreads) void append_kernel(
         if constexpr (NC == 256) codes[tid] = (uint8_t)who;
         else s_code[tid] = who;
     }
-    if constexpr (NC != 256) {                         // four 12-bit codes, little-endian, in 6 bytes
+    if constexpr (NC != 256) {                         // 12-bit codes, little-endian: code m at bits 12 m .. 12 m + 11
         __syncthreads();
-        if (tid == 0) {
-            const uint32_t lo = (uint32_t)s_code[0] | ((uint32_t)s_code[1] << 12) | ((uint32_t)s_code[2] << 24);
-            const uint32_t hi = ((uint32_t)s_code[2] >> 8) | ((uint32_t)s_code[3] << 4);
-            uint16_t* dst = (uint16_t*)codes;
+        if (tid < M / 4) {
+            const uint32_t c0 = (uint32_t)s_code[4 * tid], c1 = (uint32_t)s_code[4 * tid + 1];
+            const uint32_t c2 = (uint32_t)s_code[4 * tid + 2], c3 = (uint32_t)s_code[4 * tid + 3];
+            const uint32_t lo = c0 | (c1 << 12) | (c2 << 24);
+            const uint32_t hi = (c2 >> 8) | (c3 << 4);
+            uint16_t* dst = (uint16_t*)codes + 3 * tid;
             dst[0] = (uint16_t)lo;
             dst[1] = (uint16_t)(lo >> 16);
             dst[2] = (uint16_t)hi;
@@ -127,7 +129,8 @@ hipError_t launch_append(const Geom& g, const half_t* k_new, const half_t* v_new
 #define ANTKV_AP(DS, NCEN)                                                                                           \
     hipLaunchKernelGGL((append_kernel<DS, NCEN>), grid, block, 0, st, k_new, v_new, cb_k, cb_v, codes_k, codes_v, N_cap, \
                        idx_k, rows_k, k_k, idx_v, rows_v, k_v, N, W, g.Hkv)
-    if (g.C == 4096) ANTKV_AP(32, 4096);
+    if (g.C == 4096 && g.d == 32) ANTKV_AP(32, 4096);
+    else if (g.C == 4096) ANTKV_AP(16, 4096);
     else if (g.d == 4) ANTKV_AP(4, 256);
     else if (g.d == 8) ANTKV_AP(8, 256);
     else ANTKV_AP(16, 256);

@@ -57,20 +57,28 @@ def check_index_sets(got: np.ndarray, want: np.ndarray, margin: np.ndarray, what
     return soft
 
 
-def unpack12(packed: np.ndarray, M: int = 4) -> np.ndarray:
-    """[..., 3M/2] bytes -> [..., M] codes: the M 12-bit codes of a token packed little-endian."""
+def unpack12(packed: np.ndarray) -> np.ndarray:
+    """[..., 3M/2] bytes -> [..., M] codes: the M 12-bit codes of a token packed little-endian (code m at bits
+    12 m .. 12 m + 11 of the row, i.e. four codes per six bytes)."""
     b = packed.astype(np.int64)
-    word = np.zeros(b.shape[:-1], dtype=np.int64)
-    for i in range(b.shape[-1]):
-        word |= b[..., i] << (8 * i)
-    return np.stack([(word >> (12 * m)) & 0xFFF for m in range(M)], axis=-1).astype(np.int32)
+    assert b.shape[-1] % 6 == 0
+    out = []
+    for grp in range(b.shape[-1] // 6):
+        word = np.zeros(b.shape[:-1], dtype=np.int64)
+        for i in range(6):
+            word |= b[..., 6 * grp + i] << (8 * i)
+        out += [(word >> (12 * m)) & 0xFFF for m in range(4)]
+    return np.stack(out, axis=-1).astype(np.int32)
 
 
 def pack12(codes: np.ndarray) -> np.ndarray:
-    """[..., M] codes (< 4096) -> [..., 3M/2] bytes, the inverse of unpack12."""
+    """[..., M] codes (< 4096, M a multiple of 4) -> [..., 3M/2] bytes, the inverse of unpack12."""
     c = codes.astype(np.int64)
-    word = np.zeros(c.shape[:-1], dtype=np.int64)
-    for m in range(c.shape[-1]):
-        word |= c[..., m] << (12 * m)
-    nb = c.shape[-1] * 12 // 8
-    return np.stack([(word >> (8 * i)) & 0xFF for i in range(nb)], axis=-1).astype(np.uint8)
+    assert c.shape[-1] % 4 == 0
+    out = []
+    for grp in range(c.shape[-1] // 4):
+        word = np.zeros(c.shape[:-1], dtype=np.int64)
+        for m in range(4):
+            word |= c[..., 4 * grp + m] << (12 * m)
+        out += [(word >> (8 * i)) & 0xFF for i in range(6)]
+    return np.stack(out, axis=-1).astype(np.uint8)

@@ -40,7 +40,8 @@ def test_geometry_validation(lib):
     assert enc(_g()) == OK                                   # n_tok == 0 is a no-op
     assert enc(_g(d=2)) == EUNSUPPORTED
     assert enc(_g(d=32)) == EUNSUPPORTED
-    assert enc(_g(C=4096)) == EUNSUPPORTED
+    assert enc(_g(C=4096)) == EUNSUPPORTED                   # 4096 centroids go with d_sub 32 or 16 only
+    assert enc(_g(d=32, C=4096)) == OK and enc(_g(d=16, C=4096)) == OK
     assert enc(_g(D=64)) == EUNSUPPORTED
     assert enc(_g(Hq=64)) == EUNSUPPORTED                    # group size 8
     assert enc(_g(Hq=30)) == EINVAL                          # Hq not a multiple of Hkv

@@ -1,5 +1,6 @@
-"""GPU parity for the 12-bit codebooks (paper Sec. 4: 32-channel sub-vectors, 4096 centroids, "0.375 bit"):
-encode and decode attention against the CPU oracle, which is generic in the codebook size."""
+"""GPU parity for the 12-bit codebooks (paper Sec. 4: 4096 centroids with 32-channel sub-vectors, "0.375 bit", and with
+16-channel sub-vectors, "0.75 bit"): encode, decode attention, append and decode-time Anchor Score against the CPU
+oracle, which is generic in the codebook size."""
 import numpy as np
 import pytest
 import torch
@@ -10,14 +11,23 @@ from workloads import make_codebooks, make_qkv
 
 pytestmark = pytest.mark.gpu
 
-D_SUB, C = 32, 4096
+C = 4096
 
 
-@pytest.fixture(scope="module")
-def books():
-    """K and V codebooks [2 KV heads][4][4096][32] picked from 6000 synthetic rows."""
+class Books(tuple):
+    """(K codebook, V codebook) + the format: d = sub-vector width, M = codes per token, nbytes = 3 M / 2."""
+    def __new__(cls, k, v, d):
+        self = super().__new__(cls, (k, v))
+        self.d, self.M, self.nbytes = d, 128 // d, 128 // d * 3 // 2
+        return self
+
+
+@pytest.fixture(scope="module", params=[32, 16], ids=["d32", "d16"])
+def books(request):
+    """K and V codebooks [2 KV heads][M][4096][d] picked from 6000 synthetic rows."""
+    d = request.param
     _, k, v = make_qkv(81, 1, 2, 2, 6000, 1, 128)
-    return (make_codebooks(81, k, D_SUB, C, "k", max_sample=6000), make_codebooks(81, v, D_SUB, C, "v", max_sample=6000))
+    return Books(make_codebooks(81, k, d, C, "k", max_sample=6000), make_codebooks(81, v, d, C, "v", max_sample=6000), d)
 
 
 def test_pack_unpack_roundtrip():
@@ -25,15 +35,18 @@ def test_pack_unpack_roundtrip():
     c = rng.integers(0, 4096, size=(3, 5, 4))
     assert np.array_equal(unpack12(pack12(c)), c) and pack12(c).shape == (3, 5, 6)
     assert pack12(np.array([[0x123, 0x456, 0x789, 0xABC]])).tolist() == [[0x23, 0x61, 0x45, 0x89, 0xC7, 0xAB]]
+    c8 = rng.integers(0, 4096, size=(2, 7, 8))
+    assert np.array_equal(unpack12(pack12(c8)), c8) and pack12(c8).shape == (2, 7, 12)
+    assert np.array_equal(pack12(c8)[..., :6], pack12(c8[..., :4])) and np.array_equal(pack12(c8)[..., 6:], pack12(c8[..., 4:]))
 
 
 @pytest.mark.parametrize("B,n", [(1, 700), (2, 70), (1, 257)])
 def test_encode12_matches_oracle(oracle, books, B, n):
     _, x, _ = make_qkv(82 + n, B, 2, 2, n, 1, 128, want_v=False)
-    geom = antkv.Geometry(B, 2, 2, D_SUB, n_centroids=C)
+    geom = antkv.Geometry(B, 2, 2, books.d, n_centroids=C)
     codes = antkv.encode(geom, dev(x), dev(books[0]))
     torch.cuda.synchronize()
-    assert codes.shape == (B, 2, n, 6)
+    assert codes.shape == (B, 2, n, books.nbytes)
     got = unpack12(codes.cpu().numpy())
     want, margin = oracle.encode(x, books[0], want_margin=True)
     soft = check_codes(got, want, margin)
@@ -46,8 +59,8 @@ def test_encode12_duplicate_centroids_and_offsets(oracle, books):
     cb[:, :, 4000:4096] = cb[:, :, 100:196]                   # 96 exact duplicates far apart
     cb[:, :, 33] = cb[:, :, 32]                                 # and one inside a tile
     _, x, _ = make_qkv(83, 1, 2, 2, 300, 1, 128, want_v=False)
-    geom = antkv.Geometry(1, 2, 2, D_SUB, n_centroids=C)
-    buf = torch.full((1, 2, 400, 6), 0xEE, dtype=torch.uint8, device="cuda")
+    geom = antkv.Geometry(1, 2, 2, books.d, n_centroids=C)
+    buf = torch.full((1, 2, 400, books.nbytes), 0xEE, dtype=torch.uint8, device="cuda")
     antkv.encode(geom, dev(x), dev(cb), codes=buf, token_offset=50)
     got_all = buf.cpu().numpy()
     assert (got_all[:, :, :50] == 0xEE).all() and (got_all[:, :, 350:] == 0xEE).all()
@@ -63,8 +76,8 @@ def _decode_case(oracle, books, seed, B, Hq, Hkv, N, k_k, k_v, N_cap=None, scale
     scale = scale or 1.0 / np.sqrt(128)
     N_cap = N_cap or N
     cbk, cbv = books[0][:Hkv], books[1][:Hkv]
-    ck = rng.integers(0, C, (B, Hkv, N_cap, 4)).astype(np.int32)
-    cv = rng.integers(0, C, (B, Hkv, N_cap, 4)).astype(np.int32)
+    ck = rng.integers(0, C, (B, Hkv, N_cap, books.M)).astype(np.int32)
+    cv = rng.integers(0, C, (B, Hkv, N_cap, books.M)).astype(np.int32)
     pick = lambda k: np.stack([[np.sort(rng.choice(N, k, replace=False)) for _ in range(Hkv)]
                                for _ in range(B)]).astype(np.int32).reshape(B, Hkv, k)
     ik, iv = pick(k_k), pick(k_v)
@@ -78,7 +91,7 @@ def _decode_case(oracle, books, seed, B, Hq, Hkv, N, k_k, k_v, N_cap=None, scale
     rk = normal_fp16(seed, "rows_k", (B, Hkv, k_k, 128))
     rv = normal_fp16(seed, "rows_v", (B, Hkv, k_v, 128))
     q = make_decode_query(seed, B, Hq, 128)
-    geom = antkv.Geometry(B, Hq, Hkv, D_SUB, n_centroids=C)
+    geom = antkv.Geometry(B, Hq, Hkv, books.d, n_centroids=C)
     out = antkv.decode_attn(geom, dev(q), scale, dev(pack12(ck)), dev(pack12(cv)), dev(cbk), dev(cbv),
                             dev(ik) if k_k else None, dev(rk) if k_k else None,
                             dev(iv) if k_v else None, dev(rv) if k_v else None, N=N)
@@ -108,7 +121,7 @@ def test_encode12_then_decode12(oracle, books):
     from workloads import make_decode_query
     B, Hq, Hkv, N = 1, 8, 2, 2000
     _, k, v = make_qkv(98, B, Hq, Hkv, N, 1, 128)
-    geom = antkv.Geometry(B, Hq, Hkv, D_SUB, n_centroids=C)
+    geom = antkv.Geometry(B, Hq, Hkv, books.d, n_centroids=C)
     cbk, cbv = dev(books[0]), dev(books[1])
     ck, cv = antkv.encode(geom, dev(k), cbk), antkv.encode(geom, dev(v), cbv)
     q = make_decode_query(98, B, Hq, 128)
@@ -122,12 +135,12 @@ def test_encode12_then_decode12(oracle, books):
     assert err.max() <= 2e-3
 
 
-def test_wide_geometry_rejections():
+def test_wide_geometry_rejections(books):
     import ctypes
     lib = antkv.load_library()
-    bad = antkv.Geometry(1, 4, 2, 16, n_centroids=C).c()         # 4096 centroids need d_sub 32
+    bad = antkv.Geometry(1, 4, 2, 8, n_centroids=C).c()          # 4096 centroids need d_sub 32 or 16
     assert lib.antkv_decode_attn_workspace(ctypes.byref(bad), 100, 0, 0, 0) == 0
-    ok = antkv.Geometry(1, 4, 2, D_SUB, n_centroids=C).c()
+    ok = antkv.Geometry(1, 4, 2, books.d, n_centroids=C).c()
     assert lib.antkv_decode_attn_workspace(ctypes.byref(ok), 100, 0, 0, 0) > 0
     assert lib.antkv_decode_attn_workspace(ctypes.byref(ok), 100, 0, 0, 5) > lib.antkv_decode_attn_workspace(
         ctypes.byref(ok), 100, 0, 0, 0)
@@ -145,8 +158,8 @@ def test_append12_then_decode12(oracle, books, W):
     _, k_all, v_all = make_qkv(99 + W, B, Hq, Hkv, N0 + T, 1, 128)
     cbk, cbv = books
     N_cap = N0 + T
-    codes_k = np.zeros((B, Hkv, N_cap, 4), np.int32)
-    codes_v = np.zeros((B, Hkv, N_cap, 4), np.int32)
+    codes_k = np.zeros((B, Hkv, N_cap, books.M), np.int32)
+    codes_v = np.zeros((B, Hkv, N_cap, books.M), np.int32)
     codes_k[:, :, :N0] = oracle.encode(k_all[:, :, :N0], cbk)
     codes_v[:, :, :N0] = oracle.encode(v_all[:, :, :N0], cbv)
     anchors = np.arange(3, 3 + 11 * k_a, 11)
@@ -154,7 +167,7 @@ def test_append12_then_decode12(oracle, books, W):
     idx_k, idx_v = idx.copy(), idx.copy()
     rows_k = np.take_along_axis(k_all, idx[..., None].astype(np.int64), axis=2).copy()
     rows_v = np.take_along_axis(v_all, idx[..., None].astype(np.int64), axis=2).copy()
-    geom = antkv.Geometry(B, Hq, Hkv, D_SUB, n_centroids=C)
+    geom = antkv.Geometry(B, Hq, Hkv, books.d, n_centroids=C)
     g = dict(ck=dev(pack12(codes_k)), cv=dev(pack12(codes_v)), cbk=dev(cbk), cbv=dev(cbv),
              ik=dev(idx_k), rk=dev(rows_k), iv=dev(idx_v), rv=dev(rows_v))
     N = N0
@@ -187,19 +200,19 @@ def test_append12_then_decode12(oracle, books, W):
 @pytest.mark.parametrize("B,Hq,Hkv,N,k_k,k_v", [(1, 8, 2, 2500, 25, 25), (2, 4, 2, 900, 0, 7), (1, 2, 2, 1300, 13, 0),
                                                 (1, 8, 2, 70000, 700, 700)])
 def test_decode12_anchor_score_and_reselection(oracle, books, B, Hq, Hkv, N, k_k, k_v):
-    """Decode-time Anchor Score over 12-bit codes (two heads per workgroup, the halves add up) + re-selection."""
+    """Decode-time Anchor Score over 12-bit codes (one walk per one or two heads, the shares add up) + re-selection."""
     from gpu_util import check_index_sets
     from workloads import make_decode_query, normal_fp16, random_anchor_sets
     rng = np.random.default_rng(N)
     scale = 1.0 / np.sqrt(128)
     cbk, cbv = books[0][:Hkv], books[1][:Hkv]
-    ck = rng.integers(0, C, (B, Hkv, N, 4)).astype(np.int32)
-    cv = rng.integers(0, C, (B, Hkv, N, 4)).astype(np.int32)
+    ck = rng.integers(0, C, (B, Hkv, N, books.M)).astype(np.int32)
+    cv = rng.integers(0, C, (B, Hkv, N, books.M)).astype(np.int32)
     ik, iv = random_anchor_sets(N, "k", B, Hkv, N, k_k), random_anchor_sets(N, "v", B, Hkv, N, k_v)
     rk, rv = normal_fp16(N, "rows_k", (B, Hkv, k_k, 128)), normal_fp16(N, "rows_v", (B, Hkv, k_v, 128))
     q = make_decode_query(N, B, Hq, 128)
     k_resel = max(1, N // 100)
-    geom = antkv.Geometry(B, Hq, Hkv, D_SUB, n_centroids=C)
+    geom = antkv.Geometry(B, Hq, Hkv, books.d, n_centroids=C)
     out, ans_k, ans_v, rsk, rsv = antkv.decode_attn(
         geom, dev(q), scale, dev(pack12(ck)), dev(pack12(cv)), dev(cbk), dev(cbv), dev(ik) if k_k else None,
         dev(rk) if k_k else None, dev(iv) if k_v else None, dev(rv) if k_v else None, k_resel=k_resel)

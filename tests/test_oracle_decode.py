@@ -64,7 +64,7 @@ def test_all_tokens_anchored_is_plain_attention(oracle):
     np.testing.assert_allclose(out, _sdpa(q, k, v, 0.3), rtol=1e-11, atol=1e-13)
 
 
-@pytest.mark.parametrize("d,C,D", [(4, 256, 32), (8, 256, 32), (16, 256, 32), (32, 4096, 128)])
+@pytest.mark.parametrize("d,C,D", [(4, 256, 32), (8, 256, 32), (16, 256, 32), (32, 4096, 128), (16, 4096, 128)])
 def test_mixed_codes_and_separate_anchor_sets(oracle, d, C, D):
     # K anchors and V anchors are different sets; everything else comes from the code tables
     B, Hq, Hkv, N = 2, 8, 2, 150

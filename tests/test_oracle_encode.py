@@ -26,7 +26,7 @@ def test_hand_worked_lattice(oracle):
     assert margin[0, 0, 1, 0] > 0.1
 
 
-@pytest.mark.parametrize("d,C", [(4, 256), (8, 256), (16, 256), (8, 7), (32, 4096)])
+@pytest.mark.parametrize("d,C", [(4, 256), (8, 256), (16, 256), (8, 7), (32, 4096), (16, 4096)])
 def test_matches_scipy_vq(oracle, d, C):
     B, Hkv, n, D = 2, 3, 37, 32
     M = D // d
