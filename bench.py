@@ -311,12 +311,11 @@ def main() -> int:
             fe = lambda i: antkv.encode(pg12, pkd12, w_cbk, codes=w_codes)
             settle(fe)
             ms_e12 = timed(20, fe)
-            heads_per_wg = 4 if wd == 32 else 2                     # a group of 4 heads takes 4 / heads_per_wg gathers of a token's V centroids
             result["extra"].update({
                 f"{tagw}_decode_ms": ms_w,
                 f"{tagw}_decode_plus_reselection_ms": ms_w2,
                 f"{tagw}_decode_tokens_per_s": r.B * r.N / (ms_w * 1e-3),
-                f"{tagw}_decode_L2_gather_GBs": r.B * r.Hkv * r.N * 256 * (min(r.Hq // r.Hkv, 4) + heads_per_wg - 1) // heads_per_wg / (ms_w * 1e-3) / 1e9,
+                f"{tagw}_decode_L2_gather_GBs": r.B * r.Hkv * r.N * 256 / (ms_w * 1e-3) / 1e9,
                 f"{tagw}_encode_ms": ms_e12,
                 f"{tagw}_encode_TFLOPs": 2.0 * p.B * p.Hkv * p.N * p.D * 4096 / (ms_e12 * 1e-3) / 1e12,
                 f"{tagw}_workload": f"12-bit codes (d_sub {wd}, 4096 centroids, {wb} bytes per token row): decode on cfg4's shape "

@@ -3,8 +3,10 @@
 // sub-spaces) or 12 bytes per token (d16, eight sub-spaces).
 //
 // With 4096 centroids only the q.centroid table of the K side fits LDS: 128 KB of int16 entries, which is 4 sub-spaces
-// x 4096 codes x 4 heads for d32 and 8 sub-spaces x 4096 codes x 2 heads for d16 -- there a query group of four heads
-// is split over two workgroups that walk the same tokens.  The V codebook (1 MB per KV head) stays in L2, which is
+// x 4096 codes x 4 heads for d32 and 8 sub-spaces x 4096 codes x 2 heads for d16.  There a workgroup with more than two
+// heads walks the K codes of its token range twice: first with the table of heads 0 and 1, leaving their scores in a
+// scratch array, then with the table of heads 2 and 3, now with the softmax and the value phase for all four heads
+// (a token is handled by the same thread both times).  The V codebook (1 MB per KV head) stays in L2, which is
 // why workgroup ids are mapped so that KV head g runs on XCD g mod 8 and each XCD's L2 keeps one head's codebook.
 //   prologue   table: a small kernel computes the fp32 scores once per (sequence, KV head); each workgroup takes the
 //              maximum per head and quantises them to 16-bit fixed point with one scale per head into LDS; bitmaps of the K- and V-anchored tokens of the workgroup's token range (the stream skips
@@ -35,7 +37,7 @@ constexpr float kEmptyRef12 = -1.0e4f;   // softmax reference before any token: 
 constexpr int kLutMax12 = 32767;
 constexpr int kTabThreads = 256;
 constexpr int tab_blocks(int ds) { return (kD / ds) * kC12 / (kTabThreads * 4); }   // per (sequence, KV head), 4 entries per thread
-constexpr int heads_per_wg(int ds) { return ds == 32 ? 4 : 2; }                     // heads whose int16 table fits 128 KB
+constexpr int heads_per_table(int ds) { return ds == 32 ? 4 : 2; }                  // heads whose int16 table fits 128 KB
 constexpr float kPShift12 = 12.f;        // weights are kept scaled by 2^12 so that small ones stay normal in fp16
 
 struct D12Params {
@@ -51,7 +53,7 @@ struct D12Params {
     int k_k, k_v;
     float c1;
     int Hq, Hkv, G, S, chunk;
-    int HH;                               // workgroups that share a (sequence, KV head, token range): ceil(G / heads per workgroup)
+    float2* early;                        // [B][Hkv][N] scores of heads 0 and 1 from the first walk (d16 with G > 2), else unused
 };
 
 __device__ __forceinline__ float dot8f(const half8_t& a, const half8_t& b, float acc)
@@ -161,27 +163,27 @@ __global__ __launch_bounds__(kTabThreads) void d12_table_kernel(const half_t* __
 // LDS bytes of decode12_kernel<DS>
 constexpr size_t d12_lds(int ds)
 {
-    return (size_t)128 * 1024 + 2 * 1024 * 4 + (size_t)heads_per_wg(ds) * kD * 2 + 64 * 4 + 16 * 4 +
-           (size_t)kW12 * 64 * heads_per_wg(ds) * 2 + (size_t)kW12 * (kD / ds) * 64 * 2;
+    return (size_t)128 * 1024 + 1024 * 4 + (size_t)kNH * kD * 2 + 64 * 4 + 16 * 4 + (size_t)kW12 * 64 * kNH * 2 +
+           (size_t)kW12 * (kD / ds) * 64 * 2;
 }
 static_assert(d12_lds(32) <= 160 * 1024 && d12_lds(16) <= 160 * 1024, "LDS budget");
 
-// kD12 = sub-vector width: 32 (four sub-spaces, all four heads of a group in one workgroup) or 16 (eight sub-spaces,
-// two heads per workgroup)
+// kD12 = sub-vector width: 32 (four sub-spaces, one table for the four heads of a group) or 16 (eight sub-spaces, a
+// table holds two heads)
 template <int kD12>
 __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
 {
     constexpr int kM12 = kD / kD12;                                    // sub-spaces
-    constexpr int NHW = heads_per_wg(kD12);                            // heads of this workgroup
+    constexpr int NHW = kNH;                                           // head slots of the workgroup
+    constexpr int NHT = heads_per_table(kD12);                         // heads per table
     constexpr int LPM = kD12 / 8;                                      // value-phase lanes per sub-space
     constexpr int kTabBlocks = tab_blocks(kD12);
-    using lut_t = typename std::conditional<NHW == 4, uint2_t, uint32_t>::type;   // NHW x int16
+    using lut_t = typename std::conditional<NHT == 4, uint2_t, uint32_t>::type;   // NHT x int16
     extern __shared__ uint4_t smem_u4[];
     char* smem = (char*)smem_u4;
-    lut_t* s_lut = (lut_t*)smem;                                       // [M][4096] entries of NHW x int16 (128 KB)
-    uint32_t* s_mk = (uint32_t*)(smem + 128 * 1024);                   // K-anchored tokens of the range, 1024 words
-    uint32_t* s_mv = s_mk + 1024;                                      // V-anchored tokens
-    half_t* s_q = (half_t*)(s_mv + 1024);                              // [NHW][128]
+    lut_t* s_lut = (lut_t*)smem;                                       // [M][4096] entries of NHT x int16 (128 KB)
+    uint32_t* s_mk = (uint32_t*)(smem + 128 * 1024);                   // K- or V-anchored tokens of the range, 1024 words
+    half_t* s_q = (half_t*)(s_mk + 1024);                              // [NHW][128]
     float* s_red = (float*)(s_q + NHW * kD);                           // 64 floats of scratch
     int* s_misc = (int*)(s_red + 64);                                  // 16 ints
     // this wave's tile: for each pair of tokens (2j, 2j+1) the heads' weights as NHW half2 {P_h(2j), P_h(2j+1)}
@@ -190,13 +192,11 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // KV head g on XCD g mod 8: workgroup ids go to the XCDs round-robin
     const int g = blockIdx.x % p.Hkv;
-    int rest = blockIdx.x / p.Hkv;
-    const int hh = rest % p.HH;                                        // which NHW heads of the group
-    rest /= p.HH;
+    const int rest = blockIdx.x / p.Hkv;
     const int b = rest / p.S, sp = rest % p.S;
     const int bg = b * p.Hkv + g;
-    const int h0 = g * p.G + NHW * hh;
-    const int nh = (p.G - NHW * hh) < NHW ? (p.G - NHW * hh) : NHW;    // heads present
+    const int h0 = g * p.G;
+    const int nh = p.G;                                                // heads present (<= NHW)
     const int64_t t0 = (int64_t)sp * p.chunk;
     const int64_t t1 = (t0 + p.chunk < p.N) ? t0 + p.chunk : p.N;
     const int32_t* idx_k = p.idx_k + (int64_t)bg * p.k_k;
@@ -204,7 +204,7 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
 
     // ---- prologue ----------------------------------------------------------------------------------------------
     if (tid < NHW * kD) s_q[tid] = ((tid >> 7) < nh) ? p.q[((int64_t)b * p.Hq + h0) * kD + tid] : (half_t)0.f;
-    for (int i = tid; i < 2 * 1024; i += kT12) s_mk[i] = 0u;
+    s_mk[tid] = 0u;
     if (wave < 4) {                                                    // list ranges that fall into [t0, t1)
         const int32_t* l = (wave < 2) ? idx_k : idx_v;
         const int n = (wave < 2) ? p.k_k : p.k_v;
@@ -219,24 +219,29 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     }
     for (int i = lo_v + tid; i < hi_v; i += kT12) {
         const int rel = idx_v[i] - (int)t0;
-        atomicOr(&s_mv[rel >> 5], 1u << (rel & 31));
+        atomicOr(&s_mk[rel >> 5], 1u << (rel & 31));
     }
+    constexpr int CB = 3 * kM12 / 2;                                   // code bytes per token
+    const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * CB;
+    const uint8_t* cv = p.codes_v + (int64_t)bg * p.N_cap * CB;
+    const int64_t n_tiles = (t1 - t0 + 63) >> 6;
     // table: the fp32 scores come from d12_table_kernel; one scale per head from the per-block maxima, then 16-bit
-    // fixed point into LDS.  Thread t owns entries t + 1024 i.
-    float amax[NHW], inv_q[NHW];
+    // fixed point into LDS.  Thread t owns entries t + 1024 i.  `walk` selects the NHT heads the table holds.
+    float lut_q[NHT];                                                  // table quantum per head (log2 units)
+    auto load_table = [&](int walk) {
+        float inv_q[NHT];
 #pragma unroll
-    for (int h = 0; h < NHW; ++h) {
-        float a = 0.f;
-        for (int k = 0; k < kTabBlocks; ++k) a = fmaxf(a, p.tab_amax[((int64_t)bg * kTabBlocks + k) * kNH + NHW * hh + h]);
-        amax[h] = a;
-        inv_q[h] = a > 0.f ? (float)kLutMax12 / a : 0.f;
-    }
-    {
+        for (int h = 0; h < NHT; ++h) {
+            float a = 0.f;
+            for (int k = 0; k < kTabBlocks; ++k) a = fmaxf(a, p.tab_amax[((int64_t)bg * kTabBlocks + k) * kNH + NHT * walk + h]);
+            inv_q[h] = a > 0.f ? (float)kLutMax12 / a : 0.f;
+            lut_q[h] = a * (1.0f / (float)kLutMax12);
+        }
         const float4_t* tb = p.tab + (int64_t)bg * kM12 * kC12;
 #pragma unroll 4
         for (int e = tid; e < kM12 * kC12; e += kT12) {
             const float4_t sc = tb[e];
-            if constexpr (NHW == 4) {
+            if constexpr (NHT == 4) {
                 int q16[4];
 #pragma unroll
                 for (int h = 0; h < 4; ++h) q16[h] = (int)rintf(sc[h] * inv_q[h]);
@@ -245,20 +250,54 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
                 w[1] = ((uint32_t)q16[2] & 0xFFFFu) | ((uint32_t)q16[3] << 16);
                 s_lut[e] = w;
             } else {
-                const int qa = (int)rintf((hh ? sc[2] : sc[0]) * inv_q[0]), qb = (int)rintf((hh ? sc[3] : sc[1]) * inv_q[1]);
+                const int qa = (int)rintf((walk ? sc[2] : sc[0]) * inv_q[0]), qb = (int)rintf((walk ? sc[3] : sc[1]) * inv_q[1]);
                 s_lut[e] = ((uint32_t)qa & 0xFFFFu) | ((uint32_t)qb << 16);
             }
         }
-    }
-    float lut_q[NHW];                                                  // table quantum per head (log2 units)
+    };
+    // scores of the table's heads for one token
+    auto table_scores = [&](const uint32_t (&kw)[3], float (&s)[NHT]) {
+        int sum[NHT];
 #pragma unroll
-    for (int h = 0; h < NHW; ++h) lut_q[h] = amax[h] * (1.0f / (float)kLutMax12);
-    __syncthreads();                                                   // table and bitmaps are complete
+        for (int h = 0; h < NHT; ++h) sum[h] = 0;
+#pragma unroll
+        for (int m = 0; m < kM12; ++m) {
+            const lut_t e = s_lut[m * kC12 + code12(kw, m)];
+            if constexpr (NHT == 4) {
+                sum[0] += (int)(short)(e[0] & 0xFFFFu);
+                sum[1] += (int)e[0] >> 16;
+                sum[2] += (int)(short)(e[1] & 0xFFFFu);
+                sum[3] += (int)e[1] >> 16;
+            } else {
+                sum[0] += (int)(short)(e & 0xFFFFu);
+                sum[1] += (int)e >> 16;
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < NHT; ++h) s[h] = (float)sum[h] * lut_q[h];
+    };
+    const int n_walks = (nh + NHT - 1) / NHT;                          // 1, or 2 for d16 with more than two heads
+    float2* early = p.early + (int64_t)bg * p.N;
+    load_table(0);
+    __syncthreads();                                                   // table and bitmap are complete
+    if (NHT < NHW && n_walks > 1) {
+        // first walk: heads 0 and 1 of every token of the range; tiles go to the waves as in the stream below
+        for (int64_t tile = wave; tile < n_tiles; tile += kW12) {
+            const int64_t tok = t0 + tile * 64 + lane;
+            const int64_t ltok = tok < t1 ? tok : t1 - 1;
+            uint32_t kw[3];
+            load_cw<kD12>(ck, ltok, kw);
+            float s[NHT];
+            table_scores(kw, s);
+            if (tok < t1) early[tok] = float2{s[0], s[NHT - 1]};
+        }
+        __syncthreads();                                               // nobody reads the first table any more
+        load_table(1);
+        __syncthreads();
+    }
+    const int hb = NHT * (n_walks - 1);                                // head slot of the table's first head
 
     // ---- per-wave state and the helpers shared by the stream and the anchor tiles
-    constexpr int CB = 3 * kM12 / 2;                                   // code bytes per token
-    const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * CB;
-    const uint8_t* cv = p.codes_v + (int64_t)bg * p.N_cap * CB;
     const half_t* cbv = p.cb_v + (int64_t)g * kM12 * kC12 * kD12;
     // Value phase roles: a group of 16 lanes (grp) takes the tokens t with t mod 4 == grp of a tile, four tokens per
     // gather instruction; lane li of the group owns output channels 8 li .. 8 li + 7, i.e. 16 bytes of the centroid of
@@ -276,25 +315,28 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         for (int c = 0; c < 8; ++c) acc[h][c] = 0.f;
     }
 
-    auto lut_scores = [&](const uint32_t (&kw)[3], float (&s)[NHW]) {
-        int sum[NHW];
+    const half_t* cbk = p.cb_k + (int64_t)g * kM12 * kC12 * kD12;
+    // scores of all head slots for a token from its codes, outside the stream: the table where it holds every head,
+    // else q . centroid summed over the sub-spaces in fp32
+    auto code_scores = [&](const uint32_t (&kw)[3], float (&s)[NHW]) {
+        if constexpr (NHT == NHW) {
+            table_scores(kw, s);
+        } else {
 #pragma unroll
-        for (int h = 0; h < NHW; ++h) sum[h] = 0;
+            for (int h = 0; h < NHW; ++h) s[h] = 0.f;
 #pragma unroll
-        for (int m = 0; m < kM12; ++m) {
-            const lut_t e = s_lut[m * kC12 + code12(kw, m)];
-            if constexpr (NHW == 4) {
-                sum[0] += (int)(short)(e[0] & 0xFFFFu);
-                sum[1] += (int)e[0] >> 16;
-                sum[2] += (int)(short)(e[1] & 0xFFFFu);
-                sum[3] += (int)e[1] >> 16;
-            } else {
-                sum[0] += (int)(short)(e & 0xFFFFu);
-                sum[1] += (int)e >> 16;
+            for (int m = 0; m < kM12; ++m) {
+                const half_t* cp = cbk + ((int64_t)m * kC12 + code12(kw, m)) * kD12;
+#pragma unroll
+                for (int u = 0; u < kD12 / 8; ++u) {
+                    const half8_t cvec = *(const half8_t*)(cp + 8 * u);
+#pragma unroll
+                    for (int h = 0; h < NHW; ++h) s[h] = dot8f(cvec, *(const half8_t*)(s_q + h * kD + m * kD12 + 8 * u), s[h]);
+                }
             }
-        }
 #pragma unroll
-        for (int h = 0; h < NHW; ++h) s[h] = (float)sum[h] * lut_q[h];
+            for (int h = 0; h < NHW; ++h) s[h] *= p.c1;
+        }
     };
     // move the wave's reference of head h to at least `cand` (uniform); returns nothing, rescales the running state
     auto raise_ref = [&](int h, float cand) {
@@ -363,7 +405,6 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     };
 
     // ---- stream ------------------------------------------------------------------------------------------------
-    const int64_t n_tiles = (t1 - t0 + 63) >> 6;
     for (int64_t tile = wave; tile < n_tiles; tile += kW12) {
         const int64_t tok = t0 + tile * 64 + lane;
         const int64_t ltok = tok < t1 ? tok : t1 - 1;
@@ -371,10 +412,21 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         load_cw<kD12>(ck, ltok, kw);
         load_cw<kD12>(cv, ltok, vw);
         const int rel = (int)(ltok - t0);
-        const uint32_t mbit = ((s_mk[rel >> 5] | s_mv[rel >> 5]) >> (rel & 31)) & 1u;
+        const uint32_t mbit = (s_mk[rel >> 5] >> (rel & 31)) & 1u;
         const bool masked = tok >= t1 || mbit != 0u;
         float s[NHW];
-        lut_scores(kw, s);
+        if constexpr (NHT == NHW) {
+            table_scores(kw, s);
+        } else {
+            float st[NHT];
+            table_scores(kw, st);
+            float2 e01 = float2{0.f, 0.f};
+            if (hb) e01 = early[ltok];                                  // written by this thread in the first walk
+            s[0] = hb ? e01.x : st[0];
+            s[1] = hb ? e01.y : st[1];
+            s[2] = hb ? st[0] : 0.f;
+            s[3] = hb ? st[1] : 0.f;
+        }
         tile_weights(s, masked);
 #pragma unroll
         for (int m = 0; m < kM12; ++m) s_vc[m * 64 + (lane & 3) * 16 + (lane >> 2)] = (uint16_t)code12(vw, m);
@@ -439,7 +491,7 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
         } else {
             uint32_t kw[3];
             load_cw<kD12>(ck, tok, kw);
-            lut_scores(kw, s);
+            code_scores(kw, s);
         }
         uint32_t voff[kM12];                                           // byte offset of the token's kD12 channels per sub-space
         if (in_v) {
@@ -720,7 +772,7 @@ __global__ __launch_bounds__(kT12) void d12_ans_kernel(const D12AnsParams p)
 
 struct D12Plan {
     int S, chunk;
-    size_t off_part, off_tab, off_amax, off_stat, total;
+    size_t off_part, off_tab, off_amax, off_stat, off_early, total;
 };
 
 D12Plan d12_plan(const Geom& g, int64_t N)
@@ -743,6 +795,8 @@ D12Plan d12_plan(const Geom& g, int64_t N)
     pl.off_tab = off;  off += align_up((size_t)g.B * g.Hkv * g.M * kC12 * sizeof(float4_t));
     pl.off_amax = off; off += align_up((size_t)g.B * g.Hkv * tab_blocks(g.d) * kNH * sizeof(float));
     pl.off_stat = off; off += align_up((size_t)g.B * g.Hq * S * 2 * sizeof(float));
+    pl.off_early = off;                                                // first-walk scores: only where a table holds fewer heads than the group has
+    if (g.G > heads_per_table(g.d)) off += align_up((size_t)g.B * g.Hkv * N * sizeof(float2));
     pl.total = off;
     return pl;
 }
@@ -756,8 +810,7 @@ hipError_t launch_decode12_t(const Geom& g, const DecodeArgs& a, void* ws, hipSt
         return hipFuncSetAttribute((const void*)decode12_kernel<DS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     }();
     if (setup != hipSuccess) return setup;
-    const int HH = (g.G + heads_per_wg(DS) - 1) / heads_per_wg(DS);
-    if ((int64_t)g.B * g.Hkv * pl.S * HH > 0x7fffffffLL) return hipErrorInvalidValue;
+    if ((int64_t)g.B * g.Hkv * pl.S > 0x7fffffffLL) return hipErrorInvalidValue;
     if ((int64_t)g.B * g.Hkv * a.k_v * kD * 2 >= 0x7fffffffLL) return hipErrorInvalidValue;   // 31-bit byte offsets into rows_v
     D12Params p;
     p.q = a.q; p.codes_k = a.codes_k; p.codes_v = a.codes_v; p.cb_k = a.cb_k; p.cb_v = a.cb_v;
@@ -766,11 +819,11 @@ hipError_t launch_decode12_t(const Geom& g, const DecodeArgs& a, void* ws, hipSt
     p.part = (float*)(w + pl.off_part); p.tab = (const float4_t*)(w + pl.off_tab); p.tab_amax = (const float*)(w + pl.off_amax);
     p.N = a.N; p.N_cap = a.N_cap; p.k_k = (int)a.k_k; p.k_v = (int)a.k_v;
     p.c1 = a.scale * kLog2e; p.Hq = g.Hq; p.Hkv = g.Hkv; p.G = g.G; p.S = a.N > 0 ? pl.S : 0; p.chunk = pl.chunk;
-    p.HH = HH;
+    p.early = (float2*)(w + pl.off_early);
     if (a.N > 0) {
         hipLaunchKernelGGL(d12_table_kernel<DS>, dim3((unsigned)(g.B * g.Hkv), tab_blocks(DS)), dim3(kTabThreads), 0, st, a.q,
                            a.cb_k, p.c1, g.Hq, g.Hkv, g.G, (float4_t*)(w + pl.off_tab), (float*)(w + pl.off_amax));
-        hipLaunchKernelGGL(decode12_kernel<DS>, dim3((unsigned)(g.B * g.Hkv * HH * pl.S)), dim3(kT12), lds, st, p);
+        hipLaunchKernelGGL(decode12_kernel<DS>, dim3((unsigned)(g.B * g.Hkv * pl.S)), dim3(kT12), lds, st, p);
     }
     hipLaunchKernelGGL(decode12_merge, dim3((unsigned)(g.B * g.Hq)), dim3(kD), 0, st, (const float*)p.part, p.S, a.out);
     if (a.ans_k && a.N > 0) {
