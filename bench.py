@@ -311,6 +311,11 @@ def main() -> int:
             fe = lambda i: antkv.encode(pg12, pkd12, w_cbk, codes=w_codes)
             settle(fe)
             ms_e12 = timed(20, fe)
+            km_w12 = torch.rand((p.B, p.Hkv, p.N), dtype=torch.float32, device=devc)
+            km12 = lambda i: antkv.kmeans_step(pg12, pkd12, km_w12, w_cbk)
+            settle(km12, 0.1)
+            ms_km12 = timed(20, km12)
+            del km_w12
             result["extra"].update({
                 f"{tagw}_decode_ms": ms_w,
                 f"{tagw}_decode_plus_reselection_ms": ms_w2,
@@ -318,11 +323,13 @@ def main() -> int:
                 f"{tagw}_decode_L2_gather_GBs": r.B * r.Hkv * r.N * 256 / (ms_w * 1e-3) / 1e9,
                 f"{tagw}_encode_ms": ms_e12,
                 f"{tagw}_encode_TFLOPs": 2.0 * p.B * p.Hkv * p.N * p.D * 4096 / (ms_e12 * 1e-3) / 1e12,
+                f"{tagw}_kmeans_step_ms": ms_km12,
                 f"{tagw}_workload": f"12-bit codes (d_sub {wd}, 4096 centroids, {wb} bytes per token row): decode on cfg4's shape "
                                     f"(B1, N={r.N}, {r.k} anchors per head, random codebooks and codes); encode of cfg3's K rows "
                                     f"({p.B * p.Hkv * p.N} rows)",
             })
-            log(f"{tagw}: decode {ms_w * 1e3:.0f} us, with re-selection {ms_w2 * 1e3:.0f} us, encode of {p.B * p.Hkv * p.N} rows {ms_e12:.2f} ms")
+            log(f"{tagw}: decode {ms_w * 1e3:.0f} us, with re-selection {ms_w2 * 1e3:.0f} us, encode of {p.B * p.Hkv * p.N} rows "
+                f"{ms_e12:.2f} ms, k-means iteration on them {ms_km12:.2f} ms")
             del w_codes, w_cbk, w_cbv, w_ws
             torch.cuda.empty_cache()
         del pkd12

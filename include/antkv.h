@@ -27,8 +27,7 @@
  *       n_centroids 256, d_sub in {4, 8, 16}: one byte per code (2 / 1 / 0.5 bit per element, the paper's
  *         d4m256 / d8m256 notation, Sec. 4); every entry point supports it.
  *       n_centroids 4096, d_sub 32 or 16: 12-bit codes (0.375 / 0.75 bit per element, the d32m4096 and d16m4096
- *         points of Sec. 4).  Supported by antkv_encode, antkv_append_token and antkv_decode_attn (scores and
- *         re-selection included); antkv_kmeans_step returns EUNSUPPORTED.
+ *         points of Sec. 4); every entry point that touches codes supports it.
  *   - Codebooks: fp16 [Hkv][M][n_centroids][d_sub], separate for K and V; sub-space m covers
  *     channels [m*d_sub, (m+1)*d_sub).
  *   - Codes: uint8 [B][Hkv][N_cap][code_bytes], token-major.  code_bytes = M for one-byte codes.  For 12-bit
@@ -194,7 +193,7 @@ int antkv_prefill_attn(const antkv_geom* geom, const void* q, const void* k, con
                        float scale, void* out, float* row_max, float* row_sum, void* stream);
 
 /*
- * One iteration of the offline token-weighted k-means that learns a codebook of 256 centroids (Sec. 3.1, "Offline Token-Aware
+ * One iteration of the offline token-weighted k-means that learns a codebook (Sec. 3.1, "Offline Token-Aware
  * Centroids Learning"): every sub-vector of x is assigned to its nearest centroid of codebook_in (the same rule as
  * antkv_encode), then each centroid becomes the weighted mean of the sub-vectors assigned to it, over all B
  * sequences, with one weight per token (the paper uses the token's error-propagation factor; any w >= 0 works).
@@ -202,9 +201,9 @@ int antkv_prefill_attn(const antkv_geom* geom, const void* q, const void* k, con
  *
  *   x            fp16 [B][Hkv][n_tok][D] calibration rows of K (or V), contiguous, 16-byte aligned
  *   w            fp32 [B][Hkv][n_tok], >= 0
- *   codebook_in  fp16 [Hkv][M][256][d_sub];  codebook_out the same shape, a different buffer
- *   codes        uint8 [B][Hkv][n_tok][M], written: the assignment that was used
- *   wsum         optional fp32 [Hkv][M][256]: weight assigned to each centroid
+ *   codebook_in  fp16 [Hkv][M][n_centroids][d_sub];  codebook_out the same shape, a different buffer
+ *   codes        uint8 [B][Hkv][n_tok][code_bytes], written: the assignment that was used
+ *   wsum         optional fp32 [Hkv][M][n_centroids]: weight assigned to each centroid
  *   objective    optional fp64 [Hkv][M]: sum_j w_j ||x_j - codebook_in[code_j]||^2 per sub-space, i.e. the weighted
  *                distortion after the assignment and before the update
  *   workspace    antkv_kmeans_step_workspace(geom) bytes, 256-byte aligned; may hold any bytes on entry

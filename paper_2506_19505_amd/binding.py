@@ -164,16 +164,16 @@ def topk(scores: torch.Tensor, k: int) -> torch.Tensor:
 
 
 def kmeans_step(geom: Geometry, x: torch.Tensor, w: torch.Tensor, codebook: torch.Tensor):
-    """antkv_kmeans_step: x fp16 [B,Hkv,n,D], w fp32 [B,Hkv,n], codebook fp16 [Hkv,M,256,d] ->
-    (new codebook fp16, codes uint8 [B,Hkv,n,M], wsum fp32 [Hkv,M,256], objective fp64 [Hkv,M])."""
+    """antkv_kmeans_step: x fp16 [B,Hkv,n,D], w fp32 [B,Hkv,n], codebook fp16 [Hkv,M,C,d] ->
+    (new codebook fp16, codes uint8 [B,Hkv,n,code_bytes], wsum fp32 [Hkv,M,C], objective fp64 [Hkv,M])."""
     _need(x, torch.float16, "x")
     _need(w, torch.float32, "w")
     _need(codebook, torch.float16, "codebook")
     B, Hkv, n, _ = x.shape
     dev = x.device
     out = torch.empty_like(codebook)
-    codes = torch.empty((B, Hkv, n, geom.M), dtype=torch.uint8, device=dev)
-    wsum = torch.empty((Hkv, geom.M, 256), dtype=torch.float32, device=dev)
+    codes = torch.empty((B, Hkv, n, geom.code_bytes), dtype=torch.uint8, device=dev)
+    wsum = torch.empty((Hkv, geom.M, geom.n_centroids), dtype=torch.float32, device=dev)
     objective = torch.empty((Hkv, geom.M), dtype=torch.float64, device=dev)
     lib = load_library()
     g = geom.c()

@@ -117,7 +117,7 @@ size_t antkv_anchor_select_workspace(const antkv_geom* geom, int64_t N, int64_t 
 size_t antkv_kmeans_step_workspace(const antkv_geom* geom)
 {
     Geom g;
-    if (check_geom(geom, g) || g.C != kC) return 0;
+    if (check_geom(geom, g)) return 0;
     return kmeans_workspace_bytes(g);
 }
 
@@ -128,7 +128,6 @@ int antkv_kmeans_step(const antkv_geom* geom, const void* x, const float* w, int
     Geom g;
     int rc = check_geom(geom, g);
     if (rc) return rc;
-    if (g.C != kC) return ANTKV_EUNSUPPORTED;                    // one-byte codes only
     if (n_tok < 0 || n_tok > 0x7fffffffLL) return ANTKV_EINVAL;
     if (!codebook_in || !codebook_out || codebook_in == codebook_out) return ANTKV_EINVAL;
     if (misaligned(codebook_in, 16) || misaligned(codebook_out, 16) || misaligned(objective, 8)) return ANTKV_EINVAL;
@@ -138,8 +137,11 @@ int antkv_kmeans_step(const antkv_geom* geom, const void* x, const float* w, int
     if (!workspace || misaligned(workspace, 256) || workspace_bytes < kmeans_workspace_bytes(g)) return ANTKV_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     if (have_tokens) {
-        const hipError_t e = launch_encode(g, (const half_t*)x, (int64_t)g.Hkv * n_tok * kD, n_tok * kD, kD, n_tok,
-                                           (const half_t*)codebook_in, codes, n_tok, 0, st);
+        const hipError_t e =
+            g.C == kC ? launch_encode(g, (const half_t*)x, (int64_t)g.Hkv * n_tok * kD, n_tok * kD, kD, n_tok,
+                                      (const half_t*)codebook_in, codes, n_tok, 0, st)
+                      : launch_encode12(g, (const half_t*)x, (int64_t)g.Hkv * n_tok * kD, n_tok * kD, kD, n_tok,
+                                        (const half_t*)codebook_in, codes, n_tok, 0, st);
         if (e != hipSuccess) return ANTKV_ELAUNCH;
     }
     const hipError_t e = launch_kmeans_update(g, (const half_t*)x, w, have_tokens ? n_tok : 0, (const half_t*)codebook_in,

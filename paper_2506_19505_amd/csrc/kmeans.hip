@@ -8,6 +8,8 @@
 // accumulators in LDS (ds_add_f32; laid out [sub-space][channel][centroid] so that the lanes of one instruction
 // spread over the banks by their codes), and flushes the non-zero accumulators to the global sums with hardware float atomics.  Sums are
 // therefore fp32 and their order is not fixed: results agree to fp32 rounding, not bit for bit, from run to run.
+// With 4096 centroids (12-bit codes) the sums of one KV head are 2 MB, far beyond LDS, and 4096 targets per sub-space
+// rarely collide, so every thread adds its eight channels straight into the global sums (km_accumulate12).
 #include "common.h"
 
 namespace antkv {
@@ -94,6 +96,56 @@ __global__ __launch_bounds__(kKmThreads) void km_accumulate(
     }
 }
 
+// 4096 centroids, codes packed 12 bits each (code m at bits 12 m .. 12 m + 11 of the token's row).  A thread owns one
+// 16-byte chunk (8 channels) of a token row: tid % 16 = chunk, 16 tokens per pass of the workgroup.
+template <int DSUB>
+__global__ __launch_bounds__(kKmThreads) void km_accumulate12(
+    const half_t* __restrict__ x, const float* __restrict__ w, const uint8_t* __restrict__ codes,
+    const half_t* __restrict__ cb, int64_t n_tok, int Hkv, float* __restrict__ sums, float* __restrict__ wsum,
+    double* __restrict__ objective)
+{
+    constexpr int M = kD / DSUB, LPM = DSUB / 8, CB = 3 * M / 2, NC = 4096;
+    const int tid = threadIdx.x;
+    const int64_t bg = blockIdx.y;
+    const int g = (int)(bg % Hkv);
+    const int u = tid & 15;                                      // chunk of the row: channels 8 u .. 8 u + 7
+    const int m = u / LPM, part = u % LPM;                       // sub-space and the chunk's place inside it
+    const int64_t t0 = (int64_t)blockIdx.x * kKmChunk;
+    const int64_t t1 = (t0 + kKmChunk < n_tok) ? t0 + kKmChunk : n_tok;
+    const half_t* cbm = cb + ((int64_t)g * M + m) * NC * DSUB;
+    float* sm = sums + ((int64_t)g * M + m) * NC * DSUB;
+    float* wm = wsum + ((int64_t)g * M + m) * NC;
+    double obj = 0.0;
+    for (int64_t t = t0 + (tid >> 4); t < t1; t += kKmThreads / 16) {
+        const int64_t row = bg * n_tok + t;
+        const float wt = w[row];
+        // the 12 bits of code m start at bit 12 m of the row: two bytes hold them
+        const uint8_t* cr = codes + row * CB + (12 * m >> 3);
+        const uint32_t two = (uint32_t)cr[0] | ((uint32_t)cr[1] << 8);
+        const int c = (int)((two >> ((12 * m) & 7)) & 0xFFFu);
+        const half8_t a = *(const half8_t*)(x + row * kD + 8 * u);
+        const half8_t b = *(const half8_t*)(cbm + (int64_t)c * DSUB + 8 * part);
+        float dist = 0.f;
+        float* acc = sm + (int64_t)c * DSUB + 8 * part;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float xv = (float)a[e];
+            const float df = xv - (float)b[e];
+            dist = fmaf(df, df, dist);
+            const float v = wt * xv;
+            if (v != 0.f) unsafeAtomicAdd(acc + e, v);
+        }
+        if (part == 0 && wt != 0.f) unsafeAtomicAdd(wm + c, wt);
+        obj += (double)wt * (double)dist;
+    }
+    // objective of sub-space m: the LPM chunk lanes and the four token slots of a wave (lanes u, u+16, u+32, u+48)
+#pragma unroll
+    for (int off = 1; off < LPM; off <<= 1) obj += __shfl_xor(obj, off, 64);
+    obj += __shfl_xor(obj, 16, 64);
+    obj += __shfl_xor(obj, 32, 64);
+    if ((tid & 63) < 16 && part == 0 && objective) unsafeAtomicAdd(objective + (int64_t)g * M + m, obj);
+}
+
 // weighted means; a centroid without assigned weight keeps its old value
 template <int DSUB>
 __global__ __launch_bounds__(256) void km_finalize(const float* __restrict__ sums, const float* __restrict__ wsum,
@@ -117,14 +169,14 @@ KmPlan km_plan(const Geom& g)
 {
     KmPlan p;
     size_t off = 0;
-    p.off_sums = off; off += align_up((size_t)g.Hkv * kD * kC * sizeof(float));       // M * d_sub = D
-    p.off_wsum = off; off += align_up((size_t)g.Hkv * g.M * kC * sizeof(float));
+    p.off_sums = off; off += align_up((size_t)g.Hkv * kD * g.C * sizeof(float));      // M * d_sub = D
+    p.off_wsum = off; off += align_up((size_t)g.Hkv * g.M * g.C * sizeof(float));
     p.off_obj = off;  off += align_up((size_t)g.Hkv * g.M * sizeof(double));
     p.total = off;
     return p;
 }
 
-template <int DSUB>
+template <int DSUB, bool WIDE>
 hipError_t launch_t(const Geom& g, const half_t* x, const float* w, int64_t n_tok, const half_t* cb_in, half_t* cb_out,
                     const uint8_t* codes, float* wsum_out, double* objective, char* ws, hipStream_t st)
 {
@@ -138,11 +190,17 @@ hipError_t launch_t(const Geom& g, const half_t* x, const float* w, int64_t n_to
         hipLaunchKernelGGL(km_zero, dim3((unsigned)((g.Hkv * g.M * 2 + 255) / 256)), dim3(256), 0, st, (uint32_t*)objective,
                            (int64_t)g.Hkv * g.M * 2);
     if (n_tok > 0) {
-        dim3 grid((unsigned)((n_tok + kKmChunk - 1) / kKmChunk), (unsigned)(g.B * g.Hkv), kKmGroups);
-        hipLaunchKernelGGL(km_accumulate<DSUB>, grid, dim3(kKmThreads), 0, st, x, w, codes, cb_in, n_tok, g.Hkv, sums,
-                           wsum, obj);
+        if constexpr (WIDE) {
+            dim3 grid((unsigned)((n_tok + kKmChunk - 1) / kKmChunk), (unsigned)(g.B * g.Hkv));
+            hipLaunchKernelGGL(km_accumulate12<DSUB>, grid, dim3(kKmThreads), 0, st, x, w, codes, cb_in, n_tok, g.Hkv, sums,
+                               wsum, obj);
+        } else {
+            dim3 grid((unsigned)((n_tok + kKmChunk - 1) / kKmChunk), (unsigned)(g.B * g.Hkv), kKmGroups);
+            hipLaunchKernelGGL(km_accumulate<DSUB>, grid, dim3(kKmThreads), 0, st, x, w, codes, cb_in, n_tok, g.Hkv, sums,
+                               wsum, obj);
+        }
     }
-    const int64_t n_cen = (int64_t)g.Hkv * g.M * kC;
+    const int64_t n_cen = (int64_t)g.Hkv * g.M * g.C;
     hipLaunchKernelGGL(km_finalize<DSUB>, dim3((unsigned)((n_cen + 255) / 256)), dim3(256), 0, st, sums, wsum, cb_in,
                        cb_out, wsum_out, n_cen);
     return hipGetLastError();
@@ -152,15 +210,19 @@ hipError_t launch_t(const Geom& g, const half_t* x, const float* w, int64_t n_to
 
 size_t kmeans_workspace_bytes(const Geom& g) { return km_plan(g).total; }
 
-// codes [B][Hkv][n_tok][M] must already hold the assignment of x to cb_in
+// codes [B][Hkv][n_tok][code bytes] must already hold the assignment of x to cb_in
 hipError_t launch_kmeans_update(const Geom& g, const half_t* x, const float* w, int64_t n_tok, const half_t* cb_in,
                                 half_t* cb_out, const uint8_t* codes, float* wsum_out, double* objective, void* ws,
                                 hipStream_t st)
 {
+    if (g.C == 4096) {
+        if (g.d == 32) return launch_t<32, true>(g, x, w, n_tok, cb_in, cb_out, codes, wsum_out, objective, (char*)ws, st);
+        return launch_t<16, true>(g, x, w, n_tok, cb_in, cb_out, codes, wsum_out, objective, (char*)ws, st);
+    }
     switch (g.d) {
-    case 4: return launch_t<4>(g, x, w, n_tok, cb_in, cb_out, codes, wsum_out, objective, (char*)ws, st);
-    case 8: return launch_t<8>(g, x, w, n_tok, cb_in, cb_out, codes, wsum_out, objective, (char*)ws, st);
-    default: return launch_t<16>(g, x, w, n_tok, cb_in, cb_out, codes, wsum_out, objective, (char*)ws, st);
+    case 4: return launch_t<4, false>(g, x, w, n_tok, cb_in, cb_out, codes, wsum_out, objective, (char*)ws, st);
+    case 8: return launch_t<8, false>(g, x, w, n_tok, cb_in, cb_out, codes, wsum_out, objective, (char*)ws, st);
+    default: return launch_t<16, false>(g, x, w, n_tok, cb_in, cb_out, codes, wsum_out, objective, (char*)ws, st);
     }
 }
 

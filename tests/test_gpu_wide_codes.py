@@ -144,7 +144,7 @@ def test_wide_geometry_rejections(books):
     assert lib.antkv_decode_attn_workspace(ctypes.byref(ok), 100, 0, 0, 0) > 0
     assert lib.antkv_decode_attn_workspace(ctypes.byref(ok), 100, 0, 0, 5) > lib.antkv_decode_attn_workspace(
         ctypes.byref(ok), 100, 0, 0, 0)
-    assert lib.antkv_kmeans_step_workspace(ctypes.byref(ok)) == 0
+    assert lib.antkv_kmeans_step_workspace(ctypes.byref(ok)) >= 2 * 128 * 4096 * 4        # fp32 sums of two KV heads
 
 
 @pytest.mark.parametrize("W", [8, 0])
@@ -227,3 +227,42 @@ def test_decode12_anchor_score_and_reselection(oracle, books, B, Hq, Hkv, N, k_k
         w_idx, margin = oracle.topk(score, k_resel, want_margin=True)
         soft += check_index_sets(got.cpu().numpy(), w_idx, margin)
     print(f"N={N} G={Hq // Hkv}: scores within 3e-5, near-tie index disagreements {soft}")
+
+
+@pytest.mark.parametrize("B,n", [(2, 2500), (1, 70)])
+def test_kmeans12_step(oracle, books, B, n):
+    """One weighted k-means iteration on a 4096-centroid codebook: assignment by the code rule, update compared on the
+    assignment the GPU used (most centroids get no token here and must keep their value)."""
+    _, x, _ = make_qkv(101 + n, B, 2, 2, n, 1, 128, want_v=False)
+    w = np.random.default_rng(n).gamma(0.5, 1.0, size=(B, 2, n)).astype(np.float32)
+    w[:, :, ::7] = 0.0                                         # some tokens carry no weight at all
+    cb = books[0]
+    geom = antkv.Geometry(B, 2, 2, books.d, n_centroids=C)
+    new, codes, wsum, obj = antkv.kmeans_step(geom, dev(x), dev(w), dev(cb))
+    torch.cuda.synchronize()
+    assert codes.shape == (B, 2, n, books.nbytes) and wsum.shape == (2, books.M, C)
+    codes_h = unpack12(codes.cpu().numpy())
+    want_codes, margin = oracle.encode(x, cb, want_margin=True)
+    soft = check_codes(codes_h, want_codes, margin)
+    want, want_w, want_obj = oracle.kmeans_update(x, w, codes_h, cb)
+    np.testing.assert_allclose(wsum.cpu().numpy(), want_w, rtol=2e-5, atol=1e-30)
+    np.testing.assert_allclose(obj.cpu().numpy(), want_obj, rtol=2e-5)
+    got = new.cpu().numpy()
+    empty = want_w == 0
+    assert np.array_equal(got[empty], cb[empty]), "a centroid without assigned weight must keep its value"
+    tol = np.abs(want) * 2.0 ** -10 + 2.0 ** -24 + 1e-5 * np.abs(want)
+    assert (np.abs(got.astype(np.float64) - want) <= tol).all()
+    print(f"d{books.d} n={n}: near-tie codes {soft}, centroids without weight {int(empty.sum())} of {empty.size}")
+
+
+def test_kmeans12_iterations_descend(oracle, books):
+    _, x, _ = make_qkv(103, 2, 2, 2, 6000, 1, 128, want_v=False)
+    w = np.random.default_rng(3).gamma(0.5, 1.0, size=(2, 2, 6000)).astype(np.float32)
+    geom = antkv.Geometry(2, 2, 2, books.d, n_centroids=C)
+    xd, wd, cur = dev(x), dev(w), dev(books[1])                # start from the V codebook: a poor fit for these K rows
+    hist = []
+    for _ in range(4):
+        cur, _, _, obj = antkv.kmeans_step(geom, xd, wd, cur)
+        hist.append(obj.cpu().numpy().sum())
+    assert all(b <= a * (1 + 1e-4) for a, b in zip(hist, hist[1:])), hist
+    assert hist[-1] < 0.9 * hist[0], hist
