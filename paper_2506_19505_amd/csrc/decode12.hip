@@ -664,17 +664,23 @@ __global__ __launch_bounds__(kT12) void d12_ans_kernel(const D12AnsParams p)
             const float ss = wave_sum(fmaf(a, a, c * c));
             if (lane == 0) s_red[kW12 * 4 + wave] = sqrtf(ss);
         }
-        if (PASS == 1 && wave == 2 && lane < 2) {                      // log-sum-exp from the S partials of pass 0
+        if (PASS == 1 && (wave == 2 || wave == 3)) {                   // log-sum-exp from the S partials of pass 0: a wave per head
+            const int h = wave - 2;
             float v = 0.f;
-            if (lane < nh) {
-                const float* sp_ = p.stat_part + ((int64_t)b * p.Hq + hfirst + lane) * p.S * 2;
-                float m = kNegBig;
-                for (int s = 0; s < p.S; ++s) m = fmaxf(m, sp_[2 * s]);
-                float l = 0.f;
-                for (int s = 0; s < p.S; ++s) l += sp_[2 * s + 1] * exp2f(sp_[2 * s] - m);
-                v = m + log2f(l);
+            if (h < nh) {
+                const float2* sp_ = (const float2*)(p.stat_part + ((int64_t)b * p.Hq + hfirst + h) * p.S * 2);
+                float m = kNegBig, l = 0.f;                            // per-lane (reference, sum) over its share of the pairs
+                for (int s = lane; s < p.S; s += 64) {
+                    const float2 ml = sp_[s];
+                    const float mn = fmaxf(m, ml.x);
+                    l = l * exp2f(m - mn) + ml.y * exp2f(ml.x - mn);
+                    m = mn;
+                }
+                const float mw = wave_max(m);
+                l = wave_sum(l * exp2f(m - mw));
+                v = mw + log2f(l);
             }
-            s_red[kW12 * 4 + 4 + lane] = v;
+            if (lane == 0) s_red[kW12 * 4 + 4 + h] = v;
         }
         __syncthreads();
         const float qn0 = s_red[kW12 * 4], qn1 = s_red[kW12 * 4 + 1];

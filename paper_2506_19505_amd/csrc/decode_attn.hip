@@ -1041,17 +1041,28 @@ struct DsParams {
     float c1;
     int Hq, Hkv, G, S;
     int64_t chunk;
+    unsigned long long* trace;  // ANTKV_DA_TRACE builds: [grid][8] wall-clock stamps, else unused
 };
+
+#ifdef ANTKV_DA_TRACE
+#define DS_STAMP(i) do { if (threadIdx.x == 0) p.trace[((size_t)(PASS + 1) * gridDim.x + blockIdx.x) * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define DS_STAMP(i) do { } while (0)
+#endif
 
 template <int DSUB, int PASS>
 __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p)
 {
     constexpr int M = kD / DSUB;
     constexpr int CW = M / 4;
+    // The table is code-major, [256 codes][SLOTS] entries of 4 heads x fp32 (16 bytes), slot s holding sub-space s mod M:
+    // the bank group of an entry (slot mod 16) then depends on the slot alone, and the 16 lanes of an LDS pass, which
+    // visit sub-space (step XOR lane) in copy (lane / M), hit 16 different groups whatever the codes are.
+    constexpr int SLOTS = M < 16 ? 16 : M;
     extern __shared__ uint4_t smem_u4[];
     char* smem = (char*)smem_u4;
-    float4_t* s_lut = (float4_t*)smem;                      // [M][256] x 4 heads fp32
-    float* s_qf = (float*)(smem + M * 256 * 16);            // [4][128]
+    float4_t* s_lut = (float4_t*)smem;                      // [256][SLOTS] x 4 heads fp32
+    float* s_qf = (float*)(smem + SLOTS * 256 * 16);        // [4][128]
     float* s_red = s_qf + kNH * kD;                         // [waves][8]
     int* s_misc = (int*)(s_red + kDaWaves * 8);             // 16 ints
     uint32_t* s_mask = (uint32_t*)(s_misc + 16);            // bitmap of K-anchored tokens, 1024 words
@@ -1064,30 +1075,61 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
     const int64_t t0 = (int64_t)sp * p.chunk;
     const int64_t t1 = (t0 + p.chunk < p.N) ? t0 + p.chunk : p.N;
 
+    // K-anchored tokens are scored from their FP16 rows after the code stream, 16 lanes per token and 8 channels each;
+    // blocks of 64 list entries are dealt round-robin over the S workgroups of the (sequence, KV head), whatever token
+    // range an entry falls into, so that anchors clustered in one part of the context do not pile up in one
+    // workgroup.  The loads of a wave's first kPre rounds are issued here, ahead of everything else: one after the
+    // other behind the stream they were a chain of exposed load latencies.
+    DS_STAMP(0);
+    constexpr int kPre = 4;
+    const int a_sub = lane >> 4, a_l16 = lane & 15;
+    const int a_first = sp * (4 * kDaWaves) + 4 * wave, a_stride = p.S * (4 * kDaWaves);
+    int pre_tok[kPre];
+    half8_t pre_v[kPre];
+#pragma unroll
+    for (int u = 0; u < kPre; ++u) {
+        const int i = a_first + u * a_stride + a_sub;
+        const bool on = i < p.k_k;
+        pre_tok[u] = on ? idx_k[i] : -1;
+        pre_v[u] = *(const half8_t*)(p.rows_k + ((int64_t)bg * p.k_k + (on ? i : 0)) * kD + 8 * a_l16);
+    }
+    // this thread's centroids (entries tid + 1024 j of the table): loaded before the barrier, used after it
+    constexpr int kEnt = M * 256 / kDaThreads;
+    const half_t* cbk = p.cb_k + (size_t)g * 32768;
+    uint4_t cen[kEnt][(DSUB + 7) / 8];
+#pragma unroll
+    for (int j = 0; j < kEnt; ++j) {
+        const int e = tid + j * kDaThreads;
+        if constexpr (DSUB == 4) {
+            const uint2_t v = *(const uint2_t*)(cbk + e * 4);
+            cen[j][0] = uint4_t{v[0], v[1], 0u, 0u};
+        } else {
+#pragma unroll
+            for (int u = 0; u < DSUB / 8; ++u) cen[j][u] = *(const uint4_t*)(cbk + e * DSUB + 8 * u);
+        }
+    }
     if (tid < kNH * kD) s_qf[tid] = ((tid >> 7) < p.G) ? (float)qb[tid] : 0.f;
     for (int i = tid; i < 1024; i += kDaThreads) s_mask[i] = 0u;
-    if (wave < 2) {
+    // K-anchored positions of this range: a list of up to 16 K entries is scanned whole (independent loads, one load
+    // latency); a longer one is cut to the range by a cooperative search first (a few dependent load latencies)
+    const bool scan_list = p.k_k <= 16 * kDaThreads;
+    if (!scan_list && wave < 2) {
         const int r = wave_lower_bound(idx_k, p.k_k, (int)(wave ? t1 : t0), lane);
         if (lane == 0) s_misc[wave] = r;
     }
     __syncthreads();
     {
         // fp32 table: entry e = (m, code) holds the four heads' c1 * q_h[m] . cb_k[g][m][code]
-        const half_t* cbk = p.cb_k + (size_t)g * 32768;
-        for (int e = tid; e < M * 256; e += kDaThreads) {
+#pragma unroll
+        for (int j = 0; j < kEnt; ++j) {
+            const int e = tid + j * kDaThreads;
             const int m = e >> 8;
             float cf[DSUB];
-            if constexpr (DSUB == 4) {
-                const half4_t v = *(const half4_t*)(cbk + e * 4);
 #pragma unroll
-                for (int t = 0; t < 4; ++t) cf[t] = (float)v[t];
-            } else {
+            for (int u = 0; u < (DSUB + 7) / 8; ++u) {
+                const half8_t v = __builtin_bit_cast(half8_t, cen[j][u]);
 #pragma unroll
-                for (int u = 0; u < DSUB / 8; ++u) {
-                    const half8_t v = *(const half8_t*)(cbk + e * DSUB + 8 * u);
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) cf[8 * u + t] = (float)v[t];
-                }
+                for (int t = 0; t < (DSUB < 8 ? DSUB : 8); ++t) cf[8 * u + t] = (float)v[t];
             }
             float4_t o;
 #pragma unroll
@@ -1097,12 +1139,27 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
                 for (int t = 0; t < DSUB; ++t) s = fmaf(s_qf[h * kD + m * DSUB + t], cf[t], s);
                 o[h] = s * p.c1;
             }
-            s_lut[e] = o;
+#pragma unroll
+            for (int c = 0; c < SLOTS / M; ++c) s_lut[(e & 255) * SLOTS + m + M * c] = o;
         }
     }
-    for (int i = s_misc[0] + tid; i < s_misc[1]; i += kDaThreads) {
-        const int rel = idx_k[i] - (int)t0;
-        atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
+    if (scan_list) {
+        const uint32_t range_len = (uint32_t)(t1 - t0);
+        for (int i0 = tid; i0 < p.k_k; i0 += 4 * kDaThreads) {
+            int v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = (i0 + u * kDaThreads < p.k_k) ? idx_k[i0 + u * kDaThreads] : -1;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t rel = (uint32_t)v[u] - (uint32_t)t0;   // positions below t0 (and the -1 filler) wrap to huge values
+                if (v[u] >= 0 && rel < range_len) atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
+            }
+        }
+    } else {
+        for (int i = s_misc[0] + tid; i < s_misc[1]; i += kDaThreads) {
+            const int rel = idx_k[i] - (int)t0;
+            atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
+        }
     }
     // ||q_h||_2: one wave per head
     if (wave < kNH) {
@@ -1110,18 +1167,25 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
         const float ss = wave_sum(fmaf(a, a, c * c));
         if (lane == 0) s_red[kDaWaves * 8 - 4 + wave] = sqrtf(ss);       // parked in the last wave's slots until the barrier
     }
-    // pass 1: log-sum-exp of each head from the S partial (max, sum) pairs that pass 0 left
-    if (PASS == 1 && wave == kNH && lane < kNH) {
+    // pass 1: log-sum-exp of each head from the S partial (max, sum) pairs that pass 0 left; one wave per head, the
+    // lanes share the S pairs
+    if (PASS == 1 && wave >= kNH && wave < 2 * kNH) {
+        const int h = wave - kNH;
         float v = 0.f;
-        if (lane < p.G) {
-            const float* sp_ = p.stat_part + ((int64_t)b * p.Hq + h0 + lane) * p.S * 2;
-            float m = kNegBig;
-            for (int s = 0; s < p.S; ++s) m = fmaxf(m, sp_[2 * s]);
-            float l = 0.f;
-            for (int s = 0; s < p.S; ++s) l += sp_[2 * s + 1] * exp2f(sp_[2 * s] - m);
-            v = m + log2f(l);
+        if (h < p.G) {
+            const float2* sp_ = (const float2*)(p.stat_part + ((int64_t)b * p.Hq + h0 + h) * p.S * 2);
+            float m = kNegBig, l = 0.f;                          // per-lane (reference, sum) over its share of the pairs
+            for (int s = lane; s < p.S; s += 64) {
+                const float2 ml = sp_[s];
+                const float mn = fmaxf(m, ml.x);
+                l = l * exp2f(m - mn) + ml.y * exp2f(ml.x - mn);
+                m = mn;
+            }
+            const float mw = wave_max(m);
+            l = wave_sum(l * exp2f(m - mw));
+            v = mw + log2f(l);
         }
-        s_red[kDaWaves * 8 - 8 + lane] = v;
+        if (lane == 0) s_red[kDaWaves * 8 - 8 + h] = v;
     }
     __syncthreads();
     float qn[kNH], lse[kNH];
@@ -1131,6 +1195,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
         lse[h] = (PASS == 1) ? s_red[kDaWaves * 8 - 8 + h] : 0.f;
     }
     __syncthreads();
+    DS_STAMP(1);
     const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * M;
     float m_run[kNH], l_run[kNH];
 #pragma unroll
@@ -1179,41 +1244,67 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
             }
         }
     };
-    uint32_t kw_next[CW];
+    // lane constants of the conflict-free walk: at step st the lane reads sub-space st ^ r
+    const int r = lane & (M - 1);
+    const uint32_t slot0 = (uint32_t)(r + (M < 16 ? M * ((lane / M) & (16 / M - 1)) : 0)) * 16u;   // byte offset of the slot at step 0
+    uint32_t sh4[4];                                              // bit offset of the code byte for step st: sh4[st & 3]
 #pragma unroll
-    for (int i = 0; i < CW; ++i) kw_next[i] = 0u;
-    if (t0 + tid < t1) load_kw(t0 + tid, kw_next);
-    for (int64_t tok = t0 + tid; tok < t1; tok += kDaThreads) {
-        uint32_t kw[CW];
+    for (int e = 0; e < 4; ++e) sh4[e] = 8u * (uint32_t)(e ^ (r & 3));
+    const char* lut_bytes = (const char*)s_lut;
+    // code loads run kAhead rounds ahead of their use (more than one round in flight did not pay)
+    constexpr int kAhead = 1;
+    uint32_t kw_q[kAhead][CW];
 #pragma unroll
-        for (int i = 0; i < CW; ++i) kw[i] = kw_next[i];
-        if (tok + kDaThreads < t1) load_kw(tok + kDaThreads, kw_next);
-        float s[kNH] = {0.f, 0.f, 0.f, 0.f};
+    for (int u = 0; u < kAhead; ++u) {
 #pragma unroll
-        for (int m = 0; m < M; ++m) {
-            const uint32_t code = (kw[m >> 2] >> (8 * (m & 3))) & 255u;
-            const float4_t e = s_lut[m * 256 + code];
-#pragma unroll
-            for (int h = 0; h < kNH; ++h) s[h] += e[h];
-        }
-        const int rel = (int)(tok - t0);
-        if (!((s_mask[rel >> 5] >> (rel & 31)) & 1u)) consume(s, tok);
+        for (int i = 0; i < CW; ++i) kw_q[u][i] = 0u;
+        if (t0 + tid + (int64_t)u * kDaThreads < t1) load_kw(t0 + tid + (int64_t)u * kDaThreads, kw_q[u]);
     }
-    // ---- K-anchored tokens: the score comes from the FP16 row.  16 lanes per token, 8 channels each.  Blocks of 64
-    // list entries are dealt round-robin over the S workgroups of the (sequence, KV head), whatever token range an
-    // entry falls into, so that anchors clustered in one part of the context do not pile up in one workgroup.
+    for (int64_t tok0 = t0 + tid; tok0 < t1; tok0 += (int64_t)kAhead * kDaThreads) {
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int64_t tok = tok0 + (int64_t)u * kDaThreads;
+            uint32_t kw[CW];
+#pragma unroll
+            for (int i = 0; i < CW; ++i) kw[i] = kw_q[u][i];
+            if (tok + (int64_t)kAhead * kDaThreads < t1) load_kw(tok + (int64_t)kAhead * kDaThreads, kw_q[u]);
+            if (tok >= t1) continue;
+            // code dwords XOR-permuted by r / 4, so that step st finds its dword at the compile-time index st / 4
+#pragma unroll
+            for (int bit = 0; (4 << bit) < M; ++bit) {
+                const bool sw = (r >> (2 + bit)) & 1;
+#pragma unroll
+                for (int i = 0; i < CW; ++i) {
+                    if (!(i & (1 << bit))) {
+                        const uint32_t a = kw[i], c = kw[i | (1 << bit)];
+                        kw[i] = sw ? c : a;
+                        kw[i | (1 << bit)] = sw ? a : c;
+                    }
+                }
+            }
+            float s[kNH] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int st = 0; st < M; ++st) {
+                const uint32_t code = __builtin_amdgcn_ubfe(kw[st >> 2], sh4[st & 3], 8u);
+                const uint32_t off = (code * (uint32_t)(SLOTS * 16)) | (slot0 ^ (uint32_t)(16 * st));
+                const float4_t e = *(const float4_t*)(lut_bytes + off);
+#pragma unroll
+                for (int h = 0; h < kNH; ++h) s[h] += e[h];
+            }
+            const int rel = (int)(tok - t0);
+            if (!((s_mask[rel >> 5] >> (rel & 31)) & 1u)) consume(s, tok);
+        }
+    }
+    DS_STAMP(2);
+    // ---- K-anchored tokens: the prefetched rounds, then any further ones
     {
-        const int sub = lane >> 4, l16 = lane & 15;
+        const int l16 = a_l16;
         float qv[kNH][8];
 #pragma unroll
         for (int h = 0; h < kNH; ++h)
 #pragma unroll
             for (int e = 0; e < 8; ++e) qv[h][e] = s_qf[h * kD + 8 * l16 + e];
-        for (int i0 = sp * (4 * kDaWaves) + 4 * wave; i0 < p.k_k; i0 += p.S * (4 * kDaWaves)) {
-            const int i = i0 + sub;
-            const bool on = i < p.k_k;
-            const int64_t tok = on ? idx_k[i] : t0;
-            const half8_t v = *(const half8_t*)(p.rows_k + ((int64_t)bg * p.k_k + (on ? i : 0)) * kD + 8 * l16);
+        auto score_row = [&](const half8_t& v, int tok) {
             float s[kNH];
 #pragma unroll
             for (int h = 0; h < kNH; ++h) {
@@ -1222,9 +1313,20 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
                 for (int e = 0; e < 8; ++e) d = fmaf(qv[h][e], (float)v[e], d);
                 s[h] = row16_sum(d) * p.c1;
             }
-            if (on && l16 == 0) consume(s, tok);
+            if (tok >= 0 && l16 == 0) consume(s, tok);
+        };
+#pragma unroll
+        for (int u = 0; u < kPre; ++u)
+            if (a_first + u * a_stride < p.k_k) score_row(pre_v[u], pre_tok[u]);        // uniform per wave
+        for (int i0 = a_first + kPre * a_stride; i0 < p.k_k; i0 += a_stride) {
+            const int i = i0 + a_sub;
+            const bool on = i < p.k_k;
+            const int tok = on ? idx_k[i] : -1;
+            const half8_t v = *(const half8_t*)(p.rows_k + ((int64_t)bg * p.k_k + (on ? i : 0)) * kD + 8 * l16);
+            score_row(v, tok);
         }
     }
+    DS_STAMP(3);
     if (PASS == 0) {
 #pragma unroll
         for (int h = 0; h < kNH; ++h) {
@@ -1243,6 +1345,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
             dst[1] = l;
         }
     }
+    DS_STAMP(4);
 }
 
 
@@ -1273,7 +1376,7 @@ DaPlan da_plan(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans
     (void)k_k; (void)k_v;
     size_t off = 0;
 #ifdef ANTKV_DA_TRACE
-    off += align_up((size_t)g.B * g.Hkv * pl.S * 8 * sizeof(unsigned long long));   // trace lives at offset 0
+    off += align_up((size_t)3 * g.B * g.Hkv * pl.S * 8 * sizeof(unsigned long long));   // trace lives at offset 0: main kernel, then the two score passes
 #endif
     pl.off_part = off; off += align_up((size_t)g.B * g.Hq * pl.S * (kD + 2) * sizeof(float));
     pl.off_done = off; off += align_up((size_t)g.B * g.Hkv * sizeof(unsigned long long));
@@ -1345,7 +1448,8 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
         d.stat_part = (float*)(w + pl.off_stat); d.ans_k = a.ans_k; d.ans_v = a.ans_v;
         d.N = a.N; d.N_cap = a.N_cap; d.k_k = (int)a.k_k; d.c1 = p.c1; d.Hq = g.Hq; d.Hkv = g.Hkv; d.G = g.G;
         d.S = pl.S; d.chunk = pl.chunk;
-        const size_t sh2 = (size_t)g.M * 256 * 16 + kNH * kD * 4 + kDaWaves * 32 + 64 + 4096;
+        d.trace = (unsigned long long*)ws;
+        const size_t sh2 = (size_t)(g.M < 16 ? 16 : g.M) * 256 * 16 + kNH * kD * 4 + kDaWaves * 32 + 64 + 4096;
         static const hipError_t ans_setup = [sh2]() {              // once per process and DSUB
             hipError_t e1 = hipFuncSetAttribute((const void*)decode_ans_kernel<DSUB, 0>,
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh2);
