@@ -4,7 +4,8 @@
 //
 // argmin_c ||x - c||^2 = argmax_c (x.c - ||c||^2 / 2).  A 1 MB codebook per KV head does not fit LDS, so centroid
 // tiles come straight from global memory (L2; the four waves of a workgroup walk the same tiles, so L1 serves three
-// of them) and only the -||c||^2/2 table of the current sub-space (16 KB) is kept in LDS.
+// of them; a wave uses each tile for both of its 32-token groups) and only the -||c||^2/2 table of the current
+// sub-space (16 KB) is kept in LDS.
 //   level 1  per 32 tokens x 32 centroids: v_mfma_f32_32x32x16_f16 (one per 16 channels) with centroids on the row
 //            axis and tokens on the column axis, accumulator pre-loaded with -||c||^2/2.  A lane owns one token and 16 of the 32
 //            centroid scores; it keeps the best score and the index of the tile it came from (a max3 tree, one
@@ -70,55 +71,63 @@ __global__ __launch_bounds__(kE12Threads) void encode12_kernel(
             s_nrm[c] = -0.5f * s;
         }
         __syncthreads();
+        // the wave's two groups of 32 tokens share every centroid tile it loads
+        const half_t* xr[2];
+        half8_t xb[2][NS];                                          // B operand: k-step s holds channels 16 s + 8 kh .. + 7
+        float best[2] = {-3.0e38f, -3.0e38f};
+        int best_blk[2] = {0, 0};
 #pragma unroll
         for (int tg = 0; tg < 2; ++tg) {
             const int64_t t = (int64_t)blockIdx.x * kE12Tokens + wave * 64 + tg * 32 + n;
             const int64_t tl = t < n_tok ? t : n_tok - 1;
-            const half_t* xr = xbase + tl * xs_t + m * kD12;
-            // B operand: k-step s holds channels 16 s + 8 kh .. + 7 of this lane's token
-            half8_t xb[NS];
+            xr[tg] = xbase + tl * xs_t + m * kD12;
 #pragma unroll
-            for (int s = 0; s < NS; ++s) xb[s] = *(const half8_t*)(xr + 16 * s + 8 * kh);
-            float best = -3.0e38f;
-            int best_blk = 0;
-            // A operand of tile blk: centroid 32 blk + n, same channel split; loads run one tile ahead
-            const half_t* ap = cbm + n * kD12 + 8 * kh;
-            half8_t an[NS];
+            for (int s = 0; s < NS; ++s) xb[tg][s] = *(const half8_t*)(xr[tg] + 16 * s + 8 * kh);
+        }
+        // A operand of tile blk: centroid 32 blk + n, same channel split; loads run one tile ahead
+        const half_t* ap = cbm + n * kD12 + 8 * kh;
+        half8_t an[NS];
 #pragma unroll
-            for (int s = 0; s < NS; ++s) an[s] = *(const half8_t*)(ap + 16 * s);
+        for (int s = 0; s < NS; ++s) an[s] = *(const half8_t*)(ap + 16 * s);
 #pragma unroll 2
-            for (int blk = 0; blk < kC12 / 32; ++blk) {
-                half8_t ac[NS];
+        for (int blk = 0; blk < kC12 / 32; ++blk) {
+            half8_t ac[NS];
 #pragma unroll
-                for (int s = 0; s < NS; ++s) ac[s] = an[s];
-                if (blk + 1 < kC12 / 32) {
+            for (int s = 0; s < NS; ++s) ac[s] = an[s];
+            if (blk + 1 < kC12 / 32) {
 #pragma unroll
-                    for (int s = 0; s < NS; ++s) an[s] = *(const half8_t*)(ap + (blk + 1) * 32 * kD12 + 16 * s);
-                }
+                for (int s = 0; s < NS; ++s) an[s] = *(const half8_t*)(ap + (blk + 1) * 32 * kD12 + 16 * s);
+            }
+            float4_t nb[4];
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) nb[qd] = *(const float4_t*)(&s_nrm[blk * 32 + 8 * qd + 4 * kh]);
+#pragma unroll
+            for (int tg = 0; tg < 2; ++tg) {
                 float16_t acc;
 #pragma unroll
-                for (int qd = 0; qd < 4; ++qd) {                    // rows 8 qd + 4 kh + e live in acc[4 qd + e]
-                    const float4_t nb = *(const float4_t*)(&s_nrm[blk * 32 + 8 * qd + 4 * kh]);
+                for (int qd = 0; qd < 4; ++qd)                      // rows 8 qd + 4 kh + e live in acc[4 qd + e]
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[4 * qd + e] = nb[e];
-                }
+                    for (int e = 0; e < 4; ++e) acc[4 * qd + e] = nb[qd][e];
 #pragma unroll
-                for (int s = 0; s < NS; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ac[s], xb[s], acc, 0, 0, 0);
+                for (int s = 0; s < NS; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ac[s], xb[tg][s], acc, 0, 0, 0);
                 float mx = max3f(acc[0], acc[1], acc[2]);
 #pragma unroll
                 for (int r = 3; r < 15; r += 2) mx = max3f(mx, acc[r], acc[r + 1]);
                 mx = fmaxf(mx, acc[15]);
-                if (mx > best) { best = mx; best_blk = blk; }       // strict: an equal later tile does not replace
+                if (mx > best[tg]) { best[tg] = mx; best_blk[tg] = blk; }   // strict: an equal later tile does not replace
             }
+        }
+#pragma unroll
+        for (int tg = 0; tg < 2; ++tg) {
             // level 2: the 16 candidates of the best tile, ascending centroid index
             half8_t xf[NU];
 #pragma unroll
-            for (int u = 0; u < NU; ++u) xf[u] = *(const half8_t*)(xr + 8 * u);
+            for (int u = 0; u < NU; ++u) xf[u] = *(const half8_t*)(xr[tg] + 8 * u);
             float bv = -3.0e38f;
             int bc = 0;
 #pragma unroll 4
             for (int r = 0; r < 16; ++r) {
-                const int c = best_blk * 32 + 8 * (r >> 2) + 4 * kh + (r & 3);
+                const int c = best_blk[tg] * 32 + 8 * (r >> 2) + 4 * kh + (r & 3);
                 const half_t* cp = cbm + c * kD12;
                 float s = s_nrm[c];
 #pragma unroll

@@ -152,12 +152,16 @@ __global__ __launch_bounds__(256) void km_finalize(const float* __restrict__ sum
                                                    const half_t* __restrict__ cb_in, half_t* __restrict__ cb_out,
                                                    float* __restrict__ wsum_out, int64_t n_centroids)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // (g, m, c) flattened
+    // a thread takes up to 8 channels of one centroid, so that neighbouring threads touch neighbouring memory
+    constexpr int PER = DSUB < 8 ? DSUB : 8, PARTS = DSUB / PER;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = t / PARTS;                                         // (g, m, c) flattened
+    const int part = (int)(t % PARTS);
     if (i >= n_centroids) return;
     const float ws = wsum[i];
-    if (wsum_out) wsum_out[i] = ws;
+    if (wsum_out && part == 0) wsum_out[i] = ws;
 #pragma unroll
-    for (int e = 0; e < DSUB; ++e)
+    for (int e = PER * part; e < PER * part + PER; ++e)
         cb_out[i * DSUB + e] = ws > 0.f ? (half_t)(sums[i * DSUB + e] / ws) : cb_in[i * DSUB + e];
 }
 
@@ -201,7 +205,8 @@ hipError_t launch_t(const Geom& g, const half_t* x, const float* w, int64_t n_to
         }
     }
     const int64_t n_cen = (int64_t)g.Hkv * g.M * g.C;
-    hipLaunchKernelGGL(km_finalize<DSUB>, dim3((unsigned)((n_cen + 255) / 256)), dim3(256), 0, st, sums, wsum, cb_in,
+    const int64_t n_fin = n_cen * (DSUB < 8 ? 1 : DSUB / 8);
+    hipLaunchKernelGGL(km_finalize<DSUB>, dim3((unsigned)((n_fin + 255) / 256)), dim3(256), 0, st, sums, wsum, cb_in,
                        cb_out, wsum_out, n_cen);
     return hipGetLastError();
 }
