@@ -566,20 +566,59 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     }
 }
 
-// merge the S partials of a (sequence, query head) by log-sum-exp and round once to fp16
+// merge the S partials of a (sequence, query head) by log-sum-exp and round once to fp16.  The S references and sums go
+// through LDS first (one round of loads instead of a chain of S), then every channel thread sums its column with eight
+// independent loads in flight.
+constexpr int kMergeSlots = 1024;
+
 __global__ __launch_bounds__(kD) void decode12_merge(const float* __restrict__ part, int S, half_t* __restrict__ out)
 {
+    __shared__ float s_w[kMergeSlots];
+    __shared__ float s_tot;
     const int64_t bh = blockIdx.x;
-    const int ch = threadIdx.x;
+    const int ch = threadIdx.x, lane = ch & 63;
     const float* pb = part + bh * S * (kD + 2);
-    float m = kEmptyRef12;
-    for (int s = 0; s < S; ++s) m = fmaxf(m, pb[s * (kD + 2)]);
-    float l = 0.f, a = 0.f;
-    for (int s = 0; s < S; ++s) {
-        const float f = fast_exp2(pb[s * (kD + 2)] - m);
-        l = fmaf(pb[s * (kD + 2) + 1], f, l);
-        a = fmaf(pb[s * (kD + 2) + 2 + ch], f, a);
+    if (S > kMergeSlots) {                                             // more slots than the staging holds: plain loops
+        float m = kEmptyRef12;
+        for (int s = 0; s < S; ++s) m = fmaxf(m, pb[s * (kD + 2)]);
+        float l = 0.f, a = 0.f;
+        for (int s = 0; s < S; ++s) {
+            const float f = fast_exp2(pb[s * (kD + 2)] - m);
+            l = fmaf(pb[s * (kD + 2) + 1], f, l);
+            a = fmaf(pb[s * (kD + 2) + 2 + ch], f, a);
+        }
+        out[bh * kD + ch] = (half_t)(l > 0.f ? a / l : 0.f);
+        return;
     }
+    for (int s = ch; s < S; s += kD) s_w[s] = pb[s * (kD + 2)];
+    __syncthreads();
+    if (ch < 64) {                                                     // one wave: global reference, slot weights, total sum
+        float m = kEmptyRef12;
+        for (int s = lane; s < S; s += 64) m = fmaxf(m, s_w[s]);
+        m = wave_max(m);
+        float l = 0.f;
+        for (int s = lane; s < S; s += 64) {
+            const float f = fast_exp2(s_w[s] - m);
+            s_w[s] = f;
+            l = fmaf(pb[s * (kD + 2) + 1], f, l);
+        }
+        l = wave_sum(l);
+        if (lane == 0) s_tot = l;
+    }
+    __syncthreads();
+    float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const float* pc = pb + 2 + ch;
+    int s = 0;
+    for (; s + 8 <= S; s += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = pc[(int64_t)(s + u) * (kD + 2)];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a8[u] = fmaf(v[u], s_w[s + u], a8[u]);
+    }
+    for (; s < S; ++s) a8[0] = fmaf(pc[(int64_t)s * (kD + 2)], s_w[s], a8[0]);
+    const float a = ((a8[0] + a8[1]) + (a8[2] + a8[3])) + ((a8[4] + a8[5]) + (a8[6] + a8[7]));
+    const float l = s_tot;
     out[bh * kD + ch] = (half_t)(l > 0.f ? a / l : 0.f);
 }
 
