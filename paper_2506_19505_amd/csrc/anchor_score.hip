@@ -208,16 +208,30 @@ __global__ __launch_bounds__(256) void ans_finalize_stats(
     for (int e = 0; e < 8; ++e) s = fmaf((float)v[e], (float)v[e], s);
 #pragma unroll
     for (int off = 8; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
-    if (part_i != 0) return;
-    nq_out[row] = sqrtf(s);
     if (row_max) {
-        c_out[row] = row_max[row] * kLog2e + log2f(row_sum[row]);
-    } else {
-        float m = kNegBig;
-        for (int i = 0; i < KS; ++i) m = fmaxf(m, part[(row * KS + i) * 2]);
-        float l = 0.f;
-        for (int i = 0; i < KS; ++i) l += part[(row * KS + i) * 2 + 1] * exp2f(part[(row * KS + i) * 2] - m);
-        c_out[row] = m + log2f(l);
+        if (part_i == 0) {
+            nq_out[row] = sqrtf(s);
+            c_out[row] = row_max[row] * kLog2e + log2f(row_sum[row]);
+        }
+        return;
+    }
+    // the 16 lanes of the group share the KS partial (reference, sum) pairs, then combine
+    float m = kNegBig, l = 0.f;
+    for (int i = part_i; i < KS; i += 16) {
+        const float2 ml = *(const float2*)(part + (row * KS + i) * 2);
+        const float mn = fmaxf(m, ml.x);
+        l = l * exp2f(m - mn) + ml.y * exp2f(ml.x - mn);
+        m = mn;
+    }
+    float mg = m;
+#pragma unroll
+    for (int off = 8; off >= 1; off >>= 1) mg = fmaxf(mg, __shfl_xor(mg, off, 64));
+    l *= exp2f(m - mg);
+#pragma unroll
+    for (int off = 8; off >= 1; off >>= 1) l += __shfl_xor(l, off, 64);
+    if (part_i == 0) {
+        nq_out[row] = sqrtf(s);
+        c_out[row] = mg + log2f(l);
     }
 }
 
