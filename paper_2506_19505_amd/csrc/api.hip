@@ -288,13 +288,16 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
         a.cb_k = (const half_t*)cb_k; a.cb_v = (const half_t*)cb_v; a.idx_k = idx_k; a.rows_k = (const half_t*)rows_k;
         a.k_k = k_k; a.idx_v = idx_v; a.rows_v = (const half_t*)rows_v; a.k_v = k_v; a.out = (half_t*)out;
         a.ans_k = ans_k; a.ans_v = ans_v;
+        // with both index sets wanted, the score pass counts its scores into the selection's first histogram
+        const bool fused = N > 0 && k_resel > 0 && resel_idx_k && resel_idx_v;
+        a.topk_hist = fused ? launch_topk2_begin((int64_t)g.B * g.Hkv, N, (char*)workspace + off_topk, st) : nullptr;
         if (launch_decode12(g, a, workspace, st) != hipSuccess) return ANTKV_ELAUNCH;
         if (N > 0 && k_resel > 0 && (resel_idx_k || resel_idx_v)) {
             char* w = (char*)workspace;
             const int64_t rows = (int64_t)g.B * g.Hkv;
             const hipError_t e =
                 (resel_idx_k && resel_idx_v)
-                    ? launch_topk2(ans_k, resel_idx_k, ans_v, resel_idx_v, rows, N, k_resel, w + off_topk, st)
+                    ? launch_topk2_finish(ans_k, resel_idx_k, ans_v, resel_idx_v, rows, N, k_resel, w + off_topk, st)
                     : launch_topk(resel_idx_k ? ans_k : ans_v, rows, N, k_resel, resel_idx_k ? resel_idx_k : resel_idx_v,
                                   w + off_topk, st);
             if (e != hipSuccess) return ANTKV_ELAUNCH;
@@ -309,13 +312,16 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
     a.cb_k = (const half_t*)cb_k; a.cb_v = (const half_t*)cb_v; a.idx_k = idx_k; a.rows_k = (const half_t*)rows_k;
     a.k_k = k_k; a.idx_v = idx_v; a.rows_v = (const half_t*)rows_v; a.k_v = k_v; a.out = (half_t*)out;
     a.ans_k = ans_k; a.ans_v = ans_v;
+    // with both index sets wanted, the score pass counts its scores into the selection's first histogram
+    const bool fused = N > 0 && k_resel > 0 && resel_idx_k && resel_idx_v;
+    a.topk_hist = fused ? launch_topk2_begin((int64_t)g.B * g.Hkv, N, (char*)workspace + dp.off_topk, st) : nullptr;
     hipError_t e = launch_decode_attn(g, a, workspace, st);
     if (e != hipSuccess) return ANTKV_ELAUNCH;
     if (N > 0 && k_resel > 0) {
         char* w = (char*)workspace;
         const int64_t rows = (int64_t)g.B * g.Hkv;
         if (resel_idx_k && resel_idx_v) {
-            e = launch_topk2(ans_k, resel_idx_k, ans_v, resel_idx_v, rows, N, k_resel, w + dp.off_topk, st);
+            e = launch_topk2_finish(ans_k, resel_idx_k, ans_v, resel_idx_v, rows, N, k_resel, w + dp.off_topk, st);
             if (e != hipSuccess) return ANTKV_ELAUNCH;
         } else if (resel_idx_k || resel_idx_v) {
             e = launch_topk(resel_idx_k ? ans_k : ans_v, rows, N, k_resel, resel_idx_k ? resel_idx_k : resel_idx_v,

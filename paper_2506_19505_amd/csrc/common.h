@@ -94,6 +94,14 @@ hipError_t launch_topk(const float* scores, int64_t n_rows, int64_t N, int64_t k
                        void* ws, hipStream_t st);
 hipError_t launch_topk2(const float* scores, int32_t* idx, const float* scores_b, int32_t* idx_b, int64_t n_rows,
                         int64_t N, int64_t k, void* ws, hipStream_t st);
+// The same selection in two halves, for a producer that counts its scores while it writes them: `begin` clears the
+// workspace's counters and returns the first-level histograms, uint32 [2 n_rows][2 * kTopkBins] (row r < n_rows belongs
+// to scores row r, row n_rows + r to scores_b row r; the first kTopkBins words of a row count float_key(score) >> 21);
+// the producer adds every score it writes to them; `finish` selects from there without reading the scores for a histogram.
+constexpr int kTopkBins = 2048;
+uint32_t* launch_topk2_begin(int64_t n_rows, int64_t N, void* ws, hipStream_t st);
+hipError_t launch_topk2_finish(const float* scores, int32_t* idx, const float* scores_b, int32_t* idx_b, int64_t n_rows,
+                               int64_t N, int64_t k, void* ws, hipStream_t st);
 
 hipError_t launch_gather_rows(const Geom& g, const half_t* x, int64_t N, const int32_t* idx,
                               int64_t k, half_t* rows, hipStream_t st);
@@ -126,6 +134,7 @@ struct DecodeArgs {
     int64_t k_v;
     half_t* out;
     float *ans_k, *ans_v;
+    uint32_t* topk_hist;   // optional: first-level top-k histograms that the score pass fills (see launch_topk2_begin)
 };
 int decode_num_splits(const Geom& g, int64_t N);
 void decode_profile_next(hipEvent_t start, hipEvent_t stop);

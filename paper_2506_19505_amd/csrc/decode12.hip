@@ -640,9 +640,10 @@ struct D12AnsParams {
     int k_k;
     float c1;
     int Hq, Hkv, G, S, chunk;
+    uint32_t* hist;                       // optional (pass 1): first-level top-k histograms, [2 B Hkv][2 * kTopkBins], K rows then V rows
 };
 
-constexpr size_t kD12AnsLds = (size_t)128 * 1024 + 1024 * 4 + 2 * kD * 4 + (kW12 * 4 + 8) * 4 + 16 * 4;
+constexpr size_t kD12AnsLds = (size_t)128 * 1024 + 1024 * 4 + 2 * kD * 4 + (kW12 * 4 + 8) * 4 + 16 * 4 + 2 * kTopkBins * 4;
 
 template <int kD12, int PASS>
 __global__ __launch_bounds__(kT12) void d12_ans_kernel(const D12AnsParams p)
@@ -658,6 +659,7 @@ __global__ __launch_bounds__(kT12) void d12_ans_kernel(const D12AnsParams p)
     float* s_qf = (float*)(s_mk + 1024);                               // [2][128]
     float* s_red = s_qf + 2 * kD;                                      // [waves][4] + 8
     int* s_misc = (int*)(s_red + kW12 * 4 + 8);
+    uint32_t* s_hist = (uint32_t*)(s_misc + 16);                       // pass 1 with p.hist: [2][kTopkBins] counts of the final scores
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = blockIdx.x % p.Hkv;
     const int rest = blockIdx.x / p.Hkv;
@@ -669,8 +671,11 @@ __global__ __launch_bounds__(kT12) void d12_ans_kernel(const D12AnsParams p)
     const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * CB;
     float* out_k = p.ans_k + (int64_t)bg * p.N;
     float* out_v = p.ans_v + (int64_t)bg * p.N;
+    const bool count_scores = PASS == 1 && p.hist != nullptr;
 
     s_mk[tid] = 0u;
+    if (count_scores)
+        for (int i = tid; i < 2 * kTopkBins; i += kT12) s_hist[i] = 0u;
     if (wave < 2) {
         const int r = lower_bound64(idx_k, p.k_k, (int)(wave ? t1 : t0), lane);
         if (lane == 0) s_misc[wave] = r;
@@ -748,6 +753,10 @@ __global__ __launch_bounds__(kT12) void d12_ans_kernel(const D12AnsParams p)
                 if (hh > 0) { av += out_v[tok]; ak += out_k[tok]; }    // earlier walks' heads, written by this thread
                 out_v[tok] = av;
                 out_k[tok] = ak;
+                if (count_scores && hh == n_walks - 1) {               // final values: the selection that follows starts from these counts
+                    atomicAdd(&s_hist[float_key(ak) >> 21], 1u);
+                    atomicAdd(&s_hist[kTopkBins + (float_key(av) >> 21)], 1u);
+                }
             }
         };
 
@@ -811,6 +820,16 @@ __global__ __launch_bounds__(kT12) void d12_ans_kernel(const D12AnsParams p)
                 dst[0] = m;
                 dst[1] = l;
             }
+        }
+    }
+    if (count_scores) {
+        __syncthreads();
+        const int64_t n_bg = (int64_t)gridDim.x / p.S;                 // B * Hkv: the V rows follow the K rows
+        uint32_t* hk = p.hist + (int64_t)bg * 2 * kTopkBins;
+        uint32_t* hv = p.hist + (n_bg + bg) * 2 * kTopkBins;
+        for (int i = tid; i < kTopkBins; i += kT12) {
+            if (s_hist[i]) atomicAdd(&hk[i], s_hist[i]);
+            if (s_hist[kTopkBins + i]) atomicAdd(&hv[i], s_hist[kTopkBins + i]);
         }
     }
 }
@@ -884,6 +903,7 @@ hipError_t launch_decode12_t(const Geom& g, const DecodeArgs& a, void* ws, hipSt
         d.q = a.q; d.codes_k = a.codes_k; d.idx_k = a.idx_k; d.rows_k = a.rows_k; d.tab = p.tab;
         d.stat_part = (float*)(w + pl.off_stat); d.ans_k = a.ans_k; d.ans_v = a.ans_v; d.N = a.N; d.N_cap = a.N_cap;
         d.k_k = (int)a.k_k; d.c1 = p.c1; d.Hq = g.Hq; d.Hkv = g.Hkv; d.G = g.G; d.S = pl.S; d.chunk = pl.chunk;
+        d.hist = a.topk_hist;
         const unsigned grid = (unsigned)(g.B * g.Hkv * pl.S);
         hipLaunchKernelGGL((d12_ans_kernel<DS, 0>), dim3(grid), dim3(kT12), kD12AnsLds, st, d);
         hipLaunchKernelGGL((d12_ans_kernel<DS, 1>), dim3(grid), dim3(kT12), kD12AnsLds, st, d);

@@ -1041,6 +1041,7 @@ struct DsParams {
     float c1;
     int Hq, Hkv, G, S;
     int64_t chunk;
+    uint32_t* hist;             // optional (pass 1): first-level top-k histograms, [2 B Hkv][2 * kTopkBins], K rows then V rows
     unsigned long long* trace;  // ANTKV_DA_TRACE builds: [grid][8] wall-clock stamps, else unused
 };
 
@@ -1066,6 +1067,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
     float* s_red = s_qf + kNH * kD;                         // [waves][8]
     int* s_misc = (int*)(s_red + kDaWaves * 8);             // 16 ints
     uint32_t* s_mask = (uint32_t*)(s_misc + 16);            // bitmap of K-anchored tokens, 1024 words
+    uint32_t* s_hist = s_mask + 1024;                       // pass 1 with p.hist: [2][kTopkBins] counts of the scores written
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bg = blockIdx.x / p.S, sp = blockIdx.x % p.S;
     const int b = bg / p.Hkv, g = bg % p.Hkv;
@@ -1110,6 +1112,9 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
     }
     if (tid < kNH * kD) s_qf[tid] = ((tid >> 7) < p.G) ? (float)qb[tid] : 0.f;
     for (int i = tid; i < 1024; i += kDaThreads) s_mask[i] = 0u;
+    const bool count_scores = PASS == 1 && p.hist != nullptr;
+    if (count_scores)
+        for (int i = tid; i < 2 * kTopkBins; i += kDaThreads) s_hist[i] = 0u;
     // K-anchored positions of this range: a list of up to 16 K entries is scanned whole (independent loads, one load
     // latency); a longer one is cut to the range by a cooperative search first (a few dependent load latencies)
     const bool scan_list = p.k_k <= 16 * kDaThreads;
@@ -1228,6 +1233,10 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
             }
             p.ans_v[(int64_t)bg * p.N + tok] = av;
             p.ans_k[(int64_t)bg * p.N + tok] = ak;
+            if (count_scores) {                                  // the selection that follows starts from these counts
+                atomicAdd(&s_hist[float_key(ak) >> 21], 1u);
+                atomicAdd(&s_hist[kTopkBins + (float_key(av) >> 21)], 1u);
+            }
         }
     };
 
@@ -1345,6 +1354,15 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
             dst[1] = l;
         }
     }
+    if (count_scores) {
+        __syncthreads();
+        uint32_t* hk = p.hist + (int64_t)bg * 2 * kTopkBins;
+        uint32_t* hv = p.hist + ((int64_t)gridDim.x / p.S + bg) * 2 * kTopkBins;     // V rows follow the B * Hkv K rows
+        for (int i = tid; i < kTopkBins; i += kDaThreads) {
+            if (s_hist[i]) atomicAdd(&hk[i], s_hist[i]);
+            if (s_hist[kTopkBins + i]) atomicAdd(&hv[i], s_hist[kTopkBins + i]);
+        }
+    }
     DS_STAMP(4);
 }
 
@@ -1449,7 +1467,8 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
         d.N = a.N; d.N_cap = a.N_cap; d.k_k = (int)a.k_k; d.c1 = p.c1; d.Hq = g.Hq; d.Hkv = g.Hkv; d.G = g.G;
         d.S = pl.S; d.chunk = pl.chunk;
         d.trace = (unsigned long long*)ws;
-        const size_t sh2 = (size_t)(g.M < 16 ? 16 : g.M) * 256 * 16 + kNH * kD * 4 + kDaWaves * 32 + 64 + 4096;
+        d.hist = a.topk_hist;
+        const size_t sh2 = (size_t)(g.M < 16 ? 16 : g.M) * 256 * 16 + kNH * kD * 4 + kDaWaves * 32 + 64 + 4096 + 2 * kTopkBins * 4;
         static const hipError_t ans_setup = [sh2]() {              // once per process and DSUB
             hipError_t e1 = hipFuncSetAttribute((const void*)decode_ans_kernel<DSUB, 0>,
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh2);

@@ -22,7 +22,7 @@ namespace {
 
 constexpr int kSlice = 8192;
 constexpr int kTopkThreads = 256;
-constexpr int kBins = 2048;
+constexpr int kBins = kTopkBins;
 
 // Find the bin where the count of keys taken from the top reaches k_rem.
 // On return digit = that bin, k_new = how many keys are still needed inside it.
@@ -420,10 +420,22 @@ size_t topk_workspace_bytes(int64_t n_rows, int64_t N, int64_t k)
 
 // Two score arrays of n_rows rows each can be selected in one go (scores_b / idx_b may be NULL): the launches then
 // cover 2 n_rows rows, the first n_rows from `scores` into `idx`, the rest from `scores_b` into `idx_b`.
-hipError_t launch_topk2(const float* scores, int32_t* idx, const float* scores_b, int32_t* idx_b, int64_t n_rows,
-                        int64_t N, int64_t k, void* ws, hipStream_t st)
+namespace {
+
+// clears the histograms and headers of `rows` rows
+uint32_t* topk_clear(int64_t rows, int64_t N, void* ws, hipStream_t st)
 {
-    if (k == 0 || n_rows == 0) return hipSuccess;
+    const TopkPlan p = topk_plan(rows, N);
+    uint32_t* hist = (uint32_t*)((char*)ws + p.off_hist);
+    const int64_t nz = (int64_t)(p.off_counts / 4);             // histograms and headers
+    hipLaunchKernelGGL(zero_u32, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, hist, nz);
+    return hist;
+}
+
+// everything after the first-level histogram
+hipError_t topk_select(const float* scores, int32_t* idx, const float* scores_b, int32_t* idx_b, int64_t n_rows,
+                       int64_t N, int64_t k, void* ws, hipStream_t st)
+{
     const int64_t rows = scores_b ? 2 * n_rows : n_rows;
     const TopkPlan p = topk_plan(rows, N);
     char* w = (char*)ws;
@@ -431,11 +443,8 @@ hipError_t launch_topk2(const float* scores, int32_t* idx, const float* scores_b
     uint32_t* head = (uint32_t*)(w + p.off_head);
     uint32_t* counts = (uint32_t*)(w + p.off_counts);
     uint2_t* cand = (uint2_t*)(w + p.off_cand);
-    const int64_t nz = (int64_t)(p.off_counts / 4);             // histograms and headers
     const int ra = (int)n_rows;
-    hipLaunchKernelGGL(zero_u32, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, hist, nz);
     dim3 grid(p.n_slices, (unsigned)rows);
-    hipLaunchKernelGGL(topk_hist0, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, hist);
     hipLaunchKernelGGL(topk_collect<1>, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist, head,
                        counts, p.n_slices, cand, p.cap);
     hipLaunchKernelGGL(topk_collect<2>, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, hist, head,
@@ -445,6 +454,29 @@ hipError_t launch_topk2(const float* scores, int32_t* idx, const float* scores_b
     hipLaunchKernelGGL(topk_emit, grid, dim3(kTopkThreads), 0, st, scores, scores_b, ra, N, (uint32_t)k, head, counts,
                        p.n_slices, idx, idx_b);
     return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_topk2(const float* scores, int32_t* idx, const float* scores_b, int32_t* idx_b, int64_t n_rows,
+                        int64_t N, int64_t k, void* ws, hipStream_t st)
+{
+    if (k == 0 || n_rows == 0) return hipSuccess;
+    const int64_t rows = scores_b ? 2 * n_rows : n_rows;
+    uint32_t* hist = topk_clear(rows, N, ws, st);
+    const TopkPlan p = topk_plan(rows, N);
+    dim3 grid(p.n_slices, (unsigned)rows);
+    hipLaunchKernelGGL(topk_hist0, grid, dim3(kTopkThreads), 0, st, scores, scores_b, (int)n_rows, N, hist);
+    return topk_select(scores, idx, scores_b, idx_b, n_rows, N, k, ws, st);
+}
+
+uint32_t* launch_topk2_begin(int64_t n_rows, int64_t N, void* ws, hipStream_t st) { return topk_clear(2 * n_rows, N, ws, st); }
+
+hipError_t launch_topk2_finish(const float* scores, int32_t* idx, const float* scores_b, int32_t* idx_b, int64_t n_rows,
+                               int64_t N, int64_t k, void* ws, hipStream_t st)
+{
+    if (k == 0 || n_rows == 0) return hipSuccess;
+    return topk_select(scores, idx, scores_b, idx_b, n_rows, N, k, ws, st);
 }
 
 hipError_t launch_topk(const float* scores, int64_t n_rows, int64_t N, int64_t k, int32_t* idx, void* ws,
