@@ -9,7 +9,8 @@ distinct copies of the cache so that no buffer is re-read out of the 256 MB last
 (single-copy) rate is reported beside it.  Encode and anchor-selection rates on the 32768-token prefill
 shape ("cfg3") are reported as extras.
 
-Prints one JSON line (see README for the fields).
+Prints one JSON line: metric, value, unit, timing and workload fields, a `roofline` object for the decode kernel and a
+`cpu_baseline` object for the CPU oracle timed on the host.
 """
 from __future__ import annotations
 
@@ -63,8 +64,8 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time to spend on the oracle baseline")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (the path is a single-GPU kernel path; "
-              "see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the path is a single-GPU kernel path; nothing here uses a "
+              "second GPU); run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np
