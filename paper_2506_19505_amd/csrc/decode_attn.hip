@@ -1092,8 +1092,12 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
     for (int u = 0; u < kPre; ++u) {
         const int i = a_first + u * a_stride + a_sub;
         const bool on = i < p.k_k;
-        pre_tok[u] = on ? idx_k[i] : -1;
-        pre_v[u] = *(const half8_t*)(p.rows_k + ((int64_t)bg * p.k_k + (on ? i : 0)) * kD + 8 * a_l16);
+        pre_tok[u] = -1;
+        pre_v[u] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+        if (on) {     // an empty K list may come with null pointers: nothing is read then
+            pre_tok[u] = idx_k[i];
+            pre_v[u] = *(const half8_t*)(p.rows_k + ((int64_t)bg * p.k_k + i) * kD + 8 * a_l16);
+        }
     }
     // this thread's centroids (entries tid + 1024 j of the table): loaded before the barrier, used after it
     constexpr int kEnt = M * 256 / kDaThreads;

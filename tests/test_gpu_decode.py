@@ -167,6 +167,22 @@ def test_decode_time_anchor_score_and_reselection(oracle, d, N):
     print(f"re-selection near-tie disagreements: {soft}")
 
 
+@pytest.mark.parametrize("k_v", [0, 13])
+def test_decode_time_anchor_score_without_key_anchors(oracle, k_v):
+    """Scores and re-selection on a cache whose K list is empty (null list pointers): nothing of that list may be read."""
+    B, Hq, Hkv, N, d = 1, 4, 1, 700, 8
+    c = _cache_from_kv(oracle, 55, B, Hq, Hkv, N, d, 0, k_v, anchors="random")
+    k_resel = 9
+    (out, ans_k, ans_v, rk, rv), (want, ex) = _run_decode(oracle, c, antkv.Geometry(B, Hq, Hkv, d), 1 / np.sqrt(128),
+                                                          k_resel=k_resel)
+    _check_out(out, want, f"decode+AnS without K anchors, k_v={k_v}")
+    np.testing.assert_allclose(ans_v.cpu().numpy().astype(np.float64), ex["ans_v"], rtol=2e-5, atol=1e-12)
+    np.testing.assert_allclose(ans_k.cpu().numpy().astype(np.float64), ex["ans_k"], rtol=2e-5, atol=1e-12)
+    for got, score in ((rk, ex["ans_k"]), (rv, ex["ans_v"])):
+        wi, margin = oracle.topk(score, k_resel, want_margin=True)
+        check_index_sets(got.cpu().numpy(), wi, margin, "re-selection")
+
+
 def test_extreme_context_reselection(oracle):
     """Config 4: 840000-token context at 0.5 bit, decode step plus anchor re-selection of 8400 tokens."""
     w = CONFIGS["cfg4"]
