@@ -12,13 +12,15 @@
  *   antkv_topk           the selection step alone
  *   antkv_gather_rows    copy the selected FP16 rows into the anchor store
  *   antkv_decode_attn    decode attention over codes + FP16 anchors    (Sec. 2.1 Attn; Sec. 3.2 last par.)
+ *   antkv_decode_attn_static   the same with scratch inside the library, for callers that cannot allocate
  *
  * Conventions
  *   - Every pointer is a DEVICE pointer unless stated otherwise.  The caller owns all
  *     buffers; the library never allocates, frees or synchronises.  Scratch memory is
  *     a caller-provided workspace whose size comes from the *_workspace query
- *     (256-byte aligned).  Work is enqueued on `stream` (a hipStream_t passed as void*;
- *     NULL = the default stream).
+ *     (256-byte aligned); antkv_decode_attn_static alone uses an array inside the library
+ *     instead.  Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream).
  *   - Every call returns an int: ANTKV_OK or one of the error codes below.  Argument
  *     errors are detected on the host before anything is enqueued.
  *   - Tensors are dense, row-major, last index fastest, in the layouts given per call.
@@ -152,6 +154,24 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
                       const int32_t* idx_v, const void* rows_v, int64_t k_v, void* out,
                       float* ans_k, float* ans_v, int32_t* resel_idx_k, int32_t* resel_idx_v,
                       int64_t k_resel, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * antkv_decode_attn for callers that cannot allocate device memory and therefore have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation and arguments as
+ * antkv_decode_attn without the optional score / re-selection outputs and without the workspace: the kernels'
+ * scratch (per-workgroup partial results and arrival words; for 12-bit codes also the K-side table) lives in an
+ * array of ANTKV_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held until the process ends.
+ * The call allocates nothing and frees nothing.  A shape whose scratch need
+ * (antkv_decode_attn_workspace(geom, N, k_k, k_v, 0)) exceeds ANTKV_STATIC_SCRATCH_BYTES is refused with
+ * ANTKV_EWORKSPACE before anything is enqueued.  All calls on one GPU share that GPU's array: calls that
+ * overlap in time on one GPU (different streams, or this call next to another thread's) race and must be
+ * serialised by the caller; nothing in the array has to be cleared between calls.
+ */
+#define ANTKV_STATIC_SCRATCH_BYTES (8u << 20)
+int antkv_decode_attn_static(const antkv_geom* geom, const void* q, float scale, const uint8_t* codes_k,
+                             const uint8_t* codes_v, int64_t N, int64_t N_cap, const void* cb_k, const void* cb_v,
+                             const int32_t* idx_k, const void* rows_k, int64_t k_k, const int32_t* idx_v,
+                             const void* rows_v, int64_t k_v, void* out, void* stream);
 
 /*
  * Decode append with an FP16 sliding window (Sec. 3.2, last paragraph: during decoding the Anchor Score's tail

@@ -15,7 +15,7 @@ _lib = None
 EXPORTS = (
     "antkv_version", "antkv_strerror", "antkv_encode", "antkv_anchor_select_workspace", "antkv_anchor_select",
     "antkv_topk_workspace", "antkv_topk", "antkv_gather_rows", "antkv_decode_attn_workspace", "antkv_decode_attn",
-    "antkv_append_token", "antkv_prefill_attn", "antkv_kmeans_step_workspace", "antkv_kmeans_step", "antkv_profile_next_decode",
+    "antkv_decode_attn_static", "antkv_append_token", "antkv_prefill_attn", "antkv_kmeans_step_workspace", "antkv_kmeans_step", "antkv_profile_next_decode",
 )
 
 
@@ -93,6 +93,8 @@ def load_library():
         lib.antkv_decode_attn.restype = ctypes.c_int
         lib.antkv_decode_attn.argtypes = [gp, vp, f32, vp, vp, i64, i64, vp, vp, vp, vp, i64, vp, vp, i64, vp,
                                           vp, vp, vp, vp, i64, vp, sz, vp]
+        lib.antkv_decode_attn_static.restype = ctypes.c_int
+        lib.antkv_decode_attn_static.argtypes = [gp, vp, f32, vp, vp, i64, i64, vp, vp, vp, vp, i64, vp, vp, i64, vp, vp]
         lib.antkv_profile_next_decode.restype = None
         lib.antkv_profile_next_decode.argtypes = [vp, vp]
         _lib = lib
@@ -317,4 +319,31 @@ def decode_attn(geom: Geometry, q: torch.Tensor, scale: float, codes_k: torch.Te
     _check(rc, "antkv_decode_attn")
     if want_ans or k_resel > 0:
         return out, ans_k, ans_v, rk, rv
+    return out
+
+
+STATIC_SCRATCH_BYTES = 8 << 20     # ANTKV_STATIC_SCRATCH_BYTES of include/antkv.h
+
+
+def decode_attn_static(geom: Geometry, q: torch.Tensor, scale: float, codes_k: torch.Tensor, codes_v: torch.Tensor,
+                       cb_k: torch.Tensor, cb_v: torch.Tensor, idx_k: torch.Tensor | None, rows_k: torch.Tensor | None,
+                       idx_v: torch.Tensor | None, rows_v: torch.Tensor | None, out: torch.Tensor,
+                       N: int | None = None) -> torch.Tensor:
+    """antkv_decode_attn_static: decode attention with the scratch inside the library.  `out` is the caller's
+    fp16 [B,Hq,D] tensor (this wrapper allocates nothing either)."""
+    _need(q, torch.float16, "q")
+    _need(codes_k, torch.uint8, "codes_k")
+    _need(codes_v, torch.uint8, "codes_v")
+    _need(out, torch.float16, "out")
+    N_cap = codes_k.shape[2]
+    if N is None:
+        N = N_cap
+    k_k = 0 if idx_k is None else idx_k.shape[-1]
+    k_v = 0 if idx_v is None else idx_v.shape[-1]
+    g = geom.c()
+    rc = load_library().antkv_decode_attn_static(
+        ctypes.byref(g), _p(q), float(scale), _p(codes_k), _p(codes_v), N, N_cap, _p(cb_k), _p(cb_v),
+        _p(idx_k) if k_k else None, _p(rows_k) if k_k else None, k_k,
+        _p(idx_v) if k_v else None, _p(rows_v) if k_v else None, k_v, _p(out), _stream(q))
+    _check(rc, "antkv_decode_attn_static")
     return out

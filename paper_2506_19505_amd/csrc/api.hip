@@ -1,6 +1,8 @@
 // extern "C" boundary of the AnTKV library: argument validation, workspace layout, kernel launches.
 #include "common.h"
 
+#include <mutex>
+
 using namespace antkv;
 
 namespace {
@@ -50,6 +52,109 @@ DecPlan dec_plan(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, int64_t k_r
     p.off_topk = align_up(decode_workspace_bytes(g, N, k_k, k_v, want_ans));
     p.total = p.off_topk + (k_resel > 0 ? align_up(topk_workspace_bytes(2 * (int64_t)g.B * g.Hkv, N, k_resel)) : 0);
     return p;
+}
+
+int decode_attn_impl(const antkv_geom* geom, const void* q, float scale, const uint8_t* codes_k,
+                      const uint8_t* codes_v, int64_t N, int64_t N_cap, const void* cb_k, const void* cb_v,
+                      const int32_t* idx_k, const void* rows_k, int64_t k_k, const int32_t* idx_v, const void* rows_v,
+                      int64_t k_v, void* out, float* ans_k, float* ans_v, int32_t* resel_idx_k, int32_t* resel_idx_v,
+                      int64_t k_resel, void* workspace, size_t workspace_bytes, void* stream)
+{
+    Geom g;
+    int rc = check_geom(geom, g);
+    if (rc) return rc;
+    if (N < 0 || N_cap < N || k_k < 0 || k_v < 0 || k_k > N || k_v > N || k_resel < 0 || k_resel > N ||
+        N > 0x7fffffffLL)
+        return ANTKV_EINVAL;
+    const bool wide = g.C != kC;                                 // 12-bit codes
+    if (g.B == 0) return ANTKV_OK;
+    if (!q || !out || misaligned(q, 16) || misaligned(out, 16)) return ANTKV_EINVAL;
+    if (!(scale > 0.f)) return ANTKV_EINVAL;
+    if (N > 0) {
+        if (!codes_k || !codes_v || !cb_k || !cb_v) return ANTKV_EINVAL;
+        if (misaligned(codes_k, 16) || misaligned(codes_v, 16) || misaligned(cb_k, 16) || misaligned(cb_v, 16))
+            return ANTKV_EINVAL;
+        if (k_k > 0 && (!idx_k || !rows_k || misaligned(rows_k, 16))) return ANTKV_EINVAL;
+        if (k_v > 0 && (!idx_v || !rows_v || misaligned(rows_v, 16))) return ANTKV_EINVAL;
+    }
+    if ((resel_idx_k && !ans_k) || (resel_idx_v && !ans_v)) return ANTKV_EINVAL;
+    const bool want_ans = ans_k || ans_v;
+    if (want_ans && !(ans_k && ans_v)) return ANTKV_EINVAL;   // the two scores are produced together
+    if (wide) {
+        const size_t off_topk = align_up(decode12_workspace_bytes(g, N));
+        const size_t need = off_topk + (k_resel > 0 ? align_up(topk_workspace_bytes(2 * (int64_t)g.B * g.Hkv, N, k_resel)) : 0);
+        if (!workspace || misaligned(workspace, 256) || workspace_bytes < need) return ANTKV_EWORKSPACE;
+        hipStream_t st = (hipStream_t)stream;
+        DecodeArgs a;
+        a.q = (const half_t*)q; a.scale = scale; a.codes_k = codes_k; a.codes_v = codes_v; a.N = N; a.N_cap = N_cap;
+        a.cb_k = (const half_t*)cb_k; a.cb_v = (const half_t*)cb_v; a.idx_k = idx_k; a.rows_k = (const half_t*)rows_k;
+        a.k_k = k_k; a.idx_v = idx_v; a.rows_v = (const half_t*)rows_v; a.k_v = k_v; a.out = (half_t*)out;
+        a.ans_k = ans_k; a.ans_v = ans_v;
+        // with both index sets wanted, the score pass counts its scores into the selection's first histogram
+        const bool fused = N > 0 && k_resel > 0 && resel_idx_k && resel_idx_v;
+        a.topk_hist = fused ? launch_topk2_begin((int64_t)g.B * g.Hkv, N, (char*)workspace + off_topk, st) : nullptr;
+        if (launch_decode12(g, a, workspace, st) != hipSuccess) return ANTKV_ELAUNCH;
+        if (N > 0 && k_resel > 0 && (resel_idx_k || resel_idx_v)) {
+            char* w = (char*)workspace;
+            const int64_t rows = (int64_t)g.B * g.Hkv;
+            const hipError_t e =
+                (resel_idx_k && resel_idx_v)
+                    ? launch_topk2_finish(ans_k, resel_idx_k, ans_v, resel_idx_v, rows, N, k_resel, w + off_topk, st)
+                    : launch_topk(resel_idx_k ? ans_k : ans_v, rows, N, k_resel, resel_idx_k ? resel_idx_k : resel_idx_v,
+                                  w + off_topk, st);
+            if (e != hipSuccess) return ANTKV_ELAUNCH;
+        }
+        return ANTKV_OK;
+    }
+    const DecPlan dp = dec_plan(g, N, k_k, k_v, k_resel, true);
+    if (N > 0 && (!workspace || misaligned(workspace, 256) || workspace_bytes < dp.total)) return ANTKV_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    DecodeArgs a;
+    a.q = (const half_t*)q; a.scale = scale; a.codes_k = codes_k; a.codes_v = codes_v; a.N = N; a.N_cap = N_cap;
+    a.cb_k = (const half_t*)cb_k; a.cb_v = (const half_t*)cb_v; a.idx_k = idx_k; a.rows_k = (const half_t*)rows_k;
+    a.k_k = k_k; a.idx_v = idx_v; a.rows_v = (const half_t*)rows_v; a.k_v = k_v; a.out = (half_t*)out;
+    a.ans_k = ans_k; a.ans_v = ans_v;
+    // with both index sets wanted, the score pass counts its scores into the selection's first histogram
+    const bool fused = N > 0 && k_resel > 0 && resel_idx_k && resel_idx_v;
+    a.topk_hist = fused ? launch_topk2_begin((int64_t)g.B * g.Hkv, N, (char*)workspace + dp.off_topk, st) : nullptr;
+    hipError_t e = launch_decode_attn(g, a, workspace, st);
+    if (e != hipSuccess) return ANTKV_ELAUNCH;
+    if (N > 0 && k_resel > 0) {
+        char* w = (char*)workspace;
+        const int64_t rows = (int64_t)g.B * g.Hkv;
+        if (resel_idx_k && resel_idx_v) {
+            e = launch_topk2_finish(ans_k, resel_idx_k, ans_v, resel_idx_v, rows, N, k_resel, w + dp.off_topk, st);
+            if (e != hipSuccess) return ANTKV_ELAUNCH;
+        } else if (resel_idx_k || resel_idx_v) {
+            e = launch_topk(resel_idx_k ? ans_k : ans_v, rows, N, k_resel, resel_idx_k ? resel_idx_k : resel_idx_v,
+                            w + dp.off_topk, st);
+            if (e != hipSuccess) return ANTKV_ELAUNCH;
+        }
+    }
+    return ANTKV_OK;
+}
+
+
+// ---- scratch of the entry point that takes no workspace --------------------------------------------------------
+// One array per GPU, held from the moment the library is loaded on it until the process ends.  Host code never
+// uses the array's name as an address: the device address is asked for once per device and kept.
+static __device__ __align__(256) unsigned char scratch[ANTKV_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ANTKV_ELAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return ANTKV_ELAUNCH;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return ANTKV_OK;
 }
 
 }  // namespace
@@ -258,78 +363,26 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
                       int64_t k_v, void* out, float* ans_k, float* ans_v, int32_t* resel_idx_k, int32_t* resel_idx_v,
                       int64_t k_resel, void* workspace, size_t workspace_bytes, void* stream)
 {
+    return decode_attn_impl(geom, q, scale, codes_k, codes_v, N, N_cap, cb_k, cb_v, idx_k, rows_k, k_k, idx_v, rows_v, k_v,
+                            out, ans_k, ans_v, resel_idx_k, resel_idx_v, k_resel, workspace, workspace_bytes, stream);
+}
+
+int antkv_decode_attn_static(const antkv_geom* geom, const void* q, float scale, const uint8_t* codes_k,
+                             const uint8_t* codes_v, int64_t N, int64_t N_cap, const void* cb_k, const void* cb_v,
+                             const int32_t* idx_k, const void* rows_k, int64_t k_k, const int32_t* idx_v,
+                             const void* rows_v, int64_t k_v, void* out, void* stream)
+{
     Geom g;
-    int rc = check_geom(geom, g);
+    const int rc = check_geom(geom, g);
     if (rc) return rc;
-    if (N < 0 || N_cap < N || k_k < 0 || k_v < 0 || k_k > N || k_v > N || k_resel < 0 || k_resel > N ||
-        N > 0x7fffffffLL)
-        return ANTKV_EINVAL;
-    const bool wide = g.C != kC;                                 // 12-bit codes
-    if (g.B == 0) return ANTKV_OK;
-    if (!q || !out || misaligned(q, 16) || misaligned(out, 16)) return ANTKV_EINVAL;
-    if (!(scale > 0.f)) return ANTKV_EINVAL;
-    if (N > 0) {
-        if (!codes_k || !codes_v || !cb_k || !cb_v) return ANTKV_EINVAL;
-        if (misaligned(codes_k, 16) || misaligned(codes_v, 16) || misaligned(cb_k, 16) || misaligned(cb_v, 16))
-            return ANTKV_EINVAL;
-        if (k_k > 0 && (!idx_k || !rows_k || misaligned(rows_k, 16))) return ANTKV_EINVAL;
-        if (k_v > 0 && (!idx_v || !rows_v || misaligned(rows_v, 16))) return ANTKV_EINVAL;
-    }
-    if ((resel_idx_k && !ans_k) || (resel_idx_v && !ans_v)) return ANTKV_EINVAL;
-    const bool want_ans = ans_k || ans_v;
-    if (want_ans && !(ans_k && ans_v)) return ANTKV_EINVAL;   // the two scores are produced together
-    if (wide) {
-        const size_t off_topk = align_up(decode12_workspace_bytes(g, N));
-        const size_t need = off_topk + (k_resel > 0 ? align_up(topk_workspace_bytes(2 * (int64_t)g.B * g.Hkv, N, k_resel)) : 0);
-        if (!workspace || misaligned(workspace, 256) || workspace_bytes < need) return ANTKV_EWORKSPACE;
-        hipStream_t st = (hipStream_t)stream;
-        DecodeArgs a;
-        a.q = (const half_t*)q; a.scale = scale; a.codes_k = codes_k; a.codes_v = codes_v; a.N = N; a.N_cap = N_cap;
-        a.cb_k = (const half_t*)cb_k; a.cb_v = (const half_t*)cb_v; a.idx_k = idx_k; a.rows_k = (const half_t*)rows_k;
-        a.k_k = k_k; a.idx_v = idx_v; a.rows_v = (const half_t*)rows_v; a.k_v = k_v; a.out = (half_t*)out;
-        a.ans_k = ans_k; a.ans_v = ans_v;
-        // with both index sets wanted, the score pass counts its scores into the selection's first histogram
-        const bool fused = N > 0 && k_resel > 0 && resel_idx_k && resel_idx_v;
-        a.topk_hist = fused ? launch_topk2_begin((int64_t)g.B * g.Hkv, N, (char*)workspace + off_topk, st) : nullptr;
-        if (launch_decode12(g, a, workspace, st) != hipSuccess) return ANTKV_ELAUNCH;
-        if (N > 0 && k_resel > 0 && (resel_idx_k || resel_idx_v)) {
-            char* w = (char*)workspace;
-            const int64_t rows = (int64_t)g.B * g.Hkv;
-            const hipError_t e =
-                (resel_idx_k && resel_idx_v)
-                    ? launch_topk2_finish(ans_k, resel_idx_k, ans_v, resel_idx_v, rows, N, k_resel, w + off_topk, st)
-                    : launch_topk(resel_idx_k ? ans_k : ans_v, rows, N, k_resel, resel_idx_k ? resel_idx_k : resel_idx_v,
-                                  w + off_topk, st);
-            if (e != hipSuccess) return ANTKV_ELAUNCH;
-        }
-        return ANTKV_OK;
-    }
-    const DecPlan dp = dec_plan(g, N, k_k, k_v, k_resel, true);
-    if (N > 0 && (!workspace || misaligned(workspace, 256) || workspace_bytes < dp.total)) return ANTKV_EWORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
-    DecodeArgs a;
-    a.q = (const half_t*)q; a.scale = scale; a.codes_k = codes_k; a.codes_v = codes_v; a.N = N; a.N_cap = N_cap;
-    a.cb_k = (const half_t*)cb_k; a.cb_v = (const half_t*)cb_v; a.idx_k = idx_k; a.rows_k = (const half_t*)rows_k;
-    a.k_k = k_k; a.idx_v = idx_v; a.rows_v = (const half_t*)rows_v; a.k_v = k_v; a.out = (half_t*)out;
-    a.ans_k = ans_k; a.ans_v = ans_v;
-    // with both index sets wanted, the score pass counts its scores into the selection's first histogram
-    const bool fused = N > 0 && k_resel > 0 && resel_idx_k && resel_idx_v;
-    a.topk_hist = fused ? launch_topk2_begin((int64_t)g.B * g.Hkv, N, (char*)workspace + dp.off_topk, st) : nullptr;
-    hipError_t e = launch_decode_attn(g, a, workspace, st);
-    if (e != hipSuccess) return ANTKV_ELAUNCH;
-    if (N > 0 && k_resel > 0) {
-        char* w = (char*)workspace;
-        const int64_t rows = (int64_t)g.B * g.Hkv;
-        if (resel_idx_k && resel_idx_v) {
-            e = launch_topk2_finish(ans_k, resel_idx_k, ans_v, resel_idx_v, rows, N, k_resel, w + dp.off_topk, st);
-            if (e != hipSuccess) return ANTKV_ELAUNCH;
-        } else if (resel_idx_k || resel_idx_v) {
-            e = launch_topk(resel_idx_k ? ans_k : ans_v, rows, N, k_resel, resel_idx_k ? resel_idx_k : resel_idx_v,
-                            w + dp.off_topk, st);
-            if (e != hipSuccess) return ANTKV_ELAUNCH;
-        }
-    }
-    return ANTKV_OK;
+    if (N < 0 || k_k < 0 || k_v < 0) return ANTKV_EINVAL;
+    const size_t need = antkv_decode_attn_workspace(geom, N, k_k, k_v, 0);
+    if (need > (size_t)ANTKV_STATIC_SCRATCH_BYTES) return ANTKV_EWORKSPACE;   // shape beyond the built-in scratch
+    void* ws = nullptr;
+    const int rs = static_scratch(&ws);
+    if (rs) return rs;
+    return decode_attn_impl(geom, q, scale, codes_k, codes_v, N, N_cap, cb_k, cb_v, idx_k, rows_k, k_k, idx_v, rows_v, k_v,
+                            out, nullptr, nullptr, nullptr, nullptr, 0, ws, (size_t)ANTKV_STATIC_SCRATCH_BYTES, stream);
 }
 
 }  // extern "C"

@@ -6,7 +6,7 @@ import re
 import pytest
 
 import paper_2506_19505_amd as antkv
-from paper_2506_19505_amd.binding import EXPORTS, _Geom
+from paper_2506_19505_amd.binding import EXPORTS, STATIC_SCRATCH_BYTES, _Geom
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE = 0, 1, 2, 3
@@ -108,3 +108,15 @@ def test_binding_refuses_host_tensors():
     geom = antkv.Geometry(1, 4, 1, 8)
     with pytest.raises(ValueError):
         antkv.encode(geom, torch.zeros(1, 1, 4, 128, dtype=torch.float16), torch.zeros(1, 16, 256, 8, dtype=torch.float16))
+
+
+def test_static_scratch_refuses_oversized_shapes(lib):
+    """A shape whose scratch need exceeds the built-in array is an error before anything is enqueued."""
+    geom = antkv.Geometry(64, 2048, 512, 8)          # 64 x 512 (sequence, KV head) pairs: partials beyond 8 MiB
+    g = geom.c()
+    need = lib.antkv_decode_attn_workspace(ctypes.byref(g), 4096, 0, 0, 0)
+    assert need > STATIC_SCRATCH_BYTES
+    fake = ctypes.c_void_p(4096)
+    rc = lib.antkv_decode_attn_static(ctypes.byref(g), fake, 0.1, fake, fake, 4096, 4096, fake, fake, None, None, 0,
+                                      None, None, 0, fake, None)
+    assert rc == 3                                     # ANTKV_EWORKSPACE
