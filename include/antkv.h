@@ -235,14 +235,6 @@ int antkv_kmeans_step(const antkv_geom* geom, const void* x, const float* w, int
                       void* codebook_out, uint8_t* codes, float* wsum, double* objective, void* workspace,
                       size_t workspace_bytes, void* stream);
 
-/*
- * Measurement aid, not part of the method: the next antkv_decode_attn call made from this host thread
- * records `start_event` right before and `stop_event` right after its dominant kernel (the one that
- * streams the codes) on that call's stream.  Both are hipEvent_t handles (host handles, created by the
- * caller with timing enabled); they are used once and then forgotten.  Pass NULLs to clear.
- */
-void antkv_profile_next_decode(void* start_event, void* stop_event);
-
 #ifdef __cplusplus
 }
 #endif

@@ -18,7 +18,6 @@ from .binding import (
     gather_rows,
     lib_path,
     load_library,
-    profile_next_decode,
     topk,
     version,
 )
@@ -37,7 +36,6 @@ __all__ = [
     "gather_rows",
     "lib_path",
     "load_library",
-    "profile_next_decode",
     "topk",
     "version",
 ]

@@ -15,7 +15,7 @@ _lib = None
 EXPORTS = (
     "antkv_version", "antkv_strerror", "antkv_encode", "antkv_anchor_select_workspace", "antkv_anchor_select",
     "antkv_topk_workspace", "antkv_topk", "antkv_gather_rows", "antkv_decode_attn_workspace", "antkv_decode_attn",
-    "antkv_decode_attn_static", "antkv_append_token", "antkv_prefill_attn", "antkv_kmeans_step_workspace", "antkv_kmeans_step", "antkv_profile_next_decode",
+    "antkv_decode_attn_static", "antkv_append_token", "antkv_prefill_attn", "antkv_kmeans_step_workspace", "antkv_kmeans_step",
 )
 
 
@@ -95,8 +95,6 @@ def load_library():
                                           vp, vp, vp, vp, i64, vp, sz, vp]
         lib.antkv_decode_attn_static.restype = ctypes.c_int
         lib.antkv_decode_attn_static.argtypes = [gp, vp, f32, vp, vp, i64, i64, vp, vp, vp, vp, i64, vp, vp, i64, vp, vp]
-        lib.antkv_profile_next_decode.restype = None
-        lib.antkv_profile_next_decode.argtypes = [vp, vp]
         _lib = lib
     return _lib
 
@@ -240,12 +238,6 @@ def gather_rows(geom: Geometry, x: torch.Tensor, idx: torch.Tensor, out: torch.T
     rc = load_library().antkv_gather_rows(ctypes.byref(g), _p(x), N, _p(idx), k, _p(rows), _stream(x))
     _check(rc, "antkv_gather_rows")
     return rows
-
-
-def profile_next_decode(start: "torch.cuda.Event | None", stop: "torch.cuda.Event | None") -> None:
-    """antkv_profile_next_decode: record the two (already created) timing events around the next decode kernel."""
-    h = lambda e: None if e is None else ctypes.c_void_p(e.cuda_event)
-    load_library().antkv_profile_next_decode(h(start), h(stop))
 
 
 def append_token(geom: Geometry, k_new: torch.Tensor, v_new: torch.Tensor, N: int, W: int, cb_k: torch.Tensor,

@@ -342,11 +342,6 @@ int antkv_append_token(const antkv_geom* geom, const void* k_new, const void* v_
     return e == hipSuccess ? ANTKV_OK : ANTKV_ELAUNCH;
 }
 
-void antkv_profile_next_decode(void* start_event, void* stop_event)
-{
-    decode_profile_next((hipEvent_t)start_event, (hipEvent_t)stop_event);
-}
-
 size_t antkv_decode_attn_workspace(const antkv_geom* geom, int64_t N, int64_t k_k, int64_t k_v, int64_t k_resel)
 {
     Geom g;

@@ -137,7 +137,6 @@ struct DecodeArgs {
     uint32_t* topk_hist;   // optional: first-level top-k histograms that the score pass fills (see launch_topk2_begin)
 };
 int decode_num_splits(const Geom& g, int64_t N);
-void decode_profile_next(hipEvent_t start, hipEvent_t stop);
 size_t decode_workspace_bytes(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans);
 hipError_t launch_decode_attn(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st);
 size_t decode12_workspace_bytes(const Geom& g, int64_t N);

@@ -19,14 +19,20 @@
 //            wave's staging area for the transposed reads.
 //  stream    waves pull 64-token tiles from a shared counter, code loads running one tile ahead:
 //      K side  one lane per token: 16-byte coalesced code loads, one 8-byte LUT gather per sub-space
-//              serves the group's four query heads; an int8 MFMA with a constant block-diagonal operand
-//              sums the entries exactly (C row r of a lane = its own token, head r);
+//              serves the group's four query heads.  The gathered entries are the row operand of an int8 MFMA
+//              whose column operand is a constant block-diagonal matrix: it sums the entries exactly and, at
+//              the same time, transposes the result: lane (4 c + h, k-group g) ends up with head h's scores of
+//              the four tokens 16 c + 4 g + 0..3, which is exactly where the sparse operand of P.V wants them;
 //      softmax base-2 online softmax against a lazily updated reference maximum (the wave only pays
-//              the cross-lane reduction when some score exceeds the reference);
-//      V side  the weights (fp16, zero-extended) and the V code words go through the wave's LDS staging
-//              area; V centroids are fetched with ds_read_b64_tr_b16, whose lane transposition yields the
-//              dense MFMA operand; the 2:4-sparse MFMA accumulates P.V in fp32 with all 16 rows in use
-//              (rows = slab class x head, see the comment at sm_idx).
+//              the cross-lane reduction when some score exceeds the reference); the four fp16 weights of a
+//              lane, zero-extended, are the P.V operand as they stand: no trip through LDS;
+//      V side  P.V runs on the 2:4-sparse MFMA, all 16 rows in use (rows = slab class x head, see the comment at
+//              sm_idx).  The four positions of a group of the k axis are four different tokens, each with the
+//              16-channel slab (class + rotation) mod 4 of one half of the row, and eight MFMAs per tile (four
+//              rotations x two halves, an accumulator each) take every token through all eight slabs.  The V
+//              code bytes reach the lanes that need them through the wave's staging area, rotated by the
+//              token's class so that the reader's byte position is a constant; V centroids are fetched with
+//              ds_read_b64_tr_b16, whose lane transposition yields the dense MFMA operand.
 //      Tokens that have an FP16 anchor row (for K or for V) are masked out of the stream.
 //
 // The workgroup merges its waves and writes one partial (reference max, sum, accumulator) per query head;
@@ -40,19 +46,14 @@ namespace antkv {
 
 namespace {
 
-#ifndef ANTKV_DA_WAVES
-#define ANTKV_DA_WAVES 16
-#endif
-constexpr int kDaWaves = ANTKV_DA_WAVES;
+constexpr int kDaWaves = 16;
 constexpr int kDaThreads = kDaWaves * 64;
 constexpr int kNH = 4;                 // query-head slots per workgroup (group size G <= 4)
 constexpr float kPShift = 8.0f;        // P is scaled by 2^8 so that small weights stay normal in fp16
 constexpr float kLutMax = 16256.0f;    // largest table magnitude: 127 * 128, so that both bytes of an entry fit int8
 constexpr int kPStride = 72;           // fp16 elements between the heads of a wave's P tile (64 + pad against bank conflicts)
-constexpr int kPStride32 = 68;         // dwords between the heads of the stream's P tile (zero-extended fp16 weights)
-// per-wave staging.  Anchor tiles: fp16 P tile, then 1 KB of V rows.  Stream: dword P tile, then the V code words
-// (two padded rows of 68 dwords, or four of 36).
-constexpr int kStgBytes = 4 * kPStride32 * 4 + 4 * 36 * 4;
+// per-wave staging.  Anchor tiles: fp16 P tile, then 1 KB of V rows.  Stream: the V code bytes of a tile (up to 1 KB).
+constexpr int kStgBytes = 1664;
 static_assert(4 * kPStride * 2 + 1024 <= kStgBytes && kStgBytes % 16 == 0, "anchor staging fits the per-wave area");
 constexpr float kEmptyRef = -1.0e4f;   // softmax reference before any token was seen: finite, below every real score,
                                        // and far above the masked score kNegBig so that exp2(masked - ref) is 0
@@ -209,14 +210,7 @@ struct DaParams {
     int Hq, Hkv, G;
     int S;                      // workgroups (token ranges) per (b, g)
     int64_t chunk;              // tokens per range (multiple of 64)
-    unsigned long long* trace;  // ANTKV_DA_TRACE builds: [grid][4] wall-clock stamps (100 MHz), else unused
 };
-
-#ifdef ANTKV_DA_TRACE
-#define DA_STAMP(i) do { if (threadIdx.x == 0) p.trace[(size_t)blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define DA_STAMP(i) do { } while (0)
-#endif
 
 // LDS layout (bytes); the final merge re-uses the table area.  The two tables sit at multiples of 64 KB so
 // that a gather address is (table base | code << 8 | byte inside the code's 256-byte row).
@@ -226,7 +220,7 @@ struct Lds {
     static constexpr int lut = 0;                                  // [256 codes][32 slots][4 x (lo, hi) bytes] = 64 KB
     static constexpr int cbv = lut + 65536;                        // [256 codes][M][DSUB] fp16 = 64 KB (a 256-byte row per code)
     static constexpr int pst = cbv + 65536;                        // [waves] staging (P tile + V code words / anchor V rows)
-    static constexpr int mrg = 0;                                  // merge: [waves][4][128] fp32 (2 KB per wave)
+    static constexpr int mrg = 0;                                  // merge: [waves][4 classes][128 channels][4 heads] fp32 = 128 KB (the two tables are free by then)
     static constexpr int qh = pst + kDaWaves * kStgBytes;          // [4][128] fp16 (MFMA operand source)
     static constexpr int red = qh + 1024;                          // [waves][8] fp32 + 16 ints
     static constexpr int mask = red + kDaWaves * 32 + 64;          // bitmap over the token range
@@ -235,19 +229,16 @@ struct Lds {
     static_assert(total <= 163840, "LDS budget of one CU");
 };
 
-// Merge the waves' (m_ref, l, acc) into one partial and write it.  acc is in the C layout of the class-structured
-// sparse MFMA: register h of acc[a] in lane (cls = lane / 16, n = lane % 16) is head h, channel 16 (4a + cls) + n.
+// Merge the waves' (m_ref, l, acc) into one partial and write it.  acc[a][rho] is in the C layout of the class-structured
+// sparse MFMA: register h of a lane (cls = lane / 16, n = lane % 16) is head h, channel 16 (4 a + (cls + rho) % 4) + n,
+// summed over the tokens of class cls only, so the four classes (and the waves) still have to be added up.
 template <int DSUB>
-__device__ void wg_merge_and_store(char* smem, float (&m_ref)[kNH], float (&l_sum)[kNH], float4_t (&acc)[2],
-                                   float* __restrict__ part_bg, int slot, int slots, int nheads,
-                                   unsigned long long* trace_slot = nullptr)
+__device__ void wg_merge_and_store(char* smem, float (&m_ref)[kNH], float (&l_sum)[kNH], float4_t (&acc)[2][4],
+                                   float* __restrict__ part_bg, int slot, int slots, int nheads)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float* s_red = (float*)(smem + Lds<DSUB>::red);
-    __syncthreads();   // everyone is done with the staging area
-#ifdef ANTKV_DA_TRACE
-    if (threadIdx.x == 0 && trace_slot) *trace_slot = wall_clock64();
-#endif
+    __syncthreads();   // everyone is done with the tables and the staging area
     if (lane == 0) {
 #pragma unroll
         for (int h = 0; h < kNH; ++h) { s_red[wave * 8 + h] = m_ref[h]; s_red[wave * 8 + 4 + h] = l_sum[h]; }
@@ -264,18 +255,29 @@ __device__ void wg_merge_and_store(char* smem, float (&m_ref)[kNH], float (&l_su
 #pragma unroll
         for (int h = 0; h < kNH; ++h) { m_all[h] = lane_bcast(m_r, 16 * h); l_all[h] = lane_bcast(l_r, 16 * h); }
     }
-    float* s_mrg = (float*)(smem + Lds<DSUB>::mrg);
+    float4_t f;
+#pragma unroll
+    for (int h = 0; h < kNH; ++h) f[h] = fast_exp2(m_ref[h] - m_all[h]);
+    static_assert(kDaWaves * 4 * kD * 16 <= 131072, "the merge area is the two tables");
+    float4_t* s_mrg = (float4_t*)(smem + Lds<DSUB>::mrg);            // [wave][class][channel] x 4 heads
+    const int cls = lane >> 4, n = lane & 15;
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int r = 0; r < kNH; ++r)
-            s_mrg[(wave * kNH + r) * kD + 16 * (4 * a + (lane >> 4)) + (lane & 15)] = acc[a][r] * fast_exp2(m_ref[r] - m_all[r]);
+        for (int rho = 0; rho < 4; ++rho)
+            s_mrg[(wave * 4 + cls) * kD + 16 * (4 * a + ((cls + rho) & 3)) + n] = acc[a][rho] * f;
     __syncthreads();
     if (tid < kNH * kD) {
-        const int h = tid >> 7, dim = tid & 127;
+        const int h = tid & 3, dim = tid >> 2;                   // consecutive threads read consecutive dwords
+        const float* src = (const float*)s_mrg + dim * 4 + h;
+        float s4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+        for (int w = 0; w < kDaWaves * 4; w += 4) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) s4[u] += src[(w + u) * kD * 4];
+        }
         if (h < nheads) {
-            float s = 0.f;
-            for (int w = 0; w < kDaWaves; ++w) s += s_mrg[(w * kNH + h) * kD + dim];
+            const float s = (s4[0] + s4[1]) + (s4[2] + s4[3]);
             float* dst = part_bg + ((int64_t)h * slots + slot) * (kD + 2);
             // Device-scope stores: they write through this die's L2, so the merging workgroup (possibly
             // on another die) can read them without any cache write-back.
@@ -316,8 +318,6 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     const half_t* cbv = p.cb_v + (size_t)g * 32768;
     const int64_t t0 = (int64_t)sp * p.chunk;
     const int64_t t1 = (t0 + p.chunk < p.N) ? t0 + p.chunk : p.N;
-
-    DA_STAMP(0);
     // Arrival word of this (b, g): (launch tag << 32 | arrivals).  A word left by an earlier launch (another tag,
     // or this tag with all S arrivals when a captured launch is replayed) is replaced by (tag, 0) now, by
     // whichever workgroup gets there first, so that the arrival at the end is a single fetch-add.  Launches
@@ -407,7 +407,6 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         for (int i = tid; i < L::mask_words; i += kDaThreads) s_mask[i] = 0u;
         if (tid == 0) { s_misc[8] = 0; s_misc[9] = 0; }          // next stream tile, next anchor tile of this workgroup
         __syncthreads();
-        DA_STAMP(7);
         if (tid == 0 && ((unsigned int)(done_seen >> 32) != p.tag || (unsigned int)done_seen >= (unsigned int)p.S))
             __hip_atomic_compare_exchange_strong(&p.done[bg], &done_seen, (unsigned long long)p.tag << 32, __ATOMIC_RELAXED,
                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -423,6 +422,11 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                     if (scan_val[w2][i] >= 0 && rel < range_len) atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
                 }
             }
+        // positions between the end of the range and the end of its last tile count as anchored: the stream skips them
+        if (tid < 64) {
+            const uint32_t rel = ((range_len - 1u) & ~63u) + (uint32_t)tid;
+            if (rel >= range_len) atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
+        }
         if (!scan_k) {
             for (int i = s_misc[0] + tid; i < s_misc[1]; i += kDaThreads) {
                 const int rel = idx_k[i] - (int)t0;
@@ -465,7 +469,6 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             if (lane == 0) s_red[wave * 8 + h] = wm;
         }
         __syncthreads();
-        DA_STAMP(3);
         float inv_q[kNH];
         {
             const int hh = lane >> 4, ws = lane & 15;
@@ -509,7 +512,6 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                     s_lut[l_code * 32 + m + M * ((rep + (lane >> 2)) & (REPS - 1))] = e;
             }
         }
-        DA_STAMP(4);
         // the V table is not needed before the first P.V: its loads had the whole table build to land
         {
             uint4_t* dst = (uint4_t*)(smem + L::cbv);
@@ -518,23 +520,33 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         }
     }
     __syncthreads();
-    DA_STAMP(1);
 
-    float m_ref[kNH], l_lane[kNH];
-    float4_t acc[2];
+    // m_ref: reference maximum per head (the same in every lane).  acc[a][rho]: see sm_idx below.
+    float m_ref[kNH];
+    float4_t acc[2][4];
 #pragma unroll
-    for (int h = 0; h < kNH; ++h) { m_ref[h] = kEmptyRef; l_lane[h] = 0.f; }
-    acc[0] = acc[1] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int h = 0; h < kNH; ++h) m_ref[h] = kEmptyRef;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int rho = 0; rho < 4; ++rho) acc[a][rho] = float4_t{0.f, 0.f, 0.f, 0.f};
+    float l_own = 0.f;                                            // sum of weights, head lane % 4, this lane's share
     half_t* s_p = (half_t*)(smem + L::pst + wave * kStgBytes);    // this wave's P tile, [4][kPStride] fp16
     uint32_t* s_cw = (uint32_t*)(s_p + 4 * kPStride);             // this wave's V code words, 512 bytes
 
-    // P.V runs on the 2:4-sparse MFMA (16x16x64 f16).  Its 64 k positions are (token, channel slab) pairs; the
-    // position inside each group of four is the slab's class, and row 4 cls + h of the sparse operand keeps,
-    // in every group, only the position of its own class: the softmax weight of head h for that group's
-    // token.  Output rows (cls, h) therefore accumulate slab 4a + cls of head h, all 16 rows carry useful
-    // work, and the compressed operand is just the zero-extended fp16 weights (the index register, a per-lane
-    // constant, says where they sit).  Operand geometry: compressed dword p of a lane in k-group ga pairs with
-    // the dense operand's k-group 2 (ga % 2) + p / 2, elements 4 (2 (ga / 2) + p % 2) .. + 3.
+    // P.V runs on the 2:4-sparse MFMA (16x16x64 f16).  Its 64 k positions form 16 groups of four; the position
+    // inside a group is the class, and row 4 cls + h of the sparse operand keeps, in every group, only the
+    // position of its own class: a softmax weight of head h.  All 16 rows carry useful work, and the compressed
+    // operand is just four zero-extended fp16 weights per lane (the index register, a per-lane constant, says
+    // where they sit).  What a position means differs between the two users:
+    //   anchor tiles  the four positions of a group are the four 16-channel slabs 4 a + cls of ONE item; output row
+    //                 (cls, h) of MFMA a accumulates slab 4 a + cls;
+    //   stream        the four positions of a group are FOUR tokens (one per class), position cls carrying slab
+    //                 4 a + (cls + rho) % 4 of its token; MFMA (a, rho) accumulates into acc[a][rho], whose row
+    //                 (cls, h) is therefore slab 4 a + (cls + rho) % 4 summed over the tokens of class cls.
+    // With rho = 0 the two meanings of a row agree, so anchor tiles add into acc[a][0].
+    // Operand geometry: compressed dword p of a lane in k-group ga pairs with the dense operand's k-group
+    // 2 (ga % 2) + p / 2, elements 4 (2 (ga / 2) + p % 2) .. + 3.
     const int sm_idx = (int)(0x1111u * (uint32_t)(tj | ((tj ^ 1) << 2)));
     // P-tile slot of the (token, head) weights so that the four weights a lane needs are contiguous:
     // the item in dense k-group gb, element quad e4 of sparse MFMA i -> slot 16 i + 4 ga + p
@@ -559,6 +571,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         while (anchor_waves < kDaWaves && 5 * anchor_waves < tiles_wg) anchor_waves <<= 1;
     }
     if (n_atiles > 0 && (wave & (kDaWaves / anchor_waves - 1)) == 0) {
+        float l_lane[kNH] = {0.f, 0.f, 0.f, 0.f};                        // per-lane shares of the weight sums, per head
         const half_t* s_qh = (const half_t*)(smem + L::qh);               // Q as MFMA A operand: row = head
         half_t* s_vrows = (half_t*)s_cw;                                  // [8 items][64 channels] fp16
         int* s_win = (int*)s_cw;                                          // 64 ints in the code-word area
@@ -697,8 +710,8 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 const float m_new = fmaxf(m_ref[h], m_tile - kPShift);
                 const float alpha = fast_exp2(m_ref[h] - m_new);
                 l_lane[h] *= alpha;
-                acc[0][h] *= alpha;
-                acc[1][h] *= alpha;
+                acc[0][0][h] *= alpha;
+                acc[1][0][h] *= alpha;
                 m_ref[h] = m_new;
             }
 #pragma unroll
@@ -730,31 +743,25 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                     }
                     const half16_t bop = {vb[0][0], vb[0][1], vb[0][2], vb[0][3], vb[1][0], vb[1][1], vb[1][2], vb[1][3],
                                           vb[2][0], vb[2][1], vb[2][2], vb[2][3], vb[3][0], vb[3][1], vb[3][2], vb[3][3]};
-                    acc[a] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(pa, bop, acc[a], sm_idx, 0, 0);
+                    acc[a][0] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(pa, bop, acc[a][0], sm_idx, 0, 0);
                 }
             }
         }
+        // hand the weight sums over in the stream's form: head lane % 4 in each lane (here: all of it in lanes 0..3)
+        float tot = 0.f;
+#pragma unroll
+        for (int h = 0; h < kNH; ++h) {
+            const float t = wave_sum(l_lane[h]);
+            tot = (lane == h) ? t : tot;
+        }
+        l_own = tot;
     }
 
     // ================================================================================== stream
     {
-        // lane -> token position inside a 64-token tile: the identity.  In the P.V geometry the token is item
-        // 16 gb + y of the tile, handled by dense k-group gb = lane / 16.
-        const int pos = lane;
-        const int pslot = p_slot(tj, kgrp, tq);
-        // V gather address = table base | code << 8 | (32 cls + 8 q), plus 128 a as an immediate: one byte permute
-        // of the staged code word (byte v_byte) and a per-lane constant
-        static_assert((L::cbv & 0xffff) == 0, "the V table base must be a multiple of 64 KB");
-        const uint32_t v_const = (uint32_t)(32 * tj + 8 * tq) | (((L::cbv + (uint32_t)(uintptr_t)lsm) >> 16) << 16);
-        const uint32_t v_byte = (DSUB == 8) ? (uint32_t)(2 * (tj & 1) + (tq >> 1)) : (DSUB == 16 ? (uint32_t)tj : (uint32_t)tq);
-        const uint32_t v_sel = 0x0c020000u | ((4u + v_byte) << 8);
-        // V code words are staged per step: DW dwords of TOKS tokens, word-major ([DW][TOKS])
-        constexpr int NSTEP = (DSUB == 16) ? 1 : (DSUB == 8 ? 2 : 4);
-        constexpr int DW = (DSUB == 4) ? 4 : 2;
-        constexpr int TOKS = (DSUB == 4) ? 32 : 64;
-        constexpr int CWROW = TOKS + 4;                    // padded row: rows read together fall on different banks
-        static_assert(DW * CWROW * 4 <= kStgBytes - 4 * kPStride32 * 4, "code-word staging area");
-        const int stok = (DSUB == 4) ? 8 * kgrp + (lane & 7) : lane;                    // where this lane's token is staged
+        // Lane roles.  Code loads and the K side: lane L of the wave handles token L of the tile; the token's class
+        // is c = L / 16 and its rank r = L % 16.  The int8 MFMA leaves lane (4 c + h, k-group g) with head h's
+        // scores of tokens (c, 4 g + i), i = 0..3: from there on a lane works for one head (tq) and one class (tj).
         // K gather: this lane visits sub-space (step XOR xr) mod M at every step and reads slot (step XOR xr)
         const uint32_t xr = lane & 31;
         const uint32_t kr = xr & (M - 1);                            // XOR applied to the code byte index
@@ -768,9 +775,11 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
 #pragma unroll
             for (int j = 0; j < 4; ++j) kc[i] |= ((xr ^ (uint32_t)(4 * i + j)) << 3) << (8 * j);
         }
+        // constant operand of the int8 MFMA: column 4 g + h takes, from k-group g only, the (lo, hi) bytes of head h
+        // with the weights (1, -128)
         int4_t k_wgt;
         {
-            const int row_blk = (lane & 15) >> 2, row_h = lane & 3;
+            const int col_blk = (lane & 15) >> 2, col_h = lane & 3;
 #pragma unroll
             for (int dw = 0; dw < 4; ++dw) {
                 uint32_t wv = 0;
@@ -778,11 +787,51 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 for (int j = 0; j < 4; ++j) {
                     const int i = 4 * dw + j;                              // byte of the 16-byte operand
                     const uint32_t wt = (i & 1) ? 0x80u : 0x01u;           // -128 on hi bytes, 1 on lo bytes
-                    if (kgrp == row_blk && ((i & 7) >> 1) == row_h) wv |= wt << (8 * j);
+                    if (kgrp == col_blk && ((i & 7) >> 1) == col_h) wv |= wt << (8 * j);
                 }
                 k_wgt[dw] = (int)wv;
             }
         }
+        // V gather address = table base | code << 8 | byte offset of the 8-byte piece inside the code's row, the piece
+        // being chunk tq of slab 4 a + (tj + rho) % 4 (128 a goes into the instruction's immediate): one byte permute
+        // of a staged code dword and a per-lane constant
+        static_assert((L::cbv & 0xffff) == 0, "the V table base must be a multiple of 64 KB");
+        const uint32_t lds0 = (uint32_t)(uintptr_t)lsm;
+        uint32_t v_const[4];
+#pragma unroll
+        for (int rho = 0; rho < 4; ++rho)
+            v_const[rho] = (uint32_t)(32 * ((tj + rho) & 3) + 8 * tq) | (((L::cbv + lds0) >> 16) << 16);
+        // The writer (lane = token) rotates its code bytes by its class, so that the byte of slab (c + rho) % 4 sits
+        // at the place of slab rho: the reader's byte position then depends on rho (and its chunk) only.
+        //   d = 8:  per half (8 bytes) the byte pairs rotate; byte of (rho, chunk) = dword rho / 2, byte 2 (rho % 2) + tq / 2
+        //   d = 16: per half (4 bytes) the bytes rotate;      byte of rho          = byte rho of dword a
+        //   d = 4:  per half (16 bytes) the dwords rotate;    byte of (rho, chunk) = dword rho, byte tq
+        uint32_t v_sel[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint32_t byte = (DSUB == 8) ? (uint32_t)(2 * u + (tq >> 1)) : (uint32_t)tq;
+            v_sel[u] = 0x0c020000u | ((4u + byte) << 8);
+        }
+        uint32_t rot_lo = 0, rot_hi = 0;                             // d = 8: byte selectors of the rotated half
+        if constexpr (DSUB == 8) {
+#pragma unroll
+            for (int bb = 0; bb < 4; ++bb) {
+                rot_lo |= (uint32_t)(2 * ((kgrp + (bb >> 1)) & 3) + (bb & 1)) << (8 * bb);
+                rot_hi |= (uint32_t)(2 * ((kgrp + 2 + (bb >> 1)) & 3) + (bb & 1)) << (8 * bb);
+            }
+        }
+        // staging: token (c, r) lives in unit 16 c + (r XOR 4 c) (16-byte units, 8-byte for d = 16): writes of a class
+        // and reads of a rank both spread over all banks
+        constexpr int SU = (DSUB == 16) ? 8 : 16;
+        const uint32_t stg0 = lds0 + (uint32_t)(L::pst + wave * kStgBytes);
+        const uint32_t stg_w = stg0 + (uint32_t)SU * (uint32_t)(16 * kgrp + ((lane & 15) ^ (4 * kgrp)));
+        // reader (k-group kgrp, class tj): element quad e4 holds the token of rank 8 (e4 / 2) + 4 (kgrp / 2) + 2 (kgrp % 2) + e4 % 2
+        const uint32_t rb = (uint32_t)((4 * (kgrp >> 1) + 2 * (kgrp & 1)) ^ (4 * tj));
+        const uint32_t stg_r0 = stg0 + (uint32_t)SU * (uint32_t)(16 * tj + rb);          // e4 = 0 (and 1 at + SU)
+        const uint32_t stg_r1 = stg0 + (uint32_t)SU * (uint32_t)(16 * tj + (rb ^ 8));    // e4 = 2 (and 3 at + SU)
+        // anchored-token bits of this lane's four tokens: bits 16 tj + 4 kgrp + i of the tile's 64-bit mask
+        const uint32_t mask_dw = (uint32_t)(tj >> 1);
+        const uint32_t mask_sh = (uint32_t)(16 * (tj & 1) + 4 * kgrp);
 
         const int64_t n_tiles = (t1 - t0 + 63) >> 6;
         auto grab_tile = [&]() -> int64_t {
@@ -792,8 +841,8 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         };
         // code loads run one tile ahead of their use: HBM latency hides behind the previous tile's work
         auto load_codes = [&](int64_t tile, uint32_t (&kw_)[CW], uint32_t (&vw_)[CW]) {
-            const int64_t tok_ = t0 + tile * 64 + pos;
-            const int64_t ltok = (tok_ < t1) ? tok_ : (p.N - 1);
+            const int64_t tok_ = t0 + tile * 64 + lane;
+            const int64_t ltok = (tok_ < p.N) ? tok_ : (p.N - 1);        // tokens past the range are masked, not skipped
             if (CW == 2) {
                 const uint2_t a = *(const uint2_t*)(ck + ltok * M), c = *(const uint2_t*)(cv + ltok * M);
                 kw_[0] = a[0]; kw_[1] = a[1]; vw_[0] = c[0]; vw_[1] = c[1];
@@ -806,24 +855,38 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 }
             }
         };
-        uint32_t* s_p32 = (uint32_t*)s_p;                          // stream P tile: the sparse operand's dwords, ready-made
-        uint32_t* s_cws = s_p32 + 4 * kPStride32;                  // stream code words
-        const uint32_t* s_cws_r = s_cws + ((DSUB == 8) ? (tj >> 1) : (DSUB == 4 ? tj : 0)) * CWROW + (TOKS / 4) * kgrp;
-        const uint32_t* s_pa_r = s_p32 + (lane & 3) * kPStride32 + 4 * kgrp;
-        float lut_q[kNH];                                          // table quantum per head
+        // this lane's head: table quantum and running reference
+        float lut_q = ((const float*)s_misc)[12], neg_m = -m_ref[0];
 #pragma unroll
-        for (int h = 0; h < kNH; ++h) lut_q[h] = ((const float*)s_misc)[12 + h];
-        float neg_m[kNH];                                          // -m_ref, the addend of the exponent
-#pragma unroll
-        for (int h = 0; h < kNH; ++h) neg_m[h] = -m_ref[h];
+        for (int h = 1; h < kNH; ++h) {
+            lut_q = (tq == h) ? ((const float*)s_misc)[12 + h] : lut_q;
+            neg_m = (tq == h) ? -m_ref[h] : neg_m;
+        }
 
         auto do_tile = [&](int64_t tile, const uint32_t (&kw_in)[CW], const uint32_t (&vw)[CW]) {
-            const int64_t tok = t0 + tile * 64 + pos;
-            const int rel = (int)(tok - t0);
-            const uint32_t mbit = (s_mask[(rel >> 5) & (L::mask_words - 1)] >> (rel & 31)) & 1u;
-            // tokens that are anchored or past the end of the range get weight zero; their table gathers still
-            // run (no divergent branch around them)
-            const bool masked = (tok >= t1) || (mbit != 0u);
+            // ---- V code bytes into the staging area (first round; d = 4 stages its second half later)
+            if constexpr (DSUB == 8) {
+                uint4_t w4;
+                w4[0] = __builtin_amdgcn_perm(vw[1], vw[0], rot_lo); w4[1] = __builtin_amdgcn_perm(vw[1], vw[0], rot_hi);
+                w4[2] = __builtin_amdgcn_perm(vw[3], vw[2], rot_lo); w4[3] = __builtin_amdgcn_perm(vw[3], vw[2], rot_hi);
+                *(__attribute__((address_space(3))) uint4_t*)(uintptr_t)stg_w = w4;
+            } else if constexpr (DSUB == 16) {
+                uint2_t w2;
+                w2[0] = __builtin_amdgcn_alignbit(vw[0], vw[0], 8u * (uint32_t)kgrp);
+                w2[1] = __builtin_amdgcn_alignbit(vw[1], vw[1], 8u * (uint32_t)kgrp);
+                *(__attribute__((address_space(3))) uint2_t*)(uintptr_t)stg_w = w2;
+            }
+            auto stage_d4 = [&](int a) {
+                uint32_t t[4];
+                uint4_t w4;
+#pragma unroll
+                for (int rho = 0; rho < 4; ++rho) t[rho] = (kgrp & 1) ? vw[4 * a + ((rho + 1) & 3)] : vw[4 * a + rho];
+#pragma unroll
+                for (int rho = 0; rho < 4; ++rho) w4[rho] = (kgrp & 2) ? t[(rho + 2) & 3] : t[rho];
+                *(__attribute__((address_space(3))) uint4_t*)(uintptr_t)stg_w = w4;
+            };
+            if constexpr (DSUB == 4) stage_d4(0);
+            const uint32_t mw = s_mask[(2 * (uint32_t)tile + mask_dw) & (L::mask_words - 1)];
 
             // ---- K side: scores in log2 units.  Code dwords are XOR-permuted so that step s finds the code of
             // sub-space (s XOR kr) at a compile-time register and a per-lane constant byte selector.
@@ -843,119 +906,157 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 }
             }
             // One table read per (token, sub-space): the address (code << 8 | slot << 3) is a single byte permute
-            // of the code dword and a per-lane constant.  Two entries (16 bytes) form this lane's B operand of an
-            // int8 MFMA whose A operand is block-diagonal: row 4*(lane/16) + h carries the weights (1, -128) on
-            // the (lo, hi) bytes of head h in k-group lane/16 only, so C row r of a lane is its own token's sum
-            // for head r.
+            // of the code dword and a per-lane constant.  Two entries (16 bytes) are this lane's row of the int8
+            // MFMA's first operand (row = rank, k-group = class); the constant second operand routes them.
+            // (all gathers of a batch of 16 sub-spaces are issued before the first of them is waited for: with four
+            // waves per SIMD a chain of gather -> wait -> MFMA steps leaves the LDS latency exposed)
             int4_t si = {0, 0, 0, 0};
+            constexpr int KB = M < 16 ? M : 16;
 #pragma unroll
-            for (int st = 0; st < M; st += 2) {
-                const uint32_t a0 = __builtin_amdgcn_perm(kw[st >> 2], kc[st >> 2], ksel[st & 3]);
-                const uint32_t a1 = __builtin_amdgcn_perm(kw[(st + 1) >> 2], kc[(st + 1) >> 2], ksel[(st + 1) & 3]);
-                const uint2_t e0 = *(const lds_uint2*)(uintptr_t)a0;
-                const uint2_t e1 = *(const lds_uint2*)(uintptr_t)a1;
-                si = __builtin_amdgcn_mfma_i32_16x16x64_i8(k_wgt, int4_t{(int)e0[0], (int)e0[1], (int)e1[0], (int)e1[1]}, si, 0, 0, 0);
-            }
-            // exponent of the weight relative to the reference: x = score - m_ref
-            float x[kNH];
-            bool grow = false;
+            for (int s0 = 0; s0 < M; s0 += KB) {
+                uint2_t ent[KB];
 #pragma unroll
-            for (int h = 0; h < kNH; ++h) {
-                x[h] = fmaf((float)si[h], lut_q[h], neg_m[h]);
-                grow = grow || (x[h] > kPShift);
+                for (int u = 0; u < KB; ++u) {
+                    const int st = s0 + u;
+                    ent[u] = *(const lds_uint2*)(uintptr_t)__builtin_amdgcn_perm(kw[st >> 2], kc[st >> 2], ksel[st & 3]);
+                }
+#pragma unroll
+                for (int u = 0; u < KB; u += 2)
+                    si = __builtin_amdgcn_mfma_i32_16x16x64_i8(int4_t{(int)ent[u][0], (int)ent[u][1], (int)ent[u + 1][0], (int)ent[u + 1][1]},
+                                                               k_wgt, si, 0, 0, 0);
             }
-            if (__any(grow && !masked)) {   // some score exceeds the running maximum: move the reference, rescale
+            // ---- softmax: register i = token (tj, 4 kgrp + i), head tq.  x = score - reference.
+            const uint32_t keep_bits = ~mw >> mask_sh;                 // bit i set: token i is neither anchored nor past the range
+            float x[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[i] = fmaf((float)si[i], lut_q, neg_m);
+            if (__any(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])) > kPShift)) {
+                // some score exceeds the running maximum by more than the head room: move the reference, rescale
+                float lm = kNegBig;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) lm = fmaxf(lm, ((keep_bits >> i) & 1u) ? x[i] : kNegBig);
+                lm = fmaxf(lm, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, lm), 0x124, 0xf, 0xf, true)));   // row_ror:4
+                lm = fmaxf(lm, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, lm), 0x128, 0xf, 0xf, true)));   // row_ror:8
+                lm = fmaxf(lm, __shfl_xor(lm, 16, 64));
+                lm = fmaxf(lm, __shfl_xor(lm, 32, 64));                // largest unmasked x of head tq in the tile
+                const float m_old = -neg_m;
+                const float m_new = fmaxf(m_old, (lm - neg_m) - kPShift);
+                const float alpha = fast_exp2(m_old - m_new);
+                l_own *= alpha;
+                neg_m = -m_new;
+                // (multiplied in place through inline assembly: written as plain C++ the compiler keeps a second copy
+                // of the 32 accumulator registers for this rare path and moves all of them on every tile)
 #pragma unroll
                 for (int h = 0; h < kNH; ++h) {
-                    const float mx = wave_max_uniform(masked ? kNegBig : x[h]) - neg_m[h];   // largest unmasked score
-                    const float m_new = fmaxf(-neg_m[h], mx - kPShift);
-                    const float alpha = fast_exp2(-neg_m[h] - m_new);
-                    l_lane[h] *= alpha;
-                    acc[0][h] *= alpha;
-                    acc[1][h] *= alpha;
-                    neg_m[h] = -m_new;
-                    x[h] = fmaf((float)si[h], lut_q[h], neg_m[h]);
-                }
-            }
+                    const float ah = lane_bcast(alpha, h);              // lanes 0..3 work for heads 0..3
 #pragma unroll
-            for (int h = 0; h < kNH; ++h) {
-                const float pw = masked ? 0.f : fast_exp2(x[h]);
-                l_lane[h] += pw;
-                s_p32[h * kPStride32 + pslot] = (uint32_t)__builtin_bit_cast(unsigned short, (half_t)pw);
+                    for (int a = 0; a < 2; ++a)
+#pragma unroll
+                        for (int rho = 0; rho < 4; ++rho) {
+                            float v = acc[a][rho][h];
+                            asm volatile("v_mul_f32 %0, %1, %0" : "+v"(v) : "s"(ah));
+                            acc[a][rho][h] = v;
+                        }
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) x[i] = fmaf((float)si[i], lut_q, neg_m);
             }
+            uint4_t pa4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint32_t keep;                                           // all ones or zero (the compiler would turn the
+                asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(keep) : "v"(keep_bits), "n"(i));   // builtin into test + select)
+                const float pw = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, fast_exp2(x[i])) & keep);
+                l_own += pw;
+                pa4[i] = (uint32_t)__builtin_bit_cast(unsigned short, (half_t)pw);
+            }
+            const half8_t pa = __builtin_bit_cast(half8_t, pa4);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
 
-            // ---- V side: sparse MFMA i of slab set a takes tokens 16 gb + 4 i + e4 (e4 < 4) in dense k-group gb,
-            // the four rows of each transposed read being the four slabs 4a + cls of one token
-            half8_t pa[4];
+            // ---- V side: MFMA (a, rho): element quad e4 of this lane's k-group = token (tj, rank(e4)) with slab
+            // 4 a + (tj + rho) % 4, the four rows of a transposed read being the four classes
 #pragma unroll
-            for (int i = 0; i < 4; ++i) pa[i] = __builtin_bit_cast(half8_t, *(const uint4_t*)(s_pa_r + 16 * i));
+            for (int a = 0; a < 2; ++a) {
+                constexpr int VD = (DSUB == 4) ? 4 : 2;                // staged code dwords per token and read
+                uint32_t vt[4][VD];
+                if (a == 0 || DSUB != 16) {
+                    if constexpr (DSUB == 4) {
+                        if (a == 1) {
+                            __builtin_amdgcn_wave_barrier();
+                            stage_d4(1);
+                            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                            __builtin_amdgcn_wave_barrier();
+                        }
+                    }
 #pragma unroll
-            for (int step = 0; step < NSTEP; ++step) {
-                const int a_s = (DSUB == 8) ? step : (DSUB == 4 ? (step >> 1) : 0);
-                const int th = (DSUB == 4) ? (step & 1) : 0;
-                if (step) __builtin_amdgcn_wave_barrier();
-                if (DSUB != 4 || ((lane >> 3) & 1) == th) {
+                    for (int e4 = 0; e4 < 4; ++e4) {
+                        const uint32_t ad = ((e4 >> 1) ? stg_r1 : stg_r0) + (uint32_t)(SU * (e4 & 1)) + (DSUB == 8 ? 8u * a : 0u);
+                        if constexpr (DSUB == 4) {
+                            const uint4_t r = *(const __attribute__((address_space(3))) uint4_t*)(uintptr_t)ad;
 #pragma unroll
-                    for (int dl = 0; dl < DW; ++dl)
-                        s_cws[dl * CWROW + stok] = vw[((DSUB == 8) ? 2 * a_s : (DSUB == 4 ? 4 * a_s : 0)) + dl];
+                            for (int u = 0; u < 4; ++u) vt[e4][u] = r[u];
+                        } else {
+                            const uint2_t r = *(const lds_uint2*)(uintptr_t)ad;
+                            vt[e4][0] = r[0]; vt[e4][1] = r[1];
+                        }
+                    }
                 }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                // The units of this step (one sparse MFMA each) are software-pipelined: the transposed reads of
-                // unit u+1 are in flight while unit u waits for its own and multiplies.
-                constexpr int NU = (TOKS / 16) * ((DSUB == 16) ? 2 : 1);
-                auto unit_a = [&](int u) { return (DSUB == 16) ? (u & 1) : a_s; };
-                auto unit_i = [&](int u) { const int ii = (DSUB == 16) ? (u >> 1) : u; return (DSUB == 4) ? 2 * th + ii : ii; };
-                auto fetch_unit = [&](int u, half4_t (&vb)[4]) {
-                    const int ii = (DSUB == 16) ? (u >> 1) : u;
-                    const int a = unit_a(u);
-                    const uint4_t cw = *(const uint4_t*)(s_cws_r + ((DSUB == 16) ? a * CWROW : 0) + 4 * ii);
+                auto fetch = [&](int rho, half4_t (&vb)[4]) {
 #pragma unroll
-                    for (int e4 = 0; e4 < 4; ++e4)
-                        vb[e4] = lds_read_tr16_abs(__builtin_amdgcn_perm(cw[e4], v_const, v_sel) + 128 * a);
+                    for (int e4 = 0; e4 < 4; ++e4) {
+                        uint32_t ad;
+                        if constexpr (DSUB == 8) ad = __builtin_amdgcn_perm(vt[e4][rho >> 1], v_const[rho], v_sel[rho & 1]);
+                        else if constexpr (DSUB == 16) ad = __builtin_amdgcn_perm(vt[e4][a], v_const[rho], 0x0c020000u | ((4u + (uint32_t)rho) << 8));
+                        else ad = __builtin_amdgcn_perm(vt[e4][rho], v_const[rho], v_sel[0]);
+                        vb[e4] = lds_read_tr16_abs(ad + 128 * a);
+                    }
                 };
                 half4_t vb0[4], vb1[4];
-                fetch_unit(0, vb0);
+                fetch(0, vb0);
 #pragma unroll
-                for (int u = 0; u < NU; ++u) {
-                    half4_t (&cur)[4] = (u & 1) ? vb1 : vb0;
-                    half4_t (&nxt)[4] = (u & 1) ? vb0 : vb1;
-                    if (u + 1 < NU) fetch_unit(u + 1, nxt);
+                for (int rho = 0; rho < 4; ++rho) {
+                    half4_t (&cur)[4] = (rho & 1) ? vb1 : vb0;
+                    half4_t (&nxt)[4] = (rho & 1) ? vb0 : vb1;
+                    if (rho + 1 < 4) fetch(rho + 1, nxt);
                     const half16_t bop = {cur[0][0], cur[0][1], cur[0][2], cur[0][3], cur[1][0], cur[1][1], cur[1][2], cur[1][3],
                                           cur[2][0], cur[2][1], cur[2][2], cur[2][3], cur[3][0], cur[3][1], cur[3][2], cur[3][3]};
-                    const int a = unit_a(u);
-                    acc[a] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(pa[unit_i(u)], bop, acc[a], sm_idx, 0, 0);
+                    acc[a][rho] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(pa, bop, acc[a][rho], sm_idx, 0, 0);
                 }
             }
             __builtin_amdgcn_wave_barrier();
         };
 
+        // The next tile's codes are requested before the current tile is worked on.  The request is unconditional (a
+        // wave that has no further tile re-reads the range's last one): a conditional load would cost register copies
+        // on every tile.
         uint32_t kw_next[CW], vw_next[CW];
         int64_t tile = grab_tile();
-        if (tile < n_tiles) load_codes(tile, kw_next, vw_next);
+        load_codes(tile < n_tiles ? tile : n_tiles - 1, kw_next, vw_next);
         while (tile < n_tiles) {
             uint32_t kw_c[CW], vw_c[CW];
 #pragma unroll
             for (int i = 0; i < CW; ++i) { kw_c[i] = kw_next[i]; vw_c[i] = vw_next[i]; }
             const int64_t tile_next = grab_tile();
-            if (tile_next < n_tiles) load_codes(tile_next, kw_next, vw_next);
+            load_codes(tile_next < n_tiles ? tile_next : n_tiles - 1, kw_next, vw_next);
             do_tile(tile, kw_c, vw_c);
             tile = tile_next;
         }
 #pragma unroll
-        for (int h = 0; h < kNH; ++h) m_ref[h] = -neg_m[h];
+        for (int h = 0; h < kNH; ++h) m_ref[h] = -lane_bcast(neg_m, h);
     }
-    DA_STAMP(2);
+    // weight sums per head: add up the lanes that worked for the head
     float l_sum[kNH];
+    {
+        float v = l_own;
+        v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x124, 0xf, 0xf, true));   // row_ror:4
+        v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x128, 0xf, 0xf, true));   // row_ror:8
+        v += __shfl_xor(v, 16, 64);
+        v += __shfl_xor(v, 32, 64);
 #pragma unroll
-    for (int h = 0; h < kNH; ++h) l_sum[h] = wave_sum(l_lane[h]);
-#ifdef ANTKV_DA_TRACE
-    wg_merge_and_store<DSUB>(smem, m_ref, l_sum, acc, part_bg, sp, p.S, nheads, p.trace + (size_t)blockIdx.x * 8 + 6);
-#else
+        for (int h = 0; h < kNH; ++h) l_sum[h] = lane_bcast(v, h);
+    }
     wg_merge_and_store<DSUB>(smem, m_ref, l_sum, acc, part_bg, sp, p.S, nheads);
-#endif
     // The last workgroup of this (sequence, KV head) to arrive merges the S partials by log-sum-exp and
     // rounds once to fp16: out = sum_s acc_s 2^(m_s - m) / sum_s l_s 2^(m_s - m).
     // Ordering without a cache-wide release: the partial was written with device-scope stores, each wave
@@ -1013,7 +1114,6 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             }
         }
     }
-    DA_STAMP(5);
 }
 
 __global__ __launch_bounds__(128) void zero_out_kernel(half_t* out, int64_t n)
@@ -1042,14 +1142,7 @@ struct DsParams {
     int Hq, Hkv, G, S;
     int64_t chunk;
     uint32_t* hist;             // optional (pass 1): first-level top-k histograms, [2 B Hkv][2 * kTopkBins], K rows then V rows
-    unsigned long long* trace;  // ANTKV_DA_TRACE builds: [grid][8] wall-clock stamps, else unused
 };
-
-#ifdef ANTKV_DA_TRACE
-#define DS_STAMP(i) do { if (threadIdx.x == 0) p.trace[((size_t)(PASS + 1) * gridDim.x + blockIdx.x) * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define DS_STAMP(i) do { } while (0)
-#endif
 
 template <int DSUB, int PASS>
 __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p)
@@ -1082,7 +1175,6 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
     // range an entry falls into, so that anchors clustered in one part of the context do not pile up in one
     // workgroup.  The loads of a wave's first kPre rounds are issued here, ahead of everything else: one after the
     // other behind the stream they were a chain of exposed load latencies.
-    DS_STAMP(0);
     constexpr int kPre = 4;
     const int a_sub = lane >> 4, a_l16 = lane & 15;
     const int a_first = sp * (4 * kDaWaves) + 4 * wave, a_stride = p.S * (4 * kDaWaves);
@@ -1204,7 +1296,6 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
         lse[h] = (PASS == 1) ? s_red[kDaWaves * 8 - 8 + h] : 0.f;
     }
     __syncthreads();
-    DS_STAMP(1);
     const uint8_t* ck = p.codes_k + (int64_t)bg * p.N_cap * M;
     float m_run[kNH], l_run[kNH];
 #pragma unroll
@@ -1308,7 +1399,6 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
             if (!((s_mask[rel >> 5] >> (rel & 31)) & 1u)) consume(s, tok);
         }
     }
-    DS_STAMP(2);
     // ---- K-anchored tokens: the prefetched rounds, then any further ones
     {
         const int l16 = a_l16;
@@ -1339,7 +1429,6 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
             score_row(v, tok);
         }
     }
-    DS_STAMP(3);
     if (PASS == 0) {
 #pragma unroll
         for (int h = 0; h < kNH; ++h) {
@@ -1367,12 +1456,8 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
             if (s_hist[kTopkBins + i]) atomicAdd(&hv[i], s_hist[kTopkBins + i]);
         }
     }
-    DS_STAMP(4);
 }
 
-
-// measurement aid: events to record around the next code-stream kernel launched from this host thread
-thread_local hipEvent_t t_ev_start = nullptr, t_ev_stop = nullptr;
 
 struct DaPlan {
     int S;
@@ -1397,9 +1482,6 @@ DaPlan da_plan(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans
     if (pl.S < 1) pl.S = 1;
     (void)k_k; (void)k_v;
     size_t off = 0;
-#ifdef ANTKV_DA_TRACE
-    off += align_up((size_t)3 * g.B * g.Hkv * pl.S * 8 * sizeof(unsigned long long));   // trace lives at offset 0: main kernel, then the two score passes
-#endif
     pl.off_part = off; off += align_up((size_t)g.B * g.Hq * pl.S * (kD + 2) * sizeof(float));
     pl.off_done = off; off += align_up((size_t)g.B * g.Hkv * sizeof(unsigned long long));
     pl.off_stat = off; off += want_ans ? align_up((size_t)g.B * g.Hq * pl.S * 2 * sizeof(float)) : 0;
@@ -1410,12 +1492,6 @@ DaPlan da_plan(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans
 }  // namespace
 
 int decode_num_splits(const Geom& g, int64_t N) { return da_plan(g, N, 0, 0, false).S; }
-
-void decode_profile_next(hipEvent_t start, hipEvent_t stop)
-{
-    t_ev_start = start;
-    t_ev_stop = stop;
-}
 
 size_t decode_workspace_bytes(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans)
 {
@@ -1443,7 +1519,6 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     p.q = a.q; p.codes_k = a.codes_k; p.codes_v = a.codes_v; p.cb_k = a.cb_k; p.cb_v = a.cb_v;
     p.idx_k = a.idx_k; p.idx_v = a.idx_v; p.rows_k = a.rows_k; p.rows_v = a.rows_v;
     p.part = part; p.out = a.out; p.done = (unsigned long long*)(w + pl.off_done); p.tag = next_launch_tag(); p.N = a.N; p.N_cap = a.N_cap; p.k_k = (int)a.k_k; p.k_v = (int)a.k_v;
-    p.trace = (unsigned long long*)ws;
     p.c1 = a.scale * kLog2e; p.Hq = g.Hq; p.Hkv = g.Hkv; p.G = g.G; p.S = pl.S; p.chunk = pl.chunk;
     if (pl.S > 1024) return hipErrorInvalidValue;        // the in-kernel merge keeps one weight per slot in LDS
     const size_t shmem = Lds<DSUB>::total;
@@ -1460,17 +1535,13 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     hipError_t e = setup;
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((int64_t)g.B * g.Hkv * pl.S);
-    if (t_ev_start) (void)hipEventRecord(t_ev_start, st);
     hipLaunchKernelGGL(decode_attn_kernel<DSUB>, dim3(grid), dim3(kDaThreads), shmem, st, p);
-    if (t_ev_stop) (void)hipEventRecord(t_ev_stop, st);
-    t_ev_start = t_ev_stop = nullptr;
     if (want_ans) {
         DsParams d;
         d.q = a.q; d.codes_k = a.codes_k; d.cb_k = a.cb_k; d.idx_k = a.idx_k; d.rows_k = a.rows_k;
         d.stat_part = (float*)(w + pl.off_stat); d.ans_k = a.ans_k; d.ans_v = a.ans_v;
         d.N = a.N; d.N_cap = a.N_cap; d.k_k = (int)a.k_k; d.c1 = p.c1; d.Hq = g.Hq; d.Hkv = g.Hkv; d.G = g.G;
         d.S = pl.S; d.chunk = pl.chunk;
-        d.trace = (unsigned long long*)ws;
         d.hist = a.topk_hist;
         const size_t sh2 = (size_t)(g.M < 16 ? 16 : g.M) * 256 * 16 + kNH * kD * 4 + kDaWaves * 32 + 64 + 4096 + 2 * kTopkBins * 4;
         static const hipError_t ans_setup = [sh2]() {              // once per process and DSUB
