@@ -11,13 +11,16 @@
 //            step, i.e. it walks the sub-spaces in its own XOR-permuted order: the 32 lanes that the LDS
 //            serves per clock always hit 32 different bank pairs, whatever the codes are (random gathers
 //            would run at a third of that).
-//  anchors   the (sequence, KV head)'s anchor lists are cut into 32-entry tiles dealt round-robin to the
-//            workgroups (balanced by list index, not by position: anchors cluster at the head and tail of a
-//            context); inside a workgroup whichever wave is free takes the next tile before it joins the
-//            stream.  K_eff chunks (the FP16 row, or the de-quantised codes when only V of that token is
-//            anchored) go straight from global memory into the MFMA operand; V_eff rows pass through the
-//            wave's staging area for the transposed reads.
-//  stream    waves pull 64-token tiles from a shared counter, code loads running one tile ahead:
+//  anchors   the (sequence, KV head)'s anchor lists are cut into tiles (16 K entries or 32 V entries) dealt
+//            round-robin to the workgroups (balanced by list index, not by position: anchors cluster at the
+//            head and tail of a context) and, inside a workgroup, to the waves: every wave works on its tile
+//            before any wave streams, so the entries never compete with the stream for the LDS and the issue
+//            slots.  A tile's tokens, cross membership (is the token in the other list too?) and code rows are
+//            fetched during the prologue, its FP16 rows just before the prologue's last barrier.  K entries
+//            are scored on the dense MFMA (rows straight from global memory into the operand), V entries through
+//            the lookup table like the stream; the values are packed fp16 dot products, two entries at a time.
+//  stream    wave w starts with tile w, then waves pull 64-token tiles from a shared counter, code loads running
+//            one tile ahead:
 //      K side  one lane per token: 16-byte coalesced code loads, one 8-byte LUT gather per sub-space
 //              serves the group's four query heads.  The gathered entries are the row operand of an int8 MFMA
 //              whose column operand is a constant block-diagonal matrix: it sums the entries exactly and, at
@@ -51,10 +54,10 @@ constexpr int kDaThreads = kDaWaves * 64;
 constexpr int kNH = 4;                 // query-head slots per workgroup (group size G <= 4)
 constexpr float kPShift = 8.0f;        // P is scaled by 2^8 so that small weights stay normal in fp16
 constexpr float kLutMax = 16256.0f;    // largest table magnitude: 127 * 128, so that both bytes of an entry fit int8
-constexpr int kPStride = 72;           // fp16 elements between the heads of a wave's P tile (64 + pad against bank conflicts)
-// per-wave staging.  Anchor tiles: fp16 P tile, then 1 KB of V rows.  Stream: the V code bytes of a tile (up to 1 KB).
+// per-wave staging.  Anchor tiles: code rows of the entries, then the weights of 32 pairs of entries.  Stream: the V code
+// bytes of a tile (up to 1 KB).  Prologue: all waves' areas together hold the two anchor lists.
 constexpr int kStgBytes = 1664;
-static_assert(4 * kPStride * 2 + 1024 <= kStgBytes && kStgBytes % 16 == 0, "anchor staging fits the per-wave area");
+static_assert(kStgBytes % 16 == 0, "16-byte accesses to the staging areas");
 constexpr float kEmptyRef = -1.0e4f;   // softmax reference before any token was seen: finite, below every real score,
                                        // and far above the masked score kNegBig so that exp2(masked - ref) is 0
 
@@ -89,6 +92,14 @@ __device__ __forceinline__ uint32_t quad_bcast_sel(uint32_t x, int src)
     case 2: return quad_bcast<2>(x);
     default: return quad_bcast<3>(x);
     }
+}
+
+// Workgroup barrier that orders LDS traffic only: global loads still in flight stay in flight (__syncthreads would wait
+// for every one of them, which turns each barrier of the prologue into a full memory round trip).  Global stores that
+// other waves read after the barrier need a wait of their own before it.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 // max over the 64 lanes, result uniform
@@ -194,6 +205,17 @@ __device__ __forceinline__ int find_sorted(const int32_t* __restrict__ arr, int 
     return (lo < n && arr[lo] == key) ? lo : -1;
 }
 
+typedef __attribute__((address_space(3))) int32_t lds_int;
+__device__ __forceinline__ int find_sorted_lds(const lds_int* arr, int n, int key)
+{
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (arr[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    return (lo < n && arr[lo] == key) ? lo : -1;
+}
+
 struct DaParams {
     const half_t* q;
     const uint8_t *codes_k, *codes_v;
@@ -202,6 +224,8 @@ struct DaParams {
     const half_t *rows_k, *rows_v;
     float* part;                // [B][Hq][S][kD + 2]
     half_t* out;                // [B][Hq][kD]
+    int32_t* info;              // [B][Hkv][k_k + k_v] cross membership of the anchor entries, filled in the prologue:
+                                // K entry: its slot in the V list or -1; V entry: 1 if the token is a K anchor too (skipped), else 0
     unsigned long long* done;   // [B][Hkv] arrival words (launch tag << 32 | count); the last workgroup of a (b, g) merges
     unsigned int tag;           // this launch's tag: words carrying another tag count as zero, so no clearing pass
     int64_t N, N_cap;
@@ -236,7 +260,7 @@ template <int DSUB>
 __device__ void wg_merge_and_store(char* smem, float (&m_ref)[kNH], float (&l_sum)[kNH], float4_t (&acc)[2][4],
                                    float* __restrict__ part_bg, int slot, int slots, int nheads)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     float* s_red = (float*)(smem + Lds<DSUB>::red);
     __syncthreads();   // everyone is done with the tables and the staging area
     if (lane == 0) {
@@ -300,7 +324,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     extern __shared__ uint4_t smem_u4[];
     char* smem = (char*)smem_u4;
     const lds_char* lsm = (const lds_char*)smem_u4;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and the compiler may know it
     // Workgroups go to the 8 XCDs round-robin by their id; remap so that the S workgroups of one (sequence, KV head)
     // sit on one XCD and share its L2 for the codebooks and the anchor lists.
     const int wg = (gridDim.x & 7) == 0 ? (int)((blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3)) : (int)blockIdx.x;
@@ -318,6 +342,9 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     const half_t* cbv = p.cb_v + (size_t)g * 32768;
     const int64_t t0 = (int64_t)sp * p.chunk;
     const int64_t t1 = (t0 + p.chunk < p.N) ? t0 + p.chunk : p.N;
+    // anchor entries are processed in tiles dealt round-robin over the S workgroups: K tiles of 16 entries, then V tiles of 32
+    const int ntk = (p.k_k + 15) >> 4, ntv = (p.k_v + 31) >> 5;
+    const int n_atiles = ntk + ntv;
     // Arrival word of this (b, g): (launch tag << 32 | arrivals).  A word left by an earlier launch (another tag,
     // or this tag with all S arrivals when a captured launch is replayed) is replaced by (tag, 0) now, by
     // whichever workgroup gets there first, so that the arrival at the end is a single fetch-add.  Launches
@@ -333,6 +360,48 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
 
     int* s_misc = (int*)(smem + L::red + kDaWaves * 32);
     uint32_t* s_mask = (uint32_t*)(smem + L::mask);
+    // The first anchor tile of this wave (tile sp + S * wave of the (sequence, KV head)'s tiles): its tokens, their cross
+    // membership and their code rows are fetched during the prologue, while the memory system is idle, so that the
+    // tile itself is left with a single round trip (the FP16 rows).
+    const int T_first = sp + p.S * wave;
+    int pre_tok = 0, pre_info = 0;
+    uint32_t pre_codes[CW];
+#pragma unroll
+    for (int i = 0; i < CW; ++i) pre_codes[i] = 0u;
+    uint32_t pre_rows[32];                         // the tile's FP16 rows, in the form the tile works on (requested before the prologue's last barrier)
+    // FP16 K rows of the 16 entries from e0 on as MFMA operands: lane (entry arow, k-group kgrp) holds channels
+    // 32 st + 8 kgrp .. + 7 in r[4 st .. 4 st + 3]
+    auto load_k_rows = [&](int e0, uint32_t (&r)[32]) {
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            uint4_t v = uint4_t{0u, 0u, 0u, 0u};
+            if (e0 + arow < p.k_k) v = *(const uint4_t*)(p.rows_k + ((int64_t)bg * p.k_k + e0 + arow) * kD + 8 * (4 * st + kgrp));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r[4 * st + i] = v[i];
+        }
+    };
+    // channels 2 lane, 2 lane + 1 of the FP16 V rows of the 32 entries from j0 on (one coalesced 256-byte load per entry;
+    // entries past the list repeat the last row and get weight 0)
+    auto load_v_rows = [&](int j0, uint32_t (&r)[32]) {
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            const int j = j0 + k;
+            r[k] = *(const uint32_t*)(p.rows_v + ((int64_t)bg * p.k_v + (j < p.k_v ? j : p.k_v - 1)) * kD + 2 * lane);
+        }
+    };
+    auto load_codes = [&](const uint8_t* src, uint32_t (&dst)[CW]) {
+        if constexpr (CW == 2) {
+            const uint2_t a = *(const uint2_t*)src;
+            dst[0] = a[0]; dst[1] = a[1];
+        } else {
+#pragma unroll
+            for (int i = 0; i < CW / 4; ++i) {
+                const uint4_t a = *(const uint4_t*)(src + 16 * i);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) dst[4 * i + e] = a[e];
+            }
+        }
+    };
 
     // ================================================================================== prologue
     {
@@ -343,23 +412,26 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         if (tid < kNH * kD && (tid >> 7) < nheads) qv16 = qb[tid];
         // anchored positions of this range: short lists are scanned whole (one load latency), long lists are
         // cut to the range by a cooperative search first (a few dependent load latencies)
-        constexpr int kScanRounds = 4;
-        constexpr int kScanMax = kScanRounds * kDaThreads;
-        const bool scan_k = p.k_k <= kScanMax, scan_v = p.k_v <= kScanMax;
-        int scan_val[2][kScanRounds];
+        // both lists are short: they go to LDS whole (into the waves' staging areas, which nobody uses before the
+        // anchors), and the bitmap and the cross membership of the anchor entries are worked out from there
+        constexpr int kScanBatch = 3;                             // one load per thread and round, all in flight together
+        constexpr int kScanMax = kScanBatch * kDaThreads;
+        static_assert(2 * kScanMax * 4 <= kDaWaves * kStgBytes, "two whole lists fit the staging areas");
+        const bool lists_in_lds = p.k_k <= kScanMax && p.k_v <= kScanMax;
+        int scan_val[2][kScanBatch];
+        if (lists_in_lds) {
 #pragma unroll
-        for (int i = 0; i < kScanRounds; ++i) {
-            const int j = tid + i * kDaThreads;
-            scan_val[0][i] = -1;
-            scan_val[1][i] = -1;
-            if (scan_k && i * kDaThreads < p.k_k) scan_val[0][i] = (j < p.k_k) ? idx_k[j] : -1;   // uniform skip of empty rounds
-            if (scan_v && i * kDaThreads < p.k_v) scan_val[1][i] = (j < p.k_v) ? idx_v[j] : -1;
+            for (int i = 0; i < kScanBatch; ++i) {
+                const int j = tid + i * kDaThreads;
+                scan_val[0][i] = (j < p.k_k) ? idx_k[j] : -1;
+                scan_val[1][i] = (j < p.k_v) ? idx_v[j] : -1;
+            }
         }
         if (wave < 4) {
             const int32_t* arr = (wave < 2) ? idx_k : idx_v;
             const int n = (wave < 2) ? p.k_k : p.k_v;
             int r = 0;
-            if (!((wave < 2) ? scan_k : scan_v)) r = wave_lower_bound(arr, n, (int)((wave & 1) ? t1 : t0), lane);
+            if (!lists_in_lds) r = wave_lower_bound(arr, n, (int)((wave & 1) ? t1 : t0), lane);
             if (lane == 0) s_misc[wave] = r;
         }
         // The q.centroid table is one small matrix product per sub-space, batched on the MFMA by making the
@@ -388,6 +460,101 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 if (kgrp == l_mp && l_h < nheads) opa[j] = *(const uint4_t*)(qb + l_h * kD + (8 * j + 2 * l_mp) * 4);
             }
         }
+        if (tid < kNH * kD) ((half_t*)(smem + L::qh))[tid] = qv16;
+        int32_t* s_lk = (int32_t*)(smem + L::pst);
+        int32_t* s_lv = s_lk + kScanMax;
+        if (lists_in_lds) {
+#pragma unroll
+            for (int i = 0; i < kScanBatch; ++i) {
+                const int j = tid + i * kDaThreads;
+                if (j < p.k_k) s_lk[j] = scan_val[0][i];
+                if (j < p.k_v) s_lv[j] = scan_val[1][i];
+            }
+        }
+        for (int i = tid; i < L::mask_words; i += kDaThreads) s_mask[i] = 0u;
+        if (tid == 0) s_misc[8] = kDaWaves;                      // next stream tile to hand out (wave w starts with tile w)
+        lds_barrier();
+        if (tid == 0 && ((unsigned int)(done_seen >> 32) != p.tag || (unsigned int)done_seen >= (unsigned int)p.S))
+            __hip_atomic_compare_exchange_strong(&p.done[bg], &done_seen, (unsigned long long)p.tag << 32, __ATOMIC_RELAXED,
+                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // bitmap of anchored tokens in this range
+        const uint32_t range_len = (uint32_t)(t1 - t0);
+        if (lists_in_lds) {
+            // unsigned compare: positions below t0 wrap to huge values
+            for (int j = tid; j < p.k_k; j += kDaThreads) {
+                const uint32_t rel = (uint32_t)((const lds_int*)s_lk)[j] - (uint32_t)t0;
+                if (rel < range_len) atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
+            }
+            for (int j = tid; j < p.k_v; j += kDaThreads) {
+                const uint32_t rel = (uint32_t)((const lds_int*)s_lv)[j] - (uint32_t)t0;
+                if (rel < range_len) atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
+            }
+        }
+        // positions between the end of the range and the end of its last tile count as anchored: the stream skips them
+        if (tid < 64) {
+            const uint32_t rel = ((range_len - 1u) & ~63u) + (uint32_t)tid;
+            if (rel >= range_len) atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
+        }
+        if (!lists_in_lds) {
+            for (int i = s_misc[0] + tid; i < s_misc[1]; i += kDaThreads) {
+                const int rel = idx_k[i] - (int)t0;
+                atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
+            }
+        }
+        if (!lists_in_lds) {
+            for (int i = s_misc[2] + tid; i < s_misc[3]; i += kDaThreads) {
+                const int rel = idx_v[i] - (int)t0;
+                atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
+            }
+        }
+        // Cross membership of the anchor entries that this workgroup will process (tiles sp, sp + S, ... of the
+        // (sequence, KV head)'s entries: K tiles of 16, then V tiles of 32): a K entry needs to know whether its token
+        // has an FP16 V row too (and where), a V entry whether its token is a K anchor (then the K entry covers it).
+        {
+            // a wave's first tile: one lane per entry, answers stay in registers; the entry's code row is requested at once
+            if (T_first < n_atiles) {
+                if (T_first < ntk) {
+                    const int e = 16 * T_first + lane;
+                    if (lane < 16 && e < p.k_k) {
+                        pre_tok = lists_in_lds ? ((const lds_int*)s_lk)[e] : idx_k[e];
+                        pre_info = lists_in_lds ? find_sorted_lds((const lds_int*)s_lv, p.k_v, pre_tok) : find_sorted(idx_v, p.k_v, pre_tok);
+                        if (pre_info < 0) load_codes(cv + (int64_t)pre_tok * M, pre_codes);
+                    }
+                } else {
+                    const int j = 32 * (T_first - ntk) + lane;
+                    if (lane < 32 && j < p.k_v) {
+                        pre_tok = lists_in_lds ? ((const lds_int*)s_lv)[j] : idx_v[j];
+                        const int f = lists_in_lds ? find_sorted_lds((const lds_int*)s_lk, p.k_k, pre_tok) : find_sorted(idx_k, p.k_k, pre_tok);
+                        pre_info = f >= 0 ? 1 : 0;
+                        load_codes(ck + (int64_t)pre_tok * M, pre_codes);
+                    }
+                }
+            }
+            // further tiles (a wave takes more than one when the lists are long for the number of workgroups): one
+            // thread per entry, the answers go through global memory
+            int32_t* info_bg = p.info + (int64_t)bg * (p.k_k + p.k_v);
+            const int tiles_wg = n_atiles > sp ? (n_atiles - sp + p.S - 1) / p.S : 0;
+            if (tiles_wg > kDaWaves) {
+            for (int li = tid + 64 * kDaWaves; li < 64 * tiles_wg; li += kDaThreads) {
+                const int T = sp + p.S * (li >> 6), u = li & 63;
+                if (T < ntk) {
+                    const int e = 16 * T + u;
+                    if (u < 16 && e < p.k_k) {
+                        info_bg[e] = lists_in_lds ? find_sorted_lds((const lds_int*)s_lv, p.k_v, ((const lds_int*)s_lk)[e])
+                                                  : find_sorted(idx_v, p.k_v, idx_k[e]);
+                    }
+                } else {
+                    const int j = 32 * (T - ntk) + u;
+                    if (u < 32 && j < p.k_v) {
+                        const int f = lists_in_lds ? find_sorted_lds((const lds_int*)s_lk, p.k_k, ((const lds_int*)s_lv)[j])
+                                                   : find_sorted(idx_k, p.k_k, idx_v[j]);
+                        info_bg[p.k_k + j] = f >= 0 ? 1 : 0;
+                    }
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the answers are in memory before the barrier that precedes their readers
+            }
+        }
         // V codebook: LDS holds it code-major ([code][m][DSUB], a 256-byte row per code), so 16-byte chunk ci of
         // the LDS image comes from a permuted place of the sub-space-major global array
         uint4_t vcopy[4096 / kDaThreads];
@@ -401,42 +568,6 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             } else {
                 const uint2_t lo = ((const uint2_t*)cbv)[(2 * w16) * 256 + code], hi = ((const uint2_t*)cbv)[(2 * w16 + 1) * 256 + code];
                 vcopy[i] = uint4_t{lo[0], lo[1], hi[0], hi[1]};
-            }
-        }
-        if (tid < kNH * kD) ((half_t*)(smem + L::qh))[tid] = qv16;
-        for (int i = tid; i < L::mask_words; i += kDaThreads) s_mask[i] = 0u;
-        if (tid == 0) { s_misc[8] = 0; s_misc[9] = 0; }          // next stream tile, next anchor tile of this workgroup
-        __syncthreads();
-        if (tid == 0 && ((unsigned int)(done_seen >> 32) != p.tag || (unsigned int)done_seen >= (unsigned int)p.S))
-            __hip_atomic_compare_exchange_strong(&p.done[bg], &done_seen, (unsigned long long)p.tag << 32, __ATOMIC_RELAXED,
-                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // bitmap of anchored tokens in this range
-        const uint32_t range_len = (uint32_t)(t1 - t0);
-#pragma unroll
-        for (int w2 = 0; w2 < 2; ++w2)
-#pragma unroll
-            for (int i = 0; i < kScanRounds; ++i) {
-                if (i * kDaThreads < (w2 ? p.k_v : p.k_k)) {
-                    // unsigned compare: positions below t0 (and the -1 filler) wrap to huge values
-                    const uint32_t rel = (uint32_t)scan_val[w2][i] - (uint32_t)t0;
-                    if (scan_val[w2][i] >= 0 && rel < range_len) atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
-                }
-            }
-        // positions between the end of the range and the end of its last tile count as anchored: the stream skips them
-        if (tid < 64) {
-            const uint32_t rel = ((range_len - 1u) & ~63u) + (uint32_t)tid;
-            if (rel >= range_len) atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
-        }
-        if (!scan_k) {
-            for (int i = s_misc[0] + tid; i < s_misc[1]; i += kDaThreads) {
-                const int rel = idx_k[i] - (int)t0;
-                atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
-            }
-        }
-        if (!scan_v) {
-            for (int i = s_misc[2] + tid; i < s_misc[3]; i += kDaThreads) {
-                const int rel = idx_v[i] - (int)t0;
-                atomicOr(&s_mask[rel >> 5], 1u << (rel & 31));
             }
         }
         // LUT[m][c][h] = c1 * q_h[m*d : (m+1)*d] . cb_k[g][m][c], stored as fixed point with one scale per head
@@ -468,7 +599,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             const float wm = wave_max_uniform(amax[h]);
             if (lane == 0) s_red[wave * 8 + h] = wm;
         }
-        __syncthreads();
+        lds_barrier();
         float inv_q[kNH];
         {
             const int hh = lane >> 4, ws = lane & 15;
@@ -518,285 +649,416 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
 #pragma unroll
             for (int i = 0; i < 4096 / kDaThreads; ++i) dst[tid + i * kDaThreads] = vcopy[i];
         }
+        if (T_first < n_atiles) {
+            if (T_first < ntk) load_k_rows(16 * T_first, pre_rows);
+            else load_v_rows(32 * (T_first - ntk), pre_rows);
+        }
     }
-    __syncthreads();
+    lds_barrier();
 
     // m_ref: reference maximum per head (the same in every lane).  acc[a][rho]: see sm_idx below.
     float m_ref[kNH];
-    float4_t acc[2][4];
 #pragma unroll
     for (int h = 0; h < kNH; ++h) m_ref[h] = kEmptyRef;
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int rho = 0; rho < 4; ++rho) acc[a][rho] = float4_t{0.f, 0.f, 0.f, 0.f};
+    float4_t acc_anchor[2] = {float4_t{0.f, 0.f, 0.f, 0.f}, float4_t{0.f, 0.f, 0.f, 0.f}};   // what the anchor entries hand to acc[a][0]
     float l_own = 0.f;                                            // sum of weights, head lane % 4, this lane's share
-    half_t* s_p = (half_t*)(smem + L::pst + wave * kStgBytes);    // this wave's P tile, [4][kPStride] fp16
-    uint32_t* s_cw = (uint32_t*)(s_p + 4 * kPStride);             // this wave's V code words, 512 bytes
-
-    // P.V runs on the 2:4-sparse MFMA (16x16x64 f16).  Its 64 k positions form 16 groups of four; the position
-    // inside a group is the class, and row 4 cls + h of the sparse operand keeps, in every group, only the
-    // position of its own class: a softmax weight of head h.  All 16 rows carry useful work, and the compressed
+    // P.V of the code stream runs on the 2:4-sparse MFMA (16x16x64 f16).  Its 64 k positions form 16 groups of four;
+    // the position inside a group is the class, and row 4 cls + h of the sparse operand keeps, in every group, only
+    // the position of its own class: a softmax weight of head h.  All 16 rows carry useful work, and the compressed
     // operand is just four zero-extended fp16 weights per lane (the index register, a per-lane constant, says
-    // where they sit).  What a position means differs between the two users:
-    //   anchor tiles  the four positions of a group are the four 16-channel slabs 4 a + cls of ONE item; output row
-    //                 (cls, h) of MFMA a accumulates slab 4 a + cls;
-    //   stream        the four positions of a group are FOUR tokens (one per class), position cls carrying slab
-    //                 4 a + (cls + rho) % 4 of its token; MFMA (a, rho) accumulates into acc[a][rho], whose row
-    //                 (cls, h) is therefore slab 4 a + (cls + rho) % 4 summed over the tokens of class cls.
-    // With rho = 0 the two meanings of a row agree, so anchor tiles add into acc[a][0].
+    // where they sit).  The four positions of a group are FOUR tokens (one per class), position cls carrying slab
+    // 4 a + (cls + rho) % 4 of its token; MFMA (a, rho) accumulates into acc[a][rho], whose row (cls, h) is therefore
+    // slab 4 a + (cls + rho) % 4 summed over the tokens of class cls.
     // Operand geometry: compressed dword p of a lane in k-group ga pairs with the dense operand's k-group
     // 2 (ga % 2) + p / 2, elements 4 (2 (ga / 2) + p % 2) .. + 3.
     const int sm_idx = (int)(0x1111u * (uint32_t)(tj | ((tj ^ 1) << 2)));
-    // P-tile slot of the (token, head) weights so that the four weights a lane needs are contiguous:
-    // the item in dense k-group gb, element quad e4 of sparse MFMA i -> slot 16 i + 4 ga + p
-    auto p_slot = [](int i, int gb_, int e4) {
-        return 16 * i + 4 * ((gb_ >> 1) + 2 * (e4 >> 1)) + 2 * (gb_ & 1) + (e4 & 1);
-    };
-    auto load_pa = [&](int i) -> half8_t {
-        const uint2_t w2 = *(const uint2_t*)(s_p + (lane & 3) * kPStride + 16 * i + 4 * kgrp);
-        const uint4_t a4 = {w2[0] & 0xffffu, w2[0] >> 16, w2[1] & 0xffffu, w2[1] >> 16};
-        return __builtin_bit_cast(half8_t, a4);
-    };
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lsm;
 
-    // ================================================================================== anchors
-    const int n_items = p.k_k + p.k_v;                    // K-anchor entries, then V-anchor entries
-    const int n_atiles = (n_items + 31) >> 5;
-    // An anchor tile is a chain of dependent loads (lists, cross membership, rows) that leaves the CU idle if every
-    // wave of the workgroup sits in one at the same time.  So only some waves take anchor tiles, up to five each,
-    // while the others start streaming at once: 2, 4, 8 or all 16 waves, by the number of tiles of the workgroup.
-    int anchor_waves = 2;
-    {
-        const int tiles_wg = (n_atiles + p.S - 1) / p.S;
-        while (anchor_waves < kDaWaves && 5 * anchor_waves < tiles_wg) anchor_waves <<= 1;
-    }
-    if (n_atiles > 0 && (wave & (kDaWaves / anchor_waves - 1)) == 0) {
-        float l_lane[kNH] = {0.f, 0.f, 0.f, 0.f};                        // per-lane shares of the weight sums, per head
-        const half_t* s_qh = (const half_t*)(smem + L::qh);               // Q as MFMA A operand: row = head
-        half_t* s_vrows = (half_t*)s_cw;                                  // [8 items][64 channels] fp16
-        int* s_win = (int*)s_cw;                                          // 64 ints in the code-word area
-        const uint32_t rows_off = (uint32_t)(L::pst + wave * kStgBytes + 4 * kPStride * 2);
-        for (;;) {
-            // tiles of the (b, g) lists are dealt round-robin to the workgroups; this workgroup's tiles are
-            // handed out to its anchor waves through a counter
-            int lt = 0;
-            if (lane == 0) lt = atomicAdd(&s_misc[9], 1);
-            lt = __builtin_amdgcn_readfirstlane(lt);
-            const int t = sp + p.S * lt;
-            if (t >= n_atiles) break;
-            const int item0 = t * 32;
-            // lanes 0..31 each own one item of the tile
-            const bool is_k_tile_lane = (item0 + lane) < p.k_k;
-            int my_tok = 0x7fffffff, my_kslot = -1, my_vslot = -1, my_valid = 0;
-            if (lane < 32) {
-                const int it = item0 + lane;
-                if (it < p.k_k) { my_tok = idx_k[it]; my_kslot = it; my_valid = 1; }
-                else if (it < n_items) { my_tok = idx_v[it - p.k_k]; my_vslot = it - p.k_k; my_valid = 1; }
-            }
-            // Cross membership: a K item looks its token up in idx_v (is its V row FP16 too?), a V item in idx_k
-            // (if found there, the token is handled as a K item and this entry is skipped).  A tile can straddle
-            // the two lists, so both lookups are run; each is a cooperative search for the window of the other
-            // list that can contain the tile's tokens, then a search inside the window from LDS.
-#pragma unroll 1
-            for (int side = 0; side < 2; ++side) {
-                const int32_t* arr = side ? idx_k : idx_v;
-                const int n = side ? p.k_k : p.k_v;
-                const bool mine = my_valid && (side ? !is_k_tile_lane : is_k_tile_lane) && lane < 32;
-                const unsigned long long act = __ballot(mine);
-                if (act == 0ull || n == 0) continue;
-                const int l_first = __builtin_ctzll(act), l_last = 63 - __builtin_clzll(act);
-                const int tok_first = __shfl(my_tok, l_first, 64), tok_last = __shfl(my_tok, l_last, 64);
-                int w_lo, w_hi;
-                wave_lower_bound2(arr, n, tok_first, tok_last + 1, lane, w_lo, w_hi);
-                int found = -1;
-                if (w_hi - w_lo <= 64) {
-                    const int wv = (w_lo + lane < w_hi) ? arr[w_lo + lane] : 0x7fffffff;
-                    s_win[lane] = wv;
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                    if (mine) {
-                        int lo = 0, hi = w_hi - w_lo;
-                        while (lo < hi) { const int mid = (lo + hi) >> 1; if (s_win[mid] < my_tok) lo = mid + 1; else hi = mid; }
-                        if (lo < w_hi - w_lo && s_win[lo] == my_tok) found = w_lo + lo;
-                    }
-                    __builtin_amdgcn_wave_barrier();
-                } else if (mine) {
-                    const int f = find_sorted(arr + w_lo, w_hi - w_lo, my_tok);
-                    found = (f >= 0) ? w_lo + f : -1;
-                }
-                if (mine) {
-                    if (side == 0) my_vslot = found;            // K item: FP16 V row if the token is a V anchor too
-                    else if (found >= 0) my_valid = 0;          // V item whose token is also a K anchor: skip
-                }
-            }
-            // 16-byte chunk c (channels 8c .. 8c+7) of an item's effective row: from the FP16 row, or centroids
-            // looked up from the token's codes; zero for an entry that is skipped
-            auto fetch_chunk = [&](bool valid, int slot, const half_t* rows, int64_t n_rows_per_bg, int tok,
-                                   const uint8_t* codes, const half_t* cb, int c) -> uint4_t {
-                uint4_t r = {0u, 0u, 0u, 0u};
-                if (valid) {
-                    if (slot >= 0) {
-                        r = *(const uint4_t*)(rows + ((int64_t)bg * n_rows_per_bg + slot) * kD + 8 * c);
-                    } else if constexpr (DSUB == 8) {
-                        const uint32_t code = codes[(int64_t)tok * M + c];
-                        r = *(const uint4_t*)(cb + ((int64_t)c * 256 + code) * 8);
-                    } else if constexpr (DSUB == 16) {
-                        const int m = c >> 1;
-                        const uint32_t code = codes[(int64_t)tok * M + m];
-                        r = *(const uint4_t*)(cb + ((int64_t)m * 256 + code) * 16 + 8 * (c & 1));
-                    } else {
-                        const uint32_t c0 = codes[(int64_t)tok * M + 2 * c], c1 = codes[(int64_t)tok * M + 2 * c + 1];
-                        const uint2_t lo = *(const uint2_t*)(cb + ((int64_t)(2 * c) * 256 + c0) * 4);
-                        const uint2_t hi = *(const uint2_t*)(cb + ((int64_t)(2 * c + 1) * 256 + c1) * 4);
-                        r = uint4_t{lo[0], lo[1], hi[0], hi[1]};
-                    }
-                }
-                return r;
-            };
-            // ---- scores: S[head][item] for the two 16-item halves.  The dense operand (item along n, channels
-            // along k) is 8 consecutive channels per lane: it comes straight from global memory.
-            uint4_t kb[2][4];
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int i_tok = __shfl(my_tok, 16 * u + arow, 64), i_slot = __shfl(my_kslot, 16 * u + arow, 64);
-                const bool i_valid = __shfl(my_valid, 16 * u + arow, 64) != 0;
-#pragma unroll
-                for (int st = 0; st < 4; ++st)
-                    kb[u][st] = fetch_chunk(i_valid, i_slot, p.rows_k, p.k_k, i_tok, ck, cbk, 4 * st + kgrp);
-            }
-            // V rows go through LDS for the transposed reads, 8 items x 64 channels at a time (two of the four
-            // transposed reads of one sparse MFMA): for MFMA i, element-quad pair eh and slab set a this lane
-            // supplies chunk 8a + lane % 8 of item 16 i + 4 (lane / 16) + 2 eh + (lane / 8) % 2
-            uint4_t vq[2][2][2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int eh = 0; eh < 2; ++eh) {
-                    const int it = 16 * i + 4 * kgrp + 2 * eh + ((lane >> 3) & 1);
-                    const int r_tok = __shfl(my_tok, it, 64), r_vslot = __shfl(my_vslot, it, 64);
-                    const bool r_valid = __shfl(my_valid, it, 64) != 0;
-#pragma unroll
-                    for (int a = 0; a < 2; ++a)
-                        vq[i][eh][a] = fetch_chunk(r_valid, r_vslot, p.rows_v, p.k_v, r_tok, cv, cbv, 8 * a + (lane & 7));
-                }
-            float sc[2][4];
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                float4_t c4 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int st = 0; st < 4; ++st) {
-                    half8_t qa = *(const half8_t*)(s_qh + (arow & 3) * kD + 32 * st + 8 * kgrp);
-                    if (arow >= kNH) qa = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-                    c4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa, __builtin_bit_cast(half8_t, kb[u][st]), c4, 0, 0, 0);
-                }
-#pragma unroll
-                for (int r = 0; r < 4; ++r) sc[u][r] = c4[r] * p.c1;   // lanes 0..15: head r, item 16u + lane
-            }
-            float mx[kNH];
-#pragma unroll
-            for (int h = 0; h < kNH; ++h) mx[h] = kNegBig;
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const bool valid = __shfl(my_valid, 16 * u + arow, 64) != 0;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    if (!(valid && kgrp == 0)) sc[u][r] = kNegBig;
-                    mx[r] = fmaxf(mx[r], sc[u][r]);
-                }
-            }
-#pragma unroll
-            for (int h = 0; h < kNH; ++h) {
-                const float m_tile = wave_max_uniform(mx[h]);
-                const float m_new = fmaxf(m_ref[h], m_tile - kPShift);
-                const float alpha = fast_exp2(m_ref[h] - m_new);
-                l_lane[h] *= alpha;
-                acc[0][0][h] *= alpha;
-                acc[1][0][h] *= alpha;
-                m_ref[h] = m_new;
-            }
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float pw = fast_exp2(sc[u][r] - m_ref[r]);       // 0 for masked / non-row lanes
-                    l_lane[r] += pw;
-                    if (kgrp == 0) s_p[r * kPStride + p_slot(u, arow >> 2, arow & 3)] = (half_t)pw;
-                }
-            // ---- P.V: (item, slab) pairs along k; transposed LDS reads turn row-major V rows into the dense operand
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const half8_t pa = load_pa(i);
-#pragma unroll
-                for (int a = 0; a < 2; ++a) {
-                    half4_t vb[4];
-#pragma unroll
-                    for (int eh = 0; eh < 2; ++eh) {
-                        *(uint4_t*)(s_vrows + (2 * kgrp + ((lane >> 3) & 1)) * 64 + 8 * (lane & 7)) = vq[i][eh][a];
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                        for (int e = 0; e < 2; ++e)
-                            vb[2 * eh + e] = lds_read_tr16(lsm, rows_off + (uint32_t)((2 * kgrp + e) * 64 + 16 * tj + 4 * tq) * 2);
-                        __builtin_amdgcn_wave_barrier();
-                    }
-                    const half16_t bop = {vb[0][0], vb[0][1], vb[0][2], vb[0][3], vb[1][0], vb[1][1], vb[1][2], vb[1][3],
-                                          vb[2][0], vb[2][1], vb[2][2], vb[2][3], vb[3][0], vb[3][1], vb[3][2], vb[3][3]};
-                    acc[a][0] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(pa, bop, acc[a][0], sm_idx, 0, 0);
-                }
-            }
-        }
-        // hand the weight sums over in the stream's form: head lane % 4 in each lane (here: all of it in lanes 0..3)
-        float tot = 0.f;
-#pragma unroll
-        for (int h = 0; h < kNH; ++h) {
-            const float t = wave_sum(l_lane[h]);
-            tot = (lane == h) ? t : tot;
-        }
-        l_own = tot;
-    }
-
-    // ================================================================================== stream
-    {
-        // Lane roles.  Code loads and the K side: lane L of the wave handles token L of the tile; the token's class
-        // is c = L / 16 and its rank r = L % 16.  The int8 MFMA leaves lane (4 c + h, k-group g) with head h's
-        // scores of tokens (c, 4 g + i), i = 0..3: from there on a lane works for one head (tq) and one class (tj).
-        // K gather: this lane visits sub-space (step XOR xr) mod M at every step and reads slot (step XOR xr)
-        const uint32_t xr = lane & 31;
-        const uint32_t kr = xr & (M - 1);                            // XOR applied to the code byte index
-        static_assert(L::lut == 0, "the table gather address is an absolute LDS address below 64 KB");
+    // ---- K side of a 64-token tile (used by the stream and by the anchor entries that have no FP16 K row).
+    // Lane L handles token L of the tile; the token's class is c = L / 16 and its rank r = L % 16.  The int8 MFMA
+    // leaves lane (4 c + h, k-group g) with head h's scores of tokens (c, 4 g + i), i = 0..3: from there on a lane
+    // works for one head (tq) and one class (tj).
+    // K gather: this lane visits sub-space (step XOR xr) mod M at every step and reads slot (step XOR xr)
+    // (the constants are made where they are used, for the anchors and again for the stream: holding them across
+    // the anchor entries would cost the registers those need)
+    struct KConst {
         uint32_t ksel[4], kc[CW];
+        int4_t k_wgt;
+        uint32_t kr;
+        float lut_q;
+    };
+    static_assert(L::lut == 0, "the table gather address is an absolute LDS address below 64 KB");
+    auto make_kconst = [&](int ln) -> KConst {
+        KConst c;
+        const uint32_t xr = ln & 31;
+        c.kr = xr & (M - 1);                                         // XOR applied to the code byte index
 #pragma unroll
-        for (int j = 0; j < 4; ++j) ksel[j] = 0x0c0c0000u | ((4u + (uint32_t)(j ^ (kr & 3))) << 8) | (uint32_t)j;
+        for (int j = 0; j < 4; ++j) c.ksel[j] = 0x0c0c0000u | ((4u + (uint32_t)(j ^ (c.kr & 3))) << 8) | (uint32_t)j;
 #pragma unroll
         for (int i = 0; i < CW; ++i) {
-            kc[i] = 0;
+            c.kc[i] = 0;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) kc[i] |= ((xr ^ (uint32_t)(4 * i + j)) << 3) << (8 * j);
+            for (int j = 0; j < 4; ++j) c.kc[i] |= ((xr ^ (uint32_t)(4 * i + j)) << 3) << (8 * j);
         }
         // constant operand of the int8 MFMA: column 4 g + h takes, from k-group g only, the (lo, hi) bytes of head h
         // with the weights (1, -128)
-        int4_t k_wgt;
-        {
-            const int col_blk = (lane & 15) >> 2, col_h = lane & 3;
+        const int col_blk = (ln & 15) >> 2, col_h = ln & 3, kg = ln >> 4;
 #pragma unroll
-            for (int dw = 0; dw < 4; ++dw) {
-                uint32_t wv = 0;
+        for (int dw = 0; dw < 4; ++dw) {
+            uint32_t wv = 0;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int i = 4 * dw + j;                              // byte of the 16-byte operand
-                    const uint32_t wt = (i & 1) ? 0x80u : 0x01u;           // -128 on hi bytes, 1 on lo bytes
-                    if (kgrp == col_blk && ((i & 7) >> 1) == col_h) wv |= wt << (8 * j);
+            for (int j = 0; j < 4; ++j) {
+                const int i = 4 * dw + j;                              // byte of the 16-byte operand
+                const uint32_t wt = (i & 1) ? 0x80u : 0x01u;           // -128 on hi bytes, 1 on lo bytes
+                if (kg == col_blk && ((i & 7) >> 1) == col_h) wv |= wt << (8 * j);
+            }
+            c.k_wgt[dw] = (int)wv;
+        }
+        // the table quantum of this lane's head
+        c.lut_q = ((const float*)s_misc)[12];
+#pragma unroll
+        for (int h = 1; h < kNH; ++h) c.lut_q = (col_h == h) ? ((const float*)s_misc)[12 + h] : c.lut_q;
+        return c;
+    };
+    // integer scores (in table quanta) of the tile whose K code dwords are kw_in, lane = token
+    auto k_scores = [&](const KConst& c, const uint32_t (&kw_in)[CW]) -> int4_t {
+        // Code dwords are XOR-permuted so that step s finds the code of sub-space (s XOR kr) at a compile-time
+        // register and a per-lane constant byte selector.
+        uint32_t kw[CW];
+#pragma unroll
+        for (int i = 0; i < CW; ++i) kw[i] = kw_in[i];
+#pragma unroll
+        for (int bit = 0; (4 << bit) < M; ++bit) {
+            const bool sw = (c.kr >> (2 + bit)) & 1u;
+#pragma unroll
+            for (int i = 0; i < CW; ++i) {
+                if (!(i & (1 << bit))) {
+                    const uint32_t a = kw[i], b2 = kw[i | (1 << bit)];
+                    kw[i] = sw ? b2 : a;
+                    kw[i | (1 << bit)] = sw ? a : b2;
                 }
-                k_wgt[dw] = (int)wv;
             }
         }
+        // One table read per (token, sub-space): the address (code << 8 | slot << 3) is a single byte permute
+        // of the code dword and a per-lane constant.  Two entries (16 bytes) are this lane's row of the int8
+        // MFMA's first operand (row = rank, k-group = class); the constant second operand routes them.
+        // (all gathers of a batch of 16 sub-spaces are issued before the first of them is waited for: with four
+        // waves per SIMD a chain of gather -> wait -> MFMA steps leaves the LDS latency exposed)
+        int4_t si = {0, 0, 0, 0};
+        constexpr int KB = M < 16 ? M : 16;
+#pragma unroll
+        for (int s0 = 0; s0 < M; s0 += KB) {
+            uint2_t ent[KB];
+#pragma unroll
+            for (int u = 0; u < KB; ++u) {
+                const int st = s0 + u;
+                ent[u] = *(const lds_uint2*)(uintptr_t)__builtin_amdgcn_perm(kw[st >> 2], c.kc[st >> 2], c.ksel[st & 3]);
+            }
+            __builtin_amdgcn_sched_barrier(0);                           // nothing moves across: gathers first, then the MFMAs
+#pragma unroll
+            for (int u = 0; u < KB; u += 2)
+                si = __builtin_amdgcn_mfma_i32_16x16x64_i8(int4_t{(int)ent[u][0], (int)ent[u][1], (int)ent[u + 1][0], (int)ent[u + 1][1]},
+                                                           c.k_wgt, si, 0, 0, 0);
+        }
+        return si;
+    };
+    // max / sum over the lanes that work for the same head (lane % 4), result in all of them
+    auto head_max = [&](float v) -> float {
+        v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x124, 0xf, 0xf, true)));   // row_ror:4
+        v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x128, 0xf, 0xf, true)));   // row_ror:8
+        v = fmaxf(v, __shfl_xor(v, 16, 64));
+        return fmaxf(v, __shfl_xor(v, 32, 64));
+    };
+    auto head_sum = [&](float v) -> float {
+        v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x124, 0xf, 0xf, true));
+        v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x128, 0xf, 0xf, true));
+        v += __shfl_xor(v, 16, 64);
+        return v + __shfl_xor(v, 32, 64);
+    };
+
+    // ================================================================================== anchors
+    // Entries of the two anchor lists.  A K entry (token t, FP16 K row) needs V_eff(t): the FP16 V row if t is in the
+    // V list too, else the centroids of t's V codes.  A V entry (token t, FP16 V row) whose token is not a K anchor
+    // needs the score of t's K codes.  Tiles of entries are dealt round-robin to the workgroups (balanced by list
+    // index, not by position: anchors cluster at the head and tail of a context) and statically to the waves: wave w
+    // takes the workgroup's tiles w, w + 16, ... before it joins the stream.
+    //   K tile (16 entries)  scores q.K_row on the dense MFMA, the K rows going straight from global memory into the
+    //                        operand (entry along n, 8 channels per lane);
+    //   V tile (32 entries)  scores from the K codes through the lookup table, exactly as the stream does it.
+    // Values: a lane owns channels 2 lane, 2 lane + 1 of all four heads.  Per pair of entries it holds its two channels of
+    // both rows (of the FP16 row: one coalesced 256-byte load per entry; of the centroids: from the V table in LDS, the
+    // entry's code bytes being staged in the wave's area), and the pair's weights come back from the staging area as
+    // fp16 pairs: one packed dot product per head and channel adds two entries.
+    // code loads run one tile ahead of their use: HBM latency hides behind the previous tile's work
+    auto load_tile = [&](int64_t tile, uint32_t (&kw_)[CW], uint32_t (&vw_)[CW]) {
+        const int64_t tok_ = t0 + tile * 64 + lane;
+        const int64_t ltok = (tok_ < p.N) ? tok_ : (p.N - 1);        // tokens past the range are masked, not skipped
+        if (CW == 2) {
+            const uint2_t a = *(const uint2_t*)(ck + ltok * M), c = *(const uint2_t*)(cv + ltok * M);
+            kw_[0] = a[0]; kw_[1] = a[1]; vw_[0] = c[0]; vw_[1] = c[1];
+        } else {
+#pragma unroll
+            for (int i = 0; i < CW / 4; ++i) {
+                const uint4_t a = *(const uint4_t*)(ck + ltok * M + 16 * i), c = *(const uint4_t*)(cv + ltok * M + 16 * i);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { kw_[4 * i + e] = a[e]; vw_[4 * i + e] = c[e]; }
+            }
+        }
+    };
+    const int64_t n_tiles = (t1 - t0 + 63) >> 6;
+    uint32_t kw_next[CW], vw_next[CW];
+    if (T_first < n_atiles) {
+        typedef __attribute__((address_space(3))) uint8_t lds_u8;
+        typedef __attribute__((address_space(3))) uint32_t lds_u32;
+        typedef __attribute__((address_space(3))) uint2_t lds_u32x2;
+        typedef __attribute__((address_space(3))) uint4_t lds_u32x4;
+        const int32_t* info_bg = p.info + (int64_t)bg * (p.k_k + p.k_v);
+        const half_t* s_qh = (const half_t*)(smem + L::qh);               // Q as MFMA A operand: row = head
+        float l_lane[kNH] = {0.f, 0.f, 0.f, 0.f};                        // K tiles: per-lane shares of the weight sums, per head
+        float av[kNH][2];                                                // value sums: head h, channels 2 lane, 2 lane + 1
+#pragma unroll
+        for (int h = 0; h < kNH; ++h) av[h][0] = av[h][1] = 0.f;
+        const uint32_t stg_b = lds0 + (uint32_t)(L::pst + wave * kStgBytes);      // staged code rows: [entry][M] bytes
+        static_assert(32 * M <= kStgBytes, "the code rows of a K tile fit the wave's staging area");
+        const uint32_t m_lane = (uint32_t)(2 * lane) / DSUB;                      // sub-space of this lane's two channels
+        const uint32_t vtab = lds0 + (uint32_t)L::cbv + 4u * (uint32_t)lane;      // + code << 8: this lane's channels of a centroid row
+        // weights of a tile's entries, for the value sums: fp16 pairs of two consecutive entries, [pair][head] (16 bytes per
+        // pair, read back by all lanes at once); after the code rows in the staging area
+        constexpr int kWOff = 1024;
+        static_assert(32 * M <= kWOff && kWOff + 32 * 16 <= kStgBytes, "code rows and weights share the wave's staging area");
+        const uint32_t stg_wt = stg_b + kWOff;
+        // adds entries t, t + 1 (weights of pair `pair`, this lane's two channels of their V rows in va, vb)
+        auto add_pair = [&](int pair, uint32_t va_, uint32_t vb_) {
+            const uint4_t w4 = *(const lds_u32x4*)(uintptr_t)(stg_wt + 16u * (uint32_t)pair);
+            const half2_t lo = __builtin_bit_cast(half2_t, __builtin_amdgcn_perm(vb_, va_, 0x05040100u));   // channel 2 lane of both entries
+            const half2_t hi = __builtin_bit_cast(half2_t, __builtin_amdgcn_perm(vb_, va_, 0x07060302u));   // channel 2 lane + 1
+#pragma unroll
+            for (int h = 0; h < kNH; ++h) {
+                const uint32_t w_h = w4[h];   // (a bit_cast taken straight from the vector element reads element 0 for every h)
+                const half2_t wh = __builtin_bit_cast(half2_t, w_h);
+                av[h][0] = __builtin_amdgcn_fdot2(lo, wh, av[h][0], false);
+                av[h][1] = __builtin_amdgcn_fdot2(hi, wh, av[h][1], false);
+            }
+        };
+        auto pack2 = [](float a, float b) -> uint32_t {
+            return (uint32_t)__builtin_bit_cast(unsigned short, (half_t)a) | ((uint32_t)__builtin_bit_cast(unsigned short, (half_t)b) << 16);
+        };
+        // moves the reference maxima to cover a tile whose largest scores are m_tile[h], rescaling what was summed so far
+        auto move_reference = [&](const float (&m_tile)[kNH]) {
+            float a_own = 1.f;
+#pragma unroll
+            for (int h = 0; h < kNH; ++h) {
+                const float m_new = fmaxf(m_ref[h], m_tile[h] - kPShift);
+                const float alpha = fast_exp2(m_ref[h] - m_new);
+                l_lane[h] *= alpha;
+                av[h][0] *= alpha;
+                av[h][1] *= alpha;
+                a_own = (tq == h) ? alpha : a_own;
+                m_ref[h] = m_new;
+            }
+            l_own *= a_own;
+        };
+        for (int T = T_first; T < n_atiles; T += p.S * kDaWaves) {
+            // the tile's tokens, cross membership, code rows and FP16 rows are in pre_tok, pre_info, pre_codes, pre_rows
+            // (the first tile's since the prologue, a further tile's since the end of the tile before)
+            if (T < ntk) {
+                // ------------------------------------------------------------------ K tile: entries 32 T .. 32 T + 31
+                const int e0 = 16 * T;
+                int my_tok = 0, my_part = -1, my_valid = 0;               // lanes 0..15 each own one entry
+                if (lane < 16 && e0 + lane < p.k_k) { my_valid = 1; my_tok = pre_tok; my_part = pre_info; }
+                uint4_t kb[4];
+#pragma unroll
+                for (int st = 0; st < 4; ++st) kb[st] = uint4_t{pre_rows[4 * st], pre_rows[4 * st + 1], pre_rows[4 * st + 2], pre_rows[4 * st + 3]};
+                // V code rows of the entries without an FP16 V row
+                __builtin_amdgcn_wave_barrier();                           // the previous tile's readers are done
+                if (my_valid && my_part < 0) {
+                    if constexpr (CW == 2) {
+                        *(lds_u32x2*)(uintptr_t)(stg_b + 8u * lane) = uint2_t{pre_codes[0], pre_codes[1]};
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < CW / 4; ++i)
+                            *(lds_u32x4*)(uintptr_t)(stg_b + (uint32_t)(4 * CW) * lane + 16u * i) =
+                                uint4_t{pre_codes[4 * i], pre_codes[4 * i + 1], pre_codes[4 * i + 2], pre_codes[4 * i + 3]};
+                    }
+                }
+                // scores: lanes 0..15 hold head r of entry lane
+                float sc[4];
+                {
+                    float4_t c4 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int st = 0; st < 4; ++st) {
+                        half8_t qa = *(const half8_t*)(s_qh + (arow & 3) * kD + 32 * st + 8 * kgrp);
+                        if (arow >= kNH) qa = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                        c4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa, __builtin_bit_cast(half8_t, kb[st]), c4, 0, 0, 0);
+                    }
+                    const bool on = kgrp == 0 && e0 + arow < p.k_k;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) sc[r] = on ? c4[r] * p.c1 : kNegBig;
+                }
+                float m_tile[kNH];
+#pragma unroll
+                for (int h = 0; h < kNH; ++h) m_tile[h] = wave_max_uniform(sc[h]);
+                move_reference(m_tile);
+                float pw[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    pw[r] = fast_exp2(sc[r] - m_ref[r]);                  // 0 for lanes without an entry
+                    l_lane[r] += pw[r];
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();                           // the staged code rows are visible
+                // values.  The weights go to the staging area as fp16 pairs (lane n holds entry n: even lanes pair up
+                // with their right neighbour).  First pass, all 16 entries without a branch: the centroids of the staged
+                // codes, with weight zero where the entry has an FP16 V row (or does not exist).  Second pass, only if there
+                // is such an entry: the FP16 rows, with the weights of exactly those entries.
+                const unsigned long long both64 = __ballot(my_part >= 0);
+                auto put_weights = [&](bool coded_pass) {
+                    const bool mine = (((both64 >> arow) & 1ull) == 0ull) == coded_pass;
+                    uint4_t w4;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float a = mine ? pw[r] : 0.f;
+                        const float b = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, a), 0xB1, 0xf, 0xf, true));   // quad_perm [1,0,3,2]
+                        w4[r] = pack2(a, b);
+                    }
+                    if (kgrp == 0 && (lane & 1) == 0) *(lds_u32x4*)(uintptr_t)(stg_wt + 16u * (uint32_t)(arow >> 1)) = w4;
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                };
+                put_weights(true);
+#pragma unroll
+                for (int tb = 0; tb < 16; tb += 8) {
+                    uint32_t code[8], v2[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) code[k] = *(const lds_u8*)(uintptr_t)(stg_b + (uint32_t)((tb + k) * M) + m_lane);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v2[k] = *(const lds_u32*)(uintptr_t)(vtab + (code[k] << 8));
+#pragma unroll
+                    for (int k = 0; k < 8; k += 2) add_pair((tb + k) >> 1, v2[k], v2[k + 1]);
+                }
+                if (both64 != 0ull) {
+                    __builtin_amdgcn_wave_barrier();
+                    put_weights(false);
+#pragma unroll 1
+                    for (int pr = 0; pr < 8; ++pr) {
+                        if (((both64 >> (2 * pr)) & 3ull) == 0ull) continue;
+                        uint32_t v2[2];
+#pragma unroll
+                        for (int k = 0; k < 2; ++k) {
+                            const int part = __builtin_amdgcn_readlane(my_part, 2 * pr + k);
+                            v2[k] = 0u;
+                            if (part >= 0) v2[k] = *(const uint32_t*)(p.rows_v + ((int64_t)bg * p.k_v + part) * kD + 2 * lane);
+                        }
+                        add_pair(pr, v2[0], v2[1]);
+                    }
+                }
+            } else {
+                // ------------------------------------------------------------------ V tile: entries 64 (T - ntk) + lane
+                const int j0 = 32 * (T - ntk);
+                const bool in_list = lane < 32 && j0 + lane < p.k_v;
+                int tok = 0, skip = 1;
+                if (in_list) { tok = pre_tok; skip = pre_info; }
+                (void)tok;
+                const uint32_t (&va)[32] = pre_rows;
+                const uint32_t (&kw)[CW] = pre_codes;
+                const unsigned long long keep64 = __ballot(skip == 0);     // entries to process
+                int ln = lane;
+                asm volatile("" : "+v"(ln));                               // (a value of its own: not merged with the stream's copy)
+                const KConst kcst = make_kconst(ln);
+                const int4_t si = k_scores(kcst, kw);
+                // register i of lane (4 c + h, g) = entry 16 c + 4 g + i, head h (classes 2 and 3 are empty: keep bits 0)
+                const uint32_t keep_bits = (uint32_t)(keep64 >> (32 * (tj >> 1) + 16 * (tj & 1) + 4 * kgrp));
+                float sr[4], lm = kNegBig;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    sr[i] = (float)si[i] * kcst.lut_q;
+                    lm = fmaxf(lm, ((keep_bits >> i) & 1u) ? sr[i] : kNegBig);
+                }
+                lm = head_max(lm);
+                float m_tile[kNH];
+#pragma unroll
+                for (int h = 0; h < kNH; ++h) m_tile[h] = lane_bcast(lm, h);       // lanes 0..3 work for heads 0..3
+                move_reference(m_tile);
+                float neg_m = -m_ref[0];
+#pragma unroll
+                for (int h = 1; h < kNH; ++h) neg_m = (tq == h) ? -m_ref[h] : neg_m;
+                float pw[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    pw[i] = ((keep_bits >> i) & 1u) ? fast_exp2(sr[i] + neg_m) : 0.f;
+                    l_own += pw[i];
+                }
+                // values: register i of lane (4 c + h, g) is entry 16 c + 4 g + i, so a lane holds two pairs of its head
+                __builtin_amdgcn_wave_barrier();
+                *(lds_u32*)(uintptr_t)(stg_wt + 16u * (uint32_t)(8 * tj + 2 * kgrp) + 4u * (uint32_t)tq) = pack2(pw[0], pw[1]);
+                *(lds_u32*)(uintptr_t)(stg_wt + 16u * (uint32_t)(8 * tj + 2 * kgrp + 1) + 4u * (uint32_t)tq) = pack2(pw[2], pw[3]);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int k = 0; k < 32; k += 2) add_pair(k >> 1, va[k], va[k + 1]);
+            }
+            // a further tile of this wave: fetch it the plain way (its cross membership was worked out in the prologue)
+            const int Tn = T + p.S * kDaWaves;
+            if (Tn < n_atiles) {
+#pragma unroll
+                for (int i = 0; i < CW; ++i) pre_codes[i] = 0u;
+                if (Tn < ntk) {
+                    const int e = 16 * Tn + lane;
+                    if (lane < 16 && e < p.k_k) {
+                        pre_tok = idx_k[e];
+                        pre_info = info_bg[e];
+                        if (pre_info < 0) load_codes(cv + (int64_t)pre_tok * M, pre_codes);
+                    }
+                    load_k_rows(16 * Tn, pre_rows);
+                } else {
+                    const int j = 32 * (Tn - ntk) + lane;
+                    if (lane < 32 && j < p.k_v) {
+                        pre_tok = idx_v[j];
+                        pre_info = info_bg[p.k_k + j];
+                        load_codes(ck + (int64_t)pre_tok * M, pre_codes);
+                    }
+                    load_v_rows(32 * (Tn - ntk), pre_rows);
+                }
+            }
+        }
+        // hand over to the stream's forms.  Weight sums: head lane % 4 in each lane (the K tiles' share goes to lanes 0..3).
+#pragma unroll
+        for (int h = 0; h < kNH; ++h) {
+            const float t = wave_sum(l_lane[h]);
+            l_own += (lane == h) ? t : 0.f;
+        }
+        // Value sums: into the accumulators of MFMA (a, 0), whose register h in lane (n, cls) is head h, channel
+        // 16 (4 a + cls) + n.  Two heads at a time through the wave's staging area.
+        float* s_f = (float*)(smem + L::pst + wave * kStgBytes);            // [2][128] fp32
+        static_assert(2 * kD * 4 <= kStgBytes, "two heads of value sums fit the wave's staging area");
+#pragma unroll
+        for (int hp = 0; hp < 2; ++hp) {
+            __builtin_amdgcn_wave_barrier();
+            *(float2*)(s_f + 2 * lane) = float2{av[2 * hp][0], av[2 * hp][1]};
+            *(float2*)(s_f + kD + 2 * lane) = float2{av[2 * hp + 1][0], av[2 * hp + 1][1]};
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                acc_anchor[a][2 * hp] = s_f[16 * (4 * a + kgrp) + (lane & 15)];
+                acc_anchor[a][2 * hp + 1] = s_f[kD + 16 * (4 * a + kgrp) + (lane & 15)];
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // ================================================================================== stream
+    float4_t acc[2][4];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int rho = 0; rho < 4; ++rho) acc[a][rho] = rho == 0 ? acc_anchor[a] : float4_t{0.f, 0.f, 0.f, 0.f};
+    {
+        const KConst kcst = make_kconst(lane);
         // V gather address = table base | code << 8 | byte offset of the 8-byte piece inside the code's row, the piece
         // being chunk tq of slab 4 a + (tj + rho) % 4 (128 a goes into the instruction's immediate): one byte permute
         // of a staged code dword and a per-lane constant
         static_assert((L::cbv & 0xffff) == 0, "the V table base must be a multiple of 64 KB");
-        const uint32_t lds0 = (uint32_t)(uintptr_t)lsm;
         uint32_t v_const[4];
 #pragma unroll
         for (int rho = 0; rho < 4; ++rho)
@@ -833,35 +1095,15 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         const uint32_t mask_dw = (uint32_t)(tj >> 1);
         const uint32_t mask_sh = (uint32_t)(16 * (tj & 1) + 4 * kgrp);
 
-        const int64_t n_tiles = (t1 - t0 + 63) >> 6;
         auto grab_tile = [&]() -> int64_t {
             int t = 0;
             if (lane == 0) t = atomicAdd(&s_misc[8], 1);
             return (int64_t)__builtin_amdgcn_readfirstlane(t);
         };
-        // code loads run one tile ahead of their use: HBM latency hides behind the previous tile's work
-        auto load_codes = [&](int64_t tile, uint32_t (&kw_)[CW], uint32_t (&vw_)[CW]) {
-            const int64_t tok_ = t0 + tile * 64 + lane;
-            const int64_t ltok = (tok_ < p.N) ? tok_ : (p.N - 1);        // tokens past the range are masked, not skipped
-            if (CW == 2) {
-                const uint2_t a = *(const uint2_t*)(ck + ltok * M), c = *(const uint2_t*)(cv + ltok * M);
-                kw_[0] = a[0]; kw_[1] = a[1]; vw_[0] = c[0]; vw_[1] = c[1];
-            } else {
+        // this lane's head: running reference
+        float neg_m = -m_ref[0];
 #pragma unroll
-                for (int i = 0; i < CW / 4; ++i) {
-                    const uint4_t a = *(const uint4_t*)(ck + ltok * M + 16 * i), c = *(const uint4_t*)(cv + ltok * M + 16 * i);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) { kw_[4 * i + e] = a[e]; vw_[4 * i + e] = c[e]; }
-                }
-            }
-        };
-        // this lane's head: table quantum and running reference
-        float lut_q = ((const float*)s_misc)[12], neg_m = -m_ref[0];
-#pragma unroll
-        for (int h = 1; h < kNH; ++h) {
-            lut_q = (tq == h) ? ((const float*)s_misc)[12 + h] : lut_q;
-            neg_m = (tq == h) ? -m_ref[h] : neg_m;
-        }
+        for (int h = 1; h < kNH; ++h) neg_m = (tq == h) ? -m_ref[h] : neg_m;
 
         auto do_tile = [&](int64_t tile, const uint32_t (&kw_in)[CW], const uint32_t (&vw)[CW]) {
             // ---- V code bytes into the staging area (first round; d = 4 stages its second half later)
@@ -888,57 +1130,19 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             if constexpr (DSUB == 4) stage_d4(0);
             const uint32_t mw = s_mask[(2 * (uint32_t)tile + mask_dw) & (L::mask_words - 1)];
 
-            // ---- K side: scores in log2 units.  Code dwords are XOR-permuted so that step s finds the code of
-            // sub-space (s XOR kr) at a compile-time register and a per-lane constant byte selector.
-            uint32_t kw[CW];
-#pragma unroll
-            for (int i = 0; i < CW; ++i) kw[i] = kw_in[i];
-#pragma unroll
-            for (int bit = 0; (4 << bit) < M; ++bit) {
-                const bool sw = (kr >> (2 + bit)) & 1u;
-#pragma unroll
-                for (int i = 0; i < CW; ++i) {
-                    if (!(i & (1 << bit))) {
-                        const uint32_t a = kw[i], c = kw[i | (1 << bit)];
-                        kw[i] = sw ? c : a;
-                        kw[i | (1 << bit)] = sw ? a : c;
-                    }
-                }
-            }
-            // One table read per (token, sub-space): the address (code << 8 | slot << 3) is a single byte permute
-            // of the code dword and a per-lane constant.  Two entries (16 bytes) are this lane's row of the int8
-            // MFMA's first operand (row = rank, k-group = class); the constant second operand routes them.
-            // (all gathers of a batch of 16 sub-spaces are issued before the first of them is waited for: with four
-            // waves per SIMD a chain of gather -> wait -> MFMA steps leaves the LDS latency exposed)
-            int4_t si = {0, 0, 0, 0};
-            constexpr int KB = M < 16 ? M : 16;
-#pragma unroll
-            for (int s0 = 0; s0 < M; s0 += KB) {
-                uint2_t ent[KB];
-#pragma unroll
-                for (int u = 0; u < KB; ++u) {
-                    const int st = s0 + u;
-                    ent[u] = *(const lds_uint2*)(uintptr_t)__builtin_amdgcn_perm(kw[st >> 2], kc[st >> 2], ksel[st & 3]);
-                }
-#pragma unroll
-                for (int u = 0; u < KB; u += 2)
-                    si = __builtin_amdgcn_mfma_i32_16x16x64_i8(int4_t{(int)ent[u][0], (int)ent[u][1], (int)ent[u + 1][0], (int)ent[u + 1][1]},
-                                                               k_wgt, si, 0, 0, 0);
-            }
+            // ---- K side: scores in table quanta
+            const int4_t si = k_scores(kcst, kw_in);
             // ---- softmax: register i = token (tj, 4 kgrp + i), head tq.  x = score - reference.
             const uint32_t keep_bits = ~mw >> mask_sh;                 // bit i set: token i is neither anchored nor past the range
             float x[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) x[i] = fmaf((float)si[i], lut_q, neg_m);
+            for (int i = 0; i < 4; ++i) x[i] = fmaf((float)si[i], kcst.lut_q, neg_m);
             if (__any(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])) > kPShift)) {
                 // some score exceeds the running maximum by more than the head room: move the reference, rescale
                 float lm = kNegBig;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) lm = fmaxf(lm, ((keep_bits >> i) & 1u) ? x[i] : kNegBig);
-                lm = fmaxf(lm, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, lm), 0x124, 0xf, 0xf, true)));   // row_ror:4
-                lm = fmaxf(lm, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, lm), 0x128, 0xf, 0xf, true)));   // row_ror:8
-                lm = fmaxf(lm, __shfl_xor(lm, 16, 64));
-                lm = fmaxf(lm, __shfl_xor(lm, 32, 64));                // largest unmasked x of head tq in the tile
+                lm = head_max(lm);                                      // largest unmasked x of head tq in the tile
                 const float m_old = -neg_m;
                 const float m_new = fmaxf(m_old, (lm - neg_m) - kPShift);
                 const float alpha = fast_exp2(m_old - m_new);
@@ -959,7 +1163,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                         }
                 }
 #pragma unroll
-                for (int i = 0; i < 4; ++i) x[i] = fmaf((float)si[i], lut_q, neg_m);
+                for (int i = 0; i < 4; ++i) x[i] = fmaf((float)si[i], kcst.lut_q, neg_m);
             }
             uint4_t pa4;
 #pragma unroll
@@ -975,53 +1179,73 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             __builtin_amdgcn_wave_barrier();
 
             // ---- V side: MFMA (a, rho): element quad e4 of this lane's k-group = token (tj, rank(e4)) with slab
-            // 4 a + (tj + rho) % 4, the four rows of a transposed read being the four classes
+            // 4 a + (tj + rho) % 4, the four rows of a transposed read being the four classes.  The operand reads of
+            // kVDepth MFMAs are in flight at any time: a wave has few neighbours on its SIMD to hide the LDS latency.
+            if constexpr (DSUB != 4) {
+                uint32_t vt[2][4][2];                                  // staged code dwords: [half][element quad][dword]
 #pragma unroll
-            for (int a = 0; a < 2; ++a) {
-                constexpr int VD = (DSUB == 4) ? 4 : 2;                // staged code dwords per token and read
-                uint32_t vt[4][VD];
-                if (a == 0 || DSUB != 16) {
-                    if constexpr (DSUB == 4) {
-                        if (a == 1) {
-                            __builtin_amdgcn_wave_barrier();
-                            stage_d4(1);
-                            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                            __builtin_amdgcn_wave_barrier();
-                        }
-                    }
+                for (int a = 0; a < (DSUB == 8 ? 2 : 1); ++a)
 #pragma unroll
                     for (int e4 = 0; e4 < 4; ++e4) {
-                        const uint32_t ad = ((e4 >> 1) ? stg_r1 : stg_r0) + (uint32_t)(SU * (e4 & 1)) + (DSUB == 8 ? 8u * a : 0u);
-                        if constexpr (DSUB == 4) {
-                            const uint4_t r = *(const __attribute__((address_space(3))) uint4_t*)(uintptr_t)ad;
-#pragma unroll
-                            for (int u = 0; u < 4; ++u) vt[e4][u] = r[u];
-                        } else {
-                            const uint2_t r = *(const lds_uint2*)(uintptr_t)ad;
-                            vt[e4][0] = r[0]; vt[e4][1] = r[1];
-                        }
+                        const uint32_t ad = ((e4 >> 1) ? stg_r1 : stg_r0) + (uint32_t)(SU * (e4 & 1)) + 8u * a;
+                        const uint2_t r = *(const lds_uint2*)(uintptr_t)ad;
+                        vt[a][e4][0] = r[0]; vt[a][e4][1] = r[1];
                     }
-                }
-                auto fetch = [&](int rho, half4_t (&vb)[4]) {
+                auto fetch = [&](int u, half4_t (&vb)[4]) {
+                    const int a = u >> 2, rho = u & 3;
 #pragma unroll
                     for (int e4 = 0; e4 < 4; ++e4) {
                         uint32_t ad;
-                        if constexpr (DSUB == 8) ad = __builtin_amdgcn_perm(vt[e4][rho >> 1], v_const[rho], v_sel[rho & 1]);
-                        else if constexpr (DSUB == 16) ad = __builtin_amdgcn_perm(vt[e4][a], v_const[rho], 0x0c020000u | ((4u + (uint32_t)rho) << 8));
-                        else ad = __builtin_amdgcn_perm(vt[e4][rho], v_const[rho], v_sel[0]);
+                        if constexpr (DSUB == 8) ad = __builtin_amdgcn_perm(vt[a][e4][rho >> 1], v_const[rho], v_sel[rho & 1]);
+                        else ad = __builtin_amdgcn_perm(vt[0][e4][a], v_const[rho], 0x0c020000u | ((4u + (uint32_t)rho) << 8));
                         vb[e4] = lds_read_tr16_abs(ad + 128 * a);
                     }
                 };
-                half4_t vb0[4], vb1[4];
-                fetch(0, vb0);
+                constexpr int kVDepth = 3;
+                half4_t vb[kVDepth][4];
 #pragma unroll
-                for (int rho = 0; rho < 4; ++rho) {
-                    half4_t (&cur)[4] = (rho & 1) ? vb1 : vb0;
-                    half4_t (&nxt)[4] = (rho & 1) ? vb0 : vb1;
-                    if (rho + 1 < 4) fetch(rho + 1, nxt);
+                for (int u = 0; u < kVDepth; ++u) fetch(u, vb[u]);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    half4_t (&cur)[4] = vb[u % kVDepth];
                     const half16_t bop = {cur[0][0], cur[0][1], cur[0][2], cur[0][3], cur[1][0], cur[1][1], cur[1][2], cur[1][3],
                                           cur[2][0], cur[2][1], cur[2][2], cur[2][3], cur[3][0], cur[3][1], cur[3][2], cur[3][3]};
-                    acc[a][rho] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(pa, bop, acc[a][rho], sm_idx, 0, 0);
+                    acc[u >> 2][u & 3] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(pa, bop, acc[u >> 2][u & 3], sm_idx, 0, 0);
+                    if (u + kVDepth < 8) fetch(u + kVDepth, vb[u % kVDepth]);
+                }
+            } else {
+#pragma unroll
+                for (int a = 0; a < 2; ++a) {
+                    uint32_t vt[4][4];
+                    if (a == 1) {
+                        __builtin_amdgcn_wave_barrier();
+                        stage_d4(1);
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                    }
+#pragma unroll
+                    for (int e4 = 0; e4 < 4; ++e4) {
+                        const uint32_t ad = ((e4 >> 1) ? stg_r1 : stg_r0) + (uint32_t)(SU * (e4 & 1));
+                        const uint4_t r = *(const __attribute__((address_space(3))) uint4_t*)(uintptr_t)ad;
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) vt[e4][u] = r[u];
+                    }
+                    auto fetch = [&](int rho, half4_t (&vb)[4]) {
+#pragma unroll
+                        for (int e4 = 0; e4 < 4; ++e4)
+                            vb[e4] = lds_read_tr16_abs(__builtin_amdgcn_perm(vt[e4][rho], v_const[rho], v_sel[0]) + 128 * a);
+                    };
+                    half4_t vb0[4], vb1[4];
+                    fetch(0, vb0);
+#pragma unroll
+                    for (int rho = 0; rho < 4; ++rho) {
+                        half4_t (&cur)[4] = (rho & 1) ? vb1 : vb0;
+                        half4_t (&nxt)[4] = (rho & 1) ? vb0 : vb1;
+                        if (rho + 1 < 4) fetch(rho + 1, nxt);
+                        const half16_t bop = {cur[0][0], cur[0][1], cur[0][2], cur[0][3], cur[1][0], cur[1][1], cur[1][2], cur[1][3],
+                                              cur[2][0], cur[2][1], cur[2][2], cur[2][3], cur[3][0], cur[3][1], cur[3][2], cur[3][3]};
+                        acc[a][rho] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(pa, bop, acc[a][rho], sm_idx, 0, 0);
+                    }
                 }
             }
             __builtin_amdgcn_wave_barrier();
@@ -1030,15 +1254,14 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         // The next tile's codes are requested before the current tile is worked on.  The request is unconditional (a
         // wave that has no further tile re-reads the range's last one): a conditional load would cost register copies
         // on every tile.
-        uint32_t kw_next[CW], vw_next[CW];
-        int64_t tile = grab_tile();
-        load_codes(tile < n_tiles ? tile : n_tiles - 1, kw_next, vw_next);
+        int64_t tile = wave;                                          // the first tile of wave w is tile w
+        load_tile(tile < n_tiles ? tile : n_tiles - 1, kw_next, vw_next);
         while (tile < n_tiles) {
             uint32_t kw_c[CW], vw_c[CW];
 #pragma unroll
             for (int i = 0; i < CW; ++i) { kw_c[i] = kw_next[i]; vw_c[i] = vw_next[i]; }
             const int64_t tile_next = grab_tile();
-            load_codes(tile_next < n_tiles ? tile_next : n_tiles - 1, kw_next, vw_next);
+            load_tile(tile_next < n_tiles ? tile_next : n_tiles - 1, kw_next, vw_next);
             do_tile(tile, kw_c, vw_c);
             tile = tile_next;
         }
@@ -1048,11 +1271,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     // weight sums per head: add up the lanes that worked for the head
     float l_sum[kNH];
     {
-        float v = l_own;
-        v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x124, 0xf, 0xf, true));   // row_ror:4
-        v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x128, 0xf, 0xf, true));   // row_ror:8
-        v += __shfl_xor(v, 16, 64);
-        v += __shfl_xor(v, 32, 64);
+        const float v = head_sum(l_own);
 #pragma unroll
         for (int h = 0; h < kNH; ++h) l_sum[h] = lane_bcast(v, h);
     }
@@ -1462,7 +1681,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_ans_kernel(const DsParams p
 struct DaPlan {
     int S;
     int64_t chunk;
-    size_t off_part, off_done, off_stat, total;
+    size_t off_part, off_done, off_info, off_stat, total;
 };
 
 DaPlan da_plan(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans)
@@ -1480,10 +1699,10 @@ DaPlan da_plan(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans
     pl.chunk = chunk;
     pl.S = (int)((N + chunk - 1) / chunk);
     if (pl.S < 1) pl.S = 1;
-    (void)k_k; (void)k_v;
     size_t off = 0;
     pl.off_part = off; off += align_up((size_t)g.B * g.Hq * pl.S * (kD + 2) * sizeof(float));
     pl.off_done = off; off += align_up((size_t)g.B * g.Hkv * sizeof(unsigned long long));
+    pl.off_info = off; off += align_up((size_t)g.B * g.Hkv * (size_t)(k_k + k_v) * sizeof(int32_t));
     pl.off_stat = off; off += want_ans ? align_up((size_t)g.B * g.Hq * pl.S * 2 * sizeof(float)) : 0;
     pl.total = off;
     return pl;
@@ -1518,7 +1737,7 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     DaParams p;
     p.q = a.q; p.codes_k = a.codes_k; p.codes_v = a.codes_v; p.cb_k = a.cb_k; p.cb_v = a.cb_v;
     p.idx_k = a.idx_k; p.idx_v = a.idx_v; p.rows_k = a.rows_k; p.rows_v = a.rows_v;
-    p.part = part; p.out = a.out; p.done = (unsigned long long*)(w + pl.off_done); p.tag = next_launch_tag(); p.N = a.N; p.N_cap = a.N_cap; p.k_k = (int)a.k_k; p.k_v = (int)a.k_v;
+    p.part = part; p.out = a.out; p.done = (unsigned long long*)(w + pl.off_done); p.info = (int32_t*)(w + pl.off_info); p.tag = next_launch_tag(); p.N = a.N; p.N_cap = a.N_cap; p.k_k = (int)a.k_k; p.k_v = (int)a.k_v;
     p.c1 = a.scale * kLog2e; p.Hq = g.Hq; p.Hkv = g.Hkv; p.G = g.G; p.S = pl.S; p.chunk = pl.chunk;
     if (pl.S > 1024) return hipErrorInvalidValue;        // the in-kernel merge keeps one weight per slot in LDS
     const size_t shmem = Lds<DSUB>::total;

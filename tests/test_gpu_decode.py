@@ -72,6 +72,17 @@ def test_decode_anchor_edge_cases(oracle, k_k, k_v):
     _check_out(got, want, f"decode k_k={k_k} k_v={k_v}")
 
 
+@pytest.mark.parametrize("B,Hkv,N,k_k,k_v", [(8, 8, 6000, 2000, 1900),    # several anchor tiles per wave, lists held in LDS
+                                             (2, 2, 9000, 3500, 3100),    # lists too long for LDS: searched in global memory
+                                             (8, 8, 5000, 3300, 40)])     # one long list, one short
+def test_decode_long_anchor_lists(oracle, B, Hkv, N, k_k, k_v):
+    """Anchor lists that are long for the number of workgroups, with a large overlap between the K and the V list."""
+    d, Hq = 8, 4 * Hkv
+    c = _cache_from_kv(oracle, 70 + B, B, Hq, Hkv, N, d, k_k, k_v, anchors="random")
+    got, want = _run_decode(oracle, c, antkv.Geometry(B, Hq, Hkv, d), 1 / np.sqrt(128))
+    _check_out(got, want, f"decode B={B} N={N} k_k={k_k} k_v={k_v}")
+
+
 def test_decode_tiny_contexts(oracle):
     B, Hq, Hkv, d = 2, 4, 1, 8
     for N in (1, 2, 63, 64, 65):
