@@ -37,17 +37,50 @@ def algorithmic_bytes(w, k_k, k_v):
     return w.B * w.Hkv * per_bg + 2 * w.Hkv * w.M * w.C * w.d_sub * 2 + 2 * w.B * w.Hq * w.D * 2
 
 
-def measured_traffic(workload):
-    """HBM bytes per launch of the decode kernel from the committed hardware-counter summary (FETCH_SIZE + WRITE_SIZE,
-    scaled by the copy-kernel calibration), or None when no summary covers this workload."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"decode_attn_{workload}_hbm_traffic.txt")
+def kernel_source_digest():
+    """SHA-256 of the decode kernel's source file: the hardware-counter summaries record it, so that a figure measured on
+    an older kernel is not attached to a newer one."""
+    import hashlib
+    path = os.path.join(ROOT, "paper_2506_19505_amd", "csrc", "decode_attn.hip")
+    return hashlib.sha256(open(path, "rb").read()).hexdigest()
+
+
+def summary_fields(name):
+    """`key: value` lines of a text summary under profiles/ (empty when the file is missing)."""
+    fields = {}
     try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":", 1)[1])
+        for line in open(os.path.join(ROOT, "profiles", name)):
+            if ":" in line and not line.startswith((" ", "#", "\t")):
+                key, val = line.split(":", 1)
+                fields[key.strip()] = val.strip()
     except OSError:
         pass
-    return None
+    return fields
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of the decode kernel from the committed hardware-counter summary (FETCH_SIZE + WRITE_SIZE,
+    scaled by the copy-kernel calibration).  None when no summary covers this workload, or when the summary was taken
+    on another version of the kernel source (the reason is returned beside it)."""
+    f = summary_fields(f"decode_attn_{workload}_hbm_traffic.txt")
+    if "traffic_bytes_per_launch" not in f:
+        return None, "no hardware-counter summary for this workload"
+    if f.get("kernel_source_sha256") != kernel_source_digest():
+        return None, "the hardware-counter summary under profiles/ was taken on another version of decode_attn.hip"
+    return float(f["traffic_bytes_per_launch"]), None
+
+
+def lds_ceiling():
+    """Measured LDS read rate of the chip (conflict-free 8-byte reads, all CUs), GB/s, from profiles/lds_ceiling.txt."""
+    f = summary_fields("lds_ceiling.txt")
+    return float(f["lds_read_GBs_all_CUs"]) if "lds_read_GBs_all_CUs" in f else None
+
+
+def lds_bytes(w):
+    """LDS bytes one decode step moves by the kernel's design, per token and KV head: one 8-byte table entry per
+    sub-space (K side), the 256-byte V centroid row (V side), and the V codes written to and read back from the wave's
+    staging area."""
+    return w.B * w.Hkv * w.N * (8 * w.M + 2 * w.D + 2 * w.M)
 
 
 def main() -> int:
@@ -141,7 +174,8 @@ def main() -> int:
     def settle(fn, seconds=0.25):
         """Keep the GPU busy with `fn` until it has left its idle power state: after an idle spell (input
         generation on the host) the first ~30 ms of any kernel stream run at a lower clock, 10-15 % slower than
-        the sustained rate that a decode loop or a prefill sees.  Not part of the timed region or of --warmup."""
+        the sustained rate that a decode loop or a prefill sees.  Not part of the timed region or of --warmup;
+        returns the number of launches it made."""
         t_end = time.time() + seconds
         i = 0
         while time.time() < t_end:
@@ -149,48 +183,44 @@ def main() -> int:
                 fn(i)
                 i += 1
             torch.cuda.synchronize()
+        return i
 
-    settle(step)
+    settle_launches = settle(step)
     for i in range(args.warmup):
         step(i)
     ms_step = timed(args.steps, step)                          # headline: rotating over the cache copies
     ms_warm = timed(args.steps, lambda i: step(0))             # same buffers every step (cache-warm)
 
-    # dominant kernel alone, with HIP events recorded by the library around that launch on its stream
-    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-             for _ in range(min(args.steps, 400))]
-    for a, b in pairs:
-        a.record(); b.record()                                 # create the underlying HIP events
-    torch.cuda.synchronize()
-    for i, (a, b) in enumerate(pairs):
-        antkv.profile_next_decode(a, b)
-        step(i)
-    torch.cuda.synchronize()
-    ms_pairs = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
-    # A step is exactly one launch of the dominant kernel, so the kernel's average launch duration over the timed
-    # region is the region's length between its two HIP events divided by the launches in it.  Event pairs around
-    # every single launch read 5-6 us more: each pair fences the stream, so a launch can no longer ramp up while the
-    # previous one drains, and the pair's own signal latency is inside the interval; the profiler's per-dispatch
-    # durations agree with the region figure, not with the pairs.
+    # A step is exactly one launch of the dominant kernel (the library launches on torch's current stream, which is
+    # the stream the two events are recorded on), so the kernel's average launch duration over the timed region is
+    # the region's length between its two HIP events divided by the launches in it.
     ms_kernel = ms_step
 
     abytes = algorithmic_bytes(w, w.k, w.k)
-    traffic = measured_traffic(w.name)
+    traffic, traffic_note = measured_traffic(w.name)
     achieved = abytes / (ms_kernel * 1e-3) / 1e9
+    lds_peak = lds_ceiling()
+    lds_achieved = lds_bytes(w) / (ms_kernel * 1e-3) / 1e9
     result = {
         "metric": "decode-attn tokens/s at 128K ctx + achieved HBM GB/s (% peak); encode Mvec/s",
         "value": w.B * w.N / (ms_step * 1e-3),
         "unit": "context tokens/s (one layer, all KV heads)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "settle_launches": settle_launches,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i16-lut/f16-pv/f32-acc",
         "data": "synthetic (seeded N(0,1) K/V with channel outliers, k-means++ codebooks; stands in for LLaMA-3-8B / "
                 "Mistral-7B KV caches)",
         "config": {"workload": f"{w.name}: {w.description}", "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "N": w.N,
                    "d_sub": w.d_sub, "bits_per_element": w.bits_per_element, "anchors_per_head": w.k,
                    "cache_copies_rotated": len(caches)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": "decode_attn_kernel",
-                     "kernel_ms": ms_kernel, "kernel_ms_fenced_event_pairs": ms_pairs, "algorithmic_bytes": abytes},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_note": traffic_note,
+                     "kernel": "decode_attn_kernel", "kernel_ms": ms_kernel, "algorithmic_bytes": abytes},
+        # the same launch against the LDS: bytes the kernel's design moves through LDS per step over the chip's measured
+        # conflict-free LDS read rate (the published HBM peak above stays the headline bound)
+        "roofline_lds": {"bound": "lds", "achieved": lds_achieved, "peak": lds_peak, "unit": "GB/s",
+                         "frac": (lds_achieved / lds_peak) if lds_peak else None, "lds_bytes": lds_bytes(w),
+                         "peak_source": "profiles/lds_ceiling.txt (measured on this chip; no published figure)"},
         "extra": {"arithmetic": "u8 codes; int16 fixed-point q.centroid table; f16 softmax weights and V centroids into "
                                 "f32 MFMA accumulators; f32 online softmax; f16 output",
                   "decode_steps_per_s": w.B / (ms_step * 1e-3), "ms_per_step_warm": ms_warm,
@@ -198,8 +228,8 @@ def main() -> int:
                   "measured_copy_GBs": copy_gbs,
                   "step_GBs": abytes / (ms_step * 1e-3) / 1e9, "step_frac_of_peak": abytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
-    log(f"decode: {ms_step * 1e3:.1f} us/step rotating, {ms_warm * 1e3:.1f} us warm, kernel {ms_kernel * 1e3:.1f} us "
-        f"(fenced event pairs {ms_pairs * 1e3:.1f} us) -> {achieved:.0f} GB/s ({100 * achieved / HBM_PEAK_GBS:.1f}% of peak)")
+    log(f"decode: {ms_step * 1e3:.1f} us/step rotating, {ms_warm * 1e3:.1f} us warm -> {achieved:.0f} GB/s "
+        f"({100 * achieved / HBM_PEAK_GBS:.1f}% of peak); LDS {lds_achieved:.0f} GB/s")
 
     if not args.no_extras:
         # ------------------------------------------------------------ encode + anchor selection on the prefill shape
@@ -278,6 +308,31 @@ def main() -> int:
         log(f"cfg4 decode {ms_r[0] * 1e3:.0f} us; with re-selection {ms_r[r.k] * 1e3:.0f} us")
         del rt
         torch.cuda.empty_cache()
+
+        # ------------------------------------------------------------ the two small decode shapes (parity-test cases, not
+        # bench lines): their whole cache fits the last-level cache, so these are cache-resident times, launch-bound
+        for name in ("cfg0", "cfg1"):
+            sconf = CONFIGS[name]
+            sg = antkv.Geometry(sconf.B, sconf.Hq, sconf.Hkv, sconf.d_sub)
+            _, sks, svs = make_qkv(sconf.seed, 1, sconf.Hq, sconf.Hkv, 2048, 1, sconf.D)
+            scbk, scbv = dev(make_codebooks(sconf.seed, sks, sconf.d_sub, sconf.C, "k")), dev(make_codebooks(sconf.seed, svs, sconf.d_sub, sconf.C, "v"))
+            st = dict(q=dev(make_decode_query(sconf.seed, sconf.B, sconf.Hq, sconf.D)),
+                      ck=dev(random_codes(sconf.seed, "k", sconf.B, sconf.Hkv, sconf.N, sconf.M)),
+                      cv=dev(random_codes(sconf.seed, "v", sconf.B, sconf.Hkv, sconf.N, sconf.M)),
+                      ik=dev(random_anchor_sets(sconf.seed, "k", sconf.B, sconf.Hkv, sconf.N, sconf.k)),
+                      iv=dev(random_anchor_sets(sconf.seed, "v", sconf.B, sconf.Hkv, sconf.N, sconf.k)),
+                      rk=dev(normal_fp16(sconf.seed, "rows_k", (sconf.B, sconf.Hkv, sconf.k, sconf.D))),
+                      rv=dev(normal_fp16(sconf.seed, "rows_v", (sconf.B, sconf.Hkv, sconf.k, sconf.D))))
+            sws = antkv.DecodeWorkspace(sg, sconf.N, sconf.k, sconf.k, 0, devc)
+            fs = lambda i: antkv.decode_attn(sg, st["q"], sconf.scale, st["ck"], st["cv"], scbk, scbv, st["ik"], st["rk"], st["iv"],
+                                             st["rv"], workspace=sws)
+            settle(fs, 0.1)
+            ms_s = timed(500, fs)
+            result["extra"].update({f"{name}_decode_us_cache_resident": ms_s * 1e3,
+                                    f"{name}_workload": f"{name}: B{sconf.B}, N={sconf.N}, d_sub {sconf.d_sub}, {sconf.k} anchors per head "
+                                                        f"(random codes; {sconf.B * sconf.Hkv * sconf.N * sconf.M * 2 / 1e6:.1f} MB of codes, cache-resident)"})
+            log(f"{name} decode {ms_s * 1e3:.1f} us (cache-resident)")
+            del st, sws
 
         # ------------------------------------------------------------ 12-bit codebooks (4096 centroids): d32 = 0.375 bit, d16 = 0.75 bit
         w_ik = dev(random_anchor_sets(r.seed, "k", r.B, r.Hkv, r.N, r.k))
@@ -379,6 +434,19 @@ def main() -> int:
                                             f"{w.k} anchors/head, cache-shaped random codes) in {t_cpu:.1f} s wall, "
                                             f"fp16->fp64 widening included"}
         log(f"cpu oracle: {reps} steps in {t_cpu:.2f}s on {oracle.num_threads()} threads")
+        # the oracle's encode on a bounded sample of cfg3's K rows (the metric's "encode Mvec/s" leg)
+        e_tok = 4096
+        e_x = np.ascontiguousarray(pk[:, :, :e_tok])
+        e_reps, t0 = 0, time.time()
+        while e_reps < 1 or (time.time() - t0 < args.cpu_seconds / 2 and e_reps < 1000):
+            oracle.encode(e_x, pcbk)
+            e_reps += 1
+        t_enc = time.time() - t0
+        result["cpu_baseline"].update({
+            "encode_Mvec_per_s": e_reps * p.B * p.Hkv * e_tok / t_enc / 1e6,
+            "encode_sample": f"{e_reps} encodes of the first {e_tok} tokens of cfg3's K ({p.B * p.Hkv * e_tok} rows of 128 channels, "
+                             f"d_sub {p.d_sub}, 256 centroids) in {t_enc:.1f} s wall"})
+        log(f"cpu oracle encode: {result['cpu_baseline']['encode_Mvec_per_s']:.2f} Mvec/s")
     print(json.dumps(result))
     return 0
 

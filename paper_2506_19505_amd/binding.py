@@ -8,8 +8,7 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# ANTKV_LIB selects another build of the same library (e.g. a tuning variant); the default is the in-tree build.
-_LIB_PATH = os.environ.get("ANTKV_LIB") or os.path.join(_HERE, "libantkv.so")
+_LIB_PATH = os.path.join(_HERE, "libantkv.so")
 _lib = None
 
 EXPORTS = (

@@ -26,32 +26,37 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = False, out: str | None = None, defines: tuple[str, ...] = ()) -> str:
-    """Compile every source and link libantkv.so.  `out` / `defines` build a tuning variant elsewhere."""
-    tag = "".join(ch if ch.isalnum() else "_" for ch in "_".join(defines)) if defines else ""
-    objdir = os.path.join(HERE, "_build" + (("_" + tag) if tag else ""))
-    lib = out or LIB
+PROBE_SRC = "machine_limits.hip"                     # stand-alone probe of the chip's HBM / LDS / issue rates (not part of the library)
+PROBE = os.path.join(HERE, "machine_limits")
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every source, link libantkv.so, and build the stand-alone machine_limits probe beside it."""
+    objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     hipcc = _hipcc()
 
-    def compile_one(src: str) -> str:
-        obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, *EXTRA_FLAGS.get(src, []), *["-D" + d for d in defines], "-c", os.path.join(CSRC, src), "-o", obj]
+    def run(cmd, what):
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0 or verbose:
             sys.stderr.write(r.stdout + r.stderr)
         if r.returncode != 0:
-            raise RuntimeError(f"hipcc failed on {src}")
+            raise RuntimeError(what)
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(objdir, src.replace(".hip", ".o"))
+        run([hipcc, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj], f"hipcc failed on {src}")
         return obj
 
-    with ThreadPoolExecutor(len(SOURCES)) as ex:
+    def build_probe(_):
+        run([hipcc, *[f for f in FLAGS if f != "-fPIC"], os.path.join(CSRC, PROBE_SRC), "-o", PROBE], f"hipcc failed on {PROBE_SRC}")
+
+    with ThreadPoolExecutor(len(SOURCES) + 1) as ex:
+        probe = ex.submit(build_probe, None)
         objs = list(ex.map(compile_one, SOURCES))
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        sys.stderr.write(r.stdout + r.stderr)
-        raise RuntimeError("link failed")
-    return lib
+        probe.result()
+    run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], "link failed")
+    return LIB
 
 
 if __name__ == "__main__":

@@ -78,8 +78,6 @@ def test_encode_duplicate_centroids_and_offsets(oracle):
     got = codes.cpu().numpy()
     check_codes(got[:, :, 20:20 + n], want, margin)
     assert (got[:, :, :20] == 255).all() and (got[:, :, 20 + n:] == 255).all()
-    # every token that is itself a centroid is hit exactly (distance 0 is a known answer)
-    assert (margin == 0).sum() > 0 or True
 
 
 def test_encode_full_prefill_shape(oracle):
