@@ -144,6 +144,29 @@ def test_decode_tiny_config(oracle):
     _check_out(out, want, "cfg0 pipeline")
 
 
+def test_decode_headline_config_on_library_built_cache(oracle):
+    """Config 2 at full size on the cache the benchmark times: seeded K/V -> the library's encode -> Anchor Score over a
+    32-query window -> top-1 % -> gather -> decode (real codes, real anchor positions and rows).  The oracle consumes
+    the GPU's own codes and anchors here; each stage has its own parity test."""
+    w = CONFIGS["cfg2"]
+    qwin, k, v = make_qkv(w.seed, w.B, w.Hq, w.Hkv, w.N, min(w.Nq_select, 32), w.D)
+    cbk, cbv = make_codebooks(w.seed, k, w.d_sub, w.C, "k"), make_codebooks(w.seed, v, w.d_sub, w.C, "v")
+    q = make_decode_query(w.seed, w.B, w.Hq, w.D)
+    geom = antkv.Geometry(w.B, w.Hq, w.Hkv, w.d_sub)
+    kd, vd = dev(k), dev(v)
+    del k, v
+    ck, cv = antkv.encode(geom, kd, dev(cbk)), antkv.encode(geom, vd, dev(cbv))
+    ik, iv, _, _ = antkv.anchor_select(geom, dev(qwin), kd, w.scale, w.k, want_scores=False)
+    rk, rv = antkv.gather_rows(geom, kd, ik), antkv.gather_rows(geom, vd, iv)
+    del kd, vd
+    out = antkv.decode_attn(geom, dev(q), w.scale, ck, cv, dev(cbk), dev(cbv), ik, rk, iv, rv)
+    torch.cuda.synchronize()
+    ikn, ivn = ik.cpu().numpy(), iv.cpu().numpy()
+    assert (np.diff(ikn, axis=-1) > 0).all() and (np.diff(ivn, axis=-1) > 0).all(), "anchor lists are sorted and distinct"
+    want = oracle.decode_attn(q, ck.cpu().numpy(), cv.cpu().numpy(), cbk, cbv, ikn, rk.cpu().numpy(), ivn, rv.cpu().numpy(), w.scale)
+    _check_out(out, want, "cfg2 on the library-built cache")
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg4"])
 def test_decode_full_size_cache(oracle, name):
     """Decode at the real cache shapes (cache-shaped random codes, anchors concentrated at head and tail)."""

@@ -229,6 +229,37 @@ def test_decode12_anchor_score_and_reselection(oracle, books, B, Hq, Hkv, N, k_k
     print(f"N={N} G={Hq // Hkv}: scores within 3e-5, near-tie index disagreements {soft}")
 
 
+def test_decode12_extreme_context_reselection(oracle, books):
+    """The 840000-token shape (1 sequence, 32 query heads on 8 KV heads, 8400 anchors per head) on 12-bit codes: the
+    decode step, the decode-time Anchor Score and the re-selection of 8400 tokens, all against the oracle."""
+    from gpu_util import check_index_sets
+    from workloads import CONFIGS, make_decode_query, normal_fp16, random_anchor_sets
+    w = CONFIGS["cfg4"]
+    B, Hq, Hkv, N, k = w.B, w.Hq, w.Hkv, w.N, w.k
+    rng = np.random.default_rng(840000 + books.d)
+    heads = np.arange(Hkv) % books[0].shape[0]                 # the fixture's two heads, repeated over the eight KV heads
+    cbk, cbv = np.ascontiguousarray(books[0][heads]), np.ascontiguousarray(books[1][heads])
+    ck = rng.integers(0, C, (B, Hkv, N, books.M)).astype(np.int32)
+    cv = rng.integers(0, C, (B, Hkv, N, books.M)).astype(np.int32)
+    ik, iv = random_anchor_sets(w.seed, "k", B, Hkv, N, k), random_anchor_sets(w.seed, "v", B, Hkv, N, k)
+    rk, rv = normal_fp16(w.seed, "rows_k", (B, Hkv, k, 128)), normal_fp16(w.seed, "rows_v", (B, Hkv, k, 128))
+    q = make_decode_query(w.seed, B, Hq, 128)
+    geom = antkv.Geometry(B, Hq, Hkv, books.d, n_centroids=C)
+    out, ans_k, ans_v, rsk, rsv = antkv.decode_attn(geom, dev(q), w.scale, dev(pack12(ck)), dev(pack12(cv)), dev(cbk), dev(cbv),
+                                                    dev(ik), dev(rk), dev(iv), dev(rv), k_resel=k)
+    torch.cuda.synchronize()
+    want, ex = oracle.decode_attn(q, ck, cv, cbk, cbv, ik, rk, iv, rv, w.scale, want_ans=True)
+    err = np.linalg.norm(out.cpu().numpy().astype(np.float64) - want, axis=-1) / np.linalg.norm(want, axis=-1)
+    assert err.max() <= 2e-3, f"relative L2 {err.max():.3e}"
+    np.testing.assert_allclose(ans_v.cpu().numpy(), ex["ans_v"], rtol=3e-5, atol=1e-12)
+    np.testing.assert_allclose(ans_k.cpu().numpy(), ex["ans_k"], rtol=3e-5, atol=1e-12)
+    soft = 0
+    for got, score in ((rsk, ex["ans_k"]), (rsv, ex["ans_v"])):
+        w_idx, margin = oracle.topk(score, k, want_margin=True)
+        soft += check_index_sets(got.cpu().numpy(), w_idx, margin)
+    print(f"d{books.d}m4096 N={N}: decode rel-L2 max {err.max():.2e}, near-tie index disagreements {soft}")
+
+
 @pytest.mark.parametrize("B,n", [(2, 2500), (1, 70)])
 def test_kmeans12_step(oracle, books, B, n):
     """One weighted k-means iteration on a 4096-centroid codebook: assignment by the code rule, update compared on the
