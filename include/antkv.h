@@ -139,6 +139,12 @@ int antkv_gather_rows(const antkv_geom* geom, const void* x, int64_t N, const in
  *   idx_k    int32 [B][Hkv][k_k] strictly ascending in [0, N); rows_k fp16 [B][Hkv][k_k][D]
  *   idx_v, rows_v     likewise with k_v.  k_k and k_v may be 0 (pointers may then be NULL) up to N.
  *   out      fp16 [B][Hq][D]; accumulation is fp32, rounded once.
+ * Precision: the scores of coded tokens are sums of fixed-point table entries q_h[m] . cb_k[g][m][c] with one quantum
+ * per query head, R_h / 16256 for one-byte codes and R_h / 32767 for 12-bit codes, R_h being the largest
+ * |scale * log2(e) * q_h[m] . cb_k[g][m][c]| over m and c.  The output stays within 2e-3 relative L2 of the exact
+ * result while R_h <= L * 1e-3 / (ln 2 * sqrt(M / 12)) (L the number of levels above, M = D / d_sub sub-spaces:
+ * about 14, 20, 29 for d_sub 4, 8, 16 and 82, 58 for the 12-bit formats with d_sub 32, 16); for larger entries the
+ * bound grows in proportion to R_h.  Anchor tokens are scored from their FP16 rows and are not affected.
  * Optional decode-time Anchor Score (Eq. (4) with the single query row over K_eff):
  *   ans_k, ans_v      fp32 [B][Hkv][N], both or neither (NULL):  ans_v[j] = sum_h p_hj,
  *            ans_k[j] = sum_h p_hj (1 - p_hj) ||q_h||_2

@@ -82,3 +82,23 @@ def pack12(codes: np.ndarray) -> np.ndarray:
             word |= c[..., 4 * grp + m] << (12 * m)
         out += [(word >> (8 * i)) & 0xFF for i in range(6)]
     return np.stack(out, axis=-1).astype(np.uint8)
+
+
+def table_range(q, cb, scale, G):
+    """Largest |scale * log2(e) * q_h[m] . cb[g][m][c]| over sub-spaces and codes, per (sequence, query head): the
+    magnitude that sets the quantum of the decode kernels' fixed-point q.centroid tables."""
+    Hkv, M, C, d = cb.shape
+    B, Hq, D = q.shape
+    qr = q.astype(np.float64).reshape(B, Hkv, G, M, d)
+    lut = np.einsum("bghmd,gmcd->bghmc", qr, cb.astype(np.float64)) * (scale * np.log2(np.e))
+    return np.abs(lut).max(axis=(3, 4)).reshape(B, Hq)
+
+
+def attn_tol_for_range(R, M, levels):
+    """Output tolerance as a function of the table range R (per row).  A table entry is rounded to R / levels; a token's
+    score is the sum of M entries, so its error has standard deviation (R / levels) sqrt(M / 12) log2-units, i.e.
+    ln 2 times that relative to a softmax weight.  Up to 1e-3 this stays inside the 2e-3 tolerance (with the fp16
+    rounding of weights and the fp32 sums); beyond that range the bound grows in proportion."""
+    r_max = levels * 1e-3 / (np.log(2.0) * np.sqrt(M / 12.0))
+    return ATTN_TOL * np.maximum(1.0, np.asarray(R) / r_max)
+

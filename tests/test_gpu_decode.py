@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import paper_2506_19505_amd as antkv
-from gpu_util import ATTN_TOL, check_index_sets, dev, rel_l2_rows
+from gpu_util import ATTN_TOL, attn_tol_for_range, check_index_sets, dev, rel_l2_rows, table_range
 from workloads import (CONFIGS, anchor_count, make_codebooks, make_decode_query, make_qkv, normal_fp16,
                        random_anchor_sets, random_codes)
 
@@ -81,6 +81,26 @@ def test_decode_long_anchor_lists(oracle, B, Hkv, N, k_k, k_v):
     c = _cache_from_kv(oracle, 70 + B, B, Hq, Hkv, N, d, k_k, k_v, anchors="random")
     got, want = _run_decode(oracle, c, antkv.Geometry(B, Hq, Hkv, d), 1 / np.sqrt(128))
     _check_out(got, want, f"decode B={B} N={N} k_k={k_k} k_v={k_v}")
+
+
+@pytest.mark.parametrize("d", [4, 8, 16])
+@pytest.mark.parametrize("gain", [2, 4, 8, 16])
+def test_decode_query_gain(oracle, d, gain):
+    """Queries 2 .. 16 times larger than the synthetic recipe's (sharper softmax, larger table entries).  The 2e-3
+    tolerance holds while the largest table entry stays inside the range that the 15-bit table quantum serves
+    (about 14 / 20 / 29 log2-units for d_sub 4 / 8 / 16); beyond it the bound grows with the entry magnitude."""
+    B, Hq, Hkv, N = 2, 8, 2, 3000
+    k = anchor_count(N)
+    c = _cache_from_kv(oracle, 31 + d, B, Hq, Hkv, N, d, k, k)
+    c["q"] = (c["q"].astype(np.float32) * gain).astype(np.float16)
+    scale = 1 / np.sqrt(128)
+    got, want = _run_decode(oracle, c, antkv.Geometry(B, Hq, Hkv, d), scale)
+    err = rel_l2_rows(got.cpu().numpy(), want)
+    R = table_range(c["q"], c["cbk"], scale, Hq // Hkv)
+    tol = attn_tol_for_range(R, 128 // d, 16256).reshape(err.shape)
+    print(f"decode d={d} query gain {gain}: rel-L2 max {err.max():.2e}; table range {R.min():.1f} .. {R.max():.1f}, "
+          f"tolerance {tol.min():.1e} .. {tol.max():.1e}")
+    assert (err <= tol).all(), f"relative L2 {err.max():.3e}"
 
 
 def test_decode_tiny_contexts(oracle):
