@@ -17,6 +17,9 @@ arrays into it and adds the top-k step, which is a stable library sort.
                                 Token-Aware Centroids Learning"): nearest-centroid assignment, then weighted means
   prefill_attn(q, k, v, scale)  causal Attn (Sec. 2.1) over the prompt with the softmax row statistics
                                 that the Anchor Score pass reuses (Alg. 1, first step)
+  rope(x, pos, base, style)     rotary position embedding (Sec. 2.1, the tilde on Q and K)
+  decode_attn_prerope(...)      decode attention on a cache whose keys were stored before RoPE (Sec. 3.3, last
+                                paragraph: the pre-RoPE strategy): every key is rotated to its position when used
 """
 from __future__ import annotations
 
@@ -265,3 +268,56 @@ def kmeans_step(x, w, cb):
     codes = encode(x, cb)
     cb_new, wsum, objective = kmeans_update(x, w, codes, cb)
     return cb_new, codes, wsum, objective
+
+
+def rope(x, pos, base: float = 10000.0, style: int = 0):
+    """Rotary position embedding of the rows of x (fp64 [..., D]) at integer positions pos (broadcast over the leading
+    axes): channel pair i = 0 .. D/2-1 is rotated by the angle pos * base^(-2 i / D).  style 0 pairs the channels
+    (2 i, 2 i + 1), style 1 pairs (i, i + D/2).  Written out as the 2 x 2 rotation of each pair."""
+    x = np.asarray(x, dtype=np.float64)
+    D = x.shape[-1]
+    i = np.arange(D // 2, dtype=np.float64)
+    ang = np.asarray(pos, dtype=np.float64)[..., None] * base ** (-2.0 * i / D)
+    c, s_ = np.cos(ang), np.sin(ang)
+    out = np.empty_like(x)
+    if style == 0:
+        a, b = x[..., 0::2], x[..., 1::2]
+        out[..., 0::2] = a * c - b * s_
+        out[..., 1::2] = a * s_ + b * c
+    else:
+        a, b = x[..., : D // 2], x[..., D // 2:]
+        out[..., : D // 2] = a * c - b * s_
+        out[..., D // 2:] = a * s_ + b * c
+    return out
+
+
+def decode_attn_prerope(q, codes_k, codes_v, cb_k, cb_v, idx_k, rows_k, idx_v, rows_v, scale: float,
+                        rope_base: float = 10000.0, rope_style: int = 0, pos0: int = 0):
+    """Decode attention over a cache that holds the keys as they were BEFORE RoPE (coded or, for anchor tokens, as FP16
+    rows): K_eff[j] = RoPE_{pos0 + j}(rows_k[slot] if j is a K anchor else the centroids of codes_k[j]); the values and
+    the query are used as given (the query already carries its own rotation).  out = softmax_j(scale q . K_eff[j]) V_eff.
+    The definition written out in fp64; returns out [B, Hq, D]."""
+    q64, cbk, cbv = np.asarray(q, np.float64), np.asarray(cb_k, np.float64), np.asarray(cb_v, np.float64)
+    ck, cv = np.asarray(codes_k).astype(np.int64), np.asarray(codes_v).astype(np.int64)
+    B, Hq, D = q64.shape
+    _, Hkv, N, M = ck.shape
+    G = Hq // Hkv
+    ik = np.asarray(idx_k).reshape(B, Hkv, -1).astype(np.int64)
+    iv = np.asarray(idx_v).reshape(B, Hkv, -1).astype(np.int64)
+    rk = np.asarray(rows_k, np.float64).reshape(B, Hkv, ik.shape[-1], D)
+    rv = np.asarray(rows_v, np.float64).reshape(B, Hkv, iv.shape[-1], D)
+    out = np.zeros((B, Hq, D))
+    pos = pos0 + np.arange(N)
+    for b in range(B):
+        for g in range(Hkv):
+            k_eff = np.concatenate([cbk[g, m][ck[b, g, :, m]] for m in range(M)], axis=-1)     # [N, D], before RoPE
+            v_eff = np.concatenate([cbv[g, m][cv[b, g, :, m]] for m in range(M)], axis=-1)
+            k_eff[ik[b, g]] = rk[b, g]
+            v_eff[iv[b, g]] = rv[b, g]
+            k_eff = rope(k_eff, pos, rope_base, rope_style)
+            for h in range(g * G, (g + 1) * G):
+                s_ = scale * (k_eff @ q64[b, h])
+                p_ = np.exp(s_ - s_.max())
+                out[b, h] = (p_ / p_.sum()) @ v_eff
+    return out
+
