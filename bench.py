@@ -309,6 +309,25 @@ def main() -> int:
         del rt
         torch.cuda.empty_cache()
 
+        # ------------------------------------------------------------ keys stored before RoPE, on the headline shape
+        prt = dict(q=dev(make_decode_query(w.seed, w.B, w.Hq, w.D)),
+                   ck=dev(random_codes(w.seed, "k", w.B, w.Hkv, w.N, w.M)), cv=dev(random_codes(w.seed, "v", w.B, w.Hkv, w.N, w.M)),
+                   ik=dev(random_anchor_sets(w.seed, "k", w.B, w.Hkv, w.N, w.k)), iv=dev(random_anchor_sets(w.seed, "v", w.B, w.Hkv, w.N, w.k)),
+                   rk=dev(normal_fp16(w.seed, "rows_k", (w.B, w.Hkv, w.k, w.D))), rv=dev(normal_fp16(w.seed, "rows_v", (w.B, w.Hkv, w.k, w.D))))
+        g_c = geom.c()
+        pr_ws = torch.empty(antkv.load_library().antkv_decode_attn_prerope_workspace(__import__("ctypes").byref(g_c), w.N, w.k),
+                            dtype=torch.uint8, device=devc)
+        fpr = lambda i: antkv.decode_attn_prerope(geom, prt["q"], w.scale, prt["ck"], prt["cv"], cbk_d, cbv_d, prt["ik"], prt["rk"],
+                                                  prt["iv"], prt["rv"], rope_base=500000.0, rope_style=1, pos0=0, out=out, workspace=pr_ws)
+        settle(fpr, 0.1)
+        ms_pr = timed(20, fpr)
+        result["extra"].update({"prerope_decode_ms": ms_pr,
+                                "prerope_workload": f"{w.name}'s shape with keys stored before RoPE (rotate + de-quantise every key to an "
+                                                    f"FP16 row, then decode with every token as a K anchor); workspace {pr_ws.numel() / 1e9:.2f} GB"})
+        log(f"pre-RoPE decode on {w.name}'s shape: {ms_pr:.2f} ms")
+        del prt, pr_ws
+        torch.cuda.empty_cache()
+
         # ------------------------------------------------------------ the two small decode shapes (parity-test cases, not
         # bench lines): their whole cache fits the last-level cache, so these are cache-resident times, launch-bound
         for name in ("cfg0", "cfg1"):

@@ -162,6 +162,27 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
                       int64_t k_resel, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Decode attention on a cache whose keys were stored BEFORE the rotary position embedding (Sec. 3.3, last paragraph:
+ * the pre-RoPE strategy; Sec. 2.1 for RoPE on Q and K).  As antkv_decode_attn, with
+ *   K_eff[j] = RoPE_{pos0 + j}( rows_k[slot] if j == idx_k[slot], else concat_m cb_k[g][m][codes_k[j][m]] ):
+ * both the K codes and the FP16 K anchor rows hold un-rotated keys, and every key is rotated to its position when it
+ * is used.  RoPE_p turns channel pair i = 0 .. D/2-1 by the angle p * rope_base^(-2 i / D); rope_style 0 pairs the
+ * channels (2 i, 2 i + 1), rope_style 1 pairs (i, i + D/2).  q is used as given (the caller has rotated it to its own
+ * position); values are untouched.  No Anchor Score outputs.
+ * The call first writes the rotated keys as FP16 rows into the workspace (256 bytes per token and KV head, rounded
+ * once to fp16 after the rotation) and then runs the decode kernels with every token as a K anchor; the workspace size
+ * comes from antkv_decode_attn_prerope_workspace(geom, N, k_v).
+ * Errors: EINVAL (also rope_base <= 1, rope_style not 0 / 1, pos0 < 0), EUNSUPPORTED, EWORKSPACE, ELAUNCH.
+ */
+size_t antkv_decode_attn_prerope_workspace(const antkv_geom* geom, int64_t N, int64_t k_v);
+int antkv_decode_attn_prerope(const antkv_geom* geom, const void* q, float scale, const uint8_t* codes_k,
+                              const uint8_t* codes_v, int64_t N, int64_t N_cap, const void* cb_k,
+                              const void* cb_v, const int32_t* idx_k, const void* rows_k, int64_t k_k,
+                              const int32_t* idx_v, const void* rows_v, int64_t k_v, float rope_base,
+                              int rope_style, int64_t pos0, void* out, void* workspace,
+                              size_t workspace_bytes, void* stream);
+
+/*
  * antkv_decode_attn for callers that cannot allocate device memory and therefore have no workspace to pass: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation and arguments as
  * antkv_decode_attn without the optional score / re-selection outputs and without the workspace: the kernels'

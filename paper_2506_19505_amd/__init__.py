@@ -13,6 +13,7 @@ from .binding import (
     prefill_attn,
     kmeans_step,
     decode_attn,
+    decode_attn_prerope,
     decode_attn_static,
     encode,
     gather_rows,
@@ -31,6 +32,7 @@ __all__ = [
     "prefill_attn",
     "kmeans_step",
     "decode_attn",
+    "decode_attn_prerope",
     "decode_attn_static",
     "encode",
     "gather_rows",

@@ -14,7 +14,7 @@ _lib = None
 EXPORTS = (
     "antkv_version", "antkv_strerror", "antkv_encode", "antkv_anchor_select_workspace", "antkv_anchor_select",
     "antkv_topk_workspace", "antkv_topk", "antkv_gather_rows", "antkv_decode_attn_workspace", "antkv_decode_attn",
-    "antkv_decode_attn_static", "antkv_append_token", "antkv_prefill_attn", "antkv_kmeans_step_workspace", "antkv_kmeans_step",
+    "antkv_decode_attn_static", "antkv_decode_attn_prerope_workspace", "antkv_decode_attn_prerope", "antkv_append_token", "antkv_prefill_attn", "antkv_kmeans_step_workspace", "antkv_kmeans_step",
 )
 
 
@@ -94,6 +94,11 @@ def load_library():
                                           vp, vp, vp, vp, i64, vp, sz, vp]
         lib.antkv_decode_attn_static.restype = ctypes.c_int
         lib.antkv_decode_attn_static.argtypes = [gp, vp, f32, vp, vp, i64, i64, vp, vp, vp, vp, i64, vp, vp, i64, vp, vp]
+        lib.antkv_decode_attn_prerope_workspace.restype = sz
+        lib.antkv_decode_attn_prerope_workspace.argtypes = [gp, i64, i64]
+        lib.antkv_decode_attn_prerope.restype = ctypes.c_int
+        lib.antkv_decode_attn_prerope.argtypes = [gp, vp, f32, vp, vp, i64, i64, vp, vp, vp, vp, i64, vp, vp, i64,
+                                                  f32, ctypes.c_int, i64, vp, vp, sz, vp]
         _lib = lib
     return _lib
 
@@ -310,6 +315,35 @@ def decode_attn(geom: Geometry, q: torch.Tensor, scale: float, codes_k: torch.Te
     _check(rc, "antkv_decode_attn")
     if want_ans or k_resel > 0:
         return out, ans_k, ans_v, rk, rv
+    return out
+
+
+def decode_attn_prerope(geom: Geometry, q: torch.Tensor, scale: float, codes_k: torch.Tensor, codes_v: torch.Tensor,
+                        cb_k: torch.Tensor, cb_v: torch.Tensor, idx_k: torch.Tensor | None, rows_k: torch.Tensor | None,
+                        idx_v: torch.Tensor | None, rows_v: torch.Tensor | None, rope_base: float = 10000.0,
+                        rope_style: int = 0, pos0: int = 0, N: int | None = None, out: torch.Tensor | None = None,
+                        workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """antkv_decode_attn_prerope: decode attention on keys stored before RoPE.  Returns out fp16 [B,Hq,D]."""
+    _need(q, torch.float16, "q")
+    _need(codes_k, torch.uint8, "codes_k")
+    _need(codes_v, torch.uint8, "codes_v")
+    B, Hq, D = q.shape
+    N_cap = codes_k.shape[2]
+    if N is None:
+        N = N_cap
+    k_k = 0 if idx_k is None else idx_k.shape[-1]
+    k_v = 0 if idx_v is None else idx_v.shape[-1]
+    if out is None:
+        out = torch.empty((B, Hq, D), dtype=torch.float16, device=q.device)
+    g = geom.c()
+    if workspace is None:
+        workspace = _workspace(load_library().antkv_decode_attn_prerope_workspace(ctypes.byref(g), N, k_v), q.device)
+    rc = load_library().antkv_decode_attn_prerope(
+        ctypes.byref(g), _p(q), float(scale), _p(codes_k), _p(codes_v), N, N_cap, _p(cb_k), _p(cb_v),
+        _p(idx_k) if k_k else None, _p(rows_k) if k_k else None, k_k,
+        _p(idx_v) if k_v else None, _p(rows_v) if k_v else None, k_v,
+        float(rope_base), int(rope_style), int(pos0), _p(out), _p(workspace), workspace.numel(), _stream(q))
+    _check(rc, "antkv_decode_attn_prerope")
     return out
 
 

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libantkv.so")
-SOURCES = ["api.hip", "encode.hip", "encode12.hip", "topk.hip", "window.hip", "prefill_attn.hip", "kmeans.hip", "anchor_score.hip", "decode12.hip", "decode_attn.hip"]
+SOURCES = ["api.hip", "encode.hip", "encode12.hip", "topk.hip", "window.hip", "prefill_attn.hip", "kmeans.hip", "anchor_score.hip", "decode12.hip", "decode_attn.hip", "rope_keys.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # keep the compiler from forming packed-FP32 VALU instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

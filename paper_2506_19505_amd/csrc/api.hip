@@ -362,6 +362,47 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
                             out, ans_k, ans_v, resel_idx_k, resel_idx_v, k_resel, workspace, workspace_bytes, stream);
 }
 
+size_t antkv_decode_attn_prerope_workspace(const antkv_geom* geom, int64_t N, int64_t k_v)
+{
+    Geom g;
+    if (check_geom(geom, g) || N < 0 || k_v < 0) return 0;
+    const size_t rows = align_up((size_t)g.B * g.Hkv * (size_t)N * kD * sizeof(half_t));
+    const size_t iota = align_up((size_t)g.B * g.Hkv * (size_t)N * sizeof(int32_t));
+    return rows + iota + align_up(antkv_decode_attn_workspace(geom, N, N, k_v, 0));
+}
+
+int antkv_decode_attn_prerope(const antkv_geom* geom, const void* q, float scale, const uint8_t* codes_k,
+                              const uint8_t* codes_v, int64_t N, int64_t N_cap, const void* cb_k, const void* cb_v,
+                              const int32_t* idx_k, const void* rows_k, int64_t k_k, const int32_t* idx_v,
+                              const void* rows_v, int64_t k_v, float rope_base, int rope_style, int64_t pos0, void* out,
+                              void* workspace, size_t workspace_bytes, void* stream)
+{
+    Geom g;
+    const int rc = check_geom(geom, g);
+    if (rc) return rc;
+    if (N < 0 || N_cap < N || k_k < 0 || k_v < 0 || k_k > N || k_v > N || N > 0x7fffffffLL) return ANTKV_EINVAL;
+    if (!(rope_base > 1.f) || (rope_style != 0 && rope_style != 1) || pos0 < 0 || pos0 > (1LL << 40)) return ANTKV_EINVAL;
+    if (g.B == 0) return ANTKV_OK;
+    if (N == 0)   // nothing to rotate: the plain call writes the zeros
+        return decode_attn_impl(geom, q, scale, codes_k, codes_v, 0, N_cap, cb_k, cb_v, nullptr, nullptr, 0, nullptr, nullptr, 0,
+                                out, nullptr, nullptr, nullptr, nullptr, 0, workspace, workspace_bytes, stream);
+    if (!codes_k || !cb_k || misaligned(codes_k, 16) || misaligned(cb_k, 16)) return ANTKV_EINVAL;
+    if (k_k > 0 && (!idx_k || !rows_k || misaligned(rows_k, 16))) return ANTKV_EINVAL;
+    const size_t rows_b = align_up((size_t)g.B * g.Hkv * (size_t)N * kD * sizeof(half_t));
+    const size_t iota_b = align_up((size_t)g.B * g.Hkv * (size_t)N * sizeof(int32_t));
+    const size_t need = antkv_decode_attn_prerope_workspace(geom, N, k_v);
+    if (!workspace || misaligned(workspace, 256) || workspace_bytes < need) return ANTKV_EWORKSPACE;
+    char* w = (char*)workspace;
+    half_t* k_rot = (half_t*)w;
+    int32_t* iota = (int32_t*)(w + rows_b);
+    if (launch_rope_keys(g, codes_k, N, N_cap, (const half_t*)cb_k, idx_k, (const half_t*)rows_k, k_k, (double)rope_base,
+                         rope_style, pos0, k_rot, iota, (hipStream_t)stream) != hipSuccess)
+        return ANTKV_ELAUNCH;
+    // every token is now a K anchor whose FP16 row is its rotated key; the K codes are not read for scores any more
+    return decode_attn_impl(geom, q, scale, codes_k, codes_v, N, N_cap, cb_k, cb_v, iota, k_rot, N, idx_v, rows_v, k_v, out,
+                            nullptr, nullptr, nullptr, nullptr, 0, w + rows_b + iota_b, workspace_bytes - rows_b - iota_b, stream);
+}
+
 int antkv_decode_attn_static(const antkv_geom* geom, const void* q, float scale, const uint8_t* codes_k,
                              const uint8_t* codes_v, int64_t N, int64_t N_cap, const void* cb_k, const void* cb_v,
                              const int32_t* idx_k, const void* rows_k, int64_t k_k, const int32_t* idx_v,

@@ -139,6 +139,10 @@ struct DecodeArgs {
 int decode_num_splits(const Geom& g, int64_t N);
 size_t decode_workspace_bytes(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans);
 hipError_t launch_decode_attn(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st);
+// rows_out fp16 [B][Hkv][N][kD] = RoPE_{pos0 + j}(K_eff[j]) (anchor row or centroids of the codes), iota_out[b][g][j] = j
+hipError_t launch_rope_keys(const Geom& g, const uint8_t* codes_k, int64_t N, int64_t N_cap, const half_t* cb_k,
+                            const int32_t* idx_k, const half_t* rows_k, int64_t k_k, double rope_base, int rope_style,
+                            int64_t pos0, half_t* rows_out, int32_t* iota_out, hipStream_t st);
 size_t decode12_workspace_bytes(const Geom& g, int64_t N);
 hipError_t launch_decode12(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st);
 

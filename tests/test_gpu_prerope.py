@@ -1,0 +1,60 @@
+"""GPU parity: decode attention on keys stored before RoPE (paper Sec. 3.3, last paragraph) against the oracle's
+definition (rotate every key, coded or FP16, to its position; then plain decode attention)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2506_19505_amd as antkv
+from gpu_util import ATTN_TOL, dev, pack12, rel_l2_rows
+from workloads import make_codebooks, make_decode_query, make_qkv, normal_fp16, random_anchor_sets
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(oracle, seed, B, Hq, Hkv, N, d, C, k_k, k_v, base, style, pos0, N_cap=None):
+    N_cap = N_cap or N
+    M = 128 // d
+    rng = np.random.default_rng(seed)
+    _, k, v = make_qkv(seed, 1, Hq, Hkv, min(max(C, 300), 6000), 1, 128)
+    cbk, cbv = make_codebooks(seed, k, d, C, "k", max_sample=6000), make_codebooks(seed, v, d, C, "v", max_sample=6000)
+    ck = rng.integers(0, C, (B, Hkv, N_cap, M)).astype(np.int32)
+    cv = rng.integers(0, C, (B, Hkv, N_cap, M)).astype(np.int32)
+    ik, iv = random_anchor_sets(seed, "k", B, Hkv, N, k_k), random_anchor_sets(seed, "v", B, Hkv, N, k_v)
+    rk, rv = normal_fp16(seed, "rows_k", (B, Hkv, k_k, 128)), normal_fp16(seed, "rows_v", (B, Hkv, k_v, 128))
+    # the query as a model hands it over: rotated to the position that follows the cache
+    q = oracle.rope(make_decode_query(seed, B, Hq, 128).astype(np.float64), np.full((B, Hq), pos0 + N), base, style).astype(np.float16)
+    scale = 1 / np.sqrt(128)
+    geom = antkv.Geometry(B, Hq, Hkv, d, n_centroids=C)
+    to_dev = (lambda c: dev(c.astype(np.uint8))) if C == 256 else (lambda c: dev(pack12(c)))
+    out = antkv.decode_attn_prerope(geom, dev(q), scale, to_dev(ck), to_dev(cv), dev(cbk), dev(cbv),
+                                    dev(ik) if k_k else None, dev(rk) if k_k else None,
+                                    dev(iv) if k_v else None, dev(rv) if k_v else None,
+                                    rope_base=base, rope_style=style, pos0=pos0, N=N)
+    torch.cuda.synchronize()
+    want = oracle.decode_attn_prerope(q, ck[:, :, :N], cv[:, :, :N], cbk, cbv, ik, rk, iv, rv, scale, base, style, pos0)
+    err = rel_l2_rows(out.cpu().numpy(), want)
+    print(f"pre-RoPE d={d} C={C} N={N} anchors {k_k}/{k_v} style {style} pos0 {pos0}: rel-L2 max {err.max():.2e} mean {err.mean():.2e}")
+    assert err.max() <= ATTN_TOL, f"relative L2 {err.max():.3e}"
+
+
+@pytest.mark.parametrize("d", [4, 8, 16])
+@pytest.mark.parametrize("style,pos0", [(0, 0), (1, 100000)])
+def test_prerope_byte_codes(oracle, d, style, pos0):
+    _case(oracle, 300 + d, 2, 8, 2, 3000, d, 256, 30, 30, 10000.0, style, pos0)
+
+
+@pytest.mark.parametrize("d", [32, 16])
+def test_prerope_12bit_codes(oracle, d):
+    _case(oracle, 310 + d, 1, 8, 2, 2500, d, 4096, 25, 25, 500000.0, 1, 4096)
+
+
+def test_prerope_edge_cases(oracle):
+    _case(oracle, 320, 1, 4, 1, 700, 8, 256, 0, 0, 10000.0, 1, 0)                 # no anchors at all
+    _case(oracle, 321, 1, 4, 1, 611, 8, 256, 5, 0, 10000.0, 0, 17, N_cap=900)     # N below the capacity, K anchors only
+    _case(oracle, 322, 2, 4, 1, 65, 8, 256, 1, 1, 10000.0, 1, 0)                  # one tile and a token
+    _case(oracle, 323, 1, 4, 1, 300, 8, 256, 300, 300, 10000.0, 1, 9)             # every token an FP16 anchor in both lists
+
+
+def test_prerope_long_context(oracle):
+    """131072 positions (angles up to 1.3e5 rad on the fastest pair): the fp64 angle reduction and the fp32 stepping."""
+    _case(oracle, 330, 1, 4, 1, 131072, 8, 256, 1311, 1311, 500000.0, 1, 0)
