@@ -281,6 +281,32 @@ def test_decode_workspace_reuse_across_shapes(oracle):
         _check_out(got, want, f"reused workspace, call {rep}, N={n}")
 
 
+def test_decode_repeated_on_one_workspace(oracle):
+    """The same step 200 times back to back on one workspace, no host synchronisation in between: every launch's last
+    workgroup must merge this launch's partials (arrival words carry the launch tag; partials are written and read at
+    device scope).  A stale or half-written partial would show as a large deviation; the run-to-run differences that
+    remain come from the order in which waves pull tiles (fp32 sums in another order) and stay at rounding level."""
+    B, Hq, Hkv, N, d = 4, 32, 8, 20000, 8
+    k = anchor_count(N)
+    c = _cache_from_kv(oracle, 77, B, Hq, Hkv, N, d, k, k, anchors="random")
+    t = {n: dev(a) for n, a in c.items()}
+    geom = antkv.Geometry(B, Hq, Hkv, d)
+    ws = antkv.DecodeWorkspace(geom, N, k, k, 0, "cuda")
+    outs = torch.empty((200, B, Hq, 128), dtype=torch.float16, device="cuda")
+    for i in range(200):
+        antkv.decode_attn(geom, t["q"], 0.1, t["ck"], t["cv"], t["cbk"], t["cbv"], t["ik"], t["rk"], t["iv"], t["rv"],
+                          out=outs[i], workspace=ws)
+    torch.cuda.synchronize()
+    got = outs.cpu().numpy().astype(np.float64)
+    want = oracle.decode_attn(c["q"], c["ck"], c["cv"], c["cbk"], c["cbv"], c["ik"], c["rk"], c["iv"], c["rv"], 0.1)
+    err = np.linalg.norm(got - want[None], axis=-1) / np.linalg.norm(want, axis=-1)[None]
+    spread = np.linalg.norm(got - got[:1], axis=-1) / np.linalg.norm(want, axis=-1)[None]
+    print(f"200 launches: rel-L2 to the oracle max {err.max():.2e}; launch-to-launch spread max {spread.max():.2e}, "
+          f"bit-identical launches {(np.abs(got - got[:1]).reshape(200, -1).max(axis=1) == 0).sum()} of 200")
+    assert err.max() <= ATTN_TOL
+    assert spread.max() <= 1e-3          # one fp16 unit in the last place of the largest channels
+
+
 def test_decode_graph_replay(oracle):
     """The decode step captured into a HIP graph and replayed: every replay must equal the eager result for the inputs
     of that moment (the launch tag of the arrival words is frozen in the captured launch)."""
