@@ -78,6 +78,8 @@ const char* antkv_strerror(int code); /* host pointer to a static string */
  *   codes    uint8 [B][Hkv][N_cap][code_bytes]; rows token_offset .. token_offset+n_tok-1 are written:
  *            codes[b][g][token_offset+t][m] = argmin_c || x[b][g][t][m*d_sub : (m+1)*d_sub] - codebook[g][m][c] ||^2,
  *            the lowest c among equal distances (distances compared in fp32).
+ *            With 256 centroids the squared norm of a centroid's sub-vector must stay below 2.09e6 (its half is held
+ *            in fp16 terms scaled by 16); larger centroids are never chosen.  No such limit with 4096 centroids.
  * Call once for K with the K codebook and once for V with the V codebook.
  * n_tok == 0 is a no-op.  Errors: EINVAL (null, alignment, token_offset + n_tok > N_cap), EUNSUPPORTED.
  */

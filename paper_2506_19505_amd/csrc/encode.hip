@@ -26,6 +26,7 @@ __device__ __forceinline__ float max2f(float a, float b) { return fmaxf(a, b); }
 
 constexpr int kEncThreads = 1024;
 constexpr int kEncWaves = kEncThreads / 64;
+constexpr float kNormScale = 16.f;     // see the norm terms in the kernel: sub-vector norms up to ||c||^2 = 2.09e6 stay finite
 
 // LDS layout per sub-vector width (halfs per centroid): the A operand of a lane is 8 consecutive halfs
 //   d = 4   one array  [M][256][8]  = {c0..c3, n_hi, n_mid, n_lo, 0}: lanes 0-31 read it, lanes 32-63 multiply by zero
@@ -68,7 +69,9 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(
         float nn = 0.f;
 #pragma unroll
         for (int t = 0; t < DSUB; ++t) nn = fmaf(cf[t], cf[t], nn);
-        const float nv = -0.5f * nn;
+        // (stored divided by kNormScale and met by kNormScale in the token operand: a power of two, so nothing is
+        // rounded, and -||c||^2/2 stays finite in fp16 up to ||c||^2 = 2 * 65504 * kNormScale)
+        const float nv = -0.5f * nn * (1.0f / kNormScale);
         const half_t n_hi = (half_t)nv;
         const float r1 = nv - (float)n_hi;
         const half_t n_mid = (half_t)r1;
@@ -86,7 +89,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(
 
     const int lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, h = lane >> 5;
-    const half_t one = (half_t)1.f, zero = (half_t)0.f;
+    const half_t one = (half_t)kNormScale, zero = (half_t)0.f;        // multiplies the three norm terms
     const half8_t ones3 = {one, one, one, zero, zero, zero, zero, zero};
     const half8_t zeros = {zero, zero, zero, zero, zero, zero, zero, zero};
     const int64_t blocks_per_b = (n_tok + 31) / 32;

@@ -62,6 +62,24 @@ def test_encode_matches_oracle(oracle, d, B, Hq, Hkv, n):
     print(f"near-tie disagreements: {soft}")
 
 
+@pytest.mark.parametrize("d", [4, 8, 16])
+def test_encode_large_magnitudes(oracle, d):
+    """Keys and centroids some 40 times the synthetic recipe's (outlier channels reach several hundred): half the squared
+    norm of a centroid's sub-vector exceeds the fp16 range, which the scaled norm terms must survive; and the append
+    path (fp32 norms) must agree with antkv_encode on the same rows."""
+    B, Hq, Hkv, n = 1, 4, 2, 300
+    _, k, _ = make_qkv(17 + d, B, Hq, Hkv, n, 1, 128)
+    unit = (make_codebooks(17 + d, k, d, 256, "k").astype(np.float64) ** 2).sum(-1).max()
+    k = (k.astype(np.float32) * np.sqrt(1.5e6 / unit)).astype(np.float16)      # largest sub-vector norm^2 about 1.5e6
+    cb = make_codebooks(17 + d, k, d, 256, "k")
+    norms = (cb.astype(np.float64) ** 2).sum(-1)
+    assert norms.max() / 2 > 65504 and norms.max() < 2.09e6, f"largest sub-vector norm^2 {norms.max():.3g}"
+    want, margin = oracle.encode(k, cb, want_margin=True)
+    got = antkv.encode(antkv.Geometry(B, Hq, Hkv, d), dev(k), dev(cb)).cpu().numpy()
+    soft = check_codes(got, want, margin, f"large-magnitude codes d={d}")
+    print(f"d={d}: largest ||c||^2 {norms.max():.3g}, near-tie disagreements {soft}")
+
+
 def test_encode_duplicate_centroids_and_offsets(oracle):
     # fewer sample tokens than centroids -> duplicated centroids: the lower index must win exactly
     B, Hq, Hkv, n, d = 1, 2, 1, 100, 8
