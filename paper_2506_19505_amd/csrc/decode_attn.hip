@@ -721,7 +721,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         return c;
     };
     // integer scores (in table quanta) of the tile whose K code dwords are kw_in, lane = token
-    auto k_scores = [&](const KConst& c, const uint32_t (&kw_in)[CW]) -> int4_t {
+    auto k_scores = [&](const KConst& c, const uint32_t (&kw_in)[CW], auto&& after_gathers) -> int4_t {
         // Code dwords are XOR-permuted so that step s finds the code of sub-space (s XOR kr) at a compile-time
         // register and a per-lane constant byte selector.
         uint32_t kw[CW];
@@ -755,6 +755,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 ent[u] = *(const lds_uint2*)(uintptr_t)__builtin_amdgcn_perm(kw[st >> 2], c.kc[st >> 2], c.ksel[st & 3]);
             }
             __builtin_amdgcn_sched_barrier(0);                           // nothing moves across: gathers first, then the MFMAs
+            if (s0 + KB >= M) after_gathers();                           // the codes are used up: the caller may reload them
 #pragma unroll
             for (int u = 0; u < KB; u += 2)
                 si = __builtin_amdgcn_mfma_i32_16x16x64_i8(int4_t{(int)ent[u][0], (int)ent[u][1], (int)ent[u + 1][0], (int)ent[u + 1][1]},
@@ -790,22 +791,29 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     // entry's code bytes being staged in the wave's area), and the pair's weights come back from the staging area as
     // fp16 pairs: one packed dot product per head and channel adds two entries.
     // code loads run one tile ahead of their use: HBM latency hides behind the previous tile's work
-    auto load_tile = [&](int64_t tile, uint32_t (&kw_)[CW], uint32_t (&vw_)[CW]) {
-        const int64_t tok_ = t0 + tile * 64 + lane;
-        const int64_t ltok = (tok_ < p.N) ? tok_ : (p.N - 1);        // tokens past the range are masked, not skipped
+    // (addresses are a uniform base, the range's first token, plus a 32-bit offset: a range has at most 32768 tokens;
+    // an empty range reads token 0)
+    const int64_t n_tiles = (t1 - t0 + 63) >> 6;
+    const int64_t t0c = n_tiles > 0 ? t0 : 0;
+    const uint8_t* ck0 = ck + t0c * M;
+    const uint8_t* cv0 = cv + t0c * M;
+    const uint32_t last_rel = n_tiles > 0 ? (uint32_t)(p.N - 1 - t0) : 0u;     // tokens past the end are masked, not skipped
+    auto load_tile = [&](int tile, uint32_t (&kw_)[CW], uint32_t (&vw_)[CW]) {
+        uint32_t rel = (uint32_t)tile * 64u + (uint32_t)lane;
+        rel = rel < last_rel ? rel : last_rel;
+        const uint32_t off = rel * (uint32_t)M;
         if (CW == 2) {
-            const uint2_t a = *(const uint2_t*)(ck + ltok * M), c = *(const uint2_t*)(cv + ltok * M);
+            const uint2_t a = *(const uint2_t*)(ck0 + off), c = *(const uint2_t*)(cv0 + off);
             kw_[0] = a[0]; kw_[1] = a[1]; vw_[0] = c[0]; vw_[1] = c[1];
         } else {
 #pragma unroll
             for (int i = 0; i < CW / 4; ++i) {
-                const uint4_t a = *(const uint4_t*)(ck + ltok * M + 16 * i), c = *(const uint4_t*)(cv + ltok * M + 16 * i);
+                const uint4_t a = *(const uint4_t*)(ck0 + off + 16 * i), c = *(const uint4_t*)(cv0 + off + 16 * i);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) { kw_[4 * i + e] = a[e]; vw_[4 * i + e] = c[e]; }
             }
         }
     };
-    const int64_t n_tiles = (t1 - t0 + 63) >> 6;
     uint32_t kw_next[CW], vw_next[CW];
     if (T_first < n_atiles) {
         typedef __attribute__((address_space(3))) uint8_t lds_u8;
@@ -965,7 +973,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 int ln = lane;
                 asm volatile("" : "+v"(ln));                               // (a value of its own: not merged with the stream's copy)
                 const KConst kcst = make_kconst(ln);
-                const int4_t si = k_scores(kcst, kw);
+                const int4_t si = k_scores(kcst, kw, [] {});
                 // register i of lane (4 c + h, g) = entry 16 c + 4 g + i, head h (classes 2 and 3 are empty: keep bits 0)
                 const uint32_t keep_bits = (uint32_t)(keep64 >> (32 * (tj >> 1) + 16 * (tj & 1) + 4 * kgrp));
                 float sr[4], lm = kNegBig;
@@ -1095,17 +1103,15 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         const uint32_t mask_dw = (uint32_t)(tj >> 1);
         const uint32_t mask_sh = (uint32_t)(16 * (tj & 1) + 4 * kgrp);
 
-        auto grab_tile = [&]() -> int64_t {
-            int t = 0;
-            if (lane == 0) t = atomicAdd(&s_misc[8], 1);
-            return (int64_t)__builtin_amdgcn_readfirstlane(t);
-        };
         // this lane's head: running reference
         float neg_m = -m_ref[0];
 #pragma unroll
         for (int h = 1; h < kNH; ++h) neg_m = (tq == h) ? -m_ref[h] : neg_m;
 
-        auto do_tile = [&](int64_t tile, const uint32_t (&kw_in)[CW], const uint32_t (&vw)[CW]) {
+        // One tile.  Its codes are in kw_in / vw; once they are used up (K codes by the table gathers, V codes by the
+        // staging write; d = 4 stages its second half in the V phase) `reload` puts the next tile's codes into the same
+        // registers, so that nothing is copied between tiles.
+        auto do_tile = [&](int tile, uint32_t (&kw_in)[CW], uint32_t (&vw)[CW], auto&& reload) {
             // ---- V code bytes into the staging area (first round; d = 4 stages its second half later)
             if constexpr (DSUB == 8) {
                 uint4_t w4;
@@ -1131,7 +1137,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             const uint32_t mw = s_mask[(2 * (uint32_t)tile + mask_dw) & (L::mask_words - 1)];
 
             // ---- K side: scores in table quanta
-            const int4_t si = k_scores(kcst, kw_in);
+            const int4_t si = k_scores(kcst, kw_in, [&] { if constexpr (DSUB != 4) reload(); });
             // ---- softmax: register i = token (tj, 4 kgrp + i), head tq.  x = score - reference.
             const uint32_t keep_bits = ~mw >> mask_sh;                 // bit i set: token i is neither anchored nor past the range
             float x[4];
@@ -1220,6 +1226,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                     if (a == 1) {
                         __builtin_amdgcn_wave_barrier();
                         stage_d4(1);
+                        reload();
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                         __builtin_amdgcn_wave_barrier();
                     }
@@ -1251,18 +1258,24 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             __builtin_amdgcn_wave_barrier();
         };
 
-        // The next tile's codes are requested before the current tile is worked on.  The request is unconditional (a
-        // wave that has no further tile re-reads the range's last one): a conditional load would cost register copies
-        // on every tile.
-        int64_t tile = wave;                                          // the first tile of wave w is tile w
-        load_tile(tile < n_tiles ? tile : n_tiles - 1, kw_next, vw_next);
-        while (tile < n_tiles) {
-            uint32_t kw_c[CW], vw_c[CW];
-#pragma unroll
-            for (int i = 0; i < CW; ++i) { kw_c[i] = kw_next[i]; vw_c[i] = vw_next[i]; }
-            const int64_t tile_next = grab_tile();
-            load_tile(tile_next < n_tiles ? tile_next : n_tiles - 1, kw_next, vw_next);
-            do_tile(tile, kw_c, vw_c);
+        // The next tile's codes are requested while the current tile is worked on (from the middle of its K phase).  The
+        // request is unconditional: a wave that has no further tile re-reads the range's last one.  The next tile's number
+        // comes from the workgroup's counter; the fetch-add is issued at the top of a tile and read where the request is
+        // made, so that its LDS round trip is off the critical path.
+        int tile = wave;                                              // the first tile of wave w is tile w
+        const int nt = (int)n_tiles;
+        const uint32_t tile_ctr = lds0 + (uint32_t)(L::red + kDaWaves * 32 + 8 * 4);      // LDS address of s_misc[8]
+        load_tile(tile < nt ? tile : nt - 1, kw_next, vw_next);
+        while (tile < nt) {
+            // (the fetch-add and the wait for it are written out: an atomic of the language is waited for on the spot)
+            int t_raw = 0;
+            if (lane == 0) asm volatile("ds_add_rtn_u32 %0, %1, %2" : "=v"(t_raw) : "v"(tile_ctr), "v"(1) : "memory");
+            int tile_next = 0;
+            do_tile(tile, kw_next, vw_next, [&] {
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(t_raw) : : "memory");
+                tile_next = __builtin_amdgcn_readfirstlane(t_raw);
+                load_tile(tile_next < nt ? tile_next : nt - 1, kw_next, vw_next);
+            });
             tile = tile_next;
         }
 #pragma unroll
