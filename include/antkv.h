@@ -164,6 +164,17 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
                       int64_t k_resel, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Reproducibility of antkv_decode_attn (and of the entry points built on it).  Codes, scores of antkv_anchor_select and
+ * index sets are the same on every run.  The attention output of the one-byte-code kernel is, by default, reproducible
+ * only to rounding level: after its first tile a wave pulls 64-token tiles from a counter, so the order of the fp32
+ * sums varies from launch to launch.  antkv_set_decode_deterministic(1) makes every wave walk a fixed sequence of
+ * tiles instead: the output is then the same bit for bit for the same inputs, shape and workspace size, at a small
+ * cost in balance between the waves.  Process-wide, takes effect for launches enqueued afterwards; returns the previous
+ * setting.  The 12-bit kernels always work in a fixed order.
+ */
+int antkv_set_decode_deterministic(int on);
+
+/*
  * Decode attention on a cache whose keys were stored BEFORE the rotary position embedding (Sec. 3.3, last paragraph:
  * the pre-RoPE strategy; Sec. 2.1 for RoPE on Q and K).  As antkv_decode_attn, with
  *   K_eff[j] = RoPE_{pos0 + j}( rows_k[slot] if j == idx_k[slot], else concat_m cb_k[g][m][codes_k[j][m]] ):

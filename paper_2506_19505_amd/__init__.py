@@ -15,6 +15,7 @@ from .binding import (
     decode_attn,
     decode_attn_prerope,
     decode_attn_static,
+    set_decode_deterministic,
     encode,
     gather_rows,
     lib_path,
@@ -34,6 +35,7 @@ __all__ = [
     "decode_attn",
     "decode_attn_prerope",
     "decode_attn_static",
+    "set_decode_deterministic",
     "encode",
     "gather_rows",
     "lib_path",

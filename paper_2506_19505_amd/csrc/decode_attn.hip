@@ -314,7 +314,10 @@ __device__ void wg_merge_and_store(char* smem, float (&m_ref)[kNH], float (&l_su
     }
 }
 
-template <int DSUB>
+// DET: every wave walks a fixed sequence of tiles (w, w + 16, ...) instead of pulling them from the workgroup's counter:
+// the order of all sums is then fixed and the output is the same bit for bit on every launch (the opt-in mode of
+// antkv_set_decode_deterministic; the counter balances the waves better).
+template <int DSUB, bool DET>
 __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams p)
 {
     constexpr int M = kD / DSUB;
@@ -1269,11 +1272,17 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         while (tile < nt) {
             // (the fetch-add and the wait for it are written out: an atomic of the language is waited for on the spot)
             int t_raw = 0;
-            if (lane == 0) asm volatile("ds_add_rtn_u32 %0, %1, %2" : "=v"(t_raw) : "v"(tile_ctr), "v"(1) : "memory");
+            if constexpr (!DET) {
+                if (lane == 0) asm volatile("ds_add_rtn_u32 %0, %1, %2" : "=v"(t_raw) : "v"(tile_ctr), "v"(1) : "memory");
+            }
             int tile_next = 0;
             do_tile(tile, kw_next, vw_next, [&] {
-                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(t_raw) : : "memory");
-                tile_next = __builtin_amdgcn_readfirstlane(t_raw);
+                if constexpr (DET) {
+                    tile_next = tile + kDaWaves;
+                } else {
+                    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(t_raw) : : "memory");
+                    tile_next = __builtin_amdgcn_readfirstlane(t_raw);
+                }
                 load_tile(tile_next < nt ? tile_next : nt - 1, kw_next, vw_next);
             });
             tile = tile_next;
@@ -1730,6 +1739,9 @@ size_t decode_workspace_bytes(const Geom& g, int64_t N, int64_t k_k, int64_t k_v
     return da_plan(g, N, k_k, k_v, want_ans).total;
 }
 
+// process-wide choice between the two tile orders of decode_attn_kernel (see its DET parameter)
+static std::atomic<int> g_deterministic{0};
+
 // Launch tags are unique within the process (a wrap after 2^32 launches could only matter for a workspace
 // last used exactly 2^32 launches earlier); 0 is never handed out.
 static unsigned int next_launch_tag()
@@ -1757,17 +1769,23 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     // One-time set-up per instantiation (and per process): raise the dynamic LDS limit, and make sure the kernel has
     // no static LDS — its table gathers use absolute LDS addresses, which assumes the dynamic block starts at 0.
     static const hipError_t setup = [] {
-        hipFuncAttributes attr;
-        hipError_t r = hipFuncGetAttributes(&attr, (const void*)decode_attn_kernel<DSUB>);
-        if (r != hipSuccess) return r;
-        if (attr.sharedSizeBytes != 0) return hipErrorInvalidConfiguration;
-        return hipFuncSetAttribute((const void*)decode_attn_kernel<DSUB>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)Lds<DSUB>::total);
+        for (const void* f : {(const void*)decode_attn_kernel<DSUB, false>, (const void*)decode_attn_kernel<DSUB, true>}) {
+            hipFuncAttributes attr;
+            hipError_t r = hipFuncGetAttributes(&attr, f);
+            if (r != hipSuccess) return r;
+            if (attr.sharedSizeBytes != 0) return hipErrorInvalidConfiguration;
+            r = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)Lds<DSUB>::total);
+            if (r != hipSuccess) return r;
+        }
+        return hipSuccess;
     }();
     hipError_t e = setup;
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((int64_t)g.B * g.Hkv * pl.S);
-    hipLaunchKernelGGL(decode_attn_kernel<DSUB>, dim3(grid), dim3(kDaThreads), shmem, st, p);
+    if (g_deterministic.load(std::memory_order_relaxed))
+        hipLaunchKernelGGL((decode_attn_kernel<DSUB, true>), dim3(grid), dim3(kDaThreads), shmem, st, p);
+    else
+        hipLaunchKernelGGL((decode_attn_kernel<DSUB, false>), dim3(grid), dim3(kDaThreads), shmem, st, p);
     if (want_ans) {
         DsParams d;
         d.q = a.q; d.codes_k = a.codes_k; d.cb_k = a.cb_k; d.idx_k = a.idx_k; d.rows_k = a.rows_k;
@@ -1790,6 +1808,8 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     }
     return hipGetLastError();
 }
+
+int set_decode_deterministic(int on) { return g_deterministic.exchange(on ? 1 : 0); }
 
 hipError_t launch_decode_attn(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st)
 {
