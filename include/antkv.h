@@ -146,7 +146,8 @@ int antkv_gather_rows(const antkv_geom* geom, const void* x, int64_t N, const in
  * |scale * log2(e) * q_h[m] . cb_k[g][m][c]| over m and c.  The output stays within 2e-3 relative L2 of the exact
  * result while R_h <= L * 1e-3 / (ln 2 * sqrt(M / 12)) (L the number of levels above, M = D / d_sub sub-spaces:
  * about 14, 20, 29 for d_sub 4, 8, 16 and 82, 58 for the 12-bit formats with d_sub 32, 16); for larger entries the
- * bound grows in proportion to R_h.  Anchor tokens are scored from their FP16 rows and are not affected.
+ * bound grows in proportion to R_h (d_sub 8 and 16: unless ANTKV_DECODE_WIDE_TABLE is set, see
+ * antkv_set_decode_options).  Anchor tokens are scored from their FP16 rows and are not affected.
  * Optional decode-time Anchor Score (Eq. (4) with the single query row over K_eff):
  *   ans_k, ans_v      fp32 [B][Hkv][N], both or neither (NULL):  ans_v[j] = sum_h p_hj,
  *            ans_k[j] = sum_h p_hj (1 - p_hj) ||q_h||_2
@@ -164,15 +165,22 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
                       int64_t k_resel, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Reproducibility of antkv_decode_attn (and of the entry points built on it).  Codes, scores of antkv_anchor_select and
- * index sets are the same on every run.  The attention output of the one-byte-code kernel is, by default, reproducible
- * only to rounding level: after its first tile a wave pulls 64-token tiles from a counter, so the order of the fp32
- * sums varies from launch to launch.  antkv_set_decode_deterministic(1) makes every wave walk a fixed sequence of
- * tiles instead: the output is then the same bit for bit for the same inputs, shape and workspace size, at a small
- * cost in balance between the waves.  Process-wide, takes effect for launches enqueued afterwards; returns the previous
- * setting.  The 12-bit kernels always work in a fixed order.
+ * Options of the one-byte-code decode kernel (antkv_decode_attn and the entry points built on it).  Process-wide mask;
+ * takes effect for launches enqueued afterwards; returns the previous mask.  The default (0) is the fastest.
+ *   ANTKV_DECODE_FIXED_ORDER  Reproducibility.  Codes, scores of antkv_anchor_select and index sets are the same on every
+ *       run anyway.  The attention output is, by default, reproducible only to rounding level: after its first tile a wave
+ *       pulls 64-token tiles from a counter, so the order of the fp32 sums varies from launch to launch.  With this bit
+ *       every wave walks a fixed sequence of tiles: the output is then the same bit for bit for the same inputs, shape
+ *       and workspace size, at a small cost in balance between the waves.  (The 12-bit kernels always work in a fixed
+ *       order.)
+ *   ANTKV_DECODE_WIDE_TABLE   Score range (see "Precision" at antkv_decode_attn).  The q . centroid table carries a
+ *       second, residual entry per (code, sub-space): 30-bit instead of 15-bit fixed point, which lifts the limit on R_h
+ *       for d_sub 8 and 16 at the price of a second table walk per token (about a quarter more time per step).
+ *       d_sub 4 has no room for the second entry and ignores the bit; the 12-bit formats have 16-bit entries throughout.
  */
-int antkv_set_decode_deterministic(int on);
+#define ANTKV_DECODE_FIXED_ORDER 1
+#define ANTKV_DECODE_WIDE_TABLE 2
+int antkv_set_decode_options(int options);
 
 /*
  * Decode attention on a cache whose keys were stored BEFORE the rotary position embedding (Sec. 3.3, last paragraph:

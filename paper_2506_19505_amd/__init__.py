@@ -15,7 +15,9 @@ from .binding import (
     decode_attn,
     decode_attn_prerope,
     decode_attn_static,
-    set_decode_deterministic,
+    DECODE_FIXED_ORDER,
+    DECODE_WIDE_TABLE,
+    set_decode_options,
     encode,
     gather_rows,
     lib_path,
@@ -35,7 +37,9 @@ __all__ = [
     "decode_attn",
     "decode_attn_prerope",
     "decode_attn_static",
-    "set_decode_deterministic",
+    "DECODE_FIXED_ORDER",
+    "DECODE_WIDE_TABLE",
+    "set_decode_options",
     "encode",
     "gather_rows",
     "lib_path",

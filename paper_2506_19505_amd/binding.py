@@ -14,7 +14,7 @@ _lib = None
 EXPORTS = (
     "antkv_version", "antkv_strerror", "antkv_encode", "antkv_anchor_select_workspace", "antkv_anchor_select",
     "antkv_topk_workspace", "antkv_topk", "antkv_gather_rows", "antkv_decode_attn_workspace", "antkv_decode_attn",
-    "antkv_decode_attn_static", "antkv_set_decode_deterministic", "antkv_decode_attn_prerope_workspace", "antkv_decode_attn_prerope", "antkv_append_token", "antkv_prefill_attn", "antkv_kmeans_step_workspace", "antkv_kmeans_step",
+    "antkv_decode_attn_static", "antkv_set_decode_options", "antkv_decode_attn_prerope_workspace", "antkv_decode_attn_prerope", "antkv_append_token", "antkv_prefill_attn", "antkv_kmeans_step_workspace", "antkv_kmeans_step",
 )
 
 
@@ -94,8 +94,8 @@ def load_library():
                                           vp, vp, vp, vp, i64, vp, sz, vp]
         lib.antkv_decode_attn_static.restype = ctypes.c_int
         lib.antkv_decode_attn_static.argtypes = [gp, vp, f32, vp, vp, i64, i64, vp, vp, vp, vp, i64, vp, vp, i64, vp, vp]
-        lib.antkv_set_decode_deterministic.restype = ctypes.c_int
-        lib.antkv_set_decode_deterministic.argtypes = [ctypes.c_int]
+        lib.antkv_set_decode_options.restype = ctypes.c_int
+        lib.antkv_set_decode_options.argtypes = [ctypes.c_int]
         lib.antkv_decode_attn_prerope_workspace.restype = sz
         lib.antkv_decode_attn_prerope_workspace.argtypes = [gp, i64, i64]
         lib.antkv_decode_attn_prerope.restype = ctypes.c_int
@@ -349,10 +349,13 @@ def decode_attn_prerope(geom: Geometry, q: torch.Tensor, scale: float, codes_k: 
     return out
 
 
-def set_decode_deterministic(on: bool) -> bool:
-    """antkv_set_decode_deterministic: fixed tile order in the decode kernel (bit-reproducible output).  Returns the
-    previous setting."""
-    return bool(load_library().antkv_set_decode_deterministic(1 if on else 0))
+DECODE_FIXED_ORDER, DECODE_WIDE_TABLE = 1, 2     # ANTKV_DECODE_* of include/antkv.h
+
+
+def set_decode_options(options: int) -> int:
+    """antkv_set_decode_options: process-wide option mask of the one-byte-code decode kernel (DECODE_FIXED_ORDER for a
+    bit-reproducible output, DECODE_WIDE_TABLE for 30-bit table entries).  Returns the previous mask."""
+    return int(load_library().antkv_set_decode_options(int(options)))
 
 
 STATIC_SCRATCH_BYTES = 8 << 20     # ANTKV_STATIC_SCRATCH_BYTES of include/antkv.h

@@ -362,7 +362,7 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
                             out, ans_k, ans_v, resel_idx_k, resel_idx_v, k_resel, workspace, workspace_bytes, stream);
 }
 
-int antkv_set_decode_deterministic(int on) { return set_decode_deterministic(on); }
+int antkv_set_decode_options(int options) { return set_decode_options(options); }
 
 size_t antkv_decode_attn_prerope_workspace(const antkv_geom* geom, int64_t N, int64_t k_v)
 {

@@ -136,7 +136,7 @@ struct DecodeArgs {
     float *ans_k, *ans_v;
     uint32_t* topk_hist;   // optional: first-level top-k histograms that the score pass fills (see launch_topk2_begin)
 };
-int set_decode_deterministic(int on);   // returns the previous setting
+int set_decode_options(int options);   // ANTKV_DECODE_* mask; returns the previous mask
 int decode_num_splits(const Geom& g, int64_t N);
 size_t decode_workspace_bytes(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans);
 hipError_t launch_decode_attn(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st);

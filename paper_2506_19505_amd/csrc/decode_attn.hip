@@ -314,12 +314,20 @@ __device__ void wg_merge_and_store(char* smem, float (&m_ref)[kNH], float (&l_su
     }
 }
 
-// DET: every wave walks a fixed sequence of tiles (w, w + 16, ...) instead of pulling them from the workgroup's counter:
-// the order of all sums is then fixed and the output is the same bit for bit on every launch (the opt-in mode of
-// antkv_set_decode_deterministic; the counter balances the waves better).
-template <int DSUB, bool DET>
+// MODE is the option mask of antkv_set_decode_options, compiled in so that the default kernel carries none of it:
+//   bit 0 (fixed order)  every wave walks a fixed sequence of tiles (w, w + 16, ...) instead of pulling them from the
+//                        workgroup's counter: the order of all sums is then fixed and the output is the same bit for bit
+//                        on every launch (the counter balances the waves better);
+//   bit 1 (wide table)   the lookup table carries a second entry per (code, sub-space), the residual of the first in
+//                        units of quantum / 32512, in the slots that otherwise hold copies of the first, and every tile
+//                        walks the table twice: 30-bit instead of 15-bit entries, for queries whose products with the
+//                        centroids leave the range that the 15-bit quantum serves.  d = 4 has no spare slots (its 32
+//                        sub-spaces fill the 32 slots of a row) and ignores the bit.
+template <int DSUB, int MODE>
 __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams p)
 {
+    constexpr bool DET = (MODE & 1) != 0;
+    constexpr bool WIDE = (MODE & 2) != 0 && DSUB != 4;
     constexpr int M = kD / DSUB;
     constexpr int CW = M / 4;                          // code dwords per token
     static_assert(kDaWaves == 16, "the table build gives each of 16 waves 16 of the 256 codes");
@@ -603,13 +611,14 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             if (lane == 0) s_red[wave * 8 + h] = wm;
         }
         lds_barrier();
-        float inv_q[kNH];
+        float inv_q[kNH], quantum[kNH];
         {
             const int hh = lane >> 4, ws = lane & 15;
             const float r_r = row16_max((ws < kDaWaves) ? s_red[ws * 8 + hh] : 0.f);
 #pragma unroll
             for (int h = 0; h < kNH; ++h) {
                 const float r = lane_bcast(r_r, 16 * h);
+                if constexpr (WIDE) quantum[h] = (r > 0.f) ? r / kLutMax : 1.0f;
                 // the table quantum is parked in LDS until the stream starts (keeps registers free for the anchors)
                 if (tid == 0) ((float*)s_misc)[12 + h] = (r > 0.f) ? r / kLutMax : 1.0f;
                 inv_q[h] = (r > 0.f) ? kLutMax / r : 0.f;
@@ -644,6 +653,39 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
 #pragma unroll
                 for (int rep = 0; rep < REPS; ++rep)
                     s_lut[l_code * 32 + m + M * ((rep + (lane >> 2)) & (REPS - 1))] = e;
+            }
+        }
+        if constexpr (WIDE) {
+            // Residual entries, in units of quantum / (2 kLutMax) (|.| <= kLutMax), replace the odd copies: copy c of
+            // sub-space m is then the pair of slots m + 2 M c (first entry) and m + M + 2 M c (residual).
+            static_assert(!WIDE || REPS >= 2, "the residual entries live in the slots of the copies");
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                uint32_t hw[kNH];
+#pragma unroll
+                for (int h = 0; h < kNH; ++h) {
+                    const float first = rintf(val[j][h] * inv_q[h]);
+                    const int qv = (int)rintf((val[j][h] - first * quantum[h]) * (inv_q[h] * (2.f * kLutMax)));
+                    const int hi = (qv + 64) >> 7;
+                    const int lo = qv - 128 * hi;
+                    hw[h] = ((uint32_t)lo & 0xffu) | (((uint32_t)(-hi) & 0xffu) << 8);
+                }
+                ent[j] = uint2_t{hw[0] | (hw[1] << 16), hw[2] | (hw[3] << 16)};
+            }
+            if (ent_on) {
+#pragma unroll
+                for (int r = 0; r < NJ; ++r) {
+                    const int j = (r + lane) & (NJ - 1);
+                    uint2_t e = ent[0];
+#pragma unroll
+                    for (int jj = 1; jj < NJ; ++jj) e = (j == jj) ? ent[jj] : e;
+                    const int m = (DSUB == 8) ? 4 * j + kgrp : (DSUB == 16 ? 2 * j + kgrp : 8 * (j >> 1) + 2 * kgrp + (j & 1));
+#pragma unroll
+                    for (int rep = 0; rep < REPS; ++rep) {
+                        const int copy = (rep + (lane >> 2)) & (REPS - 1);
+                        if (copy & 1) s_lut[l_code * 32 + m + M * copy] = e;
+                    }
+                }
             }
         }
         // the V table is not needed before the first P.V: its loads had the whole table build to land
@@ -765,6 +807,24 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                                                            c.k_wgt, si, 0, 0, 0);
         }
         return si;
+    };
+    // Wide table: the second walk's constants (the slot's table bit flipped) and the combination of the two walks.  A lane's
+    // first walk summed first entries if bit log2(M) of its own number (mod 32) is clear, residuals otherwise; after the
+    // MFMA's transposition the token of register i sat in lane 16 tj + 4 kgrp + i.
+    auto other_table = [&](const KConst& c) -> KConst {
+        KConst c2 = c;
+#pragma unroll
+        for (int i = 0; i < CW; ++i) c2.kc[i] = c.kc[i] ^ (0x01010101u * (uint32_t)(M << 3));
+        return c2;
+    };
+    auto wide_x = [&](const KConst& c, const int4_t& si, const int4_t& sj, float base, float (&x)[4]) {
+        const bool swapped = (M == 16) ? (tj & 1) : (kgrp >> 1);
+        const float q2 = c.lut_q * (1.0f / (2.f * kLutMax));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int first = swapped ? sj[i] : si[i], resid = swapped ? si[i] : sj[i];
+            x[i] = fmaf((float)resid, q2, fmaf((float)first, c.lut_q, base));
+        }
     };
     // max / sum over the lanes that work for the same head (lane % 4), result in all of them
     auto head_max = [&](float v) -> float {
@@ -980,9 +1040,13 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                 // register i of lane (4 c + h, g) = entry 16 c + 4 g + i, head h (classes 2 and 3 are empty: keep bits 0)
                 const uint32_t keep_bits = (uint32_t)(keep64 >> (32 * (tj >> 1) + 16 * (tj & 1) + 4 * kgrp));
                 float sr[4], lm = kNegBig;
+                if constexpr (WIDE) {
+                    const int4_t sj = k_scores(other_table(kcst), kw, [] {});
+                    wide_x(kcst, si, sj, 0.f, sr);
+                }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    sr[i] = (float)si[i] * kcst.lut_q;
+                    if constexpr (!WIDE) sr[i] = (float)si[i] * kcst.lut_q;
                     lm = fmaxf(lm, ((keep_bits >> i) & 1u) ? sr[i] : kNegBig);
                 }
                 lm = head_max(lm);
@@ -1140,12 +1204,19 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             const uint32_t mw = s_mask[(2 * (uint32_t)tile + mask_dw) & (L::mask_words - 1)];
 
             // ---- K side: scores in table quanta
-            const int4_t si = k_scores(kcst, kw_in, [&] { if constexpr (DSUB != 4) reload(); });
+            // (wide table: two walks; the codes may be reloaded once the second walk's gathers are issued)
+            const int4_t si = k_scores(kcst, kw_in, [&] { if constexpr (DSUB != 4 && !WIDE) reload(); });
+            int4_t sj = {0, 0, 0, 0};
+            if constexpr (WIDE) sj = k_scores(other_table(kcst), kw_in, [&] { reload(); });
             // ---- softmax: register i = token (tj, 4 kgrp + i), head tq.  x = score - reference.
             const uint32_t keep_bits = ~mw >> mask_sh;                 // bit i set: token i is neither anchored nor past the range
             float x[4];
+            if constexpr (WIDE) {
+                wide_x(kcst, si, sj, neg_m, x);
+            } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) x[i] = fmaf((float)si[i], kcst.lut_q, neg_m);
+                for (int i = 0; i < 4; ++i) x[i] = fmaf((float)si[i], kcst.lut_q, neg_m);
+            }
             if (__any(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])) > kPShift)) {
                 // some score exceeds the running maximum by more than the head room: move the reference, rescale
                 float lm = kNegBig;
@@ -1171,8 +1242,12 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                             acc[a][rho][h] = v;
                         }
                 }
+                if constexpr (WIDE) {
+                    wide_x(kcst, si, sj, neg_m, x);
+                } else {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) x[i] = fmaf((float)si[i], kcst.lut_q, neg_m);
+                    for (int i = 0; i < 4; ++i) x[i] = fmaf((float)si[i], kcst.lut_q, neg_m);
+                }
             }
             uint4_t pa4;
 #pragma unroll
@@ -1739,8 +1814,8 @@ size_t decode_workspace_bytes(const Geom& g, int64_t N, int64_t k_k, int64_t k_v
     return da_plan(g, N, k_k, k_v, want_ans).total;
 }
 
-// process-wide choice between the two tile orders of decode_attn_kernel (see its DET parameter)
-static std::atomic<int> g_deterministic{0};
+// process-wide option mask of antkv_set_decode_options (see the MODE parameter of decode_attn_kernel)
+static std::atomic<int> g_options{0};
 
 // Launch tags are unique within the process (a wrap after 2^32 launches could only matter for a workspace
 // last used exactly 2^32 launches earlier); 0 is never handed out.
@@ -1769,7 +1844,8 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     // One-time set-up per instantiation (and per process): raise the dynamic LDS limit, and make sure the kernel has
     // no static LDS — its table gathers use absolute LDS addresses, which assumes the dynamic block starts at 0.
     static const hipError_t setup = [] {
-        for (const void* f : {(const void*)decode_attn_kernel<DSUB, false>, (const void*)decode_attn_kernel<DSUB, true>}) {
+        for (const void* f : {(const void*)decode_attn_kernel<DSUB, 0>, (const void*)decode_attn_kernel<DSUB, 1>,
+                              (const void*)decode_attn_kernel<DSUB, 2>, (const void*)decode_attn_kernel<DSUB, 3>}) {
             hipFuncAttributes attr;
             hipError_t r = hipFuncGetAttributes(&attr, f);
             if (r != hipSuccess) return r;
@@ -1782,10 +1858,12 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     hipError_t e = setup;
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((int64_t)g.B * g.Hkv * pl.S);
-    if (g_deterministic.load(std::memory_order_relaxed))
-        hipLaunchKernelGGL((decode_attn_kernel<DSUB, true>), dim3(grid), dim3(kDaThreads), shmem, st, p);
-    else
-        hipLaunchKernelGGL((decode_attn_kernel<DSUB, false>), dim3(grid), dim3(kDaThreads), shmem, st, p);
+    switch (g_options.load(std::memory_order_relaxed) & 3) {
+    case 0: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 0>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
+    case 1: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 1>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
+    case 2: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 2>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
+    default: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 3>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
+    }
     if (want_ans) {
         DsParams d;
         d.q = a.q; d.codes_k = a.codes_k; d.cb_k = a.cb_k; d.idx_k = a.idx_k; d.rows_k = a.rows_k;
@@ -1809,7 +1887,7 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     return hipGetLastError();
 }
 
-int set_decode_deterministic(int on) { return g_deterministic.exchange(on ? 1 : 0); }
+int set_decode_options(int options) { return g_options.exchange(options & 3); }
 
 hipError_t launch_decode_attn(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st)
 {

@@ -103,6 +103,23 @@ def test_decode_query_gain(oracle, d, gain):
     assert (err <= tol).all(), f"relative L2 {err.max():.3e}"
 
 
+@pytest.mark.parametrize("d", [8, 16])
+@pytest.mark.parametrize("gain", [1, 4, 16, 64])
+def test_decode_wide_table(oracle, d, gain):
+    """ANTKV_DECODE_WIDE_TABLE: with the residual entries in the table the plain 2e-3 tolerance holds whatever the query
+    magnitude is (here up to 64 times the recipe's), anchors, one-sided lists and a ragged tail included."""
+    B, Hq, Hkv, N = 2, 8, 2, 3000 + 37
+    k = anchor_count(N)
+    c = _cache_from_kv(oracle, 31 + d, B, Hq, Hkv, N, d, k, k // 2)
+    c["q"] = (c["q"].astype(np.float32) * gain).astype(np.float16)
+    was = antkv.set_decode_options(antkv.DECODE_WIDE_TABLE)
+    try:
+        got, want = _run_decode(oracle, c, antkv.Geometry(B, Hq, Hkv, d), 1 / np.sqrt(128))
+    finally:
+        antkv.set_decode_options(was)
+    _check_out(got, want, f"wide table d={d} query gain {gain}")
+
+
 def test_decode_tiny_contexts(oracle):
     B, Hq, Hkv, d = 2, 4, 1, 8
     for N in (1, 2, 63, 64, 65):

@@ -1,5 +1,5 @@
 """Run-twice bit comparison.  Codes, Anchor Scores and index sets are the same on every run; the decode output of the
-one-byte-code kernel is bit-reproducible in the opt-in fixed-tile-order mode (antkv_set_decode_deterministic), and the
+one-byte-code kernel is bit-reproducible in the opt-in fixed-tile-order mode (antkv_set_decode_options), and the
 12-bit kernels always are."""
 import numpy as np
 import pytest
@@ -44,14 +44,14 @@ def test_decode_fixed_tile_order_is_bit_reproducible(oracle, d):
     geom = antkv.Geometry(B, Hq, Hkv, d)
     ws = antkv.DecodeWorkspace(geom, N, k, k, 0, "cuda")
     outs = torch.empty((6, B, Hq, 128), dtype=torch.float16, device="cuda")
-    was = antkv.set_decode_deterministic(True)
+    was = antkv.set_decode_options(antkv.DECODE_FIXED_ORDER)
     try:
         for i in range(6):
             antkv.decode_attn(geom, t["q"], 0.1, t["ck"], t["cv"], t["cbk"], t["cbv"], t["ik"], t["rk"], t["iv"], t["rv"],
                               out=outs[i], workspace=ws)
         torch.cuda.synchronize()
     finally:
-        antkv.set_decode_deterministic(was)
+        antkv.set_decode_options(was)
     for i in range(1, 6):
         assert torch.equal(outs[i], outs[0]), f"launch {i} differs from launch 0"
     want = oracle.decode_attn(c["q"], c["ck"], c["cv"], c["cbk"], c["cbv"], c["ik"], c["rk"], c["iv"], c["rv"], 0.1)
