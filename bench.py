@@ -314,9 +314,7 @@ def main() -> int:
                    ck=dev(random_codes(w.seed, "k", w.B, w.Hkv, w.N, w.M)), cv=dev(random_codes(w.seed, "v", w.B, w.Hkv, w.N, w.M)),
                    ik=dev(random_anchor_sets(w.seed, "k", w.B, w.Hkv, w.N, w.k)), iv=dev(random_anchor_sets(w.seed, "v", w.B, w.Hkv, w.N, w.k)),
                    rk=dev(normal_fp16(w.seed, "rows_k", (w.B, w.Hkv, w.k, w.D))), rv=dev(normal_fp16(w.seed, "rows_v", (w.B, w.Hkv, w.k, w.D))))
-        g_c = geom.c()
-        pr_ws = torch.empty(antkv.load_library().antkv_decode_attn_prerope_workspace(__import__("ctypes").byref(g_c), w.N, w.k),
-                            dtype=torch.uint8, device=devc)
+        pr_ws = antkv.decode_attn_prerope_workspace(geom, w.N, w.k, devc)
         fpr = lambda i: antkv.decode_attn_prerope(geom, prt["q"], w.scale, prt["ck"], prt["cv"], cbk_d, cbv_d, prt["ik"], prt["rk"],
                                                   prt["iv"], prt["rv"], rope_base=500000.0, rope_style=1, pos0=0, out=out, workspace=pr_ws)
         settle(fpr, 0.1)

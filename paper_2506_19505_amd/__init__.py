@@ -14,6 +14,7 @@ from .binding import (
     kmeans_step,
     decode_attn,
     decode_attn_prerope,
+    decode_attn_prerope_workspace,
     decode_attn_static,
     DECODE_FIXED_ORDER,
     DECODE_WIDE_TABLE,
@@ -36,6 +37,7 @@ __all__ = [
     "kmeans_step",
     "decode_attn",
     "decode_attn_prerope",
+    "decode_attn_prerope_workspace",
     "decode_attn_static",
     "DECODE_FIXED_ORDER",
     "DECODE_WIDE_TABLE",

@@ -320,6 +320,12 @@ def decode_attn(geom: Geometry, q: torch.Tensor, scale: float, codes_k: torch.Te
     return out
 
 
+def decode_attn_prerope_workspace(geom: Geometry, N: int, k_v: int, device) -> torch.Tensor:
+    """A workspace of antkv_decode_attn_prerope_workspace(geom, N, k_v) bytes for decode_attn_prerope."""
+    g = geom.c()
+    return _workspace(load_library().antkv_decode_attn_prerope_workspace(ctypes.byref(g), N, k_v), device)
+
+
 def decode_attn_prerope(geom: Geometry, q: torch.Tensor, scale: float, codes_k: torch.Tensor, codes_v: torch.Tensor,
                         cb_k: torch.Tensor, cb_v: torch.Tensor, idx_k: torch.Tensor | None, rows_k: torch.Tensor | None,
                         idx_v: torch.Tensor | None, rows_v: torch.Tensor | None, rope_base: float = 10000.0,
@@ -339,7 +345,7 @@ def decode_attn_prerope(geom: Geometry, q: torch.Tensor, scale: float, codes_k: 
         out = torch.empty((B, Hq, D), dtype=torch.float16, device=q.device)
     g = geom.c()
     if workspace is None:
-        workspace = _workspace(load_library().antkv_decode_attn_prerope_workspace(ctypes.byref(g), N, k_v), q.device)
+        workspace = decode_attn_prerope_workspace(geom, N, k_v, q.device)
     rc = load_library().antkv_decode_attn_prerope(
         ctypes.byref(g), _p(q), float(scale), _p(codes_k), _p(codes_v), N, N_cap, _p(cb_k), _p(cb_v),
         _p(idx_k) if k_k else None, _p(rows_k) if k_k else None, k_k,

@@ -120,3 +120,24 @@ def test_static_scratch_refuses_oversized_shapes(lib):
     rc = lib.antkv_decode_attn_static(ctypes.byref(g), fake, 0.1, fake, fake, 4096, 4096, fake, fake, None, None, 0,
                                       None, None, 0, fake, None)
     assert rc == 3                                     # ANTKV_EWORKSPACE
+
+
+def test_decode_options_and_prerope_argument_errors(lib):
+    prev = lib.antkv_set_decode_options(3)
+    assert lib.antkv_set_decode_options(prev) == 3            # returns the previous mask; unknown bits are dropped
+    assert lib.antkv_set_decode_options(0xF0) == prev and lib.antkv_set_decode_options(prev) == 0
+    g = _g(B=1)
+    fake = ctypes.c_void_p(4096)
+    ws_bytes = lib.antkv_decode_attn_prerope_workspace(ctypes.byref(g), 1000, 0)
+    # rotated FP16 rows + the identity index list + the decode kernels' own scratch
+    assert ws_bytes >= 8 * 1000 * (256 + 4) + lib.antkv_decode_attn_workspace(ctypes.byref(g), 1000, 1000, 0, 0)
+    assert lib.antkv_decode_attn_prerope_workspace(ctypes.byref(_g(d=2)), 1000, 10) == 0
+    call = lambda base, style, pos0, ws=fake, nbytes=1 << 40: lib.antkv_decode_attn_prerope(
+        ctypes.byref(g), fake, 0.1, fake, fake, 1000, 1000, fake, fake, None, None, 0, None, None, 0,
+        base, style, pos0, fake, ws, nbytes, None)
+    assert call(1.0, 0, 0) == EINVAL                          # the base must exceed 1
+    assert call(10000.0, 2, 0) == EINVAL                      # pairing 0 or 1
+    assert call(10000.0, 1, -1) == EINVAL                     # positions start at pos0 >= 0
+    assert call(10000.0, 1, 0, ws=None) == EWORKSPACE
+    assert call(10000.0, 1, 0, nbytes=ws_bytes - 1) == EWORKSPACE
+
