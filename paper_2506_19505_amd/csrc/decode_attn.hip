@@ -318,6 +318,9 @@ __device__ void wg_merge_and_store(char* smem, float (&m_ref)[kNH], float (&l_su
 //   bit 0 (fixed order)  every wave walks a fixed sequence of tiles (w, w + 16, ...) instead of pulling them from the
 //                        workgroup's counter: the order of all sums is then fixed and the output is the same bit for bit
 //                        on every launch (the counter balances the waves better);
+//   bit 2 (long lists)   not an option of the caller: set by the launcher for anchor lists of 3073 .. 16384 entries, which
+//                        are then held whole in the two table areas during the prologue (shorter lists fit the waves'
+//                        staging areas; longer ones are searched in global memory);
 //   bit 1 (wide table)   the lookup table carries a second entry per (code, sub-space), the residual of the first in
 //                        units of quantum / 32512, in the slots that otherwise hold copies of the first, and every tile
 //                        walks the table twice: 30-bit instead of 15-bit entries, for queries whose products with the
@@ -328,6 +331,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
 {
     constexpr bool DET = (MODE & 1) != 0;
     constexpr bool WIDE = (MODE & 2) != 0 && DSUB != 4;
+    constexpr bool LONG = (MODE & 4) != 0;
     constexpr int M = kD / DSUB;
     constexpr int CW = M / 4;                          // code dwords per token
     static_assert(kDaWaves == 16, "the table build gives each of 16 waves 16 of the 256 codes");
@@ -379,6 +383,12 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     uint32_t pre_codes[CW];
 #pragma unroll
     for (int i = 0; i < CW; ++i) pre_codes[i] = 0u;
+    // (long-list kernels: a wave often has a second tile, sp + S * (wave + 16); the same is fetched for it, so that the
+    // second tile too is left with one round trip, its FP16 rows)
+    int pre2_tok = 0, pre2_info = 0;
+    uint32_t pre2_codes[CW];
+#pragma unroll
+    for (int i = 0; i < CW; ++i) pre2_codes[i] = 0u;
     uint32_t pre_rows[32];                         // the tile's FP16 rows, in the form the tile works on (requested before the prologue's last barrier)
     // FP16 K rows of the 16 entries from e0 on as MFMA operands: lane (entry arow, k-group kgrp) holds channels
     // 32 st + 8 kgrp .. + 7 in r[4 st .. 4 st + 3]
@@ -425,9 +435,13 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         // cut to the range by a cooperative search first (a few dependent load latencies)
         // both lists are short: they go to LDS whole (into the waves' staging areas, which nobody uses before the
         // anchors), and the bitmap and the cross membership of the anchor entries are worked out from there
-        constexpr int kScanBatch = 3;                             // one load per thread and round, all in flight together
-        constexpr int kScanMax = kScanBatch * kDaThreads;
-        static_assert(2 * kScanMax * 4 <= kDaWaves * kStgBytes, "two whole lists fit the staging areas");
+        // (long-list kernels, chosen by the host from the list lengths: the lists go to the two table areas instead, up
+        // to 16384 entries each, in batches of the same three rounds; the tables are written after the barrier that
+        // follows the last use of the lists)
+        constexpr int kScanBatch = LONG ? 9 : 3;                  // one load per thread and round, all in flight together
+        constexpr int kScanMax = LONG ? 16384 : kScanBatch * kDaThreads;
+        static_assert(LONG || 2 * kScanMax * 4 <= kDaWaves * kStgBytes, "two whole lists fit the staging areas");
+        static_assert(kScanMax * 4 <= 65536, "a whole list fits one table area");
         const bool lists_in_lds = p.k_k <= kScanMax && p.k_v <= kScanMax;
         int scan_val[2][kScanBatch];
         if (lists_in_lds) {
@@ -472,14 +486,32 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             }
         }
         if (tid < kNH * kD) ((half_t*)(smem + L::qh))[tid] = qv16;
-        int32_t* s_lk = (int32_t*)(smem + L::pst);
-        int32_t* s_lv = s_lk + kScanMax;
+        int32_t* s_lk = (int32_t*)(smem + (LONG ? L::lut : L::pst));
+        int32_t* s_lv = LONG ? (int32_t*)(smem + L::cbv) : s_lk + kScanMax;
         if (lists_in_lds) {
 #pragma unroll
             for (int i = 0; i < kScanBatch; ++i) {
                 const int j = tid + i * kDaThreads;
                 if (j < p.k_k) s_lk[j] = scan_val[0][i];
                 if (j < p.k_v) s_lv[j] = scan_val[1][i];
+            }
+            if constexpr (LONG) {
+                // the rest of long lists, three rounds in flight at a time
+                const int k_max = p.k_k > p.k_v ? p.k_k : p.k_v;
+                for (int base = kScanBatch * kDaThreads; base < k_max; base += kScanBatch * kDaThreads) {
+#pragma unroll
+                    for (int i = 0; i < kScanBatch; ++i) {
+                        const int j = base + tid + i * kDaThreads;
+                        scan_val[0][i] = (j < p.k_k) ? idx_k[j] : -1;
+                        scan_val[1][i] = (j < p.k_v) ? idx_v[j] : -1;
+                    }
+#pragma unroll
+                    for (int i = 0; i < kScanBatch; ++i) {
+                        const int j = base + tid + i * kDaThreads;
+                        if (j < p.k_k) s_lk[j] = scan_val[0][i];
+                        if (j < p.k_v) s_lv[j] = scan_val[1][i];
+                    }
+                }
             }
         }
         for (int i = tid; i < L::mask_words; i += kDaThreads) s_mask[i] = 0u;
@@ -523,30 +555,34 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         // has an FP16 V row too (and where), a V entry whether its token is a K anchor (then the K entry covers it).
         {
             // a wave's first tile: one lane per entry, answers stay in registers; the entry's code row is requested at once
-            if (T_first < n_atiles) {
-                if (T_first < ntk) {
-                    const int e = 16 * T_first + lane;
+            auto resolve_tile = [&](int T, int& tok_o, int& info_o, uint32_t (&codes_o)[CW]) {
+                if (T >= n_atiles) return;
+                if (T < ntk) {
+                    const int e = 16 * T + lane;
                     if (lane < 16 && e < p.k_k) {
-                        pre_tok = lists_in_lds ? ((const lds_int*)s_lk)[e] : idx_k[e];
-                        pre_info = lists_in_lds ? find_sorted_lds((const lds_int*)s_lv, p.k_v, pre_tok) : find_sorted(idx_v, p.k_v, pre_tok);
-                        if (pre_info < 0) load_codes(cv + (int64_t)pre_tok * M, pre_codes);
+                        tok_o = lists_in_lds ? ((const lds_int*)s_lk)[e] : idx_k[e];
+                        info_o = lists_in_lds ? find_sorted_lds((const lds_int*)s_lv, p.k_v, tok_o) : find_sorted(idx_v, p.k_v, tok_o);
+                        if (info_o < 0) load_codes(cv + (int64_t)tok_o * M, codes_o);
                     }
                 } else {
-                    const int j = 32 * (T_first - ntk) + lane;
+                    const int j = 32 * (T - ntk) + lane;
                     if (lane < 32 && j < p.k_v) {
-                        pre_tok = lists_in_lds ? ((const lds_int*)s_lv)[j] : idx_v[j];
-                        const int f = lists_in_lds ? find_sorted_lds((const lds_int*)s_lk, p.k_k, pre_tok) : find_sorted(idx_k, p.k_k, pre_tok);
-                        pre_info = f >= 0 ? 1 : 0;
-                        load_codes(ck + (int64_t)pre_tok * M, pre_codes);
+                        tok_o = lists_in_lds ? ((const lds_int*)s_lv)[j] : idx_v[j];
+                        const int f = lists_in_lds ? find_sorted_lds((const lds_int*)s_lk, p.k_k, tok_o) : find_sorted(idx_k, p.k_k, tok_o);
+                        info_o = f >= 0 ? 1 : 0;
+                        load_codes(ck + (int64_t)tok_o * M, codes_o);
                     }
                 }
-            }
+            };
+            resolve_tile(T_first, pre_tok, pre_info, pre_codes);
+            if constexpr (LONG) resolve_tile(T_first + p.S * kDaWaves, pre2_tok, pre2_info, pre2_codes);
             // further tiles (a wave takes more than one when the lists are long for the number of workgroups): one
             // thread per entry, the answers go through global memory
             int32_t* info_bg = p.info + (int64_t)bg * (p.k_k + p.k_v);
             const int tiles_wg = n_atiles > sp ? (n_atiles - sp + p.S - 1) / p.S : 0;
-            if (tiles_wg > kDaWaves) {
-            for (int li = tid + 64 * kDaWaves; li < 64 * tiles_wg; li += kDaThreads) {
+            constexpr int kOwnTiles = LONG ? 2 : 1;                  // tiles per wave that the waves resolve themselves
+            if (tiles_wg > kOwnTiles * kDaWaves) {
+            for (int li = tid + 64 * kOwnTiles * kDaWaves; li < 64 * tiles_wg; li += kDaThreads) {
                 const int T = sp + p.S * (li >> 6), u = li & 63;
                 if (T < ntk) {
                     const int e = 16 * T + u;
@@ -1074,7 +1110,15 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             }
             // a further tile of this wave: fetch it the plain way (its cross membership was worked out in the prologue)
             const int Tn = T + p.S * kDaWaves;
-            if (Tn < n_atiles) {
+            if (LONG && Tn < n_atiles && T == T_first) {
+                // the second tile: tokens, cross membership and code rows are there since the prologue
+                pre_tok = pre2_tok;
+                pre_info = pre2_info;
+#pragma unroll
+                for (int i = 0; i < CW; ++i) pre_codes[i] = pre2_codes[i];
+                if (Tn < ntk) load_k_rows(16 * Tn, pre_rows);
+                else load_v_rows(32 * (Tn - ntk), pre_rows);
+            } else if (Tn < n_atiles) {
 #pragma unroll
                 for (int i = 0; i < CW; ++i) pre_codes[i] = 0u;
                 if (Tn < ntk) {
@@ -1845,7 +1889,9 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     // no static LDS — its table gathers use absolute LDS addresses, which assumes the dynamic block starts at 0.
     static const hipError_t setup = [] {
         for (const void* f : {(const void*)decode_attn_kernel<DSUB, 0>, (const void*)decode_attn_kernel<DSUB, 1>,
-                              (const void*)decode_attn_kernel<DSUB, 2>, (const void*)decode_attn_kernel<DSUB, 3>}) {
+                              (const void*)decode_attn_kernel<DSUB, 2>, (const void*)decode_attn_kernel<DSUB, 3>,
+                              (const void*)decode_attn_kernel<DSUB, 4>, (const void*)decode_attn_kernel<DSUB, 5>,
+                              (const void*)decode_attn_kernel<DSUB, 6>, (const void*)decode_attn_kernel<DSUB, 7>}) {
             hipFuncAttributes attr;
             hipError_t r = hipFuncGetAttributes(&attr, f);
             if (r != hipSuccess) return r;
@@ -1858,11 +1904,18 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     hipError_t e = setup;
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((int64_t)g.B * g.Hkv * pl.S);
-    switch (g_options.load(std::memory_order_relaxed) & 3) {
+    // anchor lists between 3073 and 16384 entries go through the kernels that hold them in the table areas
+    const int64_t k_max = a.k_k > a.k_v ? a.k_k : a.k_v;
+    const int mode = (g_options.load(std::memory_order_relaxed) & 3) | ((k_max > 3 * kDaThreads && k_max <= 16384) ? 4 : 0);   // (3 rounds of 1024 fit the staging areas)
+    switch (mode) {
     case 0: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 0>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
     case 1: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 1>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
     case 2: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 2>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
-    default: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 3>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
+    case 3: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 3>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
+    case 4: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 4>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
+    case 5: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 5>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
+    case 6: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 6>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
+    default: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 7>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
     }
     if (want_ans) {
         DsParams d;
