@@ -320,8 +320,8 @@ def main() -> int:
         settle(fpr, 0.1)
         ms_pr = timed(20, fpr)
         result["extra"].update({"prerope_decode_ms": ms_pr,
-                                "prerope_workload": f"{w.name}'s shape with keys stored before RoPE (rotate + de-quantise every key to an "
-                                                    f"FP16 row, then decode with every token as a K anchor); workspace {pr_ws.numel() / 1e9:.2f} GB"})
+                                "prerope_workload": f"{w.name}'s shape with keys stored before RoPE (a pass that de-quantises and rotates every "
+                                                    f"key and leaves q.k per head, then decode on those scores); workspace {pr_ws.numel() / 1e9:.2f} GB"})
         log(f"pre-RoPE decode on {w.name}'s shape: {ms_pr:.2f} ms")
         del prt, pr_ws
         torch.cuda.empty_cache()

@@ -58,7 +58,8 @@ int decode_attn_impl(const antkv_geom* geom, const void* q, float scale, const u
                       const uint8_t* codes_v, int64_t N, int64_t N_cap, const void* cb_k, const void* cb_v,
                       const int32_t* idx_k, const void* rows_k, int64_t k_k, const int32_t* idx_v, const void* rows_v,
                       int64_t k_v, void* out, float* ans_k, float* ans_v, int32_t* resel_idx_k, int32_t* resel_idx_v,
-                      int64_t k_resel, void* workspace, size_t workspace_bytes, void* stream)
+                      int64_t k_resel, void* workspace, size_t workspace_bytes, void* stream,
+                      const float* given_scores = nullptr)
 {
     Geom g;
     int rc = check_geom(geom, g);
@@ -114,6 +115,7 @@ int decode_attn_impl(const antkv_geom* geom, const void* q, float scale, const u
     a.cb_k = (const half_t*)cb_k; a.cb_v = (const half_t*)cb_v; a.idx_k = idx_k; a.rows_k = (const half_t*)rows_k;
     a.k_k = k_k; a.idx_v = idx_v; a.rows_v = (const half_t*)rows_v; a.k_v = k_v; a.out = (half_t*)out;
     a.ans_k = ans_k; a.ans_v = ans_v;
+    a.given_scores = given_scores;
     // with both index sets wanted, the score pass counts its scores into the selection's first histogram
     const bool fused = N > 0 && k_resel > 0 && resel_idx_k && resel_idx_v;
     a.topk_hist = fused ? launch_topk2_begin((int64_t)g.B * g.Hkv, N, (char*)workspace + dp.off_topk, st) : nullptr;
@@ -368,6 +370,8 @@ size_t antkv_decode_attn_prerope_workspace(const antkv_geom* geom, int64_t N, in
 {
     Geom g;
     if (check_geom(geom, g) || N < 0 || k_v < 0) return 0;
+    if (g.C == kC)   // one-byte codes: the K side's scores (16 bytes per token and KV head), then the plain call's workspace
+        return align_up((size_t)g.B * g.Hkv * (size_t)((N + 63) / 64 * 64) * 16) + align_up(antkv_decode_attn_workspace(geom, N, 0, k_v, 0));
     const size_t rows = align_up((size_t)g.B * g.Hkv * (size_t)N * kD * sizeof(half_t));
     const size_t iota = align_up((size_t)g.B * g.Hkv * (size_t)N * sizeof(int32_t));
     return rows + iota + align_up(antkv_decode_attn_workspace(geom, N, N, k_v, 0));
@@ -395,6 +399,17 @@ int antkv_decode_attn_prerope(const antkv_geom* geom, const void* q, float scale
     const size_t need = antkv_decode_attn_prerope_workspace(geom, N, k_v);
     if (!workspace || misaligned(workspace, 256) || workspace_bytes < need) return ANTKV_EWORKSPACE;
     char* w = (char*)workspace;
+    if (g.C == kC) {
+        // one-byte codes: the rotated keys are never written out; a first pass leaves q . RoPE(K_eff) of every token and
+        // head (FP16 anchor rows included), and the decode kernel takes its scores from there instead of from a table
+        const size_t sc_b = align_up((size_t)g.B * g.Hkv * (size_t)((N + 63) / 64 * 64) * 16);
+        if (!q || misaligned(q, 16) || !(scale > 0.f)) return ANTKV_EINVAL;
+        if (launch_rope_scores(g, (const half_t*)q, scale, codes_k, N, N_cap, (const half_t*)cb_k, idx_k, (const half_t*)rows_k,
+                               k_k, (double)rope_base, rope_style, pos0, (float*)w, (hipStream_t)stream) != hipSuccess)
+            return ANTKV_ELAUNCH;
+        return decode_attn_impl(geom, q, scale, codes_k, codes_v, N, N_cap, cb_k, cb_v, nullptr, nullptr, 0, idx_v, rows_v, k_v,
+                                out, nullptr, nullptr, nullptr, nullptr, 0, w + sc_b, workspace_bytes - sc_b, stream, (const float*)w);
+    }
     half_t* k_rot = (half_t*)w;
     int32_t* iota = (int32_t*)(w + rows_b);
     if (launch_rope_keys(g, codes_k, N, N_cap, (const half_t*)cb_k, idx_k, (const half_t*)rows_k, k_k, (double)rope_base,

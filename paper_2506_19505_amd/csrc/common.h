@@ -135,6 +135,9 @@ struct DecodeArgs {
     half_t* out;
     float *ans_k, *ans_v;
     uint32_t* topk_hist;   // optional: first-level top-k histograms that the score pass fills (see launch_topk2_begin)
+    // optional (one-byte codes, k_k = 0, no Anchor Scores): the K side's scores in log2 units as launch_rope_scores writes them;
+    // the K codes, the K codebook and scale are then not used
+    const float* given_scores = nullptr;
 };
 int set_decode_options(int options);   // ANTKV_DECODE_* mask; returns the previous mask
 int decode_num_splits(const Geom& g, int64_t N);
@@ -144,6 +147,10 @@ hipError_t launch_decode_attn(const Geom& g, const DecodeArgs& a, void* ws, hipS
 hipError_t launch_rope_keys(const Geom& g, const uint8_t* codes_k, int64_t N, int64_t N_cap, const half_t* cb_k,
                             const int32_t* idx_k, const half_t* rows_k, int64_t k_k, double rope_base, int rope_style,
                             int64_t pos0, half_t* rows_out, int32_t* iota_out, hipStream_t st);
+// one-byte codes: scores_out fp32 [B][Hkv][N][4] = scale * log2(e) * q_h . RoPE_{pos0 + j}(K_eff[j]) for the group's heads
+hipError_t launch_rope_scores(const Geom& g, const half_t* q, float scale, const uint8_t* codes_k, int64_t N, int64_t N_cap,
+                              const half_t* cb_k, const int32_t* idx_k, const half_t* rows_k, int64_t k_k, double rope_base,
+                              int rope_style, int64_t pos0, float* scores_out, hipStream_t st);
 size_t decode12_workspace_bytes(const Geom& g, int64_t N);
 hipError_t launch_decode12(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st);
 

@@ -234,6 +234,9 @@ struct DaParams {
     int Hq, Hkv, G;
     int S;                      // workgroups (token ranges) per (b, g)
     int64_t chunk;              // tokens per range (multiple of 64)
+    // Kernels with given scores: codes_k points to the K side's scores in log2 units instead, fp32
+    // [B][Hkv][n_pad / 4][4 heads][4 tokens] with n_pad = N rounded up to 64 (a 64-token tile is 64 float4, float4 number
+    // 16 tj + 4 kgrp + tq being what lane (tq, tj, kgrp) of the stream needs); cb_k is not used.
 };
 
 // LDS layout (bytes); the final merge re-uses the table area.  The two tables sit at multiples of 64 KB so
@@ -326,12 +329,17 @@ __device__ void wg_merge_and_store(char* smem, float (&m_ref)[kNH], float (&l_su
 //                        walks the table twice: 30-bit instead of 15-bit entries, for queries whose products with the
 //                        centroids leave the range that the 15-bit quantum serves.  d = 4 has no spare slots (its 32
 //                        sub-spaces fill the 32 slots of a row) and ignores the bit.
+//   bit 3 (given scores) not an option of the caller: the scores of the K side come from p.scores (keys that are rotated to
+//                        their position before the product with q have no table); no table is built, the K codes are
+//                        not read, the K anchor list is empty and V entries take their token's score from p.scores.
 template <int DSUB, int MODE>
 __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams p)
 {
     constexpr bool DET = (MODE & 1) != 0;
     constexpr bool WIDE = (MODE & 2) != 0 && DSUB != 4;
     constexpr bool LONG = (MODE & 4) != 0;
+    constexpr bool GIVEN = (MODE & 8) != 0;
+    static_assert(!GIVEN || (MODE & 6) == 0, "given scores go with the plain tables and short-list prologue only");
     constexpr int M = kD / DSUB;
     constexpr int CW = M / 4;                          // code dwords per token
     static_assert(kDaWaves == 16, "the table build gives each of 16 waves 16 of the 256 codes");
@@ -410,6 +418,12 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
             r[k] = *(const uint32_t*)(p.rows_v + ((int64_t)bg * p.k_v + (j < p.k_v ? j : p.k_v - 1)) * kD + 2 * lane);
         }
     };
+    // given scores: the four heads' scores of one token
+    float4_t pre_sc = {0.f, 0.f, 0.f, 0.f};
+    auto load_score = [&](int tok) -> float4_t {
+        const float* sp_ = (const float*)p.codes_k + ((int64_t)bg * ((p.N + 63) & ~63LL) + (int64_t)(tok & ~3)) * 4 + (tok & 3);
+        return float4_t{sp_[0], sp_[4], sp_[8], sp_[12]};
+    };
     auto load_codes = [&](const uint8_t* src, uint32_t (&dst)[CW]) {
         if constexpr (CW == 2) {
             const uint2_t a = *(const uint2_t*)src;
@@ -471,7 +485,9 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             opa[j] = uint4_t{0u, 0u, 0u, 0u};
-            if constexpr (DSUB == 8) {
+            if constexpr (GIVEN) {
+                opb[j] = uint4_t{0u, 0u, 0u, 0u};
+            } else if constexpr (DSUB == 8) {
                 opb[j] = *(const uint4_t*)(cbk + ((4 * j + kgrp) * 256 + l_code) * 8);
                 if (kgrp == l_mp && l_h < nheads) opa[j] = *(const uint4_t*)(qb + l_h * kD + (4 * j + l_mp) * 8);
             } else if constexpr (DSUB == 16) {
@@ -570,7 +586,8 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                         tok_o = lists_in_lds ? ((const lds_int*)s_lv)[j] : idx_v[j];
                         const int f = lists_in_lds ? find_sorted_lds((const lds_int*)s_lk, p.k_k, tok_o) : find_sorted(idx_k, p.k_k, tok_o);
                         info_o = f >= 0 ? 1 : 0;
-                        load_codes(ck + (int64_t)tok_o * M, codes_o);
+                        if constexpr (GIVEN) pre_sc = load_score(tok_o);
+                        else load_codes(ck + (int64_t)tok_o * M, codes_o);
                     }
                 }
             };
@@ -626,7 +643,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         float amax[kNH] = {0.f, 0.f, 0.f, 0.f};
         const bool ent_on = (DSUB != 16) || kgrp < 2;       // d = 16: only blocks 0 and 1 carry sub-spaces
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) {
+        for (int j = 0; j < (GIVEN ? 0 : NJ); ++j) {
             uint4_t a4 = opa[(DSUB == 4) ? (j >> 1) : j];
             if constexpr (DSUB == 4) {                       // sub-space 2 m' + u of the pair lives in half u of the slice
                 if (j & 1) { a4[0] = 0u; a4[1] = 0u; } else { a4[2] = 0u; a4[3] = 0u; }
@@ -642,13 +659,13 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         }
         float* s_red = (float*)(smem + L::red);
 #pragma unroll
-        for (int h = 0; h < kNH; ++h) {
+        for (int h = 0; h < (GIVEN ? 0 : kNH); ++h) {
             const float wm = wave_max_uniform(amax[h]);
             if (lane == 0) s_red[wave * 8 + h] = wm;
         }
         lds_barrier();
         float inv_q[kNH], quantum[kNH];
-        {
+        if constexpr (!GIVEN) {
             const int hh = lane >> 4, ws = lane & 15;
             const float r_r = row16_max((ws < kDaWaves) ? s_red[ws * 8 + hh] : 0.f);
 #pragma unroll
@@ -663,7 +680,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         uint2_t* s_lut = (uint2_t*)(smem + L::lut);
         uint2_t ent[NJ];
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) {
+        for (int j = 0; j < (GIVEN ? 0 : NJ); ++j) {
             uint32_t hw[kNH];
 #pragma unroll
             for (int h = 0; h < kNH; ++h) {
@@ -678,7 +695,7 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
         // round r a lane therefore stores entry (r + code) mod NJ, and starts with copy (code / 4) mod REPS of it:
         // the 32 lanes of an LDS pass then spread over 16 or 32 different slots.
         constexpr int REPS = 32 / M;
-        if (ent_on) {
+        if (!GIVEN && ent_on) {
 #pragma unroll
             for (int r = 0; r < NJ; ++r) {
                 const int j = (r + lane) & (NJ - 1);
@@ -805,6 +822,10 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     auto k_scores = [&](const KConst& c, const uint32_t (&kw_in)[CW], auto&& after_gathers) -> int4_t {
         // Code dwords are XOR-permuted so that step s finds the code of sub-space (s XOR kr) at a compile-time
         // register and a per-lane constant byte selector.
+        if constexpr (GIVEN) {                                           // no table: the caller has the scores
+            after_gathers();
+            return int4_t{0, 0, 0, 0};
+        }
         uint32_t kw[CW];
 #pragma unroll
         for (int i = 0; i < CW; ++i) kw[i] = kw_in[i];
@@ -897,11 +918,17 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
     const uint8_t* ck0 = ck + t0c * M;
     const uint8_t* cv0 = cv + t0c * M;
     const uint32_t last_rel = n_tiles > 0 ? (uint32_t)(p.N - 1 - t0) : 0u;     // tokens past the end are masked, not skipped
+    float4_t sc_next = {0.f, 0.f, 0.f, 0.f};                 // given scores: head tq of tokens (tj, 4 kgrp + i) of the next tile
+    const float4_t* sc0 = nullptr;
+    if constexpr (GIVEN) sc0 = (const float4_t*)p.codes_k + (int64_t)bg * ((p.N + 63) & ~63LL) + t0c + (16 * tj + 4 * kgrp + tq);
     auto load_tile = [&](int tile, uint32_t (&kw_)[CW], uint32_t (&vw_)[CW]) {
         uint32_t rel = (uint32_t)tile * 64u + (uint32_t)lane;
         rel = rel < last_rel ? rel : last_rel;
         const uint32_t off = rel * (uint32_t)M;
-        if (CW == 2) {
+        if constexpr (GIVEN) {
+            sc_next = sc0[(uint32_t)tile * 64u];
+            load_codes(cv0 + off, vw_);
+        } else if (CW == 2) {
             const uint2_t a = *(const uint2_t*)(ck0 + off), c = *(const uint2_t*)(cv0 + off);
             kw_[0] = a[0]; kw_[1] = a[1]; vw_[0] = c[0]; vw_[1] = c[1];
         } else {
@@ -1080,9 +1107,21 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                     const int4_t sj = k_scores(other_table(kcst), kw, [] {});
                     wide_x(kcst, si, sj, 0.f, sr);
                 }
+                if constexpr (GIVEN) {
+                    // lane = entry holds its token's four scores: through the staging area into the form above
+                    __builtin_amdgcn_wave_barrier();
+                    if (lane < 32) *(lds_u32x4*)(uintptr_t)(stg_b + 16u * (uint32_t)lane) = __builtin_bit_cast(uint4_t, pre_sc);
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        sr[i] = 0.f;
+                        if (tj < 2) sr[i] = __builtin_bit_cast(float, *(const lds_u32*)(uintptr_t)(stg_b + 16u * (uint32_t)(16 * tj + 4 * kgrp + i) + 4u * (uint32_t)tq));
+                    }
+                }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    if constexpr (!WIDE) sr[i] = (float)si[i] * kcst.lut_q;
+                    if constexpr (!WIDE && !GIVEN) sr[i] = (float)si[i] * kcst.lut_q;
                     lm = fmaxf(lm, ((keep_bits >> i) & 1u) ? sr[i] : kNegBig);
                 }
                 lm = head_max(lm);
@@ -1134,7 +1173,8 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                     if (lane < 32 && j < p.k_v) {
                         pre_tok = idx_v[j];
                         pre_info = info_bg[p.k_k + j];
-                        load_codes(ck + (int64_t)pre_tok * M, pre_codes);
+                        if constexpr (GIVEN) pre_sc = load_score(pre_tok);
+                        else load_codes(ck + (int64_t)pre_tok * M, pre_codes);
                     }
                     load_v_rows(32 * (Tn - ntk), pre_rows);
                 }
@@ -1249,13 +1289,21 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
 
             // ---- K side: scores in table quanta
             // (wide table: two walks; the codes may be reloaded once the second walk's gathers are issued)
+            float sg[4] = {0.f, 0.f, 0.f, 0.f};                       // given scores: taken before the reload replaces them
+            if constexpr (GIVEN) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sg[i] = sc_next[i];
+            }
             const int4_t si = k_scores(kcst, kw_in, [&] { if constexpr (DSUB != 4 && !WIDE) reload(); });
             int4_t sj = {0, 0, 0, 0};
             if constexpr (WIDE) sj = k_scores(other_table(kcst), kw_in, [&] { reload(); });
             // ---- softmax: register i = token (tj, 4 kgrp + i), head tq.  x = score - reference.
             const uint32_t keep_bits = ~mw >> mask_sh;                 // bit i set: token i is neither anchored nor past the range
             float x[4];
-            if constexpr (WIDE) {
+            if constexpr (GIVEN) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) x[i] = sg[i] + neg_m;
+            } else if constexpr (WIDE) {
                 wide_x(kcst, si, sj, neg_m, x);
             } else {
 #pragma unroll
@@ -1286,7 +1334,10 @@ __global__ __launch_bounds__(kDaThreads) void decode_attn_kernel(const DaParams 
                             acc[a][rho][h] = v;
                         }
                 }
-                if constexpr (WIDE) {
+                if constexpr (GIVEN) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) x[i] = sg[i] + neg_m;
+                } else if constexpr (WIDE) {
                     wide_x(kcst, si, sj, neg_m, x);
                 } else {
 #pragma unroll
@@ -1883,6 +1934,10 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     p.idx_k = a.idx_k; p.idx_v = a.idx_v; p.rows_k = a.rows_k; p.rows_v = a.rows_v;
     p.part = part; p.out = a.out; p.done = (unsigned long long*)(w + pl.off_done); p.info = (int32_t*)(w + pl.off_info); p.tag = next_launch_tag(); p.N = a.N; p.N_cap = a.N_cap; p.k_k = (int)a.k_k; p.k_v = (int)a.k_v;
     p.c1 = a.scale * kLog2e; p.Hq = g.Hq; p.Hkv = g.Hkv; p.G = g.G; p.S = pl.S; p.chunk = pl.chunk;
+    if (a.given_scores) {
+        if (a.k_k != 0 || want_ans) return hipErrorInvalidValue;      // the scores cover the K anchors already
+        p.codes_k = (const uint8_t*)a.given_scores;
+    }
     if (pl.S > 1024) return hipErrorInvalidValue;        // the in-kernel merge keeps one weight per slot in LDS
     const size_t shmem = Lds<DSUB>::total;
     // One-time set-up per instantiation (and per process): raise the dynamic LDS limit, and make sure the kernel has
@@ -1891,7 +1946,8 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
         for (const void* f : {(const void*)decode_attn_kernel<DSUB, 0>, (const void*)decode_attn_kernel<DSUB, 1>,
                               (const void*)decode_attn_kernel<DSUB, 2>, (const void*)decode_attn_kernel<DSUB, 3>,
                               (const void*)decode_attn_kernel<DSUB, 4>, (const void*)decode_attn_kernel<DSUB, 5>,
-                              (const void*)decode_attn_kernel<DSUB, 6>, (const void*)decode_attn_kernel<DSUB, 7>}) {
+                              (const void*)decode_attn_kernel<DSUB, 6>, (const void*)decode_attn_kernel<DSUB, 7>,
+                              (const void*)decode_attn_kernel<DSUB, 8>, (const void*)decode_attn_kernel<DSUB, 9>}) {
             hipFuncAttributes attr;
             hipError_t r = hipFuncGetAttributes(&attr, f);
             if (r != hipSuccess) return r;
@@ -1906,7 +1962,8 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     const unsigned grid = (unsigned)((int64_t)g.B * g.Hkv * pl.S);
     // anchor lists between 3073 and 16384 entries go through the kernels that hold them in the table areas
     const int64_t k_max = a.k_k > a.k_v ? a.k_k : a.k_v;
-    const int mode = (g_options.load(std::memory_order_relaxed) & 3) | ((k_max > 3 * kDaThreads && k_max <= 16384) ? 4 : 0);   // (3 rounds of 1024 fit the staging areas)
+    int mode = (g_options.load(std::memory_order_relaxed) & 3) | ((k_max > 3 * kDaThreads && k_max <= 16384) ? 4 : 0);   // (3 rounds of 1024 fit the staging areas)
+    if (a.given_scores) mode = 8 | (mode & 1);
     switch (mode) {
     case 0: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 0>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
     case 1: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 1>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
@@ -1915,6 +1972,8 @@ static hipError_t launch_decode_t(const Geom& g, const DecodeArgs& a, void* ws, 
     case 4: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 4>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
     case 5: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 5>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
     case 6: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 6>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
+    case 8: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 8>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
+    case 9: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 9>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
     default: hipLaunchKernelGGL((decode_attn_kernel<DSUB, 7>), dim3(grid), dim3(kDaThreads), shmem, st, p); break;
     }
     if (want_ans) {

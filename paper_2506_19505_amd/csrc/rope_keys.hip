@@ -101,6 +101,238 @@ __global__ __launch_bounds__(64 * kGroups) void rope_rows_kernel(const RkParams 
     o[cb] = (half_t)(a * s + b * c);
 }
 
+// ---- scores instead of rows (one-byte codes) -----------------------------------------------------------------------
+// q . RoPE_p(k) for the group's four heads, in log2 units (scale * log2 e folded into q): 16 bytes per token and KV head
+// instead of a 256-byte rotated row.  Layout: [B][Hkv][n_pad / 4][4 heads][4 tokens] fp32 with n_pad = N rounded up to 64,
+// the form in which the decode kernel's lanes (one head, four consecutive tokens each) read it with one 16-byte load.
+// A workgroup (16 waves) owns a token range of one (sequence, KV head) and keeps in LDS the K codebook code-major with
+// rows padded to 272 bytes (a lane = a token, and all lanes read the same 16-byte column of different rows: without the
+// padding that is one bank group) and cos / sin of delta * theta_i for delta = 0 .. 63, a token's offset inside its
+// 64-token tile.  With p = (tile base) + delta, q . R_p(k) = (R_{-base} q) . (R_delta k): per tile, lane i rotates the
+// four heads' pair i of q back by the base angle (worked out exactly: fp64 reduction) and leaves it in the wave's LDS
+// area; per token and pair that leaves one rotation by a tabulated angle and the four dot products.  fp32 arithmetic on
+// the fp16 inputs.
+constexpr int kRsThreads = 1024, kRsWaves = kRsThreads / 64;
+constexpr int kRsRow = 272;                                            // bytes of a padded codebook row in LDS
+constexpr int kRsTab = 0, kRsDelta = kRsTab + kC * kRsRow;             // [256][272]; then [64 pairs][64 lanes] float2
+constexpr int kRsQ = kRsDelta + 64 * 64 * 8;                           // [waves][64 pairs][x of 4 heads, y of 4 heads] fp32
+constexpr int kRsLds = kRsQ + kRsWaves * 64 * 32;
+
+struct RsParams {
+    const half_t* q;                   // [B][Hq][128]
+    const uint8_t* codes;              // [B][Hkv][N_cap][M]
+    const half_t* cb;                  // [Hkv][M][256][d]
+    const int32_t* idx;                // K anchor list and rows (pre-RoPE), for the second kernel
+    const half_t* rows;
+    float* scores;                     // [B][Hkv][n_pad / 4][4][4]
+    int64_t N, N_cap, n_pad, pos0, chunk;
+    int k, Hq, Hkv, G, S;
+    float c1;
+    double log2_base;
+};
+
+template <int DSUB, int STYLE>
+__global__ __launch_bounds__(kRsThreads) void rope_scores_kernel(const RsParams p)
+{
+    constexpr int M = kD / DSUB;
+    extern __shared__ uint4_t rs_smem[];
+    char* smem = (char*)rs_smem;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int bg = blockIdx.x / p.S, sp = blockIdx.x % p.S;
+    const int b = bg / p.Hkv, g = bg % p.Hkv;
+    const int64_t t0 = (int64_t)sp * p.chunk;
+    const int64_t t1 = (t0 + p.chunk < p.N) ? t0 + p.chunk : p.N;
+    if (t0 >= t1) return;
+    // ---- tables
+    {
+        const half_t* cbg = p.cb + (size_t)g * 32768;
+        for (int ci = tid; ci < 4096; ci += kRsThreads) {              // 16-byte chunk w16 (8 channels) of centroid row `code`
+            const int code = ci >> 4, w16 = ci & 15;
+            uint4_t v;
+            if constexpr (DSUB == 8) {
+                v = ((const uint4_t*)cbg)[w16 * 256 + code];
+            } else if constexpr (DSUB == 16) {
+                v = ((const uint4_t*)cbg)[((w16 >> 1) * 256 + code) * 2 + (w16 & 1)];
+            } else {
+                const uint2_t lo = ((const uint2_t*)cbg)[(2 * w16) * 256 + code], hi = ((const uint2_t*)cbg)[(2 * w16 + 1) * 256 + code];
+                v = uint4_t{lo[0], lo[1], hi[0], hi[1]};
+            }
+            *(uint4_t*)(smem + kRsTab + code * kRsRow + w16 * 16) = v;
+        }
+        for (int e = tid; e < 64 * 64; e += kRsThreads) {
+            const int pair = e >> 6, delta = e & 63;
+            float c, s;
+            angle_of(delta, exp2(-(2.0 * pair / kD) * p.log2_base), c, s);
+            ((float2*)(smem + kRsDelta))[e] = float2{c, s};
+        }
+    }
+    // lane i: pair i of the four heads' queries, scaled
+    const int my_ca = STYLE == 0 ? 2 * lane : lane, my_cb = STYLE == 0 ? 2 * lane + 1 : lane + kD / 2;
+    float qa[4], qb[4];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        qa[h] = qb[h] = 0.f;
+        if (h < p.G) {
+            const half_t* qh = p.q + ((int64_t)b * p.Hq + g * p.G + h) * kD;
+            qa[h] = (float)qh[my_ca] * p.c1;
+            qb[h] = (float)qh[my_cb] * p.c1;
+        }
+    }
+    __syncthreads();
+    const double theta = exp2(-(2.0 * lane / kD) * p.log2_base);       // lane i looks after pair i's base angle
+    const uint8_t* ck = p.codes + (int64_t)bg * p.N_cap * M;
+    float4_t* s_qr = (float4_t*)(smem + kRsQ + wave * (64 * 32));       // this wave's rotated queries: [pair][x, y]
+    const int64_t n_tiles = (t1 - t0 + 63) >> 6;
+    for (int64_t tile = wave; tile < n_tiles; tile += kRsWaves) {
+        const int64_t tok0 = t0 + tile * 64;
+        const int64_t tok = tok0 + lane;
+        const int64_t ltok = tok < p.N ? tok : p.N - 1;
+        uint32_t cw[M / 4];
+        if constexpr (M == 8) {
+            const uint2_t a = *(const uint2_t*)(ck + ltok * M);
+            cw[0] = a[0]; cw[1] = a[1];
+        } else {
+#pragma unroll
+            for (int i = 0; i < M / 16; ++i) {
+                const uint4_t a = *(const uint4_t*)(ck + ltok * M + 16 * i);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) cw[4 * i + e] = a[e];
+            }
+        }
+        {
+            float bc, bs;
+            angle_of(p.pos0 + tok0, theta, bc, bs);
+            float4_t qx, qy;                                              // R_{-base} (qa, qb)
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                qx[h] = qa[h] * bc + qb[h] * bs;
+                qy[h] = qb[h] * bc - qa[h] * bs;
+            }
+            __builtin_amdgcn_wave_barrier();                              // the previous tile's readers are done
+            s_qr[2 * lane] = qx;
+            s_qr[2 * lane + 1] = qy;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+        // (the angle table never changes, but read through an address the compiler cannot follow: it would otherwise
+        // keep all 128 values of a lane across the tiles, in scratch memory)
+        uint32_t delta_off = (uint32_t)kRsDelta + 8u * (uint32_t)lane;
+        asm volatile("" : "+v"(delta_off));
+        const char* s_delta = smem + delta_off;
+        auto code_of_sub = [&](int m) -> uint32_t { return (cw[m >> 2] >> (8 * (m & 3))) & 0xffu; };
+        // 8 channels (chunk w16 of the token's de-quantised row) as floats
+        auto chunk = [&](int w16, float (&v)[8]) {
+            uint4_t r;
+            if constexpr (DSUB == 4) {
+                const uint2_t lo = *(const uint2_t*)(smem + kRsTab + code_of_sub(2 * w16) * kRsRow + w16 * 16);
+                const uint2_t hi = *(const uint2_t*)(smem + kRsTab + code_of_sub(2 * w16 + 1) * kRsRow + w16 * 16 + 8);
+                r = uint4_t{lo[0], lo[1], hi[0], hi[1]};
+            } else {
+                r = *(const uint4_t*)(smem + kRsTab + code_of_sub(DSUB == 8 ? w16 : (w16 >> 1)) * kRsRow + w16 * 16);
+            }
+            const half8_t hv = __builtin_bit_cast(half8_t, r);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = (float)hv[e];
+        };
+        float4_t acc = {0.f, 0.f, 0.f, 0.f};
+        auto pair_term = [&](int pair, float ka, float kb) {
+            const float2 d = *(const float2*)(s_delta + pair * 512);
+            const float xr = ka * d.x - kb * d.y, yr = ka * d.y + kb * d.x;
+            const float4_t qx = s_qr[2 * pair], qy = s_qr[2 * pair + 1];
+#pragma unroll
+            for (int h = 0; h < 4; ++h) acc[h] = fmaf(qx[h], xr, fmaf(qy[h], yr, acc[h]));
+        };
+        if constexpr (STYLE == 0) {
+#pragma unroll
+            for (int w16 = 0; w16 < 16; ++w16) {
+                float v[8];
+                chunk(w16, v);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) pair_term(4 * w16 + j, v[2 * j], v[2 * j + 1]);
+            }
+        } else {
+#pragma unroll
+            for (int w16 = 0; w16 < 8; ++w16) {
+                float va[8], vb[8];
+                chunk(w16, va);
+                chunk(w16 + 8, vb);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pair_term(8 * w16 + e, va[e], vb[e]);
+            }
+        }
+        // lane = token, acc = its four heads  ->  lane 4 u + h = head h of tokens 4 u .. 4 u + 3 (a 4 x 4 transposition
+        // inside every quad of lanes); the tile's 64 float4 are then consecutive.  Tokens past N (the tail of the last
+        // tile) carry the last token's score: finite, and never used.
+        float4_t v = {0.f, 0.f, 0.f, 0.f};
+        const int r0 = lane & 3;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int k = r0 ^ r;                                     // lane ^ r is token k of the quad and wants this lane's head k
+            float send = acc[0];
+#pragma unroll
+            for (int h = 1; h < 4; ++h) send = (k == h) ? acc[h] : send;
+            const float got = r == 0 ? send : __shfl_xor(send, r, 64);
+#pragma unroll
+            for (int h = 0; h < 4; ++h) v[h] = (k == h) ? got : v[h];
+        }
+        ((float4_t*)p.scores)[(int64_t)bg * p.n_pad + tok] = v;
+    }
+}
+
+// the K anchor tokens: the same score from the FP16 row (pre-RoPE), a wave per kRowsPerWave entries, lane = pair; replaces
+// the score that the kernel above wrote from the codes
+constexpr int kRowsPerWave = 4;
+template <int STYLE>
+__global__ __launch_bounds__(256) void rope_row_scores_kernel(const RsParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const int bg = blockIdx.y, b = bg / p.Hkv, g = bg % p.Hkv;
+    const int ca = STYLE == 0 ? 2 * lane : lane, cb = STYLE == 0 ? 2 * lane + 1 : lane + kD / 2;
+    const double theta = exp2(-(2.0 * lane / kD) * p.log2_base);
+    float qa[4], qb[4];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        qa[h] = qb[h] = 0.f;
+        if (h < p.G) {
+            const half_t* qh = p.q + ((int64_t)b * p.Hq + g * p.G + h) * kD;
+            qa[h] = (float)qh[ca] * p.c1;
+            qb[h] = (float)qh[cb] * p.c1;
+        }
+    }
+    const int e0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * kRowsPerWave;
+    if (e0 >= p.k) return;
+    // all entries' loads are issued before the first is used (entries past the list repeat the last one and are not written)
+    int64_t tok[kRowsPerWave];
+    float ka[kRowsPerWave], kb[kRowsPerWave];
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i) {
+        const int e = e0 + i < p.k ? e0 + i : p.k - 1;
+        tok[i] = p.idx[(int64_t)bg * p.k + e];
+        const half_t* r = p.rows + ((int64_t)bg * p.k + e) * kD;
+        ka[i] = (float)r[ca];
+        kb[i] = (float)r[cb];
+    }
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i) {
+        float c, s;
+        angle_of(p.pos0 + tok[i], theta, c, s);
+        const float xr = ka[i] * c - kb[i] * s, yr = ka[i] * s + kb[i] * c;
+        // four sums over the wave in seven exchanges: the first two halve what a lane carries (the lanes of bit 5 = a
+        // take heads 2 a, 2 a + 1; of those, the lanes of bit 4 = c take head 2 a + c), the rest add up 16 lanes
+        float v[4];
+#pragma unroll
+        for (int h = 0; h < 4; ++h) v[h] = qa[h] * xr + qb[h] * yr;
+        const bool up5 = lane & 32, up4 = lane & 16;
+        const float k0 = (up5 ? v[2] : v[0]) + __shfl_xor(up5 ? v[0] : v[2], 32, 64);
+        const float k1 = (up5 ? v[3] : v[1]) + __shfl_xor(up5 ? v[1] : v[3], 32, 64);
+        float sum = (up4 ? k1 : k0) + __shfl_xor(up4 ? k0 : k1, 16, 64);
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+        if ((lane & 15) == 0 && e0 + i < p.k)                             // lane 16 h holds head h
+            p.scores[((int64_t)bg * p.n_pad + (tok[i] & ~3LL)) * 4 + 4 * (lane >> 4) + (tok[i] & 3)] = sum;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_rope_keys(const Geom& g, const uint8_t* codes_k, int64_t N, int64_t N_cap, const half_t* cb_k,
@@ -120,6 +352,49 @@ hipError_t launch_rope_keys(const Geom& g, const uint8_t* codes_k, int64_t N, in
     if (k_k > 0) {
         dim3 grid2((unsigned)((k_k + kGroups - 1) / kGroups), (unsigned)(g.B * g.Hkv));
         hipLaunchKernelGGL(rope_rows_kernel, grid2, dim3(64 * kGroups), 0, st, p);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+hipError_t launch_rope_scores(const Geom& g, const half_t* q, float scale, const uint8_t* codes_k, int64_t N, int64_t N_cap,
+                              const half_t* cb_k, const int32_t* idx_k, const half_t* rows_k, int64_t k_k, double rope_base,
+                              int rope_style, int64_t pos0, float* scores_out, hipStream_t st)
+{
+    if (N == 0 || g.B == 0) return hipSuccess;
+    if (g.C != kC) return hipErrorInvalidValue;
+    RsParams p;
+    p.q = q; p.codes = codes_k; p.cb = cb_k; p.idx = idx_k; p.rows = rows_k; p.scores = scores_out;
+    p.n_pad = (N + 63) / 64 * 64;
+    p.N = N; p.N_cap = N_cap; p.pos0 = pos0; p.k = (int)k_k; p.Hq = g.Hq; p.Hkv = g.Hkv; p.G = g.G;
+    p.c1 = scale * kLog2e; p.log2_base = log2(rope_base);
+    const int64_t bg = (int64_t)g.B * g.Hkv;
+    int64_t S = (256 + bg - 1) / bg;                                  // about one workgroup per CU
+    const int64_t max_S = (N + 1023) / 1024;
+    if (S > max_S) S = max_S;
+    if (S < 1) S = 1;
+    int64_t chunk = ((N + S - 1) / S + 63) / 64 * 64;
+    p.chunk = chunk;
+    p.S = (int)((N + chunk - 1) / chunk);
+    const dim3 grid((unsigned)(bg * p.S));
+    hipError_t e = hipSuccess;
+#define ANTKV_RS(DS, STY)                                                                                                  \
+    do {                                                                                                                   \
+        static const hipError_t once = hipFuncSetAttribute((const void*)rope_scores_kernel<DS, STY>,                       \
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, kRsLds);            \
+        if (once != hipSuccess) return once;                                                                               \
+        hipLaunchKernelGGL((rope_scores_kernel<DS, STY>), grid, dim3(kRsThreads), kRsLds, st, p);                          \
+    } while (0)
+    if (g.d == 4) { if (rope_style == 0) ANTKV_RS(4, 0); else ANTKV_RS(4, 1); }
+    else if (g.d == 8) { if (rope_style == 0) ANTKV_RS(8, 0); else ANTKV_RS(8, 1); }
+    else { if (rope_style == 0) ANTKV_RS(16, 0); else ANTKV_RS(16, 1); }
+#undef ANTKV_RS
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (k_k > 0) {
+        const dim3 grid2((unsigned)((k_k + 4 * kRowsPerWave - 1) / (4 * kRowsPerWave)), (unsigned)bg);
+        if (rope_style == 0) hipLaunchKernelGGL(rope_row_scores_kernel<0>, grid2, dim3(256), 0, st, p);
+        else hipLaunchKernelGGL(rope_row_scores_kernel<1>, grid2, dim3(256), 0, st, p);
         e = hipGetLastError();
     }
     return e;

@@ -53,6 +53,29 @@ def test_prerope_edge_cases(oracle):
     _case(oracle, 321, 1, 4, 1, 611, 8, 256, 5, 0, 10000.0, 0, 17, N_cap=900)     # N below the capacity, K anchors only
     _case(oracle, 322, 2, 4, 1, 65, 8, 256, 1, 1, 10000.0, 1, 0)                  # one tile and a token
     _case(oracle, 323, 1, 4, 1, 300, 8, 256, 300, 300, 10000.0, 1, 9)             # every token an FP16 anchor in both lists
+    _case(oracle, 324, 2, 4, 2, 1500, 16, 256, 20, 10, 10000.0, 0, 3)             # two query heads per KV head
+    _case(oracle, 325, 1, 3, 3, 1027, 4, 256, 11, 40, 10000.0, 1, 5)              # one query head per KV head, odd N
+
+
+def test_prerope_fixed_order_is_reproducible(oracle):
+    """With ANTKV_DECODE_FIXED_ORDER the pre-RoPE path too gives the same bits on every launch."""
+    B, Hq, Hkv, N, d, k = 2, 8, 2, 40000, 8, 100
+    rng = np.random.default_rng(77)
+    geom = antkv.Geometry(B, Hq, Hkv, d)
+    q = dev(make_decode_query(77, B, Hq, 128))
+    ck = dev(rng.integers(0, 256, (B, Hkv, N, 128 // d)).astype(np.uint8))
+    cv = dev(rng.integers(0, 256, (B, Hkv, N, 128 // d)).astype(np.uint8))
+    cbk, cbv = dev(normal_fp16(77, "cb12_k", (Hkv, 128 // d, 256, d))), dev(normal_fp16(77, "cb12_v", (Hkv, 128 // d, 256, d)))
+    ik, iv = dev(random_anchor_sets(77, "k", B, Hkv, N, k)), dev(random_anchor_sets(77, "v", B, Hkv, N, k))
+    rk, rv = dev(normal_fp16(77, "rows_k", (B, Hkv, k, 128))), dev(normal_fp16(77, "rows_v", (B, Hkv, k, 128)))
+    prev = antkv.set_decode_options(antkv.DECODE_FIXED_ORDER)
+    try:
+        outs = [antkv.decode_attn_prerope(geom, q, 0.0884, ck, cv, cbk, cbv, ik, rk, iv, rv, rope_base=10000.0, rope_style=1,
+                                          pos0=11).clone() for _ in range(3)]
+        torch.cuda.synchronize()
+    finally:
+        antkv.set_decode_options(prev)
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
 
 
 def test_prerope_long_context(oracle):
