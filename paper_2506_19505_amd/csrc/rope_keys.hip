@@ -105,18 +105,21 @@ __global__ __launch_bounds__(64 * kGroups) void rope_rows_kernel(const RkParams 
 // q . RoPE_p(k) for the group's four heads, in log2 units (scale * log2 e folded into q): 16 bytes per token and KV head
 // instead of a 256-byte rotated row.  Layout: [B][Hkv][n_pad / 4][4 heads][4 tokens] fp32 with n_pad = N rounded up to 64,
 // the form in which the decode kernel's lanes (one head, four consecutive tokens each) read it with one 16-byte load.
-// A workgroup (16 waves) owns a token range of one (sequence, KV head) and keeps in LDS the K codebook code-major with
+// A workgroup (8 waves) owns a token range of one (sequence, KV head) and keeps in LDS the K codebook code-major with
 // rows padded to 272 bytes (a lane = a token, and all lanes read the same 16-byte column of different rows: without the
-// padding that is one bank group) and cos / sin of delta * theta_i for delta = 0 .. 63, a token's offset inside its
-// 64-token tile.  With p = (tile base) + delta, q . R_p(k) = (R_{-base} q) . (R_delta k): per tile, lane i rotates the
-// four heads' pair i of q back by the base angle (worked out exactly: fp64 reduction) and leaves it in the wave's LDS
-// area; per token and pair that leaves one rotation by a tabulated angle and the four dot products.  fp32 arithmetic on
-// the fp16 inputs.
-constexpr int kRsThreads = 1024, kRsWaves = kRsThreads / 64;
+// padding that is one bank group) and cos / sin of delta * theta_i for delta = 0 .. 127, a token's offset inside its
+// 128-token tile (lane l has the tokens l and l + 64 of the tile).  With p = (tile base) + delta,
+// q . R_p(k) = (R_{-base} q) . (R_delta k): per tile, lane i rotates the four heads' pair i of q back by the base angle
+// (worked out exactly: fp64 reduction) and leaves it in the wave's LDS area; per token and pair that leaves one rotation
+// by a tabulated angle and the four dot products.  The rotated query is read once per pair for both tokens of a lane:
+// those broadcast reads are what the kernel spends most LDS time on.  fp32 arithmetic on the fp16 inputs.
+constexpr int kRsThreads = 512, kRsWaves = kRsThreads / 64;
+constexpr int kRsTile = 128;                                           // tokens per wave and step
 constexpr int kRsRow = 272;                                            // bytes of a padded codebook row in LDS
-constexpr int kRsTab = 0, kRsDelta = kRsTab + kC * kRsRow;             // [256][272]; then [64 pairs][64 lanes] float2
-constexpr int kRsQ = kRsDelta + 64 * 64 * 8;                           // [waves][64 pairs][x of 4 heads, y of 4 heads] fp32
+constexpr int kRsTab = 0, kRsDelta = kRsTab + kC * kRsRow;             // [256][272]; then [64 pairs][64 lanes] x (cos, sin of l, of l + 64)
+constexpr int kRsQ = kRsDelta + 64 * 64 * 16;                          // [waves][64 pairs][x of 4 heads, y of 4 heads] fp32
 constexpr int kRsLds = kRsQ + kRsWaves * 64 * 32;
+static_assert(kRsLds <= 163840, "LDS budget of one CU");
 
 struct RsParams {
     const half_t* q;                   // [B][Hq][128]
@@ -140,7 +143,7 @@ __global__ __launch_bounds__(kRsThreads) void rope_scores_kernel(const RsParams 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int bg = blockIdx.x / p.S, sp = blockIdx.x % p.S;
     const int b = bg / p.Hkv, g = bg % p.Hkv;
-    const int64_t t0 = (int64_t)sp * p.chunk;
+    const int64_t t0 = (int64_t)sp * p.chunk;                          // a multiple of 128
     const int64_t t1 = (t0 + p.chunk < p.N) ? t0 + p.chunk : p.N;
     if (t0 >= t1) return;
     // ---- tables
@@ -160,10 +163,12 @@ __global__ __launch_bounds__(kRsThreads) void rope_scores_kernel(const RsParams 
             *(uint4_t*)(smem + kRsTab + code * kRsRow + w16 * 16) = v;
         }
         for (int e = tid; e < 64 * 64; e += kRsThreads) {
-            const int pair = e >> 6, delta = e & 63;
-            float c, s;
-            angle_of(delta, exp2(-(2.0 * pair / kD) * p.log2_base), c, s);
-            ((float2*)(smem + kRsDelta))[e] = float2{c, s};
+            const int pair = e >> 6, l = e & 63;
+            const double th = exp2(-(2.0 * pair / kD) * p.log2_base);
+            float c0, s0, c1, s1;
+            angle_of(l, th, c0, s0);
+            angle_of(l + 64, th, c1, s1);
+            ((float4_t*)(smem + kRsDelta))[e] = float4_t{c0, s0, c1, s1};
         }
     }
     // lane i: pair i of the four heads' queries, scaled
@@ -182,21 +187,25 @@ __global__ __launch_bounds__(kRsThreads) void rope_scores_kernel(const RsParams 
     const double theta = exp2(-(2.0 * lane / kD) * p.log2_base);       // lane i looks after pair i's base angle
     const uint8_t* ck = p.codes + (int64_t)bg * p.N_cap * M;
     float4_t* s_qr = (float4_t*)(smem + kRsQ + wave * (64 * 32));       // this wave's rotated queries: [pair][x, y]
-    const int64_t n_tiles = (t1 - t0 + 63) >> 6;
+    const int64_t n_tiles = (t1 - t0 + kRsTile - 1) / kRsTile;
     for (int64_t tile = wave; tile < n_tiles; tile += kRsWaves) {
-        const int64_t tok0 = t0 + tile * 64;
-        const int64_t tok = tok0 + lane;
-        const int64_t ltok = tok < p.N ? tok : p.N - 1;
-        uint32_t cw[M / 4];
-        if constexpr (M == 8) {
-            const uint2_t a = *(const uint2_t*)(ck + ltok * M);
-            cw[0] = a[0]; cw[1] = a[1];
-        } else {
+        const int64_t tok0 = t0 + tile * kRsTile;
+        const bool second = tok0 + 64 < t1;                            // the tile's second half exists (uniform)
+        uint32_t cw[2][M / 4];
 #pragma unroll
-            for (int i = 0; i < M / 16; ++i) {
-                const uint4_t a = *(const uint4_t*)(ck + ltok * M + 16 * i);
+        for (int u = 0; u < 2; ++u) {
+            const int64_t tok = tok0 + 64 * u + lane;
+            const int64_t ltok = tok < p.N ? tok : p.N - 1;
+            if constexpr (M == 8) {
+                const uint2_t a = *(const uint2_t*)(ck + ltok * M);
+                cw[u][0] = a[0]; cw[u][1] = a[1];
+            } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) cw[4 * i + e] = a[e];
+                for (int i = 0; i < M / 16; ++i) {
+                    const uint4_t a = *(const uint4_t*)(ck + ltok * M + 16 * i);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) cw[u][4 * i + e] = a[e];
+                }
             }
         }
         {
@@ -215,67 +224,78 @@ __global__ __launch_bounds__(kRsThreads) void rope_scores_kernel(const RsParams 
             __builtin_amdgcn_wave_barrier();
         }
         // (the angle table never changes, but read through an address the compiler cannot follow: it would otherwise
-        // keep all 128 values of a lane across the tiles, in scratch memory)
-        uint32_t delta_off = (uint32_t)kRsDelta + 8u * (uint32_t)lane;
+        // keep all 256 values of a lane across the tiles, in scratch memory)
+        uint32_t delta_off = (uint32_t)kRsDelta + 16u * (uint32_t)lane;
         asm volatile("" : "+v"(delta_off));
         const char* s_delta = smem + delta_off;
-        auto code_of_sub = [&](int m) -> uint32_t { return (cw[m >> 2] >> (8 * (m & 3))) & 0xffu; };
-        // 8 channels (chunk w16 of the token's de-quantised row) as floats
-        auto chunk = [&](int w16, float (&v)[8]) {
+        auto code_of_sub = [&](int u, int m) -> uint32_t { return (cw[u][m >> 2] >> (8 * (m & 3))) & 0xffu; };
+        // 8 channels (chunk w16 of a token's de-quantised row) as floats
+        auto chunk = [&](int u, int w16, float (&v)[8]) {
             uint4_t r;
             if constexpr (DSUB == 4) {
-                const uint2_t lo = *(const uint2_t*)(smem + kRsTab + code_of_sub(2 * w16) * kRsRow + w16 * 16);
-                const uint2_t hi = *(const uint2_t*)(smem + kRsTab + code_of_sub(2 * w16 + 1) * kRsRow + w16 * 16 + 8);
+                const uint2_t lo = *(const uint2_t*)(smem + kRsTab + code_of_sub(u, 2 * w16) * kRsRow + w16 * 16);
+                const uint2_t hi = *(const uint2_t*)(smem + kRsTab + code_of_sub(u, 2 * w16 + 1) * kRsRow + w16 * 16 + 8);
                 r = uint4_t{lo[0], lo[1], hi[0], hi[1]};
             } else {
-                r = *(const uint4_t*)(smem + kRsTab + code_of_sub(DSUB == 8 ? w16 : (w16 >> 1)) * kRsRow + w16 * 16);
+                r = *(const uint4_t*)(smem + kRsTab + code_of_sub(u, DSUB == 8 ? w16 : (w16 >> 1)) * kRsRow + w16 * 16);
             }
             const half8_t hv = __builtin_bit_cast(half8_t, r);
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = (float)hv[e];
         };
-        float4_t acc = {0.f, 0.f, 0.f, 0.f};
-        auto pair_term = [&](int pair, float ka, float kb) {
-            const float2 d = *(const float2*)(s_delta + pair * 512);
-            const float xr = ka * d.x - kb * d.y, yr = ka * d.y + kb * d.x;
+        float4_t acc[2] = {float4_t{0.f, 0.f, 0.f, 0.f}, float4_t{0.f, 0.f, 0.f, 0.f}};
+        // channel pair `pair` of both tokens: (ka, kb) of token l in k0, of token l + 64 in k1
+        auto pair_term = [&](int pair, float ka0, float kb0, float ka1, float kb1) {
+            const float4_t d = *(const float4_t*)(s_delta + pair * 1024);
             const float4_t qx = s_qr[2 * pair], qy = s_qr[2 * pair + 1];
+            const float xr0 = ka0 * d[0] - kb0 * d[1], yr0 = ka0 * d[1] + kb0 * d[0];
+            const float xr1 = ka1 * d[2] - kb1 * d[3], yr1 = ka1 * d[3] + kb1 * d[2];
 #pragma unroll
-            for (int h = 0; h < 4; ++h) acc[h] = fmaf(qx[h], xr, fmaf(qy[h], yr, acc[h]));
+            for (int h = 0; h < 4; ++h) {
+                acc[0][h] = fmaf(qx[h], xr0, fmaf(qy[h], yr0, acc[0][h]));
+                acc[1][h] = fmaf(qx[h], xr1, fmaf(qy[h], yr1, acc[1][h]));
+            }
         };
         if constexpr (STYLE == 0) {
 #pragma unroll
             for (int w16 = 0; w16 < 16; ++w16) {
-                float v[8];
-                chunk(w16, v);
+                float v0[8], v1[8];
+                chunk(0, w16, v0);
+                chunk(1, w16, v1);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) pair_term(4 * w16 + j, v[2 * j], v[2 * j + 1]);
+                for (int j = 0; j < 4; ++j) pair_term(4 * w16 + j, v0[2 * j], v0[2 * j + 1], v1[2 * j], v1[2 * j + 1]);
             }
         } else {
 #pragma unroll
             for (int w16 = 0; w16 < 8; ++w16) {
-                float va[8], vb[8];
-                chunk(w16, va);
-                chunk(w16 + 8, vb);
+                float va0[8], vb0[8], va1[8], vb1[8];
+                chunk(0, w16, va0);
+                chunk(0, w16 + 8, vb0);
+                chunk(1, w16, va1);
+                chunk(1, w16 + 8, vb1);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) pair_term(8 * w16 + e, va[e], vb[e]);
+                for (int e = 0; e < 8; ++e) pair_term(8 * w16 + e, va0[e], vb0[e], va1[e], vb1[e]);
             }
         }
         // lane = token, acc = its four heads  ->  lane 4 u + h = head h of tokens 4 u .. 4 u + 3 (a 4 x 4 transposition
-        // inside every quad of lanes); the tile's 64 float4 are then consecutive.  Tokens past N (the tail of the last
-        // tile) carry the last token's score: finite, and never used.
-        float4_t v = {0.f, 0.f, 0.f, 0.f};
+        // inside every quad of lanes); a half tile's 64 float4 are then consecutive.  Tokens past N (the tail of the last
+        // 64 tokens) carry the last token's score: finite, and never used.
         const int r0 = lane & 3;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int k = r0 ^ r;                                     // lane ^ r is token k of the quad and wants this lane's head k
-            float send = acc[0];
+        for (int u = 0; u < 2; ++u) {
+            float4_t v = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int h = 1; h < 4; ++h) send = (k == h) ? acc[h] : send;
-            const float got = r == 0 ? send : __shfl_xor(send, r, 64);
+            for (int r = 0; r < 4; ++r) {
+                const int k = r0 ^ r;                                 // lane ^ r is token k of the quad and wants this lane's head k
+                float send = acc[u][0];
 #pragma unroll
-            for (int h = 0; h < 4; ++h) v[h] = (k == h) ? got : v[h];
+                for (int h = 1; h < 4; ++h) send = (k == h) ? acc[u][h] : send;
+                const float got = r == 0 ? send : __shfl_xor(send, r, 64);
+#pragma unroll
+                for (int h = 0; h < 4; ++h) v[h] = (k == h) ? got : v[h];
+            }
+            if (u == 0 || second) ((float4_t*)p.scores)[(int64_t)bg * p.n_pad + tok0 + 64 * u + lane] = v;
         }
-        ((float4_t*)p.scores)[(int64_t)bg * p.n_pad + tok] = v;
     }
 }
 
@@ -373,7 +393,7 @@ hipError_t launch_rope_scores(const Geom& g, const half_t* q, float scale, const
     const int64_t max_S = (N + 1023) / 1024;
     if (S > max_S) S = max_S;
     if (S < 1) S = 1;
-    int64_t chunk = ((N + S - 1) / S + 63) / 64 * 64;
+    int64_t chunk = ((N + S - 1) / S + kRsTile - 1) / kRsTile * kRsTile;
     p.chunk = chunk;
     p.S = (int)((N + chunk - 1) / chunk);
     const dim3 grid((unsigned)(bg * p.S));
