@@ -105,14 +105,15 @@ __global__ __launch_bounds__(64 * kGroups) void rope_rows_kernel(const RkParams 
 // q . RoPE_p(k) for the group's four heads, in log2 units (scale * log2 e folded into q): 16 bytes per token and KV head
 // instead of a 256-byte rotated row.  Layout: [B][Hkv][n_pad / 4][4 heads][4 tokens] fp32 with n_pad = N rounded up to 64,
 // the form in which the decode kernel's lanes (one head, four consecutive tokens each) read it with one 16-byte load.
-// A workgroup (12 waves: as many as the LDS leaves room for) owns a token range of one (sequence, KV head) and keeps in LDS the K codebook code-major with
-// rows padded to 272 bytes (a lane = a token, and all lanes read the same 16-byte column of different rows: without the
-// padding that is one bank group) and cos / sin of delta * theta_i for delta = 0 .. 127, a token's offset inside its
-// 128-token tile (lane l has the tokens l and l + 64 of the tile).  With p = (tile base) + delta,
-// q . R_p(k) = (R_{-base} q) . (R_delta k): per tile, lane i rotates the four heads' pair i of q back by the base angle
-// (worked out exactly: fp64 reduction) and leaves it in the wave's LDS area; per token and pair that leaves one rotation
-// by a tabulated angle and the four dot products.  The rotated query is read once per pair for both tokens of a lane:
-// those broadcast reads are what the kernel spends most LDS time on.  fp32 arithmetic on the fp16 inputs.
+// A workgroup (12 waves: as many as the LDS leaves room for) owns a token range of one (sequence, KV head) and keeps
+// in LDS the K codebook code-major with rows padded to 272 bytes (a lane = a token, and all lanes read the same 16-byte
+// column of different rows: without the padding that is one bank group) and cos / sin of delta * theta_i for
+// delta = 0 .. 127, a token's offset inside its 128-token tile (lane l has the tokens l and l + 64 of the tile).
+// With p = (tile base) + delta, q . R_p(k) = (R_{-base} q) . (R_delta k): per tile, lane i rotates the four heads'
+// pair i of q back by the base angle (worked out exactly: fp64 reduction) and leaves it in the wave's LDS area; per
+// token and pair that leaves one rotation by a tabulated angle and the four dot products.  The rotated query is read
+// once per pair for both tokens of a lane: those broadcast reads are what the kernel spends most LDS time on.  fp32
+// arithmetic on the fp16 inputs.
 constexpr int kRsThreads = 768, kRsWaves = kRsThreads / 64;
 constexpr int kRsTile = 128;                                           // tokens per wave and step
 constexpr int kRsRow = 272;                                            // bytes of a padded codebook row in LDS

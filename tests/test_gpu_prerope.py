@@ -55,6 +55,7 @@ def test_prerope_edge_cases(oracle):
     _case(oracle, 323, 1, 4, 1, 300, 8, 256, 300, 300, 10000.0, 1, 9)             # every token an FP16 anchor in both lists
     _case(oracle, 324, 2, 4, 2, 1500, 16, 256, 20, 10, 10000.0, 0, 3)             # two query heads per KV head
     _case(oracle, 325, 1, 3, 3, 1027, 4, 256, 11, 40, 10000.0, 1, 5)              # one query head per KV head, odd N
+    _case(oracle, 326, 1, 4, 1, 40000, 8, 256, 3500, 3300, 10000.0, 1, 2)         # lists too long for the staging areas
 
 
 def test_prerope_fixed_order_is_reproducible(oracle):
