@@ -6,7 +6,7 @@ import torch
 
 import paper_2506_19505_amd as antkv
 from gpu_util import ATTN_TOL, dev, pack12, rel_l2_rows
-from workloads import make_codebooks, make_decode_query, make_qkv, normal_fp16, random_anchor_sets
+from workloads import make_codebooks, make_decode_query, make_qkv, normal_fp16, random_anchor_sets, random_codes
 
 pytestmark = pytest.mark.gpu
 
@@ -82,3 +82,30 @@ def test_prerope_fixed_order_is_reproducible(oracle):
 def test_prerope_long_context(oracle):
     """131072 positions (angles up to 1.3e5 rad on the fastest pair): the fp64 angle reduction and the fp32 stepping."""
     _case(oracle, 330, 1, 4, 1, 131072, 8, 256, 1311, 1311, 500000.0, 1, 0)
+
+
+def test_prerope_headline_shape_sampled(oracle):
+    """The shape the bench times for this path (4 sequences, 8 KV heads, 131072 tokens, 1311 anchors per list, one launch
+    over all of them): two (sequence, KV head) pairs are checked against the oracle, which gets their slices alone."""
+    B, Hq, Hkv, N, d, k = 4, 32, 8, 131072, 8, 1311
+    M, G, seed, base, style, pos0 = 128 // d, 4, 340, 500000.0, 1, 0
+    scale = 1 / np.sqrt(128)
+    q = oracle.rope(make_decode_query(seed, B, Hq, 128).astype(np.float64), np.full((B, Hq), pos0 + N), base, style).astype(np.float16)
+    ck, cv = random_codes(seed, "k", B, Hkv, N, M), random_codes(seed, "v", B, Hkv, N, M)
+    _, kk, vv = make_qkv(seed, 1, Hq, Hkv, 6000, 1, 128)
+    cbk, cbv = make_codebooks(seed, kk, d, 256, "k", max_sample=6000), make_codebooks(seed, vv, d, 256, "v", max_sample=6000)
+    ik, iv = random_anchor_sets(seed, "k", B, Hkv, N, k), random_anchor_sets(seed, "v", B, Hkv, N, k)
+    rk, rv = normal_fp16(seed, "rows_k", (B, Hkv, k, 128)), normal_fp16(seed, "rows_v", (B, Hkv, k, 128))
+    geom = antkv.Geometry(B, Hq, Hkv, d)
+    out = antkv.decode_attn_prerope(geom, dev(q), scale, dev(ck), dev(cv), dev(cbk), dev(cbv), dev(ik), dev(rk), dev(iv), dev(rv),
+                                    rope_base=base, rope_style=style, pos0=pos0)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    for b, g in ((0, 0), (3, 7)):
+        hs = slice(g * G, (g + 1) * G)
+        want = oracle.decode_attn_prerope(q[b:b + 1, hs], ck[b:b + 1, g:g + 1].astype(np.int32), cv[b:b + 1, g:g + 1].astype(np.int32),
+                                          cbk[g:g + 1], cbv[g:g + 1], ik[b:b + 1, g:g + 1], rk[b:b + 1, g:g + 1],
+                                          iv[b:b + 1, g:g + 1], rv[b:b + 1, g:g + 1], scale, base, style, pos0)
+        err = rel_l2_rows(got[b:b + 1, hs], want)
+        print(f"pre-RoPE headline shape, sequence {b} KV head {g}: rel-L2 max {err.max():.2e}")
+        assert err.max() <= ATTN_TOL, f"relative L2 {err.max():.3e}"
