@@ -35,9 +35,9 @@ __device__ __forceinline__ void pair_channels(int style, int i, int& ca, int& cb
 // cos, sin of pos * theta with the product reduced to (-pi, pi] in fp64
 __device__ __forceinline__ void angle_of(int64_t pos, double theta, float& c, float& s)
 {
-    const double two_pi = 6.283185307179586476925286766559;
+    const double two_pi = 6.283185307179586476925286766559, inv_two_pi = 0.15915494309189533576888376337251;
     const double a = (double)pos * theta;
-    const float r = (float)(a - two_pi * rint(a / two_pi));
+    const float r = (float)fma(-two_pi, rint(a * inv_two_pi), a);   // (a turn more or less at a tie of the rounding is the same angle)
     __sincosf(r, &s, &c);
     // the fast pair above is good to about 1e-6 on the reduced range; one Newton-like renormalisation keeps |(c, s)| = 1
     const float n = rsqrtf(c * c + s * s);
@@ -302,7 +302,7 @@ __global__ __launch_bounds__(kRsThreads) void rope_scores_kernel(const RsParams 
 
 // the K anchor tokens: the same score from the FP16 row (pre-RoPE), a wave per kRowsPerWave entries, lane = pair; replaces
 // the score that the kernel above wrote from the codes
-constexpr int kRowsPerWave = 4;
+constexpr int kRowsPerWave = 8;
 template <int STYLE>
 __global__ __launch_bounds__(256) void rope_row_scores_kernel(const RsParams p)
 {
