@@ -378,7 +378,13 @@ def main() -> int:
                                               workspace=w_ws2)
             settle(fw2)
             ms_w2 = timed(50, fw2)
-            del w_ck, w_cv, w_ws2
+            del w_ws2
+            w_ws3 = antkv.decode_attn_prerope_workspace(wg, r.N, r.k, devc)
+            fw3 = lambda i: antkv.decode_attn_prerope(wg, w_q, r.scale, w_ck, w_cv, w_cbk, w_cbv, w_ik, w_rk, w_iv, w_rv,
+                                                      rope_base=500000.0, rope_style=1, pos0=0, workspace=w_ws3)
+            settle(fw3, 0.1)
+            ms_w3 = timed(30, fw3)
+            del w_ck, w_cv, w_ws3
             w_codes = torch.empty((p.B, p.Hkv, p.N, wb), dtype=torch.uint8, device=devc)
             pg12 = antkv.Geometry(p.B, p.Hq, p.Hkv, wd, n_centroids=4096)
             fe = lambda i: antkv.encode(pg12, pkd12, w_cbk, codes=w_codes)
@@ -392,6 +398,7 @@ def main() -> int:
             result["extra"].update({
                 f"{tagw}_decode_ms": ms_w,
                 f"{tagw}_decode_plus_reselection_ms": ms_w2,
+                f"{tagw}_prerope_decode_ms": ms_w3,
                 f"{tagw}_decode_tokens_per_s": r.B * r.N / (ms_w * 1e-3),
                 f"{tagw}_decode_L2_gather_GBs": r.B * r.Hkv * r.N * 256 / (ms_w * 1e-3) / 1e9,
                 f"{tagw}_encode_ms": ms_e12,
@@ -401,7 +408,7 @@ def main() -> int:
                                     f"(B1, N={r.N}, {r.k} anchors per head, random codebooks and codes); encode of cfg3's K rows "
                                     f"({p.B * p.Hkv * p.N} rows)",
             })
-            log(f"{tagw}: decode {ms_w * 1e3:.0f} us, with re-selection {ms_w2 * 1e3:.0f} us, encode of {p.B * p.Hkv * p.N} rows "
+            log(f"{tagw}: decode {ms_w * 1e3:.0f} us, with re-selection {ms_w2 * 1e3:.0f} us, on keys stored before RoPE {ms_w3 * 1e3:.0f} us, encode of {p.B * p.Hkv * p.N} rows "
                 f"{ms_e12:.2f} ms, k-means iteration on them {ms_km12:.2f} ms")
             del w_codes, w_cbk, w_cbv, w_ws
             torch.cuda.empty_cache()

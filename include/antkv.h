@@ -190,13 +190,10 @@ int antkv_set_decode_options(int options);
  * is used.  RoPE_p turns channel pair i = 0 .. D/2-1 by the angle p * rope_base^(-2 i / D); rope_style 0 pairs the
  * channels (2 i, 2 i + 1), rope_style 1 pairs (i, i + D/2).  q is used as given (the caller has rotated it to its own
  * position); values are untouched.  No Anchor Score outputs.
- * One-byte codes (256 centroids): a first pass works out q_h . K_eff[j] for every token and head in fp32 (de-quantise,
- * rotate, dot product; the rotated keys are never written out) and leaves the scores in the workspace, 16 bytes per
- * token and KV head; the decode kernel then takes its scores from there instead of from its lookup table, which has no
- * meaning for keys that turn with their position.  ANTKV_DECODE_FIXED_ORDER applies, ANTKV_DECODE_WIDE_TABLE does not
- * (there is no table).
- * 12-bit codes: the call first writes the rotated keys as FP16 rows into the workspace (256 bytes per token and KV head,
- * rounded once to fp16 after the rotation) and then runs the decode kernels with every token as a K anchor.
+ * A first pass works out q_h . K_eff[j] for every token and head in fp32 (de-quantise, rotate, dot product; the rotated
+ * keys are never written out) and leaves the scores in the workspace, 16 bytes per token and KV head; the decode kernels
+ * then take their scores from there instead of from their lookup table, which has no meaning for keys that turn with
+ * their position.  ANTKV_DECODE_FIXED_ORDER applies, ANTKV_DECODE_WIDE_TABLE does not (there is no table).
  * The workspace size comes from antkv_decode_attn_prerope_workspace(geom, N, k_v).
  * Errors: EINVAL (also rope_base <= 1, rope_style not 0 / 1, pos0 < 0), EUNSUPPORTED, EWORKSPACE, ELAUNCH.
  */

@@ -91,6 +91,7 @@ int decode_attn_impl(const antkv_geom* geom, const void* q, float scale, const u
         a.cb_k = (const half_t*)cb_k; a.cb_v = (const half_t*)cb_v; a.idx_k = idx_k; a.rows_k = (const half_t*)rows_k;
         a.k_k = k_k; a.idx_v = idx_v; a.rows_v = (const half_t*)rows_v; a.k_v = k_v; a.out = (half_t*)out;
         a.ans_k = ans_k; a.ans_v = ans_v;
+        a.given_scores = given_scores;
         // with both index sets wanted, the score pass counts its scores into the selection's first histogram
         const bool fused = N > 0 && k_resel > 0 && resel_idx_k && resel_idx_v;
         a.topk_hist = fused ? launch_topk2_begin((int64_t)g.B * g.Hkv, N, (char*)workspace + off_topk, st) : nullptr;
@@ -366,15 +367,19 @@ int antkv_decode_attn(const antkv_geom* geom, const void* q, float scale, const 
 
 int antkv_set_decode_options(int options) { return set_decode_options(options); }
 
+// bytes of the K side's scores that the pre-RoPE path keeps in its workspace: 16 per token and KV head (one-byte codes:
+// tokens rounded up to 64, the decode kernel reads whole tiles)
+static size_t prerope_score_bytes(const Geom& g, int64_t N)
+{
+    const int64_t n = g.C == kC ? (N + 63) / 64 * 64 : N;
+    return align_up((size_t)g.B * g.Hkv * (size_t)n * 16);
+}
+
 size_t antkv_decode_attn_prerope_workspace(const antkv_geom* geom, int64_t N, int64_t k_v)
 {
     Geom g;
     if (check_geom(geom, g) || N < 0 || k_v < 0) return 0;
-    if (g.C == kC)   // one-byte codes: the K side's scores (16 bytes per token and KV head), then the plain call's workspace
-        return align_up((size_t)g.B * g.Hkv * (size_t)((N + 63) / 64 * 64) * 16) + align_up(antkv_decode_attn_workspace(geom, N, 0, k_v, 0));
-    const size_t rows = align_up((size_t)g.B * g.Hkv * (size_t)N * kD * sizeof(half_t));
-    const size_t iota = align_up((size_t)g.B * g.Hkv * (size_t)N * sizeof(int32_t));
-    return rows + iota + align_up(antkv_decode_attn_workspace(geom, N, N, k_v, 0));
+    return prerope_score_bytes(g, N) + align_up(antkv_decode_attn_workspace(geom, N, 0, k_v, 0));
 }
 
 int antkv_decode_attn_prerope(const antkv_geom* geom, const void* q, float scale, const uint8_t* codes_k,
@@ -394,30 +399,18 @@ int antkv_decode_attn_prerope(const antkv_geom* geom, const void* q, float scale
                                 out, nullptr, nullptr, nullptr, nullptr, 0, workspace, workspace_bytes, stream);
     if (!codes_k || !cb_k || misaligned(codes_k, 16) || misaligned(cb_k, 16)) return ANTKV_EINVAL;
     if (k_k > 0 && (!idx_k || !rows_k || misaligned(rows_k, 16))) return ANTKV_EINVAL;
-    const size_t rows_b = align_up((size_t)g.B * g.Hkv * (size_t)N * kD * sizeof(half_t));
-    const size_t iota_b = align_up((size_t)g.B * g.Hkv * (size_t)N * sizeof(int32_t));
+    if (!q || misaligned(q, 16) || !(scale > 0.f)) return ANTKV_EINVAL;
     const size_t need = antkv_decode_attn_prerope_workspace(geom, N, k_v);
     if (!workspace || misaligned(workspace, 256) || workspace_bytes < need) return ANTKV_EWORKSPACE;
+    // The rotated keys are never written out: a first pass leaves q . RoPE(K_eff) of every token and head (FP16 anchor
+    // rows included) in the workspace, and the decode kernels take their scores from there instead of from a table.
     char* w = (char*)workspace;
-    if (g.C == kC) {
-        // one-byte codes: the rotated keys are never written out; a first pass leaves q . RoPE(K_eff) of every token and
-        // head (FP16 anchor rows included), and the decode kernel takes its scores from there instead of from a table
-        const size_t sc_b = align_up((size_t)g.B * g.Hkv * (size_t)((N + 63) / 64 * 64) * 16);
-        if (!q || misaligned(q, 16) || !(scale > 0.f)) return ANTKV_EINVAL;
-        if (launch_rope_scores(g, (const half_t*)q, scale, codes_k, N, N_cap, (const half_t*)cb_k, idx_k, (const half_t*)rows_k,
-                               k_k, (double)rope_base, rope_style, pos0, (float*)w, (hipStream_t)stream) != hipSuccess)
-            return ANTKV_ELAUNCH;
-        return decode_attn_impl(geom, q, scale, codes_k, codes_v, N, N_cap, cb_k, cb_v, nullptr, nullptr, 0, idx_v, rows_v, k_v,
-                                out, nullptr, nullptr, nullptr, nullptr, 0, w + sc_b, workspace_bytes - sc_b, stream, (const float*)w);
-    }
-    half_t* k_rot = (half_t*)w;
-    int32_t* iota = (int32_t*)(w + rows_b);
-    if (launch_rope_keys(g, codes_k, N, N_cap, (const half_t*)cb_k, idx_k, (const half_t*)rows_k, k_k, (double)rope_base,
-                         rope_style, pos0, k_rot, iota, (hipStream_t)stream) != hipSuccess)
+    const size_t sc_b = prerope_score_bytes(g, N);
+    if (launch_rope_scores(g, (const half_t*)q, scale, codes_k, N, N_cap, (const half_t*)cb_k, idx_k, (const half_t*)rows_k, k_k,
+                           (double)rope_base, rope_style, pos0, (float*)w, (hipStream_t)stream) != hipSuccess)
         return ANTKV_ELAUNCH;
-    // every token is now a K anchor whose FP16 row is its rotated key; the K codes are not read for scores any more
-    return decode_attn_impl(geom, q, scale, codes_k, codes_v, N, N_cap, cb_k, cb_v, iota, k_rot, N, idx_v, rows_v, k_v, out,
-                            nullptr, nullptr, nullptr, nullptr, 0, w + rows_b + iota_b, workspace_bytes - rows_b - iota_b, stream);
+    return decode_attn_impl(geom, q, scale, codes_k, codes_v, N, N_cap, cb_k, cb_v, nullptr, nullptr, 0, idx_v, rows_v, k_v, out,
+                            nullptr, nullptr, nullptr, nullptr, 0, w + sc_b, workspace_bytes - sc_b, stream, (const float*)w);
 }
 
 int antkv_decode_attn_static(const antkv_geom* geom, const void* q, float scale, const uint8_t* codes_k,

@@ -135,19 +135,16 @@ struct DecodeArgs {
     half_t* out;
     float *ans_k, *ans_v;
     uint32_t* topk_hist;   // optional: first-level top-k histograms that the score pass fills (see launch_topk2_begin)
-    // optional (one-byte codes, k_k = 0, no Anchor Scores): the K side's scores in log2 units as launch_rope_scores writes them;
-    // the K codes, the K codebook and scale are then not used
+    // optional (k_k = 0, no Anchor Scores): the K side's scores in log2 units as launch_rope_scores writes them (one-byte
+    // codes: grouped by four tokens; 12-bit codes: [B][Hkv][N][4 heads]); the K codes, the K codebook and scale are then not used
     const float* given_scores = nullptr;
 };
 int set_decode_options(int options);   // ANTKV_DECODE_* mask; returns the previous mask
 int decode_num_splits(const Geom& g, int64_t N);
 size_t decode_workspace_bytes(const Geom& g, int64_t N, int64_t k_k, int64_t k_v, bool want_ans);
 hipError_t launch_decode_attn(const Geom& g, const DecodeArgs& a, void* ws, hipStream_t st);
-// rows_out fp16 [B][Hkv][N][kD] = RoPE_{pos0 + j}(K_eff[j]) (anchor row or centroids of the codes), iota_out[b][g][j] = j
-hipError_t launch_rope_keys(const Geom& g, const uint8_t* codes_k, int64_t N, int64_t N_cap, const half_t* cb_k,
-                            const int32_t* idx_k, const half_t* rows_k, int64_t k_k, double rope_base, int rope_style,
-                            int64_t pos0, half_t* rows_out, int32_t* iota_out, hipStream_t st);
-// one-byte codes: scores_out fp32 [B][Hkv][N][4] = scale * log2(e) * q_h . RoPE_{pos0 + j}(K_eff[j]) for the group's heads
+// scores_out fp32 = scale * log2(e) * q_h . RoPE_{pos0 + j}(K_eff[j]) for the group's heads (K_eff: the FP16 anchor row or the
+// centroids of the codes), in the layout that DecodeArgs::given_scores describes
 hipError_t launch_rope_scores(const Geom& g, const half_t* q, float scale, const uint8_t* codes_k, int64_t N, int64_t N_cap,
                               const half_t* cb_k, const int32_t* idx_k, const half_t* rows_k, int64_t k_k, double rope_base,
                               int rope_style, int64_t pos0, float* scores_out, hipStream_t st);

@@ -54,6 +54,8 @@ struct D12Params {
     float c1;
     int Hq, Hkv, G, S, chunk;
     float2* early;                        // [B][Hkv][N] scores of heads 0 and 1 from the first walk (d16 with G > 2), else unused
+    const float4_t* given;                // kernels with given scores: [B][Hkv][N] the four heads' scores in log2 units (the K
+                                          // codes, the table and the K anchor list are not used then)
 };
 
 __device__ __forceinline__ float dot8f(const half8_t& a, const half8_t& b, float acc)
@@ -170,7 +172,10 @@ static_assert(d12_lds(32) <= 160 * 1024 && d12_lds(16) <= 160 * 1024, "LDS budge
 
 // kD12 = sub-vector width: 32 (four sub-spaces, one table for the four heads of a group) or 16 (eight sub-spaces, a
 // table holds two heads)
-template <int kD12>
+// GIVEN: the K side's scores come from p.given (keys that are rotated to their position before the product with q have
+// no table): no table is loaded, the K codes are not read, the K anchor list is empty and V entries take their token's
+// score from p.given.
+template <int kD12, bool GIVEN>
 __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
 {
     constexpr int kM12 = kD / kD12;                                    // sub-spaces
@@ -278,9 +283,10 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     };
     const int n_walks = (nh + NHT - 1) / NHT;                          // 1, or 2 for d16 with more than two heads
     float2* early = p.early + (int64_t)bg * p.N;
-    load_table(0);
+    const float4_t* given = GIVEN ? p.given + (int64_t)bg * p.N : nullptr;
+    if constexpr (!GIVEN) load_table(0);
     __syncthreads();                                                   // table and bitmap are complete
-    if (NHT < NHW && n_walks > 1) {
+    if (!GIVEN && NHT < NHW && n_walks > 1) {
         // first walk: heads 0 and 1 of every token of the range; tiles go to the waves as in the stream below
         for (int64_t tile = wave; tile < n_tiles; tile += kW12) {
             const int64_t tok = t0 + tile * 64 + lane;
@@ -408,14 +414,18 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
     for (int64_t tile = wave; tile < n_tiles; tile += kW12) {
         const int64_t tok = t0 + tile * 64 + lane;
         const int64_t ltok = tok < t1 ? tok : t1 - 1;
-        uint32_t kw[3], vw[3];
-        load_cw<kD12>(ck, ltok, kw);
+        uint32_t kw[3] = {0u, 0u, 0u}, vw[3];
+        if constexpr (!GIVEN) load_cw<kD12>(ck, ltok, kw);
         load_cw<kD12>(cv, ltok, vw);
         const int rel = (int)(ltok - t0);
         const uint32_t mbit = (s_mk[rel >> 5] >> (rel & 31)) & 1u;
         const bool masked = tok >= t1 || mbit != 0u;
         float s[NHW];
-        if constexpr (NHT == NHW) {
+        if constexpr (GIVEN) {
+            const float4_t g4 = given[ltok];
+#pragma unroll
+            for (int h = 0; h < NHW; ++h) s[h] = g4[h];
+        } else if constexpr (NHT == NHW) {
             table_scores(kw, s);
         } else {
             float st[NHT];
@@ -488,6 +498,10 @@ __global__ __launch_bounds__(kT12) void decode12_kernel(const D12Params p)
             }
 #pragma unroll
             for (int h = 0; h < NHW; ++h) s[h] *= p.c1;
+        } else if constexpr (GIVEN) {
+            const float4_t g4 = given[tok];
+#pragma unroll
+            for (int h = 0; h < NHW; ++h) s[h] = g4[h];
         } else {
             uint32_t kw[3];
             load_cw<kD12>(ck, tok, kw);
@@ -871,7 +885,9 @@ hipError_t launch_decode12_t(const Geom& g, const DecodeArgs& a, void* ws, hipSt
     const D12Plan pl = d12_plan(g, a.N);
     constexpr size_t lds = d12_lds(DS);
     static const hipError_t setup = []() {
-        return hipFuncSetAttribute((const void*)decode12_kernel<DS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        const hipError_t e1 = hipFuncSetAttribute((const void*)decode12_kernel<DS, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e1 != hipSuccess) return e1;
+        return hipFuncSetAttribute((const void*)decode12_kernel<DS, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     }();
     if (setup != hipSuccess) return setup;
     if ((int64_t)g.B * g.Hkv * pl.S > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -884,10 +900,14 @@ hipError_t launch_decode12_t(const Geom& g, const DecodeArgs& a, void* ws, hipSt
     p.N = a.N; p.N_cap = a.N_cap; p.k_k = (int)a.k_k; p.k_v = (int)a.k_v;
     p.c1 = a.scale * kLog2e; p.Hq = g.Hq; p.Hkv = g.Hkv; p.G = g.G; p.S = a.N > 0 ? pl.S : 0; p.chunk = pl.chunk;
     p.early = (float2*)(w + pl.off_early);
-    if (a.N > 0) {
+    p.given = (const float4_t*)a.given_scores;
+    if (a.given_scores && (a.k_k != 0 || a.ans_k || a.ans_v)) return hipErrorInvalidValue;     // the scores cover the K anchors already
+    if (a.N > 0 && a.given_scores) {
+        hipLaunchKernelGGL((decode12_kernel<DS, true>), dim3((unsigned)(g.B * g.Hkv * pl.S)), dim3(kT12), lds, st, p);
+    } else if (a.N > 0) {
         hipLaunchKernelGGL(d12_table_kernel<DS>, dim3((unsigned)(g.B * g.Hkv), tab_blocks(DS)), dim3(kTabThreads), 0, st, a.q,
                            a.cb_k, p.c1, g.Hq, g.Hkv, g.G, (float4_t*)(w + pl.off_tab), (float*)(w + pl.off_amax));
-        hipLaunchKernelGGL(decode12_kernel<DS>, dim3((unsigned)(g.B * g.Hkv * pl.S)), dim3(kT12), lds, st, p);
+        hipLaunchKernelGGL((decode12_kernel<DS, false>), dim3((unsigned)(g.B * g.Hkv * pl.S)), dim3(kT12), lds, st, p);
     }
     hipLaunchKernelGGL(decode12_merge, dim3((unsigned)(g.B * g.Hq)), dim3(kD), 0, st, (const float*)p.part, p.S, a.out);
     if (a.ans_k && a.N > 0) {

@@ -1,37 +1,17 @@
-// Keys stored before RoPE (paper Sec. 3.3, last paragraph: the pre-RoPE strategy): before a decode step uses them, every
-// key of the cache is brought to its position, K_rot[j] = RoPE_{pos0 + j}(K_eff[j]) with K_eff[j] the FP16 anchor row
-// or the centroids of the token's codes (Sec. 2.1: the rotary embedding that turns K into K~).  The rotated keys are
-// written as FP16 rows, one per token, together with the identity index list; decode attention then takes them as a
-// K anchor list that covers every token.
+// Keys stored before RoPE (paper Sec. 3.3, last paragraph: the pre-RoPE strategy): a decode step needs
+// q . RoPE_{pos0 + j}(K_eff[j]) with K_eff[j] the FP16 anchor row or the centroids of the token's codes (Sec. 2.1: the
+// rotary embedding that turns K into K~).  The kernels here work out that product for every token and head of the group
+// and leave it in the caller's workspace; the rotated keys themselves are never written.  The decode kernels then take
+// their scores from there instead of from a lookup table.
 //
 // RoPE rotates channel pair i = 0 .. 63 by the angle pos * base^(-2 i / 128); the pair is (2 i, 2 i + 1) (style 0) or
-// (i, i + 64) (style 1).  One lane per pair.  The angle of a run's first token is reduced in fp64 (pos * theta reaches
-// 10^5 rad), the following tokens of the run advance by one fp32 complex multiplication with e^{i theta} each.
+// (i, i + 64) (style 1).  Angles of absolute positions are reduced in fp64 (pos * theta reaches 10^5 rad and more).
 #include "common.h"
 
 namespace antkv {
 
 namespace {
 
-constexpr int kRunTokens = 16;         // tokens a 64-lane group rotates one after another
-constexpr int kGroups = 4;             // groups per workgroup
-
-struct RkParams {
-    const uint8_t* codes;              // [B][Hkv][N_cap][code_bytes]
-    const half_t* cb;                  // [Hkv][M][C][d]
-    const int32_t* idx;                // [B][Hkv][k] positions of the FP16 rows
-    const half_t* rows;                // [B][Hkv][k][128] FP16 rows, before RoPE
-    half_t* out;                       // [B][Hkv][N][128]
-    int32_t* iota;                     // [B][Hkv][N]: iota[j] = j
-    int64_t N, N_cap, pos0;
-    int k, Hkv, d, M, C, code_bytes, style;
-    double log2_base;
-};
-
-__device__ __forceinline__ void pair_channels(int style, int i, int& ca, int& cb)
-{
-    if (style == 0) { ca = 2 * i; cb = 2 * i + 1; } else { ca = i; cb = i + kD / 2; }
-}
 // cos, sin of pos * theta with the product reduced to (-pi, pi] in fp64
 __device__ __forceinline__ void angle_of(int64_t pos, double theta, float& c, float& s)
 {
@@ -44,66 +24,10 @@ __device__ __forceinline__ void angle_of(int64_t pos, double theta, float& c, fl
     c *= n;
     s *= n;
 }
-__device__ __forceinline__ int code_of(const RkParams& p, const uint8_t* row, int m)
-{
-    if (p.C == kC) return row[m];
-    const uint8_t* t = row + 3 * (m >> 1);            // two 12-bit codes in three bytes
-    return (m & 1) ? ((t[1] >> 4) | (t[2] << 4)) : (t[0] | ((t[1] & 0xf) << 8));
-}
 
-__global__ __launch_bounds__(64 * kGroups) void rope_dequant_kernel(const RkParams p)
-{
-    const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
-    const int bg = blockIdx.y, g = bg % p.Hkv;
-    const int64_t j0 = ((int64_t)blockIdx.x * kGroups + grp) * kRunTokens;
-    if (j0 >= p.N) return;
-    int ca, cb;
-    pair_channels(p.style, lane, ca, cb);
-    const double theta = exp2(-(2.0 * lane / kD) * p.log2_base);
-    float c, s, cd, sd;
-    angle_of(p.pos0 + j0, theta, c, s);
-    angle_of(1, theta, cd, sd);
-    const int ma = ca / p.d, ea = ca % p.d, mb = cb / p.d, eb = cb % p.d;
-    const half_t* cba = p.cb + ((size_t)g * p.M + ma) * p.C * p.d + ea;
-    const half_t* cbb = p.cb + ((size_t)g * p.M + mb) * p.C * p.d + eb;
-    for (int t = 0; t < kRunTokens && j0 + t < p.N; ++t) {
-        const int64_t j = j0 + t;
-        const uint8_t* row = p.codes + ((int64_t)bg * p.N_cap + j) * p.code_bytes;
-        const float a = (float)cba[(size_t)code_of(p, row, ma) * p.d];
-        const float b = (float)cbb[(size_t)code_of(p, row, mb) * p.d];
-        half_t* o = p.out + ((int64_t)bg * p.N + j) * kD;
-        o[ca] = (half_t)(a * c - b * s);
-        o[cb] = (half_t)(a * s + b * c);
-        if (lane == 0) p.iota[(int64_t)bg * p.N + j] = (int32_t)j;
-        const float cn = c * cd - s * sd;
-        s = s * cd + c * sd;
-        c = cn;
-    }
-}
-
-// the FP16 anchor rows replace the rotated centroids of their tokens
-__global__ __launch_bounds__(64 * kGroups) void rope_rows_kernel(const RkParams p)
-{
-    const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
-    const int bg = blockIdx.y;
-    const int e = blockIdx.x * kGroups + grp;
-    if (e >= p.k) return;
-    int ca, cb;
-    pair_channels(p.style, lane, ca, cb);
-    const double theta = exp2(-(2.0 * lane / kD) * p.log2_base);
-    const int64_t j = p.idx[(int64_t)bg * p.k + e];
-    float c, s;
-    angle_of(p.pos0 + j, theta, c, s);
-    const half_t* r = p.rows + ((int64_t)bg * p.k + e) * kD;
-    const float a = (float)r[ca], b = (float)r[cb];
-    half_t* o = p.out + ((int64_t)bg * p.N + j) * kD;
-    o[ca] = (half_t)(a * c - b * s);
-    o[cb] = (half_t)(a * s + b * c);
-}
-
-// ---- scores instead of rows (one-byte codes) -----------------------------------------------------------------------
-// q . RoPE_p(k) for the group's four heads, in log2 units (scale * log2 e folded into q): 16 bytes per token and KV head
-// instead of a 256-byte rotated row.  Layout: [B][Hkv][n_pad / 4][4 heads][4 tokens] fp32 with n_pad = N rounded up to 64,
+// ---- one-byte codes ------------------------------------------------------------------------------------------------
+// q . RoPE_p(k) for the group's four heads, in log2 units (scale * log2 e folded into q): 16 bytes per token and KV
+// head.  Layout: [B][Hkv][n_pad / 4][4 heads][4 tokens] fp32 with n_pad = N rounded up to 64,
 // the form in which the decode kernel's lanes (one head, four consecutive tokens each) read it with one 16-byte load.
 // A workgroup (12 waves: as many as the LDS leaves room for) owns a token range of one (sequence, KV head) and keeps
 // in LDS the K codebook code-major with rows padded to 272 bytes (a lane = a token, and all lanes read the same 16-byte
@@ -131,6 +55,7 @@ struct RsParams {
     float* scores;                     // [B][Hkv][n_pad / 4][4][4]
     int64_t N, N_cap, n_pad, pos0, chunk;
     int k, Hq, Hkv, G, S;
+    int plain;                         // score layout [B][Hkv][N][4 heads] (the 12-bit kernels' form) instead of the grouped one
     float c1;
     double log2_base;
 };
@@ -349,44 +274,173 @@ __global__ __launch_bounds__(256) void rope_row_scores_kernel(const RsParams p)
         float sum = (up4 ? k1 : k0) + __shfl_xor(up4 ? k0 : k1, 16, 64);
 #pragma unroll
         for (int off = 8; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
-        if ((lane & 15) == 0 && e0 + i < p.k)                             // lane 16 h holds head h
-            p.scores[((int64_t)bg * p.n_pad + (tok[i] & ~3LL)) * 4 + 4 * (lane >> 4) + (tok[i] & 3)] = sum;
+        if ((lane & 15) == 0 && e0 + i < p.k) {                           // lane 16 h holds head h
+            if (p.plain) p.scores[((int64_t)bg * p.N + tok[i]) * 4 + (lane >> 4)] = sum;
+            else p.scores[((int64_t)bg * p.n_pad + (tok[i] & ~3LL)) * 4 + 4 * (lane >> 4) + (tok[i] & 3)] = sum;
+        }
+    }
+}
+
+// ---- the same scores for 12-bit codes (4096 centroids; sub-vectors of 32 or 16 channels) ------------------------------
+// The K codebook (1 MB per KV head) stays in the L2, so a token's centroids are fetched the way the 12-bit decode kernel
+// fetches its values: 16 lanes per token, each lane the 16 bytes (or two pieces of 8) that hold its four channel pairs,
+// four tokens per wave and step.  A lane therefore always works on the same four pairs: it keeps the four heads' pairs
+// of q, rotated back by the tile's base angle, in registers (the base angles of the 64 pairs are worked out by the wave,
+// lane = pair, and passed through LDS), takes cos / sin of delta * theta from the table [delta][pair] in LDS, and the
+// four partial dot products are added up over the 16 lanes.  Output: [B][Hkv][N][4 heads] fp32.
+constexpr int kR12Threads = 1024, kR12Waves = kR12Threads / 64;
+constexpr int kR12Delta = 0;                                           // [64 deltas][64 pairs] float2
+constexpr int kR12Base = kR12Delta + 64 * 64 * 8;                      // [waves][64 pairs] float2
+constexpr int kR12Codes = kR12Base + kR12Waves * 64 * 8;               // [waves][64 tokens][8 codes] uint16
+constexpr int kR12Lds = kR12Codes + kR12Waves * 64 * 16;
+
+template <int DS, int STYLE>
+__global__ __launch_bounds__(kR12Threads) void rope_scores12_kernel(const RsParams p)
+{
+    constexpr int M = kD / DS, CB = 3 * M / 2, kC12 = 4096;
+    extern __shared__ uint4_t rs_smem[];
+    char* smem = (char*)rs_smem;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int bg = blockIdx.x / p.S, sp = blockIdx.x % p.S;
+    const int b = bg / p.Hkv, g = bg % p.Hkv;
+    const int64_t t0 = (int64_t)sp * p.chunk;
+    const int64_t t1 = (t0 + p.chunk < p.N) ? t0 + p.chunk : p.N;
+    if (t0 >= t1) return;
+    for (int e = tid; e < 64 * 64; e += kR12Threads) {
+        const int delta = e >> 6, pair = e & 63;
+        float c, s;
+        angle_of(delta, exp2(-(2.0 * pair / kD) * p.log2_base), c, s);
+        ((float2*)(smem + kR12Delta))[e] = float2{c, s};
+    }
+    const int li = lane & 15, grp = lane >> 4;
+    // the lane's pairs 4 li .. 4 li + 3: channels (2 pr, 2 pr + 1), i.e. the 16 bytes from channel 8 li on, or (pr, pr + 64),
+    // i.e. 8 bytes from channel 4 li on and 8 bytes from channel 64 + 4 li on
+    float qa[4][4], qb[4][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int pr = 4 * li + j;
+        const int ca = STYLE == 0 ? 2 * pr : pr, cb = STYLE == 0 ? 2 * pr + 1 : pr + kD / 2;
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            qa[j][h] = qb[j][h] = 0.f;
+            if (h < p.G) {
+                const half_t* qh = p.q + ((int64_t)b * p.Hq + g * p.G + h) * kD;
+                qa[j][h] = (float)qh[ca] * p.c1;
+                qb[j][h] = (float)qh[cb] * p.c1;
+            }
+        }
+    }
+    __syncthreads();
+    const double theta = exp2(-(2.0 * lane / kD) * p.log2_base);       // lane i looks after pair i's base angle
+    const uint8_t* ck = p.codes + (int64_t)bg * p.N_cap * CB;
+    const char* cbg = (const char*)(p.cb + (size_t)g * M * kC12 * DS);
+    float2* s_base = (float2*)(smem + kR12Base) + wave * 64;
+    uint16_t* s_codes = (uint16_t*)(smem + kR12Codes) + wave * (64 * 8);
+    // byte offsets of the lane's pieces inside a centroid, and their sub-spaces
+    constexpr int kPieces = STYLE == 0 ? 1 : 2;
+    int piece_m[kPieces], piece_off[kPieces];
+    if constexpr (STYLE == 0) {
+        piece_m[0] = (8 * li) / DS; piece_off[0] = ((8 * li) % DS) * 2;
+    } else {
+        piece_m[0] = (4 * li) / DS; piece_off[0] = ((4 * li) % DS) * 2;
+        piece_m[1] = (64 + 4 * li) / DS; piece_off[1] = ((64 + 4 * li) % DS) * 2;
+    }
+    const int64_t n_tiles = (t1 - t0 + 63) >> 6;
+    for (int64_t tile = wave; tile < n_tiles; tile += kR12Waves) {
+        const int64_t tok0 = t0 + tile * 64;
+        {
+            float bc, bs;
+            angle_of(p.pos0 + tok0, theta, bc, bs);
+            // this lane's token of the tile: its codes, unpacked (two 12-bit codes in three bytes), go to LDS for the 16
+            // lanes that will work on the token
+            const int64_t ltok = tok0 + lane < p.N ? tok0 + lane : p.N - 1;
+            const uint8_t* row = ck + ltok * CB;                         // (rows are 2-byte aligned only)
+            uint32_t cw[CB / 2];
+#pragma unroll
+            for (int i = 0; i < CB / 2; ++i) cw[i] = *(const uint16_t*)(row + 2 * i);
+            uint32_t code[M];
+#pragma unroll
+            for (int i = 0; i < M / 2; ++i) {                             // bytes 3 i .. 3 i + 2 = 16-bit words 3 i / 2 ..
+                const uint32_t w24 = (i & 1) ? ((cw[3 * i / 2] >> 8) | (cw[3 * i / 2 + 1] << 8)) : (cw[3 * i / 2] | (cw[3 * i / 2 + 1] << 16));
+                code[2 * i] = w24 & 0xfffu;
+                code[2 * i + 1] = (w24 >> 12) & 0xfffu;
+            }
+            __builtin_amdgcn_wave_barrier();                              // the previous tile's readers are done
+            s_base[lane] = float2{bc, bs};
+            if constexpr (M == 4) {
+                *(uint2_t*)(s_codes + lane * 8) = uint2_t{code[0] | (code[1] << 16), code[2] | (code[3] << 16)};
+            } else {
+                *(uint4_t*)(s_codes + lane * 8) = uint4_t{code[0] | (code[1] << 16), code[2] | (code[3] << 16),
+                                                          code[4] | (code[5] << 16), code[6] | (code[7] << 16)};
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+        float qx[4][4], qy[4][4];                                         // R_{-base} (qa, qb) of the lane's pairs
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float2 cs = s_base[4 * li + j];
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                qx[j][h] = qa[j][h] * cs.x + qb[j][h] * cs.y;
+                qy[j][h] = qb[j][h] * cs.x - qa[j][h] * cs.y;
+            }
+        }
+        uint32_t delta_off = (uint32_t)kR12Delta + 32u * (uint32_t)li;   // (read through an address the compiler cannot follow:
+        asm volatile("" : "+v"(delta_off));                               //  the table would otherwise be kept in registers or scratch)
+#pragma unroll 4
+        for (int step = 0; step < 16; ++step) {
+            const int tl = 4 * step + grp;                                // the token's place in the tile = its delta
+            const uint16_t* cr = s_codes + tl * 8;
+            float ka[4], kb[4];
+            auto code_of_sub = [&](int m) -> uint32_t { return cr[m]; };
+            if constexpr (STYLE == 0) {
+                const uint32_t code = code_of_sub(piece_m[0]);
+                const half8_t v = *(const half8_t*)(cbg + ((size_t)(piece_m[0] * kC12 + code) * DS) * 2 + piece_off[0]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { ka[j] = (float)v[2 * j]; kb[j] = (float)v[2 * j + 1]; }
+            } else {
+                const uint32_t code_a = code_of_sub(piece_m[0]), code_b = code_of_sub(piece_m[1]);
+                const half4_t va = *(const half4_t*)(cbg + ((size_t)(piece_m[0] * kC12 + code_a) * DS) * 2 + piece_off[0]);
+                const half4_t vb = *(const half4_t*)(cbg + ((size_t)(piece_m[1] * kC12 + code_b) * DS) * 2 + piece_off[1]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { ka[j] = (float)va[j]; kb[j] = (float)vb[j]; }
+            }
+            const float4_t d01 = *(const float4_t*)(smem + delta_off + (uint32_t)tl * 512u);
+            const float4_t d23 = *(const float4_t*)(smem + delta_off + (uint32_t)tl * 512u + 16u);
+            const float dc[4] = {d01[0], d01[2], d23[0], d23[2]}, ds[4] = {d01[1], d01[3], d23[1], d23[3]};
+            float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float xr = ka[j] * dc[j] - kb[j] * ds[j], yr = ka[j] * ds[j] + kb[j] * dc[j];
+#pragma unroll
+                for (int h = 0; h < 4; ++h) acc[h] = fmaf(qx[j][h], xr, fmaf(qy[j][h], yr, acc[h]));
+            }
+            // sums over the 16 lanes of the token (rotations inside a row of 16 lanes: no LDS traffic)
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                acc[h] += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, acc[h]), 0x128, 0xf, 0xf, true));   // row_ror:8
+                acc[h] += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, acc[h]), 0x124, 0xf, 0xf, true));   // row_ror:4
+                acc[h] += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, acc[h]), 0x122, 0xf, 0xf, true));   // row_ror:2
+                acc[h] += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, acc[h]), 0x121, 0xf, 0xf, true));   // row_ror:1
+            }
+            const int64_t tok = tok0 + tl;
+            if (li == 0 && tok < p.N) ((float4_t*)p.scores)[(int64_t)bg * p.N + tok] = float4_t{acc[0], acc[1], acc[2], acc[3]};
+        }
     }
 }
 
 }  // namespace
-
-hipError_t launch_rope_keys(const Geom& g, const uint8_t* codes_k, int64_t N, int64_t N_cap, const half_t* cb_k,
-                            const int32_t* idx_k, const half_t* rows_k, int64_t k_k, double rope_base, int rope_style,
-                            int64_t pos0, half_t* rows_out, int32_t* iota_out, hipStream_t st)
-{
-    if (N == 0 || g.B == 0) return hipSuccess;
-    RkParams p;
-    p.codes = codes_k; p.cb = cb_k; p.idx = idx_k; p.rows = rows_k; p.out = rows_out; p.iota = iota_out;
-    p.N = N; p.N_cap = N_cap; p.pos0 = pos0; p.k = (int)k_k; p.Hkv = g.Hkv; p.d = g.d; p.M = g.M; p.C = g.C;
-    p.code_bytes = g.code_bytes; p.style = rope_style; p.log2_base = log2(rope_base);
-    const int64_t runs = (N + kRunTokens - 1) / kRunTokens;
-    dim3 grid((unsigned)((runs + kGroups - 1) / kGroups), (unsigned)(g.B * g.Hkv));
-    hipLaunchKernelGGL(rope_dequant_kernel, grid, dim3(64 * kGroups), 0, st, p);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    if (k_k > 0) {
-        dim3 grid2((unsigned)((k_k + kGroups - 1) / kGroups), (unsigned)(g.B * g.Hkv));
-        hipLaunchKernelGGL(rope_rows_kernel, grid2, dim3(64 * kGroups), 0, st, p);
-        e = hipGetLastError();
-    }
-    return e;
-}
 
 hipError_t launch_rope_scores(const Geom& g, const half_t* q, float scale, const uint8_t* codes_k, int64_t N, int64_t N_cap,
                               const half_t* cb_k, const int32_t* idx_k, const half_t* rows_k, int64_t k_k, double rope_base,
                               int rope_style, int64_t pos0, float* scores_out, hipStream_t st)
 {
     if (N == 0 || g.B == 0) return hipSuccess;
-    if (g.C != kC) return hipErrorInvalidValue;
     RsParams p;
     p.q = q; p.codes = codes_k; p.cb = cb_k; p.idx = idx_k; p.rows = rows_k; p.scores = scores_out;
     p.n_pad = (N + 63) / 64 * 64;
+    p.plain = g.C != kC;
     p.N = N; p.N_cap = N_cap; p.pos0 = pos0; p.k = (int)k_k; p.Hq = g.Hq; p.Hkv = g.Hkv; p.G = g.G;
     p.c1 = scale * kLog2e; p.log2_base = log2(rope_base);
     const int64_t bg = (int64_t)g.B * g.Hkv;
@@ -399,6 +453,13 @@ hipError_t launch_rope_scores(const Geom& g, const half_t* q, float scale, const
     p.S = (int)((N + chunk - 1) / chunk);
     const dim3 grid((unsigned)(bg * p.S));
     hipError_t e = hipSuccess;
+#define ANTKV_RS12(DS, STY)                                                                                                \
+    do {                                                                                                                   \
+        static const hipError_t once = hipFuncSetAttribute((const void*)rope_scores12_kernel<DS, STY>,                     \
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, kR12Lds);           \
+        if (once != hipSuccess) return once;                                                                               \
+        hipLaunchKernelGGL((rope_scores12_kernel<DS, STY>), grid, dim3(kR12Threads), kR12Lds, st, p);                      \
+    } while (0)
 #define ANTKV_RS(DS, STY)                                                                                                  \
     do {                                                                                                                   \
         static const hipError_t once = hipFuncSetAttribute((const void*)rope_scores_kernel<DS, STY>,                       \
@@ -406,10 +467,15 @@ hipError_t launch_rope_scores(const Geom& g, const half_t* q, float scale, const
         if (once != hipSuccess) return once;                                                                               \
         hipLaunchKernelGGL((rope_scores_kernel<DS, STY>), grid, dim3(kRsThreads), kRsLds, st, p);                          \
     } while (0)
-    if (g.d == 4) { if (rope_style == 0) ANTKV_RS(4, 0); else ANTKV_RS(4, 1); }
+    if (g.C != kC) {
+        if (g.d == 32) { if (rope_style == 0) ANTKV_RS12(32, 0); else ANTKV_RS12(32, 1); }
+        else { if (rope_style == 0) ANTKV_RS12(16, 0); else ANTKV_RS12(16, 1); }
+    }
+    else if (g.d == 4) { if (rope_style == 0) ANTKV_RS(4, 0); else ANTKV_RS(4, 1); }
     else if (g.d == 8) { if (rope_style == 0) ANTKV_RS(8, 0); else ANTKV_RS(8, 1); }
     else { if (rope_style == 0) ANTKV_RS(16, 0); else ANTKV_RS(16, 1); }
 #undef ANTKV_RS
+#undef ANTKV_RS12
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (k_k > 0) {

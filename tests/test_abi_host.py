@@ -129,12 +129,11 @@ def test_decode_options_and_prerope_argument_errors(lib):
     g = _g(B=1)
     fake = ctypes.c_void_p(4096)
     ws_bytes = lib.antkv_decode_attn_prerope_workspace(ctypes.byref(g), 1000, 0)
-    # one-byte codes: 16 bytes of scores per token (rounded up to 64) and KV head + the decode kernels' own scratch
+    # 16 bytes of scores per token (one-byte codes: tokens rounded up to 64) and KV head + the decode kernels' own scratch
     assert ws_bytes >= 8 * 1024 * 16 + lib.antkv_decode_attn_workspace(ctypes.byref(g), 1000, 0, 0, 0)
-    # 12-bit codes: rotated FP16 rows + the identity index list + the decode kernels' own scratch
     g12 = _g(B=1, d=32, C=4096)
     assert lib.antkv_decode_attn_prerope_workspace(ctypes.byref(g12), 1000, 0) >= \
-        8 * 1000 * (256 + 4) + lib.antkv_decode_attn_workspace(ctypes.byref(g12), 1000, 1000, 0, 0)
+        8 * 1000 * 16 + lib.antkv_decode_attn_workspace(ctypes.byref(g12), 1000, 0, 0, 0)
     assert lib.antkv_decode_attn_prerope_workspace(ctypes.byref(_g(d=2)), 1000, 10) == 0
     call = lambda base, style, pos0, ws=fake, nbytes=1 << 40: lib.antkv_decode_attn_prerope(
         ctypes.byref(g), fake, 0.1, fake, fake, 1000, 1000, fake, fake, None, None, 0, None, None, 0,

@@ -46,6 +46,8 @@ def test_prerope_byte_codes(oracle, d, style, pos0):
 @pytest.mark.parametrize("d", [32, 16])
 def test_prerope_12bit_codes(oracle, d):
     _case(oracle, 310 + d, 1, 8, 2, 2500, d, 4096, 25, 25, 500000.0, 1, 4096)
+    _case(oracle, 312 + d, 2, 4, 2, 1333, d, 4096, 14, 0, 10000.0, 0, 7)          # the other pairing, two heads per KV head, odd N
+    _case(oracle, 314 + d, 1, 2, 2, 70000, d, 4096, 700, 700, 500000.0, 1, 0, N_cap=70100)   # several ranges per KV head
 
 
 def test_prerope_edge_cases(oracle):
