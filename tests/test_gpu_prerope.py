@@ -111,3 +111,31 @@ def test_prerope_headline_shape_sampled(oracle):
         err = rel_l2_rows(got[b:b + 1, hs], want)
         print(f"pre-RoPE headline shape, sequence {b} KV head {g}: rel-L2 max {err.max():.2e}")
         assert err.max() <= ATTN_TOL, f"relative L2 {err.max():.3e}"
+
+
+@pytest.mark.parametrize("d", [32, 16])
+def test_prerope_12bit_extreme_context_sampled(oracle, d):
+    """The 840000-token shape of the paper's long-context point (Sec. 4.4) with keys stored before RoPE and 12-bit codes:
+    one launch over 8 KV heads, one of them checked against the oracle (which gets that head's slices alone)."""
+    B, Hq, Hkv, N, k = 1, 32, 8, 840000, 8400
+    M, G, seed, base, style, pos0 = 128 // d, 4, 350 + d, 500000.0, 1, 0
+    scale = 1 / np.sqrt(128)
+    rng = np.random.default_rng(seed)
+    q = oracle.rope(make_decode_query(seed, B, Hq, 128).astype(np.float64), np.full((B, Hq), pos0 + N), base, style).astype(np.float16)
+    ck = rng.integers(0, 4096, (B, Hkv, N, M)).astype(np.int32)
+    cv = rng.integers(0, 4096, (B, Hkv, N, M)).astype(np.int32)
+    cbk, cbv = normal_fp16(seed, "cb12_k", (Hkv, M, 4096, d)), normal_fp16(seed, "cb12_v", (Hkv, M, 4096, d))
+    ik, iv = random_anchor_sets(seed, "k", B, Hkv, N, k), random_anchor_sets(seed, "v", B, Hkv, N, k)
+    rk, rv = normal_fp16(seed, "rows_k", (B, Hkv, k, 128)), normal_fp16(seed, "rows_v", (B, Hkv, k, 128))
+    geom = antkv.Geometry(B, Hq, Hkv, d, n_centroids=4096)
+    out = antkv.decode_attn_prerope(geom, dev(q), scale, dev(pack12(ck)), dev(pack12(cv)), dev(cbk), dev(cbv), dev(ik), dev(rk),
+                                    dev(iv), dev(rv), rope_base=base, rope_style=style, pos0=pos0)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    g = 5
+    hs = slice(g * G, (g + 1) * G)
+    want = oracle.decode_attn_prerope(q[:, hs], ck[:, g:g + 1], cv[:, g:g + 1], cbk[g:g + 1], cbv[g:g + 1], ik[:, g:g + 1],
+                                      rk[:, g:g + 1], iv[:, g:g + 1], rv[:, g:g + 1], scale, base, style, pos0)
+    err = rel_l2_rows(got[:, hs], want)
+    print(f"pre-RoPE d={d} C=4096 N={N}, KV head {g}: rel-L2 max {err.max():.2e}")
+    assert err.max() <= ATTN_TOL, f"relative L2 {err.max():.3e}"
